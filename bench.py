@@ -1,0 +1,279 @@
+#!/usr/bin/env python3
+"""Benchmark of the fine-grained W4A8 integer-scale linear layer on one MI355X.
+
+Workload (N=1): the LLaMA-2-7B-shaped decode linears (qkv 4096->12288, o_proj 4096->4096, gate_up 4096->22016,
+down 11008->4096; group-128 int4 weights, int8 per-token activations, alpha = 2^10) at batch M in {1, 16, 64}.
+One step is one pass of the whole hot path over that workload: for every batch size and every one of `--layers`
+layers (32, each with its own weight buffers, so every GEMM streams cold weights from HBM as in a real decode
+step), the per-token activation quantiser followed by the integer-scale GEMM.  Inputs are synthetic (seeded) and
+resident in HBM before the timed region.  Launches of one (batch, linear) pair are recorded into a HIP graph and
+replayed back to back; HIP events between the graph launches give each kernel's average duration inside the timed
+region.
+
+Prints ONE JSON line.  `value` is the whole step's algorithmic bytes per second (the regime is HBM-bound); TOPS,
+per-shape figures and the integer-scale vs float-scale speedup ride along in the same line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_I8_PEAK_TOPS = 5000.0     # dense int8 MFMA
+GROUP = 128
+ALPHA_LOG2 = 10
+BATCHES = (1, 16, 64)
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=32, help="distinct weight copies per linear (LLaMA-2-7B has 32 layers)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--no-floatscale", action="store_true", help="skip the float-scale comparison pass")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
+    ap.add_argument("--cpu-sample-layers", type=int, default=4)
+    return ap.parse_args()
+
+
+class Segment:
+    """A run of launches replayed as one unit, with the bookkeeping for its roofline figures."""
+
+    def __init__(self, name, kernel, launches, alg_bytes, ops, fn, use_graph, torch):
+        self.name, self.kernel, self.launches, self.alg_bytes, self.ops = name, kernel, launches, alg_bytes, ops
+        self.fn = fn
+        self.graph = None
+        self.elapsed_ms = 0.0
+        self.count = 0
+        self.pending = []
+        if use_graph:
+            fn()                       # run once eagerly: every buffer is touched before capture
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                fn()
+            self.graph = g
+
+    def run(self):
+        if self.graph is not None:
+            self.graph.replay()
+        else:
+            self.fn()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (one process, one MI355X); run with --gpus 1. "
+              "Multi-GPU sharding is a design note, not a measured path.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2405_14597_amd as P
+    import synth_inputs as S
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    P.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    L = args.layers
+    use_graph = not args.no_graph
+
+    # ---------------------------------------------------------------- data: one layer drawn on the host, quantised on
+    # the GPU by the library, then copied into L distinct buffers (timing does not depend on the values).
+    linears = list(S.LLAMA2_7B.items())        # name -> (K, N)
+    weights = {}
+    for idx, (name, (K, N)) in enumerate(linears):
+        w = torch.from_numpy(S.make_weights(1, N, K, S.seed_for(1, idx, 1))).to(dev)
+        qw = P.is_quantize_weights_int4_group(w, GROUP, ALPHA_LOG2, P.IS_SCALE_NORM)
+        del w
+        weights[name] = dict(
+            q=qw.qweight.unsqueeze(0).repeat(L, 1, 1),
+            si=qw.scale_i32.unsqueeze(0).repeat(L, 1, 1),
+            sf=qw.scale_f32.unsqueeze(0).repeat(L, 1, 1),
+            c=qw.chan_scale.unsqueeze(0).repeat(L, 1),
+        )
+    acts = {}
+    for M in BATCHES:
+        for idx, (name, (K, N)) in enumerate(linears):
+            x = torch.from_numpy(S.make_activations(1, M, K, S.seed_for(1, idx, 2) + M)).to(dev)
+            acts[(M, name)] = dict(
+                x=x, xq=torch.empty((M, K), dtype=torch.int8, device=dev),
+                sa=torch.empty((M,), dtype=torch.float32, device=dev),
+                out=torch.empty((M, N), dtype=torch.float16, device=dev))
+    torch.cuda.synchronize()
+
+    def mt_of(M):
+        return 1 if M <= 16 else 2 if M <= 32 else 3 if M <= 48 else 4
+
+    # ---------------------------------------------------------------- segments of one step
+    def make_segments(int_scale: bool, with_quant: bool):
+        segs = []
+        for M in BATCHES:
+            for name, (K, N) in linears:
+                a, w = acts[(M, name)], weights[name]
+                if with_quant:
+                    def fq(a=a):
+                        for _ in range(L):
+                            P.is_quantize_act_int8_token(a["x"], a["xq"], a["sa"])
+                    segs.append(Segment(f"quant_{name}_M{M}", "quantize_act_kernel", L, L * (3 * M * K + 4 * M), 0, fq,
+                                        use_graph, torch))
+                if int_scale:
+                    def fg(a=a, w=w):
+                        for l in range(L):
+                            P.is_gemm_w4a8_intscale(a["xq"], a["sa"], w["q"][l], w["si"][l], w["c"][l], GROUP,
+                                                    ALPHA_LOG2, out=a["out"])
+                else:
+                    def fg(a=a, w=w):
+                        for l in range(L):
+                            P.is_gemm_w4a8_floatscale(a["xq"], a["sa"], w["q"][l], w["sf"][l], GROUP, out=a["out"])
+                kname = "gemm_skinny_kernel<%d,%s>" % (mt_of(M), "int" if int_scale else "float")
+                segs.append(Segment(f"gemm_{name}_M{M}", kname, L, L * S.algorithmic_bytes(M, N, K, GROUP),
+                                    L * S.algorithmic_ops(M, N, K), fg, use_graph, torch))
+        return segs
+
+    def run_steps(segs, n, timed):
+        for _ in range(n):
+            ev = torch.cuda.Event(enable_timing=True)
+            ev.record()
+            for s in segs:
+                s.run()
+                nxt = torch.cuda.Event(enable_timing=True)
+                nxt.record()
+                if timed:
+                    s.pending.append((ev, nxt))
+                ev = nxt
+
+    def timed_pass(segs, steps, warmup):
+        run_steps(segs, warmup, False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(segs, steps, True)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for s in segs:
+            s.elapsed_ms = sum(a.elapsed_time(b) for a, b in s.pending)
+            s.count = len(s.pending) * s.launches
+            s.pending = []
+        return (t1 - t0) / steps
+
+    segs = make_segments(int_scale=True, with_quant=True)
+    sec_per_step = timed_pass(segs, args.steps, args.warmup)
+    step_bytes = sum(s.alg_bytes for s in segs)
+    step_ops = sum(s.ops for s in segs)
+
+    shapes = []
+    for s in segs:
+        us = 1e3 * s.elapsed_ms / max(s.count, 1)
+        per_launch_bytes = s.alg_bytes / s.launches
+        shapes.append(dict(name=s.name, kernel=s.kernel, us=round(us, 3), gbs=round(per_launch_bytes / us / 1e3, 1),
+                           tops=round(s.ops / s.launches / us / 1e6, 3),
+                           hbm_frac=round(per_launch_bytes / us / 1e3 / HBM_PEAK_GBS, 4)))
+
+    # dominant kernel = the instantiation with the most time inside the timed region
+    by_kernel = {}
+    for s in segs:
+        k = by_kernel.setdefault(s.kernel, dict(ms=0.0, launches=0, bytes=0.0))
+        k["ms"] += s.elapsed_ms
+        k["launches"] += s.count
+        k["bytes"] += s.alg_bytes * (s.count / s.launches)
+    dom_name, dom = max(by_kernel.items(), key=lambda kv: kv[1]["ms"])
+    dom_us = 1e3 * dom["ms"] / dom["launches"]
+    dom_bytes = dom["bytes"] / dom["launches"]
+    achieved = dom_bytes / dom_us / 1e3
+    roofline = dict(bound="hbm", kernel=dom_name, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    avg_launch_us=round(dom_us, 3), alg_bytes_per_launch=round(dom_bytes))
+
+    # ---------------------------------------------------------------- float-scale comparison (GEMM launches only)
+    speedup = None
+    fs_detail = None
+    if not args.no_floatscale:
+        is_g = make_segments(int_scale=True, with_quant=False)
+        fs_g = make_segments(int_scale=False, with_quant=False)
+        n = max(3, args.steps // 2)
+        t_is = timed_pass(is_g, n, 2)
+        t_fs = timed_pass(fs_g, n, 2)
+        speedup = t_fs / t_is
+        fs_detail = {a.name: round(b.elapsed_ms / max(a.elapsed_ms, 1e-9), 4) for a, b in zip(is_g, fs_g)}
+        del is_g, fs_g
+
+    # ---------------------------------------------------------------- CPU oracle on a bounded sample of the same step
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        n_layers = max(1, args.cpu_sample_layers)
+        host_w = {}
+        for idx, (name, (K, N)) in enumerate(linears):
+            host_w[name] = O.quantize_weights_int4_group(S.make_weights(1, N, K, S.seed_for(1, idx, 1)), GROUP,
+                                                         ALPHA_LOG2, O.SCALE_NORM)
+        host_x = {(M, name): S.make_activations(1, M, K, S.seed_for(1, idx, 2) + M)
+                  for M in BATCHES for idx, (name, (K, N)) in enumerate(linears)}
+        t0 = time.perf_counter()
+        cpu_bytes = 0
+        for _ in range(n_layers):
+            for M in BATCHES:
+                for name, (K, N) in linears:
+                    xq, sa = O.quantize_act_int8_token(host_x[(M, name)])
+                    hw = host_w[name]
+                    ref = O.gemm_w4a8_intscale(xq, sa, hw.qweight, hw.scale_i32, hw.chan_scale, GROUP, ALPHA_LOG2)
+                    cpu_bytes += S.algorithmic_bytes(M, N, K, GROUP) + 3 * M * K + 4 * M
+        dt = time.perf_counter() - t0
+        # the last oracle result doubles as a live parity check of the GPU path
+        a = acts[(BATCHES[-1], linears[-1][0])]
+        w = weights[linears[-1][0]]
+        P.is_quantize_act_int8_token(a["x"], a["xq"], a["sa"])
+        out, acc = P.is_gemm_w4a8_intscale(a["xq"], a["sa"], w["q"][0], w["si"][0], w["c"][0], GROUP, ALPHA_LOG2,
+                                           want_acc=True)
+        torch.cuda.synchronize()
+        acc_ok = bool(np.array_equal(acc.cpu().numpy(), ref.acc))
+        got = out.cpu().numpy().astype(np.float64)
+        rel = float(np.max(np.abs(got - ref.out) / np.maximum(np.abs(ref.out), 1e-3)))
+        cpu = dict(value=round(cpu_bytes / dt / 1e9, 3), unit="GB/s", cores=O.num_threads(), kind="oracle",
+                   sample=f"{n_layers} of {L} layers x 4 linears x M in {list(BATCHES)} (quantiser + integer-scale GEMM), "
+                          f"{dt:.1f} s",
+                   parity=dict(acc_bit_exact=acc_ok, max_rel_err=rel))
+
+    value = step_bytes / sec_per_step / 1e9
+    line = {
+        "metric": "W4A8 integer-scale GEMM TOPS + HBM GB/s (% roofline); speedup vs float-scale",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(1e3 * sec_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": "llama2-7b decode linears (qkv, o_proj, gate_up, down), W4 group-128 x A8 per-token, "
+                               f"alpha=2^{ALPHA_LOG2}, M in {list(BATCHES)}, {L} layers of distinct weights",
+                   "launch": "hip-graph" if use_graph else "eager", "scale_mode": "norm"},
+        "tops": round(step_ops / sec_per_step / 1e12, 3),
+        "hbm_frac": round(value / HBM_PEAK_GBS, 4),
+        "speedup_vs_floatscale": None if speedup is None else round(speedup, 4),
+        "floatscale_over_intscale_by_shape": fs_detail,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "shapes": shapes,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

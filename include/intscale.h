@@ -1,0 +1,128 @@
+/*
+ * intscale.h — C ABI of the fine-grained W4A8 linear layer with integer group scales on MI355X (gfx950).
+ *
+ * The layer follows the Integer Scale paper: int8 per-token activations times int4 weights quantised in groups
+ * of `group` along K, where every float group scale s_g is replaced by the integer INT(s_g * alpha) so that the
+ * per-group int32 partial sums are scaled and accumulated in int32 and converted to float once per output
+ * (Eq. (2), Table 2 column "Ours").  The float-scale form (Eq. (1), Table 2 column "Atom") is exported as the
+ * baseline, built on the same kernels.
+ *
+ * Conventions for every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller, 16-byte aligned, dense row-major.
+ *     The library allocates nothing, keeps no state between calls and never synchronises.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Return value: IS_OK, or a negative IS_ERR_* code.  Arguments are validated before any HIP call; on an
+ *     argument error nothing is enqueued and the outputs are untouched.
+ *   - Notation: X is [M,K] (tokens x in-features), W is [N,K] (out-features x in-features, so the layer is
+ *     X * W^T as in Eq. (1)); groups run along K; NG = K / group; alpha = 2^alpha_log2.
+ *   - Rounding is round-half-to-even everywhere; the quantisers divide in IEEE fp32.
+ *
+ * Canonical layouts
+ *   qweight    uint8 [N, K/2]   byte j of row n = q[n,2j] in bits 0-3 | q[n,2j+1] in bits 4-7, two's-complement nibbles
+ *   scale_f32  float [N, NG]    s[n,g] = max|w| over the group / 7                      (Appendix A.1, n = 4)
+ *   scale_i32  int32 [N, NG]    INT(s * alpha) (RAW) or INT(s / c[n] * alpha) (NORM)    (Eq. (2))
+ *   chan_scale float [N]        c[n]: 1 (RAW) or max_g s[n,g] (NORM)
+ *   xq         int8  [M, K]     a_scale float [M]: s_a[m] = max|x| over the row / 127    (Appendix A.1, n = 8)
+ *   out        fp16  [M, N]     acc int32 [M, N]
+ */
+#ifndef INTSCALE_H_
+#define INTSCALE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define IS_OK 0
+#define IS_ERR_INVALID_ARG (-1) /* NULL / misaligned pointer, non-positive or inconsistent sizes, bad enum */
+#define IS_ERR_UNSUPPORTED (-2) /* valid request outside what the kernels cover (see each function) */
+#define IS_ERR_WORKSPACE (-3)   /* workspace_bytes < is_gemm_workspace_bytes(...) or workspace NULL while needed */
+#define IS_ERR_HIP (-4)         /* a HIP call failed (no device, launch failure); see is_last_hip_error() */
+
+#define IS_SCALE_RAW 0  /* IS = INT(s * alpha), c = 1: Eq. (2) as printed */
+#define IS_SCALE_NORM 1 /* c[n] = max_g s[n,g]; IS = INT(s / c * alpha): scales normalised into (0,1] (Sec. 4.1) */
+
+#define IS_ALPHA_HEURISTIC (-1) /* alpha_log2 value that selects the amplifier search of Sec. 4.1 / Listing 1 */
+#define IS_ALPHA_LOG2_MAX 16
+
+/*
+ * Offline weight preparation: group-wise symmetric int4 quantisation (Appendix A.1, A.2; group size 128 in
+ * Sec. 5) followed by the integer-scale derivation INT(s * alpha) (Eq. (2)).
+ *   w_fp16        in   fp16 [N,K]
+ *   group         even, divides K
+ *   alpha_log2    0..16, or IS_ALPHA_HEURISTIC: the smallest i >= 0 with (smallest non-zero amplified value) * 2^i >= 1,
+ *                 capped at 16 (Sec. 4.1); this needs alpha_log2_dev
+ *   scale_mode    IS_SCALE_RAW or IS_SCALE_NORM
+ *   qweight, scale_f32, scale_i32, chan_scale   out, canonical layouts above
+ *   alpha_log2_dev  out, device int*, may be NULL unless the heuristic is requested: the log2 actually used
+ * An all-zero group gets s = 0, q = 0, IS = 0.  Inputs must be finite.
+ */
+int is_quantize_weights_int4_group(const void* w_fp16, int N, int K, int group, int alpha_log2, int scale_mode,
+                                   void* qweight, float* scale_f32, int32_t* scale_i32, float* chan_scale,
+                                   int* alpha_log2_dev, void* stream);
+
+/*
+ * Online activation quantisation: per-token symmetric int8 (Appendix A.1 with n = 8; per-token in Sec. 5.1).
+ *   x_fp16 in fp16 [M,K], K a multiple of 8;  xq out int8 [M,K];  a_scale out float [M].
+ * M = 0 is a no-op.  An all-zero row gets s_a = 0 and codes 0.  Inputs must be finite.
+ */
+int is_quantize_act_int8_token(const void* x_fp16, int M, int K, int8_t* xq, float* a_scale, void* stream);
+
+/*
+ * Fine-grained W4A8 GEMM with integer scales (Eq. (2); Table 2 "Ours"):
+ *   P[m,n,g] = sum_{k in group g} xq[m,k] * q[n,k]                    int32, exact
+ *   acc[m,n] = sum_g P[m,n,g] * scale_i32[n,g]                        int32, wraps modulo 2^32
+ *   out[m,n] = fp16( float(acc[m,n]) * a_scale[m] * chan_scale[n] * 2^-alpha_log2 )
+ *   chan_scale   may be NULL (all ones)
+ *   acc_out      may be NULL; otherwise receives the raw int32 accumulators [M,N]
+ *   workspace    device scratch of at least is_gemm_workspace_bytes(M,N,K,group) bytes (may be NULL when that is 0)
+ * Requirements: K and group multiples of 128 with group dividing K (group = K gives the coarse-grained GEMM of
+ * Table 2's first column); 0 <= alpha_log2 <= 30; N >= 1; M >= 0 (M = 0 is a no-op).
+ * Any int32 scale is accepted and multiplied exactly modulo 2^32.
+ */
+int is_gemm_w4a8_intscale(const int8_t* xq, const float* a_scale, const void* qweight, const int32_t* scale_i32,
+                          const float* chan_scale, int M, int N, int K, int group, int alpha_log2, void* out_fp16,
+                          int32_t* acc_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Fine-grained W4A8 GEMM with float scales, the baseline (Eq. (1); Table 2 "Atom"):
+ *   out[m,n] = fp16( a_scale[m] * sum_g float(P[m,n,g]) * scale_f32[n,g] )    accumulated in fp32
+ * Same tiling, layouts and requirements as is_gemm_w4a8_intscale.
+ */
+int is_gemm_w4a8_floatscale(const int8_t* xq, const float* a_scale, const void* qweight, const float* scale_f32,
+                            int M, int N, int K, int group, void* out_fp16, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+/* Scratch the two GEMMs above need for this shape (0 when they need none). Returns 0 for invalid shapes. */
+size_t is_gemm_workspace_bytes(int M, int N, int K, int group);
+
+/*
+ * Mixture-of-experts form (Sec. 5.4 measures Mixtral 8x7B): one launch over `num_experts` weight sets.
+ * Rows of xq are sorted by expert; rows [row_offsets[e], row_offsets[e+1]) use weight set e.
+ *   qweight [E,N,K/2], scale_i32 / scale_f32 [E,N,NG], chan_scale [E,N] (may be NULL)
+ *   row_offsets   device int32 [E+1], non-decreasing, row_offsets[0] = 0, row_offsets[E] = M_total
+ *   M_total       number of rows of xq / out (the host does not read row_offsets)
+ * Other arguments and requirements as for the plain GEMMs.
+ */
+int is_gemm_w4a8_intscale_grouped(const int8_t* xq, const float* a_scale, const void* qweight,
+                                  const int32_t* scale_i32, const float* chan_scale, const int32_t* row_offsets,
+                                  int num_experts, int M_total, int N, int K, int group, int alpha_log2,
+                                  void* out_fp16, int32_t* acc_out, void* workspace, size_t workspace_bytes,
+                                  void* stream);
+int is_gemm_w4a8_floatscale_grouped(const int8_t* xq, const float* a_scale, const void* qweight,
+                                    const float* scale_f32, const int32_t* row_offsets, int num_experts, int M_total,
+                                    int N, int K, int group, void* out_fp16, void* workspace, size_t workspace_bytes,
+                                    void* stream);
+size_t is_gemm_grouped_workspace_bytes(int num_experts, int M_total, int N, int K, int group);
+
+/* Human-readable name of a status code (static storage). */
+const char* is_status_string(int status);
+/* Text of the last HIP error this thread's calls ran into (static storage; "" if none). */
+const char* is_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INTSCALE_H_ */

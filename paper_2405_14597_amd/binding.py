@@ -1,0 +1,276 @@
+"""Thin Python binding of libintscale.so (the C ABI declared in include/intscale.h).
+
+Argument marshalling only: torch supplies device memory and the stream, every step of the layer runs in the
+library's HIP kernels.  There is no CPU or PyTorch fallback: if the library is missing and cannot be built, or a
+call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import NamedTuple, Optional
+
+from . import build as _build
+
+IS_OK = 0
+IS_ERR_INVALID_ARG = -1
+IS_ERR_UNSUPPORTED = -2
+IS_ERR_WORKSPACE = -3
+IS_ERR_HIP = -4
+IS_SCALE_RAW = 0
+IS_SCALE_NORM = 1
+IS_ALPHA_HEURISTIC = -1
+
+EXPORTED_SYMBOLS = (
+    "is_quantize_weights_int4_group",
+    "is_quantize_act_int8_token",
+    "is_gemm_w4a8_intscale",
+    "is_gemm_w4a8_floatscale",
+    "is_gemm_workspace_bytes",
+    "is_gemm_w4a8_intscale_grouped",
+    "is_gemm_w4a8_floatscale_grouped",
+    "is_gemm_grouped_workspace_bytes",
+    "is_status_string",
+    "is_last_hip_error",
+)
+
+
+class IntScaleError(RuntimeError):
+    def __init__(self, fn: str, status: int, detail: str = ""):
+        self.status = status
+        super().__init__(f"{fn} failed: {status_string(status)}" + (f" ({detail})" if detail else ""))
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libintscale.so; build it first only if no built library is there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build_library(force=True)
+    # The library and torch must share ONE HIP runtime (device pointers and streams cross between them), so torch's
+    # runtime is loaded first and libintscale.so's libamdhip64 dependency resolves to it.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
+    lib = ctypes.CDLL(_build.LIB_PATH)
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.is_quantize_weights_int4_group.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+    lib.is_quantize_weights_int4_group.restype = ci
+    lib.is_quantize_act_int8_token.argtypes = [vp, ci, ci, vp, vp, vp]
+    lib.is_quantize_act_int8_token.restype = ci
+    lib.is_gemm_w4a8_intscale.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.is_gemm_w4a8_intscale.restype = ci
+    lib.is_gemm_w4a8_floatscale.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, vp, vp, sz, vp]
+    lib.is_gemm_w4a8_floatscale.restype = ci
+    lib.is_gemm_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.is_gemm_workspace_bytes.restype = sz
+    lib.is_gemm_w4a8_intscale_grouped.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.is_gemm_w4a8_intscale_grouped.restype = ci
+    lib.is_gemm_w4a8_floatscale_grouped.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, sz, vp]
+    lib.is_gemm_w4a8_floatscale_grouped.restype = ci
+    lib.is_gemm_grouped_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.is_gemm_grouped_workspace_bytes.restype = sz
+    lib.is_status_string.argtypes = [ci]
+    lib.is_status_string.restype = ctypes.c_char_p
+    lib.is_last_hip_error.argtypes = []
+    lib.is_last_hip_error.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().is_status_string(int(status)).decode()
+
+
+def last_hip_error() -> str:
+    return load_library().is_last_hip_error().decode()
+
+
+def _check(fn: str, status: int) -> None:
+    if status != IS_OK:
+        raise IntScaleError(fn, status, last_hip_error() if status == IS_ERR_HIP else "")
+
+
+# --------------------------------------------------------------------------------------------------------------
+# torch-tensor level.  torch is imported lazily so that the symbol/ABI checks work without it.
+# --------------------------------------------------------------------------------------------------------------
+def _torch():
+    import torch
+    return torch
+
+
+def _stream_handle(stream) -> int:
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _p(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _require(t, dtype, shape, name):
+    if t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous() or not t.is_cuda:
+        raise ValueError(f"{name}: expected contiguous cuda tensor {dtype} {tuple(shape)}, got {t.dtype} "
+                         f"{tuple(t.shape)} on {t.device}")
+
+
+class QuantizedWeights(NamedTuple):
+    qweight: "object"      # uint8 [N, K/2] (or [E,N,K/2])
+    scale_f32: "object"    # float32 [N, K/G]
+    scale_i32: "object"    # int32 [N, K/G]
+    chan_scale: "object"   # float32 [N]
+    alpha_log2_dev: "object"  # int32 [1] on the device
+
+
+def is_quantize_weights_int4_group(w, group: int, alpha_log2: int, scale_mode: int = IS_SCALE_RAW, stream=None
+                                   ) -> QuantizedWeights:
+    torch = _torch()
+    N, K = w.shape
+    _require(w, torch.float16, (N, K), "w")
+    if group <= 0 or K % group != 0:
+        raise IntScaleError("is_quantize_weights_int4_group", IS_ERR_INVALID_ARG)
+    dev = w.device
+    q = torch.empty((N, K // 2), dtype=torch.uint8, device=dev)
+    s = torch.empty((N, K // group), dtype=torch.float32, device=dev)
+    si = torch.empty((N, K // group), dtype=torch.int32, device=dev)
+    c = torch.empty((N,), dtype=torch.float32, device=dev)
+    a_dev = torch.empty((4,), dtype=torch.int32, device=dev)
+    st = load_library().is_quantize_weights_int4_group(_p(w), N, K, group, alpha_log2, scale_mode, _p(q), _p(s), _p(si),
+                                                      _p(c), _p(a_dev), _stream_handle(stream))
+    _check("is_quantize_weights_int4_group", st)
+    return QuantizedWeights(q, s, si, c, a_dev[:1])
+
+
+def is_quantize_act_int8_token(x, xq=None, a_scale=None, stream=None):
+    torch = _torch()
+    M, K = x.shape
+    _require(x, torch.float16, (M, K), "x")
+    if xq is None:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    if a_scale is None:
+        a_scale = torch.empty((M,), dtype=torch.float32, device=x.device)
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    st = load_library().is_quantize_act_int8_token(_p(x), M, K, _p(xq), _p(a_scale), _stream_handle(stream))
+    _check("is_quantize_act_int8_token", st)
+    return xq, a_scale
+
+
+def is_gemm_workspace_bytes(M: int, N: int, K: int, group: int) -> int:
+    return int(load_library().is_gemm_workspace_bytes(M, N, K, group))
+
+
+def is_gemm_grouped_workspace_bytes(E: int, M_total: int, N: int, K: int, group: int) -> int:
+    return int(load_library().is_gemm_grouped_workspace_bytes(E, M_total, N, K, group))
+
+
+def _workspace(nbytes: int, device, workspace):
+    torch = _torch()
+    if workspace is not None:
+        return workspace, workspace.numel() * workspace.element_size()
+    if nbytes == 0:
+        return None, 0
+    ws = torch.empty((nbytes,), dtype=torch.uint8, device=device)
+    return ws, nbytes
+
+
+def is_gemm_w4a8_intscale(xq, a_scale, qweight, scale_i32, chan_scale, group: int, alpha_log2: int, out=None,
+                          acc_out=None, want_acc: bool = False, workspace=None, stream=None):
+    """Returns (out fp16 [M,N], acc int32 [M,N] or None)."""
+    torch = _torch()
+    M, K = xq.shape
+    N = qweight.shape[0]
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    _require(qweight, torch.uint8, (N, K // 2), "qweight")
+    _require(scale_i32, torch.int32, (N, K // group), "scale_i32")
+    if chan_scale is not None:
+        _require(chan_scale, torch.float32, (N,), "chan_scale")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    _require(out, torch.float16, (M, N), "out")
+    if acc_out is None and want_acc:
+        acc_out = torch.empty((M, N), dtype=torch.int32, device=xq.device)
+    if acc_out is not None:
+        _require(acc_out, torch.int32, (M, N), "acc_out")
+    ws, ws_bytes = _workspace(is_gemm_workspace_bytes(M, N, K, group), xq.device, workspace)
+    st = load_library().is_gemm_w4a8_intscale(_p(xq), _p(a_scale), _p(qweight), _p(scale_i32), _p(chan_scale), M, N, K,
+                                             group, alpha_log2, _p(out), _p(acc_out), _p(ws), ws_bytes,
+                                             _stream_handle(stream))
+    _check("is_gemm_w4a8_intscale", st)
+    return out, acc_out
+
+
+def is_gemm_w4a8_floatscale(xq, a_scale, qweight, scale_f32, group: int, out=None, workspace=None, stream=None):
+    torch = _torch()
+    M, K = xq.shape
+    N = qweight.shape[0]
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    _require(qweight, torch.uint8, (N, K // 2), "qweight")
+    _require(scale_f32, torch.float32, (N, K // group), "scale_f32")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    _require(out, torch.float16, (M, N), "out")
+    ws, ws_bytes = _workspace(is_gemm_workspace_bytes(M, N, K, group), xq.device, workspace)
+    st = load_library().is_gemm_w4a8_floatscale(_p(xq), _p(a_scale), _p(qweight), _p(scale_f32), M, N, K, group,
+                                               _p(out), _p(ws), ws_bytes, _stream_handle(stream))
+    _check("is_gemm_w4a8_floatscale", st)
+    return out
+
+
+def is_gemm_w4a8_intscale_grouped(xq, a_scale, qweight, scale_i32, chan_scale, row_offsets, group: int,
+                                  alpha_log2: int, out=None, acc_out=None, want_acc: bool = False, workspace=None,
+                                  stream=None):
+    torch = _torch()
+    M, K = xq.shape
+    E, N = qweight.shape[0], qweight.shape[1]
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    _require(qweight, torch.uint8, (E, N, K // 2), "qweight")
+    _require(scale_i32, torch.int32, (E, N, K // group), "scale_i32")
+    _require(row_offsets, torch.int32, (E + 1,), "row_offsets")
+    if chan_scale is not None:
+        _require(chan_scale, torch.float32, (E, N), "chan_scale")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    _require(out, torch.float16, (M, N), "out")
+    if acc_out is None and want_acc:
+        acc_out = torch.empty((M, N), dtype=torch.int32, device=xq.device)
+    ws, ws_bytes = _workspace(is_gemm_grouped_workspace_bytes(E, M, N, K, group), xq.device, workspace)
+    st = load_library().is_gemm_w4a8_intscale_grouped(_p(xq), _p(a_scale), _p(qweight), _p(scale_i32), _p(chan_scale),
+                                                     _p(row_offsets), E, M, N, K, group, alpha_log2, _p(out),
+                                                     _p(acc_out), _p(ws), ws_bytes, _stream_handle(stream))
+    _check("is_gemm_w4a8_intscale_grouped", st)
+    return out, acc_out
+
+
+def is_gemm_w4a8_floatscale_grouped(xq, a_scale, qweight, scale_f32, row_offsets, group: int, out=None,
+                                    workspace=None, stream=None):
+    torch = _torch()
+    M, K = xq.shape
+    E, N = qweight.shape[0], qweight.shape[1]
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    _require(qweight, torch.uint8, (E, N, K // 2), "qweight")
+    _require(scale_f32, torch.float32, (E, N, K // group), "scale_f32")
+    _require(row_offsets, torch.int32, (E + 1,), "row_offsets")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    _require(out, torch.float16, (M, N), "out")
+    ws, ws_bytes = _workspace(is_gemm_grouped_workspace_bytes(E, M, N, K, group), xq.device, workspace)
+    st = load_library().is_gemm_w4a8_floatscale_grouped(_p(xq), _p(a_scale), _p(qweight), _p(scale_f32),
+                                                       _p(row_offsets), E, M, N, K, group, _p(out), _p(ws), ws_bytes,
+                                                       _stream_handle(stream))
+    _check("is_gemm_w4a8_floatscale_grouped", st)
+    return out

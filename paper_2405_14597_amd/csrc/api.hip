@@ -1,0 +1,157 @@
+// C ABI of the library: argument validation (before any HIP call) and dispatch to the gfx950 kernels.
+#include <string.h>
+
+#include "is_common.h"
+
+using namespace intscale;
+
+namespace {
+
+thread_local char g_hip_error[256] = "";
+
+int hip_status(hipError_t e) {
+    if (e == hipSuccess) return IS_OK;
+    strncpy(g_hip_error, hipGetErrorString(e), sizeof(g_hip_error) - 1);
+    g_hip_error[sizeof(g_hip_error) - 1] = '\0';
+    return IS_ERR_HIP;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool ok_ptr(const void* p) { return p != nullptr && aligned16(p); }
+inline bool ok_opt(const void* p) { return p == nullptr || aligned16(p); }
+
+// Shape rules shared by all GEMM entry points. Returns IS_OK, IS_ERR_INVALID_ARG or IS_ERR_UNSUPPORTED.
+int check_gemm_shape(int M, int N, int K, int group) {
+    if (M < 0 || N <= 0 || K <= 0 || group <= 0) return IS_ERR_INVALID_ARG;
+    if (K % group != 0 || (K & 1) || (group & 1)) return IS_ERR_INVALID_ARG;
+    if (group % 128 != 0) return IS_ERR_UNSUPPORTED;  // the kernels consume K in steps of 128
+    if (M > (1 << 20)) return IS_ERR_UNSUPPORTED;  // launch-grid limit of the row-chunk dimension
+    return IS_OK;
+}
+
+// Regime selection by the number of token rows.
+hipError_t launch_gemm(const GemmArgs& a, bool int_scale, hipStream_t stream) {
+    return launch_gemm_skinny(a, int_scale, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* is_status_string(int status) {
+    switch (status) {
+        case IS_OK: return "IS_OK";
+        case IS_ERR_INVALID_ARG: return "IS_ERR_INVALID_ARG";
+        case IS_ERR_UNSUPPORTED: return "IS_ERR_UNSUPPORTED";
+        case IS_ERR_WORKSPACE: return "IS_ERR_WORKSPACE";
+        case IS_ERR_HIP: return "IS_ERR_HIP";
+        default: return "IS_ERR_UNKNOWN";
+    }
+}
+
+const char* is_last_hip_error(void) { return g_hip_error; }
+
+int is_quantize_weights_int4_group(const void* w_fp16, int N, int K, int group, int alpha_log2, int scale_mode,
+                                   void* qweight, float* scale_f32, int32_t* scale_i32, float* chan_scale,
+                                   int* alpha_log2_dev, void* stream) {
+    if (!ok_ptr(w_fp16) || !ok_ptr(qweight) || !ok_ptr(scale_f32) || !ok_ptr(scale_i32) || !ok_ptr(chan_scale))
+        return IS_ERR_INVALID_ARG;
+    if (N <= 0 || K <= 0 || group <= 0 || K % group != 0 || (K & 1) || (group & 1)) return IS_ERR_INVALID_ARG;
+    if (alpha_log2 < IS_ALPHA_HEURISTIC || alpha_log2 > IS_ALPHA_LOG2_MAX) return IS_ERR_INVALID_ARG;
+    if (scale_mode != IS_SCALE_RAW && scale_mode != IS_SCALE_NORM) return IS_ERR_INVALID_ARG;
+    if (alpha_log2 == IS_ALPHA_HEURISTIC && alpha_log2_dev == nullptr) return IS_ERR_INVALID_ARG;
+    if (alpha_log2_dev && (reinterpret_cast<uintptr_t>(alpha_log2_dev) & 3u)) return IS_ERR_INVALID_ARG;
+    return hip_status(launch_quantize_weights(static_cast<const __half*>(w_fp16), N, K, group, alpha_log2, scale_mode,
+                                              static_cast<uint8_t*>(qweight), scale_f32, scale_i32, chan_scale,
+                                              alpha_log2_dev, static_cast<hipStream_t>(stream)));
+}
+
+int is_quantize_act_int8_token(const void* x_fp16, int M, int K, int8_t* xq, float* a_scale, void* stream) {
+    if (M < 0 || K <= 0 || (K & 7)) return IS_ERR_INVALID_ARG;
+    if (M == 0) return IS_OK;
+    if (!ok_ptr(x_fp16) || !ok_ptr(xq) || a_scale == nullptr || (reinterpret_cast<uintptr_t>(a_scale) & 3u))
+        return IS_ERR_INVALID_ARG;
+    return hip_status(launch_quantize_act(static_cast<const __half*>(x_fp16), M, K, xq, a_scale,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+size_t is_gemm_workspace_bytes(int M, int N, int K, int group) {
+    (void)M; (void)N; (void)K; (void)group;
+    return 0;  // the cross-wave K reduction lives in LDS; no kernel needs global scratch
+}
+
+size_t is_gemm_grouped_workspace_bytes(int num_experts, int M_total, int N, int K, int group) {
+    (void)num_experts; (void)M_total; (void)N; (void)K; (void)group;
+    return 0;
+}
+
+static int gemm_common(const int8_t* xq, const float* a_scale, const void* qweight, const void* scale,
+                       const float* chan_scale, const int32_t* row_offsets, int num_experts, int M, int N, int K,
+                       int group, int alpha_log2, void* out_fp16, int32_t* acc_out, void* workspace,
+                       size_t workspace_bytes, void* stream, bool int_scale, bool grouped) {
+    const int shape = check_gemm_shape(M, N, K, group);
+    if (shape != IS_OK) return shape;
+    if (int_scale && (alpha_log2 < 0 || alpha_log2 > 30)) return IS_ERR_INVALID_ARG;
+    if (grouped && (num_experts <= 0 || num_experts > 65535)) return IS_ERR_INVALID_ARG;
+    if (!ok_opt(workspace)) return IS_ERR_INVALID_ARG;
+    const size_t need = grouped ? is_gemm_grouped_workspace_bytes(num_experts, M, N, K, group)
+                                : is_gemm_workspace_bytes(M, N, K, group);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return IS_ERR_WORKSPACE;
+    if (!ok_ptr(qweight) || !ok_ptr(scale) || !ok_opt(chan_scale)) return IS_ERR_INVALID_ARG;
+    if (grouped && (row_offsets == nullptr || (reinterpret_cast<uintptr_t>(row_offsets) & 3u)))
+        return IS_ERR_INVALID_ARG;
+    if (M == 0) return IS_OK;
+    if (!ok_ptr(xq) || a_scale == nullptr || (reinterpret_cast<uintptr_t>(a_scale) & 3u) || !ok_ptr(out_fp16) ||
+        !ok_opt(acc_out))
+        return IS_ERR_INVALID_ARG;
+
+    GemmArgs a;
+    a.xq = xq;
+    a.a_scale = a_scale;
+    a.qweight = static_cast<const uint8_t*>(qweight);
+    a.scale = scale;
+    a.chan_scale = chan_scale;
+    a.row_offsets = grouped ? row_offsets : nullptr;
+    a.out = static_cast<__half*>(out_fp16);
+    a.acc_out = acc_out;
+    a.M = M;
+    a.N = N;
+    a.K = K;
+    a.group = group;
+    a.alpha_log2 = int_scale ? alpha_log2 : 0;
+    a.num_experts = grouped ? num_experts : 1;
+    return hip_status(launch_gemm(a, int_scale, static_cast<hipStream_t>(stream)));
+}
+
+int is_gemm_w4a8_intscale(const int8_t* xq, const float* a_scale, const void* qweight, const int32_t* scale_i32,
+                          const float* chan_scale, int M, int N, int K, int group, int alpha_log2, void* out_fp16,
+                          int32_t* acc_out, void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_common(xq, a_scale, qweight, scale_i32, chan_scale, nullptr, 1, M, N, K, group, alpha_log2, out_fp16,
+                       acc_out, workspace, workspace_bytes, stream, true, false);
+}
+
+int is_gemm_w4a8_floatscale(const int8_t* xq, const float* a_scale, const void* qweight, const float* scale_f32,
+                            int M, int N, int K, int group, void* out_fp16, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+    return gemm_common(xq, a_scale, qweight, scale_f32, nullptr, nullptr, 1, M, N, K, group, 0, out_fp16, nullptr,
+                       workspace, workspace_bytes, stream, false, false);
+}
+
+int is_gemm_w4a8_intscale_grouped(const int8_t* xq, const float* a_scale, const void* qweight,
+                                  const int32_t* scale_i32, const float* chan_scale, const int32_t* row_offsets,
+                                  int num_experts, int M_total, int N, int K, int group, int alpha_log2,
+                                  void* out_fp16, int32_t* acc_out, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+    return gemm_common(xq, a_scale, qweight, scale_i32, chan_scale, row_offsets, num_experts, M_total, N, K, group,
+                       alpha_log2, out_fp16, acc_out, workspace, workspace_bytes, stream, true, true);
+}
+
+int is_gemm_w4a8_floatscale_grouped(const int8_t* xq, const float* a_scale, const void* qweight,
+                                    const float* scale_f32, const int32_t* row_offsets, int num_experts, int M_total,
+                                    int N, int K, int group, void* out_fp16, void* workspace, size_t workspace_bytes,
+                                    void* stream) {
+    return gemm_common(xq, a_scale, qweight, scale_f32, nullptr, row_offsets, num_experts, M_total, N, K, group, 0,
+                       out_fp16, nullptr, workspace, workspace_bytes, stream, false, true);
+}
+
+}  // extern "C"

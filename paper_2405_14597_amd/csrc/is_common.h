@@ -1,0 +1,39 @@
+// Shared declarations of the gfx950 implementation (host side of the C ABI and the kernels behind it).
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "intscale.h"
+
+namespace intscale {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+// Everything a GEMM launch needs. Plain data so that it can be passed by value to a kernel.
+struct GemmArgs {
+    const int8_t* xq;           // [M,K]
+    const float* a_scale;       // [M]
+    const uint8_t* qweight;     // [E,N,K/2]
+    const void* scale;          // int32 or float [E,N,NG]
+    const float* chan_scale;    // [E,N] or nullptr
+    const int32_t* row_offsets; // [E+1] or nullptr (plain GEMM)
+    __half* out;                // [M,N]
+    int32_t* acc_out;           // [M,N] or nullptr
+    int M, N, K, group;
+    int alpha_log2;
+    int num_experts;
+};
+
+// Launchers (defined next to their kernels). Each returns a hipError_t from the launch.
+hipError_t launch_quantize_act(const __half* x, int M, int K, int8_t* xq, float* a_scale, hipStream_t stream);
+hipError_t launch_quantize_weights(const __half* w, int N, int K, int group, int alpha_log2, int scale_mode,
+                                   uint8_t* qweight, float* scale_f32, int32_t* scale_i32, float* chan_scale,
+                                   int* alpha_log2_dev, hipStream_t stream);
+hipError_t launch_gemm_skinny(const GemmArgs& a, bool int_scale, hipStream_t stream);
+
+}  // namespace intscale

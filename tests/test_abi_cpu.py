@@ -1,0 +1,99 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the header declares, and
+rejects bad arguments before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2405_14597_amd as P
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "intscale.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(is_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_and_library_agree():
+    names = declared_functions()
+    assert set(names) == set(P.EXPORTED_SYMBOLS)
+    lib = ctypes.CDLL(P.library_path())
+    for n in names:
+        assert hasattr(lib, n), f"libintscale.so does not export {n}"
+
+
+def test_status_strings():
+    assert P.status_string(P.IS_OK) == "IS_OK"
+    assert P.status_string(P.IS_ERR_INVALID_ARG) == "IS_ERR_INVALID_ARG"
+    assert P.status_string(P.IS_ERR_UNSUPPORTED) == "IS_ERR_UNSUPPORTED"
+    assert P.status_string(P.IS_ERR_WORKSPACE) == "IS_ERR_WORKSPACE"
+    assert P.status_string(P.IS_ERR_HIP) == "IS_ERR_HIP"
+    assert P.status_string(-99) == "IS_ERR_UNKNOWN"
+
+
+A = 0x10000  # a fake, 16-byte aligned "device pointer": validation must fail before it is ever dereferenced
+
+
+def gemm_is(lib, xq=A, sa=A, qw=A, sc=A, cs=None, M=8, N=16, K=256, G=128, a=10, out=A, acc=None, ws=None, wsb=0):
+    return lib.is_gemm_w4a8_intscale(xq, sa, qw, sc, cs, M, N, K, G, a, out, acc, ws, wsb, None)
+
+
+def test_gemm_argument_validation():
+    lib = P.load_library()
+    bad = P.IS_ERR_INVALID_ARG
+    assert gemm_is(lib, xq=None) == bad
+    assert gemm_is(lib, sa=None) == bad
+    assert gemm_is(lib, qw=None) == bad
+    assert gemm_is(lib, sc=None) == bad
+    assert gemm_is(lib, out=None) == bad
+    assert gemm_is(lib, xq=A + 4) == bad            # misaligned
+    assert gemm_is(lib, cs=A + 8) == bad
+    assert gemm_is(lib, M=-1) == bad
+    assert gemm_is(lib, N=0) == bad
+    assert gemm_is(lib, K=0) == bad
+    assert gemm_is(lib, K=200) == bad               # K not a multiple of group
+    assert gemm_is(lib, a=-1) == bad
+    assert gemm_is(lib, a=31) == bad
+    assert gemm_is(lib, K=192, G=64) == P.IS_ERR_UNSUPPORTED   # groups narrower than the kernels' K step
+    assert gemm_is(lib, M=0) == P.IS_OK             # empty batch: nothing to do, nothing launched
+    assert lib.is_gemm_workspace_bytes(8, 16, 256, 128) == 0
+
+
+def test_floatscale_and_grouped_argument_validation():
+    lib = P.load_library()
+    bad = P.IS_ERR_INVALID_ARG
+    assert lib.is_gemm_w4a8_floatscale(A, A, A, None, 8, 16, 256, 128, A, None, 0, None) == bad
+    assert lib.is_gemm_w4a8_floatscale(A, A, A, A, 8, 16, 100, 128, A, None, 0, None) == bad
+    assert lib.is_gemm_w4a8_intscale_grouped(A, A, A, A, None, None, 4, 8, 16, 256, 128, 10, A, None, None, 0, None) == bad
+    assert lib.is_gemm_w4a8_intscale_grouped(A, A, A, A, None, A, 0, 8, 16, 256, 128, 10, A, None, None, 0, None) == bad
+    assert lib.is_gemm_w4a8_floatscale_grouped(A, A, A, A, A + 2, 4, 8, 16, 256, 128, A, None, 0, None) == bad
+
+
+def test_quantizer_argument_validation():
+    lib = P.load_library()
+    bad = P.IS_ERR_INVALID_ARG
+    q = lambda **kw: lib.is_quantize_weights_int4_group(
+        kw.get("w", A), kw.get("N", 16), kw.get("K", 256), kw.get("G", 128), kw.get("a", 10), kw.get("mode", 0),
+        kw.get("q", A), kw.get("s", A), kw.get("si", A), kw.get("c", A), kw.get("adev", None), None)
+    assert q(w=None) == bad and q(q=None) == bad and q(s=None) == bad and q(si=None) == bad and q(c=None) == bad
+    assert q(N=0) == bad and q(K=255) == bad and q(G=100) == bad and q(G=0) == bad
+    assert q(a=17) == bad and q(a=-2) == bad and q(mode=2) == bad
+    assert q(a=-1, adev=None) == bad                # the amplifier search needs somewhere to put its result
+    x = lambda **kw: lib.is_quantize_act_int8_token(kw.get("x", A), kw.get("M", 4), kw.get("K", 256), kw.get("xq", A),
+                                                    kw.get("sa", A), None)
+    assert x(x=None) == bad and x(xq=None) == bad and x(sa=None) == bad
+    assert x(K=100) == bad and x(M=-1) == bad
+    assert x(M=0) == P.IS_OK
+
+
+def test_missing_device_is_reported_not_hidden():
+    """With valid arguments the call reaches HIP; without a GPU that must surface as IS_ERR_HIP, never as success."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    lib = P.load_library()
+    assert gemm_is(lib) == P.IS_ERR_HIP
+    assert P.last_hip_error() != ""

@@ -1,0 +1,245 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on the same seeded
+inputs.  Integer results (codes, integer scales, int32 accumulators) must be bit-exact; fp16 outputs must satisfy
+|gpu - ref| <= 1e-2 |ref| + 2^-24 (the tolerance the target states; the observed error is checked against the much
+smaller bound that one fp16 rounding plus three fp32 roundings allow).
+"""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from oracle import oracle as O
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+G = 128
+
+
+@pytest.fixture(scope="module")
+def P():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2405_14597_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def check_out(got16, ref64, what=""):
+    got = got16.astype(np.float64)
+    big = np.abs(ref64) > 65000.0      # at the edge of (or beyond) the fp16 range: same sign, saturated or inf
+    if np.any(big):
+        assert bool(np.all(np.sign(got[big]) == np.sign(ref64[big]))) and bool(np.all(np.abs(got[big]) > 64900.0)), what
+    err = np.abs(got[~big] - ref64[~big])
+    ref = np.abs(ref64[~big])
+    ok = bool(np.all(err <= 1e-2 * ref + 2.0 ** -24))
+    assert ok, f"{what}: fp16 output outside 1e-2 relative (max abs err {err.max()})"
+    # derived bound: half an fp16 ulp (2^-11 relative, 2^-25 absolute in the subnormal range) plus fp32 slack
+    ok = bool(np.all(err <= (2.0 ** -11 + 2.0 ** -20) * ref + 2.0 ** -24))
+    assert ok, f"{what}: more than one fp16 rounding (max abs err {err.max()})"
+
+
+def check_fs(got16, fs, what=""):
+    got = got16.astype(np.float64)
+    err = np.abs(got - fs.out)
+    # fp32 accumulation over K/G terms in a different order than the oracle's double sum
+    tol = 1e-2 * np.abs(fs.out) + 2e-5 * fs.abs_sum + 2.0 ** -24
+    ok = bool(np.all(err <= tol))
+    assert ok, f"{what}: float-scale output outside tolerance (max abs err {err.max()})"
+
+
+def rand_quantised(rng, M, N, K, is_lo=0, is_hi=1025):
+    xq = rng.integers(-128, 128, size=(M, K), dtype=np.int64).astype(np.int8)
+    q = rng.integers(-8, 8, size=(N, K), dtype=np.int64).astype(np.int8)
+    IS = rng.integers(is_lo, is_hi, size=(N, K // G), dtype=np.int64).astype(np.int32)
+    s = (rng.random((N, K // G)) * 0.02 + 1e-4).astype(np.float32)
+    sa = (rng.random(M) * 0.1 + 1e-3).astype(np.float32)
+    c = (rng.random(N) * 0.05 + 1e-3).astype(np.float32)
+    return xq, O.pack_int4(q), IS, s, sa, c
+
+
+# ------------------------------------------------------------------------------------------------ quantisers
+@pytest.mark.parametrize("M,K,kind", [(1, 4096, "outlier"), (8, 4096, "outlier"), (33, 11008, "outlier"),
+                                      (64, 1024, "student"), (5, 8, "outlier"), (130, 28672, "student")])
+def test_act_quantizer_bit_exact(P, M, K, kind):
+    x = S.activations_outlier(M, K, 11) if kind == "outlier" else S.activations_student_t(M, K, 12)
+    if M > 2:
+        x[1] = 0          # an all-zero token row
+        x[2, 0] = 60000   # a large outlier
+    xq_ref, sa_ref = O.quantize_act_int8_token(x)
+    xq, sa = P.is_quantize_act_int8_token(dev(x))
+    assert np.array_equal(host(xq), xq_ref)
+    assert np.array_equal(host(sa), sa_ref)
+
+
+def test_act_quantizer_empty(P):
+    x = torch.empty((0, 4096), dtype=torch.float16, device="cuda:0")
+    xq, sa = P.is_quantize_act_int8_token(x)
+    assert xq.shape == (0, 4096) and sa.shape == (0,)
+
+
+@pytest.mark.parametrize("N,K,group,alpha,mode", [
+    (96, 1024, 128, 10, 0), (96, 1024, 128, 10, 1), (272, 4096, 128, 6, 0), (272, 4096, 128, 12, 1),
+    (33, 2048, 32, 8, 1), (17, 512, 512, 10, 0), (64, 11008, 128, 10, 1), (40, 256, 2, 10, 0)])
+def test_weight_quantizer_bit_exact(P, N, K, group, alpha, mode):
+    w = S.weights_gaussian(N, K, 21, outlier_col_frac=0.005)
+    w[3, : min(K, 2 * group)] = 0            # zero groups
+    if N > 8:
+        w[7] = 0                             # a zero row
+    ref = O.quantize_weights_int4_group(w, group, alpha, mode)
+    got = P.is_quantize_weights_int4_group(dev(w), group, alpha, mode)
+    assert np.array_equal(host(got.qweight), ref.qweight)
+    assert np.array_equal(host(got.scale_f32), ref.scale_f32)
+    assert np.array_equal(host(got.scale_i32), ref.scale_i32)
+    assert np.array_equal(host(got.chan_scale), ref.chan_scale)
+    assert int(host(got.alpha_log2_dev)[0]) == alpha
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_weight_quantizer_amplifier_search(P, mode):
+    w = S.weights_gaussian(128, 2048, 22)
+    ref = O.quantize_weights_int4_group(w, G, -1, mode)
+    got = P.is_quantize_weights_int4_group(dev(w), G, P.IS_ALPHA_HEURISTIC, mode)
+    assert int(host(got.alpha_log2_dev)[0]) == ref.alpha_log2
+    assert np.array_equal(host(got.scale_i32), ref.scale_i32)
+    assert np.array_equal(host(got.qweight), ref.qweight)
+
+
+# ------------------------------------------------------------------------------------------------ GEMM, oracle-quantised inputs
+SHAPES = [(1, 16, 128), (1, 4096, 4096), (8, 4096, 4096), (16, 272, 1024), (17, 40, 1024), (33, 100, 2048),
+          (64, 4096, 1024), (64, 48, 11008), (100, 33, 1536), (7, 1, 256), (48, 2064, 3584)]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_gemm_intscale_bit_exact_acc(P, M, N, K):
+    rng = np.random.default_rng(1000 + M + N + K)
+    xq, qw, IS, s, sa, c = rand_quantised(rng, M, N, K)
+    ref = O.gemm_w4a8_intscale(xq, sa, qw, IS, c, G, 10)
+    out, acc = P.is_gemm_w4a8_intscale(dev(xq), dev(sa), dev(qw), dev(IS), dev(c), G, 10, want_acc=True)
+    assert np.array_equal(host(acc), ref.acc), "int32 accumulators differ"
+    check_out(host(out), ref.out, f"M{M} N{N} K{K}")
+    # without a channel scale and without the accumulator export
+    ref1 = O.gemm_w4a8_intscale(xq, sa, qw, IS, None, G, 7)
+    out1, acc1 = P.is_gemm_w4a8_intscale(dev(xq), dev(sa), dev(qw), dev(IS), None, G, 7)
+    assert acc1 is None
+    check_out(host(out1), ref1.out)
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_gemm_floatscale(P, M, N, K):
+    rng = np.random.default_rng(2000 + M + N + K)
+    xq, qw, IS, s, sa, c = rand_quantised(rng, M, N, K)
+    fs = O.gemm_w4a8_floatscale(xq, sa, qw, s, G)
+    out = P.is_gemm_w4a8_floatscale(dev(xq), dev(sa), dev(qw), dev(s), G)
+    check_fs(host(out), fs, f"M{M} N{N} K{K}")
+
+
+def test_gemm_extreme_codes_and_wide_scales(P):
+    """All codes at -128 / -8 (the largest partial sums), negative and wider-than-24-bit integer scales, wrap-around."""
+    M, N, K = 16, 32, 4096
+    xq = np.full((M, K), -128, np.int8)
+    q = np.full((N, K), -8, np.int8)
+    xq[1::2] = 127
+    q[::3] = 7
+    rng = np.random.default_rng(5)
+    sa = np.ones(M, np.float32)
+    for IS in (np.full((N, K // G), 511, np.int32), np.full((N, K // G), 40000, np.int32),
+               rng.integers(-2 ** 31, 2 ** 31, size=(N, K // G), dtype=np.int64).astype(np.int32),
+               rng.integers(-2 ** 23, 2 ** 23, size=(N, K // G), dtype=np.int64).astype(np.int32)):
+        ref = O.gemm_w4a8_intscale(xq, sa, O.pack_int4(q), IS, None, G, 10)
+        out, acc = P.is_gemm_w4a8_intscale(dev(xq), dev(sa), dev(O.pack_int4(q)), dev(IS), None, G, 10, want_acc=True)
+        assert np.array_equal(host(acc), ref.acc)
+        check_out(host(out), ref.out)
+
+
+@pytest.mark.parametrize("group", [256, 512, 1024])
+def test_gemm_wider_groups_and_coarse_grained(P, group):
+    """group = K is the coarse-grained GEMM (Table 2, first column)."""
+    M, N, K = 24, 80, 1024
+    rng = np.random.default_rng(group)
+    xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+    q = rng.integers(-8, 8, size=(N, K)).astype(np.int8)
+    IS = rng.integers(0, 300, size=(N, K // group)).astype(np.int32)
+    s = rng.random((N, K // group)).astype(np.float32) * 0.01
+    sa = rng.random(M).astype(np.float32)
+    ref = O.gemm_w4a8_intscale(xq, sa, O.pack_int4(q), IS, None, group, 8)
+    out, acc = P.is_gemm_w4a8_intscale(dev(xq), dev(sa), dev(O.pack_int4(q)), dev(IS), None, group, 8, want_acc=True)
+    assert np.array_equal(host(acc), ref.acc)
+    check_out(host(out), ref.out)
+    fs = O.gemm_w4a8_floatscale(xq, sa, O.pack_int4(q), s, group)
+    check_fs(host(P.is_gemm_w4a8_floatscale(dev(xq), dev(sa), dev(O.pack_int4(q)), dev(s), group)), fs)
+
+
+def test_gemm_empty_batch(P):
+    rng = np.random.default_rng(3)
+    xq, qw, IS, s, sa, c = rand_quantised(rng, 1, 16, 128)
+    e8 = torch.empty((0, 128), dtype=torch.int8, device="cuda:0")
+    e32 = torch.empty((0,), dtype=torch.float32, device="cuda:0")
+    out, _ = P.is_gemm_w4a8_intscale(e8, e32, dev(qw), dev(IS), None, G, 10)
+    assert out.shape == (0, 16)
+
+
+def test_gemm_repeatable(P):
+    rng = np.random.default_rng(4)
+    xq, qw, IS, s, sa, c = rand_quantised(rng, 32, 4096, 4096)
+    args = (dev(xq), dev(sa), dev(qw), dev(IS), dev(c), G, 10)
+    out0, acc0 = P.is_gemm_w4a8_intscale(*args, want_acc=True)
+    fs0 = P.is_gemm_w4a8_floatscale(args[0], args[1], args[2], dev(s), G)
+    for _ in range(3):
+        out1, acc1 = P.is_gemm_w4a8_intscale(*args, want_acc=True)
+        fs1 = P.is_gemm_w4a8_floatscale(args[0], args[1], args[2], dev(s), G)
+        assert torch.equal(acc0, acc1) and torch.equal(out0, out1) and torch.equal(fs0, fs1)
+
+
+# ------------------------------------------------------------------------------------------------ grouped (mixture of experts)
+@pytest.mark.parametrize("counts", [[5, 0, 17, 64, 1, 0, 33, 8], [0, 0, 3], [130, 2]])
+def test_grouped_gemm(P, counts):
+    E, N, K = len(counts), 48, 1024
+    rng = np.random.default_rng(sum(counts))
+    M = sum(counts)
+    off = np.zeros(E + 1, np.int32)
+    off[1:] = np.cumsum(counts)
+    xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+    sa = (rng.random(M) + 0.01).astype(np.float32)
+    q = np.stack([O.pack_int4(rng.integers(-8, 8, size=(N, K)).astype(np.int8)) for _ in range(E)])
+    IS = rng.integers(0, 1025, size=(E, N, K // G)).astype(np.int32)
+    s = (rng.random((E, N, K // G)) * 0.01).astype(np.float32)
+    c = (rng.random((E, N)) + 0.01).astype(np.float32)
+    acc_ref, out_ref = O.gemm_w4a8_intscale_grouped(xq, sa, q, IS, c, off, G, 10)
+    out, acc = P.is_gemm_w4a8_intscale_grouped(dev(xq), dev(sa), dev(q), dev(IS), dev(c), dev(off), G, 10, want_acc=True)
+    assert np.array_equal(host(acc), acc_ref)
+    assert np.array_equal(host(out), out_ref) or np.allclose(host(out).astype(np.float64), out_ref.astype(np.float64),
+                                                             rtol=2e-3, atol=2.0 ** -24)
+    fs_ref, fs_mag = O.gemm_w4a8_floatscale_grouped(xq, sa, q, s, off, G)
+    fs = host(P.is_gemm_w4a8_floatscale_grouped(dev(xq), dev(sa), dev(q), dev(s), dev(off), G)).astype(np.float64)
+    assert np.all(np.abs(fs - fs_ref) <= 1e-2 * np.abs(fs_ref) + 2e-5 * fs_mag + 2.0 ** -24)
+
+
+# ------------------------------------------------------------------------------------------------ end to end, GPU-quantised
+def test_config0_end_to_end(P):
+    """M=8, K=N=4096, group 128, alpha 2^10: fp16 in, fp16 out, every stage compared."""
+    sh = S.config_shapes(0)[0]
+    x = S.make_activations(0, sh.M, sh.K, S.seed_for(0, 0, 0))
+    w = S.make_weights(0, sh.N, sh.K, S.seed_for(0, 0, 1))
+    for mode in (O.SCALE_RAW, O.SCALE_NORM):
+        xq_r, sa_r = O.quantize_act_int8_token(x)
+        qw_r = O.quantize_weights_int4_group(w, G, 10, mode)
+        ref = O.gemm_w4a8_intscale(xq_r, sa_r, qw_r.qweight, qw_r.scale_i32, qw_r.chan_scale, G, 10)
+        fs_r = O.gemm_w4a8_floatscale(xq_r, sa_r, qw_r.qweight, qw_r.scale_f32, G)
+        xq, sa = P.is_quantize_act_int8_token(dev(x))
+        qw = P.is_quantize_weights_int4_group(dev(w), G, 10, mode)
+        out, acc = P.is_gemm_w4a8_intscale(xq, sa, qw.qweight, qw.scale_i32, qw.chan_scale, G, 10, want_acc=True)
+        fs = P.is_gemm_w4a8_floatscale(xq, sa, qw.qweight, qw.scale_f32, G)
+        assert np.array_equal(host(xq), xq_r) and np.array_equal(host(sa), sa_r)
+        assert np.array_equal(host(qw.qweight), qw_r.qweight) and np.array_equal(host(qw.scale_i32), qw_r.scale_i32)
+        assert np.array_equal(host(acc), ref.acc)
+        check_out(host(out), ref.out)
+        check_fs(host(fs), fs_r)
+        assert ref.max_prefix.max() < 2 ** 31
