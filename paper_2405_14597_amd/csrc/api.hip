@@ -1,4 +1,5 @@
 // C ABI of the library: argument validation (before any HIP call) and dispatch to the gfx950 kernels.
+#include <stdlib.h>
 #include <string.h>
 
 #include "is_common.h"
@@ -26,11 +27,19 @@ int check_gemm_shape(int M, int N, int K, int group) {
     if (K % group != 0 || (K & 1) || (group & 1)) return IS_ERR_INVALID_ARG;
     if (group % 128 != 0) return IS_ERR_UNSUPPORTED;  // the kernels consume K in steps of 128
     if (M > (1 << 20)) return IS_ERR_UNSUPPORTED;  // launch-grid limit of the row-chunk dimension
+    // the kernels address each tensor (one expert's weights and scales) with 32-bit byte offsets below 2 GB
+    if ((long long)N * (K / 2) >= (1LL << 31) || (long long)N * (K / group) * 4 >= (1LL << 31) || K > (1 << 20))
+        return IS_ERR_UNSUPPORTED;
     return IS_OK;
 }
 
 // Regime selection by the number of token rows.
 hipError_t launch_gemm(const GemmArgs& a, bool int_scale, hipStream_t stream) {
+    // INTSCALE_FORCE_KERNEL=general routes everything to the general kernel (used by the tests to cover it).
+    const char* force = getenv("INTSCALE_FORCE_KERNEL");
+    const bool general_only = force && strcmp(force, "general") == 0;
+    hipError_t err = hipSuccess;
+    if (!general_only && try_launch_gemm_decode(a, int_scale, stream, &err)) return err;
     return launch_gemm_skinny(a, int_scale, stream);
 }
 

@@ -1,0 +1,363 @@
+// Decode regime (at most 64 token rows) of the fine-grained W4A8 GEMM: a persistent, activation-stationary kernel.
+// Integer-scale form: Eq. (2) / Table 2 "Ours" of the Integer Scale paper; float-scale form: Eq. (1) / Table 2
+// "Atom".
+//
+// Why this shape.  With so few token rows the layer is a stream of packed int4 weights out of HBM, read once.  At
+// 10 us per launch what decides the speed is (1) how many bytes every CU keeps in flight, (2) that all CUs finish
+// together and (3) how many dependent memory latencies sit on the critical path.  So:
+//   - one workgroup of W waves per CU, launched once ("persistent"); workgroup j owns the 16-row weight tiles
+//     j, j+G, j+2G, ... (G = number of workgroups), so the CUs carry equal shares to within one tile;
+//   - the W waves of a workgroup split K on group boundaries; a wave keeps the activations of its K range in
+//     registers for the whole kernel (MFMA-ready, loaded once), so its only stream is the weights and group scales
+//     of its K range, tile after tile, in a rotating prefetch DT tiles deep;
+//   - the waves' partial accumulators of a tile meet in LDS (two buffers, one barrier per tile); int32 adds are
+//     order-free so the split never changes a bit, and the float-scale partials are added in wave order;
+//   - the epilogue (the one int->float conversion of Eq. (2), times s_a[m] * c[n] / alpha) is spread over the
+//     workgroup's threads, one output each, with its scalars fetched ahead of time.
+//
+// MFMA mapping (v_mfma_i32_16x16x64_i8): operand A = 16 token rows, operand B = 16 weight rows; lane l feeds
+// row/column (l & 15) and K slice (l >> 4); its 4 results are weight row (l & 15), token rows 4*(l >> 4)..+3.
+// A dot product does not care about the order of its terms, so lane-group kb simply takes the 32 consecutive
+// K-indices [32*kb, 32*kb+32) of a 128-wide step, even ones in one MFMA and odd ones in the next: each lane gets its
+// 32 int4 weights with one 16-byte load from the canonical row-major packing.
+//
+// int4 -> int8: a nibble in the high half of a byte is 16*q as a signed byte ((p << 4) & 0xF0F0F0F0 for even k,
+// p & 0xF0F0F0F0 for odd k).  The MFMA pair returns 16*P exactly (|16 P| <= 2^21), one shift recovers P.
+//
+// The scale step runs once per 128-wide step with that step's group scale; for groups wider than 128 this is the
+// same integer by distributivity ((P1 + P2) * s = P1 * s + P2 * s modulo 2^32).
+#include "is_common.h"
+
+namespace intscale {
+namespace {
+
+constexpr int kStepK = 128;
+constexpr int kOutOfRange = (int)0x80000000u;  // a buffer offset past every descriptor here: the load returns 0
+
+using rsrc_t = __amdgpu_buffer_rsrc_t;
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, size_t bytes) {
+    const unsigned n = bytes > 0x7FFFFFFFull ? 0x7FFFFFFFu : (unsigned)bytes;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, n, 0x00020000);
+}
+
+__device__ __forceinline__ int pick_even(uint32_t lo, uint32_t hi) { return (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u); }
+__device__ __forceinline__ int pick_odd(uint32_t lo, uint32_t hi) { return (int)__builtin_amdgcn_perm(hi, lo, 0x07050301u); }
+
+// Workgroup barrier that only waits for this wave's LDS traffic.  __syncthreads() would also drain every global
+// load in flight (s_waitcnt vmcnt(0)) and with it the prefetch that this kernel lives on.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// MT: 16-row token tiles.  XS: steps of K a wave owns at most (its activations stay in 8*XS*MT registers).
+// DT: weight tiles in flight per wave.
+template <int MT, int XS, int DT, bool INT_SCALE>
+__global__ __launch_bounds__(1024) void gemm_decode_kernel(GemmArgs a, DecodePlan p) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    using acc_t = typename std::conditional<INT_SCALE, int, float>::type;
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int W = p.waves;
+    const int T = W * kWave;
+    const int li = lane & 15, kb = lane >> 4;
+    const int NG = p.num_groups;
+    const int row_bytes = a.K >> 1;
+    const int G = gridDim.x;
+    const int tile0 = blockIdx.x;
+    const int my_tiles = p.tiles_q + ((int)blockIdx.x < p.tiles_r ? 1 : 0);  // >= 1: at most `tiles` workgroups run
+
+    // K range of this wave: whole groups, the first p.gr waves take one more.
+    const int g0 = wave * p.gq + min(wave, p.gr);
+    const int ng = p.gq + (wave < p.gr ? 1 : 0);
+    const int s0 = g0 * p.spg;
+    const int ns = ng * p.spg;  // <= XS by construction of the plan
+
+    const rsrc_t wres = make_rsrc(a.qweight, (size_t)a.N * row_bytes);
+    const rsrc_t sres = make_rsrc(a.scale, (size_t)a.N * NG * 4);
+    const rsrc_t xres = make_rsrc(a.xq, (size_t)a.M * a.K);
+    const rsrc_t cres = make_rsrc(a.chan_scale, a.chan_scale ? (size_t)a.N * 4 : 0);
+
+    // LDS: two buffers of partial accumulators [W][MT][64 lanes][4], then two buffers of one tile's group scales
+    // (16 rows x NG, rows padded by one word so that the 16 rows a wave reads fall into different banks).
+    int* lds = reinterpret_cast<int*>(smem_raw);
+    const int part_ints = W * MT * kWave * 4;
+    const int srow_ints = NG + 1;
+    int* lds_scale = lds + 2 * part_ints;
+    const int scale_ints = 16 * srow_ints;
+
+    // ---- role of this thread in the epilogue: one output (m_out, tile*16 + n_out) per tile
+    const int n_out = threadIdx.x & 15;
+    const int m_out = threadIdx.x >> 4;                 // 0 .. 16*MT-1 for the threads that take part
+    const bool writer = threadIdx.x < 256 * MT && m_out < a.M;
+    const float sa_out = writer ? a.a_scale[m_out] : 0.0f;
+    const float inv_alpha = __int_as_float((127 - a.alpha_log2) << 23);  // 2^-alpha_log2, exact
+    // where that output sits in a wave's partials: tile t, lane (4 rows per lane-group), register j
+    const int src_slot = ((m_out >> 4) * kWave + ((m_out & 15) >> 2) * 16 + n_out) * 4 + (m_out & 3);
+
+    // ---- role of this thread in staging a tile's group scales: the tile's 16 x NG scales are one contiguous block
+    // of the scale tensor; thread u copies words u and u + T of it (16 * NG <= 2 * T is checked by the host).
+    int stage_src[2], stage_dst[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int f = threadIdx.x + j * T;
+        const int r = f / NG;
+        stage_src[j] = f < 16 * NG ? f * 4 : kOutOfRange;
+        stage_dst[j] = f < 16 * NG ? r * srow_ints + (f - r * NG) : -1;
+    }
+
+    // ---- weight stream
+    const int woff = li * row_bytes + s0 * (kStepK / 2) + kb * 16;  // inside a tile; the tile base is a scalar
+    int scale_idx[XS];  // LDS word of the group scale of step i for this lane's weight row
+    {
+        int g = 0, sub = 0;
+#pragma unroll
+        for (int i = 0; i < XS; ++i) {
+            scale_idx[i] = li * srow_ints + g0 + g;
+            if (++sub == p.spg) {
+                sub = 0;
+                ++g;
+            }
+        }
+    }
+
+    v4i wq[DT][XS];
+    int scv[DT][2];
+    float cs[DT];
+
+    auto issue = [&](int slot, int tile) {
+        // The scale block first: it is needed one tile earlier than the weights (it goes through LDS).
+        // Rows past N (ragged last tile) read as zero.
+        const int sbase = tile * 16 * NG * 4;
+        const int s_limit = (a.N - tile * 16) * NG * 4;  // bytes of this tile's block that exist
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            scv[slot][j] = __builtin_amdgcn_raw_buffer_load_b32(sres, stage_src[j] < s_limit ? stage_src[j] : kOutOfRange, sbase, 0);
+        const bool row_ok = tile * 16 + li < a.N;
+        const int wbase = tile * 16 * row_bytes;
+#pragma unroll
+        for (int i = 0; i < XS; ++i)
+            wq[slot][i] = __builtin_amdgcn_raw_buffer_load_b128(wres, (row_ok && i < ns) ? woff + i * (kStepK / 2) : kOutOfRange, wbase, 0);
+        if constexpr (INT_SCALE) {
+            // channel scale of this thread's output column; columns past N (or no channel scales at all) read 0
+            const bool col_ok = writer && tile * 16 + n_out < a.N;
+            cs[slot] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(cres, col_ok ? n_out * 4 : kOutOfRange, tile * 64, 0));
+        }
+    };
+    auto stage_scales = [&](int slot, int buf) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            if (stage_dst[j] >= 0) lds_scale[buf * scale_ints + stage_dst[j]] = scv[slot][j];
+    };
+
+    // First requests of the stream go out before anything else that waits on memory.
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+        if (dt < my_tiles) issue(dt, tile0 + dt * G);
+    __builtin_amdgcn_sched_barrier(0);  // keep the compiler from hoisting the activation loads above the stream's
+
+    // ---- activations of this wave's K range, MFMA-ready, loaded once
+    v4i x_even[XS][MT], x_odd[XS][MT];
+#pragma unroll
+    for (int i = 0; i < XS; ++i)
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            const int m = 16 * t + li;
+            const int off = (i < ns && m < a.M) ? m * a.K + (s0 + i) * kStepK + kb * 32 : kOutOfRange;
+            const v4i x0 = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 0, 0);
+            const v4i x1 = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 16, 0);
+            x_even[i][t][0] = pick_even(x0[0], x0[1]);
+            x_even[i][t][1] = pick_even(x0[2], x0[3]);
+            x_even[i][t][2] = pick_even(x1[0], x1[1]);
+            x_even[i][t][3] = pick_even(x1[2], x1[3]);
+            x_odd[i][t][0] = pick_odd(x0[0], x0[1]);
+            x_odd[i][t][1] = pick_odd(x0[2], x0[3]);
+            x_odd[i][t][2] = pick_odd(x1[0], x1[1]);
+            x_odd[i][t][3] = pick_odd(x1[2], x1[3]);
+        }
+
+    // One pass over this workgroup's tiles.  EXACT = false multiplies by the group scale with v_mad_i32_i24, which
+    // is exact while the scale fits 24 bits (|P| <= 2^17 always does), and reports whether any scale did not;
+    // EXACT = true uses full 32-bit multiplies (exact modulo 2^32 for any scale).
+    auto run_tiles = [&](auto exact_tag) -> bool {
+        constexpr bool EXACT = decltype(exact_tag)::value;
+        uint32_t wide_bits = 0;
+        if constexpr (EXACT) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+                if (dt < my_tiles) issue(dt, tile0 + dt * G);
+        }
+        stage_scales(0, 0);
+        lds_barrier();
+
+        for (int k = 0; k < my_tiles; k += DT) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                if (k + dt < my_tiles) {
+                    const int cur = tile0 + (k + dt) * G;
+                    // group scales of the next tile go to the other scale buffer; the barrier below publishes them
+                    if (k + dt + 1 < my_tiles) stage_scales((dt + 1) % DT, (k + dt + 1) & 1);
+
+                    const int* my_scales = lds_scale + ((k + dt) & 1) * scale_ints;
+                    acc_t acc[MT][4];
+#pragma unroll
+                    for (int t = 0; t < MT; ++t)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) acc[t][j] = 0;
+
+#pragma unroll
+                    for (int i = 0; i < XS; ++i) {
+                        v4i w_even, w_odd;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const uint32_t pk = (uint32_t)wq[dt][i][q];
+                            w_even[q] = (int)((pk << 4) & 0xF0F0F0F0u);
+                            w_odd[q] = (int)(pk & 0xF0F0F0F0u);
+                        }
+                        const int s_i = i < ns ? my_scales[scale_idx[i]] : 0;
+                        if constexpr (INT_SCALE && !EXACT) wide_bits |= (uint32_t)(s_i + (1 << 23));
+                        const float s_f = __int_as_float(s_i) * 0.0625f;  // 16*P * (s/16) = float(P) * s exactly
+#pragma unroll
+                        for (int t = 0; t < MT; ++t) {
+                            v4i part = __builtin_amdgcn_mfma_i32_16x16x64_i8(x_even[i][t], w_even, v4i{0, 0, 0, 0}, 0, 0, 0);
+                            part = __builtin_amdgcn_mfma_i32_16x16x64_i8(x_odd[i][t], w_odd, part, 0, 0, 0);
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                if constexpr (!INT_SCALE) acc[t][j] = fmaf((float)part[j], s_f, acc[t][j]);  // C' += float(C_g) * s_g
+                                else if constexpr (EXACT) acc[t][j] += (part[j] >> 4) * s_i;
+                                else acc[t][j] += __mul24(part[j] >> 4, s_i);                                   // C'' += C_g * s_g^INT
+                            }
+                        }
+                    }
+                    const float c_out = a.chan_scale ? cs[dt] : 1.0f;
+
+                    if (k + dt + DT < my_tiles) issue(dt, cur + DT * G);  // refill the slot
+
+                    // partials of this tile -> LDS buffer (k+dt)&1, slot [wave][t][lane][j]
+                    int* buf = lds + ((k + dt) & 1) * part_ints;
+#pragma unroll
+                    for (int t = 0; t < MT; ++t) {
+                        v4i v;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            if constexpr (INT_SCALE) v[j] = acc[t][j];
+                            else v[j] = __float_as_int(acc[t][j]);
+                        }
+                        *reinterpret_cast<v4i*>(buf + ((wave * MT + t) * kWave + lane) * 4) = v;
+                    }
+                    lds_barrier();
+
+                    const int n = cur * 16 + n_out;
+                    if (writer && n < a.N) {
+                        acc_t tot = 0;
+                        for (int w = 0; w < W; ++w) {
+                            const int v = buf[w * MT * kWave * 4 + src_slot];
+                            if constexpr (INT_SCALE) tot += v;
+                            else tot += __int_as_float(v);
+                        }
+                        float o;
+                        if constexpr (INT_SCALE) {
+                            o = (float)tot * sa_out * (c_out * inv_alpha);
+                            if (a.acc_out) a.acc_out[(size_t)m_out * a.N + n] = tot;
+                        } else {
+                            o = tot * sa_out;
+                        }
+                        a.out[(size_t)m_out * a.N + n] = __float2half_rn(o);
+                    }
+                }
+            }
+        }
+        return (wide_bits >> 24) != 0;
+    };
+
+    const bool wide = run_tiles(std::false_type{});
+    if constexpr (INT_SCALE) {
+        // Some scale was wider than 24 bits: redo this workgroup's tiles with exact 32-bit multiplies.  Rare, and
+        // kept out of the pipelined pass so that pass stays branch-free.  The vote goes through one LDS word (a
+        // __syncthreads_or would also wait for the output stores still in flight).
+        int* vote = lds_scale + 2 * scale_ints;
+        if (threadIdx.x == 0) *vote = 0;
+        lds_barrier();
+        if (__any(wide) && lane == 0) *vote = 1;
+        lds_barrier();
+        if (*vote != 0) {
+            lds_barrier();
+            run_tiles(std::true_type{});
+        }
+    }
+}
+
+int g_cu_count = 0;
+
+int cu_count() {
+    if (g_cu_count == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            g_cu_count = n;
+        else
+            g_cu_count = 256;
+    }
+    return g_cu_count;
+}
+
+template <int MT, int XS, int DT, bool INT_SCALE>
+hipError_t launch_decode(const GemmArgs& a, const DecodePlan& p, int grid, hipStream_t stream) {
+    const size_t smem = 2 * (size_t)p.waves * MT * kWave * 16 + 2 * 16 * (size_t)(p.num_groups + 1) * 4 + 16;
+    auto kern = gemm_decode_kernel<MT, XS, DT, INT_SCALE>;
+    if (smem > 64 * 1024) {
+        static bool raised = false;  // per instantiation
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(p.waves * kWave), smem, stream, a, p);
+    return hipGetLastError();
+}
+
+template <bool INT_SCALE>
+hipError_t dispatch(const GemmArgs& a, const DecodePlan& p, int mt, int xs, int grid, hipStream_t stream) {
+    if (mt == 1) {
+        if (xs <= 2) return launch_decode<1, 2, 4, INT_SCALE>(a, p, grid, stream);
+        if (xs <= 4) return launch_decode<1, 4, 2, INT_SCALE>(a, p, grid, stream);
+        return launch_decode<1, 6, 1, INT_SCALE>(a, p, grid, stream);
+    }
+    if (mt == 2) {
+        if (xs <= 2) return launch_decode<2, 2, 4, INT_SCALE>(a, p, grid, stream);
+        return launch_decode<2, 4, 1, INT_SCALE>(a, p, grid, stream);
+    }
+    return launch_decode<4, 2, 2, INT_SCALE>(a, p, grid, stream);
+}
+
+}  // namespace
+
+// True (and the launch done) if the decode kernel covers this problem; false leaves it to the general kernel.
+bool try_launch_gemm_decode(const GemmArgs& a, bool int_scale, hipStream_t stream, hipError_t* err) {
+    if (a.row_offsets || a.M > 64 || a.M < 1) return false;
+    const int NG = a.K / a.group;
+    const int spg = a.group / kStepK;
+    int waves = 16;
+    while (waves > NG) waves >>= 1;
+    const int xs = ((NG + waves - 1) / waves) * spg;
+    const int mt = a.M <= 16 ? 1 : a.M <= 32 ? 2 : 4;
+    if (mt == 4) return false;  // 64 token rows do not fit the register budget yet without spilling
+    if (mt * xs > 8 || xs > 6) return false;  // the resident activations would not fit the register budget
+    if (waves < 4 * mt) return false;           // the epilogue needs one thread per output of a tile (256 * mt)
+    if (16 * NG > 2 * waves * kWave) return false;  // two words per thread stage a tile's group scales
+    DecodePlan p;
+    p.tiles = (a.N + 15) / 16;
+    p.waves = waves;
+    p.num_groups = NG;
+    p.gq = NG / waves;
+    p.gr = NG % waves;
+    p.spg = spg;
+    const int grid = p.tiles < cu_count() ? p.tiles : cu_count();
+    p.tiles_q = p.tiles / grid;
+    p.tiles_r = p.tiles % grid;
+    *err = int_scale ? dispatch<true>(a, p, mt, xs, grid, stream) : dispatch<false>(a, p, mt, xs, grid, stream);
+    return true;
+}
+
+}  // namespace intscale

@@ -29,11 +29,22 @@ struct GemmArgs {
     int num_experts;
 };
 
+// Work split of the decode kernel (filled by its launcher).
+struct DecodePlan {
+    int tiles;       // 16-row weight tiles
+    int waves;       // waves per workgroup = K split
+    int num_groups;  // K / group
+    int gq, gr;      // groups per wave: gq, and one more for the first gr waves
+    int spg;         // 128-wide steps per group
+    int tiles_q, tiles_r;  // tiles per workgroup: tiles_q, and one more for the first tiles_r workgroups
+};
+
 // Launchers (defined next to their kernels). Each returns a hipError_t from the launch.
 hipError_t launch_quantize_act(const __half* x, int M, int K, int8_t* xq, float* a_scale, hipStream_t stream);
 hipError_t launch_quantize_weights(const __half* w, int N, int K, int group, int alpha_log2, int scale_mode,
                                    uint8_t* qweight, float* scale_f32, int32_t* scale_i32, float* chan_scale,
                                    int* alpha_log2_dev, hipStream_t stream);
 hipError_t launch_gemm_skinny(const GemmArgs& a, bool int_scale, hipStream_t stream);
+bool try_launch_gemm_decode(const GemmArgs& a, bool int_scale, hipStream_t stream, hipError_t* err);
 
 }  // namespace intscale

@@ -24,6 +24,16 @@ def P():
     return pkg
 
 
+@pytest.fixture(params=["auto", "general"])
+def kernel(request, monkeypatch):
+    """Runs a test twice: with the library's own kernel choice, and with everything forced onto the general kernel."""
+    if request.param == "general":
+        monkeypatch.setenv("INTSCALE_FORCE_KERNEL", "general")
+    else:
+        monkeypatch.delenv("INTSCALE_FORCE_KERNEL", raising=False)
+    return request.param
+
+
 def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
 
@@ -118,7 +128,7 @@ SHAPES = [(1, 16, 128), (1, 4096, 4096), (8, 4096, 4096), (16, 272, 1024), (17, 
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
-def test_gemm_intscale_bit_exact_acc(P, M, N, K):
+def test_gemm_intscale_bit_exact_acc(P, kernel, M, N, K):
     rng = np.random.default_rng(1000 + M + N + K)
     xq, qw, IS, s, sa, c = rand_quantised(rng, M, N, K)
     ref = O.gemm_w4a8_intscale(xq, sa, qw, IS, c, G, 10)
@@ -133,7 +143,7 @@ def test_gemm_intscale_bit_exact_acc(P, M, N, K):
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
-def test_gemm_floatscale(P, M, N, K):
+def test_gemm_floatscale(P, kernel, M, N, K):
     rng = np.random.default_rng(2000 + M + N + K)
     xq, qw, IS, s, sa, c = rand_quantised(rng, M, N, K)
     fs = O.gemm_w4a8_floatscale(xq, sa, qw, s, G)
@@ -141,7 +151,7 @@ def test_gemm_floatscale(P, M, N, K):
     check_fs(host(out), fs, f"M{M} N{N} K{K}")
 
 
-def test_gemm_extreme_codes_and_wide_scales(P):
+def test_gemm_extreme_codes_and_wide_scales(P, kernel):
     """All codes at -128 / -8 (the largest partial sums), negative and wider-than-24-bit integer scales, wrap-around."""
     M, N, K = 16, 32, 4096
     xq = np.full((M, K), -128, np.int8)
@@ -160,7 +170,7 @@ def test_gemm_extreme_codes_and_wide_scales(P):
 
 
 @pytest.mark.parametrize("group", [256, 512, 1024])
-def test_gemm_wider_groups_and_coarse_grained(P, group):
+def test_gemm_wider_groups_and_coarse_grained(P, kernel, group):
     """group = K is the coarse-grained GEMM (Table 2, first column)."""
     M, N, K = 24, 80, 1024
     rng = np.random.default_rng(group)
@@ -223,7 +233,7 @@ def test_grouped_gemm(P, counts):
 
 
 # ------------------------------------------------------------------------------------------------ end to end, GPU-quantised
-def test_config0_end_to_end(P):
+def test_config0_end_to_end(P, kernel):
     """M=8, K=N=4096, group 128, alpha 2^10: fp16 in, fp16 out, every stage compared."""
     sh = S.config_shapes(0)[0]
     x = S.make_activations(0, sh.M, sh.K, S.seed_for(0, 0, 0))
