@@ -116,8 +116,19 @@ def main():
                 out=torch.empty((M, N), dtype=torch.float16, device=dev))
     torch.cuda.synchronize()
 
-    def mt_of(M):
-        return 1 if M <= 16 else 2 if M <= 32 else 3 if M <= 48 else 4
+    def kernel_name(M, K, int_scale):
+        """Name of the kernel instantiation the library picks for this shape (mirrors its dispatch; used to match the
+        per-kernel figures here with a rocprofv3 kernel trace)."""
+        tag = "true" if int_scale else "false"
+        ng = K // GROUP
+        if M <= 32:
+            mt = 1 if M <= 16 else 2
+            xs = -(-ng // 16)
+            if mt * xs <= 8 and xs <= 6:
+                xs_t, dt = {1: [(2, 4), (4, 2), (6, 1)], 2: [(2, 4), (4, 1)]}[mt][0 if xs <= 2 else 1 if xs <= 4 else 2]
+                return f"gemm_decode_kernel<{mt}, {xs_t}, {dt}, {tag}>"
+        mt = 1 if M <= 16 else 2 if M <= 32 else 3 if M <= 48 else 4
+        return f"gemm_skinny_kernel<{mt}, ...>"
 
     # ---------------------------------------------------------------- segments of one step
     def make_segments(int_scale: bool, with_quant: bool):
@@ -140,7 +151,7 @@ def main():
                     def fg(a=a, w=w):
                         for l in range(L):
                             P.is_gemm_w4a8_floatscale(a["xq"], a["sa"], w["q"][l], w["sf"][l], GROUP, out=a["out"])
-                kname = "gemm_skinny_kernel<%d,%s>" % (mt_of(M), "int" if int_scale else "float")
+                kname = kernel_name(M, K, int_scale)
                 segs.append(Segment(f"gemm_{name}_M{M}", kname, L, L * S.algorithmic_bytes(M, N, K, GROUP),
                                     L * S.algorithmic_ops(M, N, K), fg, use_graph, torch))
         return segs
