@@ -50,15 +50,17 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 
 // MT: 16-row token tiles.  XS: steps of K a wave owns at most (its activations stay in 8*XS*MT registers).
 // DT: weight tiles in flight per wave.
-template <int MT, int XS, int DT, bool INT_SCALE>
-__global__ __launch_bounds__(1024) void gemm_decode_kernel(GemmArgs a, DecodePlan p) {
+// WAVES: waves per workgroup (16 leaves 128 vector registers per lane, 8 leaves 256).
+template <int MT, int XS, int DT, int WAVES, bool INT_SCALE>
+__global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, DecodePlan p) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     using acc_t = typename std::conditional<INT_SCALE, int, float>::type;
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int W = p.waves;
-    const int T = W * kWave;
+    constexpr int W = WAVES;
+    constexpr int T = W * kWave;
+    constexpr int OPT = (256 * MT + T - 1) / T;  // outputs of a tile each thread finishes
     const int li = lane & 15, kb = lane >> 4;
     const int NG = p.num_groups;
     const int row_bytes = a.K >> 1;
@@ -85,40 +87,13 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(GemmArgs a, DecodePla
     int* lds_scale = lds + 2 * part_ints;
     const int scale_ints = 16 * srow_ints;
 
-    // ---- role of this thread in the epilogue: one output (m_out, tile*16 + n_out) per tile
+    // ---- cheap parts of this thread's roles, needed to start the stream (the rest is set up while it is in flight)
     const int n_out = threadIdx.x & 15;
-    const int m_out = threadIdx.x >> 4;                 // 0 .. 16*MT-1 for the threads that take part
-    const bool writer = threadIdx.x < 256 * MT && m_out < a.M;
-    const float sa_out = writer ? a.a_scale[m_out] : 0.0f;
-    const float inv_alpha = __int_as_float((127 - a.alpha_log2) << 23);  // 2^-alpha_log2, exact
-    // where that output sits in a wave's partials: tile t, lane (4 rows per lane-group), register j
-    const int src_slot = ((m_out >> 4) * kWave + ((m_out & 15) >> 2) * 16 + n_out) * 4 + (m_out & 3);
-
-    // ---- role of this thread in staging a tile's group scales: the tile's 16 x NG scales are one contiguous block
-    // of the scale tensor; thread u copies words u and u + T of it (16 * NG <= 2 * T is checked by the host).
-    int stage_src[2], stage_dst[2];
+    const bool writer0 = threadIdx.x < 256 * MT && (int)(threadIdx.x >> 4) < a.M;
+    int stage_src[2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int f = threadIdx.x + j * T;
-        const int r = f / NG;
-        stage_src[j] = f < 16 * NG ? f * 4 : kOutOfRange;
-        stage_dst[j] = f < 16 * NG ? r * srow_ints + (f - r * NG) : -1;
-    }
-
-    // ---- weight stream
+    for (int j = 0; j < 2; ++j) stage_src[j] = (int)threadIdx.x + j * T < 16 * NG ? ((int)threadIdx.x + j * T) * 4 : kOutOfRange;
     const int woff = li * row_bytes + s0 * (kStepK / 2) + kb * 16;  // inside a tile; the tile base is a scalar
-    int scale_idx[XS];  // LDS word of the group scale of step i for this lane's weight row
-    {
-        int g = 0, sub = 0;
-#pragma unroll
-        for (int i = 0; i < XS; ++i) {
-            scale_idx[i] = li * srow_ints + g0 + g;
-            if (++sub == p.spg) {
-                sub = 0;
-                ++g;
-            }
-        }
-    }
 
     v4i wq[DT][XS];
     int scv[DT][2];
@@ -139,16 +114,10 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(GemmArgs a, DecodePla
             wq[slot][i] = __builtin_amdgcn_raw_buffer_load_b128(wres, (row_ok && i < ns) ? woff + i * (kStepK / 2) : kOutOfRange, wbase, 0);
         if constexpr (INT_SCALE) {
             // channel scale of this thread's output column; columns past N (or no channel scales at all) read 0
-            const bool col_ok = writer && tile * 16 + n_out < a.N;
+            const bool col_ok = writer0 && tile * 16 + n_out < a.N;
             cs[slot] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(cres, col_ok ? n_out * 4 : kOutOfRange, tile * 64, 0));
         }
     };
-    auto stage_scales = [&](int slot, int buf) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-            if (stage_dst[j] >= 0) lds_scale[buf * scale_ints + stage_dst[j]] = scv[slot][j];
-    };
-
     // First requests of the stream go out before anything else that waits on memory.
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -175,17 +144,51 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(GemmArgs a, DecodePla
             x_odd[i][t][3] = pick_odd(x1[2], x1[3]);
         }
 
-    // One pass over this workgroup's tiles.  EXACT = false multiplies by the group scale with v_mad_i32_i24, which
-    // is exact while the scale fits 24 bits (|P| <= 2^17 always does), and reports whether any scale did not;
-    // EXACT = true uses full 32-bit multiplies (exact modulo 2^32 for any scale).
-    auto run_tiles = [&](auto exact_tag) -> bool {
-        constexpr bool EXACT = decltype(exact_tag)::value;
-        uint32_t wide_bits = 0;
-        if constexpr (EXACT) {
+    // ---- role of this thread in the epilogue: outputs (m_out[o], tile*16 + n_out) of every tile
+    int m_out[OPT], src_slot[OPT];
+    float sa_out[OPT];
+    bool writer[OPT];
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-                if (dt < my_tiles) issue(dt, tile0 + dt * G);
+    for (int o = 0; o < OPT; ++o) {
+        m_out[o] = (threadIdx.x + o * T) >> 4;  // 0 .. 16*MT-1 for the threads that take part
+        writer[o] = threadIdx.x + o * T < 256 * MT && m_out[o] < a.M;
+        sa_out[o] = writer[o] ? a.a_scale[m_out[o]] : 0.0f;
+        // where that output sits in a wave's partials: tile t, lane (4 rows per lane-group), register j
+        src_slot[o] = ((m_out[o] >> 4) * kWave + ((m_out[o] & 15) >> 2) * 16 + n_out) * 4 + (m_out[o] & 3);
+    }
+    const float inv_alpha = __int_as_float((127 - a.alpha_log2) << 23);  // 2^-alpha_log2, exact
+
+    // ---- role of this thread in staging a tile's group scales: the tile's 16 x NG scales are one contiguous block
+    // of the scale tensor; thread u copies words u and u + T of it (16 * NG <= 2 * T is checked by the host).
+    int stage_dst[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int f = threadIdx.x + j * T;
+        const int r = f / NG;
+        stage_dst[j] = f < 16 * NG ? r * srow_ints + (f - r * NG) : -1;
+    }
+
+    int scale_idx[XS];  // LDS word of the group scale of step i for this lane's weight row
+    {
+        int g = 0, sub = 0;
+#pragma unroll
+        for (int i = 0; i < XS; ++i) {
+            scale_idx[i] = li * srow_ints + g0 + g;
+            if (++sub == p.spg) {
+                sub = 0;
+                ++g;
+            }
         }
+    }
+
+    auto stage_scales = [&](int slot, int buf) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            if (stage_dst[j] >= 0) lds_scale[buf * scale_ints + stage_dst[j]] = scv[slot][j];
+    };
+
+    // The pass over this workgroup's tiles.
+    {
         stage_scales(0, 0);
         lds_barrier();
 
@@ -214,19 +217,28 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(GemmArgs a, DecodePla
                             w_odd[q] = (int)(pk & 0xF0F0F0F0u);
                         }
                         const int s_i = i < ns ? my_scales[scale_idx[i]] : 0;
-                        if constexpr (INT_SCALE && !EXACT) wide_bits |= (uint32_t)(s_i + (1 << 23));
+                        // Integer scale step: v_mad_i32_i24 is exact while the scale fits 24 bits (|P| <= 2^17 always
+                        // does); a wave that meets a wider scale takes the full 32-bit multiply for this step.  Both
+                        // are exact modulo 2^32.
+                        const bool wide = INT_SCALE && __any(((uint32_t)(s_i + (1 << 23)) >> 24) != 0);
                         const float s_f = __int_as_float(s_i) * 0.0625f;  // 16*P * (s/16) = float(P) * s exactly
 #pragma unroll
                         for (int t = 0; t < MT; ++t) {
                             v4i part = __builtin_amdgcn_mfma_i32_16x16x64_i8(x_even[i][t], w_even, v4i{0, 0, 0, 0}, 0, 0, 0);
                             part = __builtin_amdgcn_mfma_i32_16x16x64_i8(x_odd[i][t], w_odd, part, 0, 0, 0);
+                            if constexpr (!INT_SCALE) {
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                if constexpr (!INT_SCALE) acc[t][j] = fmaf((float)part[j], s_f, acc[t][j]);  // C' += float(C_g) * s_g
-                                else if constexpr (EXACT) acc[t][j] += (part[j] >> 4) * s_i;
-                                else acc[t][j] += __mul24(part[j] >> 4, s_i);                                   // C'' += C_g * s_g^INT
+                                for (int j = 0; j < 4; ++j) acc[t][j] = fmaf((float)part[j], s_f, acc[t][j]);  // C' += float(C_g) * s_g
+                            } else if (__builtin_expect(wide, 0)) {
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) acc[t][j] += (part[j] >> 4) * s_i;
+                            } else {
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) acc[t][j] += __mul24(part[j] >> 4, s_i);             // C'' += C_g * s_g^INT
                             }
                         }
+                        // with many token tiles the scheduler otherwise unpacks several steps ahead and spills
+                        if constexpr (MT * XS >= 8) __builtin_amdgcn_sched_barrier(0);
                     }
                     const float c_out = a.chan_scale ? cs[dt] : 1.0f;
 
@@ -247,43 +259,30 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(GemmArgs a, DecodePla
                     lds_barrier();
 
                     const int n = cur * 16 + n_out;
-                    if (writer && n < a.N) {
-                        acc_t tot = 0;
-                        for (int w = 0; w < W; ++w) {
-                            const int v = buf[w * MT * kWave * 4 + src_slot];
-                            if constexpr (INT_SCALE) tot += v;
-                            else tot += __int_as_float(v);
+#pragma unroll
+                    for (int o = 0; o < OPT; ++o) {
+                        if (writer[o] && n < a.N) {
+                            acc_t tot = 0;
+                            for (int w = 0; w < W; ++w) {
+                                const int v = buf[w * MT * kWave * 4 + src_slot[o]];
+                                if constexpr (INT_SCALE) tot += v;
+                                else tot += __int_as_float(v);
+                            }
+                            float out_v;
+                            if constexpr (INT_SCALE) {
+                                out_v = (float)tot * sa_out[o] * (c_out * inv_alpha);
+                                if (a.acc_out) a.acc_out[(size_t)m_out[o] * a.N + n] = tot;
+                            } else {
+                                out_v = tot * sa_out[o];
+                            }
+                            a.out[(size_t)m_out[o] * a.N + n] = __float2half_rn(out_v);
                         }
-                        float o;
-                        if constexpr (INT_SCALE) {
-                            o = (float)tot * sa_out * (c_out * inv_alpha);
-                            if (a.acc_out) a.acc_out[(size_t)m_out * a.N + n] = tot;
-                        } else {
-                            o = tot * sa_out;
-                        }
-                        a.out[(size_t)m_out * a.N + n] = __float2half_rn(o);
                     }
                 }
             }
         }
-        return (wide_bits >> 24) != 0;
-    };
-
-    const bool wide = run_tiles(std::false_type{});
-    if constexpr (INT_SCALE) {
-        // Some scale was wider than 24 bits: redo this workgroup's tiles with exact 32-bit multiplies.  Rare, and
-        // kept out of the pipelined pass so that pass stays branch-free.  The vote goes through one LDS word (a
-        // __syncthreads_or would also wait for the output stores still in flight).
-        int* vote = lds_scale + 2 * scale_ints;
-        if (threadIdx.x == 0) *vote = 0;
-        lds_barrier();
-        if (__any(wide) && lane == 0) *vote = 1;
-        lds_barrier();
-        if (*vote != 0) {
-            lds_barrier();
-            run_tiles(std::true_type{});
-        }
     }
+
 }
 
 int g_cu_count = 0;
@@ -300,10 +299,10 @@ int cu_count() {
     return g_cu_count;
 }
 
-template <int MT, int XS, int DT, bool INT_SCALE>
+template <int MT, int XS, int DT, int WAVES, bool INT_SCALE>
 hipError_t launch_decode(const GemmArgs& a, const DecodePlan& p, int grid, hipStream_t stream) {
-    const size_t smem = 2 * (size_t)p.waves * MT * kWave * 16 + 2 * 16 * (size_t)(p.num_groups + 1) * 4 + 16;
-    auto kern = gemm_decode_kernel<MT, XS, DT, INT_SCALE>;
+    const size_t smem = 2 * (size_t)WAVES * MT * kWave * 16 + 2 * 16 * (size_t)(p.num_groups + 1) * 4;
+    auto kern = gemm_decode_kernel<MT, XS, DT, WAVES, INT_SCALE>;
     if (smem > 64 * 1024) {
         static bool raised = false;  // per instantiation
         if (!raised) {
@@ -313,22 +312,22 @@ hipError_t launch_decode(const GemmArgs& a, const DecodePlan& p, int grid, hipSt
             raised = true;
         }
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(p.waves * kWave), smem, stream, a, p);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * kWave), smem, stream, a, p);
     return hipGetLastError();
 }
 
 template <bool INT_SCALE>
 hipError_t dispatch(const GemmArgs& a, const DecodePlan& p, int mt, int xs, int grid, hipStream_t stream) {
     if (mt == 1) {
-        if (xs <= 2) return launch_decode<1, 2, 4, INT_SCALE>(a, p, grid, stream);
-        if (xs <= 4) return launch_decode<1, 4, 2, INT_SCALE>(a, p, grid, stream);
-        return launch_decode<1, 6, 1, INT_SCALE>(a, p, grid, stream);
+        if (xs <= 2) return launch_decode<1, 2, 4, 16, INT_SCALE>(a, p, grid, stream);
+        if (xs <= 4) return launch_decode<1, 4, 2, 16, INT_SCALE>(a, p, grid, stream);
+        return launch_decode<1, 6, 1, 16, INT_SCALE>(a, p, grid, stream);
     }
     if (mt == 2) {
-        if (xs <= 2) return launch_decode<2, 2, 4, INT_SCALE>(a, p, grid, stream);
-        return launch_decode<2, 4, 1, INT_SCALE>(a, p, grid, stream);
+        if (xs <= 2) return launch_decode<2, 2, 4, 16, INT_SCALE>(a, p, grid, stream);
+        return launch_decode<2, 4, 1, 16, INT_SCALE>(a, p, grid, stream);
     }
-    return launch_decode<4, 2, 2, INT_SCALE>(a, p, grid, stream);
+    return launch_decode<4, 4, 1, 8, INT_SCALE>(a, p, grid, stream);
 }
 
 }  // namespace
@@ -338,14 +337,13 @@ bool try_launch_gemm_decode(const GemmArgs& a, bool int_scale, hipStream_t strea
     if (a.row_offsets || a.M > 64 || a.M < 1) return false;
     const int NG = a.K / a.group;
     const int spg = a.group / kStepK;
-    int waves = 16;
-    while (waves > NG) waves >>= 1;
-    const int xs = ((NG + waves - 1) / waves) * spg;
     const int mt = a.M <= 16 ? 1 : a.M <= 32 ? 2 : 4;
-    if (mt == 4) return false;  // 64 token rows do not fit the register budget yet without spilling
-    if (mt * xs > 8 || xs > 6) return false;  // the resident activations would not fit the register budget
-    if (waves < 4 * mt) return false;           // the epilogue needs one thread per output of a tile (256 * mt)
-    if (16 * NG > 2 * waves * kWave) return false;  // two words per thread stage a tile's group scales
+    // 64 token rows: 8 waves per workgroup, so that a wave's resident activations (128 registers) fit
+    const int waves = mt == 4 ? 8 : 16;
+    if (waves > NG) return false;
+    const int xs = ((NG + waves - 1) / waves) * spg;
+    if (mt == 4 ? xs > 4 : (mt * xs > 8 || xs > 6)) return false;  // resident activations beyond the register budget
+    if (16 * NG > 2 * waves * kWave) return false;                  // two words per thread stage a tile's group scales
     DecodePlan p;
     p.tiles = (a.N + 15) / 16;
     p.waves = waves;
