@@ -44,46 +44,80 @@ __device__ __forceinline__ int quant_code(float x, float s, float lo, float hi) 
 // ---------------------------------------------------------------------------------------------------------
 constexpr int kActThreads = 256;
 
+__device__ __forceinline__ uint2 quantize8(uint4 v, float s) {
+    const __half2* h = reinterpret_cast<const __half2*>(&v);
+    uint32_t packed[2] = {0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float2 f = __half22float2(h[i]);
+        int q0 = 0, q1 = 0;
+        if (s > 0.0f) {
+            q0 = quant_code(f.x, s, -128.0f, 127.0f);
+            q1 = quant_code(f.y, s, -128.0f, 127.0f);
+        }
+        uint32_t two = ((uint32_t)q0 & 0xFFu) | (((uint32_t)q1 & 0xFFu) << 8);
+        packed[i >> 1] |= two << ((i & 1) * 16);
+    }
+    return make_uint2(packed[0], packed[1]);
+}
+
+__device__ __forceinline__ float block_max(float v, float* red) {
+    v = wave_max(v);
+    if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = v;
+    __syncthreads();
+    v = red[0];
+#pragma unroll
+    for (int i = 1; i < kActThreads / kWave; ++i) v = fmaxf(v, red[i]);
+    return v;
+}
+
+// Rows of up to 2048 * CH elements: the row is read once and stays in registers (CH 16-byte chunks per lane) between
+// the absmax reduction and the rounding, so a token row costs one trip to memory, not two.
+template <int CH>
+__global__ __launch_bounds__(kActThreads) void quantize_act_resident_kernel(const __half* __restrict__ x, int M, int K,
+                                                                            int8_t* __restrict__ xq,
+                                                                            float* __restrict__ a_scale) {
+    __shared__ float red[kActThreads / kWave];
+    const int m = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int nchunk = K >> 3;
+    const uint4* row = reinterpret_cast<const uint4*>(x + (size_t)m * K);
+    uint4 v[CH];
+    float amax = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int idx = tid + c * kActThreads;
+        v[c] = idx < nchunk ? row[idx] : make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int c = 0; c < CH; ++c) amax = fmaxf(amax, absmax8(v[c]));
+    amax = block_max(amax, red);
+    const float s = amax / 127.0f;
+    if (tid == 0) a_scale[m] = s;
+    uint2* dst = reinterpret_cast<uint2*>(xq + (size_t)m * K);
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int idx = tid + c * kActThreads;
+        if (idx < nchunk) dst[idx] = quantize8(v[c], s);
+    }
+}
+
+// Longer rows: two passes, the second re-reads the row (from L2).
 __global__ __launch_bounds__(kActThreads) void quantize_act_kernel(const __half* __restrict__ x, int M, int K,
                                                                    int8_t* __restrict__ xq,
                                                                    float* __restrict__ a_scale) {
     __shared__ float red[kActThreads / kWave];
     const int m = blockIdx.x;
-    if (m >= M) return;
     const int tid = threadIdx.x;
     const int nchunk = K >> 3;
     const uint4* row = reinterpret_cast<const uint4*>(x + (size_t)m * K);
-
     float amax = 0.0f;
     for (int c = tid; c < nchunk; c += kActThreads) amax = fmaxf(amax, absmax8(row[c]));
-    amax = wave_max(amax);
-    if ((tid & (kWave - 1)) == 0) red[tid / kWave] = amax;
-    __syncthreads();
-    amax = red[0];
-#pragma unroll
-    for (int i = 1; i < kActThreads / kWave; ++i) amax = fmaxf(amax, red[i]);
-
+    amax = block_max(amax, red);
     const float s = amax / 127.0f;
     if (tid == 0) a_scale[m] = s;
-
     uint2* dst = reinterpret_cast<uint2*>(xq + (size_t)m * K);
-    for (int c = tid; c < nchunk; c += kActThreads) {
-        uint4 v = row[c];
-        const __half2* h = reinterpret_cast<const __half2*>(&v);
-        uint32_t packed[2] = {0u, 0u};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float2 f = __half22float2(h[i]);
-            int q0 = 0, q1 = 0;
-            if (s > 0.0f) {
-                q0 = quant_code(f.x, s, -128.0f, 127.0f);
-                q1 = quant_code(f.y, s, -128.0f, 127.0f);
-            }
-            uint32_t two = ((uint32_t)q0 & 0xFFu) | (((uint32_t)q1 & 0xFFu) << 8);
-            packed[i >> 1] |= two << ((i & 1) * 16);
-        }
-        dst[c] = make_uint2(packed[0], packed[1]);
-    }
+    for (int c = tid; c < nchunk; c += kActThreads) dst[c] = quantize8(row[c], s);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -193,7 +227,15 @@ __global__ __launch_bounds__(kWqThreads) void apply_searched_amplifier_kernel(co
 }  // namespace
 
 hipError_t launch_quantize_act(const __half* x, int M, int K, int8_t* xq, float* a_scale, hipStream_t stream) {
-    hipLaunchKernelGGL(quantize_act_kernel, dim3(M), dim3(kActThreads), 0, stream, x, M, K, xq, a_scale);
+    const int chunks_per_lane = ((K >> 3) + kActThreads - 1) / kActThreads;
+    if (chunks_per_lane <= 2)
+        hipLaunchKernelGGL(quantize_act_resident_kernel<2>, dim3(M), dim3(kActThreads), 0, stream, x, M, K, xq, a_scale);
+    else if (chunks_per_lane <= 8)
+        hipLaunchKernelGGL(quantize_act_resident_kernel<8>, dim3(M), dim3(kActThreads), 0, stream, x, M, K, xq, a_scale);
+    else if (chunks_per_lane <= 16)
+        hipLaunchKernelGGL(quantize_act_resident_kernel<16>, dim3(M), dim3(kActThreads), 0, stream, x, M, K, xq, a_scale);
+    else
+        hipLaunchKernelGGL(quantize_act_kernel, dim3(M), dim3(kActThreads), 0, stream, x, M, K, xq, a_scale);
     return hipGetLastError();
 }
 
