@@ -33,13 +33,20 @@ int check_gemm_shape(int M, int N, int K, int group) {
     return IS_OK;
 }
 
-// Regime selection by the number of token rows.
-hipError_t launch_gemm(const GemmArgs& a, bool int_scale, hipStream_t stream) {
+// Regime selection by the number of token rows.  More than 64 rows (per expert on average, for the grouped form)
+// go to the MFMA-bound tiled kernel, which needs workspace for its zero-point corrections.
+bool general_forced() {
     // INTSCALE_FORCE_KERNEL=general routes everything to the general kernel (used by the tests to cover it).
     const char* force = getenv("INTSCALE_FORCE_KERNEL");
-    const bool general_only = force && strcmp(force, "general") == 0;
+    return force && strcmp(force, "general") == 0;
+}
+
+bool wants_prefill(int M, int num_experts) { return !general_forced() && M > 64 * num_experts; }
+
+hipError_t launch_gemm(const GemmArgs& a, bool int_scale, void* workspace, hipStream_t stream) {
+    if (wants_prefill(a.M, a.num_experts)) return launch_gemm_prefill(a, int_scale, workspace, stream);
     hipError_t err = hipSuccess;
-    if (!general_only && try_launch_gemm_decode(a, int_scale, stream, &err)) return err;
+    if (!general_forced() && try_launch_gemm_decode(a, int_scale, stream, &err)) return err;
     return launch_gemm_skinny(a, int_scale, stream);
 }
 
@@ -85,13 +92,14 @@ int is_quantize_act_int8_token(const void* x_fp16, int M, int K, int8_t* xq, flo
 }
 
 size_t is_gemm_workspace_bytes(int M, int N, int K, int group) {
-    (void)M; (void)N; (void)K; (void)group;
-    return 0;  // the cross-wave K reduction lives in LDS; no kernel needs global scratch
+    if (check_gemm_shape(M, N, K, group) != IS_OK) return 0;
+    // decode-sized problems reduce in LDS and need nothing; the tiled kernel keeps one int32 per (K step, token row)
+    return wants_prefill(M, 1) ? gemm_prefill_workspace_bytes(M, K) : 0;
 }
 
 size_t is_gemm_grouped_workspace_bytes(int num_experts, int M_total, int N, int K, int group) {
-    (void)num_experts; (void)M_total; (void)N; (void)K; (void)group;
-    return 0;
+    if (num_experts <= 0 || check_gemm_shape(M_total, N, K, group) != IS_OK) return 0;
+    return wants_prefill(M_total, num_experts) ? gemm_prefill_workspace_bytes(M_total, K) : 0;
 }
 
 static int gemm_common(const int8_t* xq, const float* a_scale, const void* qweight, const void* scale,
@@ -129,7 +137,7 @@ static int gemm_common(const int8_t* xq, const float* a_scale, const void* qweig
     a.group = group;
     a.alpha_log2 = int_scale ? alpha_log2 : 0;
     a.num_experts = grouped ? num_experts : 1;
-    return hip_status(launch_gemm(a, int_scale, static_cast<hipStream_t>(stream)));
+    return hip_status(launch_gemm(a, int_scale, workspace, static_cast<hipStream_t>(stream)));
 }
 
 int is_gemm_w4a8_intscale(const int8_t* xq, const float* a_scale, const void* qweight, const int32_t* scale_i32,
