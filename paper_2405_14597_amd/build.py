@@ -8,7 +8,7 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
-LIB_PATH = os.path.join(PKG_DIR, "libintscale.so")
+LIB_PATH = os.environ.get("INTSCALE_LIBRARY", os.path.join(PKG_DIR, "libintscale.so"))
 
 SOURCES = ["api.hip", "quantize.hip", "gemm_skinny.hip", "gemm_decode.hip", "gemm_prefill.hip"]
 
