@@ -93,13 +93,14 @@ int is_quantize_act_int8_token(const void* x_fp16, int M, int K, int8_t* xq, flo
 
 size_t is_gemm_workspace_bytes(int M, int N, int K, int group) {
     if (check_gemm_shape(M, N, K, group) != IS_OK) return 0;
-    // decode-sized problems reduce in LDS and need nothing; the tiled kernel keeps one int32 per (K step, token row)
-    return wants_prefill(M, 1) ? gemm_prefill_workspace_bytes(M, K) : 0;
+    // decode-sized problems reduce in LDS and need nothing; the tiled kernel keeps its zero-point corrections, a
+    // transposed copy of the scales and a reordered copy of the activations
+    return wants_prefill(M, 1) ? gemm_prefill_workspace_bytes(1, M, N, K, group) : 0;
 }
 
 size_t is_gemm_grouped_workspace_bytes(int num_experts, int M_total, int N, int K, int group) {
     if (num_experts <= 0 || check_gemm_shape(M_total, N, K, group) != IS_OK) return 0;
-    return wants_prefill(M_total, num_experts) ? gemm_prefill_workspace_bytes(M_total, K) : 0;
+    return wants_prefill(M_total, num_experts) ? gemm_prefill_workspace_bytes(num_experts, M_total, N, K, group) : 0;
 }
 
 static int gemm_common(const int8_t* xq, const float* a_scale, const void* qweight, const void* scale,

@@ -6,62 +6,124 @@
 // Tiling.  A workgroup of 8 waves (2 x 4) owns 128 token rows x 256 weight rows; a wave owns 64 x 64, as 4 x 4
 // sub-tiles of v_mfma_i32_16x16x64_i8 (operand A = 16 token rows, operand B = 16 weight rows, so a lane's 4 results
 // share one weight row and with it one group scale).  A wave stays below 256 registers, so two waves share a SIMD
-// and one's scale step overlaps the other's matrix work; inside a wave the three stages of the step (unpack
-// sub-tile ns+2, multiply ns+1, scale ns) are software-pipelined for the same reason.  K advances in steps of 128
-// through double-buffered LDS tiles; the global loads of step s+1 are in flight while step s is multiplied.
-// Workgroups are numbered so that the ones an XCD runs together form an 8 x 4 block of tiles and share their
-// operand tiles through that XCD's L2.
+// and one's scale step overlaps the other's matrix work; inside a wave the three stages of a K step (unpack
+// sub-tile ns+2, multiply ns+1, scale ns) are software-pipelined for the same reason.  Workgroups are numbered so
+// that the ones an XCD runs together form an 8 x 4 block of tiles and share their operand tiles through that XCD's L2.
 //
-// int4 -> int8 with a zero point instead of a sign extension: the loader stores q + 8 (nibble ^ 8), so a byte is
-// unpacked with one AND (even k) or a shift and an AND (odd k), and the product sum comes out as
-// P + 8 * sum_k x[m,k].  The correction -8 * sum_k x[m,k] per (token row, K step) is computed once by a small kernel
-// into the workspace and enters each MFMA chain as its initial accumulator, so the chain returns P exactly and the
-// scale step costs one instruction per element.
+// Operand pipeline.  K advances in steps of 128 through a ring of 4 LDS stages.  The tiles travel from global memory
+// straight into LDS (buffer loads with the LDS bit: no staging registers, no vector instructions), three steps
+// ahead of their use, so a miss in L2 is covered by two full steps of arithmetic.  Such a load writes lane i's
+// 16 bytes at (base + 16 i); the XOR swizzles that keep the later operand reads free of bank conflicts are therefore
+// applied to the *global* address each lane fetches.  The loads are issued from inline assembly so that the only
+// waits on them are the counted ones written here (the compiler would wait for all of them before any LDS read).
 //
-// LDS layouts.  Activations: row-major 128 B per row and step, 16-byte chunks XOR-swizzled by the row so that the
-// 16-byte operand reads of 32 rows spread over all banks; inside a 16-k chunk the bytes are stored as
+// The group scales are transposed to [group][weight row] by a second preparation kernel (which also finds out whether
+// every integer scale fits the 24-bit multiplier), so that the 256 scales of a step are one contiguous kilobyte.
+//
+// Activations are not read in their canonical layout: a preparation kernel writes a copy whose 16-byte chunks hold
 // [even k of 0..7 | even k of 8..15 | odd k of 0..7 | odd k of 8..15], the order in which the unpacked weights come
-// out (a dot product does not care about the order of its terms as long as both operands agree).  Weights: 64 B per
-// row and step, 8-byte chunks swizzled the same way.
+// out (a dot product does not care about the order of its terms as long as both operands agree).
+//
+// int4 -> int8 with a zero point instead of a sign extension: a packed word is XORed with 0x88888888 (q -> q + 8),
+// then a byte is unpacked with one AND (even k) or a shift and an AND (odd k), and the product sum comes out as
+// P + 8 * sum_k x[m,k].  The correction -8 * sum_k x[m,k] per (token row, K step) is computed once by the
+// preparation kernel and enters each MFMA chain as its initial accumulator, so the chain returns P exactly and the
+// scale step costs one instruction per element.
 #include "is_common.h"
 
 namespace intscale {
 namespace {
 
 constexpr int kStepK = 128;
-constexpr int kOutOfRange = (int)0x80000000u;  // a buffer offset past every descriptor here: the load returns 0
 constexpr int kBM = 128;
 constexpr int kBN = 256;
 constexpr int kThreads = 512;
-constexpr int kXcds = 8;     // workgroup i is dispatched to XCD i % 8
-constexpr int kGroupM = 8;   // tile rows of the block of tiles an XCD works on at a time
+constexpr int kWaves = kThreads / kWave;
+constexpr int kXcds = 8;    // workgroup i is dispatched to XCD i % 8
+constexpr int kGroupM = 8;  // tile rows of the block of tiles an XCD works on at a time
+constexpr int kStages = 4;  // LDS ring; tiles are requested kStages - 1 steps ahead
+constexpr int kTileLoads = 4;  // buffer-to-LDS loads per wave and step: 2 activation, 2 weight (+1 on waves 0 and 1)
+constexpr int kXBytes = kBM * 128, kWBytes = kBN * 64, kAuxBytes = 2048;  // aux: 256 scales, 128 corrections
+constexpr int kStageBytes = kXBytes + kWBytes + kAuxBytes;
 #ifndef INTSCALE_SWZ_A
 #define INTSCALE_SWZ_A 1
 #endif
 #ifndef INTSCALE_SWZ_B
 #define INTSCALE_SWZ_B 1
 #endif
-constexpr int kSwzA = INTSCALE_SWZ_A;  // activation rows: 16-byte chunk index ^= (row >> kSwzA) & 7
-constexpr int kSwzB = INTSCALE_SWZ_B;  // weight rows: 8-byte chunk index ^= (row >> kSwzB) & 7
+constexpr int kSwzA = INTSCALE_SWZ_A;  // activation rows (128 B): 16-byte chunk index ^= (row >> kSwzA) & 7
+constexpr int kSwzB = INTSCALE_SWZ_B;  // weight rows (64 B): 16-byte chunk index ^= (row >> kSwzB) & 3
 
 typedef float v4f __attribute__((ext_vector_type(4)));
-using rsrc_t = __amdgpu_buffer_rsrc_t;
 
-__device__ __forceinline__ rsrc_t make_rsrc(const void* base, size_t bytes) {
-    const unsigned n = bytes > 0x7FFFFFFFull ? 0x7FFFFFFFu : (unsigned)bytes;
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, n, 0x00020000);
+// Buffer descriptor in four scalar registers: base address, no stride, byte count, raw 32-bit format.  Offsets at or
+// past the byte count read as zero.
+__device__ __forceinline__ v4i make_desc(const void* base, size_t bytes) {
+    const uint64_t p = reinterpret_cast<uint64_t>(base);
+    v4i d;
+    d[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+    d[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)((p >> 32) & 0xFFFFu));
+    d[2] = __builtin_amdgcn_readfirstlane((int)(bytes > 0x7FFFFFFFull ? 0x7FFFFFFFu : (uint32_t)bytes));
+    d[3] = 0x00020000;
+    return d;
 }
+
+// 64 lanes x 16 bytes (or x 4 bytes) from global memory to LDS at lds_base + lane * 16 (* 4).  Completion is visible
+// through the vector memory counter only.
+__device__ __forceinline__ void load_to_lds_b128(v4i desc, unsigned lds_base, int voffset, int soffset) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voffset), "s"(desc), "s"(soffset)
+                 : "memory");
+}
+__device__ __forceinline__ void load_to_lds_b32(v4i desc, unsigned lds_base, int voffset, int soffset) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voffset), "s"(desc), "s"(soffset)
+                 : "memory");
+}
+
 __device__ __forceinline__ int pick_even(uint32_t lo, uint32_t hi) { return (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u); }
 __device__ __forceinline__ int pick_odd(uint32_t lo, uint32_t hi) { return (int)__builtin_amdgcn_perm(hi, lo, 0x07050301u); }
 
-// s8[step][m] = -8 * sum over the 128 k of the step of xq[m,k]: the zero-point correction of the q+8 weight bytes.
-// One wave per token row; 8 lanes share a step.
-__global__ __launch_bounds__(256) void step_sums_kernel(const int8_t* __restrict__ xq, int M, int K,
-                                                        int32_t* __restrict__ s8) {
+// Preparation of the scales: st[e][g][n] = scale[e][n][g] (32-bit words, integer or float alike), through a 64 x 64
+// LDS tile so that both sides are coalesced; CHECK also raises the flag if an integer scale does not fit 24 signed
+// bits (the limit of v_mad_i32_i24).
+template <bool CHECK>
+__global__ __launch_bounds__(256) void prepare_scales_kernel(const int32_t* __restrict__ scale, int N, int NG,
+                                                             int32_t* __restrict__ st, int32_t* __restrict__ wide_flag) {
+    __shared__ int32_t tile[64][65];
+    const size_t e = blockIdx.z;
+    const int n0 = blockIdx.x * 64, g0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    bool wide = false;
+    for (int r = ty; r < 64; r += 4) {
+        const int n = n0 + r, g = g0 + tx;
+        int32_t v = 0;
+        if (n < N && g < NG) v = scale[(e * N + n) * NG + g];
+        if (CHECK) wide |= ((uint32_t)(v + (1 << 23)) >> 24) != 0;
+        tile[r][tx] = v;
+    }
+    __syncthreads();
+    for (int r = ty; r < 64; r += 4) {
+        const int g = g0 + r, n = n0 + tx;
+        if (g < NG && n < N) st[(e * NG + g) * N + n] = tile[tx][r];
+    }
+    if (CHECK && __any(wide) && (threadIdx.x & (kWave - 1)) == 0) atomicOr(wide_flag, 1);
+}
+
+// Preparation, one wave per token row: xp = the activations with every 16-byte chunk reordered to
+// [even | even | odd | odd] (see the top of the file), and s8[step][m] = -8 * sum over the 128 k of the step of
+// xq[m,k], the zero-point correction of the q + 8 weight bytes (8 lanes share a step).
+__global__ __launch_bounds__(256) void prepare_activations_kernel(const int8_t* __restrict__ xq, int M, int K,
+                                                                  int8_t* __restrict__ xp, int32_t* __restrict__ s8,
+                                                                  int32_t* __restrict__ wide_flag) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *wide_flag = 0;  // prepare_scales_kernel, next in the stream, may set it
     const int m = blockIdx.x * 4 + threadIdx.x / kWave;
     if (m >= M) return;
     const int lane = threadIdx.x & (kWave - 1);
     const uint4* row = reinterpret_cast<const uint4*>(xq + (size_t)m * K);
+    uint4* prow = reinterpret_cast<uint4*>(xp + (size_t)m * K);
     const int nchunk = K >> 4;
     for (int c0 = 0; c0 < nchunk; c0 += kWave) {
         const int c = c0 + lane;
@@ -72,6 +134,12 @@ __global__ __launch_bounds__(256) void step_sums_kernel(const int8_t* __restrict
             sum = __builtin_amdgcn_sdot4((int)v.y, 0x01010101, sum, false);
             sum = __builtin_amdgcn_sdot4((int)v.z, 0x01010101, sum, false);
             sum = __builtin_amdgcn_sdot4((int)v.w, 0x01010101, sum, false);
+            uint4 p;
+            p.x = (uint32_t)pick_even(v.x, v.y);
+            p.y = (uint32_t)pick_even(v.z, v.w);
+            p.z = (uint32_t)pick_odd(v.x, v.y);
+            p.w = (uint32_t)pick_odd(v.z, v.w);
+            prow[c] = p;
         }
         sum += __shfl_xor(sum, 1, kWave);
         sum += __shfl_xor(sum, 2, kWave);
@@ -80,29 +148,15 @@ __global__ __launch_bounds__(256) void step_sums_kernel(const int8_t* __restrict
     }
 }
 
-// WIDE selects the integer scale step: false = v_mad_i32_i24 (exact while every scale fits 24 bits), true = full
-// 32-bit multiplies (exact modulo 2^32 for any scale).  Both instantiations are launched; the flag written by
-// scan_scales_kernel makes exactly one of them do the work, so neither carries the other's code or registers.
+// One output tile.  WIDE selects the integer scale step: false = v_mad_i32_i24 (exact while every scale fits 24
+// bits), true = full 32-bit multiplies (exact modulo 2^32 for any scale).  `scale_t` are the transposed scales.
 template <bool INT_SCALE, bool WIDE>
-__global__ __launch_bounds__(kThreads) void gemm_prefill_kernel(GemmArgs a, const int32_t* __restrict__ s8,
-                                                                const int32_t* __restrict__ wide_flag) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    if constexpr (INT_SCALE) {
-        if ((*wide_flag != 0) != WIDE) return;
-    }
-    constexpr int XL = kBM * 8 / kThreads;  // 16-byte activation chunks per thread and step
-    constexpr int WL = kBN * 4 / kThreads;  // 16-byte weight chunks per thread and step
-    constexpr int X_BYTES = kBM * 128, W_BYTES = kBN * 64;
-    unsigned char* lds_x = smem;                                             // [2][128][128]
-    unsigned char* lds_w = smem + 2 * X_BYTES;                               // [2][256][64]
-    // every thread stores one scale and one correction word per step (the ones past 256 / 128 are zeros nobody
-    // reads): the K loop stays one basic block, which keeps the instruction order chosen below
-    int* lds_sc = reinterpret_cast<int*>(smem + 2 * X_BYTES + 2 * W_BYTES);  // [2][512]
-    int* lds_s8 = lds_sc + 2 * kThreads;                                     // [2][512]
-
+__device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_t* __restrict__ xp,
+                                                  const int32_t* __restrict__ s8, const int32_t* __restrict__ scale_t,
+                                                  unsigned char* smem) {
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
-    const int wave = tid / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int wm = wave >> 2, wn = wave & 3;
 
     // ---- which tile.  Linear tile numbers are dealt out so that XCD x (workgroups x, x+8, ...) gets one contiguous
@@ -140,73 +194,70 @@ __global__ __launch_bounds__(kThreads) void gemm_prefill_kernel(GemmArgs a, cons
     const int steps = a.K / kStepK;
     const int row_bytes = a.K >> 1;
 
-    const rsrc_t xres = make_rsrc(a.xq + (size_t)m0 * a.K, (size_t)m_rows * a.K);
-    const rsrc_t wres = make_rsrc(a.qweight + (expert * (size_t)a.N + n0) * row_bytes, (size_t)n_rows * row_bytes);
-    const rsrc_t sres = make_rsrc(reinterpret_cast<const int*>(a.scale) + (expert * (size_t)a.N + n0) * NG,
-                                  (size_t)n_rows * NG * 4);
-    const rsrc_t zres = make_rsrc(s8, (size_t)steps * a.M * 4);
-
-    // ---- loader roles.  Thread t copies activation chunks t, t+512 (64 rows apart) and weight chunks t, t+512
-    // (128 rows apart); rows past the end of the tensors lie outside the descriptors and read as zero.  The XOR
-    // swizzles only look at row bits below those strides, so one source and one destination offset do.
-    const int x_src0 = (tid >> 3) * a.K + (tid & 7) * 16;
-    const int x_dst0 = (tid >> 3) * 128 + (((tid & 7) ^ (((tid >> 3) >> kSwzA) & 7)) << 4);
-    const int w_src0 = (tid >> 2) * row_bytes + (tid & 3) * 16;
-    const int w_dst0 = (tid >> 2) * 64 + (((2 * (tid & 3)) ^ (((tid >> 2) >> kSwzB) & 7)) << 3);  // second half: chunk index ^ 1
-    int sc_src = tid < n_rows ? tid * NG * 4 : kOutOfRange;  // advances by one scale per group
-    const int z_src = tid < m_rows ? tid * 4 : kOutOfRange;
-
-    v4i rx[XL], rw[WL];
-    int rsc, rz;
-    int ld_sub = 0;  // K steps already loaded of the current group (steps are loaded in order)
-    auto load_step = [&](int s) {
+    // ---- loader roles: per step a wave requests two 1 KB blocks of the activation tile (8 rows each) and two of the
+    // weight tile (16 rows each).  Rows past the end of a tensor lie outside its descriptor and read as zero.  A
+    // lane's LDS slot is fixed by the load; the swizzle picks the global chunk that belongs there.
+    const v4i xdesc = make_desc(xp + (size_t)m0 * a.K, (size_t)m_rows * a.K);
+    const v4i wdesc = make_desc(a.qweight + (expert * (size_t)a.N + n0) * row_bytes, (size_t)n_rows * row_bytes);
+    // wave 0 also fetches the step's 256 scales (1 KB of the transposed copy), wave 1 its 128 corrections
+    v4i adesc = make_desc(nullptr, 0);
+    int aux_voff = lane * 16, aux_inc = 0, grp_inc = 0;  // advance of aux_soff per K step / per finished group
+    if (wave == 0) {
+        adesc = make_desc(scale_t + (expert * NG) * (size_t)a.N + n0, ((size_t)(NG - 1) * a.N + n_rows) * 4);
+        grp_inc = a.N * 4;
+    } else if (wave == 1) {
+        adesc = make_desc(s8 + m0, ((size_t)(steps - 1) * a.M + m_rows) * 4);
+        if (lane >= 32) aux_voff = (int)0x80000000u;  // 128 rows = 32 lanes; the rest reads nothing
+        aux_inc = a.M * 4;
+    }
+    int aux_soff = 0;
+    int x_voff[2], w_voff[2];
 #pragma unroll
-        for (int i = 0; i < XL; ++i) rx[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, x_src0 + i * 64 * a.K, s * kStepK, 0);
+    for (int i = 0; i < 2; ++i) {
+        const int xr = 8 * (wave + 8 * i) + (lane >> 3);
+        x_voff[i] = xr * a.K + (((lane & 7) ^ ((xr >> kSwzA) & 7)) << 4);
+        const int wr = 16 * (wave + 8 * i) + (lane >> 2);
+        w_voff[i] = wr * row_bytes + (((lane & 3) ^ ((wr >> kSwzB) & 3)) << 4);
+    }
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;  // LDS byte offset
+    int ld_sub = 0;  // K steps already requested of the current group (steps are requested in order)
+    // Requests step t into stage t % kStages; past the last step the descriptors are emptied, so the same number of
+    // loads is in flight at every step and the counted waits below hold to the end.
+    auto request_step = [&](int t) {
+        const bool live = t < steps;
+        v4i xd = xdesc, wd = wdesc, ad = adesc;
+        xd[2] = live ? xdesc[2] : 0;
+        wd[2] = live ? wdesc[2] : 0;
+        ad[2] = live ? adesc[2] : 0;
+        const unsigned base = lds0 + (unsigned)(t % kStages) * kStageBytes;
 #pragma unroll
-        for (int i = 0; i < WL; ++i)
-            rw[i] = __builtin_amdgcn_raw_buffer_load_b128(wres, w_src0 + i * 128 * row_bytes, s * (kStepK / 2), 0);
-        rsc = __builtin_amdgcn_raw_buffer_load_b32(sres, sc_src, 0, 0);
-        rz = __builtin_amdgcn_raw_buffer_load_b32(zres, z_src, (s * a.M + m0) * 4, 0);
-        if (++ld_sub == spg) {
-            ld_sub = 0;
-            sc_src += 4;
-        }
-    };
-    auto store_step = [&](int buf) {
+        for (int i = 0; i < 2; ++i)
+            load_to_lds_b128(xd, base + (wave + 8 * i) * 1024, x_voff[i], t * kStepK);
 #pragma unroll
-        for (int i = 0; i < XL; ++i) {
-            v4i p;
-            p[0] = pick_even(rx[i][0], rx[i][1]);
-            p[1] = pick_even(rx[i][2], rx[i][3]);
-            p[2] = pick_odd(rx[i][0], rx[i][1]);
-            p[3] = pick_odd(rx[i][2], rx[i][3]);
-            *reinterpret_cast<v4i*>(lds_x + buf * X_BYTES + x_dst0 + i * 8192) = p;
-        }
-#pragma unroll
-        for (int i = 0; i < WL; ++i) {
-            // q -> q + 8: flip the top bit of every nibble
-            const int2 lo = make_int2(rw[i][0] ^ (int)0x88888888u, rw[i][1] ^ (int)0x88888888u);
-            const int2 hi = make_int2(rw[i][2] ^ (int)0x88888888u, rw[i][3] ^ (int)0x88888888u);
-            *reinterpret_cast<int2*>(lds_w + buf * W_BYTES + w_dst0 + i * 8192) = lo;
-            *reinterpret_cast<int2*>(lds_w + buf * W_BYTES + (w_dst0 ^ 8) + i * 8192) = hi;
-        }
-        lds_sc[buf * kThreads + tid] = rsc;
-        lds_s8[buf * kThreads + tid] = rz;
+        for (int i = 0; i < 2; ++i)
+            load_to_lds_b128(wd, base + kXBytes + (wave + 8 * i) * 1024, w_voff[i], t * (kStepK / 2));
+        if (wave < 2) load_to_lds_b128(ad, base + kXBytes + kWBytes + wave * 1024, aux_voff, aux_soff);
+        const bool group_done = ++ld_sub == spg;
+        ld_sub = group_done ? 0 : ld_sub;
+        aux_soff += aux_inc + (group_done ? grp_inc : 0);
     };
 
-    // ---- consumer roles.  MFMA 16x16x64: lane l feeds token row / weight row (l & 15) and the 16-k chunk (l >> 4) of
-    // each half step; its 4 results are weight row (l & 15), token rows 4*(l >> 4)..+3.
+    // ---- consumer roles.  MFMA 16x16x64: lane l feeds token row / weight row (l & 15) and 16 of the 64 k of each
+    // half step, chosen by (l >> 4); its 4 results are weight row (l & 15), token rows 4*(l >> 4)..+3.  Lane group
+    // lq takes the 32 k of its 16 packed weight bytes: activation chunks 2 lq (first half step) and 2 lq + 1.
     constexpr int MS = 4;  // 16-row token sub-tiles per wave
     constexpr int NS = 4;  // 16-row weight sub-tiles per wave
     const int l16 = lane & 15, lq = lane >> 4;
-    const int a_row = (wm * 64 + l16) * 128;
-    const int b_row = (wn * 64 + l16) * 64;
-    int a_off[2], b_off[2];
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-        a_off[kk] = a_row + (((4 * kk + lq) ^ ((l16 >> kSwzA) & 7)) << 4);
-        b_off[kk] = b_row + (((4 * kk + lq) ^ ((l16 >> kSwzB) & 7)) << 3);
+    int a_off[2];
+    {
+        const int ar = wm * 64 + l16;  // + 16 ms: the swizzle bits used are below 16 for kSwzA <= 1
+        a_off[0] = ar * 128 + (((2 * lq) ^ ((ar >> kSwzA) & 7)) << 4);
+        a_off[1] = ar * 128 + (((2 * lq + 1) ^ ((ar >> kSwzA) & 7)) << 4);
     }
+    const int br = wn * 64 + l16;
+    const int b_off = kXBytes + br * 64 + ((lq ^ ((br >> kSwzB) & 3)) << 4);
+    const int sc_off = kXBytes + kWBytes + (wn * 64 + l16) * 4;
+    const int ci_off = kXBytes + kWBytes + 1024 + (wm * 64 + 4 * lq) * 4;
 
     using acc4 = typename std::conditional<INT_SCALE, v4i, v4f>::type;
     acc4 acc[MS][NS];
@@ -217,33 +268,36 @@ __global__ __launch_bounds__(kThreads) void gemm_prefill_kernel(GemmArgs a, cons
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[ms][ns][r] = 0;
 
-    // One K step out of LDS buffer `buf`.  The three stages of weight sub-tile ns -- unpack, multiply, scale -- are
+    // One K step out of LDS stage `stage`.  The three phases of weight sub-tile ns -- unpack, multiply, scale -- are
     // issued as unpack(ns+2), multiply(ns+1), scale(ns), so that the matrix pipe and the vector ALU work together.
-    auto compute_step = [&](int buf) {
-        const unsigned char* xs = lds_x + buf * X_BYTES;
-        const unsigned char* ws = lds_w + buf * W_BYTES;
-        v4i af[MS][2], cinit[MS];
+    auto compute_step = [&](const unsigned char* st) {
+        v4i af[MS][2], cinit[MS], braw[NS];
+        int scl[NS];
 #pragma unroll
         for (int ms = 0; ms < MS; ++ms) {
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) af[ms][kk] = *reinterpret_cast<const v4i*>(xs + ms * 2048 + a_off[kk]);
+            for (int kk = 0; kk < 2; ++kk) af[ms][kk] = *reinterpret_cast<const v4i*>(st + ms * 2048 + a_off[kk]);
             // initial accumulator: -8 * sum_k x[m,k] for this lane's 4 token rows
-            cinit[ms] = *reinterpret_cast<const v4i*>(lds_s8 + buf * kThreads + wm * 64 + ms * 16 + 4 * lq);
+            cinit[ms] = *reinterpret_cast<const v4i*>(st + ci_off + ms * 64);
+        }
+#pragma unroll
+        for (int ns = 0; ns < NS; ++ns) {
+            braw[ns] = *reinterpret_cast<const v4i*>(st + b_off + ns * 1024);
+            scl[ns] = *reinterpret_cast<const int*>(st + sc_off + ns * 64);
         }
         v4i bfu[2][2], part[2][MS];
-        int scl[2];
         auto unpack = [&](int ns) {
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                const int2 p = *reinterpret_cast<const int2*>(ws + ns * 1024 + b_off[kk]);
-                bfu[ns & 1][kk][0] = p.x & 0x0F0F0F0F;
-                bfu[ns & 1][kk][1] = p.y & 0x0F0F0F0F;
-                bfu[ns & 1][kk][2] = (int)(((uint32_t)p.x >> 4) & 0x0F0F0F0Fu);
-                bfu[ns & 1][kk][3] = (int)(((uint32_t)p.y >> 4) & 0x0F0F0F0Fu);
+                // q -> q + 8 flips the top bit of a nibble; XOR and mask fuse into one three-input bit operation
+                const uint32_t p0 = (uint32_t)braw[ns][2 * kk], p1 = (uint32_t)braw[ns][2 * kk + 1];
+                bfu[ns & 1][kk][0] = (int)((p0 ^ 0x08080808u) & 0x0F0F0F0Fu);
+                bfu[ns & 1][kk][1] = (int)((p1 ^ 0x08080808u) & 0x0F0F0F0Fu);
+                bfu[ns & 1][kk][2] = (int)(((p0 >> 4) ^ 0x08080808u) & 0x0F0F0F0Fu);
+                bfu[ns & 1][kk][3] = (int)(((p1 >> 4) ^ 0x08080808u) & 0x0F0F0F0Fu);
             }
         };
         auto multiply = [&](int ns) {
-            scl[ns & 1] = lds_sc[buf * kThreads + wn * 64 + ns * 16 + l16];
 #pragma unroll
             for (int ms = 0; ms < MS; ++ms)
                 part[ns & 1][ms] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[ms][0], bfu[ns & 1][0], cinit[ms], 0, 0, 0);
@@ -253,7 +307,7 @@ __global__ __launch_bounds__(kThreads) void gemm_prefill_kernel(GemmArgs a, cons
                     __builtin_amdgcn_mfma_i32_16x16x64_i8(af[ms][1], bfu[ns & 1][1], part[ns & 1][ms], 0, 0, 0);
         };
         auto scale = [&](int ns) {  // per-group scale step of Table 2
-            const int sc_i = scl[ns & 1];
+            const int sc_i = scl[ns];
             const float s_f = __int_as_float(sc_i);
 #pragma unroll
             for (int ms = 0; ms < MS; ++ms)
@@ -283,18 +337,20 @@ __global__ __launch_bounds__(kThreads) void gemm_prefill_kernel(GemmArgs a, cons
         }
     };
 
-    load_step(0);
-    store_step(0);
-    __syncthreads();
-    for (int s = 0; s + 1 < steps; ++s) {
-        load_step(s + 1);
-        compute_step(s & 1);
-        store_step((s & 1) ^ 1);
-        __syncthreads();
+#pragma unroll
+    for (int t = 0; t < kStages - 1; ++t) request_step(t);
+    for (int s = 0; s < steps; ++s) {
+        // This wave's share of step s has landed once at most the loads of steps s+1 and s+2 are outstanding; past
+        // the barrier everybody's has, and nobody reads step s-1 any more, whose stage step s+3 now overwrites.
+        if (wave < 2) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((kStages - 2) * (kTileLoads + 1)) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((kStages - 2) * kTileLoads) : "memory");
+        request_step(s + kStages - 1);
+        compute_step(smem + (s % kStages) * kStageBytes);
     }
-    compute_step((steps - 1) & 1);
 
     // ---- epilogue, once per output: FLOAT(acc) * s_a[m] * c[n] / alpha (Eq. (2)), or facc * s_a[m] (Eq. (1))
+    // all requests have landed (the emptied tail ones still write zeros) and nobody reads operand tiles any more
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
     const float inv_alpha = __int_as_float((127 - a.alpha_log2) << 23);
     float sa[MS][4];
 #pragma unroll
@@ -304,6 +360,11 @@ __global__ __launch_bounds__(kThreads) void gemm_prefill_kernel(GemmArgs a, cons
             const int ml = wm * 64 + ms * 16 + 4 * lq + r;
             sa[ms][r] = ml < m_rows ? a.a_scale[m0 + ml] : 0.0f;
         }
+    // Rows of 8-aligned length go through an fp16 copy of the tile in LDS and leave as 16-byte stores, 512
+    // contiguous bytes per token row; otherwise (and for the diagnostic accumulator output) element by element.
+    const bool staged = (a.N & 7) == 0 && a.acc_out == nullptr;
+    constexpr int kPitch = 264;  // halves per LDS row: 256 + 8, so that rows keep 16-byte alignment
+    __half* otile = reinterpret_cast<__half*>(smem);
 #pragma unroll
     for (int ns = 0; ns < NS; ++ns) {
         const int nl = wn * 64 + ns * 16 + l16;
@@ -319,73 +380,100 @@ __global__ __launch_bounds__(kThreads) void gemm_prefill_kernel(GemmArgs a, cons
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int ml = wm * 64 + ms * 16 + 4 * lq + r;
-                if (ml >= m_rows) continue;
-                const size_t o = (size_t)(m0 + ml) * a.N + n;
-                if constexpr (INT_SCALE) {
-                    if (a.acc_out) a.acc_out[o] = acc[ms][ns][r];
-                    a.out[o] = __float2half_rn((float)acc[ms][ns][r] * sa[ms][r] * c);
-                } else {
-                    a.out[o] = __float2half_rn(acc[ms][ns][r] * sa[ms][r]);
+                __half h;
+                if constexpr (INT_SCALE) h = __float2half_rn((float)acc[ms][ns][r] * sa[ms][r] * c);
+                else h = __float2half_rn(acc[ms][ns][r] * sa[ms][r]);
+                if (staged) {
+                    otile[ml * kPitch + nl] = h;
+                } else if (ml < m_rows) {
+                    const size_t o = (size_t)(m0 + ml) * a.N + n;
+                    if constexpr (INT_SCALE) {
+                        if (a.acc_out) a.acc_out[o] = acc[ms][ns][r];
+                    }
+                    a.out[o] = h;
                 }
             }
     }
+    if (staged) {
+        __syncthreads();
+        const int chunk = tid & 31;  // 8 outputs
+        if (chunk * 8 < n_rows) {
+#pragma unroll
+            for (int pass = 0; pass < kBM / 16; ++pass) {
+                const int ml = pass * 16 + (tid >> 5);
+                if (ml < m_rows)
+                    *reinterpret_cast<uint4*>(a.out + (size_t)(m0 + ml) * a.N + n0 + chunk * 8) =
+                        *reinterpret_cast<const uint4*>(otile + ml * kPitch + chunk * 8);
+            }
+        }
+    }
 }
 
-// flag = 1 if any integer scale does not fit 24 signed bits (the limit of v_mad_i32_i24).
-__global__ __launch_bounds__(256) void scan_scales_kernel(const int32_t* __restrict__ scale, size_t count,
-                                                          int32_t* __restrict__ flag) {
-    bool wide = false;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (size_t)gridDim.x * 256)
-        wide |= ((uint32_t)(scale[i] + (1 << 23)) >> 24) != 0;
-    if (__any(wide) && (threadIdx.x & (kWave - 1)) == 0) atomicOr(flag, 1);
-}
-
-__global__ void clear_flag_kernel(int32_t* flag) {
-    if (threadIdx.x == 0) *flag = 0;
+// INT_SCALE: Eq. (2) with the scale step chosen by the flag the scale preparation left; else Eq. (1).
+template <bool INT_SCALE>
+__global__ __launch_bounds__(kThreads) void gemm_prefill_kernel(GemmArgs a, const int8_t* __restrict__ xp,
+                                                                const int32_t* __restrict__ s8,
+                                                                const int32_t* __restrict__ scale_t,
+                                                                const int32_t* __restrict__ wide_flag) {
+    extern __shared__ __align__(16) unsigned char smem[];  // [kStages][activations 16 KB | weights 16 KB | aux 2 KB]
+    if constexpr (INT_SCALE) {
+        if (*wide_flag != 0) gemm_prefill_tile<true, true>(a, xp, s8, scale_t, smem);
+        else gemm_prefill_tile<true, false>(a, xp, s8, scale_t, smem);
+    } else {
+        gemm_prefill_tile<false, false>(a, xp, s8, scale_t, smem);
+    }
 }
 
 template <bool INT_SCALE>
-hipError_t launch_tile(const GemmArgs& a, const int32_t* s8, const int32_t* flag, hipStream_t stream) {
-    const size_t smem = 2 * (size_t)kBM * 128 + 2 * (size_t)kBN * 64 + 4 * (size_t)kThreads * 4;
+hipError_t launch_tile(const GemmArgs& a, const int8_t* xp, const int32_t* s8, const int32_t* scale_t,
+                       const int32_t* flag, hipStream_t stream) {
+    const size_t smem = (size_t)kStages * kStageBytes;
     const int experts = a.row_offsets ? a.num_experts : 1;
     const int tiles = ((a.N + kBN - 1) / kBN) * ((a.M + kBM - 1) / kBM);
-    dim3 grid(tiles, 1, experts);
     static bool raised = false;
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_prefill_kernel<INT_SCALE, false>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_prefill_kernel<INT_SCALE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e == hipSuccess && INT_SCALE)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_prefill_kernel<INT_SCALE, true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((gemm_prefill_kernel<INT_SCALE, false>), grid, dim3(kThreads), smem, stream, a, s8, flag);
-    if (INT_SCALE)
-        hipLaunchKernelGGL((gemm_prefill_kernel<INT_SCALE, true>), grid, dim3(kThreads), smem, stream, a, s8, flag);
+    hipLaunchKernelGGL((gemm_prefill_kernel<INT_SCALE>), dim3(tiles, 1, experts), dim3(kThreads), smem, stream, a, xp,
+                       s8, scale_t, flag);
     return hipGetLastError();
 }
 
+constexpr size_t kHeaderBytes = 256;  // the workspace starts with the wide-scale flag
+size_t pad256(size_t bytes) { return (bytes + 255) & ~(size_t)255; }
+size_t corrections_bytes(int M, int K) { return pad256((size_t)(K / kStepK) * (size_t)M * 4); }
+size_t scales_bytes(int experts, int N, int K, int group) { return pad256((size_t)experts * N * (K / group) * 4); }
+
 }  // namespace
 
-constexpr size_t kHeaderBytes = 256;  // the workspace starts with the wide-scale flag
-
-size_t gemm_prefill_workspace_bytes(int M, int K) { return kHeaderBytes + (size_t)(K / kStepK) * (size_t)M * 4; }
+// workspace = [flag, padded to 256 B | s8: K/128 x M words | transposed scales: experts x K/group x N words |
+//              reordered activations: M x K bytes]
+size_t gemm_prefill_workspace_bytes(int num_experts, int M, int N, int K, int group) {
+    return kHeaderBytes + corrections_bytes(M, K) + scales_bytes(num_experts, N, K, group) + (size_t)M * K;
+}
 
 hipError_t launch_gemm_prefill(const GemmArgs& a, bool int_scale, void* workspace, hipStream_t stream) {
-    int32_t* flag = static_cast<int32_t*>(workspace);
-    int32_t* s8 = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(workspace) + kHeaderBytes);
-    hipLaunchKernelGGL(step_sums_kernel, dim3((a.M + 3) / 4), dim3(256), 0, stream, a.xq, a.M, a.K, s8);
-    if (int_scale) {
-        const int experts = a.row_offsets ? a.num_experts : 1;
-        const size_t count = (size_t)experts * a.N * (a.K / a.group);
-        hipLaunchKernelGGL(clear_flag_kernel, dim3(1), dim3(kWave), 0, stream, flag);
-        hipLaunchKernelGGL(scan_scales_kernel, dim3(512), dim3(256), 0, stream, static_cast<const int32_t*>(a.scale),
-                           count, flag);
-    }
+    const int experts = a.row_offsets ? a.num_experts : 1;
+    const int NG = a.K / a.group;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    int32_t* flag = reinterpret_cast<int32_t*>(ws);
+    int32_t* s8 = reinterpret_cast<int32_t*>(ws + kHeaderBytes);
+    int32_t* scale_t = reinterpret_cast<int32_t*>(ws + kHeaderBytes + corrections_bytes(a.M, a.K));
+    int8_t* xp = reinterpret_cast<int8_t*>(ws + kHeaderBytes + corrections_bytes(a.M, a.K) +
+                                           scales_bytes(experts, a.N, a.K, a.group));
+    hipLaunchKernelGGL(prepare_activations_kernel, dim3((a.M + 3) / 4), dim3(256), 0, stream, a.xq, a.M, a.K, xp, s8,
+                       flag);
+    const dim3 sgrid((a.N + 63) / 64, (NG + 63) / 64, experts);
+    const int32_t* scale = static_cast<const int32_t*>(a.scale);
+    if (int_scale) hipLaunchKernelGGL(prepare_scales_kernel<true>, sgrid, dim3(256), 0, stream, scale, a.N, NG, scale_t, flag);
+    else hipLaunchKernelGGL(prepare_scales_kernel<false>, sgrid, dim3(256), 0, stream, scale, a.N, NG, scale_t, flag);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return int_scale ? launch_tile<true>(a, s8, flag, stream) : launch_tile<false>(a, s8, flag, stream);
+    return int_scale ? launch_tile<true>(a, xp, s8, scale_t, flag, stream)
+                     : launch_tile<false>(a, xp, s8, scale_t, flag, stream);
 }
 
 }  // namespace intscale

@@ -46,8 +46,9 @@ hipError_t launch_quantize_weights(const __half* w, int N, int K, int group, int
                                    int* alpha_log2_dev, hipStream_t stream);
 hipError_t launch_gemm_skinny(const GemmArgs& a, bool int_scale, hipStream_t stream);
 bool try_launch_gemm_decode(const GemmArgs& a, bool int_scale, hipStream_t stream, hipError_t* err);
-// MFMA-bound tiled kernel; `workspace` holds gemm_prefill_workspace_bytes(M, K) bytes.
-size_t gemm_prefill_workspace_bytes(int M, int K);
+// MFMA-bound tiled kernel; `workspace` holds gemm_prefill_workspace_bytes(...) bytes (num_experts = 1 and M = all
+// token rows for the plain form).
+size_t gemm_prefill_workspace_bytes(int num_experts, int M, int N, int K, int group);
 hipError_t launch_gemm_prefill(const GemmArgs& a, bool int_scale, void* workspace, hipStream_t stream);
 
 }  // namespace intscale
