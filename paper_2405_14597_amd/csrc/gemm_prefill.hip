@@ -268,29 +268,53 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[ms][ns][r] = 0;
 
-    // One K step out of LDS stage `stage`.  The three phases of weight sub-tile ns -- unpack, multiply, scale -- are
-    // issued as unpack(ns+2), multiply(ns+1), scale(ns), so that the matrix pipe and the vector ALU work together.
-    auto compute_step = [&](const unsigned char* st) {
-        v4i af[MS][2], cinit[MS], braw[NS];
-        int scl[NS];
+    // Operand registers of one K step.  Two sets alternate: while step s is multiplied out of one, the other is
+    // filled from the LDS stage of step s+1, so that no step starts by waiting for LDS.
+    struct Operands {
+        v4i af[MS][2];  // activation fragments
+        v4i cinit[MS];  // initial accumulators: -8 * sum_k x[m,k] for this lane's 4 token rows
+        v4i braw[NS];   // packed weight fragments
+        int scl[NS];    // group scales
+    };
+    auto read_fragments = [&](Operands& o, const unsigned char* st) {
 #pragma unroll
-        for (int ms = 0; ms < MS; ++ms) {
+        for (int ns = 0; ns < 2; ++ns) o.braw[ns] = *reinterpret_cast<const v4i*>(st + b_off + ns * 1024);
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) af[ms][kk] = *reinterpret_cast<const v4i*>(st + ms * 2048 + a_off[kk]);
-            // initial accumulator: -8 * sum_k x[m,k] for this lane's 4 token rows
-            cinit[ms] = *reinterpret_cast<const v4i*>(st + ci_off + ms * 64);
-        }
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int ms = 0; ms < MS; ++ms) o.af[ms][kk] = *reinterpret_cast<const v4i*>(st + ms * 2048 + a_off[kk]);
+#pragma unroll
+        for (int ns = 2; ns < NS; ++ns) o.braw[ns] = *reinterpret_cast<const v4i*>(st + b_off + ns * 1024);
+    };
+    auto read_corrections = [&](Operands& o, const unsigned char* st, bool live) {
+#pragma unroll
+        for (int ms = 0; ms < MS; ++ms) o.cinit[ms] = *reinterpret_cast<const v4i*>(st + ci_off + ms * 64);
 #pragma unroll
         for (int ns = 0; ns < NS; ++ns) {
-            braw[ns] = *reinterpret_cast<const v4i*>(st + b_off + ns * 1024);
-            scl[ns] = *reinterpret_cast<const int*>(st + sc_off + ns * 64);
+            const int v = *reinterpret_cast<const int*>(st + sc_off + ns * 64);
+            o.scl[ns] = live ? v : 0;  // a step past the end contributes nothing, whatever its stage holds
         }
+    };
+    // The wait that makes step t's tile visible: this wave's requests up to step t have landed once only those of the
+    // two steps after it are outstanding (waves 0 and 1 issue one more per step), its own LDS reads are done, and past
+    // the barrier the same holds for every wave.
+    auto wait_tile_and_sync = [&]() {
+        if (wave < 2) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * (kTileLoads + 1)) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * kTileLoads) : "memory");
+    };
+
+    // One K step: cur holds step s, nxt receives step s+1.  The three phases of weight sub-tile ns -- unpack,
+    // multiply, scale -- are issued as unpack(ns+2), multiply(ns+1), scale(ns), so that the matrix pipe and the
+    // vector ALU work together.  Half way, the barrier that publishes step s+1 (everybody has then also finished
+    // reading step s out of LDS, whose stage is handed to step s+4), then the reads for nxt as its registers or
+    // their predecessors' fall free.
+    auto compute_step = [&](Operands& cur, Operands& nxt, int s) {
         v4i bfu[2][2], part[2][MS];
         auto unpack = [&](int ns) {
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
                 // q -> q + 8 flips the top bit of a nibble; XOR and mask fuse into one three-input bit operation
-                const uint32_t p0 = (uint32_t)braw[ns][2 * kk], p1 = (uint32_t)braw[ns][2 * kk + 1];
+                const uint32_t p0 = (uint32_t)cur.braw[ns][2 * kk], p1 = (uint32_t)cur.braw[ns][2 * kk + 1];
                 bfu[ns & 1][kk][0] = (int)((p0 ^ 0x08080808u) & 0x0F0F0F0Fu);
                 bfu[ns & 1][kk][1] = (int)((p1 ^ 0x08080808u) & 0x0F0F0F0Fu);
                 bfu[ns & 1][kk][2] = (int)(((p0 >> 4) ^ 0x08080808u) & 0x0F0F0F0Fu);
@@ -300,14 +324,15 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
         auto multiply = [&](int ns) {
 #pragma unroll
             for (int ms = 0; ms < MS; ++ms)
-                part[ns & 1][ms] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[ms][0], bfu[ns & 1][0], cinit[ms], 0, 0, 0);
+                part[ns & 1][ms] =
+                    __builtin_amdgcn_mfma_i32_16x16x64_i8(cur.af[ms][0], bfu[ns & 1][0], cur.cinit[ms], 0, 0, 0);
 #pragma unroll
             for (int ms = 0; ms < MS; ++ms)
                 part[ns & 1][ms] =
-                    __builtin_amdgcn_mfma_i32_16x16x64_i8(af[ms][1], bfu[ns & 1][1], part[ns & 1][ms], 0, 0, 0);
+                    __builtin_amdgcn_mfma_i32_16x16x64_i8(cur.af[ms][1], bfu[ns & 1][1], part[ns & 1][ms], 0, 0, 0);
         };
         auto scale = [&](int ns) {  // per-group scale step of Table 2
-            const int sc_i = scl[ns];
+            const int sc_i = cur.scl[ns];
             const float s_f = __int_as_float(sc_i);
 #pragma unroll
             for (int ms = 0; ms < MS; ++ms)
@@ -319,33 +344,40 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
                     else acc[ms][ns][r] += __mul24(pv, sc_i);                                       // C'' += C_g * s_g^INT
                 }
         };
+        const unsigned char* next_stage = smem + ((s + 1) % kStages) * kStageBytes;
         unpack(0);
         multiply(0);
         unpack(1);
 #pragma unroll
         for (int ns = 0; ns < NS; ++ns) {
+            if (ns == 2) {
+                wait_tile_and_sync();
+                request_step(s + kStages);
+                read_fragments(nxt, next_stage);
+            }
+            if (ns == 3) read_corrections(nxt, next_stage, s + 1 < steps);
             if (ns + 1 < NS) multiply(ns + 1);
             if (ns + 2 < NS) unpack(ns + 2);
             scale(ns);
-            // issue order inside this stage: one MFMA, then a few vector instructions, repeated
-#pragma unroll
-            for (int i = 0; i < 2 * MS; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
         }
+        // keep the accumulators whole between steps: regrouped sums over two steps (two multiplies and a 3-input add)
+        // cost more instructions than two multiply-adds
+        asm volatile(""
+                     : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[0][2]), "+v"(acc[0][3]), "+v"(acc[1][0]), "+v"(acc[1][1]),
+                       "+v"(acc[1][2]), "+v"(acc[1][3]), "+v"(acc[2][0]), "+v"(acc[2][1]), "+v"(acc[2][2]), "+v"(acc[2][3]),
+                       "+v"(acc[3][0]), "+v"(acc[3][1]), "+v"(acc[3][2]), "+v"(acc[3][3]));
     };
 
+    Operands ops0, ops1;
 #pragma unroll
-    for (int t = 0; t < kStages - 1; ++t) request_step(t);
-    for (int s = 0; s < steps; ++s) {
-        // This wave's share of step s has landed once at most the loads of steps s+1 and s+2 are outstanding; past
-        // the barrier everybody's has, and nobody reads step s-1 any more, whose stage step s+3 now overwrites.
-        if (wave < 2) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((kStages - 2) * (kTileLoads + 1)) : "memory");
-        else asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"((kStages - 2) * kTileLoads) : "memory");
-        request_step(s + kStages - 1);
-        compute_step(smem + (s % kStages) * kStageBytes);
+    for (int t = 0; t < kStages; ++t) request_step(t);
+    if (wave < 2) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(3 * (kTileLoads + 1)) : "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(3 * kTileLoads) : "memory");
+    read_fragments(ops0, smem);
+    read_corrections(ops0, smem, true);
+    for (int s = 0; s < steps; s += 2) {  // an odd count runs one idle step (zero scales) at the end
+        compute_step(ops0, ops1, s);
+        compute_step(ops1, ops0, s + 1);
     }
 
     // ---- epilogue, once per output: FLOAT(acc) * s_a[m] * c[n] / alpha (Eq. (2)), or facc * s_a[m] (Eq. (1))
