@@ -12,6 +12,10 @@ region.
 
 Prints ONE JSON line.  `value` is the whole step's algorithmic bytes per second (the regime is HBM-bound); TOPS,
 per-shape figures and the integer-scale vs float-scale speedup ride along in the same line.
+
+`--workload prefill` measures the other regime instead: the LLaMA-3-8B-shaped prefill linears (qkv 4096->6144,
+gate_up 4096->28672, down 14336->4096) at M = 4096 heavy-tailed token rows; there `value` is int8 tera-operations
+per second and the roofline is the dense int8 MFMA peak.
 """
 from __future__ import annotations
 
@@ -42,7 +46,22 @@ def parse_args():
     ap.add_argument("--no-floatscale", action="store_true", help="skip the float-scale comparison pass")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-sample-layers", type=int, default=4)
+    ap.add_argument("--workload", choices=("decode", "prefill"), default="decode")
     return ap.parse_args()
+
+
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` as measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE, scaled by what
+    the same counters read for a copy of known size); the figures sit in the profile summary of this workload as lines
+    `TRAFFIC <kernel name> <bytes per launch>`.  None when no such line exists."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload}_pmc_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for ln in open(path):
+        parts = ln.rstrip("\n").split("\t")
+        if len(parts) == 3 and parts[0] == "TRAFFIC" and parts[1] == kernel:
+            return float(parts[2])
+    return None
 
 
 class Segment:
@@ -76,6 +95,8 @@ def main():
         print("bench.py: this build measures one GPU only (one process, one MI355X); run with --gpus 1. "
               "Multi-GPU sharding is a design note, not a measured path.", file=sys.stderr)
         sys.exit(2)
+    if args.workload == "prefill":
+        return prefill_main(args)
 
     import numpy as np
     import torch
@@ -121,12 +142,15 @@ def main():
         per-kernel figures here with a rocprofv3 kernel trace)."""
         tag = "true" if int_scale else "false"
         ng = K // GROUP
-        if M <= 32:
-            mt = 1 if M <= 16 else 2
-            xs = -(-ng // 16)
-            if mt * xs <= 8 and xs <= 6:
-                xs_t, dt = {1: [(2, 4), (4, 2), (6, 1)], 2: [(2, 4), (4, 1)]}[mt][0 if xs <= 2 else 1 if xs <= 4 else 2]
-                return f"gemm_decode_kernel<{mt}, {xs_t}, {dt}, {tag}>"
+        spg = GROUP // 128
+        mt = 1 if M <= 16 else 2 if M <= 32 else 4
+        waves = 8 if mt == 4 else 16
+        xs = -(-ng // waves) * spg
+        fits = xs <= 4 if mt == 4 else (mt * xs <= 8 and xs <= 6)
+        if M <= 64 and waves <= ng and fits and 16 * ng <= 2 * waves * 64:
+            variants = {1: [(2, 4), (4, 2), (6, 1)], 2: [(2, 4), (4, 1), (4, 1)], 4: [(4, 1), (4, 1), (4, 1)]}[mt]
+            xs_t, dt = variants[0 if xs <= 2 else 1 if xs <= 4 else 2]
+            return f"gemm_decode_kernel<{mt}, {xs_t}, {dt}, {waves}, {tag}>"
         mt = 1 if M <= 16 else 2 if M <= 32 else 3 if M <= 48 else 4
         return f"gemm_skinny_kernel<{mt}, ...>"
 
@@ -206,7 +230,7 @@ def main():
     dom_bytes = dom["bytes"] / dom["launches"]
     achieved = dom_bytes / dom_us / 1e3
     roofline = dict(bound="hbm", kernel=dom_name, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=measured_traffic(dom_name, "llama2_7b_decode"),
                     avg_launch_us=round(dom_us, 3), alg_bytes_per_launch=round(dom_bytes))
 
     # ---------------------------------------------------------------- float-scale comparison (GEMM launches only)
@@ -277,6 +301,152 @@ def main():
                    "launch": "hip-graph" if use_graph else "eager", "scale_mode": "norm"},
         "tops": round(step_ops / sec_per_step / 1e12, 3),
         "hbm_frac": round(value / HBM_PEAK_GBS, 4),
+        "speedup_vs_floatscale": None if speedup is None else round(speedup, 4),
+        "floatscale_over_intscale_by_shape": fs_detail,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "shapes": shapes,
+    }
+    print(json.dumps(line))
+
+
+def prefill_main(args):
+    """LLaMA-3-8B-shaped prefill at M = 4096: per linear, the activation quantiser and the integer-scale GEMM."""
+    import numpy as np
+    import torch
+
+    import paper_2405_14597_amd as P
+    import synth_inputs as S
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    P.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    M = 4096
+    linears = list(S.LLAMA3_8B.items())
+    data = []
+    for idx, (name, (K, N)) in enumerate(linears):
+        w = torch.from_numpy(S.make_weights(3, N, K, S.seed_for(3, idx, 1))).to(dev)
+        qw = P.is_quantize_weights_int4_group(w, GROUP, ALPHA_LOG2, P.IS_SCALE_NORM)
+        del w
+        x = torch.from_numpy(S.make_activations(3, M, K, S.seed_for(3, idx, 2))).to(dev)
+        data.append(dict(name=name, K=K, N=N, qw=qw, x=x, xq=torch.empty((M, K), dtype=torch.int8, device=dev),
+                         sa=torch.empty((M,), dtype=torch.float32, device=dev),
+                         out=torch.empty((M, N), dtype=torch.float16, device=dev),
+                         ws=torch.empty(P.is_gemm_workspace_bytes(M, N, K, GROUP), dtype=torch.uint8, device=dev)))
+    torch.cuda.synchronize()
+
+    def quant(d):
+        P.is_quantize_act_int8_token(d["x"], d["xq"], d["sa"])
+
+    def gemm_is(d):
+        q = d["qw"]
+        P.is_gemm_w4a8_intscale(d["xq"], d["sa"], q.qweight, q.scale_i32, q.chan_scale, GROUP, ALPHA_LOG2, out=d["out"],
+                                workspace=d["ws"])
+
+    def gemm_fs(d):
+        q = d["qw"]
+        P.is_gemm_w4a8_floatscale(d["xq"], d["sa"], q.qweight, q.scale_f32, GROUP, out=d["out"], workspace=d["ws"])
+
+    def timed(fns, steps, warmup):
+        """fns: list of (label, callable); returns seconds per step and per-label average milliseconds."""
+        for _ in range(warmup):
+            for _, f in fns:
+                f()
+        torch.cuda.synchronize()
+        marks = []
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            ev = torch.cuda.Event(enable_timing=True)
+            ev.record()
+            for label, f in fns:
+                f()
+                nxt = torch.cuda.Event(enable_timing=True)
+                nxt.record()
+                marks.append((label, ev, nxt))
+                ev = nxt
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        per = {}
+        for label, a, b in marks:
+            per[label] = per.get(label, 0.0) + a.elapsed_time(b)
+        return (t1 - t0) / steps, {k: v / steps for k, v in per.items()}
+
+    fns = []
+    for d in data:
+        fns.append((f"quant_{d['name']}", lambda d=d: quant(d)))
+        fns.append((f"gemm_{d['name']}", lambda d=d: gemm_is(d)))
+    sec_per_step, per = timed(fns, args.steps, args.warmup)
+    step_ops = sum(S.algorithmic_ops(M, d["N"], d["K"]) for d in data)
+    shapes = []
+    gemm_ms = gemm_ops = 0.0
+    for d in data:
+        ms = per[f"gemm_{d['name']}"]
+        ops = S.algorithmic_ops(M, d["N"], d["K"])
+        gemm_ms += ms
+        gemm_ops += ops
+        shapes.append(dict(name=f"gemm_{d['name']}_M{M}", us=round(1e3 * ms, 2), tops=round(ops / ms / 1e9, 1),
+                           mfma_frac=round(ops / ms / 1e9 / MFMA_I8_PEAK_TOPS, 4),
+                           quant_us=round(1e3 * per[f"quant_{d['name']}"], 2)))
+    achieved = gemm_ops / gemm_ms / 1e9
+    kernel = "gemm_prefill_kernel<true>"
+    roofline = dict(bound="mfma", kernel=kernel, achieved=round(achieved, 1), peak=MFMA_I8_PEAK_TOPS, unit="TOP/s",
+                    frac=round(achieved / MFMA_I8_PEAK_TOPS, 4), traffic=measured_traffic(kernel, "llama3_8b_prefill"),
+                    avg_launch_us=round(1e3 * gemm_ms / len(data), 2),
+                    note="per GEMM call: the tile kernel plus its two preparation kernels (about 10 % of the call)")
+
+    speedup = fs_detail = None
+    if not args.no_floatscale:
+        n = max(3, args.steps // 2)
+        _, per_is = timed([(d["name"], lambda d=d: gemm_is(d)) for d in data], n, 2)
+        _, per_fs = timed([(d["name"], lambda d=d: gemm_fs(d)) for d in data], n, 2)
+        speedup = sum(per_fs.values()) / sum(per_is.values())
+        fs_detail = {k: round(per_fs[k] / per_is[k], 4) for k in per_is}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        d = data[0]
+        rows = 128                     # the first 128 token rows of the qkv linear: 1/32 of its work
+        K, N = d["K"], d["N"]
+        hw = O.quantize_weights_int4_group(S.make_weights(3, N, K, S.seed_for(3, 0, 1)), GROUP, ALPHA_LOG2, O.SCALE_NORM)
+        hx = S.make_activations(3, M, K, S.seed_for(3, 0, 2))[:rows]
+        t0 = time.perf_counter()
+        xq, sa = O.quantize_act_int8_token(hx)
+        ref = O.gemm_w4a8_intscale(xq, sa, hw.qweight, hw.scale_i32, hw.chan_scale, GROUP, ALPHA_LOG2)
+        dt = time.perf_counter() - t0
+        quant(d)
+        q = d["qw"]
+        out, acc = P.is_gemm_w4a8_intscale(d["xq"], d["sa"], q.qweight, q.scale_i32, q.chan_scale, GROUP, ALPHA_LOG2,
+                                           want_acc=True)
+        torch.cuda.synchronize()
+        acc_ok = bool(np.array_equal(acc[:rows].cpu().numpy(), ref.acc))
+        got = out[:rows].cpu().numpy().astype(np.float64)
+        rel = float(np.max(np.abs(got - ref.out) / np.maximum(np.abs(ref.out), 1e-3)))
+        cpu = dict(value=round(S.algorithmic_ops(rows, N, K) / dt / 1e12, 4), unit="TOP/s", cores=O.num_threads(),
+                   kind="oracle", sample=f"first {rows} of {M} token rows of the qkv linear (quantiser + integer-scale "
+                                         f"GEMM), {dt:.1f} s",
+                   parity=dict(acc_bit_exact=acc_ok, max_rel_err=rel))
+
+    value = step_ops / sec_per_step / 1e12
+    line = {
+        "metric": "W4A8 integer-scale GEMM TOPS + HBM GB/s (% roofline); speedup vs float-scale",
+        "value": round(value, 1),
+        "unit": "TOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(1e3 * sec_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": f"llama3-8b prefill linears (qkv, gate_up, down) at M={M} Student-t token rows, W4 group-128 "
+                               f"x A8 per-token, alpha=2^{ALPHA_LOG2}", "launch": "eager", "scale_mode": "norm"},
+        "mfma_frac": round(value / MFMA_I8_PEAK_TOPS, 4),
         "speedup_vs_floatscale": None if speedup is None else round(speedup, 4),
         "floatscale_over_intscale_by_shape": fs_detail,
         "roofline": roofline,
