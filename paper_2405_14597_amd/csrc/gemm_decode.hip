@@ -95,18 +95,23 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     for (int j = 0; j < 2; ++j) stage_src[j] = (int)threadIdx.x + j * T < 16 * NG ? ((int)threadIdx.x + j * T) * 4 : kOutOfRange;
     const int woff = li * row_bytes + s0 * (kStepK / 2) + kb * 16;  // inside a tile; the tile base is a scalar
 
+    // The group scales of a tile go through LDS and are needed one tile before its weights, so they travel in slots
+    // of their own, at least two deep (with one weight slot the next tile's scales must already be on their way
+    // while the current tile is multiplied).
+    constexpr int SD = DT > 1 ? DT : 2;
     v4i wq[DT][XS];
-    int scv[DT][2];
+    int scv[SD][2];
     float cs[DT];
 
-    auto issue = [&](int slot, int tile) {
-        // The scale block first: it is needed one tile earlier than the weights (it goes through LDS).
+    auto issue_scales = [&](int slot, int tile) {
         // Rows past N (ragged last tile) read as zero.
         const int sbase = tile * 16 * NG * 4;
         const int s_limit = (a.N - tile * 16) * NG * 4;  // bytes of this tile's block that exist
 #pragma unroll
         for (int j = 0; j < 2; ++j)
             scv[slot][j] = __builtin_amdgcn_raw_buffer_load_b32(sres, stage_src[j] < s_limit ? stage_src[j] : kOutOfRange, sbase, 0);
+    };
+    auto issue_weights = [&](int slot, int tile) {
         const bool row_ok = tile * 16 + li < a.N;
         const int wbase = tile * 16 * row_bytes;
 #pragma unroll
@@ -120,8 +125,10 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     };
     // First requests of the stream go out before anything else that waits on memory.
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-        if (dt < my_tiles) issue(dt, tile0 + dt * G);
+    for (int u = 0; u < SD; ++u) {
+        if (u < my_tiles) issue_scales(u, tile0 + u * G);
+        if (u < DT && u < my_tiles) issue_weights(u, tile0 + u * G);
+    }
     __builtin_amdgcn_sched_barrier(0);  // keep the compiler from hoisting the activation loads above the stream's
 
     // ---- activations of this wave's K range, MFMA-ready, loaded once
@@ -190,17 +197,23 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     // The pass over this workgroup's tiles.
     {
         stage_scales(0, 0);
+        if (SD < my_tiles) issue_scales(0, tile0 + SD * G);
         lds_barrier();
 
-        for (int k = 0; k < my_tiles; k += DT) {
+        for (int k = 0; k < my_tiles; k += SD) {
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                if (k + dt < my_tiles) {
-                    const int cur = tile0 + (k + dt) * G;
-                    // group scales of the next tile go to the other scale buffer; the barrier below publishes them
-                    if (k + dt + 1 < my_tiles) stage_scales((dt + 1) % DT, (k + dt + 1) & 1);
+            for (int u = 0; u < SD; ++u) {
+                if (k + u < my_tiles) {
+                    const int dt = u % DT;  // weight slot of this tile
+                    const int cur = tile0 + (k + u) * G;
+                    // group scales of the next tile go to the other scale buffer (the barrier below publishes them),
+                    // and their register slot takes the request for the tile SD after that one
+                    if (k + u + 1 < my_tiles) {
+                        stage_scales((u + 1) % SD, (k + u + 1) & 1);
+                        if (k + u + 1 + SD < my_tiles) issue_scales((u + 1) % SD, cur + (1 + SD) * G);
+                    }
 
-                    const int* my_scales = lds_scale + ((k + dt) & 1) * scale_ints;
+                    const int* my_scales = lds_scale + ((k + u) & 1) * scale_ints;
                     acc_t acc[MT][4];
 #pragma unroll
                     for (int t = 0; t < MT; ++t)
@@ -242,10 +255,10 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
                     }
                     const float c_out = a.chan_scale ? cs[dt] : 1.0f;
 
-                    if (k + dt + DT < my_tiles) issue(dt, cur + DT * G);  // refill the slot
+                    if (k + u + DT < my_tiles) issue_weights(dt, cur + DT * G);  // refill the slot
 
                     // partials of this tile -> LDS buffer (k+dt)&1, slot [wave][t][lane][j]
-                    int* buf = lds + ((k + dt) & 1) * part_ints;
+                    int* buf = lds + ((k + u) & 1) * part_ints;
 #pragma unroll
                     for (int t = 0; t < MT; ++t) {
                         v4i v;

@@ -1,0 +1,177 @@
+"""GPU parity at the full sizes of the five benchmark configurations, end to end (fp16 in, fp16 out) through the
+C ABI, in the launch configuration bench.py times (default kernel choice, caller-provided outputs and workspace).
+Every stage is compared with the CPU oracle on the same seeded inputs: quantised codes, float and integer scales and
+int32 accumulators bit for bit, fp16 outputs within the stated tolerance; the float-scale twin against the oracle's
+double-precision Eq. (1).
+"""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from oracle import oracle as O
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+G = 128
+
+
+@pytest.fixture(scope="module")
+def P():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2405_14597_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def check_out(got16, ref64, what):
+    got = got16.astype(np.float64)
+    big = np.abs(ref64) > 65000.0
+    if np.any(big):
+        assert bool(np.all(np.sign(got[big]) == np.sign(ref64[big]))) and bool(np.all(np.abs(got[big]) > 64900.0)), what
+    err = np.abs(got[~big] - ref64[~big])
+    ref = np.abs(ref64[~big])
+    assert bool(np.all(err <= 1e-2 * ref + 2.0 ** -24)), f"{what}: fp16 output outside 1e-2 relative"
+    assert bool(np.all(err <= (2.0 ** -11 + 2.0 ** -20) * ref + 2.0 ** -24)), f"{what}: more than one fp16 rounding"
+
+
+def check_fs(got16, fs, what):
+    err = np.abs(got16.astype(np.float64) - fs.out)
+    assert bool(np.all(err <= 1e-2 * np.abs(fs.out) + 2e-5 * fs.abs_sum + 2.0 ** -24)), f"{what}: float-scale output"
+
+
+class Layer:
+    """One linear's weights, quantised on both sides once (RAW and NORM scales for a given amplifier on demand)."""
+
+    def __init__(self, P, config, index, K, N):
+        self.P, self.K, self.N = P, K, N
+        self.w = S.make_weights(config, N, K, S.seed_for(config, index, 1))
+        self.w_dev = dev(self.w)
+        self.cache = {}
+
+    def quantised(self, alpha, mode):
+        key = (alpha, mode)
+        if key not in self.cache:
+            ref = O.quantize_weights_int4_group(self.w, G, alpha, mode)
+            got = self.P.is_quantize_weights_int4_group(self.w_dev, G, alpha, mode)
+            assert np.array_equal(host(got.qweight), ref.qweight), "int4 codes"
+            assert np.array_equal(host(got.scale_f32), ref.scale_f32), "float scales"
+            assert np.array_equal(host(got.scale_i32), ref.scale_i32), "integer scales"
+            assert np.array_equal(host(got.chan_scale), ref.chan_scale), "channel scales"
+            self.cache = {key: (ref, got)}  # keep one: the big layers would not all fit comfortably
+        return self.cache[key]
+
+
+def run_linear(P, layer, x, alpha, mode, what, float_twin=True):
+    ref_w, got_w = layer.quantised(alpha, mode)
+    M = x.shape[0]
+    xq_r, sa_r = O.quantize_act_int8_token(x)
+    ref = O.gemm_w4a8_intscale(xq_r, sa_r, ref_w.qweight, ref_w.scale_i32, ref_w.chan_scale, G, alpha)
+    xq, sa = P.is_quantize_act_int8_token(dev(x))
+    assert np.array_equal(host(xq), xq_r) and np.array_equal(host(sa), sa_r), f"{what}: activation codes"
+    # as bench.py calls it: outputs and workspace provided by the caller, no accumulator export
+    out = torch.empty((M, layer.N), dtype=torch.float16, device="cuda:0")
+    ws = torch.empty(P.is_gemm_workspace_bytes(M, layer.N, layer.K, G), dtype=torch.uint8, device="cuda:0")
+    P.is_gemm_w4a8_intscale(xq, sa, got_w.qweight, got_w.scale_i32, got_w.chan_scale, G, alpha, out=out, workspace=ws)
+    check_out(host(out), ref.out, what)
+    # and with the accumulators
+    out2, acc = P.is_gemm_w4a8_intscale(xq, sa, got_w.qweight, got_w.scale_i32, got_w.chan_scale, G, alpha, want_acc=True,
+                                        workspace=ws)
+    assert np.array_equal(host(acc), ref.acc), f"{what}: int32 accumulators"
+    check_out(host(out2), ref.out, what)
+    if float_twin:
+        fs_r = O.gemm_w4a8_floatscale(xq_r, sa_r, ref_w.qweight, ref_w.scale_f32, G)
+        fs = P.is_gemm_w4a8_floatscale(xq, sa, got_w.qweight, got_w.scale_f32, G, workspace=ws)
+        check_fs(host(fs), fs_r, what)
+    return ref
+
+
+# ------------------------------------------------------------------------------------------------ configs[1]
+@pytest.mark.parametrize("index,name", list(enumerate(S.LLAMA2_7B)))
+def test_config1_llama2_7b_decode(P, index, name):
+    K, N = S.LLAMA2_7B[name]
+    layer = Layer(P, 1, index, K, N)
+    for M in (1, 16, 64):
+        x = S.make_activations(1, M, K, S.seed_for(1, index, 2) + M)
+        ref = run_linear(P, layer, x, 10, O.SCALE_NORM, f"{name} M{M}")
+        assert ref.max_prefix.max() < 2 ** 31  # no int32 overflow at alpha = 2^10 (the paper's operating point)
+
+
+# ------------------------------------------------------------------------------------------------ configs[2]
+@pytest.mark.parametrize("index,name", [(i, n) for i, n in enumerate(S.LLAMA2_70B) if n != "up"])
+def test_config2_llama2_70b_decode_and_prefill(P, index, name):
+    K, N = S.LLAMA2_70B[name]
+    layer = Layer(P, 2, index, K, N)
+    for M in (1, 32, 2048):
+        x = S.make_activations(2, M, K, S.seed_for(2, index, 2) + M)
+        run_linear(P, layer, x, 10, O.SCALE_NORM, f"{name} M{M}", float_twin=(M != 2048 or name == "o_proj"))
+
+
+@pytest.mark.parametrize("mode", [O.SCALE_RAW, O.SCALE_NORM])
+def test_config2_amplifier_sweep(P, mode):
+    """alpha in {2^6, 2^8, 2^10, 2^12}: the integer-scale output approaches the float-scale one as alpha grows, and the
+    accumulators stay bit-exact whether or not they wrap."""
+    K, N = S.LLAMA2_70B["o_proj"]
+    layer = Layer(P, 2, 1, K, N)
+    for M in (32, 2048):
+        x = S.make_activations(2, M, K, S.seed_for(2, 1, 2) + M)
+        dist = []
+        for alpha in (6, 8, 10, 12):
+            ref = run_linear(P, layer, x, alpha, mode, f"o_proj M{M} alpha 2^{alpha}", float_twin=False)
+            ref_w, _ = layer.quantised(alpha, mode)
+            xq_r, sa_r = O.quantize_act_int8_token(x)
+            fs = O.gemm_w4a8_floatscale(xq_r, sa_r, ref_w.qweight, ref_w.scale_f32, G)
+            if ref.max_prefix.max() < 2 ** 31:
+                dist.append(float(np.sqrt(np.mean((ref.out - fs.out) ** 2))))
+        assert len(dist) >= 2 and dist[-1] < dist[0], "no convergence towards the float-scale output"
+
+
+# ------------------------------------------------------------------------------------------------ configs[3]
+@pytest.mark.parametrize("index,name", list(enumerate(S.LLAMA3_8B)))
+def test_config3_llama3_8b_prefill(P, index, name):
+    K, N = S.LLAMA3_8B[name]
+    layer = Layer(P, 3, index, K, N)
+    x = S.make_activations(3, 4096, K, S.seed_for(3, index, 2))
+    run_linear(P, layer, x, 10, O.SCALE_NORM, f"{name} M4096")
+
+
+# ------------------------------------------------------------------------------------------------ configs[4]
+@pytest.mark.parametrize("index,name", list(enumerate(S.MIXTRAL_8X7B)))
+def test_config4_mixtral_grouped(P, index, name):
+    """8 experts, 512 tokens, top-2 uniform router: 1024 token rows sorted by expert, uneven counts."""
+    K, N = S.MIXTRAL_8X7B[name]
+    E = 8
+    token, expert, offsets = S.moe_routing(512, E, 2, S.seed_for(4, index, 3))
+    x_tok = S.make_activations(4, 512, K, S.seed_for(4, index, 2))
+    x = np.ascontiguousarray(x_tok[token])
+    M = x.shape[0]
+    assert M == 1024 and len(set(np.diff(offsets).tolist())) > 1
+    qw, sf, si, cs = [], [], [], []
+    for e in range(E):
+        w = S.make_weights(4, N, K, S.seed_for(4, index, 1) + 7 * e)
+        r = O.quantize_weights_int4_group(w, G, 10, O.SCALE_NORM)
+        g = P.is_quantize_weights_int4_group(dev(w), G, 10, O.SCALE_NORM)
+        assert np.array_equal(host(g.qweight), r.qweight) and np.array_equal(host(g.scale_i32), r.scale_i32)
+        qw.append(r.qweight), sf.append(r.scale_f32), si.append(r.scale_i32), cs.append(r.chan_scale)
+    qw, sf, si, cs = np.stack(qw), np.stack(sf), np.stack(si), np.stack(cs)
+    xq_r, sa_r = O.quantize_act_int8_token(x)
+    acc_ref, out_ref = O.gemm_w4a8_intscale_grouped(xq_r, sa_r, qw, si, cs, offsets, G, 10)
+    xq, sa = P.is_quantize_act_int8_token(dev(x))
+    assert np.array_equal(host(xq), xq_r)
+    out, acc = P.is_gemm_w4a8_intscale_grouped(xq, sa, dev(qw), dev(si), dev(cs), dev(offsets), G, 10, want_acc=True)
+    assert np.array_equal(host(acc), acc_ref), "int32 accumulators"
+    # the grouped oracle hands back its output already rounded to fp16: allow the two roundings to differ by one ulp
+    got, want = host(out).astype(np.float64), out_ref.astype(np.float64)
+    assert np.all(np.abs(got - want) <= 2.0 ** -10 * np.abs(want) + 2.0 ** -24), name
+    fs_ref, fs_mag = O.gemm_w4a8_floatscale_grouped(xq_r, sa_r, qw, sf, offsets, G)
+    fs = host(P.is_gemm_w4a8_floatscale_grouped(xq, sa, dev(qw), dev(sf), dev(offsets), G)).astype(np.float64)
+    assert np.all(np.abs(fs - fs_ref) <= 1e-2 * np.abs(fs_ref) + 2e-5 * fs_mag + 2.0 ** -24)

@@ -125,7 +125,9 @@ def test_weight_quantizer_amplifier_search(P, mode):
 # ------------------------------------------------------------------------------------------------ GEMM, oracle-quantised inputs
 SHAPES = [(1, 16, 128), (1, 4096, 4096), (8, 4096, 4096), (16, 272, 1024), (17, 40, 1024), (33, 100, 2048),
           (64, 4096, 1024), (64, 48, 11008), (100, 33, 1536), (7, 1, 256), (48, 2064, 3584),
-          (65, 256, 128), (129, 300, 1024), (256, 512, 2048), (300, 700, 1152), (513, 257, 512)]
+          (65, 256, 128), (129, 300, 1024), (256, 512, 2048), (300, 700, 1152), (513, 257, 512),
+          # several 16-row tiles per workgroup in every decode variant (more than 256 tiles)
+          (1, 8208, 4096), (16, 5008, 11008), (32, 4360, 8192), (24, 4120, 1024), (64, 8208, 4096), (40, 4200, 1024)]
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
