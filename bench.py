@@ -46,8 +46,37 @@ def parse_args():
     ap.add_argument("--no-floatscale", action="store_true", help="skip the float-scale comparison pass")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-sample-layers", type=int, default=4)
-    ap.add_argument("--workload", choices=("decode", "prefill"), default="decode")
+    ap.add_argument("--workload", choices=("decode", "prefill", "moe"), default="decode")
     return ap.parse_args()
+
+
+def measured_peaks(P, torch):
+    """What this chip delivers, from the same run: a plain streaming read of 1 GiB out of HBM, and a register-only
+    loop of int8 MFMAs (the library's two probe kernels, timed with events)."""
+    dev = torch.device("cuda:0")
+    buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    buf.fill_(1)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def time_ms(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    nbytes = P.is_probe_stream_read(buf, sink)
+    ms_read = time_ms(lambda: P.is_probe_stream_read(buf, sink), 10)
+    ops = P.is_probe_mfma_i8(2000, sink)
+    ms_mfma = time_ms(lambda: P.is_probe_mfma_i8(2000, sink), 5)
+    del buf
+    return dict(hbm_read_gbs=round(nbytes / ms_read / 1e6, 1), mfma_i8_tops=round(ops / ms_mfma / 1e9, 1),
+                how="library probe kernels, same run: 1 GiB streaming read; register-only loop of independent "
+                    "v_mfma_i32_16x16x64_i8, two waves per SIMD")
 
 
 def measured_traffic(kernel, workload):
@@ -97,6 +126,8 @@ def main():
         sys.exit(2)
     if args.workload == "prefill":
         return prefill_main(args)
+    if args.workload == "moe":
+        return moe_main(args)
 
     import numpy as np
     import torch
@@ -232,6 +263,8 @@ def main():
     roofline = dict(bound="hbm", kernel=dom_name, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4), traffic=measured_traffic(dom_name, "llama2_7b_decode"),
                     avg_launch_us=round(dom_us, 3), alg_bytes_per_launch=round(dom_bytes))
+    peaks = measured_peaks(P, torch)
+    roofline["frac_of_measured_peak"] = round(achieved / peaks["hbm_read_gbs"], 4)
 
     # ---------------------------------------------------------------- float-scale comparison (GEMM launches only)
     speedup = None
@@ -304,6 +337,7 @@ def main():
         "speedup_vs_floatscale": None if speedup is None else round(speedup, 4),
         "floatscale_over_intscale_by_shape": fs_detail,
         "roofline": roofline,
+        "measured_peaks": peaks,
         "cpu_baseline": cpu,
         "shapes": shapes,
     }
@@ -395,7 +429,9 @@ def prefill_main(args):
     roofline = dict(bound="mfma", kernel=kernel, achieved=round(achieved, 1), peak=MFMA_I8_PEAK_TOPS, unit="TOP/s",
                     frac=round(achieved / MFMA_I8_PEAK_TOPS, 4), traffic=measured_traffic(kernel, "llama3_8b_prefill"),
                     avg_launch_us=round(1e3 * gemm_ms / len(data), 2),
-                    note="per GEMM call: the tile kernel plus its two preparation kernels (about 10 % of the call)")
+                    note="per GEMM call: the tile kernel plus its two preparation kernels (about 6 % of the call)")
+    peaks = measured_peaks(P, torch)
+    roofline["frac_of_measured_peak"] = round(achieved / peaks["mfma_i8_tops"], 4)
 
     speedup = fs_detail = None
     if not args.no_floatscale:
@@ -456,8 +492,156 @@ def prefill_main(args):
         "speedup_vs_floatscale": None if speedup is None else round(speedup, 4),
         "floatscale_over_intscale_by_shape": fs_detail,
         "roofline": roofline,
+        "measured_peaks": peaks,
         "cpu_baseline": cpu,
         "shapes": shapes,
+    }
+    print(json.dumps(line))
+
+
+def moe_main(args):
+    """Mixtral-8x7B-shaped expert FFN as grouped GEMMs: 8 experts, 512 tokens, top-2 uniform router (1024 token rows,
+    uneven per expert); w1 and w3 4096->14336, w2 14336->4096.  One step = quantiser + grouped integer-scale GEMM per
+    linear, over `--layers` (default 4 here) distinct sets of expert weights so that the weights come from HBM."""
+    import numpy as np
+    import torch
+
+    import paper_2405_14597_amd as P
+    import synth_inputs as S
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    P.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    E, TOKENS, TOPK = 8, 512, 2
+    L = args.layers if args.layers != 32 else 4
+    data = []
+    for idx, (name, (K, N)) in enumerate(S.MIXTRAL_8X7B.items()):
+        token, expert, offsets = S.moe_routing(TOKENS, E, TOPK, S.seed_for(4, idx, 3))
+        x = torch.from_numpy(np.ascontiguousarray(S.make_activations(4, TOKENS, K, S.seed_for(4, idx, 2))[token])).to(dev)
+        M = x.shape[0]
+        qs = []
+        for e in range(E):
+            w = torch.from_numpy(S.make_weights(4, N, K, S.seed_for(4, idx, 1) + 7 * e)).to(dev)
+            qs.append(P.is_quantize_weights_int4_group(w, GROUP, ALPHA_LOG2, P.IS_SCALE_NORM))
+            del w
+        stack = lambda f: torch.stack([f(q) for q in qs]).unsqueeze(0).repeat(L, *([1] * (f(qs[0]).dim() + 1)))
+        data.append(dict(name=name, K=K, N=N, M=M, counts=np.diff(offsets).tolist(), off=torch.from_numpy(offsets).to(dev),
+                         q=stack(lambda q: q.qweight), si=stack(lambda q: q.scale_i32), sf=stack(lambda q: q.scale_f32),
+                         c=stack(lambda q: q.chan_scale), x=x,
+                         xq=torch.empty((M, K), dtype=torch.int8, device=dev),
+                         sa=torch.empty((M,), dtype=torch.float32, device=dev),
+                         out=torch.empty((M, N), dtype=torch.float16, device=dev),
+                         ws=torch.empty(P.is_gemm_grouped_workspace_bytes(E, M, N, K, GROUP), dtype=torch.uint8, device=dev)))
+        del qs
+    torch.cuda.synchronize()
+
+    def quant(d):
+        P.is_quantize_act_int8_token(d["x"], d["xq"], d["sa"])
+
+    def gemm(d, l, int_scale):
+        if int_scale:
+            P.is_gemm_w4a8_intscale_grouped(d["xq"], d["sa"], d["q"][l], d["si"][l], d["c"][l], d["off"], GROUP, ALPHA_LOG2,
+                                            out=d["out"], workspace=d["ws"])
+        else:
+            P.is_gemm_w4a8_floatscale_grouped(d["xq"], d["sa"], d["q"][l], d["sf"][l], d["off"], GROUP, out=d["out"],
+                                              workspace=d["ws"])
+
+    def run(int_scale, with_quant, steps, warmup):
+        per = {d["name"]: 0.0 for d in data}
+        for it in range(warmup + steps):
+            if it == warmup:
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+            for d in data:
+                for l in range(L):
+                    if with_quant:
+                        quant(d)
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    gemm(d, l, int_scale)
+                    e1.record()
+                    if it >= warmup:
+                        d.setdefault("marks", []).append((e0, e1))
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / steps
+        for d in data:
+            per[d["name"]] = sum(a.elapsed_time(b) for a, b in d.pop("marks")) / (steps * L)
+        return sec, per
+
+    sec_per_step, per = run(True, True, args.steps, args.warmup)
+
+    def alg_bytes(d):  # every expert's weights and scales once, the routed rows once
+        return E * (d["N"] * d["K"] // 2 + 4 * d["N"] * (d["K"] // GROUP) + 4 * d["N"]) + d["M"] * d["K"] + 2 * d["M"] * d["N"] + 4 * d["M"]
+
+    step_bytes = L * sum(alg_bytes(d) + 3 * d["M"] * d["K"] + 4 * d["M"] for d in data)
+    step_ops = L * sum(S.algorithmic_ops(d["M"], d["N"], d["K"]) for d in data)
+    shapes = []
+    for d in data:
+        ms = per[d["name"]]
+        t_hbm = alg_bytes(d) / (HBM_PEAK_GBS * 1e9)
+        t_mfma = S.algorithmic_ops(d["M"], d["N"], d["K"]) / (MFMA_I8_PEAK_TOPS * 1e12)
+        shapes.append(dict(name=f"grouped_{d['name']}", rows_per_expert=d["counts"], us=round(1e3 * ms, 2),
+                           gbs=round(alg_bytes(d) / ms / 1e6, 1), tops=round(S.algorithmic_ops(d["M"], d["N"], d["K"]) / ms / 1e9, 1),
+                           roofline_frac=round(max(t_hbm, t_mfma) / (ms * 1e-3), 4)))
+    tot_ms = sum(per.values())
+    achieved = sum(alg_bytes(d) for d in data) / tot_ms / 1e6
+    kernel = "gemm_prefill_kernel<true>"
+    roofline = dict(bound="hbm", kernel=kernel, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=measured_traffic(kernel, "mixtral_moe"),
+                    avg_launch_us=round(1e3 * tot_ms / len(data), 2),
+                    note="per grouped call (tile kernel plus preparation kernels); near the ridge: per-shape "
+                         "roofline_frac takes the larger of the HBM and the MFMA time")
+    peaks = measured_peaks(P, torch)
+    roofline["frac_of_measured_peak"] = round(achieved / peaks["hbm_read_gbs"], 4)
+    speedup = fs_detail = None
+    if not args.no_floatscale:
+        n = max(3, args.steps // 2)
+        _, per_is = run(True, False, n, 2)
+        _, per_fs = run(False, False, n, 2)
+        speedup = sum(per_fs.values()) / sum(per_is.values())
+        fs_detail = {k: round(per_fs[k] / per_is[k], 4) for k in per_is}
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        dt, cpu_bytes, ok_all, rel_all = 0.0, 0, True, 0.0
+        for d in data:
+            xq_h = None
+            quant(d)
+            torch.cuda.synchronize()
+            x_h = d["x"].cpu().numpy()
+            q_h, si_h, c_h, off_h = (d["q"][0].cpu().numpy(), d["si"][0].cpu().numpy(), d["c"][0].cpu().numpy(),
+                                     d["off"].cpu().numpy())
+            t0 = time.perf_counter()
+            xq_h, sa_h = O.quantize_act_int8_token(x_h)
+            acc_ref, out_ref = O.gemm_w4a8_intscale_grouped(xq_h, sa_h, q_h, si_h, c_h, off_h, GROUP, ALPHA_LOG2)
+            dt += time.perf_counter() - t0
+            cpu_bytes += alg_bytes(d) + 3 * d["M"] * d["K"] + 4 * d["M"]
+            out, acc = P.is_gemm_w4a8_intscale_grouped(d["xq"], d["sa"], d["q"][0], d["si"][0], d["c"][0], d["off"], GROUP,
+                                                       ALPHA_LOG2, want_acc=True)
+            torch.cuda.synchronize()
+            ok_all = ok_all and bool(np.array_equal(acc.cpu().numpy(), acc_ref))
+            got, want = out.cpu().numpy().astype(np.float64), out_ref.astype(np.float64)
+            rel_all = max(rel_all, float(np.max(np.abs(got - want) / np.maximum(np.abs(want), 1e-3))))
+        cpu = dict(value=round(cpu_bytes / dt / 1e9, 3), unit="GB/s", cores=O.num_threads(), kind="oracle",
+                   sample=f"one of {L} weight sets, all three grouped linears (quantiser + integer-scale GEMM; the expert "
+                          f"weights were quantised on the GPU, bit-identical to the oracle's), {dt:.1f} s",
+                   parity=dict(acc_bit_exact=ok_all, max_rel_err=rel_all))
+    value = step_bytes / sec_per_step / 1e9
+    line = {
+        "metric": "W4A8 integer-scale GEMM TOPS + HBM GB/s (% roofline); speedup vs float-scale",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(1e3 * sec_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"mixtral-8x7b expert FFN (w1, w3, w2) as grouped GEMMs over {E} experts, {TOKENS} tokens top-{TOPK} "
+                               f"uniform router, W4 group-128 x A8 per-token, alpha=2^{ALPHA_LOG2}, {L} sets of expert weights",
+                   "launch": "eager", "scale_mode": "norm"},
+        "tops": round(step_ops / sec_per_step / 1e12, 3), "hbm_frac": round(value / HBM_PEAK_GBS, 4),
+        "speedup_vs_floatscale": None if speedup is None else round(speedup, 4),
+        "floatscale_over_intscale_by_shape": fs_detail, "roofline": roofline, "measured_peaks": peaks,
+        "cpu_baseline": cpu, "shapes": shapes,
     }
     print(json.dumps(line))
 

@@ -117,6 +117,17 @@ int is_gemm_w4a8_floatscale_grouped(const int8_t* xq, const float* a_scale, cons
                                     void* stream);
 size_t is_gemm_grouped_workspace_bytes(int num_experts, int M_total, int N, int K, int group);
 
+/*
+ * Measurement aids (no part of the method): the two rates the GEMMs are priced against, as this chip delivers them.
+ *   is_probe_stream_read  reads `bytes` bytes (a multiple of 16) at `src` (device) once, 16 bytes per lane
+ *   is_probe_mfma_i8      every wave of a chip-filling launch issues `iters` rounds of 16 independent
+ *                         v_mfma_i32_16x16x64_i8 on registers; *ops_out (host, may be NULL) = int8 operations done
+ * `sink` is a device int the kernels may write (4-byte aligned).  Both enqueue one kernel on `stream`; time them with
+ * events.  Errors as for the other calls.
+ */
+int is_probe_stream_read(const void* src, size_t bytes, int* sink, void* stream);
+int is_probe_mfma_i8(int iters, int* sink, double* ops_out, void* stream);
+
 /* Human-readable name of a status code (static storage). */
 const char* is_status_string(int status);
 /* Text of the last HIP error this thread's calls ran into (static storage; "" if none). */

@@ -21,6 +21,8 @@ from .binding import (  # noqa: F401
     is_gemm_w4a8_intscale,
     is_gemm_w4a8_intscale_grouped,
     is_gemm_workspace_bytes,
+    is_probe_mfma_i8,
+    is_probe_stream_read,
     is_quantize_act_int8_token,
     is_quantize_weights_int4_group,
     last_hip_error,

@@ -30,6 +30,8 @@ EXPORTED_SYMBOLS = (
     "is_gemm_w4a8_intscale_grouped",
     "is_gemm_w4a8_floatscale_grouped",
     "is_gemm_grouped_workspace_bytes",
+    "is_probe_stream_read",
+    "is_probe_mfma_i8",
     "is_status_string",
     "is_last_hip_error",
 )
@@ -79,6 +81,10 @@ def load_library() -> ctypes.CDLL:
     lib.is_gemm_w4a8_floatscale_grouped.restype = ci
     lib.is_gemm_grouped_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.is_gemm_grouped_workspace_bytes.restype = sz
+    lib.is_probe_stream_read.argtypes = [vp, sz, vp, vp]
+    lib.is_probe_stream_read.restype = ci
+    lib.is_probe_mfma_i8.argtypes = [ci, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.is_probe_mfma_i8.restype = ci
     lib.is_status_string.argtypes = [ci]
     lib.is_status_string.restype = ctypes.c_char_p
     lib.is_last_hip_error.argtypes = []
@@ -274,3 +280,18 @@ def is_gemm_w4a8_floatscale_grouped(xq, a_scale, qweight, scale_f32, row_offsets
                                                        _stream_handle(stream))
     _check("is_gemm_w4a8_floatscale_grouped", st)
     return out
+
+
+def is_probe_stream_read(src, sink, stream=None) -> int:
+    """Enqueues one streaming read of the whole tensor `src`; returns the bytes read."""
+    nbytes = (src.numel() * src.element_size()) // 16 * 16
+    _check("is_probe_stream_read", load_library().is_probe_stream_read(_p(src), nbytes, _p(sink), _stream_handle(stream)))
+    return nbytes
+
+
+def is_probe_mfma_i8(iters: int, sink, stream=None) -> float:
+    """Enqueues the int8 MFMA loop; returns the int8 operations it performs."""
+    ops = ctypes.c_double(0.0)
+    _check("is_probe_mfma_i8", load_library().is_probe_mfma_i8(iters, _p(sink), ctypes.byref(ops), _stream_handle(stream)))
+    return float(ops.value)
+

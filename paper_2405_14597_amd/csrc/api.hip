@@ -67,6 +67,17 @@ const char* is_status_string(int status) {
 
 const char* is_last_hip_error(void) { return g_hip_error; }
 
+int is_probe_stream_read(const void* src, size_t bytes, int* sink, void* stream) {
+    if (!ok_ptr(src) || sink == nullptr || (reinterpret_cast<uintptr_t>(sink) & 3u) || bytes == 0 || (bytes & 15))
+        return IS_ERR_INVALID_ARG;
+    return hip_status(launch_probe_stream_read(src, bytes, sink, static_cast<hipStream_t>(stream)));
+}
+
+int is_probe_mfma_i8(int iters, int* sink, double* ops_out, void* stream) {
+    if (iters <= 0 || sink == nullptr || (reinterpret_cast<uintptr_t>(sink) & 3u)) return IS_ERR_INVALID_ARG;
+    return hip_status(launch_probe_mfma_i8(iters, sink, ops_out, static_cast<hipStream_t>(stream)));
+}
+
 int is_quantize_weights_int4_group(const void* w_fp16, int N, int K, int group, int alpha_log2, int scale_mode,
                                    void* qweight, float* scale_f32, int32_t* scale_i32, float* chan_scale,
                                    int* alpha_log2_dev, void* stream) {

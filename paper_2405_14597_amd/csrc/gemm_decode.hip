@@ -99,6 +99,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     // of their own, at least two deep (with one weight slot the next tile's scales must already be on their way
     // while the current tile is multiplied).
     constexpr int SD = DT > 1 ? DT : 2;
+    constexpr bool kStepRefill = DT == 1 && WAVES == 8;
     v4i wq[DT][XS];
     int scv[SD][2];
     float cs[DT];
@@ -111,17 +112,23 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
         for (int j = 0; j < 2; ++j)
             scv[slot][j] = __builtin_amdgcn_raw_buffer_load_b32(sres, stage_src[j] < s_limit ? stage_src[j] : kOutOfRange, sbase, 0);
     };
-    auto issue_weights = [&](int slot, int tile) {
+    // One K step of a tile's weights: 16 bytes per lane.
+    auto issue_weight_step = [&](int slot, int i, int tile) {
         const bool row_ok = tile * 16 + li < a.N;
-        const int wbase = tile * 16 * row_bytes;
-#pragma unroll
-        for (int i = 0; i < XS; ++i)
-            wq[slot][i] = __builtin_amdgcn_raw_buffer_load_b128(wres, (row_ok && i < ns) ? woff + i * (kStepK / 2) : kOutOfRange, wbase, 0);
+        wq[slot][i] = __builtin_amdgcn_raw_buffer_load_b128(wres, (row_ok && i < ns) ? woff + i * (kStepK / 2) : kOutOfRange,
+                                                            tile * 16 * row_bytes, 0);
+    };
+    auto issue_chan_scale = [&](int slot, int tile) {
         if constexpr (INT_SCALE) {
             // channel scale of this thread's output column; columns past N (or no channel scales at all) read 0
             const bool col_ok = writer0 && tile * 16 + n_out < a.N;
             cs[slot] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(cres, col_ok ? n_out * 4 : kOutOfRange, tile * 64, 0));
         }
+    };
+    auto issue_weights = [&](int slot, int tile) {
+#pragma unroll
+        for (int i = 0; i < XS; ++i) issue_weight_step(slot, i, tile);
+        issue_chan_scale(slot, tile);
     };
     // First requests of the stream go out before anything else that waits on memory.
 #pragma unroll
@@ -214,6 +221,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
                     }
 
                     const int* my_scales = lds_scale + ((k + u) & 1) * scale_ints;
+                    const bool refill = k + u + DT < my_tiles;
                     acc_t acc[MT][4];
 #pragma unroll
                     for (int t = 0; t < MT; ++t)
@@ -228,6 +236,12 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
                             const uint32_t pk = (uint32_t)wq[dt][i][q];
                             w_even[q] = (int)((pk << 4) & 0xF0F0F0F0u);
                             w_odd[q] = (int)(pk & 0xF0F0F0F0u);
+                        }
+                        // With a single weight slot the registers of this step, now used up, take the same step of
+                        // the next tile at once, so that the stream never pauses for a whole tile (where registers
+                        // are scarce, 16 waves, the longer live ranges would spill: there the slot refills below).
+                        if constexpr (kStepRefill) {
+                            if (refill) issue_weight_step(dt, i, cur + DT * G);
                         }
                         const int s_i = i < ns ? my_scales[scale_idx[i]] : 0;
                         // Integer scale step: v_mad_i32_i24 is exact while the scale fits 24 bits (|P| <= 2^17 always
@@ -254,8 +268,10 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
                         if constexpr (MT * XS >= 8) __builtin_amdgcn_sched_barrier(0);
                     }
                     const float c_out = a.chan_scale ? cs[dt] : 1.0f;
-
-                    if (k + u + DT < my_tiles) issue_weights(dt, cur + DT * G);  // refill the slot
+                    if (refill) {
+                        if constexpr (kStepRefill) issue_chan_scale(dt, cur + DT * G);
+                        else issue_weights(dt, cur + DT * G);
+                    }
 
                     // partials of this tile -> LDS buffer (k+dt)&1, slot [wave][t][lane][j]
                     int* buf = lds + ((k + u) & 1) * part_ints;
@@ -296,20 +312,6 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
         }
     }
 
-}
-
-int g_cu_count = 0;
-
-int cu_count() {
-    if (g_cu_count == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            g_cu_count = n;
-        else
-            g_cu_count = 256;
-    }
-    return g_cu_count;
 }
 
 template <int MT, int XS, int DT, int WAVES, bool INT_SCALE>

@@ -51,4 +51,10 @@ bool try_launch_gemm_decode(const GemmArgs& a, bool int_scale, hipStream_t strea
 size_t gemm_prefill_workspace_bytes(int num_experts, int M, int N, int K, int group);
 hipError_t launch_gemm_prefill(const GemmArgs& a, bool int_scale, void* workspace, hipStream_t stream);
 
+int cu_count();  // compute units of the current device
+
+// Measurement aids: a streaming read of `bytes` bytes, and a loop of independent int8 MFMAs (*ops = operations done).
+hipError_t launch_probe_stream_read(const void* src, size_t bytes, int* sink, hipStream_t stream);
+hipError_t launch_probe_mfma_i8(int iters, int* sink, double* ops, hipStream_t stream);
+
 }  // namespace intscale
