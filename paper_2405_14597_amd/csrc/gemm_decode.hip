@@ -90,10 +90,15 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     // ---- cheap parts of this thread's roles, needed to start the stream (the rest is set up while it is in flight)
     const int n_out = threadIdx.x & 15;
     const bool writer0 = threadIdx.x < 256 * MT && (int)(threadIdx.x >> 4) < a.M;
+    // Byte offsets inside a tile; a tile's base is added per request.  The whole offset travels in the vector offset,
+    // which is what the descriptor's range check sees: rows and columns past N read as zero without a compare, and an
+    // offset that starts out of range (0x80000000 + anything below 2 GB) stays there.
     int stage_src[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) stage_src[j] = (int)threadIdx.x + j * T < 16 * NG ? ((int)threadIdx.x + j * T) * 4 : kOutOfRange;
-    const int woff = li * row_bytes + s0 * (kStepK / 2) + kb * 16;  // inside a tile; the tile base is a scalar
+    const int woff = li * row_bytes + s0 * (kStepK / 2) + kb * 16;  // step i: + 64 i (scalar, or out of range past ns)
+    const int cs_off = writer0 ? n_out * 4 : kOutOfRange;
+    const int tile_w_bytes = 16 * row_bytes, tile_s_bytes = 16 * NG * 4;
 
     // The group scales of a tile go through LDS and are needed one tile before its weights, so they travel in slots
     // of their own, at least two deep (with one weight slot the next tile's scales must already be on their way
@@ -105,25 +110,18 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     float cs[DT];
 
     auto issue_scales = [&](int slot, int tile) {
-        // Rows past N (ragged last tile) read as zero.
-        const int sbase = tile * 16 * NG * 4;
-        const int s_limit = (a.N - tile * 16) * NG * 4;  // bytes of this tile's block that exist
+        const int sbase = tile * tile_s_bytes;
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-            scv[slot][j] = __builtin_amdgcn_raw_buffer_load_b32(sres, stage_src[j] < s_limit ? stage_src[j] : kOutOfRange, sbase, 0);
+        for (int j = 0; j < 2; ++j) scv[slot][j] = __builtin_amdgcn_raw_buffer_load_b32(sres, stage_src[j] + sbase, 0, 0);
     };
     // One K step of a tile's weights: 16 bytes per lane.
     auto issue_weight_step = [&](int slot, int i, int tile) {
-        const bool row_ok = tile * 16 + li < a.N;
-        wq[slot][i] = __builtin_amdgcn_raw_buffer_load_b128(wres, (row_ok && i < ns) ? woff + i * (kStepK / 2) : kOutOfRange,
-                                                            tile * 16 * row_bytes, 0);
+        const int step_base = i < ns ? tile * tile_w_bytes + i * (kStepK / 2) : kOutOfRange;  // wave-uniform
+        wq[slot][i] = __builtin_amdgcn_raw_buffer_load_b128(wres, woff + step_base, 0, 0);
     };
     auto issue_chan_scale = [&](int slot, int tile) {
-        if constexpr (INT_SCALE) {
-            // channel scale of this thread's output column; columns past N (or no channel scales at all) read 0
-            const bool col_ok = writer0 && tile * 16 + n_out < a.N;
-            cs[slot] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(cres, col_ok ? n_out * 4 : kOutOfRange, tile * 64, 0));
-        }
+        // channel scale of this thread's output column (no channel scales at all: an empty descriptor, reads 0)
+        if constexpr (INT_SCALE) cs[slot] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(cres, cs_off + tile * 64, 0, 0));
     };
     auto issue_weights = [&](int slot, int tile) {
 #pragma unroll
@@ -140,10 +138,57 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
 
     // ---- activations of this wave's K range, MFMA-ready, loaded once
     v4i x_even[XS][MT], x_odd[XS][MT];
+    // With 64 token rows a workgroup reads 64 x K bytes of activations, several times its share of the weights, and
+    // the operand layout (a lane takes 2 x 16 bytes of one of 16 rows a whole row apart) is a poor way to fetch them:
+    // there the wave fetches 16 rows at a time the coalesced way (consecutive lanes, consecutive 16 bytes of a row's
+    // XS*128-byte slice) and turns them into the operand layout through a private piece of LDS.  No barrier: LDS
+    // serves one wave's requests in order.  Chunk index XOR row keeps both sides off each other's banks.
+    constexpr bool kStageX = WAVES == 8;
+    [[maybe_unused]] unsigned char* xstage = reinterpret_cast<unsigned char*>(lds_scale + 2 * scale_ints) + wave * (XS * 2048);
+    constexpr int kChunks = XS * 8;  // 16-byte chunks of a row's slice
+    [[maybe_unused]] auto fetch_rows = [&](int t, v4i (&raw)[XS * 2]) {
+#pragma unroll
+        for (int q = 0; q < XS * 2; ++q) {
+            const int e = q * kWave + lane, r = e / kChunks, c = e % kChunks;
+            const int m = 16 * t + r;
+            const int off = (m < a.M && c < ns * 8) ? m * a.K + s0 * kStepK + c * 16 : kOutOfRange;
+            raw[q] = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 0, 0);
+        }
+    };
+    [[maybe_unused]] auto turn_rows = [&](int t, const v4i (&raw)[XS * 2]) {
+#pragma unroll
+        for (int q = 0; q < XS * 2; ++q) {
+            const int e = q * kWave + lane, r = e / kChunks, c = e % kChunks;
+            *reinterpret_cast<v4i*>(xstage + r * (XS * 128) + ((c ^ r) << 4)) = raw[q];
+        }
+#pragma unroll
+        for (int i = 0; i < XS; ++i) {
+            const v4i x0 = *reinterpret_cast<const v4i*>(xstage + li * (XS * 128) + (((i * 8 + kb * 2) ^ li) << 4));
+            const v4i x1 = *reinterpret_cast<const v4i*>(xstage + li * (XS * 128) + (((i * 8 + kb * 2 + 1) ^ li) << 4));
+            x_even[i][t][0] = pick_even(x0[0], x0[1]);
+            x_even[i][t][1] = pick_even(x0[2], x0[3]);
+            x_even[i][t][2] = pick_even(x1[0], x1[1]);
+            x_even[i][t][3] = pick_even(x1[2], x1[3]);
+            x_odd[i][t][0] = pick_odd(x0[0], x0[1]);
+            x_odd[i][t][1] = pick_odd(x0[2], x0[3]);
+            x_odd[i][t][2] = pick_odd(x1[0], x1[1]);
+            x_odd[i][t][3] = pick_odd(x1[2], x1[3]);
+        }
+    };
+    if constexpr (kStageX) {
+        static_assert(!kStageX || kChunks == 32, "the staging swizzle assumes 32 chunks per row slice");
+        v4i raw[2][XS * 2];
+        fetch_rows(0, raw[0]);
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            if (t + 1 < MT) fetch_rows(t + 1, raw[(t + 1) & 1]);  // the next 16 rows are on their way meanwhile
+            turn_rows(t, raw[t & 1]);
+        }
+    }
 #pragma unroll
     for (int i = 0; i < XS; ++i)
 #pragma unroll
-        for (int t = 0; t < MT; ++t) {
+        for (int t = 0; t < (kStageX ? 0 : MT); ++t) {
             const int m = 16 * t + li;
             const int off = (i < ns && m < a.M) ? m * a.K + (s0 + i) * kStepK + kb * 32 : kOutOfRange;
             const v4i x0 = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 0, 0);
@@ -178,7 +223,9 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int f = threadIdx.x + j * T;
-        const int r = f / NG;
+        // f / NG for f < 2048, NG <= 128: (f + 0.5) / NG is at least 0.5 / NG away from an integer, far more than the
+        // rounding error of the float product
+        const int r = (int)(((float)f + 0.5f) * (1.0f / (float)NG));
         stage_dst[j] = f < 16 * NG ? r * srow_ints + (f - r * NG) : -1;
     }
 
@@ -316,13 +363,14 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
 
 template <int MT, int XS, int DT, int WAVES, bool INT_SCALE>
 hipError_t launch_decode(const GemmArgs& a, const DecodePlan& p, int grid, hipStream_t stream) {
-    const size_t smem = 2 * (size_t)WAVES * MT * kWave * 16 + 2 * 16 * (size_t)(p.num_groups + 1) * 4;
+    const size_t smem = 2 * (size_t)WAVES * MT * kWave * 16 + 2 * 16 * (size_t)(p.num_groups + 1) * 4 +
+                        (WAVES == 8 ? (size_t)WAVES * XS * 2048 : 0);  // + the activation staging of the 8-wave form
     auto kern = gemm_decode_kernel<MT, XS, DT, WAVES, INT_SCALE>;
     if (smem > 64 * 1024) {
         static bool raised = false;  // per instantiation
         if (!raised) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
             if (e != hipSuccess) return e;
             raised = true;
         }
