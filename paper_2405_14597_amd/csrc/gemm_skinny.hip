@@ -110,6 +110,18 @@ __global__ __launch_bounds__(max_waves(MT, R, D) * kWave) void gemm_skinny_kerne
     }
 #pragma unroll
     for (int t = 0; t < MT; ++t) xoff[t] = 16 * t + li < m_rows ? (16 * t + li) * a.K + kb * 32 : kOutOfRange;
+    // With 48 or 64 token rows the activations are most of what a workgroup reads, and the operand layout (a lane
+    // takes 2 x 16 bytes of one of 16 rows a whole row apart) is a poor way to fetch them.  There a step's rows are
+    // fetched the coalesced way instead -- request q: lane l takes chunk (l & 7) of row 8 q + (l >> 3), whole 128-byte
+    // lines -- and turned into the operand layout through a private piece of LDS when the step is consumed (no
+    // barrier: LDS serves one wave's requests in order; chunk index XOR row keeps both sides off each other's banks).
+    constexpr bool kStageX = MT >= 3;
+    [[maybe_unused]] const int xrow_off = (lane >> 3) * a.K + (lane & 7) * 16;  // rows past m_rows: past the descriptor
+    [[maybe_unused]] unsigned char* xstage =
+        smem_raw + (size_t)nwaves * R * MT * kWave * sizeof(v4i) + (size_t)wave * (MT * 2048);
+    [[maybe_unused]] const int st_wr = (lane >> 3) * 128 + (((lane & 7) ^ ((lane >> 3) & 7)) << 4);
+    [[maybe_unused]] const int st_rd0 = li * 128 + (((2 * kb) ^ (li & 7)) << 4);
+    [[maybe_unused]] const int st_rd1 = li * 128 + (((2 * kb + 1) ^ (li & 7)) << 4);
 
     // Groups of this wave: an even split of NG over the waves, the first (NG % nwaves) waves take one more.
     const int gq = NG / nwaves, gr = NG % nwaves;
@@ -139,9 +151,15 @@ __global__ __launch_bounds__(max_waves(MT, R, D) * kWave) void gemm_skinny_kerne
         for (int r = 0; r < R; ++r) wq[slot][r] = load16(wres, live ? woff[r] : kOutOfRange, nx_w);
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
-            const int xo = live ? xoff[t] : kOutOfRange;
-            xa[slot][t][0] = load16(xres, xo, nx_x);
-            xa[slot][t][1] = load16(xres, xo, nx_x + 16);
+            if constexpr (kStageX) {
+                // the range check sees the vector offset only: the row term goes there, the step term is scalar
+                xa[slot][t][0] = load16(xres, live ? xrow_off + (2 * t) * 8 * a.K : kOutOfRange, nx_x);
+                xa[slot][t][1] = load16(xres, live ? xrow_off + (2 * t + 1) * 8 * a.K : kOutOfRange, nx_x);
+            } else {
+                const int xo = live ? xoff[t] : kOutOfRange;
+                xa[slot][t][0] = load16(xres, xo, nx_x);
+                xa[slot][t][1] = load16(xres, xo, nx_x + 16);
+            }
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) sc[slot][r] = load4(sres, live ? soff[r] : kOutOfRange, nx_g);
@@ -181,9 +199,20 @@ __global__ __launch_bounds__(max_waves(MT, R, D) * kWave) void gemm_skinny_kerne
                 }
             }
             v4i x_even[MT], x_odd[MT];
+            if constexpr (kStageX) {
+#pragma unroll
+                for (int q = 0; q < 2 * MT; ++q) *reinterpret_cast<v4i*>(xstage + q * 1024 + st_wr) = xa[d][q >> 1][q & 1];
+            }
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
-                const v4i x0 = xa[d][t][0], x1 = xa[d][t][1];
+                v4i x0, x1;
+                if constexpr (kStageX) {
+                    x0 = *reinterpret_cast<const v4i*>(xstage + t * 2048 + st_rd0);
+                    x1 = *reinterpret_cast<const v4i*>(xstage + t * 2048 + st_rd1);
+                } else {
+                    x0 = xa[d][t][0];
+                    x1 = xa[d][t][1];
+                }
                 x_even[t][0] = pick_even(x0[0], x0[1]);
                 x_even[t][1] = pick_even(x0[2], x0[3]);
                 x_even[t][2] = pick_even(x1[0], x1[1]);
@@ -334,7 +363,8 @@ SkinnyConfig choose_config(const GemmArgs& a) {
     }
     c.r = env_int("INTSCALE_SKINNY_R", c.r);
     if (c.r != 1 && c.r != 2 && c.r != 4) c.r = 1;
-    c.d = (c.mt * c.r >= 8) ? 2 : 4;
+    // 48 or 64 token rows: the staged activations leave registers for two steps in flight, not four
+    c.d = (c.mt >= 3 || c.mt * c.r >= 8) ? 2 : 4;
     c.d = env_int("INTSCALE_SKINNY_D", c.d);
     if (c.d != 2 && c.d != 4) c.d = 2;
     const long long tiles = (long long)((a.N + 16 * c.r - 1) / (16 * c.r)) * m_chunks;
@@ -353,11 +383,24 @@ template <int MT, int R, int D, bool INT_SCALE>
 hipError_t launch_one(const GemmArgs& a, const SkinnyConfig& c, hipStream_t stream) {
     const int experts = a.row_offsets ? a.num_experts : 1;
     dim3 grid((a.N + 16 * R - 1) / (16 * R), (a.M + 16 * MT - 1) / (16 * MT), experts);
-    const size_t smem = (size_t)c.nwaves * R * MT * kWave * sizeof(v4i);
-    if (a.group == kStepK)
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, R, D, INT_SCALE, true>), grid, dim3(c.nwaves * kWave), smem, stream, a);
-    else
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, R, D, INT_SCALE, false>), grid, dim3(c.nwaves * kWave), smem, stream, a);
+    // reduction slots, then (48 or 64 token rows) one step of activations per wave
+    const size_t smem = (size_t)c.nwaves * R * MT * kWave * sizeof(v4i) + (MT >= 3 ? (size_t)c.nwaves * MT * 2048 : 0);
+    auto k1 = gemm_skinny_kernel<MT, R, D, INT_SCALE, true>;
+    auto k2 = gemm_skinny_kernel<MT, R, D, INT_SCALE, false>;
+    if (smem > 64 * 1024) {
+        static bool raised = false;  // per instantiation
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               160 * 1024);
+            if (e == hipSuccess)
+                e = hipFuncSetAttribute(reinterpret_cast<const void*>(k2), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        160 * 1024);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    if (a.group == kStepK) hipLaunchKernelGGL(k1, grid, dim3(c.nwaves * kWave), smem, stream, a);
+    else hipLaunchKernelGGL(k2, grid, dim3(c.nwaves * kWave), smem, stream, a);
     return hipGetLastError();
 }
 
