@@ -68,21 +68,15 @@ __device__ __forceinline__ v4i make_desc(const void* base, size_t bytes) {
     return d;
 }
 
-// 64 lanes x 16 bytes (or x 4 bytes) from global memory to LDS at lds_base + lane * 16 (* 4).  Completion is visible
-// through the vector memory counter only.
-__device__ __forceinline__ void load_to_lds_b128(v4i desc, unsigned lds_base, int voffset, int soffset) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+// 64 lanes x 16 bytes from global memory to LDS at lds_base + lds_offset + lane * 16.  Completion is visible through
+// the vector memory counter only.
+__device__ __forceinline__ void load_to_lds_b128(v4i desc, unsigned lds_base, unsigned lds_offset, int voffset,
+                                                 int soffset) {
+    asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, %4 offen lds"
                  :
-                 : "s"(lds_base), "v"(voffset), "s"(desc), "s"(soffset)
-                 : "memory");
+                 : "s"(lds_base), "s"(lds_offset), "v"(voffset), "s"(desc), "s"(soffset)
+                 : "memory", "scc");
 }
-__device__ __forceinline__ void load_to_lds_b32(v4i desc, unsigned lds_base, int voffset, int soffset) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
-                 :
-                 : "s"(lds_base), "v"(voffset), "s"(desc), "s"(soffset)
-                 : "memory");
-}
-
 __device__ __forceinline__ int pick_even(uint32_t lo, uint32_t hi) { return (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u); }
 __device__ __forceinline__ int pick_odd(uint32_t lo, uint32_t hi) { return (int)__builtin_amdgcn_perm(hi, lo, 0x07050301u); }
 
@@ -210,7 +204,6 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
         if (lane >= 32) aux_voff = (int)0x80000000u;  // 128 rows = 32 lanes; the rest reads nothing
         aux_inc = a.M * 4;
     }
-    int aux_soff = 0;
     int x_voff[2], w_voff[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -220,23 +213,24 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
         w_voff[i] = wr * row_bytes + (((lane & 3) ^ ((wr >> kSwzB) & 3)) << 4);
     }
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;  // LDS byte offset
+    // Request state, all scalar and advanced by additions: the stage's LDS base, the step's offsets into the two
+    // tensors, the scale / correction offset.  Steps past the last one request nothing.
+    const unsigned lds_x0 = wave * 1024, lds_x1 = lds_x0 + 8192, lds_w0 = kXBytes + lds_x0, lds_w1 = kXBytes + lds_x1;
+    const unsigned lds_aux = kXBytes + kWBytes + wave * 1024;
+    unsigned rq_base = lds0;
+    int rq_x = 0, rq_w = 0, aux_soff = 0;
     int ld_sub = 0;  // K steps already requested of the current group (steps are requested in order)
-    // Requests step t into stage t % kStages; past the last step the descriptors are emptied, so the same number of
-    // loads is in flight at every step and the counted waits below hold to the end.
     auto request_step = [&](int t) {
-        const bool live = t < steps;
-        v4i xd = xdesc, wd = wdesc, ad = adesc;
-        xd[2] = live ? xdesc[2] : 0;
-        wd[2] = live ? wdesc[2] : 0;
-        ad[2] = live ? adesc[2] : 0;
-        const unsigned base = lds0 + (unsigned)(t % kStages) * kStageBytes;
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            load_to_lds_b128(xd, base + (wave + 8 * i) * 1024, x_voff[i], t * kStepK);
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            load_to_lds_b128(wd, base + kXBytes + (wave + 8 * i) * 1024, w_voff[i], t * (kStepK / 2));
-        if (wave < 2) load_to_lds_b128(ad, base + kXBytes + kWBytes + wave * 1024, aux_voff, aux_soff);
+        if (t < steps) {
+            load_to_lds_b128(xdesc, rq_base, lds_x0, x_voff[0], rq_x);
+            load_to_lds_b128(xdesc, rq_base, lds_x1, x_voff[1], rq_x);
+            load_to_lds_b128(wdesc, rq_base, lds_w0, w_voff[0], rq_w);
+            load_to_lds_b128(wdesc, rq_base, lds_w1, w_voff[1], rq_w);
+            if (wave < 2) load_to_lds_b128(adesc, rq_base, lds_aux, aux_voff, aux_soff);
+        }
+        rq_x += kStepK;
+        rq_w += kStepK / 2;
+        rq_base = rq_base + kStageBytes == lds0 + kStages * kStageBytes ? lds0 : rq_base + kStageBytes;
         const bool group_done = ++ld_sub == spg;
         ld_sub = group_done ? 0 : ld_sub;
         aux_soff += aux_inc + (group_done ? grp_inc : 0);
@@ -286,20 +280,19 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
 #pragma unroll
         for (int ns = 2; ns < NS; ++ns) o.braw[ns] = *reinterpret_cast<const v4i*>(st + b_off + ns * 1024);
     };
-    auto read_corrections = [&](Operands& o, const unsigned char* st, bool live) {
+    auto read_corrections = [&](Operands& o, const unsigned char* st) {
 #pragma unroll
         for (int ms = 0; ms < MS; ++ms) o.cinit[ms] = *reinterpret_cast<const v4i*>(st + ci_off + ms * 64);
 #pragma unroll
-        for (int ns = 0; ns < NS; ++ns) {
-            const int v = *reinterpret_cast<const int*>(st + sc_off + ns * 64);
-            o.scl[ns] = live ? v : 0;  // a step past the end contributes nothing, whatever its stage holds
-        }
+        for (int ns = 0; ns < NS; ++ns) o.scl[ns] = *reinterpret_cast<const int*>(st + sc_off + ns * 64);
     };
     // The wait that makes step t's tile visible: this wave's requests up to step t have landed once only those of the
-    // two steps after it are outstanding (waves 0 and 1 issue one more per step), its own LDS reads are done, and past
-    // the barrier the same holds for every wave.
-    auto wait_tile_and_sync = [&]() {
-        if (wave < 2) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * (kTileLoads + 1)) : "memory");
+    // two steps after it are outstanding (waves 0 and 1 issue one more per step; near the end fewer steps are in
+    // flight and the wait is for all of them), its own LDS reads are done, and past the barrier the same holds for
+    // every wave.
+    auto wait_tile_and_sync = [&](bool full_flight) {
+        if (!full_flight) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");  // the last steps
+        else if (wave < 2) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * (kTileLoads + 1)) : "memory");
         else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * kTileLoads) : "memory");
     };
 
@@ -351,11 +344,11 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
 #pragma unroll
         for (int ns = 0; ns < NS; ++ns) {
             if (ns == 2) {
-                wait_tile_and_sync();
+                wait_tile_and_sync(s + kStages - 1 < steps);  // steps s+2 and s+3 were both requested
                 request_step(s + kStages);
                 read_fragments(nxt, next_stage);
             }
-            if (ns == 3) read_corrections(nxt, next_stage, s + 1 < steps);
+            if (ns == 3) read_corrections(nxt, next_stage);
             if (ns + 1 < NS) multiply(ns + 1);
             if (ns + 2 < NS) unpack(ns + 2);
             scale(ns);
@@ -371,13 +364,14 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
     Operands ops0, ops1;
 #pragma unroll
     for (int t = 0; t < kStages; ++t) request_step(t);
-    if (wave < 2) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(3 * (kTileLoads + 1)) : "memory");
+    if (steps < kStages) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    else if (wave < 2) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(3 * (kTileLoads + 1)) : "memory");
     else asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(3 * kTileLoads) : "memory");
     read_fragments(ops0, smem);
-    read_corrections(ops0, smem, true);
-    for (int s = 0; s < steps; s += 2) {  // an odd count runs one idle step (zero scales) at the end
+    read_corrections(ops0, smem);
+    for (int s = 0; s < steps; s += 2) {
         compute_step(ops0, ops1, s);
-        compute_step(ops1, ops0, s + 1);
+        if (s + 1 < steps) compute_step(ops1, ops0, s + 1);  // uniform over the workgroup (it holds a barrier)
     }
 
     // ---- epilogue, once per output: FLOAT(acc) * s_a[m] * c[n] / alpha (Eq. (2)), or facc * s_a[m] (Eq. (1))
