@@ -91,7 +91,8 @@ __global__ __launch_bounds__(256) void prepare_scales_kernel(const int32_t* __re
     const int n0 = blockIdx.x * 64, g0 = blockIdx.y * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     bool wide = false;
-    for (int r = ty; r < 64; r += 4) {
+#pragma unroll
+    for (int r = ty; r < 64; r += 4) {  // unrolled: the 16 loads of a thread are in flight together
         const int n = n0 + r, g = g0 + tx;
         int32_t v = 0;
         if (n < N && g < NG) v = scale[(e * N + n) * NG + g];
@@ -99,6 +100,7 @@ __global__ __launch_bounds__(256) void prepare_scales_kernel(const int32_t* __re
         tile[r][tx] = v;
     }
     __syncthreads();
+#pragma unroll
     for (int r = ty; r < 64; r += 4) {
         const int g = g0 + r, n = n0 + tx;
         if (g < NG && n < N) st[(e * NG + g) * N + n] = tile[tx][r];
