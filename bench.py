@@ -175,12 +175,17 @@ def main():
         ng = K // GROUP
         spg = GROUP // 128
         mt = 1 if M <= 16 else 2 if M <= 32 else 4
-        waves = 8 if mt == 4 else 16
+        xs16 = -(-ng // 16) * spg
+        waves = 16 if (mt == 1 or (mt == 2 and xs16 <= 2)) else 8
         xs = -(-ng // waves) * spg
-        fits = xs <= 4 if mt == 4 else (mt * xs <= 8 and xs <= 6)
+        fits = xs <= (6 if mt == 1 else (2 if waves == 16 else 8) if mt == 2 else 4)
         if M <= 64 and waves <= ng and fits and 16 * ng <= 2 * waves * 64:
-            variants = {1: [(2, 4), (4, 2), (6, 1)], 2: [(2, 4), (4, 1), (4, 1)], 4: [(4, 1), (4, 1), (4, 1)]}[mt]
-            xs_t, dt = variants[0 if xs <= 2 else 1 if xs <= 4 else 2]
+            if mt == 1:
+                xs_t, dt = (2, 4) if xs <= 2 else (4, 2) if xs <= 4 else (6, 1)
+            elif mt == 2:
+                xs_t, dt = (2, 4) if waves == 16 else (8, 1)
+            else:
+                xs_t, dt = 4, 1
             return f"gemm_decode_kernel<{mt}, {xs_t}, {dt}, {waves}, {tag}>"
         mt = 1 if M <= 16 else 2 if M <= 32 else 3 if M <= 48 else 4
         return f"gemm_skinny_kernel<{mt}, ...>"

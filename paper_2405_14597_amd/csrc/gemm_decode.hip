@@ -22,7 +22,10 @@
 // 32 int4 weights with one 16-byte load from the canonical row-major packing.
 //
 // int4 -> int8: a nibble in the high half of a byte is 16*q as a signed byte ((p << 4) & 0xF0F0F0F0 for even k,
-// p & 0xF0F0F0F0 for odd k).  The MFMA pair returns 16*P exactly (|16 P| <= 2^21), one shift recovers P.
+// p & 0xF0F0F0F0 for odd k).  The MFMA pair returns 16*P exactly (|16 P| <= 2^21), one shift recovers P.  (A zero
+// point instead, q + 8 with the correction -8 * sum_k x as the MFMA's initial accumulator, saves that shift but puts
+// an LDS read of the correction in front of every MFMA pair; measured here it made every shape 5-15 % slower: what
+// bounds this kernel is the chain of dependent latencies per tile, not the count of vector instructions.)
 //
 // The scale step runs once per 128-wide step with that step's group scale; for groups wider than 128 this is the
 // same integer by distributivity ((P1 + P2) * s = P1 * s + P2 * s modulo 2^32).
@@ -86,6 +89,9 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     const int srow_ints = NG + 1;
     int* lds_scale = lds + 2 * part_ints;
     const int scale_ints = 16 * srow_ints;
+    // then, per scale buffer, one word per wave: "a scale staged by this wave does not fit 24 bits"; then (64 token
+    // rows) the activation staging
+    int* lds_wide = lds_scale + 2 * scale_ints;
 
     // ---- cheap parts of this thread's roles, needed to start the stream (the rest is set up while it is in flight)
     const int n_out = threadIdx.x & 15;
@@ -93,9 +99,6 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     // Byte offsets inside a tile; a tile's base is added per request.  The whole offset travels in the vector offset,
     // which is what the descriptor's range check sees: rows and columns past N read as zero without a compare, and an
     // offset that starts out of range (0x80000000 + anything below 2 GB) stays there.
-    int stage_src[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) stage_src[j] = (int)threadIdx.x + j * T < 16 * NG ? ((int)threadIdx.x + j * T) * 4 : kOutOfRange;
     const int woff = li * row_bytes + s0 * (kStepK / 2) + kb * 16;  // step i: + 64 i (scalar, or out of range past ns)
     const int cs_off = writer0 ? n_out * 4 : kOutOfRange;
     const int tile_w_bytes = 16 * row_bytes, tile_s_bytes = 16 * NG * 4;
@@ -104,22 +107,38 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     // of their own, at least two deep (with one weight slot the next tile's scales must already be on their way
     // while the current tile is multiplied).
     constexpr int SD = DT > 1 ? DT : 2;
+    // Where the "some scale needs more than 24 bits" test of the integer scale step is made: once per tile while its
+    // scales are staged (one word of LDS per wave and tile; pays with several token tiles, where it keeps the branch
+    // out of every step), else per step on the scales just read (one token tile: an LDS read more per tile would
+    // lengthen the chain of dependent latencies that bounds those shapes).
+    constexpr bool kTileFlag = MT >= 2;
     constexpr bool kStepRefill = DT == 1 && WAVES == 8;
     v4i wq[DT][XS];
-    int scv[SD][2];
+    // words of a tile's 16 x NG block of scales each thread copies: NG <= XS * WAVES by construction of the plan
+    constexpr int SJ = (16 * XS * WAVES + T - 1) / T;
+    int scv[SD][SJ];
     float cs[DT];
 
+    // (The tile number is made opaque to the optimiser in these requests: it would otherwise keep one precomputed
+    // vector offset per unrolled position of the tile loop for the whole kernel, and spill.)
     auto issue_scales = [&](int slot, int tile) {
+        asm volatile("" : "+s"(tile));
         const int sbase = tile * tile_s_bytes;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) scv[slot][j] = __builtin_amdgcn_raw_buffer_load_b32(sres, stage_src[j] + sbase, 0, 0);
+        for (int j = 0; j < SJ; ++j) {
+            // thread u fetches words u (and u + T) of the tile's block of 16 x NG scales
+            const int f = (int)threadIdx.x + j * T;
+            scv[slot][j] = __builtin_amdgcn_raw_buffer_load_b32(sres, (f < 16 * NG ? f * 4 : kOutOfRange) + sbase, 0, 0);
+        }
     };
     // One K step of a tile's weights: 16 bytes per lane.
     auto issue_weight_step = [&](int slot, int i, int tile) {
+        asm volatile("" : "+s"(tile));
         const int step_base = i < ns ? tile * tile_w_bytes + i * (kStepK / 2) : kOutOfRange;  // wave-uniform
         wq[slot][i] = __builtin_amdgcn_raw_buffer_load_b128(wres, woff + step_base, 0, 0);
     };
     auto issue_chan_scale = [&](int slot, int tile) {
+        asm volatile("" : "+s"(tile));
         // channel scale of this thread's output column (no channel scales at all: an empty descriptor, reads 0)
         if constexpr (INT_SCALE) cs[slot] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(cres, cs_off + tile * 64, 0, 0));
     };
@@ -143,8 +162,8 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     // there the wave fetches 16 rows at a time the coalesced way (consecutive lanes, consecutive 16 bytes of a row's
     // XS*128-byte slice) and turns them into the operand layout through a private piece of LDS.  No barrier: LDS
     // serves one wave's requests in order.  Chunk index XOR row keeps both sides off each other's banks.
-    constexpr bool kStageX = WAVES == 8;
-    [[maybe_unused]] unsigned char* xstage = reinterpret_cast<unsigned char*>(lds_scale + 2 * scale_ints) + wave * (XS * 2048);
+    constexpr bool kStageX = WAVES == 8 && MT == 4;
+    [[maybe_unused]] unsigned char* xstage = reinterpret_cast<unsigned char*>(lds_wide + 2 * W) + wave * (XS * 2048);
     constexpr int kChunks = XS * 8;  // 16-byte chunks of a row's slice
     [[maybe_unused]] auto fetch_rows = [&](int t, v4i (&raw)[XS * 2]) {
 #pragma unroll
@@ -204,7 +223,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
         }
 
     // ---- role of this thread in the epilogue: outputs (m_out[o], tile*16 + n_out) of every tile
-    int m_out[OPT], src_slot[OPT];
+    int m_out[OPT];
     float sa_out[OPT];
     bool writer[OPT];
 #pragma unroll
@@ -212,29 +231,23 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
         m_out[o] = (threadIdx.x + o * T) >> 4;  // 0 .. 16*MT-1 for the threads that take part
         writer[o] = threadIdx.x + o * T < 256 * MT && m_out[o] < a.M;
         sa_out[o] = writer[o] ? a.a_scale[m_out[o]] : 0.0f;
-        // where that output sits in a wave's partials: tile t, lane (4 rows per lane-group), register j
-        src_slot[o] = ((m_out[o] >> 4) * kWave + ((m_out[o] & 15) >> 2) * 16 + n_out) * 4 + (m_out[o] & 3);
     }
     const float inv_alpha = __int_as_float((127 - a.alpha_log2) << 23);  // 2^-alpha_log2, exact
 
     // ---- role of this thread in staging a tile's group scales: the tile's 16 x NG scales are one contiguous block
-    // of the scale tensor; thread u copies words u and u + T of it (16 * NG <= 2 * T is checked by the host).
-    int stage_dst[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int f = threadIdx.x + j * T;
-        // f / NG for f < 2048, NG <= 128: (f + 0.5) / NG is at least 0.5 / NG away from an integer, far more than the
-        // rounding error of the float product
-        const int r = (int)(((float)f + 0.5f) * (1.0f / (float)NG));
-        stage_dst[j] = f < 16 * NG ? r * srow_ints + (f - r * NG) : -1;
-    }
+    // of the scale tensor; thread u copies word u (and u + T where NG can exceed T / 16) of it.  Word f
+    // = (row r, group c) goes to LDS word r * (NG + 1) + c = f + r.
+    const float inv_ng = 1.0f / (float)NG, half_inv_ng = 0.5f * inv_ng;
 
-    int scale_idx[XS];  // LDS word of the group scale of step i for this lane's weight row
+    // LDS word of the group scale of step i for this lane's weight row: scale_row + group_of[i], the latter the same
+    // for the whole wave (scalar registers)
+    const int scale_row = li * srow_ints + g0;
+    int group_of[XS];
     {
         int g = 0, sub = 0;
 #pragma unroll
         for (int i = 0; i < XS; ++i) {
-            scale_idx[i] = li * srow_ints + g0 + g;
+            group_of[i] = g;
             if (++sub == p.spg) {
                 sub = 0;
                 ++g;
@@ -243,9 +256,24 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     }
 
     auto stage_scales = [&](int slot, int buf) {
+        int f = threadIdx.x;
+        asm volatile("" : "+v"(f));  // worked out here every time rather than held in registers throughout
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-            if (stage_dst[j] >= 0) lds_scale[buf * scale_ints + stage_dst[j]] = scv[slot][j];
+        for (int j = 0; j < SJ; ++j, f += T) {
+            // r = f / NG for f < 2048, NG <= 128: (f + 0.5) / NG is at least 0.5 / NG away from an integer, far more
+            // than the rounding error of the float arithmetic
+            const int r = (int)fmaf((float)f, inv_ng, half_inv_ng);
+            if (f < 16 * NG) lds_scale[buf * scale_ints + f + r] = scv[slot][j];
+        }
+        if constexpr (INT_SCALE && kTileFlag) {
+            // v_mad_i32_i24 is exact while the scale fits 24 signed bits (|P| <= 2^17 always does); a tile with a
+            // wider scale takes full 32-bit multiplies.  Words past the block were fetched as 0.
+            bool wide = false;
+#pragma unroll
+            for (int j = 0; j < SJ; ++j) wide |= ((uint32_t)(scv[slot][j] + (1 << 23)) >> 24) != 0;
+            const bool any_wide = __any(wide);
+            if (lane == 0) lds_wide[buf * W + wave] = any_wide ? 1 : 0;
+        }
     };
 
     // The pass over this workgroup's tiles.
@@ -267,7 +295,11 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
                         if (k + u + 1 + SD < my_tiles) issue_scales((u + 1) % SD, cur + (1 + SD) * G);
                     }
 
-                    const int* my_scales = lds_scale + ((k + u) & 1) * scale_ints;
+                    int my_row = ((k + u) & 1) * scale_ints + scale_row;
+                    // opaque to the optimiser: it would otherwise keep the address of every (buffer, step) pair in a
+                    // register of its own for the whole kernel, and spill
+                    asm volatile("" : "+v"(my_row));
+                    const int* my_scales = lds_scale + my_row;
                     const bool refill = k + u + DT < my_tiles;
                     acc_t acc[MT][4];
 #pragma unroll
@@ -275,6 +307,12 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
 #pragma unroll
                         for (int j = 0; j < 4; ++j) acc[t][j] = 0;
 
+                    // Integer scale step: v_mad_i32_i24 is exact while the scale fits 24 signed bits (|P| <= 2^17
+                    // always does); a tile (or step) with a wider scale takes 32-bit multiplies.  Both are exact
+                    // modulo 2^32.
+                    bool wide_tile = false;
+                    if constexpr (INT_SCALE && kTileFlag)
+                        wide_tile = __any(lds_wide[((k + u) & 1) * W + (lane & (W - 1))] != 0);
 #pragma unroll
                     for (int i = 0; i < XS; ++i) {
                         v4i w_even, w_odd;
@@ -290,28 +328,43 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
                         if constexpr (kStepRefill) {
                             if (refill) issue_weight_step(dt, i, cur + DT * G);
                         }
-                        const int s_i = i < ns ? my_scales[scale_idx[i]] : 0;
-                        // Integer scale step: v_mad_i32_i24 is exact while the scale fits 24 bits (|P| <= 2^17 always
-                        // does); a wave that meets a wider scale takes the full 32-bit multiply for this step.  Both
-                        // are exact modulo 2^32.
-                        const bool wide = INT_SCALE && __any(((uint32_t)(s_i + (1 << 23)) >> 24) != 0);
+                        const int s_i = i < ns ? my_scales[group_of[i]] : 0;
                         const float s_f = __int_as_float(s_i) * 0.0625f;  // 16*P * (s/16) = float(P) * s exactly
+                        bool wide = wide_tile;
+                        if constexpr (INT_SCALE && !kTileFlag) wide = __any(((uint32_t)(s_i + (1 << 23)) >> 24) != 0);
+                        v4i part[MT];
 #pragma unroll
                         for (int t = 0; t < MT; ++t) {
-                            v4i part = __builtin_amdgcn_mfma_i32_16x16x64_i8(x_even[i][t], w_even, v4i{0, 0, 0, 0}, 0, 0, 0);
-                            part = __builtin_amdgcn_mfma_i32_16x16x64_i8(x_odd[i][t], w_odd, part, 0, 0, 0);
-                            if constexpr (!INT_SCALE) {
-#pragma unroll
-                                for (int j = 0; j < 4; ++j) acc[t][j] = fmaf((float)part[j], s_f, acc[t][j]);  // C' += float(C_g) * s_g
-                            } else if (__builtin_expect(wide, 0)) {
-#pragma unroll
-                                for (int j = 0; j < 4; ++j) acc[t][j] += (part[j] >> 4) * s_i;
-                            } else {
-#pragma unroll
-                                for (int j = 0; j < 4; ++j) acc[t][j] += __mul24(part[j] >> 4, s_i);             // C'' += C_g * s_g^INT
-                            }
+                            part[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(x_even[i][t], w_even, v4i{0, 0, 0, 0}, 0, 0, 0);
+                            part[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(x_odd[i][t], w_odd, part[t], 0, 0, 0);
                         }
-                        // with many token tiles the scheduler otherwise unpacks several steps ahead and spills
+                        if constexpr (!INT_SCALE) {
+#pragma unroll
+                            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) acc[t][j] = fmaf((float)part[t][j], s_f, acc[t][j]);  // C' += float(C_g) * s_g
+                        } else if (__builtin_expect(wide, 0)) {
+#pragma unroll
+                            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) {
+                                    int prod = (part[t][j] >> 4) * s_i;
+                                    asm volatile("" : "+v"(prod));  // else a 64-bit multiply-add with register pairs
+                                    acc[t][j] += prod;
+                                }
+                        } else {
+#pragma unroll
+                            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) acc[t][j] += __mul24(part[t][j] >> 4, s_i);          // C'' += C_g * s_g^INT
+                        }
+                        // The step's scale arithmetic is done here, not later: left alone, the compiler moves it below
+                        // the following steps (keeping every step's partial products in registers) and, with many
+                        // token tiles, unpacks several steps ahead; both spill.
+#pragma unroll
+                        for (int t = 0; t < MT; ++t)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(acc[t][j]));
                         if constexpr (MT * XS >= 8) __builtin_amdgcn_sched_barrier(0);
                     }
                     const float c_out = a.chan_scale ? cs[dt] : 1.0f;
@@ -338,9 +391,14 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
 #pragma unroll
                     for (int o = 0; o < OPT; ++o) {
                         if (writer[o] && n < a.N) {
+                            // where that output sits in a wave's partials: tile t, lane (4 rows per lane-group),
+                            // register j (worked out here, per tile, to keep it out of the long-lived registers)
+                            int mo = m_out[o];
+                            asm volatile("" : "+v"(mo));
+                            const int src_slot = ((mo >> 4) * kWave + ((mo & 15) >> 2) * 16 + n_out) * 4 + (mo & 3);
                             acc_t tot = 0;
                             for (int w = 0; w < W; ++w) {
-                                const int v = buf[w * MT * kWave * 4 + src_slot[o]];
+                                const int v = buf[w * MT * kWave * 4 + src_slot];
                                 if constexpr (INT_SCALE) tot += v;
                                 else tot += __int_as_float(v);
                             }
@@ -363,8 +421,10 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
 
 template <int MT, int XS, int DT, int WAVES, bool INT_SCALE>
 hipError_t launch_decode(const GemmArgs& a, const DecodePlan& p, int grid, hipStream_t stream) {
+    // partial accumulators, group scales, wide-scale words, activation staging (64 token rows)
     const size_t smem = 2 * (size_t)WAVES * MT * kWave * 16 + 2 * 16 * (size_t)(p.num_groups + 1) * 4 +
-                        (WAVES == 8 ? (size_t)WAVES * XS * 2048 : 0);  // + the activation staging of the 8-wave form
+                        2 * (size_t)WAVES * 4 +
+                        (WAVES == 8 && MT == 4 ? (size_t)WAVES * XS * 2048 : 0);
     auto kern = gemm_decode_kernel<MT, XS, DT, WAVES, INT_SCALE>;
     if (smem > 64 * 1024) {
         static bool raised = false;  // per instantiation
@@ -387,8 +447,8 @@ hipError_t dispatch(const GemmArgs& a, const DecodePlan& p, int mt, int xs, int 
         return launch_decode<1, 6, 1, 16, INT_SCALE>(a, p, grid, stream);
     }
     if (mt == 2) {
-        if (xs <= 2) return launch_decode<2, 2, 4, 16, INT_SCALE>(a, p, grid, stream);
-        return launch_decode<2, 4, 1, 16, INT_SCALE>(a, p, grid, stream);
+        if (p.waves == 16) return launch_decode<2, 2, 4, 16, INT_SCALE>(a, p, grid, stream);
+        return launch_decode<2, 8, 1, 8, INT_SCALE>(a, p, grid, stream);
     }
     return launch_decode<4, 4, 1, 8, INT_SCALE>(a, p, grid, stream);
 }
@@ -401,12 +461,15 @@ bool try_launch_gemm_decode(const GemmArgs& a, bool int_scale, hipStream_t strea
     const int NG = a.K / a.group;
     const int spg = a.group / kStepK;
     const int mt = a.M <= 16 ? 1 : a.M <= 32 ? 2 : 4;
-    // 64 token rows: 8 waves per workgroup, so that a wave's resident activations (128 registers) fit
-    const int waves = mt == 4 ? 8 : 16;
+    // A wave's resident activations take 8 registers per token tile and step of its K slice: with 16 waves (128
+    // registers each) up to 6 steps for one token tile and 2 for two, with 8 waves (256 registers) 8 steps for two
+    // token tiles and 4 for four.
+    const int xs16 = ((NG + 15) / 16) * spg;
+    const int waves = (mt == 1 || (mt == 2 && xs16 <= 2)) ? 16 : 8;
     if (waves > NG) return false;
     const int xs = ((NG + waves - 1) / waves) * spg;
-    if (mt == 4 ? xs > 4 : (mt * xs > 8 || xs > 6)) return false;  // resident activations beyond the register budget
-    if (16 * NG > 2 * waves * kWave) return false;                  // two words per thread stage a tile's group scales
+    if (xs > (mt == 1 ? 6 : mt == 2 ? (waves == 16 ? 2 : 8) : 4)) return false;
+    if (16 * NG > 2 * waves * kWave) return false;  // at most two words per thread stage a tile's group scales
     DecodePlan p;
     p.tiles = (a.N + 15) / 16;
     p.waves = waves;

@@ -92,7 +92,8 @@ __global__ __launch_bounds__(256) void prepare_scales_kernel(const int32_t* __re
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     bool wide = false;
 #pragma unroll
-    for (int r = ty; r < 64; r += 4) {  // unrolled: the 16 loads of a thread are in flight together
+    for (int q = 0; q < 16; ++q) {  // unrolled: the 16 loads of a thread are in flight together
+        const int r = ty + 4 * q;
         const int n = n0 + r, g = g0 + tx;
         int32_t v = 0;
         if (n < N && g < NG) v = scale[(e * N + n) * NG + g];
@@ -101,7 +102,8 @@ __global__ __launch_bounds__(256) void prepare_scales_kernel(const int32_t* __re
     }
     __syncthreads();
 #pragma unroll
-    for (int r = ty; r < 64; r += 4) {
+    for (int q = 0; q < 16; ++q) {
+        const int r = ty + 4 * q;
         const int g = g0 + r, n = n0 + tx;
         if (g < NG && n < N) st[(e * NG + g) * N + n] = tile[tx][r];
     }
