@@ -110,13 +110,30 @@ __global__ __launch_bounds__(256) void prepare_scales_kernel(const int32_t* __re
     if (CHECK && __any(wide) && (threadIdx.x & (kWave - 1)) == 0) atomicOr(wide_flag, 1);
 }
 
+// Row-tile slots of the grouped form (see prepare_activations_kernel).
+__host__ __device__ inline int tile_slots(int M, int num_experts) { return (M + kBM - 1) / kBM + num_experts; }
+
 // Preparation, one wave per token row: xp = the activations with every 16-byte chunk reordered to
 // [even | even | odd | odd] (see the top of the file), and s8[step][m] = -8 * sum over the 128 k of the step of
 // xq[m,k], the zero-point correction of the q + 8 weight bytes (8 lanes share a step).
 __global__ __launch_bounds__(256) void prepare_activations_kernel(const int8_t* __restrict__ xq, int M, int K,
                                                                   int8_t* __restrict__ xp, int32_t* __restrict__ s8,
-                                                                  int32_t* __restrict__ wide_flag) {
+                                                                  int32_t* __restrict__ wide_flag,
+                                                                  const int32_t* __restrict__ row_offsets,
+                                                                  int num_experts, int2* __restrict__ tile_table) {
     if (blockIdx.x == 0 && threadIdx.x == 0) *wide_flag = 0;  // prepare_scales_kernel, next in the stream, may set it
+    // Grouped form: the list of (expert, row tile) pairs that exist, one per slot, the rest marked empty.  The sum
+    // over experts of ceil(rows / 128) is at most ceil(M / 128) + num_experts, the number of slots the tile kernel is
+    // launched with; without the list it would need ceil(M / 128) row tiles per expert, nearly all of them empty.
+    if (row_offsets != nullptr && blockIdx.x == gridDim.x - 1 && threadIdx.x == 255) {
+        const int slots = tile_slots(M, num_experts);
+        int slot = 0;
+        for (int e = 0; e < num_experts; ++e) {
+            const int rows = row_offsets[e + 1] - row_offsets[e];
+            for (int t = 0; t * kBM < rows && slot < slots; ++t) tile_table[slot++] = make_int2(e, t);
+        }
+        for (; slot < slots; ++slot) tile_table[slot] = make_int2(-1, 0);
+    }
     const int m = blockIdx.x * 4 + threadIdx.x / kWave;
     if (m >= M) return;
     const int lane = threadIdx.x & (kWave - 1);
@@ -151,7 +168,7 @@ __global__ __launch_bounds__(256) void prepare_activations_kernel(const int8_t* 
 template <bool INT_SCALE, bool WIDE>
 __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_t* __restrict__ xp,
                                                   const int32_t* __restrict__ s8, const int32_t* __restrict__ scale_t,
-                                                  unsigned char* smem) {
+                                                  const int2* __restrict__ tile_table, unsigned char* smem) {
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -160,9 +177,16 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
     // ---- which tile.  Linear tile numbers are dealt out so that XCD x (workgroups x, x+8, ...) gets one contiguous
     // range of them, and a range walks the output in blocks of kGroupM tile rows, column by column.
     const int tiles_n = (a.N + kBN - 1) / kBN;
-    const int tiles_m = (a.M + kBM - 1) / kBM;
+    const int tiles_m = a.row_offsets ? tile_slots(a.M, a.num_experts) : (a.M + kBM - 1) / kBM;  // grouped: slots
     int tile_m, tile_n;
-    {
+    if (a.row_offsets) {
+        // Grouped form: the slots that exist come first and how many there are is known on the device only, so the
+        // tiles are simply taken in order, slot by slot: workgroup i runs on XCD i % 8, every XCD gets every eighth
+        // tile (equal shares of the real work, to within one tile), and the two row tiles of an expert with more than
+        // 128 rows meet on the same XCD for the same tile column whenever the number of tile columns divides by 8.
+        tile_m = blockIdx.x / tiles_n;
+        tile_n = blockIdx.x - tile_m * tiles_n;
+    } else {
         const int total = tiles_m * tiles_n;
         const int q = total / kXcds, rem = total - q * kXcds;
         const int xcd = blockIdx.x % kXcds, idx = blockIdx.x / kXcds;
@@ -177,7 +201,10 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
     int m_begin = 0, m_end = a.M;
     size_t expert = 0;
     if (a.row_offsets) {
-        expert = blockIdx.z;
+        const int2 entry = tile_table[tile_m];  // which expert and which of its row tiles this slot stands for
+        if (entry.x < 0) return;                // an empty slot (uniform over the workgroup, before any barrier)
+        expert = entry.x;
+        tile_m = entry.y;
         m_begin = a.row_offsets[expert];
         m_end = a.row_offsets[expert + 1];
     }
@@ -371,11 +398,21 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
     if (steps < kStages) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
     else if (wave < 2) asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(3 * (kTileLoads + 1)) : "memory");
     else asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(3 * kTileLoads) : "memory");
-    read_fragments(ops0, smem);
-    read_corrections(ops0, smem);
-    for (int s = 0; s < steps; s += 2) {
-        compute_step(ops0, ops1, s);
-        if (s + 1 < steps) compute_step(ops1, ops0, s + 1);  // uniform over the workgroup (it holds a barrier)
+    if (wm * 64 >= m_rows) {
+        // None of this wave's 64 token rows exists (the tile at the ragged end of the rows, typically the second tile
+        // of a mixture-of-experts expert): it keeps up its share of the requests and the barriers, and leaves the
+        // SIMD's issue slots to the wave that has rows.
+        for (int s = 0; s < steps; ++s) {
+            wait_tile_and_sync(s + kStages - 1 < steps);
+            request_step(s + kStages);
+        }
+    } else {
+        read_fragments(ops0, smem);
+        read_corrections(ops0, smem);
+        for (int s = 0; s < steps; s += 2) {
+            compute_step(ops0, ops1, s);
+            if (s + 1 < steps) compute_step(ops1, ops0, s + 1);  // uniform over the workgroup (it holds a barrier)
+        }
     }
 
     // ---- epilogue, once per output: FLOAT(acc) * s_a[m] * c[n] / alpha (Eq. (2)), or facc * s_a[m] (Eq. (1))
@@ -444,22 +481,23 @@ template <bool INT_SCALE>
 __global__ __launch_bounds__(kThreads) void gemm_prefill_kernel(GemmArgs a, const int8_t* __restrict__ xp,
                                                                 const int32_t* __restrict__ s8,
                                                                 const int32_t* __restrict__ scale_t,
-                                                                const int32_t* __restrict__ wide_flag) {
+                                                                const int32_t* __restrict__ wide_flag,
+                                                                const int2* __restrict__ tile_table) {
     extern __shared__ __align__(16) unsigned char smem[];  // [kStages][activations 16 KB | weights 16 KB | aux 2 KB]
     if constexpr (INT_SCALE) {
-        if (*wide_flag != 0) gemm_prefill_tile<true, true>(a, xp, s8, scale_t, smem);
-        else gemm_prefill_tile<true, false>(a, xp, s8, scale_t, smem);
+        if (*wide_flag != 0) gemm_prefill_tile<true, true>(a, xp, s8, scale_t, tile_table, smem);
+        else gemm_prefill_tile<true, false>(a, xp, s8, scale_t, tile_table, smem);
     } else {
-        gemm_prefill_tile<false, false>(a, xp, s8, scale_t, smem);
+        gemm_prefill_tile<false, false>(a, xp, s8, scale_t, tile_table, smem);
     }
 }
 
 template <bool INT_SCALE>
 hipError_t launch_tile(const GemmArgs& a, const int8_t* xp, const int32_t* s8, const int32_t* scale_t,
-                       const int32_t* flag, hipStream_t stream) {
+                       const int32_t* flag, const int2* tile_table, hipStream_t stream) {
     const size_t smem = (size_t)kStages * kStageBytes;
-    const int experts = a.row_offsets ? a.num_experts : 1;
-    const int tiles = ((a.N + kBN - 1) / kBN) * ((a.M + kBM - 1) / kBM);
+    const int tiles_m = a.row_offsets ? tile_slots(a.M, a.num_experts) : (a.M + kBM - 1) / kBM;
+    const int tiles = ((a.N + kBN - 1) / kBN) * tiles_m;
     static bool raised = false;
     if (!raised) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_prefill_kernel<INT_SCALE>),
@@ -467,43 +505,46 @@ hipError_t launch_tile(const GemmArgs& a, const int8_t* xp, const int32_t* s8, c
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((gemm_prefill_kernel<INT_SCALE>), dim3(tiles, 1, experts), dim3(kThreads), smem, stream, a, xp,
-                       s8, scale_t, flag);
+    hipLaunchKernelGGL((gemm_prefill_kernel<INT_SCALE>), dim3(tiles), dim3(kThreads), smem, stream, a, xp, s8, scale_t,
+                       flag, tile_table);
     return hipGetLastError();
 }
 
-constexpr size_t kHeaderBytes = 256;  // the workspace starts with the wide-scale flag
 size_t pad256(size_t bytes) { return (bytes + 255) & ~(size_t)255; }
+// the workspace starts with the wide-scale flag (16 bytes), then the table of row-tile slots
+size_t header_bytes(int experts, int M) { return pad256(16 + (size_t)tile_slots(M, experts) * sizeof(int2)); }
 size_t corrections_bytes(int M, int K) { return pad256((size_t)(K / kStepK) * (size_t)M * 4); }
 size_t scales_bytes(int experts, int N, int K, int group) { return pad256((size_t)experts * N * (K / group) * 4); }
 
 }  // namespace
 
-// workspace = [flag, padded to 256 B | s8: K/128 x M words | transposed scales: experts x K/group x N words |
-//              reordered activations: M x K bytes]
+// workspace = [flag and row-tile slots, padded to 256 B | s8: K/128 x M words | transposed scales: experts x K/group x
+//              N words | reordered activations: M x K bytes]
 size_t gemm_prefill_workspace_bytes(int num_experts, int M, int N, int K, int group) {
-    return kHeaderBytes + corrections_bytes(M, K) + scales_bytes(num_experts, N, K, group) + (size_t)M * K;
+    return header_bytes(num_experts, M) + corrections_bytes(M, K) + scales_bytes(num_experts, N, K, group) + (size_t)M * K;
 }
 
 hipError_t launch_gemm_prefill(const GemmArgs& a, bool int_scale, void* workspace, hipStream_t stream) {
     const int experts = a.row_offsets ? a.num_experts : 1;
     const int NG = a.K / a.group;
     unsigned char* ws = static_cast<unsigned char*>(workspace);
+    const size_t header = header_bytes(experts, a.M);
     int32_t* flag = reinterpret_cast<int32_t*>(ws);
-    int32_t* s8 = reinterpret_cast<int32_t*>(ws + kHeaderBytes);
-    int32_t* scale_t = reinterpret_cast<int32_t*>(ws + kHeaderBytes + corrections_bytes(a.M, a.K));
-    int8_t* xp = reinterpret_cast<int8_t*>(ws + kHeaderBytes + corrections_bytes(a.M, a.K) +
+    int2* tile_table = reinterpret_cast<int2*>(ws + 16);
+    int32_t* s8 = reinterpret_cast<int32_t*>(ws + header);
+    int32_t* scale_t = reinterpret_cast<int32_t*>(ws + header + corrections_bytes(a.M, a.K));
+    int8_t* xp = reinterpret_cast<int8_t*>(ws + header + corrections_bytes(a.M, a.K) +
                                            scales_bytes(experts, a.N, a.K, a.group));
     hipLaunchKernelGGL(prepare_activations_kernel, dim3((a.M + 3) / 4), dim3(256), 0, stream, a.xq, a.M, a.K, xp, s8,
-                       flag);
+                       flag, a.row_offsets, experts, tile_table);
     const dim3 sgrid((a.N + 63) / 64, (NG + 63) / 64, experts);
     const int32_t* scale = static_cast<const int32_t*>(a.scale);
     if (int_scale) hipLaunchKernelGGL(prepare_scales_kernel<true>, sgrid, dim3(256), 0, stream, scale, a.N, NG, scale_t, flag);
     else hipLaunchKernelGGL(prepare_scales_kernel<false>, sgrid, dim3(256), 0, stream, scale, a.N, NG, scale_t, flag);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return int_scale ? launch_tile<true>(a, xp, s8, scale_t, flag, stream)
-                     : launch_tile<false>(a, xp, s8, scale_t, flag, stream);
+    return int_scale ? launch_tile<true>(a, xp, s8, scale_t, flag, tile_table, stream)
+                     : launch_tile<false>(a, xp, s8, scale_t, flag, tile_table, stream);
 }
 
 }  // namespace intscale
