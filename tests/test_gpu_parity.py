@@ -212,9 +212,13 @@ def test_gemm_repeatable(P):
 
 
 # ------------------------------------------------------------------------------------------------ grouped (mixture of experts)
-@pytest.mark.parametrize("counts", [[5, 0, 17, 64, 1, 0, 33, 8], [0, 0, 3], [130, 2]])
-def test_grouped_gemm(P, counts):
-    E, N, K = len(counts), 48, 1024
+# (the first two go to the general kernel; from 65 rows per expert on average the tiled kernel takes over, with its table
+# of existing row tiles: experts without rows, with several tiles, with exactly one full tile, ragged tile columns)
+@pytest.mark.parametrize("counts,N", [([5, 0, 17, 64, 1, 0, 33, 8], 48), ([0, 0, 3], 48), ([130, 2], 48),
+                                      ([0, 300, 0, 129, 70], 520), ([128, 128, 128], 256), ([0, 0, 0, 270], 48),
+                                      ([257, 1, 1], 264)])
+def test_grouped_gemm(P, counts, N):
+    E, K = len(counts), 1024
     rng = np.random.default_rng(sum(counts))
     M = sum(counts)
     off = np.zeros(E + 1, np.int32)
