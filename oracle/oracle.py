@@ -258,3 +258,36 @@ def overflow_safe_scale_bound(K: int, group: int) -> int:
     """Largest integer scale for which no input can overflow the 32-bit accumulator:
     |acc| <= (K/G) * G * 128 * 8 * IS_max < 2^31  (|xq| <= 128, |q| <= 8)."""
     return (2 ** 31 - 1) // (K * 128 * 8)
+
+
+def layer_overflow_bound(scale_i32: np.ndarray, group: int) -> int:
+    """Largest |accumulator| the integer-scale GEMM of Eq. (2) can reach with these integer scales, over all int8
+    activation codes and int4 weight codes: max_n sum_g |IS[n,g]| * G * 128 * 8 (a group's partial sum is at most
+    G * 128 * 8 in magnitude, reached by xq = -128, q = -8).  The 32-bit accumulator cannot overflow iff this is
+    below 2^31 (the overflow risk the paper's Sec. 5.6 and Limitations discuss).  Python integer."""
+    IS = np.abs(np.asarray(scale_i32).astype(np.int64))
+    return int(IS.sum(axis=1).max()) * group * 128 * 8 if IS.size else 0
+
+
+class SafeResult(NamedTuple):
+    out: np.ndarray          # float64 [M,N], before the final rounding to fp16
+    out_fp16: np.ndarray     # float16 [M,N]
+    abs_sum: np.ndarray      # float64 [M,N], s_a * c / alpha * sum_g |P_g * IS_g|
+
+
+def gemm_w4a8_intscale_safe(xq, a_scale, qweight, scale_i32, chan_scale, group: int, alpha_log2: int) -> SafeResult:
+    """The overflow-safe ("degraded") form the paper's Limitations section names: the integer scales are kept but
+    the amplifier is taken out group by group, so nothing accumulates in 32 bits:
+        out[m,n] = s_a[m] * sum_g P[m,n,g] * (IS[n,g] * c[n] / alpha)
+    Here the sum is exact (64-bit integers; it cannot wrap for any int32 scales and K < 2^20) and rounded once."""
+    r = gemm_w4a8_intscale(xq, a_scale, qweight, scale_i32, chan_scale, group, alpha_log2)
+    M, N = r.acc64.shape
+    sa = _c(a_scale, np.float32).astype(np.float64)[:, None]
+    c = np.ones((1, N)) if chan_scale is None else _c(chan_scale, np.float32).astype(np.float64)[None, :]
+    factor = sa * c / float(2 ** alpha_log2)
+    out = r.acc64.astype(np.float64) * factor
+    p = group_partials(xq, qweight, group).astype(np.int64)
+    mag = np.abs(p * np.asarray(scale_i32).astype(np.int64)[None, :, :]).sum(axis=2).astype(np.float64) * factor
+    with np.errstate(over="ignore"):
+        out16 = out.astype(np.float16)
+    return SafeResult(out, out16, mag)

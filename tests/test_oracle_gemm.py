@@ -229,3 +229,58 @@ def test_shape_mismatch_raises():
     xq = np.zeros((2, 8), np.int8)
     with pytest.raises(ValueError):
         O.gemm_w4a8_intscale(xq, np.ones(2, np.float32), np.zeros((3, 4), np.uint8), np.zeros((3, 1), np.int32), None, 4, 10)
+
+
+# ------------------------------------------------------------------------------------------------ overflow-safe form
+def test_layer_overflow_bound_is_reached_by_the_extreme_codes():
+    """The bound is attained: all activation codes -128, all weight codes -8, non-negative scales."""
+    rng = np.random.default_rng(11)
+    N, K, G = 5, 256, 128
+    IS = rng.integers(0, 5000, size=(N, K // G)).astype(np.int32)
+    assert O.layer_overflow_bound(np.array([[3, -4]], np.int32), 128) == 7 * 128 * 128 * 8  # by hand
+    bound = O.layer_overflow_bound(IS, G)
+    assert bound == max(int(IS[n].astype(np.int64).sum()) for n in range(N)) * G * 1024
+    xq = np.full((1, K), -128, np.int8)
+    q = np.full((N, K), -8, np.int8)
+    r = O.gemm_w4a8_intscale(xq, np.ones(1, np.float32), O.pack_int4(q), IS, None, G, 0)
+    assert int(r.acc64.max()) == bound
+    # scales within overflow_safe_scale_bound can never overflow
+    cap = O.overflow_safe_scale_bound(K, G)
+    assert O.layer_overflow_bound(np.full((3, K // G), cap, np.int32), G) < 2 ** 31
+    assert O.layer_overflow_bound(np.full((3, K // G), cap + 1, np.int32), G) >= 2 ** 31
+
+
+def test_safe_form_python_integers_and_overflow():
+    """Brute force with python integers; where the 32-bit accumulator wraps, the safe form keeps the true value and
+    differs from the wrapped one by a multiple of 2^32 (times the output factor)."""
+    rng = np.random.default_rng(12)
+    M, N, K, G, a = 3, 4, 32, 8, 10
+    xq, q, _, _, sa, c = _rand_problem(rng, M, N, K, G)
+    IS = rng.integers(-2 ** 27, 2 ** 27, size=(N, K // G)).astype(np.int32)  # large enough to wrap
+    r = O.gemm_w4a8_intscale(xq, sa, O.pack_int4(q), IS, c, G, a)
+    sres = O.gemm_w4a8_intscale_safe(xq, sa, O.pack_int4(q), IS, c, G, a)
+    wrapped = 0
+    for m in range(M):
+        for n in range(N):
+            acc, mag = 0, 0
+            for g in range(K // G):
+                p = sum(int(xq[m, k]) * int(q[n, k]) for k in range(g * G, (g + 1) * G))
+                acc += p * int(IS[n, g])
+                mag += abs(p * int(IS[n, g]))
+            factor = Fraction(float(sa[m])) * Fraction(float(c[n])) / (2 ** a)
+            assert sres.out[m, n] == pytest.approx(float(acc * factor), rel=1e-14, abs=0)
+            assert sres.abs_sum[m, n] == pytest.approx(float(mag * factor), rel=1e-14, abs=0)
+            assert (acc - int(r.acc[m, n])) % (2 ** 32) == 0
+            wrapped += acc != int(r.acc[m, n])
+    assert wrapped > 0, "the test is meant to include wrapped accumulators"
+
+
+def test_safe_form_equals_eq2_without_overflow():
+    rng = np.random.default_rng(13)
+    M, N, K, G, a = 5, 24, 512, 128, 10
+    xq, q, IS, _, sa, c = _rand_problem(rng, M, N, K, G)
+    r = O.gemm_w4a8_intscale(xq, sa, O.pack_int4(q), IS, c, G, a)
+    sres = O.gemm_w4a8_intscale_safe(xq, sa, O.pack_int4(q), IS, c, G, a)
+    assert np.array_equal(r.acc.astype(np.int64), r.acc64)
+    assert np.allclose(sres.out, r.out, rtol=1e-15, atol=0) and np.array_equal(sres.out_fp16, r.out_fp16)
+    assert np.all(sres.abs_sum >= np.abs(sres.out) * (1 - 1e-12))
