@@ -191,7 +191,9 @@ def main():
         return f"gemm_skinny_kernel<{mt}, ...>"
 
     # ---------------------------------------------------------------- segments of one step
-    def make_segments(int_scale: bool, with_quant: bool):
+    safe_ws = {}
+
+    def make_segments(int_scale: bool, with_quant: bool, safe: bool = False):
         segs = []
         for M in BATCHES:
             for name, (K, N) in linears:
@@ -202,7 +204,17 @@ def main():
                             P.is_quantize_act_int8_token(a["x"], a["xq"], a["sa"])
                     segs.append(Segment(f"quant_{name}_M{M}", "quantize_act_kernel", L, L * (3 * M * K + 4 * M), 0, fq,
                                         use_graph, torch))
-                if int_scale:
+                if safe:
+                    key = (M, name)
+                    if key not in safe_ws:
+                        safe_ws[key] = torch.empty(P.is_gemm_safe_workspace_bytes(M, N, K, GROUP), dtype=torch.uint8,
+                                                   device=dev)
+
+                    def fg(a=a, w=w, ws=safe_ws[key]):
+                        for l in range(L):
+                            P.is_gemm_w4a8_intscale_safe(a["xq"], a["sa"], w["q"][l], w["si"][l], w["c"][l], GROUP,
+                                                         ALPHA_LOG2, out=a["out"], workspace=ws)
+                elif int_scale:
                     def fg(a=a, w=w):
                         for l in range(L):
                             P.is_gemm_w4a8_intscale(a["xq"], a["sa"], w["q"][l], w["si"][l], w["c"][l], GROUP,
@@ -274,6 +286,7 @@ def main():
     # ---------------------------------------------------------------- float-scale comparison (GEMM launches only)
     speedup = None
     fs_detail = None
+    overflow = None
     if not args.no_floatscale:
         is_g = make_segments(int_scale=True, with_quant=False)
         fs_g = make_segments(int_scale=False, with_quant=False)
@@ -282,7 +295,16 @@ def main():
         t_fs = timed_pass(fs_g, n, 2)
         speedup = t_fs / t_is
         fs_detail = {a.name: round(b.elapsed_ms / max(a.elapsed_ms, 1e-9), 4) for a, b in zip(is_g, fs_g)}
-        del is_g, fs_g
+        # the overflow-safe form (integer scales, amplifier taken out per group) and each layer's worst-case bound
+        safe_g = make_segments(int_scale=True, with_quant=False, safe=True)
+        timed_pass(safe_g, n, 2)
+        overflow = dict(
+            safe_over_intscale_by_shape={a.name: round(b.elapsed_ms / max(a.elapsed_ms, 1e-9), 4)
+                                         for a, b in zip(is_g, safe_g)},
+            worst_case_bound_log2={name: round(float(np.log2(max(1, int(
+                P.is_intscale_overflow_bound(weights[name]["si"][0], GROUP).cpu()[0])))), 2) for name, _ in linears},
+            note="bound = max_n sum_g |IS| * G * 1024; a layer cannot overflow int32 iff it is below 31")
+        del is_g, fs_g, safe_g
 
     # ---------------------------------------------------------------- CPU oracle on a bounded sample of the same step
     cpu = None
@@ -341,6 +363,7 @@ def main():
         "hbm_frac": round(value / HBM_PEAK_GBS, 4),
         "speedup_vs_floatscale": None if speedup is None else round(speedup, 4),
         "floatscale_over_intscale_by_shape": fs_detail,
+        "overflow": overflow,
         "roofline": roofline,
         "measured_peaks": peaks,
         "cpu_baseline": cpu,

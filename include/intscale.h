@@ -118,6 +118,31 @@ int is_gemm_w4a8_floatscale_grouped(const int8_t* xq, const float* a_scale, cons
 size_t is_gemm_grouped_workspace_bytes(int num_experts, int M_total, int N, int K, int group);
 
 /*
+ * Overflow risk of a layer (Sec. 5.6, the appendix on maximum activations, Limitations): the largest |accumulator|
+ * the integer-scale GEMM can reach with these integer scales over all int8 activation codes and int4 weight codes,
+ *   bound = max_n sum_g |scale_i32[n,g]| * group * 128 * 8
+ * (a group's partial sum is at most group * 128 * 8 in magnitude).  The int32 accumulator cannot overflow iff
+ * bound < 2^31.  A property of the weights alone: meant to be asked once, offline, per layer and amplifier.
+ *   scale_i32   in   int32 [N, K/group]        bound_dev   out  device unsigned 64-bit integer, 8-byte aligned
+ */
+int is_intscale_overflow_bound(const int32_t* scale_i32, int N, int K, int group, unsigned long long* bound_dev,
+                               void* stream);
+
+/*
+ * Overflow-safe form of the integer-scale GEMM, for layers whose bound is too large: the "degraded" kernel of the
+ * Limitations section, which keeps the integer scales but takes the amplifier out group by group, so that nothing is
+ * accumulated in 32 bits:
+ *   out[m,n] = fp16( a_scale[m] * sum_g float(P[m,n,g]) * (float(scale_i32[n,g]) * chan_scale[n] * 2^-alpha_log2) )
+ * accumulated in fp32 (the per-group conversions of Eq. (1) are back: this is the price).  Arguments as for
+ * is_gemm_w4a8_intscale, without acc_out; workspace of at least is_gemm_safe_workspace_bytes(M,N,K,group) bytes
+ * (never 0: it holds the derived scales).
+ */
+int is_gemm_w4a8_intscale_safe(const int8_t* xq, const float* a_scale, const void* qweight, const int32_t* scale_i32,
+                               const float* chan_scale, int M, int N, int K, int group, int alpha_log2,
+                               void* out_fp16, void* workspace, size_t workspace_bytes, void* stream);
+size_t is_gemm_safe_workspace_bytes(int M, int N, int K, int group);
+
+/*
  * Measurement aids (no part of the method): the two rates the GEMMs are priced against, as this chip delivers them.
  *   is_probe_stream_read  reads `bytes` bytes (a multiple of 16) at `src` (device) once, 16 bytes per lane
  *   is_probe_mfma_i8      every wave of a chip-filling launch issues `iters` rounds of 16 independent

@@ -16,11 +16,14 @@ from .binding import (  # noqa: F401
     IntScaleError,
     QuantizedWeights,
     is_gemm_grouped_workspace_bytes,
+    is_gemm_safe_workspace_bytes,
     is_gemm_w4a8_floatscale,
     is_gemm_w4a8_floatscale_grouped,
     is_gemm_w4a8_intscale,
     is_gemm_w4a8_intscale_grouped,
+    is_gemm_w4a8_intscale_safe,
     is_gemm_workspace_bytes,
+    is_intscale_overflow_bound,
     is_probe_mfma_i8,
     is_probe_stream_read,
     is_quantize_act_int8_token,

@@ -30,6 +30,9 @@ EXPORTED_SYMBOLS = (
     "is_gemm_w4a8_intscale_grouped",
     "is_gemm_w4a8_floatscale_grouped",
     "is_gemm_grouped_workspace_bytes",
+    "is_intscale_overflow_bound",
+    "is_gemm_w4a8_intscale_safe",
+    "is_gemm_safe_workspace_bytes",
     "is_probe_stream_read",
     "is_probe_mfma_i8",
     "is_status_string",
@@ -81,6 +84,12 @@ def load_library() -> ctypes.CDLL:
     lib.is_gemm_w4a8_floatscale_grouped.restype = ci
     lib.is_gemm_grouped_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.is_gemm_grouped_workspace_bytes.restype = sz
+    lib.is_intscale_overflow_bound.argtypes = [vp, ci, ci, ci, vp, vp]
+    lib.is_intscale_overflow_bound.restype = ci
+    lib.is_gemm_w4a8_intscale_safe.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, sz, vp]
+    lib.is_gemm_w4a8_intscale_safe.restype = ci
+    lib.is_gemm_safe_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.is_gemm_safe_workspace_bytes.restype = sz
     lib.is_probe_stream_read.argtypes = [vp, sz, vp, vp]
     lib.is_probe_stream_read.restype = ci
     lib.is_probe_mfma_i8.argtypes = [ci, vp, ctypes.POINTER(ctypes.c_double), vp]
@@ -233,6 +242,45 @@ def is_gemm_w4a8_floatscale(xq, a_scale, qweight, scale_f32, group: int, out=Non
                                                _p(out), _p(ws), ws_bytes, _stream_handle(stream))
     _check("is_gemm_w4a8_floatscale", st)
     return out
+
+
+def is_gemm_safe_workspace_bytes(M: int, N: int, K: int, group: int) -> int:
+    return int(load_library().is_gemm_safe_workspace_bytes(M, N, K, group))
+
+
+def is_gemm_w4a8_intscale_safe(xq, a_scale, qweight, scale_i32, chan_scale, group: int, alpha_log2: int, out=None,
+                               workspace=None, stream=None):
+    torch = _torch()
+    M, K = xq.shape
+    N = qweight.shape[0]
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    _require(qweight, torch.uint8, (N, K // 2), "qweight")
+    _require(scale_i32, torch.int32, (N, K // group), "scale_i32")
+    if chan_scale is not None:
+        _require(chan_scale, torch.float32, (N,), "chan_scale")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    _require(out, torch.float16, (M, N), "out")
+    ws, ws_bytes = _workspace(is_gemm_safe_workspace_bytes(M, N, K, group), xq.device, workspace)
+    st = load_library().is_gemm_w4a8_intscale_safe(_p(xq), _p(a_scale), _p(qweight), _p(scale_i32), _p(chan_scale), M,
+                                                  N, K, group, alpha_log2, _p(out), _p(ws), ws_bytes,
+                                                  _stream_handle(stream))
+    _check("is_gemm_w4a8_intscale_safe", st)
+    return out
+
+
+def is_intscale_overflow_bound(scale_i32, group: int, bound=None, stream=None):
+    """Returns a device tensor holding the layer's worst-case |accumulator| (int64 view of the unsigned 64-bit value)."""
+    torch = _torch()
+    N, NG = scale_i32.shape
+    _require(scale_i32, torch.int32, (N, NG), "scale_i32")
+    if bound is None:
+        bound = torch.empty((1,), dtype=torch.int64, device=scale_i32.device)
+    _require(bound, torch.int64, (1,), "bound")
+    st = load_library().is_intscale_overflow_bound(_p(scale_i32), N, NG * group, group, _p(bound), _stream_handle(stream))
+    _check("is_intscale_overflow_bound", st)
+    return bound
 
 
 def is_gemm_w4a8_intscale_grouped(xq, a_scale, qweight, scale_i32, chan_scale, row_offsets, group: int,

@@ -183,4 +183,41 @@ int is_gemm_w4a8_floatscale_grouped(const int8_t* xq, const float* a_scale, cons
                        out_fp16, nullptr, workspace, workspace_bytes, stream, false, true);
 }
 
+size_t is_gemm_safe_workspace_bytes(int M, int N, int K, int group) {
+    if (check_gemm_shape(M, N, K, group) != IS_OK) return 0;
+    // the derived float scales, then whatever the GEMM itself needs
+    return (((size_t)N * (K / group) * 4 + 255) & ~(size_t)255) + is_gemm_workspace_bytes(M, N, K, group);
+}
+
+int is_gemm_w4a8_intscale_safe(const int8_t* xq, const float* a_scale, const void* qweight, const int32_t* scale_i32,
+                               const float* chan_scale, int M, int N, int K, int group, int alpha_log2,
+                               void* out_fp16, void* workspace, size_t workspace_bytes, void* stream) {
+    const int shape = check_gemm_shape(M, N, K, group);
+    if (shape != IS_OK) return shape;
+    if (alpha_log2 < 0 || alpha_log2 > 30) return IS_ERR_INVALID_ARG;
+    if (!ok_ptr(scale_i32) || !ok_opt(chan_scale) || !ok_opt(workspace)) return IS_ERR_INVALID_ARG;
+    if (workspace == nullptr || workspace_bytes < is_gemm_safe_workspace_bytes(M, N, K, group)) return IS_ERR_WORKSPACE;
+    const size_t scales_bytes = ((size_t)N * (K / group) * 4 + 255) & ~(size_t)255;
+    float* derived = static_cast<float*>(workspace);
+    // the arguments of the GEMM itself are checked before anything is enqueued
+    if (!ok_ptr(qweight)) return IS_ERR_INVALID_ARG;
+    if (M > 0 && (!ok_ptr(xq) || a_scale == nullptr || (reinterpret_cast<uintptr_t>(a_scale) & 3u) || !ok_ptr(out_fp16)))
+        return IS_ERR_INVALID_ARG;
+    if (M == 0) return IS_OK;
+    const int st = hip_status(launch_derive_safe_scales(scale_i32, chan_scale, (size_t)N, K / group, alpha_log2, derived,
+                                                        static_cast<hipStream_t>(stream)));
+    if (st != IS_OK) return st;
+    return gemm_common(xq, a_scale, qweight, derived, nullptr, nullptr, 1, M, N, K, group, 0, out_fp16, nullptr,
+                       static_cast<unsigned char*>(workspace) + scales_bytes, workspace_bytes - scales_bytes, stream, false,
+                       false);
+}
+
+int is_intscale_overflow_bound(const int32_t* scale_i32, int N, int K, int group, unsigned long long* bound_dev,
+                               void* stream) {
+    if (N <= 0 || K <= 0 || group <= 0 || K % group != 0) return IS_ERR_INVALID_ARG;
+    if (!ok_ptr(scale_i32) || bound_dev == nullptr || (reinterpret_cast<uintptr_t>(bound_dev) & 7u))
+        return IS_ERR_INVALID_ARG;
+    return hip_status(launch_overflow_bound(scale_i32, N, K / group, group, bound_dev, static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

@@ -51,7 +51,14 @@ bool try_launch_gemm_decode(const GemmArgs& a, bool int_scale, hipStream_t strea
 size_t gemm_prefill_workspace_bytes(int num_experts, int M, int N, int K, int group);
 hipError_t launch_gemm_prefill(const GemmArgs& a, bool int_scale, void* workspace, hipStream_t stream);
 
-int cu_count();  // compute units of the current device
+int cu_count();
+
+// Overflow handling (overflow.hip): the layer's worst-case |accumulator| into *bound_dev, and the float scales
+// float(IS) * c * 2^-alpha_log2 of the overflow-safe form (`rows` = N, or E * N for stacked weight sets).
+hipError_t launch_overflow_bound(const int32_t* scale_i32, int N, int NG, int group, unsigned long long* bound_dev,
+                                 hipStream_t stream);
+hipError_t launch_derive_safe_scales(const int32_t* scale_i32, const float* chan_scale, size_t rows, int NG,
+                                     int alpha_log2, float* out, hipStream_t stream);  // compute units of the current device
 
 // Measurement aids: a streaming read of `bytes` bytes, and a loop of independent int8 MFMAs (*ops = operations done).
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, int* sink, hipStream_t stream);

@@ -72,6 +72,24 @@ def test_floatscale_and_grouped_argument_validation():
     assert lib.is_gemm_w4a8_floatscale_grouped(A, A, A, A, A + 2, 4, 8, 16, 256, 128, A, None, 0, None) == bad
 
 
+def test_overflow_entry_points_argument_validation():
+    lib = P.load_library()
+    bad = P.IS_ERR_INVALID_ARG
+    assert lib.is_intscale_overflow_bound(None, 16, 256, 128, A, None) == bad
+    assert lib.is_intscale_overflow_bound(A, 16, 256, 128, None, None) == bad
+    assert lib.is_intscale_overflow_bound(A, 16, 256, 128, A + 4, None) == bad      # 8-byte alignment of the result
+    assert lib.is_intscale_overflow_bound(A, 0, 256, 128, A, None) == bad
+    assert lib.is_intscale_overflow_bound(A, 16, 250, 128, A, None) == bad
+    need = lib.is_gemm_safe_workspace_bytes(8, 16, 256, 128)
+    assert need >= 16 * 2 * 4 and lib.is_gemm_safe_workspace_bytes(8, 16, 250, 128) == 0
+    safe = lambda **kw: lib.is_gemm_w4a8_intscale_safe(
+        kw.get("xq", A), kw.get("sa", A), kw.get("q", A), kw.get("si", A), kw.get("c", None), kw.get("M", 8), 16,
+        kw.get("K", 256), 128, kw.get("a", 10), kw.get("out", A), kw.get("ws", A), kw.get("wsb", need), None)
+    assert safe(si=None) == bad and safe(q=None) == bad and safe(xq=None) == bad and safe(out=None) == bad
+    assert safe(a=31) == bad and safe(K=250) == bad and safe(c=A + 4) == bad
+    assert safe(ws=None) == P.IS_ERR_WORKSPACE and safe(wsb=need - 1) == P.IS_ERR_WORKSPACE
+
+
 def test_quantizer_argument_validation():
     lib = P.load_library()
     bad = P.IS_ERR_INVALID_ARG

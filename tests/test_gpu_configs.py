@@ -135,6 +135,33 @@ def test_config2_amplifier_sweep(P, mode):
         assert len(dist) >= 2 and dist[-1] < dist[0], "no convergence towards the float-scale output"
 
 
+@pytest.mark.parametrize("mode", [O.SCALE_RAW, O.SCALE_NORM])
+def test_overflow_policy_with_searched_amplifier(P, mode):
+    """Per-layer amplifier by the search of Sec. 4.1, then the layer's worst-case bound decides between Eq. (2) as is and
+    its overflow-safe form; either way the output equals the exact (unwrapped) sum, and on these layers the measured
+    accumulators stay far below 2^31 although the worst case does not (the paper's observation in Sec. 5.6)."""
+    K, N = S.LLAMA2_70B["o_proj"]
+    w = S.make_weights(2, N, K, S.seed_for(2, 1, 1))
+    ref_w = O.quantize_weights_int4_group(w, G, -1, mode)
+    got_w = P.is_quantize_weights_int4_group(dev(w), G, -1, mode)
+    a = int(host(got_w.alpha_log2_dev)[0])
+    assert a == ref_w.alpha_log2 and np.array_equal(host(got_w.scale_i32), ref_w.scale_i32)
+    bound = int(host(P.is_intscale_overflow_bound(got_w.scale_i32, G))[0])
+    assert bound == O.layer_overflow_bound(ref_w.scale_i32, G)
+    x = S.make_activations(2, 32, K, S.seed_for(2, 1, 2) + 32)
+    xq_r, sa_r = O.quantize_act_int8_token(x)
+    xq, sa = P.is_quantize_act_int8_token(dev(x))
+    exact = O.gemm_w4a8_intscale_safe(xq_r, sa_r, ref_w.qweight, ref_w.scale_i32, ref_w.chan_scale, G, a)
+    plain = O.gemm_w4a8_intscale(xq_r, sa_r, ref_w.qweight, ref_w.scale_i32, ref_w.chan_scale, G, a)
+    assert plain.max_prefix.max() < 2 ** 31 and np.array_equal(plain.acc.astype(np.int64), plain.acc64)
+    if bound < 2 ** 31:
+        out, _ = P.is_gemm_w4a8_intscale(xq, sa, got_w.qweight, got_w.scale_i32, got_w.chan_scale, G, a)
+    else:
+        out = P.is_gemm_w4a8_intscale_safe(xq, sa, got_w.qweight, got_w.scale_i32, got_w.chan_scale, G, a)
+    err = np.abs(host(out).astype(np.float64) - exact.out)
+    assert np.all(err <= 1e-2 * np.abs(exact.out) + 2e-5 * exact.abs_sum + 2.0 ** -24)
+
+
 # ------------------------------------------------------------------------------------------------ configs[3]
 @pytest.mark.parametrize("index,name", list(enumerate(S.LLAMA3_8B)))
 def test_config3_llama3_8b_prefill(P, index, name):

@@ -211,6 +211,37 @@ def test_gemm_repeatable(P):
         assert torch.equal(acc0, acc1) and torch.equal(out0, out1) and torch.equal(fs0, fs1)
 
 
+# ------------------------------------------------------------------------------------------------ overflow handling
+@pytest.mark.parametrize("N,K,group", [(16, 128, 128), (300, 4096, 128), (4096, 11008, 128), (40, 1024, 512)])
+def test_overflow_bound(P, N, K, group):
+    rng = np.random.default_rng(N + K)
+    for IS in (rng.integers(0, 1025, size=(N, K // group)).astype(np.int32),
+               rng.integers(-2 ** 31, 2 ** 31, size=(N, K // group), dtype=np.int64).astype(np.int32),
+               np.zeros((N, K // group), np.int32)):
+        got = int(host(P.is_intscale_overflow_bound(dev(IS), group))[0])
+        assert got == O.layer_overflow_bound(IS, group)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 4096, 4096), (16, 272, 1024), (64, 48, 11008), (48, 2064, 3584), (129, 300, 1024),
+                                   (300, 700, 1152)])
+def test_gemm_intscale_safe(P, kernel, M, N, K):
+    """The overflow-safe form against the oracle's exact sum: with ordinary scales, and with scales that wrap the
+    32-bit accumulator of Eq. (2) (where the safe form must keep the true value)."""
+    rng = np.random.default_rng(3000 + M + N + K)
+    xq, qw, IS, s, sa, c = rand_quantised(rng, M, N, K)
+    big = rng.integers(-2 ** 20, 2 ** 20, size=IS.shape, dtype=np.int64).astype(np.int32)
+    for scales, chan, a in ((IS, c, 10), (big, None, 12), (big, c, 0)):
+        ref = O.gemm_w4a8_intscale_safe(xq, sa, qw, scales, chan, G, a)
+        out = host(P.is_gemm_w4a8_intscale_safe(dev(xq), dev(sa), dev(qw), dev(scales), None if chan is None else dev(chan),
+                                               G, a)).astype(np.float64)
+        fin = np.abs(ref.out) < 60000.0
+        err = np.abs(out[fin] - ref.out[fin])
+        assert np.all(err <= 1e-2 * np.abs(ref.out[fin]) + 2e-5 * ref.abs_sum[fin] + 2.0 ** -24), f"M{M} N{N} K{K} a{a}"
+        assert np.all(np.sign(out[~fin]) == np.sign(ref.out[~fin]))
+    wrapped = O.gemm_w4a8_intscale(xq, sa, qw, big, None, G, 12)
+    assert np.any(wrapped.acc.astype(np.int64) != wrapped.acc64), "the big scales are meant to wrap Eq. (2)'s accumulator"
+
+
 # ------------------------------------------------------------------------------------------------ grouped (mixture of experts)
 # (the first two go to the general kernel; from 65 rows per expert on average the tiled kernel takes over, with its table
 # of existing row tiles: experts without rows, with several tiles, with exactly one full tile, ragged tile columns)
