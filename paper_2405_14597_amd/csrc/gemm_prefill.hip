@@ -165,7 +165,11 @@ __global__ __launch_bounds__(256) void prepare_activations_kernel(const int8_t* 
 
 // One output tile.  WIDE selects the integer scale step: false = v_mad_i32_i24 (exact while every scale fits 24
 // bits), true = full 32-bit multiplies (exact modulo 2^32 for any scale).  `scale_t` are the transposed scales.
-template <bool INT_SCALE, bool WIDE>
+// COARSE is the coarse-grained GEMM (one group spanning all of K; Table 2, first column): the partial products stay in
+// the MFMA accumulators from the first K step to the last, nothing but unpacking is left for the vector ALU, and the
+// one scale per weight row is applied in the epilogue.  Its zero-point correction is the sum over all K steps, which a
+// third preparation kernel leaves in the slot of step 0; it enters as the initial value of the accumulators.
+template <bool INT_SCALE, bool WIDE, bool COARSE = false>
 __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_t* __restrict__ xp,
                                                   const int32_t* __restrict__ s8, const int32_t* __restrict__ scale_t,
                                                   const int2* __restrict__ tile_table, unsigned char* smem) {
@@ -286,12 +290,16 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
 
     using acc4 = typename std::conditional<INT_SCALE, v4i, v4f>::type;
     acc4 acc[MS][NS];
+    [[maybe_unused]] v4i chain[MS][NS];  // COARSE: the unscaled integer sums, carried from step to step by the MFMAs
 #pragma unroll
     for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
         for (int ns = 0; ns < NS; ++ns)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) acc[ms][ns][r] = 0;
+            for (int r = 0; r < 4; ++r) {
+                acc[ms][ns][r] = 0;
+                if constexpr (COARSE) chain[ms][ns][r] = 0;
+            }
 
     // Operand registers of one K step.  Two sets alternate: while step s is multiplied out of one, the other is
     // filled from the LDS stage of step s+1, so that no step starts by waiting for LDS.
@@ -346,6 +354,17 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
             }
         };
         auto multiply = [&](int ns) {
+            if constexpr (COARSE) {
+#pragma unroll
+                for (int ms = 0; ms < MS; ++ms)
+                    chain[ms][ns] =
+                        __builtin_amdgcn_mfma_i32_16x16x64_i8(cur.af[ms][0], bfu[ns & 1][0], chain[ms][ns], 0, 0, 0);
+#pragma unroll
+                for (int ms = 0; ms < MS; ++ms)
+                    chain[ms][ns] =
+                        __builtin_amdgcn_mfma_i32_16x16x64_i8(cur.af[ms][1], bfu[ns & 1][1], chain[ms][ns], 0, 0, 0);
+                return;
+            }
 #pragma unroll
             for (int ms = 0; ms < MS; ++ms)
                 part[ns & 1][ms] =
@@ -356,6 +375,7 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
                     __builtin_amdgcn_mfma_i32_16x16x64_i8(cur.af[ms][1], bfu[ns & 1][1], part[ns & 1][ms], 0, 0, 0);
         };
         auto scale = [&](int ns) {  // per-group scale step of Table 2
+            if constexpr (COARSE) return;  // one group: its scale waits for the epilogue
             const int sc_i = cur.scl[ns];
             const float s_f = __int_as_float(sc_i);
 #pragma unroll
@@ -386,10 +406,12 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
         }
         // keep the accumulators whole between steps: regrouped sums over two steps (two multiplies and a 3-input add)
         // cost more instructions than two multiply-adds
-        asm volatile(""
-                     : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[0][2]), "+v"(acc[0][3]), "+v"(acc[1][0]), "+v"(acc[1][1]),
-                       "+v"(acc[1][2]), "+v"(acc[1][3]), "+v"(acc[2][0]), "+v"(acc[2][1]), "+v"(acc[2][2]), "+v"(acc[2][3]),
-                       "+v"(acc[3][0]), "+v"(acc[3][1]), "+v"(acc[3][2]), "+v"(acc[3][3]));
+        if constexpr (!COARSE)
+            asm volatile(""
+                         : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[0][2]), "+v"(acc[0][3]), "+v"(acc[1][0]),
+                           "+v"(acc[1][1]), "+v"(acc[1][2]), "+v"(acc[1][3]), "+v"(acc[2][0]), "+v"(acc[2][1]),
+                           "+v"(acc[2][2]), "+v"(acc[2][3]), "+v"(acc[3][0]), "+v"(acc[3][1]), "+v"(acc[3][2]),
+                           "+v"(acc[3][3]));
     };
 
     Operands ops0, ops1;
@@ -409,6 +431,12 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
     } else {
         read_fragments(ops0, smem);
         read_corrections(ops0, smem);
+        if constexpr (COARSE) {  // the slot of step 0 holds the correction of the whole row
+#pragma unroll
+            for (int ms = 0; ms < MS; ++ms)
+#pragma unroll
+                for (int ns = 0; ns < NS; ++ns) chain[ms][ns] = ops0.cinit[ms];
+        }
         for (int s = 0; s < steps; s += 2) {
             compute_step(ops0, ops1, s);
             if (s + 1 < steps) compute_step(ops1, ops0, s + 1);  // uniform over the workgroup (it holds a barrier)
@@ -442,20 +470,34 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
             if (a.chan_scale) c = a.chan_scale[expert * (size_t)a.N + n];
             c *= inv_alpha;
         }
+        [[maybe_unused]] int row_scale = 0;  // COARSE: the one scale of weight row n
+        if constexpr (COARSE) row_scale = scale_t[expert * (size_t)a.N + n];
 #pragma unroll
         for (int ms = 0; ms < MS; ++ms)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int ml = wm * 64 + ms * 16 + 4 * lq + r;
                 __half h;
-                if constexpr (INT_SCALE) h = __float2half_rn((float)acc[ms][ns][r] * sa[ms][r] * c);
-                else h = __float2half_rn(acc[ms][ns][r] * sa[ms][r]);
+                [[maybe_unused]] int acc_i = 0;
+                if constexpr (COARSE) {
+                    if constexpr (INT_SCALE) {
+                        acc_i = chain[ms][ns][r] * row_scale;  // wraps modulo 2^32 like the grouped sum
+                        h = __float2half_rn((float)acc_i * sa[ms][r] * c);
+                    } else {
+                        h = __float2half_rn((float)chain[ms][ns][r] * __int_as_float(row_scale) * sa[ms][r]);
+                    }
+                } else if constexpr (INT_SCALE) {
+                    acc_i = acc[ms][ns][r];
+                    h = __float2half_rn((float)acc_i * sa[ms][r] * c);
+                } else {
+                    h = __float2half_rn(acc[ms][ns][r] * sa[ms][r]);
+                }
                 if (staged) {
                     otile[ml * kPitch + nl] = h;
                 } else if (ml < m_rows) {
                     const size_t o = (size_t)(m0 + ml) * a.N + n;
                     if constexpr (INT_SCALE) {
-                        if (a.acc_out) a.acc_out[o] = acc[ms][ns][r];
+                        if (a.acc_out) a.acc_out[o] = acc_i;
                     }
                     a.out[o] = h;
                 }
@@ -476,15 +518,28 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
     }
 }
 
-// INT_SCALE: Eq. (2) with the scale step chosen by the flag the scale preparation left; else Eq. (1).
-template <bool INT_SCALE>
+// Coarse-grained form only: the correction of a whole token row, the sum of its per-step corrections, replaces the
+// one of step 0.
+__global__ __launch_bounds__(256) void sum_row_corrections_kernel(int32_t* __restrict__ s8, int steps, int M) {
+    const int m = blockIdx.x * 256 + threadIdx.x;
+    if (m >= M) return;
+    int total = 0;
+    for (int t = 0; t < steps; ++t) total += s8[(size_t)t * M + m];
+    s8[m] = total;
+}
+
+// INT_SCALE: Eq. (2) with the scale step chosen by the flag the scale preparation left; else Eq. (1).  COARSE: one
+// group over all of K.
+template <bool INT_SCALE, bool COARSE>
 __global__ __launch_bounds__(kThreads) void gemm_prefill_kernel(GemmArgs a, const int8_t* __restrict__ xp,
                                                                 const int32_t* __restrict__ s8,
                                                                 const int32_t* __restrict__ scale_t,
                                                                 const int32_t* __restrict__ wide_flag,
                                                                 const int2* __restrict__ tile_table) {
     extern __shared__ __align__(16) unsigned char smem[];  // [kStages][activations 16 KB | weights 16 KB | aux 2 KB]
-    if constexpr (INT_SCALE) {
+    if constexpr (COARSE) {
+        gemm_prefill_tile<INT_SCALE, false, true>(a, xp, s8, scale_t, tile_table, smem);
+    } else if constexpr (INT_SCALE) {
         if (*wide_flag != 0) gemm_prefill_tile<true, true>(a, xp, s8, scale_t, tile_table, smem);
         else gemm_prefill_tile<true, false>(a, xp, s8, scale_t, tile_table, smem);
     } else {
@@ -492,7 +547,7 @@ __global__ __launch_bounds__(kThreads) void gemm_prefill_kernel(GemmArgs a, cons
     }
 }
 
-template <bool INT_SCALE>
+template <bool INT_SCALE, bool COARSE>
 hipError_t launch_tile(const GemmArgs& a, const int8_t* xp, const int32_t* s8, const int32_t* scale_t,
                        const int32_t* flag, const int2* tile_table, hipStream_t stream) {
     const size_t smem = (size_t)kStages * kStageBytes;
@@ -500,13 +555,13 @@ hipError_t launch_tile(const GemmArgs& a, const int8_t* xp, const int32_t* s8, c
     const int tiles = ((a.N + kBN - 1) / kBN) * tiles_m;
     static bool raised = false;
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_prefill_kernel<INT_SCALE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_prefill_kernel<INT_SCALE, COARSE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((gemm_prefill_kernel<INT_SCALE>), dim3(tiles), dim3(kThreads), smem, stream, a, xp, s8, scale_t,
-                       flag, tile_table);
+    hipLaunchKernelGGL((gemm_prefill_kernel<INT_SCALE, COARSE>), dim3(tiles), dim3(kThreads), smem, stream, a, xp, s8,
+                       scale_t, flag, tile_table);
     return hipGetLastError();
 }
 
@@ -543,8 +598,15 @@ hipError_t launch_gemm_prefill(const GemmArgs& a, bool int_scale, void* workspac
     else hipLaunchKernelGGL(prepare_scales_kernel<false>, sgrid, dim3(256), 0, stream, scale, a.N, NG, scale_t, flag);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return int_scale ? launch_tile<true>(a, xp, s8, scale_t, flag, tile_table, stream)
-                     : launch_tile<false>(a, xp, s8, scale_t, flag, tile_table, stream);
+    if (a.group == a.K && a.K > kStepK) {  // coarse-grained: one group over several K steps
+        hipLaunchKernelGGL(sum_row_corrections_kernel, dim3((a.M + 255) / 256), dim3(256), 0, stream, s8, a.K / kStepK, a.M);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        return int_scale ? launch_tile<true, true>(a, xp, s8, scale_t, flag, tile_table, stream)
+                         : launch_tile<false, true>(a, xp, s8, scale_t, flag, tile_table, stream);
+    }
+    return int_scale ? launch_tile<true, false>(a, xp, s8, scale_t, flag, tile_table, stream)
+                     : launch_tile<false, false>(a, xp, s8, scale_t, flag, tile_table, stream);
 }
 
 }  // namespace intscale

@@ -190,6 +190,30 @@ def test_gemm_wider_groups_and_coarse_grained(P, kernel, group):
     check_fs(host(P.is_gemm_w4a8_floatscale(dev(xq), dev(sa), dev(O.pack_int4(q)), dev(s), group)), fs)
 
 
+@pytest.mark.parametrize("M,N,K", [(200, 300, 1024), (130, 80, 2048), (65, 264, 256), (513, 257, 1152)])
+def test_coarse_grained_tiled_kernel(P, M, N, K):
+    """group = K with more than 64 token rows: the tiled kernel's coarse-grained instance (partial products carried by
+    the MFMA accumulators across all K steps, one scale per weight row in the epilogue), including extreme codes and
+    scales that wrap the 32-bit result."""
+    rng = np.random.default_rng(K + M)
+    xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+    q = rng.integers(-8, 8, size=(N, K)).astype(np.int8)
+    xq[0], xq[1], q[0], q[1] = -128, 127, -8, 7
+    sa = rng.random(M).astype(np.float32)
+    c = (rng.random(N) + 0.01).astype(np.float32)
+    s = rng.random((N, 1)).astype(np.float32) * 0.01
+    for IS in (rng.integers(0, 1025, size=(N, 1)).astype(np.int32),
+               rng.integers(-2 ** 31, 2 ** 31, size=(N, 1), dtype=np.int64).astype(np.int32)):
+        ref = O.gemm_w4a8_intscale(xq, sa, O.pack_int4(q), IS, c, K, 9)
+        out, acc = P.is_gemm_w4a8_intscale(dev(xq), dev(sa), dev(O.pack_int4(q)), dev(IS), dev(c), K, 9, want_acc=True)
+        assert np.array_equal(host(acc), ref.acc)
+        check_out(host(out), ref.out)
+        out2, _ = P.is_gemm_w4a8_intscale(dev(xq), dev(sa), dev(O.pack_int4(q)), dev(IS), dev(c), K, 9)
+        check_out(host(out2), ref.out)
+    fs = O.gemm_w4a8_floatscale(xq, sa, O.pack_int4(q), s, K)
+    check_fs(host(P.is_gemm_w4a8_floatscale(dev(xq), dev(sa), dev(O.pack_int4(q)), dev(s), K)), fs)
+
+
 def test_gemm_empty_batch(P):
     rng = np.random.default_rng(3)
     xq, qw, IS, s, sa, c = rand_quantised(rng, 1, 16, 128)
