@@ -291,3 +291,80 @@ def gemm_w4a8_intscale_safe(xq, a_scale, qweight, scale_i32, chan_scale, group: 
     with np.errstate(over="ignore"):
         out16 = out.astype(np.float16)
     return SafeResult(out, out16, mag)
+
+
+# ---------------------------------------------------------------------------------------------------------------------
+# Fine-grained W8A8 (int8 weights; the paper's LLaMA-3 recipe uses it for down-projection layers, Sec. 5.5 / Table 5).
+# Same equations with n = 8 on the weight side; written out in numpy (int64 / float64), no blocking.
+# ---------------------------------------------------------------------------------------------------------------------
+class QuantizedWeights8(NamedTuple):
+    qweight: np.ndarray      # int8 [N,K]
+    scale_f32: np.ndarray    # float32 [N,K/G], s = max|w| / 127
+    scale_i32: np.ndarray    # int32 [N,K/G]
+    chan_scale: np.ndarray   # float32 [N]
+    alpha_log2: int
+
+
+def quantize_weights_int8_group(w: np.ndarray, group: int, alpha_log2: int, scale_mode: int = SCALE_RAW
+                                ) -> QuantizedWeights8:
+    """Appendix A.1 with n = 8 on every (row, group): s = max|w| / 127, q = clamp(rne(w / s), -128, 127), both in
+    IEEE fp32; then INT(s * alpha) of Eq. (2) (RAW) or INT(s / c * alpha) with c[n] = max_g s[n,g] (NORM);
+    alpha_log2 = -1 runs the amplifier search of Sec. 4.1."""
+    w32 = np.asarray(w).astype(np.float32)
+    N, K = w32.shape
+    if K % group or group <= 0 or not (-1 <= alpha_log2 <= 16) or scale_mode not in (SCALE_RAW, SCALE_NORM):
+        raise ValueError("oracle quantize_weights_int8_group: bad arguments")
+    NG = K // group
+    wg = w32.reshape(N, NG, group)
+    amax = np.abs(wg).max(axis=2).astype(np.float32)
+    s = (amax / np.float32(127.0)).astype(np.float32)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        r = np.rint((wg / s[:, :, None]).astype(np.float32))
+    q = np.where(s[:, :, None] > 0, np.clip(r, -128.0, 127.0), 0.0).astype(np.int8).reshape(N, K)
+    if scale_mode == SCALE_NORM:
+        c = s.max(axis=1).astype(np.float32)
+        with np.errstate(divide="ignore", invalid="ignore"):
+            amplified = np.where(c[:, None] > 0, (s / c[:, None]).astype(np.float32), np.float32(0)).astype(np.float32)
+    else:
+        c = np.ones(N, np.float32)
+        amplified = s
+    a = amplifier_log2(amplified) if alpha_log2 < 0 else alpha_log2
+    IS = np.rint(np.ldexp(amplified, a).astype(np.float32)).astype(np.int32)
+    return QuantizedWeights8(q, s, IS, c, a)
+
+
+def group_partials_w8(xq: np.ndarray, q8: np.ndarray, group: int) -> np.ndarray:
+    """P[m,n,g] = sum over group g of xq[m,k] * q[n,k], int64 [M,N,K/G] (|P| <= G * 128 * 128)."""
+    M, K = xq.shape
+    N = q8.shape[0]
+    xg = np.asarray(xq).astype(np.int64).reshape(M, K // group, group)
+    qg = np.asarray(q8).astype(np.int64).reshape(N, K // group, group)
+    return np.einsum("mgk,ngk->mng", xg, qg)
+
+
+def gemm_w8a8_intscale(xq, a_scale, q8, scale_i32, chan_scale, group: int, alpha_log2: int) -> IntScaleResult:
+    """Eq. (2) / Table 2 "Ours" with int8 weights: acc = sum_g P_g * IS_g in int32 (wrapping), one conversion."""
+    p = group_partials_w8(xq, q8, group)
+    terms = p * np.asarray(scale_i32).astype(np.int64)[None, :, :]
+    acc64 = terms.sum(axis=2)
+    peak = np.abs(np.cumsum(terms, axis=2)).max(axis=2)
+    acc = ((acc64 + 2 ** 31) % 2 ** 32 - 2 ** 31).astype(np.int32)
+    N = acc.shape[1]
+    sa = _c(a_scale, np.float32).astype(np.float64)[:, None]
+    c = np.ones((1, N)) if chan_scale is None else _c(chan_scale, np.float32).astype(np.float64)[None, :]
+    out = acc.astype(np.float64) * sa * c / float(2 ** alpha_log2)
+    with np.errstate(over="ignore"):
+        out16 = out.astype(np.float16)
+    return IntScaleResult(acc, out, out16, acc64, peak)
+
+
+def gemm_w8a8_floatscale(xq, a_scale, q8, scale_f32, group: int) -> FloatScaleResult:
+    """Eq. (1) / Table 2 "Atom" with int8 weights, accumulated in double."""
+    p = group_partials_w8(xq, q8, group).astype(np.float64)
+    s = _c(scale_f32, np.float32).astype(np.float64)[None, :, :]
+    sa = _c(a_scale, np.float32).astype(np.float64)[:, None]
+    out = (p * s).sum(axis=2) * sa
+    mag = (np.abs(p) * s).sum(axis=2) * sa
+    with np.errstate(over="ignore"):
+        out16 = out.astype(np.float16)
+    return FloatScaleResult(out, out16, mag)

@@ -284,3 +284,61 @@ def test_safe_form_equals_eq2_without_overflow():
     assert np.array_equal(r.acc.astype(np.int64), r.acc64)
     assert np.allclose(sres.out, r.out, rtol=1e-15, atol=0) and np.array_equal(sres.out_fp16, r.out_fp16)
     assert np.all(sres.abs_sum >= np.abs(sres.out) * (1 - 1e-12))
+
+
+# ------------------------------------------------------------------------------------------------ W8A8
+def test_w8a8_brute_force_and_plain_matmul():
+    rng = np.random.default_rng(21)
+    M, N, K, G, a = 3, 4, 24, 8, 9
+    xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+    q = rng.integers(-128, 128, size=(N, K)).astype(np.int8)
+    IS = rng.integers(-300, 300, size=(N, K // G)).astype(np.int32)
+    s = (rng.random((N, K // G)) * 0.1).astype(np.float32)
+    sa = (rng.random(M) + 0.01).astype(np.float32)
+    c = (rng.random(N) + 0.01).astype(np.float32)
+    r = O.gemm_w8a8_intscale(xq, sa, q, IS, c, G, a)
+    f = O.gemm_w8a8_floatscale(xq, sa, q, s, G)
+    for m in range(M):
+        for n in range(N):
+            acc, fs = 0, Fraction(0)
+            for g in range(K // G):
+                p = sum(int(xq[m, k]) * int(q[n, k]) for k in range(g * G, (g + 1) * G))
+                acc += p * int(IS[n, g])
+                fs += Fraction(p) * Fraction(float(s[n, g]))
+            assert int(r.acc[m, n]) == acc == int(r.acc64[m, n])
+            exact = Fraction(acc) * Fraction(float(sa[m])) * Fraction(float(c[n])) / 2 ** a
+            assert r.out[m, n] == pytest.approx(float(exact), rel=1e-14, abs=0)
+            assert f.out[m, n] == pytest.approx(float(Fraction(float(sa[m])) * fs), rel=1e-13, abs=1e-300)
+    # one group with unit scale is the plain integer matmul; codes that fit 4 bits agree with the W4 oracle
+    ones = np.ones((N, 1), np.int32)
+    assert np.array_equal(O.gemm_w8a8_intscale(xq, sa, q, ones, None, K, 0).acc64, xq.astype(np.int64) @ q.astype(np.int64).T)
+    q4 = rng.integers(-8, 8, size=(N, K)).astype(np.int8)
+    r4 = O.gemm_w4a8_intscale(xq, sa, O.pack_int4(q4), IS, c, G, a)
+    r8 = O.gemm_w8a8_intscale(xq, sa, q4, IS, c, G, a)
+    assert np.array_equal(r4.acc, r8.acc) and np.array_equal(r4.out, r8.out) and np.array_equal(r4.max_prefix, r8.max_prefix)
+    # wrap-around of the 32-bit accumulator
+    big = np.full((N, K // G), 2 ** 30, np.int32)
+    rw = O.gemm_w8a8_intscale(xq, sa, q, big, None, G, 0)
+    assert np.all((rw.acc64 - rw.acc.astype(np.int64)) % 2 ** 32 == 0) and np.any(rw.acc64 != rw.acc)
+
+
+def test_w8_weight_quantizer_hand_example_and_invariants():
+    # s = 127 / 127 = 1 exactly: codes are the values rounded half to even
+    w = np.array([[127.0, -126.5, 0.5, 1.5, 2.5, -0.5, -127.0, 64.0]], np.float16)
+    r = O.quantize_weights_int8_group(w, 8, 3, O.SCALE_RAW)
+    assert r.scale_f32[0, 0] == 1.0 and r.qweight.tolist() == [[127, -126, 0, 2, 2, 0, -127, 64]]
+    assert r.scale_i32[0, 0] == 8 and r.chan_scale[0] == 1.0
+    rng = np.random.default_rng(22)
+    w = (rng.standard_normal((12, 512)) * 0.02).astype(np.float16)
+    w[3, 128:256] = 0
+    for mode in (O.SCALE_RAW, O.SCALE_NORM):
+        r = O.quantize_weights_int8_group(w, 128, 10, mode)
+        wg = w.astype(np.float64).reshape(12, 4, 128)
+        qg = r.qweight.astype(np.float64).reshape(12, 4, 128)
+        nz = r.scale_f32 > 0
+        assert np.all(np.abs(qg).max(axis=2)[nz] == 127) and np.all(qg[~nz] == 0) and not nz[3, 1]
+        assert np.all(np.abs(wg - qg * r.scale_f32.astype(np.float64)[:, :, None]) <= 0.5000001 * r.scale_f32[:, :, None])
+        ratio = r.scale_f32 / r.chan_scale[:, None] if mode == O.SCALE_NORM else r.scale_f32
+        assert np.all(np.abs(r.scale_i32 / 1024.0 - ratio) <= 0.5 / 1024 + 1e-7)
+    assert O.quantize_weights_int8_group(w, 128, -1, O.SCALE_NORM).alpha_log2 == O.amplifier_log2(
+        (r.scale_f32 / r.chan_scale[:, None]).astype(np.float32))
