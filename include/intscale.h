@@ -118,6 +118,27 @@ int is_gemm_w4a8_floatscale_grouped(const int8_t* xq, const float* a_scale, cons
 size_t is_gemm_grouped_workspace_bytes(int num_experts, int M_total, int N, int K, int group);
 
 /*
+ * Fine-grained W8A8 (int8 weights in groups along K; the paper's LLaMA-3 recipe uses it for the down-projection
+ * layers, Sec. 5.5 / Table 5).  Same equations with n = 8 on the weight side (Appendix A.1):
+ *   s = max|w| over the group / 127,  q = clamp(rne(w / s), -128, 127),  integer scales as for int4.
+ *   qweight8   int8 [N, K], one code per byte, row-major; the other tensors as in the canonical layouts above
+ * is_quantize_weights_int8_group takes the arguments and requirements of is_quantize_weights_int4_group.
+ * The GEMMs compute Eq. (2) resp. Eq. (1) exactly as their W4A8 counterparts (a group's partial sum is at most 2^21
+ * in magnitude, so the same integer scale step applies); group and K multiples of 128, any M >= 0, any N >= 1;
+ * `workspace` of at least is_gemm_w8a8_workspace_bytes(M,N,K,group) bytes is always needed (transposed scales).
+ */
+int is_quantize_weights_int8_group(const void* w_fp16, int N, int K, int group, int alpha_log2, int scale_mode,
+                                   int8_t* qweight8, float* scale_f32, int32_t* scale_i32, float* chan_scale,
+                                   int* alpha_log2_dev, void* stream);
+int is_gemm_w8a8_intscale(const int8_t* xq, const float* a_scale, const int8_t* qweight8, const int32_t* scale_i32,
+                          const float* chan_scale, int M, int N, int K, int group, int alpha_log2, void* out_fp16,
+                          int32_t* acc_out, void* workspace, size_t workspace_bytes, void* stream);
+int is_gemm_w8a8_floatscale(const int8_t* xq, const float* a_scale, const int8_t* qweight8, const float* scale_f32, int M,
+                            int N, int K, int group, void* out_fp16, void* workspace, size_t workspace_bytes,
+                            void* stream);
+size_t is_gemm_w8a8_workspace_bytes(int M, int N, int K, int group);
+
+/*
  * Overflow risk of a layer (Sec. 5.6, the appendix on maximum activations, Limitations): the largest |accumulator|
  * the integer-scale GEMM can reach with these integer scales over all int8 activation codes and int4 weight codes,
  *   bound = max_n sum_g |scale_i32[n,g]| * group * 128 * 8

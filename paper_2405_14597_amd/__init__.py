@@ -22,12 +22,16 @@ from .binding import (  # noqa: F401
     is_gemm_w4a8_intscale,
     is_gemm_w4a8_intscale_grouped,
     is_gemm_w4a8_intscale_safe,
+    is_gemm_w8a8_floatscale,
+    is_gemm_w8a8_intscale,
+    is_gemm_w8a8_workspace_bytes,
     is_gemm_workspace_bytes,
     is_intscale_overflow_bound,
     is_probe_mfma_i8,
     is_probe_stream_read,
     is_quantize_act_int8_token,
     is_quantize_weights_int4_group,
+    is_quantize_weights_int8_group,
     last_hip_error,
     library_path,
     load_library,

@@ -30,6 +30,10 @@ EXPORTED_SYMBOLS = (
     "is_gemm_w4a8_intscale_grouped",
     "is_gemm_w4a8_floatscale_grouped",
     "is_gemm_grouped_workspace_bytes",
+    "is_quantize_weights_int8_group",
+    "is_gemm_w8a8_intscale",
+    "is_gemm_w8a8_floatscale",
+    "is_gemm_w8a8_workspace_bytes",
     "is_intscale_overflow_bound",
     "is_gemm_w4a8_intscale_safe",
     "is_gemm_safe_workspace_bytes",
@@ -84,6 +88,14 @@ def load_library() -> ctypes.CDLL:
     lib.is_gemm_w4a8_floatscale_grouped.restype = ci
     lib.is_gemm_grouped_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.is_gemm_grouped_workspace_bytes.restype = sz
+    lib.is_quantize_weights_int8_group.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+    lib.is_quantize_weights_int8_group.restype = ci
+    lib.is_gemm_w8a8_intscale.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.is_gemm_w8a8_intscale.restype = ci
+    lib.is_gemm_w8a8_floatscale.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, vp, vp, sz, vp]
+    lib.is_gemm_w8a8_floatscale.restype = ci
+    lib.is_gemm_w8a8_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.is_gemm_w8a8_workspace_bytes.restype = sz
     lib.is_intscale_overflow_bound.argtypes = [vp, ci, ci, ci, vp, vp]
     lib.is_intscale_overflow_bound.restype = ci
     lib.is_gemm_w4a8_intscale_safe.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, sz, vp]
@@ -241,6 +253,75 @@ def is_gemm_w4a8_floatscale(xq, a_scale, qweight, scale_f32, group: int, out=Non
     st = load_library().is_gemm_w4a8_floatscale(_p(xq), _p(a_scale), _p(qweight), _p(scale_f32), M, N, K, group,
                                                _p(out), _p(ws), ws_bytes, _stream_handle(stream))
     _check("is_gemm_w4a8_floatscale", st)
+    return out
+
+
+def is_quantize_weights_int8_group(w, group: int, alpha_log2: int, scale_mode: int = IS_SCALE_RAW, stream=None
+                                   ) -> QuantizedWeights:
+    """Fine-grained W8A8 weights: qweight is int8 [N,K]."""
+    torch = _torch()
+    N, K = w.shape
+    _require(w, torch.float16, (N, K), "w")
+    if group <= 0 or K % group != 0:
+        raise IntScaleError("is_quantize_weights_int8_group", IS_ERR_INVALID_ARG)
+    dev = w.device
+    q = torch.empty((N, K), dtype=torch.int8, device=dev)
+    s = torch.empty((N, K // group), dtype=torch.float32, device=dev)
+    si = torch.empty((N, K // group), dtype=torch.int32, device=dev)
+    c = torch.empty((N,), dtype=torch.float32, device=dev)
+    a_dev = torch.empty((4,), dtype=torch.int32, device=dev)
+    st = load_library().is_quantize_weights_int8_group(_p(w), N, K, group, alpha_log2, scale_mode, _p(q), _p(s), _p(si),
+                                                      _p(c), _p(a_dev), _stream_handle(stream))
+    _check("is_quantize_weights_int8_group", st)
+    return QuantizedWeights(q, s, si, c, a_dev[:1])
+
+
+def is_gemm_w8a8_workspace_bytes(M: int, N: int, K: int, group: int) -> int:
+    return int(load_library().is_gemm_w8a8_workspace_bytes(M, N, K, group))
+
+
+def is_gemm_w8a8_intscale(xq, a_scale, qweight8, scale_i32, chan_scale, group: int, alpha_log2: int, out=None,
+                          acc_out=None, want_acc: bool = False, workspace=None, stream=None):
+    """Returns (out fp16 [M,N], acc int32 [M,N] or None)."""
+    torch = _torch()
+    M, K = xq.shape
+    N = qweight8.shape[0]
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    _require(qweight8, torch.int8, (N, K), "qweight8")
+    _require(scale_i32, torch.int32, (N, K // group), "scale_i32")
+    if chan_scale is not None:
+        _require(chan_scale, torch.float32, (N,), "chan_scale")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    _require(out, torch.float16, (M, N), "out")
+    if acc_out is None and want_acc:
+        acc_out = torch.empty((M, N), dtype=torch.int32, device=xq.device)
+    if acc_out is not None:
+        _require(acc_out, torch.int32, (M, N), "acc_out")
+    ws, ws_bytes = _workspace(is_gemm_w8a8_workspace_bytes(M, N, K, group), xq.device, workspace)
+    st = load_library().is_gemm_w8a8_intscale(_p(xq), _p(a_scale), _p(qweight8), _p(scale_i32), _p(chan_scale), M, N, K,
+                                             group, alpha_log2, _p(out), _p(acc_out), _p(ws), ws_bytes,
+                                             _stream_handle(stream))
+    _check("is_gemm_w8a8_intscale", st)
+    return out, acc_out
+
+
+def is_gemm_w8a8_floatscale(xq, a_scale, qweight8, scale_f32, group: int, out=None, workspace=None, stream=None):
+    torch = _torch()
+    M, K = xq.shape
+    N = qweight8.shape[0]
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    _require(qweight8, torch.int8, (N, K), "qweight8")
+    _require(scale_f32, torch.float32, (N, K // group), "scale_f32")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    _require(out, torch.float16, (M, N), "out")
+    ws, ws_bytes = _workspace(is_gemm_w8a8_workspace_bytes(M, N, K, group), xq.device, workspace)
+    st = load_library().is_gemm_w8a8_floatscale(_p(xq), _p(a_scale), _p(qweight8), _p(scale_f32), M, N, K, group,
+                                               _p(out), _p(ws), ws_bytes, _stream_handle(stream))
+    _check("is_gemm_w8a8_floatscale", st)
     return out
 
 

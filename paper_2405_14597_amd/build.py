@@ -10,7 +10,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.environ.get("INTSCALE_LIBRARY", os.path.join(PKG_DIR, "libintscale.so"))
 
-SOURCES = ["api.hip", "quantize.hip", "gemm_skinny.hip", "gemm_decode.hip", "gemm_prefill.hip", "overflow.hip", "probe.hip"]
+SOURCES = ["api.hip", "quantize.hip", "gemm_skinny.hip", "gemm_decode.hip", "gemm_prefill.hip", "gemm_tile_w8.hip", "overflow.hip", "probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",

@@ -78,9 +78,9 @@ int is_probe_mfma_i8(int iters, int* sink, double* ops_out, void* stream) {
     return hip_status(launch_probe_mfma_i8(iters, sink, ops_out, static_cast<hipStream_t>(stream)));
 }
 
-int is_quantize_weights_int4_group(const void* w_fp16, int N, int K, int group, int alpha_log2, int scale_mode,
+static int quantize_weights_common(const void* w_fp16, int N, int K, int group, int alpha_log2, int scale_mode,
                                    void* qweight, float* scale_f32, int32_t* scale_i32, float* chan_scale,
-                                   int* alpha_log2_dev, void* stream) {
+                                   int* alpha_log2_dev, void* stream, int bits) {
     if (!ok_ptr(w_fp16) || !ok_ptr(qweight) || !ok_ptr(scale_f32) || !ok_ptr(scale_i32) || !ok_ptr(chan_scale))
         return IS_ERR_INVALID_ARG;
     if (N <= 0 || K <= 0 || group <= 0 || K % group != 0 || (K & 1) || (group & 1)) return IS_ERR_INVALID_ARG;
@@ -90,7 +90,21 @@ int is_quantize_weights_int4_group(const void* w_fp16, int N, int K, int group, 
     if (alpha_log2_dev && (reinterpret_cast<uintptr_t>(alpha_log2_dev) & 3u)) return IS_ERR_INVALID_ARG;
     return hip_status(launch_quantize_weights(static_cast<const __half*>(w_fp16), N, K, group, alpha_log2, scale_mode,
                                               static_cast<uint8_t*>(qweight), scale_f32, scale_i32, chan_scale,
-                                              alpha_log2_dev, static_cast<hipStream_t>(stream)));
+                                              alpha_log2_dev, static_cast<hipStream_t>(stream), bits));
+}
+
+int is_quantize_weights_int4_group(const void* w_fp16, int N, int K, int group, int alpha_log2, int scale_mode,
+                                   void* qweight, float* scale_f32, int32_t* scale_i32, float* chan_scale,
+                                   int* alpha_log2_dev, void* stream) {
+    return quantize_weights_common(w_fp16, N, K, group, alpha_log2, scale_mode, qweight, scale_f32, scale_i32,
+                                   chan_scale, alpha_log2_dev, stream, 4);
+}
+
+int is_quantize_weights_int8_group(const void* w_fp16, int N, int K, int group, int alpha_log2, int scale_mode,
+                                   int8_t* qweight8, float* scale_f32, int32_t* scale_i32, float* chan_scale,
+                                   int* alpha_log2_dev, void* stream) {
+    return quantize_weights_common(w_fp16, N, K, group, alpha_log2, scale_mode, qweight8, scale_f32, scale_i32,
+                                   chan_scale, alpha_log2_dev, stream, 8);
 }
 
 int is_quantize_act_int8_token(const void* x_fp16, int M, int K, int8_t* xq, float* a_scale, void* stream) {
@@ -181,6 +195,63 @@ int is_gemm_w4a8_floatscale_grouped(const int8_t* xq, const float* a_scale, cons
                                     void* stream) {
     return gemm_common(xq, a_scale, qweight, scale_f32, nullptr, row_offsets, num_experts, M_total, N, K, group, 0,
                        out_fp16, nullptr, workspace, workspace_bytes, stream, false, true);
+}
+
+// ---- fine-grained W8A8
+static int check_w8_shape(int M, int N, int K, int group) {
+    if (M < 0 || N <= 0 || K <= 0 || group <= 0 || K % group != 0) return IS_ERR_INVALID_ARG;
+    if (group % 128 != 0) return IS_ERR_UNSUPPORTED;
+    if (M > (1 << 20) || K > (1 << 20) || (long long)N * (K / group) * 4 >= (1LL << 31)) return IS_ERR_UNSUPPORTED;
+    return IS_OK;
+}
+
+size_t is_gemm_w8a8_workspace_bytes(int M, int N, int K, int group) {
+    return check_w8_shape(M, N, K, group) == IS_OK ? gemm_w8_workspace_bytes(1, M, N, K, group) : 0;
+}
+
+static int gemm_w8_common(const int8_t* xq, const float* a_scale, const int8_t* qweight8, const void* scale,
+                          const float* chan_scale, int M, int N, int K, int group, int alpha_log2, void* out_fp16,
+                          int32_t* acc_out, void* workspace, size_t workspace_bytes, void* stream, bool int_scale) {
+    const int shape = check_w8_shape(M, N, K, group);
+    if (shape != IS_OK) return shape;
+    if (int_scale && (alpha_log2 < 0 || alpha_log2 > 30)) return IS_ERR_INVALID_ARG;
+    if (!ok_opt(workspace)) return IS_ERR_INVALID_ARG;
+    if (workspace == nullptr || workspace_bytes < gemm_w8_workspace_bytes(1, M, N, K, group)) return IS_ERR_WORKSPACE;
+    if (!ok_ptr(qweight8) || !ok_ptr(scale) || !ok_opt(chan_scale)) return IS_ERR_INVALID_ARG;
+    if (M == 0) return IS_OK;
+    if (!ok_ptr(xq) || a_scale == nullptr || (reinterpret_cast<uintptr_t>(a_scale) & 3u) || !ok_ptr(out_fp16) ||
+        !ok_opt(acc_out))
+        return IS_ERR_INVALID_ARG;
+    GemmArgs a;
+    a.xq = xq;
+    a.a_scale = a_scale;
+    a.qweight = reinterpret_cast<const uint8_t*>(qweight8);
+    a.scale = scale;
+    a.chan_scale = chan_scale;
+    a.row_offsets = nullptr;
+    a.out = static_cast<__half*>(out_fp16);
+    a.acc_out = acc_out;
+    a.M = M;
+    a.N = N;
+    a.K = K;
+    a.group = group;
+    a.alpha_log2 = int_scale ? alpha_log2 : 0;
+    a.num_experts = 1;
+    return hip_status(launch_gemm_w8(a, int_scale, workspace, static_cast<hipStream_t>(stream)));
+}
+
+int is_gemm_w8a8_intscale(const int8_t* xq, const float* a_scale, const int8_t* qweight8, const int32_t* scale_i32,
+                          const float* chan_scale, int M, int N, int K, int group, int alpha_log2, void* out_fp16,
+                          int32_t* acc_out, void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_w8_common(xq, a_scale, qweight8, scale_i32, chan_scale, M, N, K, group, alpha_log2, out_fp16, acc_out,
+                          workspace, workspace_bytes, stream, true);
+}
+
+int is_gemm_w8a8_floatscale(const int8_t* xq, const float* a_scale, const int8_t* qweight8, const float* scale_f32, int M,
+                            int N, int K, int group, void* out_fp16, void* workspace, size_t workspace_bytes,
+                            void* stream) {
+    return gemm_w8_common(xq, a_scale, qweight8, scale_f32, nullptr, M, N, K, group, 0, out_fp16, nullptr, workspace,
+                          workspace_bytes, stream, false);
 }
 
 size_t is_gemm_safe_workspace_bytes(int M, int N, int K, int group) {

@@ -43,7 +43,7 @@ struct DecodePlan {
 hipError_t launch_quantize_act(const __half* x, int M, int K, int8_t* xq, float* a_scale, hipStream_t stream);
 hipError_t launch_quantize_weights(const __half* w, int N, int K, int group, int alpha_log2, int scale_mode,
                                    uint8_t* qweight, float* scale_f32, int32_t* scale_i32, float* chan_scale,
-                                   int* alpha_log2_dev, hipStream_t stream);
+                                   int* alpha_log2_dev, hipStream_t stream, int bits = 4);  // bits: 4 or 8 (one byte per code)
 hipError_t launch_gemm_skinny(const GemmArgs& a, bool int_scale, hipStream_t stream);
 bool try_launch_gemm_decode(const GemmArgs& a, bool int_scale, hipStream_t stream, hipError_t* err);
 // MFMA-bound tiled kernel; `workspace` holds gemm_prefill_workspace_bytes(...) bytes (num_experts = 1 and M = all
@@ -51,6 +51,9 @@ bool try_launch_gemm_decode(const GemmArgs& a, bool int_scale, hipStream_t strea
 size_t gemm_prefill_workspace_bytes(int num_experts, int M, int N, int K, int group);
 hipError_t launch_gemm_prefill(const GemmArgs& a, bool int_scale, void* workspace, hipStream_t stream);
 
+// Fine-grained W8A8 (gemm_tile_w8.hip): `a.qweight` holds int8 codes [N,K]; one tiled kernel for every M.
+size_t gemm_w8_workspace_bytes(int num_experts, int M, int N, int K, int group);
+hipError_t launch_gemm_w8(const GemmArgs& a, bool int_scale, void* workspace, hipStream_t stream);
 int cu_count();
 
 // Overflow handling (overflow.hip): the layer's worst-case |accumulator| into *bound_dev, and the float scales

@@ -122,13 +122,16 @@ __global__ __launch_bounds__(kActThreads) void quantize_act_kernel(const __half*
 
 // ---------------------------------------------------------------------------------------------------------
 // Weights, step 1: one wave per (row, group).  Each lane owns pairs of neighbouring k so that it writes whole
-// bytes of the canonical packing (even k in the low nibble).
+// bytes of the canonical packing (even k in the low nibble).  BITS = 4: codes -8..7, s = absmax / 7, two codes per
+// byte; BITS = 8 (the fine-grained W8A8 recipe): codes -128..127, s = absmax / 127, one code per byte, row-major.
 // ---------------------------------------------------------------------------------------------------------
 constexpr int kWqThreads = 256;
 
+template <int BITS>
 __global__ __launch_bounds__(kWqThreads) void quantize_weight_groups_kernel(const __half* __restrict__ w, int N, int K,
                                                                             int G, uint8_t* __restrict__ qweight,
                                                                             float* __restrict__ scale_f32) {
+    constexpr float kHi = BITS == 4 ? 7.0f : 127.0f, kLo = -kHi - 1.0f;
     const int NG = K / G;
     const long long unit = (long long)blockIdx.x * (kWqThreads / kWave) + threadIdx.x / kWave;
     if (unit >= (long long)N * NG) return;
@@ -145,18 +148,22 @@ __global__ __launch_bounds__(kWqThreads) void quantize_weight_groups_kernel(cons
         amax = fmaxf(amax, fmaxf(fabsf(f.x), fabsf(f.y)));
     }
     amax = wave_max(amax);
-    const float s = amax / 7.0f;
+    const float s = amax / kHi;
     if (lane == 0) scale_f32[unit] = s;
 
-    uint8_t* dst = qweight + (base >> 1);
+    uint8_t* dst = qweight + (BITS == 4 ? base >> 1 : base);
     for (int p = lane; p < npairs; p += kWave) {
         float2 f = __half22float2(src[p]);
         int q0 = 0, q1 = 0;
         if (s > 0.0f) {
-            q0 = quant_code(f.x, s, -8.0f, 7.0f);
-            q1 = quant_code(f.y, s, -8.0f, 7.0f);
+            q0 = quant_code(f.x, s, kLo, kHi);
+            q1 = quant_code(f.y, s, kLo, kHi);
         }
-        dst[p] = (uint8_t)(((uint32_t)q0 & 0xFu) | (((uint32_t)q1 & 0xFu) << 4));
+        if constexpr (BITS == 4) {
+            dst[p] = (uint8_t)(((uint32_t)q0 & 0xFu) | (((uint32_t)q1 & 0xFu) << 4));
+        } else {
+            reinterpret_cast<uint16_t*>(dst)[p] = (uint16_t)(((uint32_t)q0 & 0xFFu) | (((uint32_t)q1 & 0xFFu) << 8));
+        }
     }
 }
 
@@ -241,13 +248,17 @@ hipError_t launch_quantize_act(const __half* x, int M, int K, int8_t* xq, float*
 
 hipError_t launch_quantize_weights(const __half* w, int N, int K, int group, int alpha_log2, int scale_mode,
                                    uint8_t* qweight, float* scale_f32, int32_t* scale_i32, float* chan_scale,
-                                   int* alpha_log2_dev, hipStream_t stream) {
+                                   int* alpha_log2_dev, hipStream_t stream, int bits) {
     const int NG = K / group;
     const long long units = (long long)N * NG;
     const int waves_per_block = kWqThreads / kWave;
     const unsigned blocks1 = (unsigned)((units + waves_per_block - 1) / waves_per_block);
-    hipLaunchKernelGGL(quantize_weight_groups_kernel, dim3(blocks1), dim3(kWqThreads), 0, stream, w, N, K, group,
-                       qweight, scale_f32);
+    if (bits == 4)
+        hipLaunchKernelGGL(quantize_weight_groups_kernel<4>, dim3(blocks1), dim3(kWqThreads), 0, stream, w, N, K, group,
+                           qweight, scale_f32);
+    else
+        hipLaunchKernelGGL(quantize_weight_groups_kernel<8>, dim3(blocks1), dim3(kWqThreads), 0, stream, w, N, K, group,
+                           qweight, scale_f32);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (alpha_log2 < 0) {

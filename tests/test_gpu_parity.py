@@ -235,6 +235,47 @@ def test_gemm_repeatable(P):
         assert torch.equal(acc0, acc1) and torch.equal(out0, out1) and torch.equal(fs0, fs1)
 
 
+# ------------------------------------------------------------------------------------------------ fine-grained W8A8
+@pytest.mark.parametrize("N,K,group,alpha,mode", [(16, 128, 128, 10, 0), (300, 1024, 128, 10, 1), (64, 2048, 256, -1, 1),
+                                                  (33, 512, 512, -1, 0)])
+def test_w8_weight_quantizer_bit_exact(P, N, K, group, alpha, mode):
+    w = S.weights_gaussian(N, K, 31 + N)
+    w[N // 2, :group] = 0
+    ref = O.quantize_weights_int8_group(w, group, alpha, mode)
+    got = P.is_quantize_weights_int8_group(dev(w), group, alpha, mode)
+    assert np.array_equal(host(got.qweight), ref.qweight)
+    assert np.array_equal(host(got.scale_f32), ref.scale_f32)
+    assert np.array_equal(host(got.scale_i32), ref.scale_i32)
+    assert np.array_equal(host(got.chan_scale), ref.chan_scale)
+    assert int(host(got.alpha_log2_dev)[0]) == ref.alpha_log2
+
+
+@pytest.mark.parametrize("M,N,K,group", [(1, 16, 128, 128), (8, 512, 1024, 128), (16, 272, 1024, 128), (64, 48, 2048, 128),
+                                         (65, 256, 128, 128), (129, 300, 1024, 128), (300, 700, 1152, 128),
+                                         (200, 264, 1024, 256), (130, 80, 512, 512), (513, 257, 512, 128)])
+def test_w8a8_gemm(P, M, N, K, group):
+    rng = np.random.default_rng(4000 + M + N + K)
+    xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+    q = rng.integers(-128, 128, size=(N, K)).astype(np.int8)
+    xq[0], q[0] = -128, -128  # the largest partial sums
+    if M > 1:
+        xq[1] = 127
+    sa = (rng.random(M) + 0.01).astype(np.float32)
+    c = (rng.random(N) + 0.01).astype(np.float32)
+    s = (rng.random((N, K // group)) * 1e-4).astype(np.float32)  # keeps the extreme rows inside the fp16 range
+    for IS, chan, a in ((rng.integers(0, 1025, size=(N, K // group)).astype(np.int32), c, 10),
+                        (rng.integers(-2 ** 31, 2 ** 31, size=(N, K // group), dtype=np.int64).astype(np.int32), None, 7)):
+        ref = O.gemm_w8a8_intscale(xq, sa, q, IS, chan, group, a)
+        out, acc = P.is_gemm_w8a8_intscale(dev(xq), dev(sa), dev(q), dev(IS), None if chan is None else dev(chan), group, a,
+                                           want_acc=True)
+        assert np.array_equal(host(acc), ref.acc), "int32 accumulators differ"
+        check_out(host(out), ref.out, f"M{M} N{N} K{K}")
+        out1, _ = P.is_gemm_w8a8_intscale(dev(xq), dev(sa), dev(q), dev(IS), None if chan is None else dev(chan), group, a)
+        check_out(host(out1), ref.out)
+    fs = O.gemm_w8a8_floatscale(xq, sa, q, s, group)
+    check_fs(host(P.is_gemm_w8a8_floatscale(dev(xq), dev(sa), dev(q), dev(s), group)), fs, f"M{M} N{N} K{K}")
+
+
 # ------------------------------------------------------------------------------------------------ overflow handling
 @pytest.mark.parametrize("N,K,group", [(16, 128, 128), (300, 4096, 128), (4096, 11008, 128), (40, 1024, 512)])
 def test_overflow_bound(P, N, K, group):
