@@ -46,7 +46,7 @@ def parse_args():
     ap.add_argument("--no-floatscale", action="store_true", help="skip the float-scale comparison pass")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-sample-layers", type=int, default=32)
-    ap.add_argument("--workload", choices=("decode", "prefill", "moe"), default="decode")
+    ap.add_argument("--workload", choices=("decode", "prefill", "moe", "w8a8"), default="decode")
     return ap.parse_args()
 
 
@@ -126,6 +126,8 @@ def main():
         sys.exit(2)
     if args.workload == "prefill":
         return prefill_main(args)
+    if args.workload == "w8a8":
+        return w8a8_main(args)
     if args.workload == "moe":
         return moe_main(args)
 
@@ -522,6 +524,129 @@ def prefill_main(args):
         "roofline": roofline,
         "measured_peaks": peaks,
         "cpu_baseline": cpu,
+        "shapes": shapes,
+    }
+    print(json.dumps(line))
+
+
+def w8a8_main(args):
+    """Fine-grained W8A8 on the layer the paper's LLaMA-3 recipe uses it for: the LLaMA-3-8B down projection
+    (14336 -> 4096), at M in {1, 16, 64} (weight stream, general kernel) and M = 4096 (tiled kernel).  One step =
+    activation quantiser + integer-scale GEMM per M over `--layers` (default 8 here) distinct weight sets.  `value`
+    is the algorithmic GB/s of the three small-M calls (HBM bound); the M = 4096 call is reported in `shapes` in TOP/s."""
+    import numpy as np
+    import torch
+
+    import paper_2405_14597_amd as P
+    import synth_inputs as S
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    P.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, N = S.LLAMA3_8B["down"]
+    L = args.layers if args.layers != 32 else 8
+    MS = (1, 16, 64, 4096)
+    w = torch.from_numpy(S.make_weights(3, N, K, S.seed_for(3, 2, 1))).to(dev)
+    qw = P.is_quantize_weights_int8_group(w, GROUP, ALPHA_LOG2, P.IS_SCALE_NORM)
+    del w
+    q = qw.qweight.unsqueeze(0).repeat(L, 1, 1)  # L copies: 59 MB each, so that the weights come from HBM
+    acts = {}
+    for M in MS:
+        x = torch.from_numpy(S.make_activations(3, M, K, S.seed_for(3, 2, 2) + M)).to(dev)
+        acts[M] = dict(x=x, xq=torch.empty((M, K), dtype=torch.int8, device=dev),
+                       sa=torch.empty((M,), dtype=torch.float32, device=dev),
+                       out=torch.empty((M, N), dtype=torch.float16, device=dev),
+                       ws=torch.empty(P.is_gemm_w8a8_workspace_bytes(M, N, K, GROUP), dtype=torch.uint8, device=dev))
+    torch.cuda.synchronize()
+
+    def gemm(M, l, int_scale):
+        a = acts[M]
+        if int_scale:
+            P.is_gemm_w8a8_intscale(a["xq"], a["sa"], q[l], qw.scale_i32, qw.chan_scale, GROUP, ALPHA_LOG2, out=a["out"],
+                                    workspace=a["ws"])
+        else:
+            P.is_gemm_w8a8_floatscale(a["xq"], a["sa"], q[l], qw.scale_f32, GROUP, out=a["out"], workspace=a["ws"])
+
+    def run(int_scale, with_quant, steps, warmup):
+        per = {M: 0.0 for M in MS}
+        for it in range(warmup + steps):
+            if it == warmup:
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+            for M in MS:
+                a = acts[M]
+                for l in range(L):
+                    if with_quant:
+                        P.is_quantize_act_int8_token(a["x"], a["xq"], a["sa"])
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    gemm(M, l, int_scale)
+                    e1.record()
+                    if it >= warmup:
+                        a.setdefault("ev", []).append((e0, e1))
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / steps
+        for M in MS:
+            ev = acts[M].pop("ev")
+            per[M] = 1e3 * sum(x.elapsed_time(y) for x, y in ev) / len(ev)
+        return sec, per
+
+    def alg_bytes(M):  # int8 weights, int32 scales, int8 activations, fp16 out, row/column scales
+        return N * K + 4 * N * (K // GROUP) + M * K + 2 * M * N + 4 * M + 4 * N
+
+    sec, per = run(True, True, args.steps, args.warmup)
+    small = [M for M in MS if M <= 64]
+    # value: the small-M calls only (quantiser + GEMM time measured per call below)
+    small_us = sum(per[M] for M in small)
+    value = sum(alg_bytes(M) for M in small) / small_us / 1e3
+    shapes = [dict(name=f"w8a8_down_M{M}", us=round(per[M], 2), gbs=round(alg_bytes(M) / per[M] / 1e3, 1),
+                   tops=round(2.0 * M * N * K / per[M] / 1e6, 1)) for M in MS]
+    dom = max(small, key=lambda M: per[M])
+    roofline = dict(bound="hbm", kernel="gemm_skinny_kernel<..., W8>", achieved=round(alg_bytes(dom) / per[dom] / 1e3, 1),
+                    peak=HBM_PEAK_GBS, unit="GB/s", frac=round(alg_bytes(dom) / per[dom] / 1e3 / HBM_PEAK_GBS, 4), traffic=None,
+                    avg_launch_us=round(per[dom], 2), note=f"the M = {dom} call; M = 4096 (tiled kernel, MFMA bound): "
+                    f"{2.0 * 4096 * N * K / per[4096] / 1e6:.0f} TOP/s = {2.0 * 4096 * N * K / per[4096] / 1e6 / MFMA_I8_PEAK_TOPS:.3f} of the int8 peak")
+    peaks = measured_peaks(P, torch)
+    roofline["frac_of_measured_peak"] = round(roofline["achieved"] / peaks["hbm_read_gbs"], 4)
+    speedup = fs_detail = None
+    if not args.no_floatscale:
+        n = max(3, args.steps // 2)
+        _, per_is = run(True, False, n, 2)
+        _, per_fs = run(False, False, n, 2)
+        fs_detail = {f"M{M}": round(per_fs[M] / per_is[M], 4) for M in MS}
+        speedup = sum(per_fs.values()) / sum(per_is.values())
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        M = 16
+        hw = O.quantize_weights_int8_group(S.make_weights(3, N, K, S.seed_for(3, 2, 1)), GROUP, ALPHA_LOG2, O.SCALE_NORM)
+        hx = S.make_activations(3, M, K, S.seed_for(3, 2, 2) + M)
+        t0 = time.perf_counter()
+        xq, sa = O.quantize_act_int8_token(hx)
+        ref = O.gemm_w8a8_intscale(xq, sa, hw.qweight, hw.scale_i32, hw.chan_scale, GROUP, ALPHA_LOG2)
+        dt = time.perf_counter() - t0
+        a = acts[M]
+        P.is_quantize_act_int8_token(a["x"], a["xq"], a["sa"])
+        out, acc = P.is_gemm_w8a8_intscale(a["xq"], a["sa"], q[0], qw.scale_i32, qw.chan_scale, GROUP, ALPHA_LOG2,
+                                           want_acc=True, workspace=a["ws"])
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        cpu = dict(value=round(alg_bytes(M) / dt / 1e9, 3), unit="GB/s", cores=1, kind="oracle",
+                   sample=f"the M = {M} call once (quantiser + integer-scale GEMM, numpy), {dt:.1f} s",
+                   parity=dict(acc_bit_exact=bool(np.array_equal(acc.cpu().numpy(), ref.acc)),
+                               weights_bit_exact=bool(np.array_equal(qw.qweight.cpu().numpy(), hw.qweight)),
+                               max_rel_err=float(np.max(np.abs(got - ref.out) / np.maximum(np.abs(ref.out), 1e-3)))))
+    line = {
+        "metric": "W8A8 integer-scale GEMM TOPS + HBM GB/s (% roofline); speedup vs float-scale", "value": round(value, 1),
+        "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(1e3 * sec, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"llama3-8b down projection ({K}->{N}) as fine-grained W8A8, group {GROUP}, alpha=2^{ALPHA_LOG2}, "
+                               f"M in {list(MS)}, {L} distinct weight sets", "launch": "eager", "scale_mode": "norm"},
+        "speedup_vs_floatscale": None if speedup is None else round(speedup, 4),
+        "floatscale_over_intscale_by_shape": fs_detail, "roofline": roofline, "measured_peaks": peaks, "cpu_baseline": cpu,
         "shapes": shapes,
     }
     print(json.dumps(line))

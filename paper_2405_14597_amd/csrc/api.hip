@@ -41,6 +41,12 @@ bool general_forced() {
     return force && strcmp(force, "general") == 0;
 }
 
+bool general_forced_off() {
+    // INTSCALE_FORCE_KERNEL=tiled sends the W8A8 GEMMs to the tiled kernel whatever M is (used by the tests to cover it).
+    const char* force = getenv("INTSCALE_FORCE_KERNEL");
+    return force && strcmp(force, "tiled") == 0;
+}
+
 bool wants_prefill(int M, int num_experts) { return !general_forced() && M > 64 * num_experts; }
 
 hipError_t launch_gemm(const GemmArgs& a, bool int_scale, void* workspace, hipStream_t stream) {
@@ -163,6 +169,7 @@ static int gemm_common(const int8_t* xq, const float* a_scale, const void* qweig
     a.group = group;
     a.alpha_log2 = int_scale ? alpha_log2 : 0;
     a.num_experts = grouped ? num_experts : 1;
+    a.w_bits = 4;
     return hip_status(launch_gemm(a, int_scale, workspace, static_cast<hipStream_t>(stream)));
 }
 
@@ -237,6 +244,10 @@ static int gemm_w8_common(const int8_t* xq, const float* a_scale, const int8_t* 
     a.group = group;
     a.alpha_log2 = int_scale ? alpha_log2 : 0;
     a.num_experts = 1;
+    a.w_bits = 8;
+    // up to 64 token rows the layer is a weight stream: the bandwidth-bound general kernel; else the tiled kernel
+    if (M <= 64 && !general_forced_off())
+        return hip_status(launch_gemm_skinny(a, int_scale, static_cast<hipStream_t>(stream)));
     return hip_status(launch_gemm_w8(a, int_scale, workspace, static_cast<hipStream_t>(stream)));
 }
 

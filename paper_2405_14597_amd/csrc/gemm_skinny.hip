@@ -54,8 +54,8 @@ __device__ __forceinline__ int load4(rsrc_t r, int voff, int soff) {
 // Largest workgroup (in waves) a tile shape may use.  Two limits: the vector registers its prefetch slots,
 // accumulators and operands need (a 16-wave workgroup leaves 128 per lane, 8 waves 256, 4 waves 512), and the LDS
 // reduction buffer of nwaves * R * MT KB, capped at 64 KB.
-constexpr int max_waves(int mt, int r, int d) {
-    const int regs = 8 * d * mt + 5 * d * r + 8 * r * mt + 8 * r + 8 * mt + 12;
+constexpr int max_waves(int mt, int r, int d, bool w8 = false) {
+    const int regs = 8 * d * mt + (w8 ? 9 : 5) * d * r + 8 * r * mt + 8 * r + 8 * mt + 12;
     const int by_regs = regs <= 120 ? 16 : regs <= 240 ? 8 : 4;
     const int by_lds = 64 / (mt * r);
     return by_regs < by_lds ? by_regs : by_lds;
@@ -64,9 +64,11 @@ constexpr int max_waves(int mt, int r, int d) {
 constexpr int kOutOfRange = (int)0x80000000u;  // a buffer offset past every descriptor here: the load returns 0
 
 // SPG1: every group is exactly one 128-wide step (group size 128), the common case, compiled without the
-// step-in-group counters.
-template <int MT, int R, int D, bool INT_SCALE, bool SPG1>
-__global__ __launch_bounds__(max_waves(MT, R, D) * kWave) void gemm_skinny_kernel(GemmArgs a) {
+// step-in-group counters.  W8: int8 weights (fine-grained W8A8): a lane's 32 codes of a step are two 16-byte loads,
+// used as they are, first half with the first 16 activations of the lane's K slice and second with the rest, and the
+// MFMA chain returns P itself.
+template <int MT, int R, int D, bool INT_SCALE, bool SPG1, bool W8 = false>
+__global__ __launch_bounds__(max_waves(MT, R, D, W8) * kWave) void gemm_skinny_kernel(GemmArgs a) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     using acc_t = typename std::conditional<INT_SCALE, int, float>::type;
 
@@ -91,7 +93,8 @@ __global__ __launch_bounds__(max_waves(MT, R, D) * kWave) void gemm_skinny_kerne
     const int NG = a.K / a.group;
     const int steps_per_group = SPG1 ? 1 : a.group / kStepK;
     const int n0 = blockIdx.x * (16 * R);
-    const int row_bytes = a.K >> 1;
+    const int row_bytes = W8 ? a.K : a.K >> 1;
+    constexpr int kStepBytes = W8 ? kStepK : kStepK / 2;  // weight bytes of a row per step
 
     // Buffer descriptors: this expert's weights and scales, this workgroup's token rows.
     const rsrc_t wres = make_rsrc(a.qweight + expert * (size_t)a.N * row_bytes, (size_t)a.N * row_bytes);
@@ -105,7 +108,7 @@ __global__ __launch_bounds__(max_waves(MT, R, D) * kWave) void gemm_skinny_kerne
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int n = n0 + 16 * r + li;
-        woff[r] = n < a.N ? n * row_bytes + kb * 16 : kOutOfRange;
+        woff[r] = n < a.N ? n * row_bytes + kb * (W8 ? 32 : 16) : kOutOfRange;
         soff[r] = n < a.N ? n * NG * 4 : kOutOfRange;
     }
 #pragma unroll
@@ -139,16 +142,19 @@ __global__ __launch_bounds__(max_waves(MT, R, D) * kWave) void gemm_skinny_kerne
             for (int j = 0; j < 4; ++j) acc[r][t][j] = 0;
 
     // Rotating prefetch slots and the scalar cursor of the next step to request.
-    v4i wq[D][R];
+    v4i wq[D][R][W8 ? 2 : 1];
     v4i xa[D][MT][2];
     int sc[D][R];
-    int nx_w = g_begin * steps_per_group * (kStepK / 2), nx_x = g_begin * steps_per_group * kStepK, nx_g = g_begin * 4;
+    int nx_w = g_begin * steps_per_group * kStepBytes, nx_x = g_begin * steps_per_group * kStepK, nx_g = g_begin * 4;
     int nx_left = n_steps, nx_sub = 0;
 
     auto issue = [&](int slot) {
         const bool live = nx_left > 0;
 #pragma unroll
-        for (int r = 0; r < R; ++r) wq[slot][r] = load16(wres, live ? woff[r] : kOutOfRange, nx_w);
+        for (int r = 0; r < R; ++r) {
+            wq[slot][r][0] = load16(wres, live ? woff[r] : kOutOfRange, nx_w);
+            if constexpr (W8) wq[slot][r][1] = load16(wres, live ? woff[r] : kOutOfRange, nx_w + 16);
+        }
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
             if constexpr (kStageX) {
@@ -163,7 +169,7 @@ __global__ __launch_bounds__(max_waves(MT, R, D) * kWave) void gemm_skinny_kerne
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) sc[slot][r] = load4(sres, live ? soff[r] : kOutOfRange, nx_g);
-        nx_w += kStepK / 2;
+        nx_w += kStepBytes;
         nx_x += kStepK;
         --nx_left;
         if (SPG1) {
@@ -183,6 +189,7 @@ __global__ __launch_bounds__(max_waves(MT, R, D) * kWave) void gemm_skinny_kerne
 #pragma unroll
         for (int t = 0; t < MT; ++t) part[r][t] = v4i{0, 0, 0, 0};
     int cur_sub = 0;
+    constexpr int kShift = W8 ? 0 : 4;  // the int4 unpack leaves 16 * P
 
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
@@ -191,11 +198,16 @@ __global__ __launch_bounds__(max_waves(MT, R, D) * kWave) void gemm_skinny_kerne
             v4i w_even[R], w_odd[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
+                if constexpr (W8) {
+                    w_even[r] = wq[d][r][0];  // ("even" / "odd" read "first" / "second half" for int8 weights)
+                    w_odd[r] = wq[d][r][W8 ? 1 : 0];
+                } else {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const uint32_t p = (uint32_t)wq[d][r][i];
-                    w_even[r][i] = (int)((p << 4) & 0xF0F0F0F0u);
-                    w_odd[r][i] = (int)(p & 0xF0F0F0F0u);
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t p = (uint32_t)wq[d][r][0][i];
+                        w_even[r][i] = (int)((p << 4) & 0xF0F0F0F0u);
+                        w_odd[r][i] = (int)(p & 0xF0F0F0F0u);
+                    }
                 }
             }
             v4i x_even[MT], x_odd[MT];
@@ -212,6 +224,11 @@ __global__ __launch_bounds__(max_waves(MT, R, D) * kWave) void gemm_skinny_kerne
                 } else {
                     x0 = xa[d][t][0];
                     x1 = xa[d][t][1];
+                }
+                if constexpr (W8) {
+                    x_even[t] = x0;
+                    x_odd[t] = x1;
+                    continue;
                 }
                 x_even[t][0] = pick_even(x0[0], x0[1]);
                 x_even[t][1] = pick_even(x0[2], x0[3]);
@@ -243,7 +260,8 @@ __global__ __launch_bounds__(max_waves(MT, R, D) * kWave) void gemm_skinny_kerne
                 if constexpr (INT_SCALE) {
                     // v_mad_i32_i24 multiplies exactly when both factors fit 24 bits (|P| <= 2^18 always does);
                     // scales wider than that take the full 32-bit multiply.  Both are exact modulo 2^32.
-                    bool wide = false;
+                    // (a group's partial sum itself outgrows 24 bits from 8192 int4 or 512 int8 weights on)
+                    bool wide = a.group > (W8 ? 256 : 4096);
 #pragma unroll
                     for (int r = 0; r < R; ++r) wide |= ((uint32_t)(scl[r] + (1 << 23)) >> 24) != 0;
                     if (__builtin_expect(__any(wide), 0)) {
@@ -252,20 +270,20 @@ __global__ __launch_bounds__(max_waves(MT, R, D) * kWave) void gemm_skinny_kerne
 #pragma unroll
                             for (int t = 0; t < MT; ++t)
 #pragma unroll
-                                for (int j = 0; j < 4; ++j) acc[r][t][j] += (part[r][t][j] >> 4) * scl[r];
+                                for (int j = 0; j < 4; ++j) acc[r][t][j] += (part[r][t][j] >> kShift) * scl[r];
                     } else {
 #pragma unroll
                         for (int r = 0; r < R; ++r)
 #pragma unroll
                             for (int t = 0; t < MT; ++t)
 #pragma unroll
-                                for (int j = 0; j < 4; ++j) acc[r][t][j] += __mul24(part[r][t][j] >> 4, scl[r]);
+                                for (int j = 0; j < 4; ++j) acc[r][t][j] += __mul24(part[r][t][j] >> kShift, scl[r]);
                     }
                 } else {
 #pragma unroll
                     for (int r = 0; r < R; ++r) {
                         // 16*P * (s/16): the power-of-two factor is exact, so this is float(P) * s
-                        const float fsc = __int_as_float(scl[r]) * 0.0625f;
+                        const float fsc = __int_as_float(scl[r]) * (W8 ? 1.0f : 0.0625f);
 #pragma unroll
                         for (int t = 0; t < MT; ++t)
 #pragma unroll
@@ -367,10 +385,11 @@ SkinnyConfig choose_config(const GemmArgs& a) {
     c.d = (c.mt >= 3 || c.mt * c.r >= 8) ? 2 : 4;
     c.d = env_int("INTSCALE_SKINNY_D", c.d);
     if (c.d != 2 && c.d != 4) c.d = 2;
+    if (a.w_bits == 8) c.d = 2;
     const long long tiles = (long long)((a.N + 16 * c.r - 1) / (16 * c.r)) * m_chunks;
     int nw = 1;
     // LDS: nwaves * R * MT KB for the reduction, at most 64 KB.
-    const int cap = max_waves(c.mt, c.r, c.d);
+    const int cap = max_waves(c.mt, c.r, c.d, a.w_bits == 8);
     while (nw * 2 <= cap && nw * 2 <= NG && tiles * nw < 4096) nw *= 2;
     nw = env_int("INTSCALE_SKINNY_WAVES", nw);
     if (nw < 1) nw = 1;
@@ -379,14 +398,14 @@ SkinnyConfig choose_config(const GemmArgs& a) {
     return c;
 }
 
-template <int MT, int R, int D, bool INT_SCALE>
+template <int MT, int R, int D, bool INT_SCALE, bool W8 = false>
 hipError_t launch_one(const GemmArgs& a, const SkinnyConfig& c, hipStream_t stream) {
     const int experts = a.row_offsets ? a.num_experts : 1;
     dim3 grid((a.N + 16 * R - 1) / (16 * R), (a.M + 16 * MT - 1) / (16 * MT), experts);
     // reduction slots, then (48 or 64 token rows) one step of activations per wave
     const size_t smem = (size_t)c.nwaves * R * MT * kWave * sizeof(v4i) + (MT >= 3 ? (size_t)c.nwaves * MT * 2048 : 0);
-    auto k1 = gemm_skinny_kernel<MT, R, D, INT_SCALE, true>;
-    auto k2 = gemm_skinny_kernel<MT, R, D, INT_SCALE, false>;
+    auto k1 = gemm_skinny_kernel<MT, R, D, INT_SCALE, true, W8>;
+    auto k2 = gemm_skinny_kernel<MT, R, D, INT_SCALE, false, W8>;
     if (smem > 64 * 1024) {
         static bool raised = false;  // per instantiation
         if (!raised) {
@@ -406,6 +425,13 @@ hipError_t launch_one(const GemmArgs& a, const SkinnyConfig& c, hipStream_t stre
 
 template <int MT, bool INT_SCALE>
 hipError_t launch_mt(const GemmArgs& a, const SkinnyConfig& c, hipStream_t stream) {
+    if (a.w_bits == 8) {  // int8 weights: two steps in flight (a step's weights take twice the registers)
+        switch (c.r) {
+            case 1: return launch_one<MT, 1, 2, INT_SCALE, true>(a, c, stream);
+            case 2: return launch_one<MT, 2, 2, INT_SCALE, true>(a, c, stream);
+            default: return launch_one<MT, 4, 2, INT_SCALE, true>(a, c, stream);
+        }
+    }
     if (c.d == 2) {
         switch (c.r) {
             case 1: return launch_one<MT, 1, 2, INT_SCALE>(a, c, stream);

@@ -18,7 +18,7 @@ constexpr int kWave = 64;
 struct GemmArgs {
     const int8_t* xq;           // [M,K]
     const float* a_scale;       // [M]
-    const uint8_t* qweight;     // [E,N,K/2]
+    const uint8_t* qweight;     // [E,N,K/2] int4 pairs, or [E,N,K] int8 codes when w_bits = 8
     const void* scale;          // int32 or float [E,N,NG]
     const float* chan_scale;    // [E,N] or nullptr
     const int32_t* row_offsets; // [E+1] or nullptr (plain GEMM)
@@ -27,6 +27,7 @@ struct GemmArgs {
     int M, N, K, group;
     int alpha_log2;
     int num_experts;
+    int w_bits;                 // 4 (W4A8) or 8 (fine-grained W8A8)
 };
 
 // Work split of the decode kernel (filled by its launcher).

@@ -214,6 +214,21 @@ def test_coarse_grained_tiled_kernel(P, M, N, K):
     check_fs(host(P.is_gemm_w4a8_floatscale(dev(xq), dev(sa), dev(O.pack_int4(q)), dev(s), K)), fs)
 
 
+def test_group_sums_beyond_24_bits(P, kernel):
+    """One group of 8192 int4 weights with the extreme codes: the partial sum is 2^23, one more than the signed 24-bit
+    multiplier holds, so the scale step must take the 32-bit multiply whatever the scale."""
+    M, N, K = 2, 16, 8192
+    xq = np.full((M, K), -128, np.int8)
+    q = np.full((N, K), -8, np.int8)
+    IS = np.full((N, 1), 3, np.int32)
+    sa = np.ones(M, np.float32)
+    ref = O.gemm_w4a8_intscale(xq, sa, O.pack_int4(q), IS, None, K, 10)
+    assert int(ref.acc64[0, 0]) == 3 * 2 ** 23
+    out, acc = P.is_gemm_w4a8_intscale(dev(xq), dev(sa), dev(O.pack_int4(q)), dev(IS), None, K, 10, want_acc=True)
+    assert np.array_equal(host(acc), ref.acc)
+    check_out(host(out), ref.out)
+
+
 def test_gemm_empty_batch(P):
     rng = np.random.default_rng(3)
     xq, qw, IS, s, sa, c = rand_quantised(rng, 1, 16, 128)
@@ -252,8 +267,17 @@ def test_w8_weight_quantizer_bit_exact(P, N, K, group, alpha, mode):
 
 @pytest.mark.parametrize("M,N,K,group", [(1, 16, 128, 128), (8, 512, 1024, 128), (16, 272, 1024, 128), (64, 48, 2048, 128),
                                          (65, 256, 128, 128), (129, 300, 1024, 128), (300, 700, 1152, 128),
-                                         (200, 264, 1024, 256), (130, 80, 512, 512), (513, 257, 512, 128)])
-def test_w8a8_gemm(P, M, N, K, group):
+                                         (200, 264, 1024, 256), (130, 80, 512, 512), (513, 257, 512, 128),
+                                         (1, 4096, 14336, 128), (24, 1040, 2048, 256), (33, 100, 1024, 1024),
+                                         (48, 2064, 3584, 128)])
+@pytest.mark.parametrize("route", ["auto", "tiled"])
+def test_w8a8_gemm(P, monkeypatch, route, M, N, K, group):
+    """Up to 64 token rows the library takes the general (bandwidth-bound) kernel, above that the tiled one; "tiled"
+    sends every shape to the tiled kernel."""
+    if route == "tiled":
+        monkeypatch.setenv("INTSCALE_FORCE_KERNEL", "tiled")
+    else:
+        monkeypatch.delenv("INTSCALE_FORCE_KERNEL", raising=False)
     rng = np.random.default_rng(4000 + M + N + K)
     xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
     q = rng.integers(-128, 128, size=(N, K)).astype(np.int8)
