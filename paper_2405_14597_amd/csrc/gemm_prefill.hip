@@ -328,7 +328,11 @@ __device__ __forceinline__ void gemm_prefill_tile(const GemmArgs& a, const int8_
                 for (int r = 0; r < 4; ++r) {
                     const int pv = part[ns & 1][ms][r];
                     if constexpr (!INT_SCALE) acc[ms][ns][r] = fmaf((float)pv, s_f, acc[ms][ns][r]);  // C' += float(C_g) * s_g
-                    else if constexpr (WIDE) acc[ms][ns][r] += pv * sc_i;
+                    else if constexpr (WIDE) {
+                        int prod = pv * sc_i;
+                        asm volatile("" : "+v"(prod));  // else a 64-bit multiply-add with register pairs
+                        acc[ms][ns][r] += prod;
+                    }
                     else acc[ms][ns][r] += __mul24(pv, sc_i);                                       // C'' += C_g * s_g^INT
                 }
         };

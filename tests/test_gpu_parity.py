@@ -172,6 +172,23 @@ def test_gemm_extreme_codes_and_wide_scales(P, kernel):
         check_out(host(out), ref.out)
 
 
+@pytest.mark.parametrize("M,N,K", [(200, 300, 1024), (129, 520, 2048)])
+def test_tiled_kernel_wide_scales(P, M, N, K):
+    """More than 64 token rows with integer scales beyond 24 bits (and extreme codes): the tiled kernel's 32-bit
+    multiply instance, bit-exact modulo 2^32."""
+    rng = np.random.default_rng(77 + M)
+    xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+    q = rng.integers(-8, 8, size=(N, K)).astype(np.int8)
+    xq[0], xq[1], q[0], q[1] = -128, 127, -8, 7
+    sa = rng.random(M).astype(np.float32)
+    for IS in (rng.integers(-2 ** 31, 2 ** 31, size=(N, K // G), dtype=np.int64).astype(np.int32),
+               np.where(rng.random((N, K // G)) < 0.01, 2 ** 24, 5).astype(np.int32)):
+        ref = O.gemm_w4a8_intscale(xq, sa, O.pack_int4(q), IS, None, G, 10)
+        out, acc = P.is_gemm_w4a8_intscale(dev(xq), dev(sa), dev(O.pack_int4(q)), dev(IS), None, G, 10, want_acc=True)
+        assert np.array_equal(host(acc), ref.acc)
+        check_out(host(out), ref.out)
+
+
 @pytest.mark.parametrize("group", [256, 512, 1024])
 def test_gemm_wider_groups_and_coarse_grained(P, kernel, group):
     """group = K is the coarse-grained GEMM (Table 2, first column)."""
