@@ -368,3 +368,70 @@ def gemm_w8a8_floatscale(xq, a_scale, q8, scale_f32, group: int) -> FloatScaleRe
     with np.errstate(over="ignore"):
         out16 = out.astype(np.float16)
     return FloatScaleResult(out, out16, mag)
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Activation quantisation folded into the operator that produces the activation ("kernel fusion", Sec. 4.3 and
+# Sec. 5.2): the result is DEFINED as the unfused pipeline, producer -> fp16 tensor -> Appendix A.1 quantiser,
+# so that fusing changes no code.  The producers are written as a fixed sequence of separately rounded
+# single-precision operations (stated in each docstring), because their fp16 result decides integer codes.
+# ---------------------------------------------------------------------------------------------------------
+def rmsnorm_fp16(x: np.ndarray, gamma: np.ndarray, eps: float) -> np.ndarray:
+    """RMSNorm of fp16 rows: y = fp16( (x * r) * gamma ), r = 1 / sqrt(mean(x^2) + eps).
+
+    Sum of squares in double (every fp16 square is exact there), mean rounded once to single, then single
+    precision: add eps, square root, reciprocal, the two products in the order written, one rounding to fp16.
+    """
+    x16 = np.asarray(x, dtype=np.float16)
+    g32 = np.asarray(gamma, dtype=np.float16).astype(np.float32)
+    M, K = x16.shape
+    ss = np.zeros((M,), dtype=np.float64)
+    x64 = x16.astype(np.float64)
+    for m in range(M):
+        ss[m] = np.sum(x64[m] * x64[m])
+    mean = (ss / np.float64(K)).astype(np.float32)
+    r = np.float32(1.0) / np.sqrt(mean + np.float32(eps), dtype=np.float32)
+    x32 = x16.astype(np.float32)
+    y = (x32 * r[:, None]) * g32[None, :]
+    return y.astype(np.float16)
+
+
+def rmsnorm_quantize_act_int8_token(x: np.ndarray, gamma: np.ndarray, eps: float):
+    """RMSNorm, then Appendix A.1 (n = 8) per token row on its fp16 output. Returns (xq, a_scale)."""
+    return quantize_act_int8_token(rmsnorm_fp16(x, gamma, eps))
+
+
+def exp_f32(t: np.ndarray) -> np.ndarray:
+    """e^t in single precision by a stated sequence of separately rounded operations.
+
+    t is clamped to [-87, 88]; n = rint(t * log2(e)); r = (t - n * ln2_hi) - n * ln2_lo; the degree-6 Taylor
+    polynomial of e^r in Horner form (multiply, then add, each rounded); the result is scaled by 2^n exactly.
+    """
+    f = np.float32
+    t = np.minimum(np.maximum(np.asarray(t, dtype=np.float32), f(-87.0)), f(88.0))
+    n = np.rint(t * f(1.4426950408889634))
+    r = (t - n * f(0.693145751953125)) - n * f(1.428606765330187e-06)
+    p = f(1.0 / 720.0)
+    for c in (1.0 / 120.0, 1.0 / 24.0, 1.0 / 6.0, 0.5, 1.0, 1.0):
+        p = p * r + f(c)
+    return np.ldexp(p, n.astype(np.int32)).astype(np.float32)
+
+
+def silu_f32(g: np.ndarray) -> np.ndarray:
+    """SiLU(g) = g / (1 + e^-g) in single precision: exp_f32, one addition, one division."""
+    g = np.asarray(g, dtype=np.float32)
+    return g / (np.float32(1.0) + exp_f32(-g))
+
+
+def silu_mul_fp16(gate_up: np.ndarray) -> np.ndarray:
+    """h = fp16( SiLU(gate) * up ) for gate_up = [gate | up] along the last axis (fp16 [M, 2I] -> fp16 [M, I])."""
+    gu = np.asarray(gate_up, dtype=np.float16).astype(np.float32)
+    inter = gu.shape[1] // 2
+    if gu.shape[1] != 2 * inter:
+        raise ValueError("oracle silu_mul: the last axis must hold gate and up halves of equal length")
+    return (silu_f32(gu[:, :inter]) * gu[:, inter:]).astype(np.float16)
+
+
+def silu_mul_quantize_act_int8_token(gate_up: np.ndarray):
+    """SiLU(gate) * up, then Appendix A.1 (n = 8) per token row on its fp16 output. Returns (xq, a_scale)."""
+    return quantize_act_int8_token(silu_mul_fp16(gate_up))
