@@ -46,7 +46,7 @@ def parse_args():
     ap.add_argument("--no-floatscale", action="store_true", help="skip the float-scale comparison pass")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-sample-layers", type=int, default=32)
-    ap.add_argument("--workload", choices=("decode", "prefill", "moe", "w8a8"), default="decode")
+    ap.add_argument("--workload", choices=("decode", "prefill", "moe", "w8a8", "producers"), default="decode")
     return ap.parse_args()
 
 
@@ -130,6 +130,8 @@ def main():
         return w8a8_main(args)
     if args.workload == "moe":
         return moe_main(args)
+    if args.workload == "producers":
+        return producers_main(args)
 
     import numpy as np
     import torch
@@ -656,6 +658,118 @@ def w8a8_main(args):
         "speedup_vs_floatscale": None if speedup is None else round(speedup, 4),
         "floatscale_over_intscale_by_shape": fs_detail, "roofline": roofline, "measured_peaks": peaks, "cpu_baseline": cpu,
         "shapes": shapes,
+    }
+    print(json.dumps(line))
+
+
+def producers_main(args):
+    """The activation quantiser folded into its producer, on LLaMA-3-8B shapes: RMSNorm + quantiser on [M, 4096]
+    (in front of qkv and gate_up) and SiLU(gate) * up + quantiser on [M, 2 * 14336] (in front of down), at M = 4096
+    (HBM bound; `value`) and M in {1, 16, 64} (latency bound; `shapes`).  Inputs rotate over enough buffers that each
+    call reads from HBM.  One step = both calls at every M.  The library's plain quantiser on the same output shapes is
+    timed beside them: the unfused chain costs at least that plus the producer's own pass."""
+    import numpy as np
+    import torch
+
+    import paper_2405_14597_amd as P
+    import synth_inputs as S
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    P.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K = S.LLAMA3_8B["qkv"][0]
+    inter = S.LLAMA3_8B["down"][0]
+    MS = (1, 16, 64, 4096)
+    eps = 1e-5
+    gamma = torch.from_numpy((1.0 + 0.1 * np.random.default_rng(1).standard_normal(K)).astype(np.float16)).to(dev)
+    bufs = {}
+    for M in MS:
+        copies_x = max(2, min(16, (768 << 20) // (2 * M * K)))
+        copies_g = max(2, min(16, (768 << 20) // (4 * M * inter)))
+        x = torch.from_numpy(S.make_activations(3, M, K, S.seed_for(3, 0, 2) + M)).to(dev)
+        g = torch.from_numpy(S.make_activations(3, M, 2 * inter, S.seed_for(3, 2, 3) + M)).to(dev)
+        bufs[M] = dict(x=[x.clone() for _ in range(copies_x)], gu=[g.clone() for _ in range(copies_g)],
+                       h=g[:, :inter].contiguous(),
+                       xq=torch.empty((M, K), dtype=torch.int8, device=dev),
+                       hq=torch.empty((M, inter), dtype=torch.int8, device=dev),
+                       sa=torch.empty((M,), dtype=torch.float32, device=dev))
+    torch.cuda.synchronize()
+
+    def run(steps, warmup, fused=True):
+        ev = {(M, k): [] for M in MS for k in ("norm", "silu")}
+        for it in range(warmup + steps):
+            if it == warmup:
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+            for M in MS:
+                b = bufs[M]
+                for k in ("norm", "silu"):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    if k == "norm":
+                        src = b["x"][it % len(b["x"])]
+                        if fused:
+                            P.is_rmsnorm_quantize_act_int8_token(src, gamma, eps, b["xq"], b["sa"])
+                        else:
+                            P.is_quantize_act_int8_token(src, b["xq"], b["sa"])
+                    else:
+                        if fused:
+                            P.is_silu_mul_quantize_act_int8_token(b["gu"][it % len(b["gu"])], b["hq"], b["sa"])
+                        else:
+                            P.is_quantize_act_int8_token(b["h"], b["hq"], b["sa"])
+                    e1.record()
+                    if it >= warmup:
+                        ev[(M, k)].append((e0, e1))
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / steps
+        return sec, {key: 1e3 * sum(x.elapsed_time(y) for x, y in v) / len(v) for key, v in ev.items()}
+
+    def alg_bytes(M, k):  # fp16 in, int8 out, one float per row (and gamma once)
+        return 3 * M * K + 2 * K + 4 * M if k == "norm" else 5 * M * inter + 4 * M
+
+    sec, per = run(args.steps, args.warmup)
+    _, per_q = run(max(3, args.steps // 2), 2, fused=False)
+    big = 4096
+    value = sum(alg_bytes(big, k) for k in ("norm", "silu")) / (per[(big, "norm")] + per[(big, "silu")]) / 1e3
+    shapes = [dict(name=f"{k}_quant_M{M}", us=round(per[(M, k)], 2), gbs=round(alg_bytes(M, k) / per[(M, k)] / 1e3, 1),
+                   plain_quantiser_us=round(per_q[(M, k)], 2)) for M in MS for k in ("norm", "silu")]
+    dom = max(("norm", "silu"), key=lambda k: per[(big, k)])
+    ach = alg_bytes(big, dom) / per[(big, dom)] / 1e3
+    kern = "silu_mul_quantize_resident_kernel<8>" if dom == "silu" else "rmsnorm_quantize_resident_kernel<2>"
+    roofline = dict(bound="hbm", kernel=kern, achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(ach / HBM_PEAK_GBS, 4), traffic=None, avg_launch_us=round(per[(big, dom)], 2))
+    peaks = measured_peaks(P, torch)
+    roofline["frac_of_measured_peak"] = round(ach / peaks["hbm_read_gbs"], 4)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        M = 1024
+        hx = S.make_activations(3, M, K, S.seed_for(3, 0, 2) + M)
+        hg = S.make_activations(3, M, 2 * inter, S.seed_for(3, 2, 3) + M)
+        hgamma = gamma.cpu().numpy()
+        t0 = time.perf_counter()
+        rq, rs = O.rmsnorm_quantize_act_int8_token(hx, hgamma, eps)
+        sq, ss = O.silu_mul_quantize_act_int8_token(hg)
+        dt = time.perf_counter() - t0
+        gq, gs = P.is_rmsnorm_quantize_act_int8_token(torch.from_numpy(hx).to(dev), gamma, eps)
+        tq, ts = P.is_silu_mul_quantize_act_int8_token(torch.from_numpy(hg).to(dev))
+        torch.cuda.synchronize()
+        cpu = dict(value=round((alg_bytes(M, "norm") + alg_bytes(M, "silu")) / dt / 1e9, 3), unit="GB/s", cores=1,
+                   kind="oracle", sample=f"both calls once at M = {M} (numpy), {dt:.1f} s",
+                   parity=dict(norm_codes_bit_exact=bool(np.array_equal(gq.cpu().numpy(), rq)),
+                               norm_scales_bit_exact=bool(np.array_equal(gs.cpu().numpy(), rs)),
+                               silu_codes_bit_exact=bool(np.array_equal(tq.cpu().numpy(), sq)),
+                               silu_scales_bit_exact=bool(np.array_equal(ts.cpu().numpy(), ss))))
+    line = {
+        "metric": "activation quantiser folded into its producer: HBM GB/s (% roofline)", "value": round(value, 1),
+        "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(1e3 * sec, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"llama3-8b producers: RMSNorm+quant on [M,{K}], SiLU*up+quant on [M,2*{inter}], "
+                               f"M in {list(MS)}; value = the M = {big} pair", "launch": "eager"},
+        "roofline": roofline, "measured_peaks": peaks, "cpu_baseline": cpu, "shapes": shapes,
     }
     print(json.dumps(line))
 

@@ -71,6 +71,31 @@ int is_quantize_weights_int4_group(const void* w_fp16, int N, int K, int group, 
 int is_quantize_act_int8_token(const void* x_fp16, int M, int K, int8_t* xq, float* a_scale, void* stream);
 
 /*
+ * The activation quantiser folded into the operator that produces the activation (the kernel fusion of Sec. 4.3 and
+ * Sec. 5.2).  Each call returns exactly what its producer, an fp16 tensor and is_quantize_act_int8_token would,
+ * without the fp16 tensor's trip through memory.  The producer's arithmetic is a fixed sequence of separately
+ * rounded single-precision operations, because its fp16 value decides integer codes:
+ *
+ * RMSNorm:  y[m,k] = fp16( (x[m,k] * r[m]) * gamma[k] ),  r[m] = 1 / sqrt( float(sum_k x[m,k]^2 / K) + eps ),
+ *           the sum of squares taken in double precision.
+ *   x_fp16 in fp16 [M,K], K a multiple of 8;  gamma_fp16 in fp16 [K];  eps > 0 and finite;
+ *   xq out int8 [M,K];  a_scale out float [M].
+ *
+ * SiLU * up:  h[m,i] = fp16( (g / (1 + e)) * u ),  g = gate_up[m,i], u = gate_up[m,inter+i], e = exp(-g) computed as
+ *           t = clamp(-g, -87, 88), n = rint(t * log2 e), r = (t - n * 0.693145751953125) - n * 1.428606765330187e-06,
+ *           the degree-6 Taylor polynomial of e^r by Horner's rule, times 2^n.
+ *   gate_up_fp16 in fp16 [M, 2*inter] (gate half, then up half, of every row), inter a multiple of 8;
+ *   xq out int8 [M,inter];  a_scale out float [M].
+ *
+ * M = 0 is a no-op.  A row whose products are all zero gets s_a = 0 and codes 0.  Inputs must be finite and the
+ * fp16 results must not overflow.
+ */
+int is_rmsnorm_quantize_act_int8_token(const void* x_fp16, const void* gamma_fp16, float eps, int M, int K,
+                                       int8_t* xq, float* a_scale, void* stream);
+int is_silu_mul_quantize_act_int8_token(const void* gate_up_fp16, int M, int inter, int8_t* xq, float* a_scale,
+                                        void* stream);
+
+/*
  * Fine-grained W4A8 GEMM with integer scales (Eq. (2); Table 2 "Ours"):
  *   P[m,n,g] = sum_{k in group g} xq[m,k] * q[n,k]                    int32, exact
  *   acc[m,n] = sum_g P[m,n,g] * scale_i32[n,g]                        int32, wraps modulo 2^32

@@ -24,6 +24,8 @@ IS_ALPHA_HEURISTIC = -1
 EXPORTED_SYMBOLS = (
     "is_quantize_weights_int4_group",
     "is_quantize_act_int8_token",
+    "is_rmsnorm_quantize_act_int8_token",
+    "is_silu_mul_quantize_act_int8_token",
     "is_gemm_w4a8_intscale",
     "is_gemm_w4a8_floatscale",
     "is_gemm_workspace_bytes",
@@ -76,6 +78,10 @@ def load_library() -> ctypes.CDLL:
     lib.is_quantize_weights_int4_group.restype = ci
     lib.is_quantize_act_int8_token.argtypes = [vp, ci, ci, vp, vp, vp]
     lib.is_quantize_act_int8_token.restype = ci
+    lib.is_rmsnorm_quantize_act_int8_token.argtypes = [vp, vp, ctypes.c_float, ci, ci, vp, vp, vp]
+    lib.is_rmsnorm_quantize_act_int8_token.restype = ci
+    lib.is_silu_mul_quantize_act_int8_token.argtypes = [vp, ci, ci, vp, vp, vp]
+    lib.is_silu_mul_quantize_act_int8_token.restype = ci
     lib.is_gemm_w4a8_intscale.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
     lib.is_gemm_w4a8_intscale.restype = ci
     lib.is_gemm_w4a8_floatscale.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, vp, vp, sz, vp]
@@ -190,6 +196,40 @@ def is_quantize_act_int8_token(x, xq=None, a_scale=None, stream=None):
     _require(a_scale, torch.float32, (M,), "a_scale")
     st = load_library().is_quantize_act_int8_token(_p(x), M, K, _p(xq), _p(a_scale), _stream_handle(stream))
     _check("is_quantize_act_int8_token", st)
+    return xq, a_scale
+
+
+def is_rmsnorm_quantize_act_int8_token(x, gamma, eps: float, xq=None, a_scale=None, stream=None):
+    torch = _torch()
+    M, K = x.shape
+    _require(x, torch.float16, (M, K), "x")
+    _require(gamma, torch.float16, (K,), "gamma")
+    if xq is None:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    if a_scale is None:
+        a_scale = torch.empty((M,), dtype=torch.float32, device=x.device)
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    st = load_library().is_rmsnorm_quantize_act_int8_token(_p(x), _p(gamma), float(eps), M, K, _p(xq), _p(a_scale),
+                                                           _stream_handle(stream))
+    _check("is_rmsnorm_quantize_act_int8_token", st)
+    return xq, a_scale
+
+
+def is_silu_mul_quantize_act_int8_token(gate_up, xq=None, a_scale=None, stream=None):
+    torch = _torch()
+    M, two_inter = gate_up.shape
+    inter = two_inter // 2
+    _require(gate_up, torch.float16, (M, 2 * inter), "gate_up")
+    if xq is None:
+        xq = torch.empty((M, inter), dtype=torch.int8, device=gate_up.device)
+    if a_scale is None:
+        a_scale = torch.empty((M,), dtype=torch.float32, device=gate_up.device)
+    _require(xq, torch.int8, (M, inter), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    st = load_library().is_silu_mul_quantize_act_int8_token(_p(gate_up), M, inter, _p(xq), _p(a_scale),
+                                                            _stream_handle(stream))
+    _check("is_silu_mul_quantize_act_int8_token", st)
     return xq, a_scale
 
 

@@ -10,7 +10,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.environ.get("INTSCALE_LIBRARY", os.path.join(PKG_DIR, "libintscale.so"))
 
-SOURCES = ["api.hip", "quantize.hip", "gemm_skinny.hip", "gemm_decode.hip", "gemm_prefill.hip", "gemm_tile_w8.hip", "overflow.hip", "probe.hip"]
+SOURCES = ["api.hip", "quantize.hip", "act_producers.hip", "gemm_skinny.hip", "gemm_decode.hip", "gemm_prefill.hip", "gemm_tile_w8.hip", "overflow.hip", "probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
@@ -28,7 +28,8 @@ def needs_build() -> bool:
     if not os.path.exists(LIB_PATH):
         return True
     t = os.path.getmtime(LIB_PATH)
-    deps = sources() + [os.path.join(CSRC, "is_common.h"), os.path.join(INCLUDE, "intscale.h")]
+    deps = sources() + [os.path.join(CSRC, "is_common.h"), os.path.join(CSRC, "act_common.h"),
+                        os.path.join(CSRC, "tile_common.h"), os.path.join(INCLUDE, "intscale.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

@@ -1,0 +1,68 @@
+// Device helpers shared by the activation quantiser and by the kernels that fold it into the operator producing the
+// activation: wave and workgroup reductions, and Appendix A.1's code for eight fp16 values at a time.  The quotient
+// x / s is a true IEEE fp32 division and rounding is round-half-to-even, because they decide the integer code.
+#pragma once
+#include "is_common.h"
+
+namespace intscale {
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+__device__ __forceinline__ float absmax8(uint4 v) {
+    const __half2* h = reinterpret_cast<const __half2*>(&v);
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float2 f = __half22float2(h[i]);
+        m = fmaxf(m, fmaxf(fabsf(f.x), fabsf(f.y)));
+    }
+    return m;
+}
+
+__device__ __forceinline__ int quant_code(float x, float s, float lo, float hi) {
+    // s > 0 is checked by the caller
+    float r = rintf(x / s);
+    r = fminf(fmaxf(r, lo), hi);
+    return (int)r;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Activations: one workgroup per token row.  Pass 1 finds the row's absmax (16-byte loads), pass 2 re-reads the
+// row (it is at most a few tens of KB, so it comes back from L2) and writes 8 codes per lane as one 8-byte store.
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kActThreads = 256;
+
+__device__ __forceinline__ uint2 quantize8(uint4 v, float s) {
+    const __half2* h = reinterpret_cast<const __half2*>(&v);
+    uint32_t packed[2] = {0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float2 f = __half22float2(h[i]);
+        int q0 = 0, q1 = 0;
+        if (s > 0.0f) {
+            q0 = quant_code(f.x, s, -128.0f, 127.0f);
+            q1 = quant_code(f.y, s, -128.0f, 127.0f);
+        }
+        uint32_t two = ((uint32_t)q0 & 0xFFu) | (((uint32_t)q1 & 0xFFu) << 8);
+        packed[i >> 1] |= two << ((i & 1) * 16);
+    }
+    return make_uint2(packed[0], packed[1]);
+}
+
+// NW = waves in the workgroup; `red` holds NW floats
+template <int NW = kActThreads / kWave>
+__device__ __forceinline__ float block_max(float v, float* red) {
+    v = wave_max(v);
+    if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x / kWave] = v;
+    __syncthreads();
+    v = red[0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) v = fmaxf(v, red[i]);
+    return v;
+}
+
+}  // namespace intscale

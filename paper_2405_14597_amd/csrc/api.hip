@@ -122,6 +122,28 @@ int is_quantize_act_int8_token(const void* x_fp16, int M, int K, int8_t* xq, flo
                                           static_cast<hipStream_t>(stream)));
 }
 
+int is_rmsnorm_quantize_act_int8_token(const void* x_fp16, const void* gamma_fp16, float eps, int M, int K,
+                                       int8_t* xq, float* a_scale, void* stream) {
+    if (M < 0 || K <= 0 || (K & 7) || !(eps > 0.0f) || !(eps < INFINITY)) return IS_ERR_INVALID_ARG;
+    if (M == 0) return IS_OK;
+    if (!ok_ptr(x_fp16) || !ok_ptr(gamma_fp16) || !ok_ptr(xq) || a_scale == nullptr ||
+        (reinterpret_cast<uintptr_t>(a_scale) & 3u))
+        return IS_ERR_INVALID_ARG;
+    return hip_status(launch_rmsnorm_quantize_act(static_cast<const __half*>(x_fp16),
+                                                  static_cast<const __half*>(gamma_fp16), eps, M, K, xq, a_scale,
+                                                  static_cast<hipStream_t>(stream)));
+}
+
+int is_silu_mul_quantize_act_int8_token(const void* gate_up_fp16, int M, int inter, int8_t* xq, float* a_scale,
+                                        void* stream) {
+    if (M < 0 || inter <= 0 || (inter & 7) || inter > (1 << 29)) return IS_ERR_INVALID_ARG;
+    if (M == 0) return IS_OK;
+    if (!ok_ptr(gate_up_fp16) || !ok_ptr(xq) || a_scale == nullptr || (reinterpret_cast<uintptr_t>(a_scale) & 3u))
+        return IS_ERR_INVALID_ARG;
+    return hip_status(launch_silu_mul_quantize_act(static_cast<const __half*>(gate_up_fp16), M, inter, xq, a_scale,
+                                                   static_cast<hipStream_t>(stream)));
+}
+
 size_t is_gemm_workspace_bytes(int M, int N, int K, int group) {
     if (check_gemm_shape(M, N, K, group) != IS_OK) return 0;
     // decode-sized problems reduce in LDS and need nothing; the tiled kernel keeps its zero-point corrections, a

@@ -38,7 +38,6 @@ constexpr int kStepK = 128;
 constexpr int kBM = kTileRows;
 constexpr int kBN = 256;
 constexpr int kThreads = 512;
-constexpr int kWaves = kThreads / kWave;
 constexpr int kXcds = 8;    // workgroup i is dispatched to XCD i % 8
 constexpr int kGroupM = 8;  // tile rows of the block of tiles an XCD works on at a time
 constexpr int kStages = 4;  // LDS ring; tiles are requested kStages - 1 steps ahead

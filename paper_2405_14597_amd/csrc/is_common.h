@@ -42,6 +42,10 @@ struct DecodePlan {
 
 // Launchers (defined next to their kernels). Each returns a hipError_t from the launch.
 hipError_t launch_quantize_act(const __half* x, int M, int K, int8_t* xq, float* a_scale, hipStream_t stream);
+hipError_t launch_rmsnorm_quantize_act(const __half* x, const __half* gamma, float eps, int M, int K, int8_t* xq,
+                                       float* a_scale, hipStream_t stream);
+hipError_t launch_silu_mul_quantize_act(const __half* gate_up, int M, int inter, int8_t* xq, float* a_scale,
+                                        hipStream_t stream);
 hipError_t launch_quantize_weights(const __half* w, int N, int K, int group, int alpha_log2, int scale_mode,
                                    uint8_t* qweight, float* scale_f32, int32_t* scale_i32, float* chan_scale,
                                    int* alpha_log2_dev, hipStream_t stream, int bits = 4);  // bits: 4 or 8 (one byte per code)

@@ -107,6 +107,23 @@ def test_quantizer_argument_validation():
     assert x(M=0) == P.IS_OK
 
 
+def test_fused_producer_argument_validation():
+    lib = P.load_library()
+    bad = P.IS_ERR_INVALID_ARG
+    n = lambda **kw: lib.is_rmsnorm_quantize_act_int8_token(kw.get("x", A), kw.get("g", A), kw.get("eps", 1e-5),
+                                                            kw.get("M", 4), kw.get("K", 256), kw.get("xq", A),
+                                                            kw.get("sa", A), None)
+    assert n(x=None) == bad and n(g=None) == bad and n(xq=None) == bad and n(sa=None) == bad and n(sa=A + 2) == bad
+    assert n(K=100) == bad and n(K=0) == bad and n(M=-1) == bad
+    assert n(eps=0.0) == bad and n(eps=-1e-5) == bad and n(eps=float("inf")) == bad and n(eps=float("nan")) == bad
+    assert n(M=0) == P.IS_OK
+    s = lambda **kw: lib.is_silu_mul_quantize_act_int8_token(kw.get("gu", A), kw.get("M", 4), kw.get("I", 256),
+                                                             kw.get("xq", A), kw.get("sa", A), None)
+    assert s(gu=None) == bad and s(xq=None) == bad and s(sa=None) == bad
+    assert s(I=100) == bad and s(I=0) == bad and s(M=-1) == bad
+    assert s(M=0) == P.IS_OK
+
+
 def test_missing_device_is_reported_not_hidden():
     """With valid arguments the call reaches HIP; without a GPU that must surface as IS_ERR_HIP, never as success."""
     import torch

@@ -1,0 +1,120 @@
+"""GPU parity of the activation quantiser folded into its producer (RMSNorm, SiLU * up) against the CPU oracle:
+codes and token scales bit-exact, since both sides take every floating-point decision in the same precision and
+order.
+"""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from oracle import oracle as O
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2405_14597_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def _gamma(K, seed):
+    return (1.0 + 0.25 * np.random.default_rng(seed).standard_normal(K)).astype(np.float16)
+
+
+# few rows (1024 lanes per row, 1 / 2 / 4 chunks per lane), many rows (256 lanes, 2 / 8 / 16 chunks), the three-pass
+# kernel (K = 40000), one chunk, ragged last chunk slots
+@pytest.mark.parametrize("M,K,eps", [(1, 4096, 1e-5), (7, 4096, 1e-6), (33, 5120, 1e-5), (5, 8192, 1e-5),
+                                     (3, 14336, 1e-5), (2, 28672, 1e-6), (2, 40000, 1e-5), (64, 128, 1e-5),
+                                     (3, 8, 1e-5), (130, 11008, 1e-2), (260, 11008, 1e-5), (257, 28672, 1e-5), (300, 2048, 1e-5)])
+def test_rmsnorm_quantize_bit_exact(P, M, K, eps):
+    x = S.activations_outlier(M, K, 100 + K % 97).astype(np.float16)
+    if M > 2:
+        x[1] = 0                       # an all-zero token row: r = 1 / sqrt(eps), codes 0
+        x[2, K // 2] = 30000           # a large outlier
+    gamma = _gamma(K, 7)
+    gamma[0] = 0
+    xq_ref, sa_ref = O.rmsnorm_quantize_act_int8_token(x, gamma, eps)
+    xq, sa = P.is_rmsnorm_quantize_act_int8_token(dev(x), dev(gamma), eps)
+    assert np.array_equal(host(sa), sa_ref)
+    assert np.array_equal(host(xq), xq_ref)
+
+
+def test_rmsnorm_quantize_prefill_size(P):
+    M, K = 4096, 4096
+    x = S.activations_outlier(M, K, 5).astype(np.float16)
+    gamma = _gamma(K, 9)
+    xq_ref, sa_ref = O.rmsnorm_quantize_act_int8_token(x, gamma, 1e-5)
+    xq, sa = P.is_rmsnorm_quantize_act_int8_token(dev(x), dev(gamma), 1e-5)
+    assert np.array_equal(host(sa), sa_ref)
+    assert np.array_equal(host(xq), xq_ref)
+
+
+def test_rmsnorm_quantize_matches_unfused_chain(P):
+    """The fused call against the library's own quantiser fed with the oracle's fp16 norm output."""
+    M, K = 19, 4096
+    x = S.activations_student_t(M, K, 15).astype(np.float16)
+    gamma = _gamma(K, 3)
+    y = O.rmsnorm_fp16(x, gamma, 1e-5)
+    xq_u, sa_u = P.is_quantize_act_int8_token(dev(y))
+    xq, sa = P.is_rmsnorm_quantize_act_int8_token(dev(x), dev(gamma), 1e-5)
+    assert torch.equal(xq, xq_u) and torch.equal(sa, sa_u)
+
+
+def test_rmsnorm_quantize_empty_and_bad_arguments(P):
+    x = torch.empty((0, 4096), dtype=torch.float16, device="cuda:0")
+    g = torch.ones((4096,), dtype=torch.float16, device="cuda:0")
+    xq, sa = P.is_rmsnorm_quantize_act_int8_token(x, g, 1e-5)
+    assert xq.shape == (0, 4096) and sa.shape == (0,)
+    x1 = torch.ones((2, 4096), dtype=torch.float16, device="cuda:0")
+    for eps in (0.0, -1.0, float("inf"), float("nan")):
+        with pytest.raises(P.IntScaleError):
+            P.is_rmsnorm_quantize_act_int8_token(x1, g, eps)
+
+
+# few rows (1024 lanes per row), many rows (256 lanes, 2 / 8 / 16 chunks per lane), the two-pass kernel
+# (inter = 40960), one chunk, a ragged tail
+@pytest.mark.parametrize("M,inter", [(1, 11008), (8, 11008), (33, 14336), (3, 28672), (2, 40960), (64, 136),
+                                     (5, 8), (130, 4096), (260, 11008), (257, 28672), (300, 2048)])
+def test_silu_mul_quantize_bit_exact(P, M, inter):
+    rng = np.random.default_rng(200 + inter % 89)
+    gate = (3.0 * rng.standard_normal((M, inter))).astype(np.float16)
+    up = S.activations_outlier(M, inter, 300 + M).astype(np.float16)
+    up = np.clip(up, -200, 200).astype(np.float16)
+    if M > 2:
+        up[1] = 0                      # an all-zero product row
+        gate[2, :8] = [-100, 100, -20, 20, -88, 88, 0, -0.0]     # both clamps of the exponent, zeros
+    gu = np.concatenate([gate, up], axis=1)
+    xq_ref, sa_ref = O.silu_mul_quantize_act_int8_token(gu)
+    xq, sa = P.is_silu_mul_quantize_act_int8_token(dev(gu))
+    assert np.array_equal(host(sa), sa_ref)
+    assert np.array_equal(host(xq), xq_ref)
+
+
+def test_silu_mul_quantize_prefill_size(P):
+    M, inter = 2048, 14336
+    rng = np.random.default_rng(41)
+    gate = (2.0 * rng.standard_normal((M, inter))).astype(np.float16)
+    up = rng.standard_normal((M, inter)).astype(np.float16)
+    gu = np.concatenate([gate, up], axis=1)
+    xq_ref, sa_ref = O.silu_mul_quantize_act_int8_token(gu)
+    xq, sa = P.is_silu_mul_quantize_act_int8_token(dev(gu))
+    assert np.array_equal(host(sa), sa_ref)
+    assert np.array_equal(host(xq), xq_ref)
+
+
+def test_silu_mul_quantize_empty(P):
+    gu = torch.empty((0, 256), dtype=torch.float16, device="cuda:0")
+    xq, sa = P.is_silu_mul_quantize_act_int8_token(gu)
+    assert xq.shape == (0, 128) and sa.shape == (0,)
