@@ -738,9 +738,10 @@ def producers_main(args):
                    plain_quantiser_us=round(per_q[(M, k)], 2)) for M in MS for k in ("norm", "silu")]
     dom = max(("norm", "silu"), key=lambda k: per[(big, k)])
     ach = alg_bytes(big, dom) / per[(big, dom)] / 1e3
-    kern = "silu_mul_quantize_resident_kernel<8>" if dom == "silu" else "rmsnorm_quantize_resident_kernel<2>"
+    kern = "silu_mul_quantize_resident_kernel<8, 256>" if dom == "silu" else "rmsnorm_quantize_resident_kernel<2, 256>"
     roofline = dict(bound="hbm", kernel=kern, achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(ach / HBM_PEAK_GBS, 4), traffic=None, avg_launch_us=round(per[(big, dom)], 2))
+                    frac=round(ach / HBM_PEAK_GBS, 4), traffic=measured_traffic(kern, "llama3_8b_producers"),
+                    avg_launch_us=round(per[(big, dom)], 2))
     peaks = measured_peaks(P, torch)
     roofline["frac_of_measured_peak"] = round(ach / peaks["hbm_read_gbs"], 4)
     cpu = None
