@@ -16,12 +16,13 @@ __device__ __forceinline__ float wave_min(float v) {
 }
 
 // Rows of up to 2048 * CH elements: the row is read once and stays in registers (CH 16-byte chunks per lane) between
-// the absmax reduction and the rounding, so a token row costs one trip to memory, not two.
-template <int CH>
-__global__ __launch_bounds__(kActThreads) void quantize_act_resident_kernel(const __half* __restrict__ x, int M, int K,
-                                                                            int8_t* __restrict__ xq,
-                                                                            float* __restrict__ a_scale) {
-    __shared__ float red[kActThreads / kWave];
+// the absmax reduction and the rounding, so a token row costs one trip to memory, not two.  With few rows (a decode
+// step) a row is spread over up to 1024 lanes: the chip is far from full and the row's latency is what counts.
+template <int CH, int THREADS>
+__global__ __launch_bounds__(THREADS) void quantize_act_resident_kernel(const __half* __restrict__ x, int M, int K,
+                                                                        int8_t* __restrict__ xq,
+                                                                        float* __restrict__ a_scale) {
+    __shared__ float red[THREADS / kWave];
     const int m = blockIdx.x;
     const int tid = threadIdx.x;
     const int nchunk = K >> 3;
@@ -30,18 +31,18 @@ __global__ __launch_bounds__(kActThreads) void quantize_act_resident_kernel(cons
     float amax = 0.0f;
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-        const int idx = tid + c * kActThreads;
+        const int idx = tid + c * THREADS;
         v[c] = idx < nchunk ? row[idx] : make_uint4(0u, 0u, 0u, 0u);
     }
 #pragma unroll
     for (int c = 0; c < CH; ++c) amax = fmaxf(amax, absmax8(v[c]));
-    amax = block_max(amax, red);
+    amax = block_max<THREADS / kWave>(amax, red);
     const float s = amax / 127.0f;
     if (tid == 0) a_scale[m] = s;
     uint2* dst = reinterpret_cast<uint2*>(xq + (size_t)m * K);
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-        const int idx = tid + c * kActThreads;
+        const int idx = tid + c * THREADS;
         if (idx < nchunk) dst[idx] = quantize8(v[c], s);
     }
 }
@@ -178,15 +179,24 @@ __global__ __launch_bounds__(kWqThreads) void apply_searched_amplifier_kernel(co
 }  // namespace
 
 hipError_t launch_quantize_act(const __half* x, int M, int K, int8_t* xq, float* a_scale, hipStream_t stream) {
-    const int chunks_per_lane = ((K >> 3) + kActThreads - 1) / kActThreads;
-    if (chunks_per_lane <= 2)
-        hipLaunchKernelGGL(quantize_act_resident_kernel<2>, dim3(M), dim3(kActThreads), 0, stream, x, M, K, xq, a_scale);
-    else if (chunks_per_lane <= 8)
-        hipLaunchKernelGGL(quantize_act_resident_kernel<8>, dim3(M), dim3(kActThreads), 0, stream, x, M, K, xq, a_scale);
-    else if (chunks_per_lane <= 16)
-        hipLaunchKernelGGL(quantize_act_resident_kernel<16>, dim3(M), dim3(kActThreads), 0, stream, x, M, K, xq, a_scale);
+    const int nchunk = K >> 3;
+    const dim3 grid(M);
+#define ACT_LAUNCH(CH, T) \
+    hipLaunchKernelGGL((quantize_act_resident_kernel<CH, T>), grid, dim3(T), 0, stream, x, M, K, xq, a_scale)
+    if (M <= 256 && nchunk > kActThreads && nchunk <= 4096) {  // few rows: one chunk per lane where 1024 lanes reach
+        if (nchunk <= 512) ACT_LAUNCH(1, 512);
+        else if (nchunk <= 1024) ACT_LAUNCH(1, 1024);
+        else if (nchunk <= 2048) ACT_LAUNCH(2, 1024);
+        else ACT_LAUNCH(4, 1024);
+        return hipGetLastError();
+    }
+    const int chunks_per_lane = (nchunk + kActThreads - 1) / kActThreads;
+    if (chunks_per_lane <= 2) ACT_LAUNCH(2, kActThreads);
+    else if (chunks_per_lane <= 8) ACT_LAUNCH(8, kActThreads);
+    else if (chunks_per_lane <= 16) ACT_LAUNCH(16, kActThreads);
     else
-        hipLaunchKernelGGL(quantize_act_kernel, dim3(M), dim3(kActThreads), 0, stream, x, M, K, xq, a_scale);
+        hipLaunchKernelGGL(quantize_act_kernel, grid, dim3(kActThreads), 0, stream, x, M, K, xq, a_scale);
+#undef ACT_LAUNCH
     return hipGetLastError();
 }
 

@@ -77,7 +77,11 @@ def rand_quantised(rng, M, N, K, is_lo=0, is_hi=1025):
 
 # ------------------------------------------------------------------------------------------------ quantisers
 @pytest.mark.parametrize("M,K,kind", [(1, 4096, "outlier"), (8, 4096, "outlier"), (33, 11008, "outlier"),
-                                      (64, 1024, "student"), (5, 8, "outlier"), (130, 28672, "student")])
+                                      (64, 1024, "student"), (5, 8, "outlier"), (130, 28672, "student"),
+                                      # few rows spread over 512 / 1024 lanes, many rows with 2 / 8 / 16 chunks per
+                                      # lane, rows too long for registers
+                                      (20, 8192, "outlier"), (300, 4096, "outlier"), (260, 11008, "student"),
+                                      (257, 28672, "outlier"), (3, 40000, "outlier"), (300, 40000, "student")])
 def test_act_quantizer_bit_exact(P, M, K, kind):
     x = S.activations_outlier(M, K, 11) if kind == "outlier" else S.activations_student_t(M, K, 12)
     if M > 2:
