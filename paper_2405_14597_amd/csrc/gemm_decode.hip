@@ -147,7 +147,38 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
         for (int i = 0; i < XS; ++i) issue_weight_step(slot, i, tile);
         issue_chan_scale(slot, tile);
     };
-    // First requests of the stream go out before anything else that waits on memory.
+    // ---- role of this thread in the epilogue: outputs (m_out[o], tile*16 + n_out) of every tile
+    int m_out[OPT];
+    float sa_out[OPT];
+    bool writer[OPT];
+#pragma unroll
+    for (int o = 0; o < OPT; ++o) {
+        m_out[o] = (threadIdx.x + o * T) >> 4;  // 0 .. 16*MT-1 for the threads that take part
+        writer[o] = threadIdx.x + o * T < 256 * MT && m_out[o] < a.M;
+        sa_out[o] = writer[o] ? a.a_scale[m_out[o]] : 0.0f;
+    }
+
+    // Loads come back in the order they were issued.  With several tiles in flight per wave, whatever is requested
+    // after the stream's first requests arrives after all of them: the token scales above and, below, the
+    // activations go out first where the window is deep (DT >= 2), so that the first tile is multiplied and written
+    // while the others are still on their way.  (They are a few requests per lane; with one tile in flight, and the
+    // long activation slices that go with it, the stream starts first instead.)
+    constexpr bool kStageX = WAVES == 8 && MT == 4;
+    constexpr bool kXFirst = DT >= 2 && !kStageX;
+    [[maybe_unused]] v4i xr0[kXFirst ? XS : 1][kXFirst ? MT : 1], xr1[kXFirst ? XS : 1][kXFirst ? MT : 1];
+    if constexpr (kXFirst) {
+#pragma unroll
+        for (int i = 0; i < XS; ++i)
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                const int m = 16 * t + li;
+                const int off = (i < ns && m < a.M) ? m * a.K + (s0 + i) * kStepK + kb * 32 : kOutOfRange;
+                xr0[i][t] = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 0, 0);
+                xr1[i][t] = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 16, 0);
+            }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // First requests of the stream go out before anything else that waits on memory (but see above).
 #pragma unroll
     for (int u = 0; u < SD; ++u) {
         if (u < my_tiles) issue_scales(u, tile0 + u * G);
@@ -162,7 +193,6 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     // there the wave fetches 16 rows at a time the coalesced way (consecutive lanes, consecutive 16 bytes of a row's
     // XS*128-byte slice) and turns them into the operand layout through a private piece of LDS.  No barrier: LDS
     // serves one wave's requests in order.  Chunk index XOR row keeps both sides off each other's banks.
-    constexpr bool kStageX = WAVES == 8 && MT == 4;
     [[maybe_unused]] unsigned char* xstage = reinterpret_cast<unsigned char*>(lds_wide + 2 * W) + wave * (XS * 2048);
     constexpr int kChunks = XS * 8;  // 16-byte chunks of a row's slice
     [[maybe_unused]] auto fetch_rows = [&](int t, v4i (&raw)[XS * 2]) {
@@ -208,10 +238,16 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     for (int i = 0; i < XS; ++i)
 #pragma unroll
         for (int t = 0; t < (kStageX ? 0 : MT); ++t) {
-            const int m = 16 * t + li;
-            const int off = (i < ns && m < a.M) ? m * a.K + (s0 + i) * kStepK + kb * 32 : kOutOfRange;
-            const v4i x0 = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 0, 0);
-            const v4i x1 = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 16, 0);
+            v4i x0, x1;
+            if constexpr (kXFirst) {
+                x0 = xr0[i][t];
+                x1 = xr1[i][t];
+            } else {
+                const int m = 16 * t + li;
+                const int off = (i < ns && m < a.M) ? m * a.K + (s0 + i) * kStepK + kb * 32 : kOutOfRange;
+                x0 = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 0, 0);
+                x1 = __builtin_amdgcn_raw_buffer_load_b128(xres, off, 16, 0);
+            }
             x_even[i][t][0] = pick_even(x0[0], x0[1]);
             x_even[i][t][1] = pick_even(x0[2], x0[3]);
             x_even[i][t][2] = pick_even(x1[0], x1[1]);
@@ -222,16 +258,6 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
             x_odd[i][t][3] = pick_odd(x1[2], x1[3]);
         }
 
-    // ---- role of this thread in the epilogue: outputs (m_out[o], tile*16 + n_out) of every tile
-    int m_out[OPT];
-    float sa_out[OPT];
-    bool writer[OPT];
-#pragma unroll
-    for (int o = 0; o < OPT; ++o) {
-        m_out[o] = (threadIdx.x + o * T) >> 4;  // 0 .. 16*MT-1 for the threads that take part
-        writer[o] = threadIdx.x + o * T < 256 * MT && m_out[o] < a.M;
-        sa_out[o] = writer[o] ? a.a_scale[m_out[o]] : 0.0f;
-    }
     const float inv_alpha = __int_as_float((127 - a.alpha_log2) << 23);  // 2^-alpha_log2, exact
 
     // ---- role of this thread in staging a tile's group scales: the tile's 16 x NG scales are one contiguous block
