@@ -5,7 +5,8 @@ Workload (N=1): the LLaMA-2-7B-shaped decode linears (qkv 4096->12288, o_proj 40
 down 11008->4096; group-128 int4 weights, int8 per-token activations, alpha = 2^10) at batch M in {1, 16, 64}.
 One step is one pass of the whole hot path over that workload: for every batch size and every one of `--layers`
 layers (32, each with its own weight buffers, so every GEMM streams cold weights from HBM as in a real decode
-step), the per-token activation quantiser followed by the integer-scale GEMM.  Inputs are synthetic (seeded) and
+step), the per-token activation quantiser followed by the integer-scale GEMM (for one token, M = 1, both behind the library's one-kernel linear call, whose
+decode kernel quantises the token itself).  Inputs are synthetic (seeded) and
 resident in HBM before the timed region.  Launches of one (batch, linear) pair are recorded into a HIP graph and
 replayed back to back; HIP events between the graph launches give each kernel's average duration inside the timed
 region.
@@ -44,6 +45,8 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=32, help="distinct weight copies per linear (LLaMA-2-7B has 32 layers)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-floatscale", action="store_true", help="skip the float-scale comparison pass")
+    ap.add_argument("--no-fused-token", action="store_true",
+                    help="M = 1: quantiser kernel + GEMM kernel instead of the one-kernel linear call")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-sample-layers", type=int, default=32)
     ap.add_argument("--workload", choices=("decode", "prefill", "moe", "w8a8", "producers"), default="decode")
@@ -172,7 +175,7 @@ def main():
                 out=torch.empty((M, N), dtype=torch.float16, device=dev))
     torch.cuda.synchronize()
 
-    def kernel_name(M, K, int_scale):
+    def kernel_name(M, K, int_scale, fused=False):
         """Name of the kernel instantiation the library picks for this shape (mirrors its dispatch; used to match the
         per-kernel figures here with a rocprofv3 kernel trace)."""
         tag = "true" if int_scale else "false"
@@ -190,12 +193,13 @@ def main():
                 xs_t, dt = (2, 4) if waves == 16 else (8, 1)
             else:
                 xs_t, dt = 4, 1
-            return f"gemm_decode_kernel<{mt}, {xs_t}, {dt}, {waves}, {tag}>"
+            return f"gemm_decode_kernel<{mt}, {xs_t}, {dt}, {waves}, {tag}, {'true' if fused else 'false'}>"
         mt = 1 if M <= 16 else 2 if M <= 32 else 3 if M <= 48 else 4
         return f"gemm_skinny_kernel<{mt}, ...>"
 
     # ---------------------------------------------------------------- segments of one step
     safe_ws = {}
+    lin_ws = {}
 
     def make_segments(int_scale: bool, with_quant: bool, safe: bool = False, hot: bool = False):
         """hot: every launch reads the first layer's weights (they stay in the 256 MB Infinity Cache / L2)."""
@@ -203,6 +207,23 @@ def main():
         for M in BATCHES:
             for name, (K, N) in linears:
                 a, w = acts[(M, name)], weights[name]
+                if with_quant and M == 1 and int_scale and not safe and not args.no_fused_token:
+                    # one token: the linear call (fp16 in), whose decode kernel quantises the token itself
+                    kname = kernel_name(M, K, True, fused=True)
+                    if kname.startswith("gemm_decode_kernel"):
+                        if (M, name) not in lin_ws:
+                            lin_ws[(M, name)] = torch.empty(P.is_linear_workspace_bytes(M, N, K, GROUP),
+                                                            dtype=torch.uint8, device=dev)
+
+                        def fl(a=a, w=w, ws=lin_ws[(M, name)]):
+                            for l in range(L):
+                                P.is_linear_w4a8_intscale(a["x"], w["q"][l], w["si"][l], w["c"][l], GROUP, ALPHA_LOG2,
+                                                          out=a["out"], workspace=ws)
+                        # fp16 token in instead of int8 codes and their scale
+                        nbytes = S.algorithmic_bytes(M, N, K, GROUP) + M * K - 4 * M
+                        segs.append(Segment(f"linear_{name}_M{M}", kname, L, L * nbytes, L * S.algorithmic_ops(M, N, K),
+                                            fl, use_graph, torch))
+                        continue
                 if with_quant:
                     def fq(a=a):
                         for _ in range(L):

@@ -120,6 +120,23 @@ int is_gemm_w4a8_floatscale(const int8_t* xq, const float* a_scale, const void* 
                             int M, int N, int K, int group, void* out_fp16, void* workspace,
                             size_t workspace_bytes, void* stream);
 
+/*
+ * The linear layer on fp16 activations: is_quantize_act_int8_token followed by is_gemm_w4a8_intscale (or the
+ * float-scale twin), behind one call and with the same results to the bit (Appendix A.1 per token, then Eq. (2) or
+ * Eq. (1)).  For one token (M = 1, a decode step at batch 1) whose K the decode kernel covers, the quantiser runs
+ * inside the GEMM kernel and no other kernel is launched; otherwise the two kernels run one after the other.
+ *   x_fp16 in fp16 [M,K], K a multiple of 8;  the other arguments as for the GEMMs
+ *   workspace    device scratch of at least is_linear_workspace_bytes(M,N,K,group) bytes (never 0 for M > 0): it
+ *                receives the quantised activations [M,K], then (256-byte aligned) the token scales [M], then the
+ *                GEMM's own workspace; with the one-kernel route only the token scale is written
+ */
+size_t is_linear_workspace_bytes(int M, int N, int K, int group);
+int is_linear_w4a8_intscale(const void* x_fp16, const void* qweight, const int32_t* scale_i32, const float* chan_scale,
+                            int M, int N, int K, int group, int alpha_log2, void* out_fp16, int32_t* acc_out,
+                            void* workspace, size_t workspace_bytes, void* stream);
+int is_linear_w4a8_floatscale(const void* x_fp16, const void* qweight, const float* scale_f32, int M, int N, int K,
+                              int group, void* out_fp16, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Scratch the two GEMMs above need for this shape (0 when they need none). Returns 0 for invalid shapes. */
 size_t is_gemm_workspace_bytes(int M, int N, int K, int group);
 

@@ -29,6 +29,9 @@ EXPORTED_SYMBOLS = (
     "is_gemm_w4a8_intscale",
     "is_gemm_w4a8_floatscale",
     "is_gemm_workspace_bytes",
+    "is_linear_workspace_bytes",
+    "is_linear_w4a8_intscale",
+    "is_linear_w4a8_floatscale",
     "is_gemm_w4a8_intscale_grouped",
     "is_gemm_w4a8_floatscale_grouped",
     "is_gemm_grouped_workspace_bytes",
@@ -88,6 +91,12 @@ def load_library() -> ctypes.CDLL:
     lib.is_gemm_w4a8_floatscale.restype = ci
     lib.is_gemm_workspace_bytes.argtypes = [ci, ci, ci, ci]
     lib.is_gemm_workspace_bytes.restype = sz
+    lib.is_linear_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.is_linear_workspace_bytes.restype = sz
+    lib.is_linear_w4a8_intscale.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.is_linear_w4a8_intscale.restype = ci
+    lib.is_linear_w4a8_floatscale.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp, sz, vp]
+    lib.is_linear_w4a8_floatscale.restype = ci
     lib.is_gemm_w4a8_intscale_grouped.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
     lib.is_gemm_w4a8_intscale_grouped.restype = ci
     lib.is_gemm_w4a8_floatscale_grouped.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, sz, vp]
@@ -293,6 +302,53 @@ def is_gemm_w4a8_floatscale(xq, a_scale, qweight, scale_f32, group: int, out=Non
     st = load_library().is_gemm_w4a8_floatscale(_p(xq), _p(a_scale), _p(qweight), _p(scale_f32), M, N, K, group,
                                                _p(out), _p(ws), ws_bytes, _stream_handle(stream))
     _check("is_gemm_w4a8_floatscale", st)
+    return out
+
+
+def is_linear_workspace_bytes(M: int, N: int, K: int, group: int) -> int:
+    return int(load_library().is_linear_workspace_bytes(M, N, K, group))
+
+
+def is_linear_w4a8_intscale(x, qweight, scale_i32, chan_scale, group: int, alpha_log2: int, out=None, acc_out=None,
+                            want_acc: bool = False, workspace=None, stream=None):
+    """fp16 activations in: quantiser + integer-scale GEMM behind one call. Returns (out fp16 [M,N], acc or None)."""
+    torch = _torch()
+    M, K = x.shape
+    N = qweight.shape[0]
+    _require(x, torch.float16, (M, K), "x")
+    _require(qweight, torch.uint8, (N, K // 2), "qweight")
+    _require(scale_i32, torch.int32, (N, K // group), "scale_i32")
+    if chan_scale is not None:
+        _require(chan_scale, torch.float32, (N,), "chan_scale")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _require(out, torch.float16, (M, N), "out")
+    if acc_out is None and want_acc:
+        acc_out = torch.empty((M, N), dtype=torch.int32, device=x.device)
+    if acc_out is not None:
+        _require(acc_out, torch.int32, (M, N), "acc_out")
+    ws, ws_bytes = _workspace(is_linear_workspace_bytes(M, N, K, group), x.device, workspace)
+    st = load_library().is_linear_w4a8_intscale(_p(x), _p(qweight), _p(scale_i32), _p(chan_scale), M, N, K, group,
+                                               alpha_log2, _p(out), _p(acc_out), _p(ws), ws_bytes,
+                                               _stream_handle(stream))
+    _check("is_linear_w4a8_intscale", st)
+    return out, acc_out
+
+
+def is_linear_w4a8_floatscale(x, qweight, scale_f32, group: int, out=None, workspace=None, stream=None):
+    torch = _torch()
+    M, K = x.shape
+    N = qweight.shape[0]
+    _require(x, torch.float16, (M, K), "x")
+    _require(qweight, torch.uint8, (N, K // 2), "qweight")
+    _require(scale_f32, torch.float32, (N, K // group), "scale_f32")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _require(out, torch.float16, (M, N), "out")
+    ws, ws_bytes = _workspace(is_linear_workspace_bytes(M, N, K, group), x.device, workspace)
+    st = load_library().is_linear_w4a8_floatscale(_p(x), _p(qweight), _p(scale_f32), M, N, K, group, _p(out), _p(ws),
+                                                 ws_bytes, _stream_handle(stream))
+    _check("is_linear_w4a8_floatscale", st)
     return out
 
 

@@ -6,10 +6,19 @@
 
 namespace intscale {
 
+// Maximum over the 64 lanes of a wave, for values that are >= 0 in every lane (an absmax): their bit patterns order
+// like unsigned integers.  Four lane-swizzled steps inside each row of 16 lanes (neighbour, pair, mirrored half,
+// mirrored row), then the four row results meet in scalar registers.  No trip through the LDS crossbar, whose
+// latency would sit six times in a row on the critical path of a one-token kernel.
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
-    return v;
+    unsigned x = __float_as_uint(v);
+    x = max(x, (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    x = max(x, (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    x = max(x, (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xF, 0xF, true));  // row_half_mirror
+    x = max(x, (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x140, 0xF, 0xF, true));  // row_mirror
+    const unsigned r0 = __builtin_amdgcn_readlane((int)x, 0), r1 = __builtin_amdgcn_readlane((int)x, 16);
+    const unsigned r2 = __builtin_amdgcn_readlane((int)x, 32), r3 = __builtin_amdgcn_readlane((int)x, 48);
+    return __uint_as_float(max(max(r0, r1), max(r2, r3)));
 }
 
 __device__ __forceinline__ float absmax8(uint4 v) {

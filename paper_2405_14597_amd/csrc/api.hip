@@ -226,6 +226,75 @@ int is_gemm_w4a8_floatscale_grouped(const int8_t* xq, const float* a_scale, cons
                        out_fp16, nullptr, workspace, workspace_bytes, stream, false, true);
 }
 
+// ---- linear layer on fp16 activations: quantiser + GEMM behind one call
+static size_t pad_256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+size_t is_linear_workspace_bytes(int M, int N, int K, int group) {
+    if (check_gemm_shape(M, N, K, group) != IS_OK || (K & 7)) return 0;
+    // quantised activations and token scales for the two-kernel route, then the GEMM's own workspace
+    return pad_256((size_t)M * K) + pad_256((size_t)M * 4) + is_gemm_workspace_bytes(M, N, K, group);
+}
+
+static int linear_common(const void* x_fp16, const void* qweight, const void* scale, const float* chan_scale, int M,
+                         int N, int K, int group, int alpha_log2, void* out_fp16, int32_t* acc_out, void* workspace,
+                         size_t workspace_bytes, void* stream, bool int_scale) {
+    const int shape = check_gemm_shape(M, N, K, group);
+    if (shape != IS_OK) return shape;
+    if (K & 7) return IS_ERR_INVALID_ARG;
+    if (int_scale && (alpha_log2 < 0 || alpha_log2 > 30)) return IS_ERR_INVALID_ARG;
+    const size_t need = is_linear_workspace_bytes(M, N, K, group);  // 0 only for M = 0
+    if (!ok_opt(workspace)) return IS_ERR_INVALID_ARG;
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return IS_ERR_WORKSPACE;
+    if (!ok_ptr(qweight) || !ok_ptr(scale) || !ok_opt(chan_scale)) return IS_ERR_INVALID_ARG;
+    if (M == 0) return IS_OK;
+    if (!ok_ptr(x_fp16) || !ok_ptr(out_fp16) || !ok_opt(acc_out)) return IS_ERR_INVALID_ARG;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    int8_t* xq = reinterpret_cast<int8_t*>(ws);
+    float* sa = reinterpret_cast<float*>(ws + pad_256((size_t)M * K));
+    unsigned char* rest = ws + pad_256((size_t)M * K) + pad_256((size_t)M * 4);
+    if (M == 1 && !general_forced()) {
+        // one token: the decode kernel quantises it itself (every workgroup its own copy, the waves their K slices)
+        GemmArgs a;
+        a.xq = nullptr;
+        a.a_scale = nullptr;
+        a.qweight = static_cast<const uint8_t*>(qweight);
+        a.scale = scale;
+        a.chan_scale = chan_scale;
+        a.row_offsets = nullptr;
+        a.out = static_cast<__half*>(out_fp16);
+        a.acc_out = acc_out;
+        a.M = M;
+        a.N = N;
+        a.K = K;
+        a.group = group;
+        a.alpha_log2 = int_scale ? alpha_log2 : 0;
+        a.num_experts = 1;
+        a.w_bits = 4;
+        a.x_fp16 = static_cast<const __half*>(x_fp16);
+        a.a_scale_out = sa;
+        hipError_t err = hipSuccess;
+        if (try_launch_linear_decode(a, int_scale, static_cast<hipStream_t>(stream), &err)) return hip_status(err);
+    }
+    const int st = hip_status(launch_quantize_act(static_cast<const __half*>(x_fp16), M, K, xq, sa,
+                                                  static_cast<hipStream_t>(stream)));
+    if (st != IS_OK) return st;
+    return gemm_common(xq, sa, qweight, scale, chan_scale, nullptr, 1, M, N, K, group, alpha_log2, out_fp16, acc_out,
+                       rest, workspace_bytes - (size_t)(rest - ws), stream, int_scale, false);
+}
+
+int is_linear_w4a8_intscale(const void* x_fp16, const void* qweight, const int32_t* scale_i32, const float* chan_scale,
+                            int M, int N, int K, int group, int alpha_log2, void* out_fp16, int32_t* acc_out,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    return linear_common(x_fp16, qweight, scale_i32, chan_scale, M, N, K, group, alpha_log2, out_fp16, acc_out,
+                         workspace, workspace_bytes, stream, true);
+}
+
+int is_linear_w4a8_floatscale(const void* x_fp16, const void* qweight, const float* scale_f32, int M, int N, int K,
+                              int group, void* out_fp16, void* workspace, size_t workspace_bytes, void* stream) {
+    return linear_common(x_fp16, qweight, scale_f32, nullptr, M, N, K, group, 0, out_fp16, nullptr, workspace,
+                         workspace_bytes, stream, false);
+}
+
 // ---- fine-grained W8A8
 static int check_w8_shape(int M, int N, int K, int group) {
     if (M < 0 || N <= 0 || K <= 0 || group <= 0 || K % group != 0) return IS_ERR_INVALID_ARG;

@@ -29,6 +29,7 @@
 //
 // The scale step runs once per 128-wide step with that step's group scale; for groups wider than 128 this is the
 // same integer by distributivity ((P1 + P2) * s = P1 * s + P2 * s modulo 2^32).
+#include "act_common.h"
 #include "is_common.h"
 
 namespace intscale {
@@ -54,8 +55,11 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 // MT: 16-row token tiles.  XS: steps of K a wave owns at most (its activations stay in 8*XS*MT registers).
 // DT: weight tiles in flight per wave.
 // WAVES: waves per workgroup (16 leaves 128 vector registers per lane, 8 leaves 256).
-template <int MT, int XS, int DT, int WAVES, bool INT_SCALE>
+// FUSEQ: one fp16 token (M = 1) instead of quantised activations: the per-token quantiser of Appendix A.1 runs in the
+// prologue (every wave covers its own K slice, the absmax meets in LDS behind the barrier that is there anyway).
+template <int MT, int XS, int DT, int WAVES, bool INT_SCALE, bool FUSEQ = false>
 __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, DecodePlan p) {
+    static_assert(!FUSEQ || MT == 1, "the fused quantiser handles one token");
     extern __shared__ __align__(16) unsigned char smem_raw[];
     using acc_t = typename std::conditional<INT_SCALE, int, float>::type;
 
@@ -79,7 +83,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
 
     const rsrc_t wres = make_rsrc(a.qweight, (size_t)a.N * row_bytes);
     const rsrc_t sres = make_rsrc(a.scale, (size_t)a.N * NG * 4);
-    const rsrc_t xres = make_rsrc(a.xq, (size_t)a.M * a.K);
+    const rsrc_t xres = FUSEQ ? make_rsrc(a.x_fp16, (size_t)a.K * 2) : make_rsrc(a.xq, (size_t)a.M * a.K);
     const rsrc_t cres = make_rsrc(a.chan_scale, a.chan_scale ? (size_t)a.N * 4 : 0);
 
     // LDS: two buffers of partial accumulators [W][MT][64 lanes][4], then two buffers of one tile's group scales
@@ -155,7 +159,8 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     for (int o = 0; o < OPT; ++o) {
         m_out[o] = (threadIdx.x + o * T) >> 4;  // 0 .. 16*MT-1 for the threads that take part
         writer[o] = threadIdx.x + o * T < 256 * MT && m_out[o] < a.M;
-        sa_out[o] = writer[o] ? a.a_scale[m_out[o]] : 0.0f;
+        if constexpr (FUSEQ) sa_out[o] = 0.0f;  // known once the token's absmax is
+        else sa_out[o] = writer[o] ? a.a_scale[m_out[o]] : 0.0f;
     }
 
     // Loads come back in the order they were issued.  With several tiles in flight per wave, whatever is requested
@@ -164,7 +169,15 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     // while the others are still on their way.  (They are a few requests per lane; with one tile in flight, and the
     // long activation slices that go with it, the stream starts first instead.)
     constexpr bool kStageX = WAVES == 8 && MT == 4;
-    constexpr bool kXFirst = DT >= 2 && !kStageX;
+    constexpr bool kXFirst = DT >= 2 && !kStageX && !FUSEQ;
+    // fused quantiser: lane l takes k = 2l, 2l+1 of every step of its wave's K slice (two fp16 values, one word)
+    [[maybe_unused]] int xh[XS];
+    if constexpr (FUSEQ) {
+#pragma unroll
+        for (int i = 0; i < XS; ++i)
+            xh[i] = __builtin_amdgcn_raw_buffer_load_b32(xres, i < ns ? ((s0 + i) * kStepK + 2 * lane) * 2 : kOutOfRange, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
     [[maybe_unused]] v4i xr0[kXFirst ? XS : 1][kXFirst ? MT : 1], xr1[kXFirst ? XS : 1][kXFirst ? MT : 1];
     if constexpr (kXFirst) {
 #pragma unroll
@@ -194,6 +207,22 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     // XS*128-byte slice) and turns them into the operand layout through a private piece of LDS.  No barrier: LDS
     // serves one wave's requests in order.  Chunk index XOR row keeps both sides off each other's banks.
     [[maybe_unused]] unsigned char* xstage = reinterpret_cast<unsigned char*>(lds_wide + 2 * W) + wave * (XS * 2048);
+    // fused quantiser: one absmax word per wave, then per wave the codes of its slice, even k and odd k apart
+    [[maybe_unused]] float* lds_amax = reinterpret_cast<float*>(lds_wide + 2 * W);
+    [[maybe_unused]] signed char* qstage = reinterpret_cast<signed char*>(lds_amax + W) + wave * (XS * 128);
+    [[maybe_unused]] float xf0[XS], xf1[XS];
+    if constexpr (FUSEQ) {
+        float amax = 0.0f;
+#pragma unroll
+        for (int i = 0; i < XS; ++i) {
+            const float2 f = __half22float2(*reinterpret_cast<const __half2*>(&xh[i]));
+            xf0[i] = f.x;
+            xf1[i] = f.y;
+            amax = fmaxf(amax, fmaxf(fabsf(f.x), fabsf(f.y)));
+        }
+        amax = wave_max(amax);
+        if (lane == 0) lds_amax[wave] = amax;
+    }
     constexpr int kChunks = XS * 8;  // 16-byte chunks of a row's slice
     [[maybe_unused]] auto fetch_rows = [&](int t, v4i (&raw)[XS * 2]) {
 #pragma unroll
@@ -237,7 +266,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
 #pragma unroll
     for (int i = 0; i < XS; ++i)
 #pragma unroll
-        for (int t = 0; t < (kStageX ? 0 : MT); ++t) {
+        for (int t = 0; t < (kStageX || FUSEQ ? 0 : MT); ++t) {
             v4i x0, x1;
             if constexpr (kXFirst) {
                 x0 = xr0[i][t];
@@ -307,6 +336,34 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
         stage_scales(0, 0);
         if (SD < my_tiles) issue_scales(0, tile0 + SD * G);
         lds_barrier();
+        if constexpr (FUSEQ) {
+            // Appendix A.1, n = 8: s_a = absmax / 127 and codes clamp(rne(x / s_a)), a true division as in the
+            // stand-alone quantiser.  The codes of the wave's slice go through its own piece of LDS into the operand
+            // layout.  (Behind the barrier that publishes the first tile's scales: a barrier of its own, earlier, was slower.)
+            static_assert(!FUSEQ || W == 16, "one absmax word per wave, read by lane & 15");
+            const float amax = wave_max(lds_amax[lane & (W - 1)]);
+            const float s_a = amax / 127.0f;
+#pragma unroll
+            for (int i = 0; i < XS; ++i) {
+                int q0 = 0, q1 = 0;
+                if (s_a > 0.0f) {
+                    q0 = quant_code(xf0[i], s_a, -128.0f, 127.0f);
+                    q1 = quant_code(xf1[i], s_a, -128.0f, 127.0f);
+                }
+                qstage[i * 128 + lane] = (signed char)q0;
+                qstage[i * 128 + 64 + lane] = (signed char)q1;
+            }
+#pragma unroll
+            for (int i = 0; i < XS; ++i) {
+                // every lane of a K slice takes the token's codes: operand rows 1..15 then repeat row 0, and their
+                // results are never written (there is one token)
+                x_even[i][0] = *reinterpret_cast<const v4i*>(qstage + i * 128 + kb * 16);
+                x_odd[i][0] = *reinterpret_cast<const v4i*>(qstage + i * 128 + 64 + kb * 16);
+            }
+#pragma unroll
+            for (int o = 0; o < OPT; ++o) sa_out[o] = writer[o] ? s_a : 0.0f;
+            if (a.a_scale_out && blockIdx.x == 0 && threadIdx.x == 0) *a.a_scale_out = s_a;
+        }
 
         for (int k = 0; k < my_tiles; k += SD) {
 #pragma unroll
@@ -445,13 +502,14 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
 
 }
 
-template <int MT, int XS, int DT, int WAVES, bool INT_SCALE>
+template <int MT, int XS, int DT, int WAVES, bool INT_SCALE, bool FUSEQ = false>
 hipError_t launch_decode(const GemmArgs& a, const DecodePlan& p, int grid, hipStream_t stream) {
     // partial accumulators, group scales, wide-scale words, activation staging (64 token rows)
     const size_t smem = 2 * (size_t)WAVES * MT * kWave * 16 + 2 * 16 * (size_t)(p.num_groups + 1) * 4 +
                         2 * (size_t)WAVES * 4 +
-                        (WAVES == 8 && MT == 4 ? (size_t)WAVES * XS * 2048 : 0);
-    auto kern = gemm_decode_kernel<MT, XS, DT, WAVES, INT_SCALE>;
+                        (WAVES == 8 && MT == 4 ? (size_t)WAVES * XS * 2048 : 0) +
+                        (FUSEQ ? (size_t)WAVES * (4 + XS * 128) : 0);
+    auto kern = gemm_decode_kernel<MT, XS, DT, WAVES, INT_SCALE, FUSEQ>;
     if (smem > 64 * 1024) {
         static bool raised = false;  // per instantiation
         if (!raised) {
@@ -467,6 +525,11 @@ hipError_t launch_decode(const GemmArgs& a, const DecodePlan& p, int grid, hipSt
 
 template <bool INT_SCALE>
 hipError_t dispatch(const GemmArgs& a, const DecodePlan& p, int mt, int xs, int grid, hipStream_t stream) {
+    if (a.x_fp16) {  // one fp16 token, quantised in the kernel
+        if (xs <= 2) return launch_decode<1, 2, 4, 16, INT_SCALE, true>(a, p, grid, stream);
+        if (xs <= 4) return launch_decode<1, 4, 2, 16, INT_SCALE, true>(a, p, grid, stream);
+        return launch_decode<1, 6, 1, 16, INT_SCALE, true>(a, p, grid, stream);
+    }
     if (mt == 1) {
         if (xs <= 2) return launch_decode<1, 2, 4, 16, INT_SCALE>(a, p, grid, stream);
         if (xs <= 4) return launch_decode<1, 4, 2, 16, INT_SCALE>(a, p, grid, stream);
@@ -484,6 +547,7 @@ hipError_t dispatch(const GemmArgs& a, const DecodePlan& p, int mt, int xs, int 
 // True (and the launch done) if the decode kernel covers this problem; false leaves it to the general kernel.
 bool try_launch_gemm_decode(const GemmArgs& a, bool int_scale, hipStream_t stream, hipError_t* err) {
     if (a.row_offsets || a.M > 64 || a.M < 1) return false;
+    if (a.x_fp16 && a.M != 1) return false;
     const int NG = a.K / a.group;
     const int spg = a.group / kStepK;
     const int mt = a.M <= 16 ? 1 : a.M <= 32 ? 2 : 4;
@@ -508,6 +572,11 @@ bool try_launch_gemm_decode(const GemmArgs& a, bool int_scale, hipStream_t strea
     p.tiles_r = p.tiles % grid;
     *err = int_scale ? dispatch<true>(a, p, mt, xs, grid, stream) : dispatch<false>(a, p, mt, xs, grid, stream);
     return true;
+}
+
+bool try_launch_linear_decode(const GemmArgs& a, bool int_scale, hipStream_t stream, hipError_t* err) {
+    if (!a.x_fp16) return false;
+    return try_launch_gemm_decode(a, int_scale, stream, err);
 }
 
 }  // namespace intscale

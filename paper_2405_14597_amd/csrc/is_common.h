@@ -28,6 +28,10 @@ struct GemmArgs {
     int alpha_log2;
     int num_experts;
     int w_bits;                 // 4 (W4A8) or 8 (fine-grained W8A8)
+    // Linear layer on an fp16 token (decode kernel, M = 1 only): the activation quantiser runs inside the GEMM, xq and
+    // a_scale above are unused; a_scale_out (may be nullptr) receives the token's scale.
+    const __half* x_fp16 = nullptr;
+    float* a_scale_out = nullptr;
 };
 
 // Work split of the decode kernel (filled by its launcher).
@@ -51,6 +55,8 @@ hipError_t launch_quantize_weights(const __half* w, int N, int K, int group, int
                                    int* alpha_log2_dev, hipStream_t stream, int bits = 4);  // bits: 4 or 8 (one byte per code)
 hipError_t launch_gemm_skinny(const GemmArgs& a, bool int_scale, hipStream_t stream);
 bool try_launch_gemm_decode(const GemmArgs& a, bool int_scale, hipStream_t stream, hipError_t* err);
+// The same with the activation quantiser inside the kernel (a.x_fp16 set, a.M == 1).
+bool try_launch_linear_decode(const GemmArgs& a, bool int_scale, hipStream_t stream, hipError_t* err);
 // MFMA-bound tiled kernel; `workspace` holds gemm_prefill_workspace_bytes(...) bytes (num_experts = 1 and M = all
 // token rows for the plain form).
 size_t gemm_prefill_workspace_bytes(int num_experts, int M, int N, int K, int group);

@@ -271,6 +271,61 @@ def test_gemm_repeatable(P):
         assert torch.equal(acc0, acc1) and torch.equal(out0, out1) and torch.equal(fs0, fs1)
 
 
+# ------------------------------------------------------------------------------------------------ linear on fp16 activations
+# one token through the decode kernel's three one-tile instances (K slices of 2, 4 and 6 steps, even and uneven
+# splits of the groups over the waves, fewer tiles than workgroups, many tiles per workgroup), one token with K
+# beyond the decode kernel, and several tokens (quantiser kernel + GEMM)
+LINEAR_SHAPES = [(1, 4096, 4096), (1, 12288, 4096), (1, 4096, 8192), (1, 4096, 11008), (1, 272, 12288), (1, 40, 1024),
+                 (1, 16, 128), (1, 8208, 2048), (1, 64, 28672), (8, 4096, 4096), (100, 300, 1024), (64, 48, 11008)]
+
+
+@pytest.mark.parametrize("M,N,K", LINEAR_SHAPES)
+def test_linear_fp16_activations(P, kernel, M, N, K):
+    rng = np.random.default_rng(7000 + M + N + K)
+    _, qw, IS, s, _, c = rand_quantised(rng, 1, N, K)
+    x = S.activations_outlier(M, K, 77 + K % 13)
+    xq_ref, sa_ref = O.quantize_act_int8_token(x)
+    ref = O.gemm_w4a8_intscale(xq_ref, sa_ref, qw, IS, c, G, 10)
+    out, acc = P.is_linear_w4a8_intscale(dev(x), dev(qw), dev(IS), dev(c), G, 10, want_acc=True)
+    assert np.array_equal(host(acc), ref.acc), "int32 accumulators differ"
+    check_out(host(out), ref.out, f"M{M} N{N} K{K}")
+    fs = O.gemm_w4a8_floatscale(xq_ref, sa_ref, qw, s, G)
+    out_fs = P.is_linear_w4a8_floatscale(dev(x), dev(qw), dev(s), G)
+    check_fs(host(out_fs), fs, f"M{M} N{N} K{K}")
+
+
+def test_linear_fp16_token_scale_and_zero_token(P):
+    """The one-kernel route leaves the token's scale where the two-kernel route does, and an all-zero token gives
+    scale 0 and an all-zero output."""
+    N, K = 512, 4096
+    rng = np.random.default_rng(7100)
+    _, qw, IS, s, _, c = rand_quantised(rng, 1, N, K)
+    x = S.activations_student_t(1, K, 5)
+    _, sa_ref = O.quantize_act_int8_token(x)
+    nbytes = P.is_linear_workspace_bytes(1, N, K, G)
+    assert nbytes >= K + 256
+    ws = torch.zeros((nbytes,), dtype=torch.uint8, device="cuda:0")
+    P.is_linear_w4a8_intscale(dev(x), dev(qw), dev(IS), dev(c), G, 10, workspace=ws)
+    sa = ws[K:K + 4].view(torch.float32)          # K = 4096 is already a multiple of 256
+    assert np.array_equal(host(sa), sa_ref)
+    out, acc = P.is_linear_w4a8_intscale(dev(np.zeros((1, K), np.float16)), dev(qw), dev(IS), dev(c), G, 10,
+                                         want_acc=True, workspace=ws)
+    assert not host(acc).any() and not host(out).any()
+    assert host(ws[K:K + 4].view(torch.float32))[0] == 0.0
+
+
+def test_linear_fp16_argument_checks(P):
+    N, K = 64, 1024
+    rng = np.random.default_rng(7200)
+    _, qw, IS, s, _, c = rand_quantised(rng, 1, N, K)
+    x = dev(S.activations_outlier(2, K, 3))
+    small = torch.empty((16,), dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(P.IntScaleError):
+        P.is_linear_w4a8_intscale(x, dev(qw), dev(IS), dev(c), G, 10, workspace=small)
+    out, _ = P.is_linear_w4a8_intscale(x[:0], dev(qw), dev(IS), dev(c), G, 10)
+    assert out.shape == (0, N)
+
+
 # ------------------------------------------------------------------------------------------------ fine-grained W8A8
 @pytest.mark.parametrize("N,K,group,alpha,mode", [(16, 128, 128, 10, 0), (300, 1024, 128, 10, 1), (64, 2048, 256, -1, 1),
                                                   (33, 512, 512, -1, 0)])
