@@ -124,6 +124,22 @@ def test_fused_producer_argument_validation():
     assert s(M=0) == P.IS_OK
 
 
+def test_linear_argument_validation():
+    lib = P.load_library()
+    bad = P.IS_ERR_INVALID_ARG
+    need = lib.is_linear_workspace_bytes(8, 16, 256, 128)
+    assert need >= 8 * 256 + 8 * 4 and lib.is_linear_workspace_bytes(8, 16, 250, 128) == 0
+    assert lib.is_linear_workspace_bytes(0, 16, 256, 128) == 0
+    lin = lambda **kw: lib.is_linear_w4a8_intscale(
+        kw.get("x", A), kw.get("q", A), kw.get("si", A), kw.get("c", None), kw.get("M", 8), 16, kw.get("K", 256), 128,
+        kw.get("a", 10), kw.get("out", A), None, kw.get("ws", A), kw.get("wsb", need), None)
+    assert lin(x=None) == bad and lin(q=None) == bad and lin(si=None) == bad and lin(out=None) == bad
+    assert lin(a=31) == bad and lin(K=250) == bad and lin(c=A + 4) == bad and lin(M=-1) == bad
+    assert lin(ws=None) == P.IS_ERR_WORKSPACE and lin(wsb=need - 1) == P.IS_ERR_WORKSPACE
+    assert lin(M=0, ws=None, wsb=0) == P.IS_OK
+    assert lib.is_linear_w4a8_floatscale(A, A, None, 8, 16, 256, 128, A, A, need, None) == bad
+
+
 def test_missing_device_is_reported_not_hidden():
     """With valid arguments the call reaches HIP; without a GPU that must surface as IS_ERR_HIP, never as success."""
     import torch
