@@ -92,6 +92,13 @@ def run_linear(P, layer, x, alpha, mode, what, float_twin=True):
         fs_r = O.gemm_w4a8_floatscale(xq_r, sa_r, ref_w.qweight, ref_w.scale_f32, G)
         fs = P.is_gemm_w4a8_floatscale(xq, sa, got_w.qweight, got_w.scale_f32, G, workspace=ws)
         check_fs(host(fs), fs_r, what)
+    if M <= 16:
+        # the linear call on the fp16 activations (bench.py uses it for one token: the decode kernel quantises itself)
+        lws = torch.empty(P.is_linear_workspace_bytes(M, layer.N, layer.K, G), dtype=torch.uint8, device="cuda:0")
+        out3, acc3 = P.is_linear_w4a8_intscale(dev(x), got_w.qweight, got_w.scale_i32, got_w.chan_scale, G, alpha,
+                                               want_acc=True, workspace=lws)
+        assert np.array_equal(host(acc3), ref.acc), f"{what}: int32 accumulators of the linear call"
+        check_out(host(out3), ref.out, what)
     return ref
 
 
