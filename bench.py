@@ -469,11 +469,25 @@ def prefill_main(args):
             per[label] = per.get(label, 0.0) + a.elapsed_time(b)
         return (t1 - t0) / steps, {k: v / steps for k, v in per.items()}
 
+    def linear_is(d):
+        q = d["qw"]
+        P.is_linear_w4a8_intscale(d["x"], q.qweight, q.scale_i32, q.chan_scale, GROUP, ALPHA_LOG2, out=d["out"],
+                                  workspace=d["lws"])
+
+    # One step: every linear on its fp16 activations through the linear call (quantiser inside the tiled kernel's
+    # activation preparation); with --no-fused-token the quantiser kernel and the GEMM call one after the other.
     fns = []
     for d in data:
-        fns.append((f"quant_{d['name']}", lambda d=d: quant(d)))
-        fns.append((f"gemm_{d['name']}", lambda d=d: gemm_is(d)))
-    sec_per_step, per = timed(fns, args.steps, args.warmup)
+        if args.no_fused_token:
+            fns.append((f"quant_{d['name']}", lambda d=d: quant(d)))
+            fns.append((f"gemm_{d['name']}", lambda d=d: gemm_is(d)))
+        else:
+            d["lws"] = torch.empty(P.is_linear_workspace_bytes(M, d["N"], d["K"], GROUP), dtype=torch.uint8, device=dev)
+            fns.append((f"linear_{d['name']}", lambda d=d: linear_is(d)))
+    sec_per_step, per_step = timed(fns, args.steps, args.warmup)
+    # the GEMM calls alone (quantised activations in), for the roofline figure of the tile kernel
+    _, per = timed([(f"gemm_{d['name']}", lambda d=d: gemm_is(d)) for d in data] +
+                   [(f"quant_{d['name']}", lambda d=d: quant(d)) for d in data], max(3, args.steps // 2), 2)
     step_ops = sum(S.algorithmic_ops(M, d["N"], d["K"]) for d in data)
     shapes = []
     gemm_ms = gemm_ops = 0.0
@@ -484,7 +498,8 @@ def prefill_main(args):
         gemm_ops += ops
         shapes.append(dict(name=f"gemm_{d['name']}_M{M}", us=round(1e3 * ms, 2), tops=round(ops / ms / 1e9, 1),
                            mfma_frac=round(ops / ms / 1e9 / MFMA_I8_PEAK_TOPS, 4),
-                           quant_us=round(1e3 * per[f"quant_{d['name']}"], 2)))
+                           quant_us=round(1e3 * per[f"quant_{d['name']}"], 2),
+                           step_call_us=round(1e3 * sum(v for k, v in per_step.items() if k.endswith("_" + d["name"])), 2)))
     achieved = gemm_ops / gemm_ms / 1e9
     kernel = "gemm_prefill_kernel<true>"
     roofline = dict(bound="mfma", kernel=kernel, achieved=round(achieved, 1), peak=MFMA_I8_PEAK_TOPS, unit="TOP/s",

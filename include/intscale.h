@@ -124,11 +124,12 @@ int is_gemm_w4a8_floatscale(const int8_t* xq, const float* a_scale, const void* 
  * The linear layer on fp16 activations: is_quantize_act_int8_token followed by is_gemm_w4a8_intscale (or the
  * float-scale twin), behind one call and with the same results to the bit (Appendix A.1 per token, then Eq. (2) or
  * Eq. (1)).  For one token (M = 1, a decode step at batch 1) whose K the decode kernel covers, the quantiser runs
- * inside the GEMM kernel and no other kernel is launched; otherwise the two kernels run one after the other.
+ * inside the GEMM kernel and no other kernel is launched; for more than 64 tokens with K <= 16384 the tiled kernel's
+ * activation preparation quantises on the way; otherwise the two kernels run one after the other.
  *   x_fp16 in fp16 [M,K], K a multiple of 8;  the other arguments as for the GEMMs
  *   workspace    device scratch of at least is_linear_workspace_bytes(M,N,K,group) bytes (never 0 for M > 0): it
  *                receives the quantised activations [M,K], then (256-byte aligned) the token scales [M], then the
- *                GEMM's own workspace; with the one-kernel route only the token scale is written
+ *                GEMM's own workspace; the routes that quantise inside the GEMM write only the token scales
  */
 size_t is_linear_workspace_bytes(int M, int N, int K, int group);
 int is_linear_w4a8_intscale(const void* x_fp16, const void* qweight, const int32_t* scale_i32, const float* chan_scale,

@@ -275,6 +275,28 @@ static int linear_common(const void* x_fp16, const void* qweight, const void* sc
         hipError_t err = hipSuccess;
         if (try_launch_linear_decode(a, int_scale, static_cast<hipStream_t>(stream), &err)) return hip_status(err);
     }
+    if (wants_prefill(M, 1) && gemm_prefill_takes_fp16(K)) {
+        // many tokens: the tiled kernel's activation preparation quantises on the way (no canonical codes written)
+        GemmArgs a;
+        a.xq = nullptr;
+        a.a_scale = sa;
+        a.qweight = static_cast<const uint8_t*>(qweight);
+        a.scale = scale;
+        a.chan_scale = chan_scale;
+        a.row_offsets = nullptr;
+        a.out = static_cast<__half*>(out_fp16);
+        a.acc_out = acc_out;
+        a.M = M;
+        a.N = N;
+        a.K = K;
+        a.group = group;
+        a.alpha_log2 = int_scale ? alpha_log2 : 0;
+        a.num_experts = 1;
+        a.w_bits = 4;
+        a.x_fp16 = static_cast<const __half*>(x_fp16);
+        a.a_scale_out = sa;
+        return hip_status(launch_gemm_prefill(a, int_scale, rest, static_cast<hipStream_t>(stream)));
+    }
     const int st = hip_status(launch_quantize_act(static_cast<const __half*>(x_fp16), M, K, xq, sa,
                                                   static_cast<hipStream_t>(stream)));
     if (st != IS_OK) return st;

@@ -29,6 +29,7 @@
 // P + 8 * sum_k x[m,k].  The correction -8 * sum_k x[m,k] per (token row, K step) is computed once by the
 // preparation kernel and enters each MFMA chain as its initial accumulator, so the chain returns P exactly and the
 // scale step costs one instruction per element.
+#include "act_common.h"
 #include "tile_common.h"
 
 namespace intscale {
@@ -97,6 +98,59 @@ __global__ __launch_bounds__(256) void prepare_activations_kernel(const int8_t* 
             p.y = (uint32_t)pick_even(v.z, v.w);
             p.z = (uint32_t)pick_odd(v.x, v.y);
             p.w = (uint32_t)pick_odd(v.z, v.w);
+            prow[c] = p;
+        }
+        sum += __shfl_xor(sum, 1, kWave);
+        sum += __shfl_xor(sum, 2, kWave);
+        sum += __shfl_xor(sum, 4, kWave);
+        if ((lane & 7) == 0 && c < nchunk) s8[(size_t)(c >> 3) * M + m] = -8 * sum;
+    }
+}
+
+// The same preparation straight from fp16 activations (the linear call): the per-token quantiser of Appendix A.1 and
+// the preparation in one pass, one wave per token row, the row held in registers (CH chunks of 16 values per lane)
+// between the absmax and the rounding.  Saves writing the canonical codes and reading them back.
+template <int CH>
+__global__ __launch_bounds__(256) void quantize_prepare_activations_kernel(const __half* __restrict__ x, int M, int K,
+                                                                           int8_t* __restrict__ xp,
+                                                                           int32_t* __restrict__ s8,
+                                                                           float* __restrict__ a_scale,
+                                                                           int32_t* __restrict__ wide_flag) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *wide_flag = 0;
+    const int m = blockIdx.x * 4 + threadIdx.x / kWave;
+    if (m >= M) return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint4* row = reinterpret_cast<const uint4*>(x + (size_t)m * K);  // 8 fp16 values each
+    uint4* prow = reinterpret_cast<uint4*>(xp + (size_t)m * K);
+    const int nchunk = K >> 4;
+    uint4 v[CH][2];
+    float amax = 0.0f;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+        const int c = lane + j * kWave;
+        v[j][0] = c < nchunk ? row[2 * c] : make_uint4(0u, 0u, 0u, 0u);
+        v[j][1] = c < nchunk ? row[2 * c + 1] : make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int j = 0; j < CH; ++j) amax = fmaxf(amax, fmaxf(absmax8(v[j][0]), absmax8(v[j][1])));
+    amax = wave_max(amax);
+    const float s = amax / 127.0f;
+    if (lane == 0) a_scale[m] = s;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+        const int c = lane + j * kWave;
+        int sum = 0;
+        if (c < nchunk) {
+            const uint2 lo = quantize8(v[j][0], s), hi = quantize8(v[j][1], s);  // the canonical 16 codes, in k order
+            sum = __builtin_amdgcn_sdot4((int)lo.x, 0x01010101, sum, false);
+            sum = __builtin_amdgcn_sdot4((int)lo.y, 0x01010101, sum, false);
+            sum = __builtin_amdgcn_sdot4((int)hi.x, 0x01010101, sum, false);
+            sum = __builtin_amdgcn_sdot4((int)hi.y, 0x01010101, sum, false);
+            uint4 p;
+            p.x = (uint32_t)pick_even(lo.x, lo.y);
+            p.y = (uint32_t)pick_even(hi.x, hi.y);
+            p.z = (uint32_t)pick_odd(lo.x, lo.y);
+            p.w = (uint32_t)pick_odd(hi.x, hi.y);
             prow[c] = p;
         }
         sum += __shfl_xor(sum, 1, kWave);
@@ -525,6 +579,9 @@ size_t gemm_prefill_workspace_bytes(int num_experts, int M, int N, int K, int gr
     return header_bytes(num_experts, M) + corrections_bytes(M, K) + scales_bytes(num_experts, N, K, group) + (size_t)M * K;
 }
 
+// rows the fused quantiser + preparation holds in registers: 16 chunks of 16 values per lane
+bool gemm_prefill_takes_fp16(int K) { return (K & 15) == 0 && (K >> 4) <= 16 * kWave; }
+
 hipError_t launch_gemm_prefill(const GemmArgs& a, bool int_scale, void* workspace, hipStream_t stream) {
     const int experts = a.row_offsets ? a.num_experts : 1;
     const int NG = a.K / a.group;
@@ -536,8 +593,22 @@ hipError_t launch_gemm_prefill(const GemmArgs& a, bool int_scale, void* workspac
     int32_t* scale_t = reinterpret_cast<int32_t*>(ws + header + corrections_bytes(a.M, a.K));
     int8_t* xp = reinterpret_cast<int8_t*>(ws + header + corrections_bytes(a.M, a.K) +
                                            scales_bytes(experts, a.N, a.K, a.group));
-    hipLaunchKernelGGL(prepare_activations_kernel, dim3((a.M + 3) / 4), dim3(256), 0, stream, a.xq, a.M, a.K, xp, s8,
-                       flag, a.row_offsets, experts, tile_table);
+    if (a.x_fp16) {  // fp16 activations (plain form only): quantised on the way, the token scales go to a.a_scale_out
+        const dim3 pgrid((a.M + 3) / 4), pblock(256);
+        const int chunks_per_lane = ((a.K >> 4) + kWave - 1) / kWave;
+        if (chunks_per_lane <= 4)
+            hipLaunchKernelGGL(quantize_prepare_activations_kernel<4>, pgrid, pblock, 0, stream, a.x_fp16, a.M, a.K, xp, s8,
+                               a.a_scale_out, flag);
+        else if (chunks_per_lane <= 8)
+            hipLaunchKernelGGL(quantize_prepare_activations_kernel<8>, pgrid, pblock, 0, stream, a.x_fp16, a.M, a.K, xp, s8,
+                               a.a_scale_out, flag);
+        else
+            hipLaunchKernelGGL(quantize_prepare_activations_kernel<16>, pgrid, pblock, 0, stream, a.x_fp16, a.M, a.K, xp, s8,
+                               a.a_scale_out, flag);
+    } else {
+        hipLaunchKernelGGL(prepare_activations_kernel, dim3((a.M + 3) / 4), dim3(256), 0, stream, a.xq, a.M, a.K, xp, s8,
+                           flag, a.row_offsets, experts, tile_table);
+    }
     const dim3 sgrid((a.N + 63) / 64, (NG + 63) / 64, experts);
     const int32_t* scale = static_cast<const int32_t*>(a.scale);
     if (int_scale) hipLaunchKernelGGL(prepare_scales_kernel<true>, sgrid, dim3(256), 0, stream, scale, a.N, NG, scale_t, flag);

@@ -28,8 +28,10 @@ struct GemmArgs {
     int alpha_log2;
     int num_experts;
     int w_bits;                 // 4 (W4A8) or 8 (fine-grained W8A8)
-    // Linear layer on an fp16 token (decode kernel, M = 1 only): the activation quantiser runs inside the GEMM, xq and
-    // a_scale above are unused; a_scale_out (may be nullptr) receives the token's scale.
+    // Linear layer on fp16 activations: the activation quantiser runs inside the GEMM's kernels and xq above is unused.
+    // Decode kernel (M = 1 only): a_scale is unused too, a_scale_out (may be nullptr) receives the token's scale.
+    // Tiled kernel (plain form, gemm_prefill_takes_fp16(K)): the token scales are written to a_scale_out, and a_scale
+    // must be the same pointer.
     const __half* x_fp16 = nullptr;
     float* a_scale_out = nullptr;
 };
@@ -60,6 +62,7 @@ bool try_launch_linear_decode(const GemmArgs& a, bool int_scale, hipStream_t str
 // MFMA-bound tiled kernel; `workspace` holds gemm_prefill_workspace_bytes(...) bytes (num_experts = 1 and M = all
 // token rows for the plain form).
 size_t gemm_prefill_workspace_bytes(int num_experts, int M, int N, int K, int group);
+bool gemm_prefill_takes_fp16(int K);
 hipError_t launch_gemm_prefill(const GemmArgs& a, bool int_scale, void* workspace, hipStream_t stream);
 
 // Fine-grained W8A8 (gemm_tile_w8.hip): `a.qweight` holds int8 codes [N,K]; one tiled kernel for every M.

@@ -276,7 +276,10 @@ def test_gemm_repeatable(P):
 # splits of the groups over the waves, fewer tiles than workgroups, many tiles per workgroup), one token with K
 # beyond the decode kernel, and several tokens (quantiser kernel + GEMM)
 LINEAR_SHAPES = [(1, 4096, 4096), (1, 12288, 4096), (1, 4096, 8192), (1, 4096, 11008), (1, 272, 12288), (1, 40, 1024),
-                 (1, 16, 128), (1, 8208, 2048), (1, 64, 28672), (8, 4096, 4096), (100, 300, 1024), (64, 48, 11008)]
+                 (1, 16, 128), (1, 8208, 2048), (1, 64, 28672), (8, 4096, 4096), (100, 300, 1024), (64, 48, 11008),
+                 # more than 64 tokens: the tiled kernel's preparation quantises on the way (rows of 4, 8 and 16 chunks
+                 # per lane, a ragged last row tile), and rows too long for that (quantiser kernel first)
+                 (130, 512, 4096), (70, 272, 8192), (200, 256, 14336), (66, 128, 28672), (257, 40, 2048)]
 
 
 @pytest.mark.parametrize("M,N,K", LINEAR_SHAPES)
