@@ -501,7 +501,7 @@ def prefill_main(args):
                            quant_us=round(1e3 * per[f"quant_{d['name']}"], 2),
                            step_call_us=round(1e3 * sum(v for k, v in per_step.items() if k.endswith("_" + d["name"])), 2)))
     achieved = gemm_ops / gemm_ms / 1e9
-    kernel = "gemm_prefill_kernel<true>"
+    kernel = "gemm_prefill_kernel<true, false>"
     roofline = dict(bound="mfma", kernel=kernel, achieved=round(achieved, 1), peak=MFMA_I8_PEAK_TOPS, unit="TOP/s",
                     frac=round(achieved / MFMA_I8_PEAK_TOPS, 4), traffic=measured_traffic(kernel, "llama3_8b_prefill"),
                     avg_launch_us=round(1e3 * gemm_ms / len(data), 2),
@@ -901,7 +901,7 @@ def moe_main(args):
                            roofline_frac=round(max(t_hbm, t_mfma) / (ms * 1e-3), 4)))
     tot_ms = sum(per.values())
     achieved = sum(alg_bytes(d) for d in data) / tot_ms / 1e6
-    kernel = "gemm_prefill_kernel<true>"
+    kernel = "gemm_prefill_kernel<true, false>"
     roofline = dict(bound="hbm", kernel=kernel, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4), traffic=measured_traffic(kernel, "mixtral_moe"),
                     avg_launch_us=round(1e3 * tot_ms / len(data), 2),
