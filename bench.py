@@ -651,8 +651,11 @@ def w8a8_main(args):
     shapes = [dict(name=f"w8a8_down_M{M}", us=round(per[M], 2), gbs=round(alg_bytes(M) / per[M] / 1e3, 1),
                    tops=round(2.0 * M * N * K / per[M] / 1e6, 1)) for M in MS]
     dom = max(small, key=lambda M: per[M])
-    roofline = dict(bound="hbm", kernel="gemm_skinny_kernel<..., W8>", achieved=round(alg_bytes(dom) / per[dom] / 1e3, 1),
-                    peak=HBM_PEAK_GBS, unit="GB/s", frac=round(alg_bytes(dom) / per[dom] / 1e3 / HBM_PEAK_GBS, 4), traffic=None,
+    # the general kernel's int8 instance for this many token rows (as a rocprofv3 kernel trace names it)
+    dom_kernel = "gemm_skinny_kernel<%d, 1, 2, true, true, true>" % (1 if dom <= 16 else 2 if dom <= 32 else 3 if dom <= 48 else 4)
+    roofline = dict(bound="hbm", kernel=dom_kernel, achieved=round(alg_bytes(dom) / per[dom] / 1e3, 1),
+                    peak=HBM_PEAK_GBS, unit="GB/s", frac=round(alg_bytes(dom) / per[dom] / 1e3 / HBM_PEAK_GBS, 4),
+                    traffic=measured_traffic(dom_kernel, "llama3_8b_w8a8"),
                     avg_launch_us=round(per[dom], 2), note=f"the M = {dom} call; M = 4096 (tiled kernel, MFMA bound): "
                     f"{2.0 * 4096 * N * K / per[4096] / 1e6:.0f} TOP/s = {2.0 * 4096 * N * K / per[4096] / 1e6 / MFMA_I8_PEAK_TOPS:.3f} of the int8 peak")
     peaks = measured_peaks(P, torch)
