@@ -297,6 +297,26 @@ def test_linear_fp16_activations(P, kernel, M, N, K):
     check_fs(host(out_fs), fs, f"M{M} N{N} K{K}")
 
 
+@pytest.mark.parametrize("M", [1, 100])
+@pytest.mark.parametrize("group", [256, 1024, 4096])
+def test_linear_fp16_wider_groups(P, kernel, M, group):
+    """Groups wider than a K step (several steps share a scale; group = K is the coarse-grained GEMM) and scales that
+    need 32-bit multiplies, through both one-call routes that quantise inside the GEMM."""
+    N, K = 272, 4096
+    rng = np.random.default_rng(7300 + group + M)
+    q = rng.integers(-8, 8, size=(N, K)).astype(np.int8)
+    qw = O.pack_int4(q)
+    c = (rng.random(N) * 0.05 + 1e-3).astype(np.float32)
+    x = S.activations_student_t(M, K, 7300 + M)
+    xq_ref, sa_ref = O.quantize_act_int8_token(x)
+    for IS in (rng.integers(0, 1025, size=(N, K // group)).astype(np.int32),
+               rng.integers(-2 ** 31, 2 ** 31, size=(N, K // group), dtype=np.int64).astype(np.int32)):
+        ref = O.gemm_w4a8_intscale(xq_ref, sa_ref, qw, IS, c, group, 10)
+        out, acc = P.is_linear_w4a8_intscale(dev(x), dev(qw), dev(IS), dev(c), group, 10, want_acc=True)
+        assert np.array_equal(host(acc), ref.acc), "int32 accumulators differ"
+        check_out(host(out), ref.out, f"M{M} group {group}")
+
+
 def test_linear_fp16_token_scale_and_zero_token(P):
     """The one-kernel route leaves the token's scale where the two-kernel route does, and an all-zero token gives
     scale 0 and an all-zero output."""
