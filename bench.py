@@ -185,15 +185,18 @@ def main():
         xs16 = -(-ng // 16) * spg
         waves = 16 if (mt == 1 or (mt == 2 and xs16 <= 2)) else 8
         xs = -(-ng // waves) * spg
-        fits = xs <= (6 if mt == 1 else (2 if waves == 16 else 8) if mt == 2 else 4)
-        if M <= 64 and waves <= ng and fits and 16 * ng <= 2 * waves * 64:
+        fits = xs <= ((10 if M == 1 else 6) if mt == 1 else (2 if waves == 16 else 8) if mt == 2 else 4)
+        if M <= 64 and waves <= ng and fits:
+            lds_operands = False
             if mt == 1:
-                xs_t, dt = (2, 4) if xs <= 2 else (4, 2) if xs <= 4 else (6, 1)
+                lds_operands = xs > 6             # one token, long K: operands read from LDS
+                xs_t, dt = (2, 4) if xs <= 2 else (4, 2) if xs <= 4 else (6, 1) if xs <= 6 else (10, 1)
             elif mt == 2:
                 xs_t, dt = (2, 4) if waves == 16 else (8, 1)
             else:
                 xs_t, dt = 4, 1
-            return f"gemm_decode_kernel<{mt}, {xs_t}, {dt}, {waves}, {tag}, {'true' if fused else 'false'}>"
+            return (f"gemm_decode_kernel<{mt}, {xs_t}, {dt}, {waves}, {tag}, {'true' if fused else 'false'}, "
+                    f"{'true' if lds_operands else 'false'}>")
         mt = 1 if M <= 16 else 2 if M <= 32 else 3 if M <= 48 else 4
         return f"gemm_skinny_kernel<{mt}, ...>"
 

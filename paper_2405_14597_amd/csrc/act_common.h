@@ -45,11 +45,34 @@ __device__ __forceinline__ int quant_code(float x, float s, float lo, float hi) 
 // ---------------------------------------------------------------------------------------------------------
 constexpr int kActThreads = 256;
 
-// Appendix A.1 codes of eight values: clamp(rne(x / s)) with the quotient rounded as a true division rounds it.
-// A division costs a dozen instructions, so the codes are first taken from t = x * (1 / s): t and the correctly rounded
-// quotient both lie within 1.6e-5 of x / s (|x / s| <= 127, three roundings of 2^-24), so whenever t is at least 5e-5
-// away from the nearest half-integer the two round to the same integer.  If any value of the wave comes closer, all
-// eight are redone with the division itself (about one chunk in thirty).
+// Appendix A.1 codes of N values of one token row: clamp(rne(x / s)) with the quotient rounded as a true division
+// rounds it.  A division costs a dozen instructions, so the codes are first taken from t = x * (1 / s): t and the
+// correctly rounded quotient both lie within 1.6e-5 of x / s (|x / s| <= 127, three roundings of 2^-24), so whenever t
+// is at least 5e-5 away from the nearest half-integer the two round to the same integer.  If any value of the wave
+// comes closer, all N are redone with the division itself (about one chunk of eight in thirty).
+template <int N>
+__device__ __forceinline__ void quant_codes(const float (&x)[N], float s, float (&q)[N]) {
+    if (s > 0.0f) {
+        const float r = 1.0f / s;
+        bool close = false;
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const float t = x[i] * r;
+            q[i] = rintf(t);
+            close |= fabsf(t - q[i]) > 0.49995f;
+        }
+        if (__any(close)) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) q[i] = rintf(x[i] / s);
+        }
+#pragma unroll
+        for (int i = 0; i < N; ++i) q[i] = fminf(fmaxf(q[i], -128.0f), 127.0f);
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) q[i] = 0.0f;
+    }
+}
+
 __device__ __forceinline__ uint2 quantize8(uint4 v, float s) {
     const __half2* h = reinterpret_cast<const __half2*>(&v);
     float x[8], q[8];
@@ -59,25 +82,7 @@ __device__ __forceinline__ uint2 quantize8(uint4 v, float s) {
         x[2 * i] = f.x;
         x[2 * i + 1] = f.y;
     }
-    if (s > 0.0f) {
-        const float r = 1.0f / s;
-        bool close = false;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const float t = x[i] * r;
-            q[i] = rintf(t);
-            close |= fabsf(t - q[i]) > 0.49995f;
-        }
-        if (__any(close)) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) q[i] = rintf(x[i] / s);
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) q[i] = fminf(fmaxf(q[i], -128.0f), 127.0f);
-    } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) q[i] = 0.0f;
-    }
+    quant_codes<8>(x, s, q);
     uint32_t packed[2] = {0u, 0u};
 #pragma unroll
     for (int i = 0; i < 8; ++i) packed[i >> 2] |= ((uint32_t)(int)q[i] & 0xFFu) << ((i & 3) * 8);

@@ -57,9 +57,13 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 // WAVES: waves per workgroup (16 leaves 128 vector registers per lane, 8 leaves 256).
 // FUSEQ: one fp16 token (M = 1) instead of quantised activations: the per-token quantiser of Appendix A.1 runs in the
 // prologue (every wave covers its own K slice, the absmax meets in LDS behind the barrier that is there anyway).
-template <int MT, int XS, int DT, int WAVES, bool INT_SCALE, bool FUSEQ = false>
+// XLDS: one token (M = 1) whose K slice per wave is too long to keep its operand registers for the whole kernel
+// (K from 12288 to 20480): the token's codes stay in LDS, one copy per workgroup, and every step reads its two operand
+// registers from there.
+template <int MT, int XS, int DT, int WAVES, bool INT_SCALE, bool FUSEQ = false, bool XLDS = false>
 __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, DecodePlan p) {
     static_assert(!FUSEQ || MT == 1, "the fused quantiser handles one token");
+    static_assert(!XLDS || MT == 1, "operands from LDS: one token");
     extern __shared__ __align__(16) unsigned char smem_raw[];
     using acc_t = typename std::conditional<INT_SCALE, int, float>::type;
 
@@ -116,7 +120,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     // out of every step), else per step on the scales just read (one token tile: an LDS read more per tile would
     // lengthen the chain of dependent latencies that bounds those shapes).
     constexpr bool kTileFlag = MT >= 2;
-    constexpr bool kStepRefill = DT == 1 && WAVES == 8;
+    constexpr bool kStepRefill = DT == 1 && (WAVES == 8 || XLDS);
     v4i wq[DT][XS];
     // words of a tile's 16 x NG block of scales each thread copies: NG <= XS * WAVES by construction of the plan
     constexpr int SJ = (16 * XS * WAVES + T - 1) / T;
@@ -169,13 +173,21 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     // while the others are still on their way.  (They are a few requests per lane; with one tile in flight, and the
     // long activation slices that go with it, the stream starts first instead.)
     constexpr bool kStageX = WAVES == 8 && MT == 4;
-    constexpr bool kXFirst = DT >= 2 && !kStageX && !FUSEQ;
+    constexpr bool kXFirst = DT >= 2 && !kStageX && !FUSEQ && !XLDS;
     // fused quantiser: lane l takes k = 2l, 2l+1 of every step of its wave's K slice (two fp16 values, one word)
     [[maybe_unused]] int xh[XS];
     if constexpr (FUSEQ) {
 #pragma unroll
         for (int i = 0; i < XS; ++i)
             xh[i] = __builtin_amdgcn_raw_buffer_load_b32(xres, i < ns ? ((s0 + i) * kStepK + 2 * lane) * 2 : kOutOfRange, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // operands from LDS, quantised token in: the same two values per lane and step, as codes (one 16-bit word)
+    [[maybe_unused]] int xb[XLDS && !FUSEQ ? XS : 1];
+    if constexpr (XLDS && !FUSEQ) {
+#pragma unroll
+        for (int i = 0; i < XS; ++i)
+            xb[i] = __builtin_amdgcn_raw_buffer_load_b16(xres, i < ns ? (s0 + i) * kStepK + 2 * lane : kOutOfRange, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
     }
     [[maybe_unused]] v4i xr0[kXFirst ? XS : 1][kXFirst ? MT : 1], xr1[kXFirst ? XS : 1][kXFirst ? MT : 1];
@@ -200,7 +212,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
     __builtin_amdgcn_sched_barrier(0);  // keep the compiler from hoisting the activation loads above the stream's
 
     // ---- activations of this wave's K range, MFMA-ready, loaded once
-    v4i x_even[XS][MT], x_odd[XS][MT];
+    v4i x_even[XLDS ? 1 : XS][MT], x_odd[XLDS ? 1 : XS][MT];
     // With 64 token rows a workgroup reads 64 x K bytes of activations, several times its share of the weights, and
     // the operand layout (a lane takes 2 x 16 bytes of one of 16 rows a whole row apart) is a poor way to fetch them:
     // there the wave fetches 16 rows at a time the coalesced way (consecutive lanes, consecutive 16 bytes of a row's
@@ -266,7 +278,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
 #pragma unroll
     for (int i = 0; i < XS; ++i)
 #pragma unroll
-        for (int t = 0; t < (kStageX || FUSEQ ? 0 : MT); ++t) {
+        for (int t = 0; t < (kStageX || FUSEQ || XLDS ? 0 : MT); ++t) {
             v4i x0, x1;
             if constexpr (kXFirst) {
                 x0 = xr0[i][t];
@@ -315,7 +327,7 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
         asm volatile("" : "+v"(f));  // worked out here every time rather than held in registers throughout
 #pragma unroll
         for (int j = 0; j < SJ; ++j, f += T) {
-            // r = f / NG for f < 2048, NG <= 128: (f + 0.5) / NG is at least 0.5 / NG away from an integer, far more
+            // r = f / NG for f < 4096, NG <= 224: (f + 0.5) / NG is at least 0.5 / NG away from an integer, far more
             // than the rounding error of the float arithmetic
             const int r = (int)fmaf((float)f, inv_ng, half_inv_ng);
             if (f < 16 * NG) lds_scale[buf * scale_ints + f + r] = scv[slot][j];
@@ -336,29 +348,41 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
         stage_scales(0, 0);
         if (SD < my_tiles) issue_scales(0, tile0 + SD * G);
         lds_barrier();
+        if constexpr (XLDS && !FUSEQ) {
+            // the codes of this wave's K slice, even k and odd k apart, in its own piece of LDS
+#pragma unroll
+            for (int i = 0; i < XS; ++i) {
+                qstage[i * 128 + lane] = (signed char)(xb[i] & 0xFF);
+                qstage[i * 128 + 64 + lane] = (signed char)((xb[i] >> 8) & 0xFF);
+            }
+        }
         if constexpr (FUSEQ) {
-            // Appendix A.1, n = 8: s_a = absmax / 127 and codes clamp(rne(x / s_a)), a true division as in the
-            // stand-alone quantiser.  The codes of the wave's slice go through its own piece of LDS into the operand
+            // Appendix A.1, n = 8: s_a = absmax / 127 and codes clamp(rne(x / s_a)), rounded as the true quotient
+            // rounds, as in the stand-alone quantiser.  The codes of the wave's slice go through its own piece of LDS into the operand
             // layout.  (Behind the barrier that publishes the first tile's scales: a barrier of its own, earlier, was slower.)
-            static_assert(!FUSEQ || W == 16, "one absmax word per wave, read by lane & 15");
+            static_assert(!FUSEQ || (W <= 16 && (W & (W - 1)) == 0), "one absmax word per wave, read by lane & (W - 1)");
             const float amax = wave_max(lds_amax[lane & (W - 1)]);
             const float s_a = amax / 127.0f;
+            float xv[2 * XS], qv[2 * XS];
 #pragma unroll
             for (int i = 0; i < XS; ++i) {
-                int q0 = 0, q1 = 0;
-                if (s_a > 0.0f) {
-                    q0 = quant_code(xf0[i], s_a, -128.0f, 127.0f);
-                    q1 = quant_code(xf1[i], s_a, -128.0f, 127.0f);
-                }
-                qstage[i * 128 + lane] = (signed char)q0;
-                qstage[i * 128 + 64 + lane] = (signed char)q1;
+                xv[2 * i] = xf0[i];
+                xv[2 * i + 1] = xf1[i];
             }
+            quant_codes<2 * XS>(xv, s_a, qv);
 #pragma unroll
             for (int i = 0; i < XS; ++i) {
-                // every lane of a K slice takes the token's codes: operand rows 1..15 then repeat row 0, and their
-                // results are never written (there is one token)
-                x_even[i][0] = *reinterpret_cast<const v4i*>(qstage + i * 128 + kb * 16);
-                x_odd[i][0] = *reinterpret_cast<const v4i*>(qstage + i * 128 + 64 + kb * 16);
+                qstage[i * 128 + lane] = (signed char)(int)qv[2 * i];
+                qstage[i * 128 + 64 + lane] = (signed char)(int)qv[2 * i + 1];
+            }
+            if constexpr (!XLDS) {
+#pragma unroll
+                for (int i = 0; i < XS; ++i) {
+                    // every lane of a K slice takes the token's codes: operand rows 1..15 then repeat row 0, and their
+                    // results are never written (there is one token)
+                    x_even[i][0] = *reinterpret_cast<const v4i*>(qstage + i * 128 + kb * 16);
+                    x_odd[i][0] = *reinterpret_cast<const v4i*>(qstage + i * 128 + 64 + kb * 16);
+                }
             }
 #pragma unroll
             for (int o = 0; o < OPT; ++o) sa_out[o] = writer[o] ? s_a : 0.0f;
@@ -418,8 +442,19 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
                         v4i part[MT];
 #pragma unroll
                         for (int t = 0; t < MT; ++t) {
-                            part[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(x_even[i][t], w_even, v4i{0, 0, 0, 0}, 0, 0, 0);
-                            part[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(x_odd[i][t], w_odd, part[t], 0, 0, 0);
+                            if constexpr (XLDS) {
+                                // (the offset is opaque so that these reads are not hoisted out of the tile loop and
+                                // kept in registers for all steps, which is what does not fit)
+                                int qoff = i * 128 + kb * 16;
+                                asm volatile("" : "+v"(qoff));
+                                const v4i xe = *reinterpret_cast<const v4i*>(qstage + qoff);
+                                const v4i xo = *reinterpret_cast<const v4i*>(qstage + qoff + 64);
+                                part[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xe, w_even, v4i{0, 0, 0, 0}, 0, 0, 0);
+                                part[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xo, w_odd, part[t], 0, 0, 0);
+                            } else {
+                                part[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(x_even[i][t], w_even, v4i{0, 0, 0, 0}, 0, 0, 0);
+                                part[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(x_odd[i][t], w_odd, part[t], 0, 0, 0);
+                            }
                         }
                         if constexpr (!INT_SCALE) {
 #pragma unroll
@@ -502,14 +537,14 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
 
 }
 
-template <int MT, int XS, int DT, int WAVES, bool INT_SCALE, bool FUSEQ = false>
+template <int MT, int XS, int DT, int WAVES, bool INT_SCALE, bool FUSEQ = false, bool XLDS = false>
 hipError_t launch_decode(const GemmArgs& a, const DecodePlan& p, int grid, hipStream_t stream) {
     // partial accumulators, group scales, wide-scale words, activation staging (64 token rows)
     const size_t smem = 2 * (size_t)WAVES * MT * kWave * 16 + 2 * 16 * (size_t)(p.num_groups + 1) * 4 +
                         2 * (size_t)WAVES * 4 +
                         (WAVES == 8 && MT == 4 ? (size_t)WAVES * XS * 2048 : 0) +
-                        (FUSEQ ? (size_t)WAVES * (4 + XS * 128) : 0);
-    auto kern = gemm_decode_kernel<MT, XS, DT, WAVES, INT_SCALE, FUSEQ>;
+                        (FUSEQ || XLDS ? (size_t)WAVES * (4 + XS * 128) : 0);
+    auto kern = gemm_decode_kernel<MT, XS, DT, WAVES, INT_SCALE, FUSEQ, XLDS>;
     if (smem > 64 * 1024) {
         static bool raised = false;  // per instantiation
         if (!raised) {
@@ -525,6 +560,10 @@ hipError_t launch_decode(const GemmArgs& a, const DecodePlan& p, int grid, hipSt
 
 template <bool INT_SCALE>
 hipError_t dispatch(const GemmArgs& a, const DecodePlan& p, int mt, int xs, int grid, hipStream_t stream) {
+    if (mt == 1 && xs > 6) {  // one token, a long K slice per wave: operands from LDS (quantised or fp16 token)
+        if (a.x_fp16) return launch_decode<1, 10, 1, 16, INT_SCALE, true, true>(a, p, grid, stream);
+        return launch_decode<1, 10, 1, 16, INT_SCALE, false, true>(a, p, grid, stream);
+    }
     if (a.x_fp16) {  // one fp16 token, quantised in the kernel
         if (xs <= 2) return launch_decode<1, 2, 4, 16, INT_SCALE, true>(a, p, grid, stream);
         if (xs <= 4) return launch_decode<1, 4, 2, 16, INT_SCALE, true>(a, p, grid, stream);
@@ -558,8 +597,10 @@ bool try_launch_gemm_decode(const GemmArgs& a, bool int_scale, hipStream_t strea
     const int waves = (mt == 1 || (mt == 2 && xs16 <= 2)) ? 16 : 8;
     if (waves > NG) return false;
     const int xs = ((NG + waves - 1) / waves) * spg;
-    if (xs > (mt == 1 ? 6 : mt == 2 ? (waves == 16 ? 2 : 8) : 4)) return false;
-    if (16 * NG > 2 * waves * kWave) return false;  // at most two words per thread stage a tile's group scales
+    // one token: up to 10 steps per wave with the operands in LDS (K up to 20480)
+    if (xs > (mt == 1 ? (a.M == 1 ? 10 : 6) : mt == 2 ? (waves == 16 ? 2 : 8) : 4)) return false;
+    // (a tile's 16 x NG group scales are staged by the workgroup's threads, ceil(16 XS WAVES / threads) words each:
+    // NG <= XS * WAVES / spg by construction)
     DecodePlan p;
     p.tiles = (a.N + 15) / 16;
     p.waves = waves;

@@ -127,7 +127,7 @@ def test_weight_quantizer_amplifier_search(P, mode):
 
 
 # ------------------------------------------------------------------------------------------------ GEMM, oracle-quantised inputs
-SHAPES = [(1, 16, 128), (1, 4096, 4096), (8, 4096, 4096), (16, 272, 1024), (17, 40, 1024), (33, 100, 2048),
+SHAPES = [(1, 16, 128), (1, 4096, 4096), (1, 4096, 14336), (1, 100, 20480), (1, 4200, 12416), (8, 4096, 4096), (16, 272, 1024), (17, 40, 1024), (33, 100, 2048),
           (64, 4096, 1024), (64, 48, 11008), (100, 33, 1536), (7, 1, 256), (48, 2064, 3584),
           (65, 256, 128), (129, 300, 1024), (256, 512, 2048), (300, 700, 1152), (513, 257, 512),
           # several 16-row tiles per workgroup in every decode variant (more than 256 tiles)
@@ -277,6 +277,8 @@ def test_gemm_repeatable(P):
 # beyond the decode kernel, and several tokens (quantiser kernel + GEMM)
 LINEAR_SHAPES = [(1, 4096, 4096), (1, 12288, 4096), (1, 4096, 8192), (1, 4096, 11008), (1, 272, 12288), (1, 40, 1024),
                  (1, 16, 128), (1, 8208, 2048), (1, 64, 28672), (8, 4096, 4096), (100, 300, 1024), (64, 48, 11008),
+                 # one token, K slices of 7 to 10 steps per wave: the operands stay in LDS
+                 (1, 4096, 14336), (1, 272, 20480), (1, 4360, 13312),
                  # more than 64 tokens: the tiled kernel's preparation quantises on the way (rows of 4, 8 and 16 chunks
                  # per lane, a ragged last row tile), and rows too long for that (quantiser kernel first)
                  (130, 512, 4096), (70, 272, 8192), (200, 256, 14336), (66, 128, 28672), (257, 40, 2048)]
