@@ -45,6 +45,8 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=32, help="distinct weight copies per linear (LLaMA-2-7B has 32 layers)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-floatscale", action="store_true", help="skip the float-scale comparison pass")
+    ap.add_argument("--coarse", action="store_true",
+                    help="prefill workload: coarse-grained weights, one group per weight row (the paper's upper bound)")
     ap.add_argument("--no-fused-token", action="store_true",
                     help="M = 1: quantiser kernel + GEMM kernel instead of the one-kernel linear call")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
@@ -427,13 +429,14 @@ def prefill_main(args):
     data = []
     for idx, (name, (K, N)) in enumerate(linears):
         w = torch.from_numpy(S.make_weights(3, N, K, S.seed_for(3, idx, 1))).to(dev)
-        qw = P.is_quantize_weights_int4_group(w, GROUP, ALPHA_LOG2, P.IS_SCALE_NORM)
+        grp = K if args.coarse else GROUP   # --coarse: one group per weight row (Table 2, first column)
+        qw = P.is_quantize_weights_int4_group(w, grp, ALPHA_LOG2, P.IS_SCALE_NORM)
         del w
         x = torch.from_numpy(S.make_activations(3, M, K, S.seed_for(3, idx, 2))).to(dev)
-        data.append(dict(name=name, K=K, N=N, qw=qw, x=x, xq=torch.empty((M, K), dtype=torch.int8, device=dev),
+        data.append(dict(name=name, K=K, N=N, G=grp, qw=qw, x=x, xq=torch.empty((M, K), dtype=torch.int8, device=dev),
                          sa=torch.empty((M,), dtype=torch.float32, device=dev),
                          out=torch.empty((M, N), dtype=torch.float16, device=dev),
-                         ws=torch.empty(P.is_gemm_workspace_bytes(M, N, K, GROUP), dtype=torch.uint8, device=dev)))
+                         ws=torch.empty(P.is_gemm_workspace_bytes(M, N, K, grp), dtype=torch.uint8, device=dev)))
     torch.cuda.synchronize()
 
     def quant(d):
@@ -441,12 +444,12 @@ def prefill_main(args):
 
     def gemm_is(d):
         q = d["qw"]
-        P.is_gemm_w4a8_intscale(d["xq"], d["sa"], q.qweight, q.scale_i32, q.chan_scale, GROUP, ALPHA_LOG2, out=d["out"],
+        P.is_gemm_w4a8_intscale(d["xq"], d["sa"], q.qweight, q.scale_i32, q.chan_scale, d["G"], ALPHA_LOG2, out=d["out"],
                                 workspace=d["ws"])
 
     def gemm_fs(d):
         q = d["qw"]
-        P.is_gemm_w4a8_floatscale(d["xq"], d["sa"], q.qweight, q.scale_f32, GROUP, out=d["out"], workspace=d["ws"])
+        P.is_gemm_w4a8_floatscale(d["xq"], d["sa"], q.qweight, q.scale_f32, d["G"], out=d["out"], workspace=d["ws"])
 
     def timed(fns, steps, warmup):
         """fns: list of (label, callable); returns seconds per step and per-label average milliseconds."""
@@ -474,7 +477,7 @@ def prefill_main(args):
 
     def linear_is(d):
         q = d["qw"]
-        P.is_linear_w4a8_intscale(d["x"], q.qweight, q.scale_i32, q.chan_scale, GROUP, ALPHA_LOG2, out=d["out"],
+        P.is_linear_w4a8_intscale(d["x"], q.qweight, q.scale_i32, q.chan_scale, d["G"], ALPHA_LOG2, out=d["out"],
                                   workspace=d["lws"])
 
     # One step: every linear on its fp16 activations through the linear call (quantiser inside the tiled kernel's
@@ -485,7 +488,7 @@ def prefill_main(args):
             fns.append((f"quant_{d['name']}", lambda d=d: quant(d)))
             fns.append((f"gemm_{d['name']}", lambda d=d: gemm_is(d)))
         else:
-            d["lws"] = torch.empty(P.is_linear_workspace_bytes(M, d["N"], d["K"], GROUP), dtype=torch.uint8, device=dev)
+            d["lws"] = torch.empty(P.is_linear_workspace_bytes(M, d["N"], d["K"], d["G"]), dtype=torch.uint8, device=dev)
             fns.append((f"linear_{d['name']}", lambda d=d: linear_is(d)))
     sec_per_step, per_step = timed(fns, args.steps, args.warmup)
     # the GEMM calls alone (quantised activations in), for the roofline figure of the tile kernel
@@ -504,7 +507,7 @@ def prefill_main(args):
                            quant_us=round(1e3 * per[f"quant_{d['name']}"], 2),
                            step_call_us=round(1e3 * sum(v for k, v in per_step.items() if k.endswith("_" + d["name"])), 2)))
     achieved = gemm_ops / gemm_ms / 1e9
-    kernel = "gemm_prefill_kernel<true, false>"
+    kernel = "gemm_prefill_kernel<true, true>" if args.coarse else "gemm_prefill_kernel<true, false>"
     roofline = dict(bound="mfma", kernel=kernel, achieved=round(achieved, 1), peak=MFMA_I8_PEAK_TOPS, unit="TOP/s",
                     frac=round(achieved / MFMA_I8_PEAK_TOPS, 4), traffic=measured_traffic(kernel, "llama3_8b_prefill"),
                     avg_launch_us=round(1e3 * gemm_ms / len(data), 2),
@@ -529,18 +532,18 @@ def prefill_main(args):
         ok_all, rel_all = True, 0.0
         for idx, d in enumerate(data):
             K, N = d["K"], d["N"]
-            hw = O.quantize_weights_int4_group(S.make_weights(3, N, K, S.seed_for(3, idx, 1)), GROUP, ALPHA_LOG2,
+            hw = O.quantize_weights_int4_group(S.make_weights(3, N, K, S.seed_for(3, idx, 1)), d["G"], ALPHA_LOG2,
                                                O.SCALE_NORM)
             hx = S.make_activations(3, M, K, S.seed_for(3, idx, 2))
             t0 = time.perf_counter()
             xq, sa = O.quantize_act_int8_token(hx)
-            ref = O.gemm_w4a8_intscale(xq, sa, hw.qweight, hw.scale_i32, hw.chan_scale, GROUP, ALPHA_LOG2)
+            ref = O.gemm_w4a8_intscale(xq, sa, hw.qweight, hw.scale_i32, hw.chan_scale, d["G"], ALPHA_LOG2)
             dt += time.perf_counter() - t0
             cpu_ops += S.algorithmic_ops(M, N, K)
             # the oracle result doubles as a live parity check of the GPU path
             quant(d)
             q = d["qw"]
-            out, acc = P.is_gemm_w4a8_intscale(d["xq"], d["sa"], q.qweight, q.scale_i32, q.chan_scale, GROUP,
+            out, acc = P.is_gemm_w4a8_intscale(d["xq"], d["sa"], q.qweight, q.scale_i32, q.chan_scale, d["G"],
                                                ALPHA_LOG2, want_acc=True)
             torch.cuda.synchronize()
             ok_all = ok_all and bool(np.array_equal(acc.cpu().numpy(), ref.acc))
@@ -565,7 +568,8 @@ def prefill_main(args):
         "vs_baseline": None,
         "dtype": "int8",
         "data": "synthetic",
-        "config": {"workload": f"llama3-8b prefill linears (qkv, gate_up, down) at M={M} Student-t token rows, W4 group-128 "
+        "config": {"workload": f"llama3-8b prefill linears (qkv, gate_up, down) at M={M} Student-t token rows, W4 "
+                               f"{'coarse-grained (one group per weight row)' if args.coarse else 'group-128'} "
                                f"x A8 per-token, alpha=2^{ALPHA_LOG2}", "launch": "eager", "scale_mode": "norm"},
         "mfma_frac": round(value / MFMA_I8_PEAK_TOPS, 4),
         "speedup_vs_floatscale": None if speedup is None else round(speedup, 4),
