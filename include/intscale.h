@@ -124,7 +124,7 @@ int is_gemm_w4a8_floatscale(const int8_t* xq, const float* a_scale, const void* 
  * The linear layer on fp16 activations: is_quantize_act_int8_token followed by is_gemm_w4a8_intscale (or the
  * float-scale twin), behind one call and with the same results to the bit (Appendix A.1 per token, then Eq. (2) or
  * Eq. (1)).  For one token (M = 1, a decode step at batch 1) whose K the decode kernel covers, the quantiser runs
- * inside the GEMM kernel and no other kernel is launched; for more than 64 tokens with K <= 16384 the tiled kernel's
+ * inside the GEMM kernel and no other kernel is launched; for more than 64 tokens with K <= 32768 the tiled kernel's
  * activation preparation quantises on the way; otherwise the two kernels run one after the other.
  *   x_fp16 in fp16 [M,K], K a multiple of 8;  the other arguments as for the GEMMs
  *   workspace    device scratch of at least is_linear_workspace_bytes(M,N,K,group) bytes (never 0 for M > 0): it

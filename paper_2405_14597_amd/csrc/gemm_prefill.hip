@@ -108,18 +108,23 @@ __global__ __launch_bounds__(256) void prepare_activations_kernel(const int8_t* 
 }
 
 // The same preparation straight from fp16 activations (the linear call): the per-token quantiser of Appendix A.1 and
-// the preparation in one pass, one wave per token row, the row held in registers (CH chunks of 16 values per lane)
-// between the absmax and the rounding.  Saves writing the canonical codes and reading them back.
-template <int CH>
+// the preparation in one pass, the row held in registers (CH chunks of 16 values per lane) between the absmax and the
+// rounding.  Saves writing the canonical codes and reading them back.  WPR waves share a token row: one (four rows per
+// workgroup) for rows of up to 4096 values, four (a workgroup per row) beyond, so that a lane never holds more than
+// 8 chunks and enough waves fit a SIMD to hide the memory latency.
+template <int CH, int WPR>
 __global__ __launch_bounds__(256) void quantize_prepare_activations_kernel(const __half* __restrict__ x, int M, int K,
                                                                            int8_t* __restrict__ xp,
                                                                            int32_t* __restrict__ s8,
                                                                            float* __restrict__ a_scale,
                                                                            int32_t* __restrict__ wide_flag) {
+    static_assert(WPR == 1 || WPR == 4, "a wave or a workgroup per token row");
+    __shared__ float red[4];
     if (blockIdx.x == 0 && threadIdx.x == 0) *wide_flag = 0;
-    const int m = blockIdx.x * 4 + threadIdx.x / kWave;
-    if (m >= M) return;
-    const int lane = threadIdx.x & (kWave - 1);
+    constexpr int kLanes = WPR * kWave;  // lanes per token row
+    const int m = WPR == 1 ? blockIdx.x * 4 + threadIdx.x / kWave : blockIdx.x;
+    if (m >= M) return;  // uniform over the wave (WPR = 1) or the workgroup (WPR = 4)
+    const int lane = threadIdx.x & (kLanes - 1);
     const uint4* row = reinterpret_cast<const uint4*>(x + (size_t)m * K);  // 8 fp16 values each
     uint4* prow = reinterpret_cast<uint4*>(xp + (size_t)m * K);
     const int nchunk = K >> 4;
@@ -127,18 +132,19 @@ __global__ __launch_bounds__(256) void quantize_prepare_activations_kernel(const
     float amax = 0.0f;
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
-        const int c = lane + j * kWave;
+        const int c = lane + j * kLanes;
         v[j][0] = c < nchunk ? row[2 * c] : make_uint4(0u, 0u, 0u, 0u);
         v[j][1] = c < nchunk ? row[2 * c + 1] : make_uint4(0u, 0u, 0u, 0u);
     }
 #pragma unroll
     for (int j = 0; j < CH; ++j) amax = fmaxf(amax, fmaxf(absmax8(v[j][0]), absmax8(v[j][1])));
-    amax = wave_max(amax);
+    if constexpr (WPR == 1) amax = wave_max(amax);
+    else amax = block_max<4>(amax, red);
     const float s = amax / 127.0f;
     if (lane == 0) a_scale[m] = s;
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
-        const int c = lane + j * kWave;
+        const int c = lane + j * kLanes;
         int sum = 0;
         if (c < nchunk) {
             const uint2 lo = quantize8(v[j][0], s), hi = quantize8(v[j][1], s);  // the canonical 16 codes, in k order
@@ -579,8 +585,8 @@ size_t gemm_prefill_workspace_bytes(int num_experts, int M, int N, int K, int gr
     return header_bytes(num_experts, M) + corrections_bytes(M, K) + scales_bytes(num_experts, N, K, group) + (size_t)M * K;
 }
 
-// rows the fused quantiser + preparation holds in registers: 16 chunks of 16 values per lane
-bool gemm_prefill_takes_fp16(int K) { return (K & 15) == 0 && (K >> 4) <= 16 * kWave; }
+// rows the fused quantiser + preparation holds in registers: 8 chunks of 16 values per lane, 256 lanes
+bool gemm_prefill_takes_fp16(int K) { return (K & 15) == 0 && (K >> 4) <= 8 * 256; }
 
 hipError_t launch_gemm_prefill(const GemmArgs& a, bool int_scale, void* workspace, hipStream_t stream) {
     const int experts = a.row_offsets ? a.num_experts : 1;
@@ -594,17 +600,14 @@ hipError_t launch_gemm_prefill(const GemmArgs& a, bool int_scale, void* workspac
     int8_t* xp = reinterpret_cast<int8_t*>(ws + header + corrections_bytes(a.M, a.K) +
                                            scales_bytes(experts, a.N, a.K, a.group));
     if (a.x_fp16) {  // fp16 activations (plain form only): quantised on the way, the token scales go to a.a_scale_out
-        const dim3 pgrid((a.M + 3) / 4), pblock(256);
-        const int chunks_per_lane = ((a.K >> 4) + kWave - 1) / kWave;
-        if (chunks_per_lane <= 4)
-            hipLaunchKernelGGL(quantize_prepare_activations_kernel<4>, pgrid, pblock, 0, stream, a.x_fp16, a.M, a.K, xp, s8,
-                               a.a_scale_out, flag);
-        else if (chunks_per_lane <= 8)
-            hipLaunchKernelGGL(quantize_prepare_activations_kernel<8>, pgrid, pblock, 0, stream, a.x_fp16, a.M, a.K, xp, s8,
-                               a.a_scale_out, flag);
-        else
-            hipLaunchKernelGGL(quantize_prepare_activations_kernel<16>, pgrid, pblock, 0, stream, a.x_fp16, a.M, a.K, xp, s8,
-                               a.a_scale_out, flag);
+        const int nchunk = a.K >> 4;
+#define QP_LAUNCH(CH, WPR, GRID) \
+    hipLaunchKernelGGL((quantize_prepare_activations_kernel<CH, WPR>), dim3(GRID), dim3(256), 0, stream, a.x_fp16, a.M, \
+                       a.K, xp, s8, a.a_scale_out, flag)
+        if (nchunk <= 4 * kWave) QP_LAUNCH(4, 1, (a.M + 3) / 4);
+        else if (nchunk <= 4 * 256) QP_LAUNCH(4, 4, a.M);
+        else QP_LAUNCH(8, 4, a.M);
+#undef QP_LAUNCH
     } else {
         hipLaunchKernelGGL(prepare_activations_kernel, dim3((a.M + 3) / 4), dim3(256), 0, stream, a.xq, a.M, a.K, xp, s8,
                            flag, a.row_offsets, experts, tile_table);

@@ -279,9 +279,11 @@ LINEAR_SHAPES = [(1, 4096, 4096), (1, 12288, 4096), (1, 4096, 8192), (1, 4096, 1
                  (1, 16, 128), (1, 8208, 2048), (1, 64, 28672), (8, 4096, 4096), (100, 300, 1024), (64, 48, 11008),
                  # one token, K slices of 7 to 10 steps per wave: the operands stay in LDS
                  (1, 4096, 14336), (1, 272, 20480), (1, 4360, 13312),
-                 # more than 64 tokens: the tiled kernel's preparation quantises on the way (rows of 4, 8 and 16 chunks
-                 # per lane, a ragged last row tile), and rows too long for that (quantiser kernel first)
-                 (130, 512, 4096), (70, 272, 8192), (200, 256, 14336), (66, 128, 28672), (257, 40, 2048)]
+                 # more than 64 tokens: the tiled kernel's preparation quantises on the way (a wave per row; a workgroup
+                 # per row with 4 and 8 chunks per lane; a ragged last row tile), and rows too long for that (quantiser
+                 # kernel first)
+                 (130, 512, 4096), (70, 272, 8192), (200, 256, 14336), (66, 128, 28672), (257, 40, 2048),
+                 (70, 48, 40960)]
 
 
 @pytest.mark.parametrize("M,N,K", LINEAR_SHAPES)
