@@ -57,7 +57,7 @@ constexpr int kSwzB = INTSCALE_SWZ_B;  // weight rows (64 B): 16-byte chunk inde
 __device__ __forceinline__ int pick_even(uint32_t lo, uint32_t hi) { return (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u); }
 __device__ __forceinline__ int pick_odd(uint32_t lo, uint32_t hi) { return (int)__builtin_amdgcn_perm(hi, lo, 0x07050301u); }
 
-// Preparation, one wave per token row: xp = the activations with every 16-byte chunk reordered to
+// Preparation, one workgroup per token row: xp = the activations with every 16-byte chunk reordered to
 // [even | even | odd | odd] (see the top of the file), and s8[step][m] = -8 * sum over the 128 k of the step of
 // xq[m,k], the zero-point correction of the q + 8 weight bytes (8 lanes share a step).
 __global__ __launch_bounds__(256) void prepare_activations_kernel(const int8_t* __restrict__ xq, int M, int K,
@@ -78,13 +78,12 @@ __global__ __launch_bounds__(256) void prepare_activations_kernel(const int8_t* 
         }
         for (; slot < slots; ++slot) tile_table[slot] = make_int2(-1, 0);
     }
-    const int m = blockIdx.x * 4 + threadIdx.x / kWave;
-    if (m >= M) return;
-    const int lane = threadIdx.x & (kWave - 1);
+    const int m = blockIdx.x;
+    const int lane = threadIdx.x;
     const uint4* row = reinterpret_cast<const uint4*>(xq + (size_t)m * K);
     uint4* prow = reinterpret_cast<uint4*>(xp + (size_t)m * K);
     const int nchunk = K >> 4;
-    for (int c0 = 0; c0 < nchunk; c0 += kWave) {
+    for (int c0 = 0; c0 < nchunk; c0 += 256) {
         const int c = c0 + lane;
         int sum = 0;
         if (c < nchunk) {
@@ -108,23 +107,20 @@ __global__ __launch_bounds__(256) void prepare_activations_kernel(const int8_t* 
 }
 
 // The same preparation straight from fp16 activations (the linear call): the per-token quantiser of Appendix A.1 and
-// the preparation in one pass, the row held in registers (CH chunks of 16 values per lane) between the absmax and the
-// rounding.  Saves writing the canonical codes and reading them back.  WPR waves share a token row: one (four rows per
-// workgroup) for rows of up to 4096 values, four (a workgroup per row) beyond, so that a lane never holds more than
-// 8 chunks and enough waves fit a SIMD to hide the memory latency.
-template <int CH, int WPR>
+// the preparation in one pass, a workgroup per token row, the row held in registers (CH chunks of 16 values per lane)
+// between the absmax and the rounding.  Saves writing the canonical codes and reading them back.  (A wave per row, as
+// in the preparation above, keeps four times the registers per lane and was slower.)
+template <int CH>
 __global__ __launch_bounds__(256) void quantize_prepare_activations_kernel(const __half* __restrict__ x, int M, int K,
                                                                            int8_t* __restrict__ xp,
                                                                            int32_t* __restrict__ s8,
                                                                            float* __restrict__ a_scale,
                                                                            int32_t* __restrict__ wide_flag) {
-    static_assert(WPR == 1 || WPR == 4, "a wave or a workgroup per token row");
     __shared__ float red[4];
     if (blockIdx.x == 0 && threadIdx.x == 0) *wide_flag = 0;
-    constexpr int kLanes = WPR * kWave;  // lanes per token row
-    const int m = WPR == 1 ? blockIdx.x * 4 + threadIdx.x / kWave : blockIdx.x;
-    if (m >= M) return;  // uniform over the wave (WPR = 1) or the workgroup (WPR = 4)
-    const int lane = threadIdx.x & (kLanes - 1);
+    constexpr int kLanes = 256;  // lanes per token row
+    const int m = blockIdx.x;
+    const int lane = threadIdx.x;
     const uint4* row = reinterpret_cast<const uint4*>(x + (size_t)m * K);  // 8 fp16 values each
     uint4* prow = reinterpret_cast<uint4*>(xp + (size_t)m * K);
     const int nchunk = K >> 4;
@@ -138,8 +134,7 @@ __global__ __launch_bounds__(256) void quantize_prepare_activations_kernel(const
     }
 #pragma unroll
     for (int j = 0; j < CH; ++j) amax = fmaxf(amax, fmaxf(absmax8(v[j][0]), absmax8(v[j][1])));
-    if constexpr (WPR == 1) amax = wave_max(amax);
-    else amax = block_max<4>(amax, red);
+    amax = block_max<4>(amax, red);
     const float s = amax / 127.0f;
     if (lane == 0) a_scale[m] = s;
 #pragma unroll
@@ -601,15 +596,16 @@ hipError_t launch_gemm_prefill(const GemmArgs& a, bool int_scale, void* workspac
                                            scales_bytes(experts, a.N, a.K, a.group));
     if (a.x_fp16) {  // fp16 activations (plain form only): quantised on the way, the token scales go to a.a_scale_out
         const int nchunk = a.K >> 4;
-#define QP_LAUNCH(CH, WPR, GRID) \
-    hipLaunchKernelGGL((quantize_prepare_activations_kernel<CH, WPR>), dim3(GRID), dim3(256), 0, stream, a.x_fp16, a.M, \
-                       a.K, xp, s8, a.a_scale_out, flag)
-        if (nchunk <= 4 * kWave) QP_LAUNCH(4, 1, (a.M + 3) / 4);
-        else if (nchunk <= 4 * 256) QP_LAUNCH(4, 4, a.M);
-        else QP_LAUNCH(8, 4, a.M);
+#define QP_LAUNCH(CH, GRID) \
+    hipLaunchKernelGGL(quantize_prepare_activations_kernel<CH>, dim3(GRID), dim3(256), 0, stream, a.x_fp16, a.M, a.K, xp, \
+                       s8, a.a_scale_out, flag)
+        if (nchunk <= 256) QP_LAUNCH(1, a.M);
+        else if (nchunk <= 2 * 256) QP_LAUNCH(2, a.M);
+        else if (nchunk <= 4 * 256) QP_LAUNCH(4, a.M);
+        else QP_LAUNCH(8, a.M);
 #undef QP_LAUNCH
     } else {
-        hipLaunchKernelGGL(prepare_activations_kernel, dim3((a.M + 3) / 4), dim3(256), 0, stream, a.xq, a.M, a.K, xp, s8,
+        hipLaunchKernelGGL(prepare_activations_kernel, dim3(a.M), dim3(256), 0, stream, a.xq, a.M, a.K, xp, s8,
                            flag, a.row_offsets, experts, tile_table);
     }
     const dim3 sgrid((a.N + 63) / 64, (NG + 63) / 64, experts);
