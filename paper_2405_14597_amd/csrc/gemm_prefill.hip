@@ -45,14 +45,8 @@ constexpr int kStages = 4;  // LDS ring; tiles are requested kStages - 1 steps a
 constexpr int kTileLoads = 4;  // buffer-to-LDS loads per wave and step: 2 activation, 2 weight (+1 on waves 0 and 1)
 constexpr int kXBytes = kBM * 128, kWBytes = kBN * 64, kAuxBytes = 2048;  // aux: 256 scales, 128 corrections
 constexpr int kStageBytes = kXBytes + kWBytes + kAuxBytes;
-#ifndef INTSCALE_SWZ_A
-#define INTSCALE_SWZ_A 1
-#endif
-#ifndef INTSCALE_SWZ_B
-#define INTSCALE_SWZ_B 1
-#endif
-constexpr int kSwzA = INTSCALE_SWZ_A;  // activation rows (128 B): 16-byte chunk index ^= (row >> kSwzA) & 7
-constexpr int kSwzB = INTSCALE_SWZ_B;  // weight rows (64 B): 16-byte chunk index ^= (row >> kSwzB) & 3
+constexpr int kSwzA = 1;  // activation rows (128 B): 16-byte chunk index ^= (row >> kSwzA) & 7
+constexpr int kSwzB = 1;  // weight rows (64 B): 16-byte chunk index ^= (row >> kSwzB) & 3
 
 __device__ __forceinline__ int pick_even(uint32_t lo, uint32_t hi) { return (int)__builtin_amdgcn_perm(hi, lo, 0x06040200u); }
 __device__ __forceinline__ int pick_odd(uint32_t lo, uint32_t hi) { return (int)__builtin_amdgcn_perm(hi, lo, 0x07050301u); }
