@@ -353,6 +353,43 @@ def test_linear_fp16_argument_checks(P):
     assert out.shape == (0, N)
 
 
+# ------------------------------------------------------------------------------------------------ seeded random shapes
+def _random_shapes(seed, count):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        M = int(rng.choice([1, 1, 2, 7, 16, 17, 32, 33, 48, 64, 65, 100, 130]))
+        N = int(rng.integers(1, 700))
+        steps = int(rng.integers(1, 161 if M == 1 else 100))      # K up to 20480 for one token, 12672 otherwise
+        spg = int(rng.choice([1, 1, 1, 2, 4]))                    # 128-wide steps per group
+        K = 128 * spg * max(1, steps // spg)
+        out.append((M, N, K, 128 * spg))
+    return out
+
+
+@pytest.mark.parametrize("M,N,K,group", _random_shapes(20240514, 48))
+def test_random_shapes_both_entry_points(P, M, N, K, group):
+    """Kernel choice, K split over the waves, ragged tiles: the GEMM on quantised activations and the linear call on
+    the fp16 ones against the oracle, on shapes drawn from a fixed seed."""
+    rng = np.random.default_rng(M * 1000003 + N * 1009 + K + group)
+    q = rng.integers(-8, 8, size=(N, K)).astype(np.int8)
+    qw = O.pack_int4(q)
+    IS = rng.integers(0, 1025, size=(N, K // group)).astype(np.int32)
+    s = (rng.random((N, K // group)) * 0.02 + 1e-4).astype(np.float32)
+    c = (rng.random(N) * 0.05 + 1e-3).astype(np.float32)
+    x = S.activations_outlier(M, K, int(rng.integers(1, 1 << 30)))
+    xq, sa = O.quantize_act_int8_token(x)
+    ref = O.gemm_w4a8_intscale(xq, sa, qw, IS, c, group, 10)
+    out, acc = P.is_gemm_w4a8_intscale(dev(xq), dev(sa), dev(qw), dev(IS), dev(c), group, 10, want_acc=True)
+    assert np.array_equal(host(acc), ref.acc), "int32 accumulators differ"
+    check_out(host(out), ref.out, f"M{M} N{N} K{K} G{group}")
+    out2, acc2 = P.is_linear_w4a8_intscale(dev(x), dev(qw), dev(IS), dev(c), group, 10, want_acc=True)
+    assert np.array_equal(host(acc2), ref.acc), "int32 accumulators of the linear call differ"
+    check_out(host(out2), ref.out, f"linear M{M} N{N} K{K} G{group}")
+    fs = O.gemm_w4a8_floatscale(xq, sa, qw, s, group)
+    check_fs(host(P.is_linear_w4a8_floatscale(dev(x), dev(qw), dev(s), group)), fs, f"M{M} N{N} K{K} G{group}")
+
+
 # ------------------------------------------------------------------------------------------------ fine-grained W8A8
 @pytest.mark.parametrize("N,K,group,alpha,mode", [(16, 128, 128, 10, 0), (300, 1024, 128, 10, 1), (64, 2048, 256, -1, 1),
                                                   (33, 512, 512, -1, 0)])
