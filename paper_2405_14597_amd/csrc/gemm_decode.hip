@@ -417,6 +417,10 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
                     // Integer scale step: v_mad_i32_i24 is exact while the scale fits 24 signed bits (|P| <= 2^17
                     // always does); a tile (or step) with a wider scale takes 32-bit multiplies.  Both are exact
                     // modulo 2^32.
+                    // operands from LDS: this lane's offset in a step's codes, opaque per tile so that the reads are
+                    // not hoisted out of the tile loop and kept in registers for all steps, which is what does not fit
+                    [[maybe_unused]] int qbase = kb * 16;
+                    if constexpr (XLDS) asm volatile("" : "+v"(qbase));
                     bool wide_tile = false;
                     if constexpr (INT_SCALE && kTileFlag)
                         wide_tile = __any(lds_wide[((k + u) & 1) * W + (lane & (W - 1))] != 0);
@@ -443,12 +447,8 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_kernel(GemmArgs a, 
 #pragma unroll
                         for (int t = 0; t < MT; ++t) {
                             if constexpr (XLDS) {
-                                // (the offset is opaque so that these reads are not hoisted out of the tile loop and
-                                // kept in registers for all steps, which is what does not fit)
-                                int qoff = i * 128 + kb * 16;
-                                asm volatile("" : "+v"(qoff));
-                                const v4i xe = *reinterpret_cast<const v4i*>(qstage + qoff);
-                                const v4i xo = *reinterpret_cast<const v4i*>(qstage + qoff + 64);
+                                const v4i xe = *reinterpret_cast<const v4i*>(qstage + qbase + i * 128);
+                                const v4i xo = *reinterpret_cast<const v4i*>(qstage + qbase + i * 128 + 64);
                                 part[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xe, w_even, v4i{0, 0, 0, 0}, 0, 0, 0);
                                 part[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xo, w_odd, part[t], 0, 0, 0);
                             } else {
