@@ -142,6 +142,61 @@ int is_linear_w4a8_floatscale(const void* x_fp16, const void* qweight, const flo
 size_t is_gemm_workspace_bytes(int M, int N, int K, int group);
 
 /*
+ * Kernel layout of a quantised weight matrix ("prepacked").  Sec. 4.2 converts the amplified scales to INT32 offline
+ * and passes the weights through an "efficient weight processing" it does not describe; here that offline step
+ * reorders both tensors into the order the gfx950 kernels consume them (same bytes, N padded to 16):
+ *   qweight_packed   [ceil(N/16)] [K/128] blocks of 1 KB = 16 weight rows x 128 k; in a block, the 16 bytes at
+ *                    (kb * 16 + r) * 16 hold row 16 t + r: byte j = q[n, 128 s + 16 kb + j] (bits 0-3) |
+ *                    q[n, 128 s + 64 + 16 kb + j] (bits 4-7), two's-complement nibbles; rows past N are zero
+ *   scales_packed    256-byte header (word 0: flags, bit 0 = some integer scale needs more than 24 signed bits,
+ *                    bit 1 = float scales; words 1-3: N, K, group), then [ceil(N/16)] [K/group] [16 rows] 32-bit words
+ * is_prepack_w4 takes the canonical qweight and exactly one of scale_i32 / scale_f32 (the other NULL); pack the same
+ * weights twice to have both forms.  Sizes: is_prepack_w4_weight_bytes, is_prepack_w4_scale_bytes (0 for shapes that
+ * are not covered).  Requirements: K and group multiples of 128 (IS_ERR_UNSUPPORTED otherwise: a 128-wide block has one
+ * group scale per row), group dividing K, packed tensors below 2 GB.
+ */
+size_t is_prepack_w4_weight_bytes(int N, int K);
+size_t is_prepack_w4_scale_bytes(int N, int K, int group);
+int is_prepack_w4(const void* qweight, const int32_t* scale_i32, const float* scale_f32, int N, int K, int group,
+                  void* qweight_packed, void* scales_packed, void* stream);
+
+/*
+ * The GEMMs of Eq. (2) and Eq. (1) on prepacked weights: same arithmetic and results as is_gemm_w4a8_intscale /
+ * is_gemm_w4a8_floatscale (accumulators bit for bit; the float-scale sums in a different but fixed order).
+ *   qweight_packed, scales_packed   from is_prepack_w4 (integer scales for the first, float scales for the second)
+ *   workspace   at least is_gemm_prepacked_workspace_bytes(M,N,K,group) bytes (0 for most decode shapes).  When it is
+ *               not 0 the K dimension is split across workgroups and the first 64 KB of the workspace are arrival
+ *               counters: they must be ZERO when a call starts and every call leaves them zero, so zero the workspace
+ *               once after allocating it.  Calls sharing one workspace must not overlap.
+ * Covered: 1 <= M <= 64 (the weight-streaming kernel).  IS_ERR_UNSUPPORTED beyond, and for N above
+ * 16 * 256 * (compute units) rows.  M = 0 is a no-op.
+ */
+size_t is_gemm_prepacked_workspace_bytes(int M, int N, int K, int group);
+int is_gemm_w4a8_intscale_prepacked(const int8_t* xq, const float* a_scale, const void* qweight_packed,
+                                    const void* scales_packed, const float* chan_scale, int M, int N, int K, int group,
+                                    int alpha_log2, void* out_fp16, int32_t* acc_out, void* workspace,
+                                    size_t workspace_bytes, void* stream);
+int is_gemm_w4a8_floatscale_prepacked(const int8_t* xq, const float* a_scale, const void* qweight_packed,
+                                      const void* scales_packed, int M, int N, int K, int group, void* out_fp16,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The linear layer on fp16 activations and prepacked weights: Appendix A.1 per token, then Eq. (2) / Eq. (1), with the
+ * results of is_quantize_act_int8_token followed by the prepacked GEMM, to the bit.  One token (M = 1, K <= 32768) is
+ * quantised inside the GEMM kernel (one launch); otherwise the quantiser runs first.
+ *   workspace   at least is_linear_prepacked_workspace_bytes(M,N,K,group) bytes: quantised activations [M,K], token
+ *               scales [M] (each padded to 256 bytes), then the GEMM's workspace, whose zero-counter rule applies.
+ */
+size_t is_linear_prepacked_workspace_bytes(int M, int N, int K, int group);
+int is_linear_w4a8_intscale_prepacked(const void* x_fp16, const void* qweight_packed, const void* scales_packed,
+                                      const float* chan_scale, int M, int N, int K, int group, int alpha_log2,
+                                      void* out_fp16, int32_t* acc_out, void* workspace, size_t workspace_bytes,
+                                      void* stream);
+int is_linear_w4a8_floatscale_prepacked(const void* x_fp16, const void* qweight_packed, const void* scales_packed, int M,
+                                        int N, int K, int group, void* out_fp16, void* workspace,
+                                        size_t workspace_bytes, void* stream);
+
+/*
  * Mixture-of-experts form (Sec. 5.4 measures Mixtral 8x7B): one launch over `num_experts` weight sets.
  * Rows of xq are sorted by expert; rows [row_offsets[e], row_offsets[e+1]) use weight set e.
  *   qweight [E,N,K/2], scale_i32 / scale_f32 [E,N,NG], chan_scale [E,N] (may be NULL)

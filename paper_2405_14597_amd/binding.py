@@ -42,6 +42,15 @@ EXPORTED_SYMBOLS = (
     "is_intscale_overflow_bound",
     "is_gemm_w4a8_intscale_safe",
     "is_gemm_safe_workspace_bytes",
+    "is_prepack_w4_weight_bytes",
+    "is_prepack_w4_scale_bytes",
+    "is_prepack_w4",
+    "is_gemm_prepacked_workspace_bytes",
+    "is_gemm_w4a8_intscale_prepacked",
+    "is_gemm_w4a8_floatscale_prepacked",
+    "is_linear_prepacked_workspace_bytes",
+    "is_linear_w4a8_intscale_prepacked",
+    "is_linear_w4a8_floatscale_prepacked",
     "is_probe_stream_read",
     "is_probe_mfma_i8",
     "is_status_string",
@@ -117,6 +126,24 @@ def load_library() -> ctypes.CDLL:
     lib.is_gemm_w4a8_intscale_safe.restype = ci
     lib.is_gemm_safe_workspace_bytes.argtypes = [ci, ci, ci, ci]
     lib.is_gemm_safe_workspace_bytes.restype = sz
+    lib.is_prepack_w4_weight_bytes.argtypes = [ci, ci]
+    lib.is_prepack_w4_weight_bytes.restype = sz
+    lib.is_prepack_w4_scale_bytes.argtypes = [ci, ci, ci]
+    lib.is_prepack_w4_scale_bytes.restype = sz
+    lib.is_prepack_w4.argtypes = [vp, vp, vp, ci, ci, ci, vp, vp, vp]
+    lib.is_prepack_w4.restype = ci
+    lib.is_gemm_prepacked_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.is_gemm_prepacked_workspace_bytes.restype = sz
+    lib.is_gemm_w4a8_intscale_prepacked.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.is_gemm_w4a8_intscale_prepacked.restype = ci
+    lib.is_gemm_w4a8_floatscale_prepacked.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, vp, vp, sz, vp]
+    lib.is_gemm_w4a8_floatscale_prepacked.restype = ci
+    lib.is_linear_prepacked_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.is_linear_prepacked_workspace_bytes.restype = sz
+    lib.is_linear_w4a8_intscale_prepacked.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.is_linear_w4a8_intscale_prepacked.restype = ci
+    lib.is_linear_w4a8_floatscale_prepacked.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp, sz, vp]
+    lib.is_linear_w4a8_floatscale_prepacked.restype = ci
     lib.is_probe_stream_read.argtypes = [vp, sz, vp, vp]
     lib.is_probe_stream_read.restype = ci
     lib.is_probe_mfma_i8.argtypes = [ci, vp, ctypes.POINTER(ctypes.c_double), vp]
@@ -520,3 +547,151 @@ def is_probe_mfma_i8(iters: int, sink, stream=None) -> float:
     _check("is_probe_mfma_i8", load_library().is_probe_mfma_i8(iters, _p(sink), ctypes.byref(ops), _stream_handle(stream)))
     return float(ops.value)
 
+
+
+# --------------------------------------------------------------------------------------------------------------
+# prepacked weights (kernel layout)
+# --------------------------------------------------------------------------------------------------------------
+class PackedWeights(NamedTuple):
+    wpack: "object"    # uint8, kernel layout of the int4 weights
+    spack: "object"    # uint8, header + kernel layout of the group scales (integer or float)
+    N: int
+    K: int
+    group: int
+    float_scales: bool
+
+
+def is_prepack_w4(qweight, scale, group: int, stream=None) -> PackedWeights:
+    """Canonical qweight [N,K/2] + scale_i32 or scale_f32 [N,K/group] -> kernel layout."""
+    torch = _torch()
+    lib = load_library()
+    N, K2 = qweight.shape
+    K = 2 * K2
+    _require(qweight, torch.uint8, (N, K2), "qweight")
+    if scale.dtype not in (torch.int32, torch.float32):
+        raise ValueError("scale: int32 or float32 expected")
+    _require(scale, scale.dtype, (N, K // group), "scale")
+    wb, sb = int(lib.is_prepack_w4_weight_bytes(N, K)), int(lib.is_prepack_w4_scale_bytes(N, K, group))
+    if wb == 0 or sb == 0:
+        raise IntScaleError("is_prepack_w4", IS_ERR_UNSUPPORTED)
+    wpack = torch.empty((wb,), dtype=torch.uint8, device=qweight.device)
+    spack = torch.empty((sb,), dtype=torch.uint8, device=qweight.device)
+    is_float = scale.dtype == torch.float32
+    st = lib.is_prepack_w4(_p(qweight), None if is_float else _p(scale), _p(scale) if is_float else None, N, K, group,
+                           _p(wpack), _p(spack), _stream_handle(stream))
+    _check("is_prepack_w4", st)
+    return PackedWeights(wpack, spack, N, K, group, is_float)
+
+
+def is_gemm_prepacked_workspace_bytes(M: int, N: int, K: int, group: int) -> int:
+    return int(load_library().is_gemm_prepacked_workspace_bytes(M, N, K, group))
+
+
+def is_linear_prepacked_workspace_bytes(M: int, N: int, K: int, group: int) -> int:
+    return int(load_library().is_linear_prepacked_workspace_bytes(M, N, K, group))
+
+
+def _zero_workspace(nbytes: int, device, workspace):
+    """The prepacked GEMMs want their arrival counters zero: a fresh workspace is zero-filled."""
+    torch = _torch()
+    if workspace is not None:
+        return workspace, workspace.numel() * workspace.element_size()
+    if nbytes == 0:
+        return None, 0
+    return torch.zeros((nbytes,), dtype=torch.uint8, device=device), nbytes
+
+
+def is_gemm_w4a8_intscale_prepacked(xq, a_scale, packed: PackedWeights, chan_scale, alpha_log2: int, out=None,
+                                    acc_out=None, want_acc: bool = False, workspace=None, stream=None):
+    """Returns (out fp16 [M,N], acc int32 [M,N] or None)."""
+    torch = _torch()
+    M, K = xq.shape
+    N, group = packed.N, packed.group
+    if K != packed.K or packed.float_scales:
+        raise ValueError("packed weights: K mismatch or float scales")
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    if chan_scale is not None:
+        _require(chan_scale, torch.float32, (N,), "chan_scale")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    _require(out, torch.float16, (M, N), "out")
+    if acc_out is None and want_acc:
+        acc_out = torch.empty((M, N), dtype=torch.int32, device=xq.device)
+    if acc_out is not None:
+        _require(acc_out, torch.int32, (M, N), "acc_out")
+    ws, ws_bytes = _zero_workspace(is_gemm_prepacked_workspace_bytes(M, N, K, group), xq.device, workspace)
+    st = load_library().is_gemm_w4a8_intscale_prepacked(_p(xq), _p(a_scale), _p(packed.wpack), _p(packed.spack),
+                                                       _p(chan_scale), M, N, K, group, alpha_log2, _p(out), _p(acc_out),
+                                                       _p(ws), ws_bytes, _stream_handle(stream))
+    _check("is_gemm_w4a8_intscale_prepacked", st)
+    if ws is not None and workspace is None and stream is not None:
+        ws.record_stream(stream)
+    return out, acc_out
+
+
+def is_gemm_w4a8_floatscale_prepacked(xq, a_scale, packed: PackedWeights, out=None, workspace=None, stream=None):
+    torch = _torch()
+    M, K = xq.shape
+    N, group = packed.N, packed.group
+    if K != packed.K or not packed.float_scales:
+        raise ValueError("packed weights: K mismatch or integer scales")
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    _require(out, torch.float16, (M, N), "out")
+    ws, ws_bytes = _zero_workspace(is_gemm_prepacked_workspace_bytes(M, N, K, group), xq.device, workspace)
+    st = load_library().is_gemm_w4a8_floatscale_prepacked(_p(xq), _p(a_scale), _p(packed.wpack), _p(packed.spack), M, N,
+                                                         K, group, _p(out), _p(ws), ws_bytes, _stream_handle(stream))
+    _check("is_gemm_w4a8_floatscale_prepacked", st)
+    if ws is not None and workspace is None and stream is not None:
+        ws.record_stream(stream)
+    return out
+
+
+def is_linear_w4a8_intscale_prepacked(x, packed: PackedWeights, chan_scale, alpha_log2: int, out=None, acc_out=None,
+                                      want_acc: bool = False, workspace=None, stream=None):
+    """fp16 activations in, prepacked weights. Returns (out fp16 [M,N], acc or None)."""
+    torch = _torch()
+    M, K = x.shape
+    N, group = packed.N, packed.group
+    if K != packed.K or packed.float_scales:
+        raise ValueError("packed weights: K mismatch or float scales")
+    _require(x, torch.float16, (M, K), "x")
+    if chan_scale is not None:
+        _require(chan_scale, torch.float32, (N,), "chan_scale")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _require(out, torch.float16, (M, N), "out")
+    if acc_out is None and want_acc:
+        acc_out = torch.empty((M, N), dtype=torch.int32, device=x.device)
+    if acc_out is not None:
+        _require(acc_out, torch.int32, (M, N), "acc_out")
+    ws, ws_bytes = _zero_workspace(is_linear_prepacked_workspace_bytes(M, N, K, group), x.device, workspace)
+    st = load_library().is_linear_w4a8_intscale_prepacked(_p(x), _p(packed.wpack), _p(packed.spack), _p(chan_scale), M, N,
+                                                         K, group, alpha_log2, _p(out), _p(acc_out), _p(ws), ws_bytes,
+                                                         _stream_handle(stream))
+    _check("is_linear_w4a8_intscale_prepacked", st)
+    if ws is not None and workspace is None and stream is not None:
+        ws.record_stream(stream)
+    return out, acc_out
+
+
+def is_linear_w4a8_floatscale_prepacked(x, packed: PackedWeights, out=None, workspace=None, stream=None):
+    torch = _torch()
+    M, K = x.shape
+    N, group = packed.N, packed.group
+    if K != packed.K or not packed.float_scales:
+        raise ValueError("packed weights: K mismatch or integer scales")
+    _require(x, torch.float16, (M, K), "x")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    _require(out, torch.float16, (M, N), "out")
+    ws, ws_bytes = _zero_workspace(is_linear_prepacked_workspace_bytes(M, N, K, group), x.device, workspace)
+    st = load_library().is_linear_w4a8_floatscale_prepacked(_p(x), _p(packed.wpack), _p(packed.spack), M, N, K, group,
+                                                           _p(out), _p(ws), ws_bytes, _stream_handle(stream))
+    _check("is_linear_w4a8_floatscale_prepacked", st)
+    if ws is not None and workspace is None and stream is not None:
+        ws.record_stream(stream)
+    return out

@@ -10,7 +10,9 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.environ.get("INTSCALE_LIBRARY", os.path.join(PKG_DIR, "libintscale.so"))
 
-SOURCES = ["api.hip", "quantize.hip", "act_producers.hip", "gemm_skinny.hip", "gemm_decode.hip", "gemm_prefill.hip", "gemm_tile_w8.hip", "overflow.hip", "probe.hip"]
+SOURCES = ["api.hip", "quantize.hip", "act_producers.hip", "gemm_skinny.hip", "gemm_decode.hip", "gemm_prefill.hip",
+           "gemm_tile_w8.hip", "overflow.hip", "probe.hip", "prepack.hip", "gemm_decode_pk.hip"]
+HEADERS = ["is_common.h", "act_common.h", "tile_common.h", "pk_common.h"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
@@ -28,8 +30,7 @@ def needs_build() -> bool:
     if not os.path.exists(LIB_PATH):
         return True
     t = os.path.getmtime(LIB_PATH)
-    deps = sources() + [os.path.join(CSRC, "is_common.h"), os.path.join(CSRC, "act_common.h"),
-                        os.path.join(CSRC, "tile_common.h"), os.path.join(INCLUDE, "intscale.h")]
+    deps = sources() + [os.path.join(CSRC, h) for h in HEADERS] + [os.path.join(INCLUDE, "intscale.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 
@@ -38,10 +39,25 @@ def build_library(force: bool = True, verbose: bool = False, extra_flags=()) -> 
     if not force and not needs_build():
         return LIB_PATH
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, "-I", CSRC, "-o", LIB_PATH, *sources()]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    # one object per source, compiled side by side, then one link (the objects live in a scratch folder)
+    import concurrent.futures
+    import tempfile
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    with tempfile.TemporaryDirectory(prefix="intscale_build_") as tmp:
+        def compile_one(src):
+            obj = os.path.join(tmp, os.path.basename(src) + ".o")
+            cmd = [hipcc, *flags, *extra_flags, "-I", INCLUDE, "-I", CSRC, "-c", src, "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            subprocess.run(cmd, check=True)
+            return obj
+        jobs = max(1, min(8, os.cpu_count() or 1))
+        with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as pool:
+            objs = list(pool.map(compile_one, sources()))
+        link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
+        if verbose:
+            print(" ".join(link), flush=True)
+        subprocess.run(link, check=True)
     return LIB_PATH
 
 

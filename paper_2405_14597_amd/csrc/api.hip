@@ -3,6 +3,7 @@
 #include <string.h>
 
 #include "is_common.h"
+#include "pk_common.h"
 
 using namespace intscale;
 
@@ -315,6 +316,152 @@ int is_linear_w4a8_floatscale(const void* x_fp16, const void* qweight, const flo
                               int group, void* out_fp16, void* workspace, size_t workspace_bytes, void* stream) {
     return linear_common(x_fp16, qweight, scale_f32, nullptr, M, N, K, group, 0, out_fp16, nullptr, workspace,
                          workspace_bytes, stream, false);
+}
+
+// ---- kernel layout of the weights ("prepacked"): offline conversion, and the GEMMs that consume it
+static int check_pk_shape(int N, int K, int group) {
+    if (N <= 0 || K <= 0 || group <= 0 || K % group != 0) return IS_ERR_INVALID_ARG;
+    if (K % 128 != 0 || group % 128 != 0) return IS_ERR_UNSUPPORTED;  // blocks of 128 k; a block has one group scale
+    if (K > (1 << 20) || pk_weight_bytes(N, K) >= (1ull << 31) || pk_scale_bytes(N, K, group) >= (1ull << 31))
+        return IS_ERR_UNSUPPORTED;
+    return IS_OK;
+}
+
+size_t is_prepack_w4_weight_bytes(int N, int K) {
+    return check_pk_shape(N, K, 128) == IS_OK ? pk_weight_bytes(N, K) : 0;
+}
+
+size_t is_prepack_w4_scale_bytes(int N, int K, int group) {
+    return check_pk_shape(N, K, group) == IS_OK ? pk_scale_bytes(N, K, group) : 0;
+}
+
+int is_prepack_w4(const void* qweight, const int32_t* scale_i32, const float* scale_f32, int N, int K, int group,
+                  void* qweight_packed, void* scales_packed, void* stream) {
+    const int shape = check_pk_shape(N, K, group);
+    if (shape != IS_OK) return shape;
+    if ((scale_i32 == nullptr) == (scale_f32 == nullptr)) return IS_ERR_INVALID_ARG;  // exactly one kind of scales
+    const void* scale = scale_i32 ? static_cast<const void*>(scale_i32) : static_cast<const void*>(scale_f32);
+    if (!ok_ptr(qweight) || !ok_ptr(scale) || !ok_ptr(qweight_packed) || !ok_ptr(scales_packed)) return IS_ERR_INVALID_ARG;
+    return hip_status(launch_prepack_w4(static_cast<const uint8_t*>(qweight), scale, scale_f32 != nullptr, N, K, group,
+                                        static_cast<uint8_t*>(qweight_packed), static_cast<uint8_t*>(scales_packed),
+                                        static_cast<hipStream_t>(stream)));
+}
+
+size_t is_gemm_prepacked_workspace_bytes(int M, int N, int K, int group) {
+    if (M < 0 || check_pk_shape(N, K, group) != IS_OK) return 0;
+    if (M == 0) return 0;
+    if (M <= 64) return pk_decode_workspace_bytes(M, N, K, group);
+    return 0;
+}
+
+static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_scale, float* a_scale_out,
+                          const void* wpack, const void* spack, const float* chan_scale, int M, int N, int K, int group,
+                          int alpha_log2, void* out_fp16, int32_t* acc_out, void* workspace, size_t workspace_bytes,
+                          void* stream, bool int_scale) {
+    if (M < 0) return IS_ERR_INVALID_ARG;
+    const int shape = check_pk_shape(N, K, group);
+    if (shape != IS_OK) return shape;
+    if (int_scale && (alpha_log2 < 0 || alpha_log2 > 30)) return IS_ERR_INVALID_ARG;
+    if (M > 64) return IS_ERR_UNSUPPORTED;
+    if (!ok_opt(workspace)) return IS_ERR_INVALID_ARG;
+    PkPlan plan;
+    if (M > 0 && !pk_decode_plan(M, N, K, group, x_fp16 != nullptr, &plan)) return IS_ERR_UNSUPPORTED;
+    const size_t need = is_gemm_prepacked_workspace_bytes(M, N, K, group);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return IS_ERR_WORKSPACE;
+    if (!ok_ptr(wpack) || !ok_ptr(spack) || !ok_opt(chan_scale)) return IS_ERR_INVALID_ARG;
+    if (M == 0) return IS_OK;
+    if (x_fp16 ? !ok_ptr(x_fp16) : (!ok_ptr(xq) || a_scale == nullptr || (reinterpret_cast<uintptr_t>(a_scale) & 3u)))
+        return IS_ERR_INVALID_ARG;
+    if (!ok_ptr(out_fp16) || !ok_opt(acc_out)) return IS_ERR_INVALID_ARG;
+    PkArgs a;
+    a.xq = xq;
+    a.x_fp16 = static_cast<const __half*>(x_fp16);
+    a.a_scale = a_scale;
+    a.a_scale_out = a_scale_out;
+    a.wpack = static_cast<const uint8_t*>(wpack);
+    a.spack = static_cast<const uint8_t*>(spack);
+    a.chan_scale = chan_scale;
+    a.out = static_cast<__half*>(out_fp16);
+    a.acc_out = acc_out;
+    a.counters = static_cast<int32_t*>(workspace);
+    a.partials = need > 0 ? reinterpret_cast<int32_t*>(static_cast<unsigned char*>(workspace) + kPkCounterBytes) : nullptr;
+    a.M = M;
+    a.N = N;
+    a.K = K;
+    a.group = group;
+    a.alpha_log2 = int_scale ? alpha_log2 : 0;
+    return hip_status(launch_gemm_decode_pk(a, int_scale, static_cast<hipStream_t>(stream)));
+}
+
+int is_gemm_w4a8_intscale_prepacked(const int8_t* xq, const float* a_scale, const void* qweight_packed,
+                                    const void* scales_packed, const float* chan_scale, int M, int N, int K, int group,
+                                    int alpha_log2, void* out_fp16, int32_t* acc_out, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+    return gemm_pk_common(xq, nullptr, a_scale, nullptr, qweight_packed, scales_packed, chan_scale, M, N, K, group,
+                          alpha_log2, out_fp16, acc_out, workspace, workspace_bytes, stream, true);
+}
+
+int is_gemm_w4a8_floatscale_prepacked(const int8_t* xq, const float* a_scale, const void* qweight_packed,
+                                      const void* scales_packed, int M, int N, int K, int group, void* out_fp16,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_pk_common(xq, nullptr, a_scale, nullptr, qweight_packed, scales_packed, nullptr, M, N, K, group, 0,
+                          out_fp16, nullptr, workspace, workspace_bytes, stream, false);
+}
+
+size_t is_linear_prepacked_workspace_bytes(int M, int N, int K, int group) {
+    if (M < 0 || check_pk_shape(N, K, group) != IS_OK) return 0;
+    if (M == 0) return 0;
+    return pad_256((size_t)M * K) + pad_256((size_t)M * 4) + is_gemm_prepacked_workspace_bytes(M, N, K, group);
+}
+
+static int linear_pk_common(const void* x_fp16, const void* wpack, const void* spack, const float* chan_scale, int M,
+                            int N, int K, int group, int alpha_log2, void* out_fp16, int32_t* acc_out, void* workspace,
+                            size_t workspace_bytes, void* stream, bool int_scale) {
+    if (M < 0) return IS_ERR_INVALID_ARG;
+    const int shape = check_pk_shape(N, K, group);
+    if (shape != IS_OK) return shape;
+    if (M > 64) return IS_ERR_UNSUPPORTED;
+    const size_t need = is_linear_prepacked_workspace_bytes(M, N, K, group);
+    if (!ok_opt(workspace)) return IS_ERR_INVALID_ARG;
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return IS_ERR_WORKSPACE;
+    if (M == 0) return IS_OK;
+    if (!ok_ptr(x_fp16)) return IS_ERR_INVALID_ARG;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    int8_t* xq = reinterpret_cast<int8_t*>(ws);
+    float* sa = reinterpret_cast<float*>(ws + pad_256((size_t)M * K));
+    unsigned char* rest = ws + pad_256((size_t)M * K) + pad_256((size_t)M * 4);
+    const size_t rest_bytes = workspace_bytes - (size_t)(rest - ws);
+    PkPlan plan;
+    if (M == 1 && pk_decode_plan(1, N, K, group, true, &plan))  // one token: quantised inside the GEMM kernel
+        return gemm_pk_common(nullptr, x_fp16, nullptr, sa, wpack, spack, chan_scale, M, N, K, group, alpha_log2,
+                              out_fp16, acc_out, rest, rest_bytes, stream, int_scale);
+    // the arguments of the GEMM are checked before the quantiser is enqueued
+    if (!ok_ptr(wpack) || !ok_ptr(spack) || !ok_opt(chan_scale) || !ok_ptr(out_fp16) || !ok_opt(acc_out))
+        return IS_ERR_INVALID_ARG;
+    if (int_scale && (alpha_log2 < 0 || alpha_log2 > 30)) return IS_ERR_INVALID_ARG;
+    if (!pk_decode_plan(M, N, K, group, false, &plan)) return IS_ERR_UNSUPPORTED;
+    const int st = hip_status(launch_quantize_act(static_cast<const __half*>(x_fp16), M, K, xq, sa,
+                                                  static_cast<hipStream_t>(stream)));
+    if (st != IS_OK) return st;
+    return gemm_pk_common(xq, nullptr, sa, nullptr, wpack, spack, chan_scale, M, N, K, group, alpha_log2, out_fp16,
+                          acc_out, rest, rest_bytes, stream, int_scale);
+}
+
+int is_linear_w4a8_intscale_prepacked(const void* x_fp16, const void* qweight_packed, const void* scales_packed,
+                                      const float* chan_scale, int M, int N, int K, int group, int alpha_log2,
+                                      void* out_fp16, int32_t* acc_out, void* workspace, size_t workspace_bytes,
+                                      void* stream) {
+    if (K & 7) return IS_ERR_INVALID_ARG;
+    return linear_pk_common(x_fp16, qweight_packed, scales_packed, chan_scale, M, N, K, group, alpha_log2, out_fp16,
+                            acc_out, workspace, workspace_bytes, stream, true);
+}
+
+int is_linear_w4a8_floatscale_prepacked(const void* x_fp16, const void* qweight_packed, const void* scales_packed, int M,
+                                        int N, int K, int group, void* out_fp16, void* workspace,
+                                        size_t workspace_bytes, void* stream) {
+    if (K & 7) return IS_ERR_INVALID_ARG;
+    return linear_pk_common(x_fp16, qweight_packed, scales_packed, nullptr, M, N, K, group, 0, out_fp16, nullptr,
+                            workspace, workspace_bytes, stream, false);
 }
 
 // ---- fine-grained W8A8

@@ -1,0 +1,605 @@
+// Decode regime (at most 64 token rows) of the fine-grained W4A8 GEMM on prepacked weights: a weight-streaming kernel
+// with no synchronisation inside its main loop.  Integer-scale form: Eq. (2) / Table 2 "Ours" of the Integer Scale
+// paper; float-scale form: Eq. (1) / Table 2 "Atom".
+//
+// Work split.  The weight matrix is a grid of 1 KB blocks (16 weight rows x 128 k, see pk_common.h).  K is cut into
+// `slabs` ranges of K steps, each slab owned by its own set of workgroups (one per CU in total); inside a slab a
+// workgroup owns a range of whole row tiles, and its blocks, taken tile after tile and along K inside a tile, are dealt
+// out evenly over its waves as contiguous ranges.  So every wave streams one contiguous piece of the packed weights,
+// all waves of the chip carry the same number of blocks to within one, and nobody waits for anybody until the end.
+// The quantised activations of the slab sit in LDS in MFMA operand order (written once per workgroup); a wave keeps
+// its int32 accumulators in registers while it walks along K and meets the other waves only when a row tile is
+// finished: pieces of a tile that several waves hold are added in LDS behind the single barrier at the end of the
+// kernel (int32 adds are order-free; the float-scale partials are added in wave order), and with more than one slab
+// the slabs' partial tiles meet in a workspace: each workgroup stores its partial, raises the tile's arrival counter,
+// and the one that arrives last adds the partials in slab order and runs the epilogue.  Nobody ever waits for another
+// workgroup.
+//
+// Per block: one 16-byte load per lane (issued DT blocks ahead), two bit operations per register for the two B
+// operands (16 * q as signed bytes: the nibble in the high half of a byte), two v_mfma_i32_16x16x64_i8 per token tile
+// whose A operands come from LDS, one shift and one v_mad_i32_i24 per partial product (Eq. (2): C'' += C_g * s_g^INT),
+// against a convert and a multiply-add for the float-scale form (Eq. (1)).  The epilogue is the one conversion of
+// Eq. (2): float(acc) * s_a[m] * c[n] / alpha.
+#include "act_common.h"
+#include "pk_common.h"
+
+namespace intscale {
+namespace {
+
+constexpr int kOutOfRange = (int)0x80000000u;  // a buffer offset past every descriptor here: the load returns 0
+constexpr int kFill = 8;                       // activation chunks a thread has in flight while it fills LDS
+constexpr int kFuseChunks = 4;                 // fused quantiser: 16-byte chunks of the fp16 token per thread
+
+using rsrc_t = __amdgpu_buffer_rsrc_t;
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, size_t bytes) {
+    const unsigned n = bytes > 0x7FFFFFFFull ? 0x7FFFFFFFu : (unsigned)bytes;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, n, 0x00020000);
+}
+
+// Workgroup barrier that only waits for this wave's LDS traffic (not for the weight loads in flight).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+struct PkKernelPlan {
+    int n16;          // row tiles
+    int steps;        // K / 128
+    int num_groups;   // K / group
+    int spg;          // K steps per group
+    int slabs;        // K split across workgroups
+    int wg_per_slab;
+    int rows;         // token rows kept per tile in LDS (power of two)
+    int cs_offset;    // LDS byte offset of the workgroup's channel scales (behind the activations / the shared pieces)
+    size_t wbytes, sbytes;
+};
+
+template <int MT, int DT, int WAVES, bool INT_SCALE, bool FUSEQ, bool WIDE>
+__device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPlan& p, unsigned char* smem) {
+    using acc_t = typename std::conditional<INT_SCALE, int, float>::type;
+    static_assert(DT >= 2 && DT <= 8, "ring of 2 to 8 blocks");
+    constexpr int W = WAVES;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int li = lane & 15, kb = lane >> 4;
+
+    // ---- this workgroup's slab and row tiles, this wave's blocks
+    const int slab = blockIdx.x / p.wg_per_slab;
+    const int jw = blockIdx.x - slab * p.wg_per_slab;
+    const int s_lo = (int)((long long)slab * p.steps / p.slabs);
+    const int ksl = (int)((long long)(slab + 1) * p.steps / p.slabs) - s_lo;
+    const int t0 = (int)((long long)jw * p.n16 / p.wg_per_slab);
+    const int t1 = (int)((long long)(jw + 1) * p.n16 / p.wg_per_slab);
+    const int B = (t1 - t0) * ksl;
+    if (B <= 0) return;  // uniform over the workgroup, before any barrier
+    const int b0 = (int)((long long)wave * B / W), b1 = (int)((long long)(wave + 1) * B / W);
+
+    const rsrc_t wres = make_rsrc(a.wpack, p.wbytes);
+    const rsrc_t sres = make_rsrc(a.spack + kPkHeaderBytes, p.sbytes);
+    const rsrc_t cres = make_rsrc(a.chan_scale, a.chan_scale ? (size_t)a.N * 4 : 0);
+
+    // ---- the activations of the slab: requested first (loads return in issue order), written to LDS below.
+    // A fill unit is 8 token rows x one K step (8 x 128 bytes); unit u = step * RB + row block.
+    const int rs = p.rows;
+    const int unit_b = 64 * rs;  // bytes of one (step, token tile, MFMA half) unit: 4 k-chunks x rs rows x 16 bytes
+    const int step_stride = MT * 2 * unit_b;
+    [[maybe_unused]] uint4 xh[FUSEQ ? kFuseChunks : 1];
+    [[maybe_unused]] v4i xraw[FUSEQ ? 1 : kFill];
+    const int RB = (a.M + 7) >> 3;
+    const int units = ksl * RB;
+    const float inv_rb = 1.0f / (float)RB;
+    [[maybe_unused]] auto fill_load = [&](int base) {
+        const rsrc_t xres = make_rsrc(a.xq, (size_t)a.M * a.K);
+#pragma unroll
+        for (int i = 0; i < kFill; ++i) {
+            const int u = base + i * W + wave;
+            const int step = (int)(((float)u + 0.5f) * inv_rb);  // u / RB, exact for u < 2^20
+            const int row = (u - step * RB) * 8 + (lane >> 3);
+            const bool ok = u < units && row < a.M;
+            xraw[i] = __builtin_amdgcn_raw_buffer_load_b128(
+                xres, ok ? row * a.K + (s_lo + step) * 128 + (lane & 7) * 16 : kOutOfRange, 0, 0);
+        }
+    };
+    [[maybe_unused]] auto fill_store = [&](int base) {
+#pragma unroll
+        for (int i = 0; i < kFill; ++i) {
+            const int u = base + i * W + wave;
+            const int step = (int)(((float)u + 0.5f) * inv_rb);
+            const int row = (u - step * RB) * 8 + (lane >> 3);
+            const int c8 = lane & 7;
+            if (u < units && row < a.M)
+                *reinterpret_cast<v4i*>(smem + ((step * MT + (row >> 4)) * 2 + (c8 >> 2)) * unit_b + (c8 & 3) * 16 * rs +
+                                        (row & 15) * 16) = xraw[i];
+        }
+    };
+    if constexpr (FUSEQ) {
+        const uint4* xrow = reinterpret_cast<const uint4*>(a.x_fp16);
+        const int chunks = a.K >> 3;
+#pragma unroll
+        for (int i = 0; i < kFuseChunks; ++i) {
+            const int c = (int)threadIdx.x + i * W * kWave;
+            xh[i] = c < chunks ? xrow[c] : make_uint4(0u, 0u, 0u, 0u);
+        }
+    } else {
+        fill_load(0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- token scales of this lane's output rows
+    float sa[MT][4];
+    if constexpr (!FUSEQ) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int m = 16 * t + 4 * kb + r;
+                sa[t][r] = m < a.M ? a.a_scale[m] : 0.0f;
+            }
+    }
+    // channel scales of this workgroup's row tiles: into LDS (behind the activations), so that an epilogue in
+    // mid-stream never waits on the vector memory counter, behind which the whole weight stream queues
+    float* lds_cs = reinterpret_cast<float*>(smem + p.cs_offset);
+    {
+        const int words = (t1 - t0) * 16;
+        for (int i = threadIdx.x; i < words; i += W * kWave) {
+            const float c = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(cres, (t0 * 16 + i) * 4, 0, 0));
+            lds_cs[i] = a.chan_scale ? c : 1.0f;
+        }
+    }
+
+    // ---- the weight stream.  A wave's blocks are cut into segments (its run of K steps inside one row tile), a
+    // segment into turns of DT blocks; the last turn of a segment is filled up with empty blocks (requests that lie
+    // outside the buffer and return zeros, with a zero scale), so that the ring of DT register slots always starts a
+    // segment at slot 0 and the turn below is straight-line code: slot u of a turn is requested while slot u of the
+    // turn before is used.
+    v4i wq[DT];
+    int scl[DT];
+    const float inv_spg = 1.0f / (float)p.spg;
+    const int w_lane = lane * 16, s_lane = li * 4;
+    // issue cursor (one turn ahead of the consume cursor)
+    int rem_i = b1 - b0;
+    int tile_i, step_i, left_i;
+    {
+        const int q = b0 / ksl;
+        tile_i = t0 + q;
+        step_i = b0 - q * ksl;
+        left_i = min(ksl - step_i, rem_i);
+    }
+    int woff_i = 0, soff_i = 0, sub_i = 0;
+    auto issue_state = [&]() {
+        const int s_abs = s_lo + step_i;
+        const int g = (int)(((float)s_abs + 0.5f) * inv_spg);  // s_abs / spg, exact below 2^20
+        woff_i = (tile_i * p.steps + s_abs) * kPkBlockBytes;
+        soff_i = (tile_i * p.num_groups + g) * 64;
+        sub_i = s_abs - g * p.spg;
+    };
+    auto issue_advance = [&]() {
+        const int adv = min(DT, left_i);
+        rem_i -= adv;
+        step_i += adv;
+        left_i -= adv;
+        if (left_i == 0) {
+            ++tile_i;
+            step_i = 0;
+            left_i = min(ksl, rem_i);
+        }
+        issue_state();
+    };
+    int sub_run = 0, goff_run = 0;  // inside a turn: K step in its group, byte offset of its group from the turn's first
+    auto issue = [&](int u) {
+        // the whole offset travels in the vector offset: that is what the descriptor's range check sees
+        const bool ok = u < left_i;
+        wq[u] = __builtin_amdgcn_raw_buffer_load_b128(wres, w_lane + (ok ? woff_i + u * kPkBlockBytes : kOutOfRange), 0, 0);
+        scl[u] = __builtin_amdgcn_raw_buffer_load_b32(sres, s_lane + (ok ? soff_i + goff_run : kOutOfRange), 0, 0);
+        if (++sub_run == p.spg) {
+            sub_run = 0;
+            goff_run += 64;
+        }
+    };
+    issue_state();
+    sub_run = sub_i;
+#pragma unroll
+    for (int u = 0; u < DT; ++u) issue(u);
+    issue_advance();
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- activations into LDS
+    if constexpr (FUSEQ) {
+        // Appendix A.1, n = 8, for the one token: s_a = absmax / 127, codes clamp(rne(x / s_a)) rounded as the true
+        // quotient rounds (as the stand-alone quantiser).  With one row the operand order is the natural order of k.
+        float* red = reinterpret_cast<float*>(smem + p.cs_offset - 64);
+        float amax = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kFuseChunks; ++i) amax = fmaxf(amax, absmax8(xh[i]));
+        amax = wave_max(amax);
+        if (lane == 0) red[wave] = amax;
+        lds_barrier();
+        float v = red[0];
+#pragma unroll
+        for (int i = 1; i < W; ++i) v = fmaxf(v, red[i]);
+        const float s_a = v / 127.0f;
+        const int chunks = a.K >> 3;
+#pragma unroll
+        for (int i = 0; i < kFuseChunks; ++i) {
+            const int c = (int)threadIdx.x + i * W * kWave;
+            if (c < chunks) *reinterpret_cast<uint2*>(smem + 8 * c) = quantize8(xh[i], s_a);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sa[0][r] = s_a;
+        if (a.a_scale_out && blockIdx.x == 0 && threadIdx.x == 0) *a.a_scale_out = s_a;
+    } else {
+        fill_store(0);
+        for (int base = kFill * W; base < units; base += kFill * W) {
+            fill_load(base);
+            fill_store(base);
+        }
+    }
+    lds_barrier();
+
+    // ---- main loop
+    const float inv_alpha = __int_as_float((127 - a.alpha_log2) << 23);  // 2^-alpha_log2, exact
+    const int a_lane = kb * 16 * rs + (li & (rs - 1)) * 16;
+    acc_t acc[MT][4], headp[MT][4];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            acc[t][r] = 0;
+            headp[t][r] = 0;
+        }
+    int head_tile = -1, tail_tile = -1;
+    int done_lo = 0, done_hi = 0;  // K split: tiles [done_lo, done_hi) whose slab partial this wave stored whole
+
+    // Epilogue of one row tile from accumulators in MFMA result layout: lane (li, kb) holds weight row 16 tile + li,
+    // token rows 16 t + 4 kb .. + 3.
+    auto epilogue = [&](int tile, const acc_t (&v)[MT][4]) {
+        const int n = tile * 16 + li;
+        if (n >= a.N) return;
+        const float cc = lds_cs[(tile - t0) * 16 + li] * inv_alpha;
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int m = 16 * t + 4 * kb + r;
+                if (m < a.M) {
+                    float o;
+                    if constexpr (INT_SCALE) {
+                        o = (float)v[t][r] * sa[t][r] * cc;
+                        if (a.acc_out) a.acc_out[(size_t)m * a.N + n] = v[t][r];
+                    } else {
+                        o = v[t][r] * sa[t][r];
+                    }
+                    a.out[(size_t)m * a.N + n] = __float2half_rn(o);
+                }
+            }
+    };
+    auto store_partial = [&](int tile, const acc_t (&v)[MT][4]) {
+        int32_t* dst = a.partials + ((size_t)(tile * p.slabs + slab) * MT) * 256 + lane * 4;
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            v4i o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if constexpr (INT_SCALE) o[r] = v[t][r];
+                else o[r] = __float_as_int(v[t][r]);
+            }
+            *reinterpret_cast<v4i*>(dst + t * 256) = o;
+        }
+    };
+
+    // consume cursor
+    int rem_c = b1 - b0;
+    int tile_c, step_c, left_c;
+    {
+        const int q = b0 / ksl;
+        tile_c = t0 + q;
+        step_c = b0 - q * ksl;
+        left_c = min(ksl - step_c, rem_c);
+    }
+    bool seg_whole = step_c == 0 && left_c == ksl;
+    bool seg_first = true;
+    while (rem_c > 0) {
+        // ---- one turn of the ring: straight-line code
+        sub_run = sub_i;
+        goff_run = 0;
+#pragma unroll
+        for (int u = 0; u < DT; ++u) {
+            const int a_off = a_lane + (u < left_c ? (step_c + u) * step_stride : 0);  // empty block: any valid address
+            v4i xa[MT][2];
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    if constexpr (MT > 1) xa[t][h] = *reinterpret_cast<const v4i*>(smem + a_off + (t * 2 + h) * 1024);
+                    else xa[t][h] = *reinterpret_cast<const v4i*>(smem + a_off + h * unit_b);
+                }
+            v4i w_lo, w_hi;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t pk = (uint32_t)wq[u][q];
+                w_lo[q] = (int)((pk << 4) & 0xF0F0F0F0u);
+                w_hi[q] = (int)(pk & 0xF0F0F0F0u);
+            }
+            const int s_i = scl[u];
+            const float s_f = __int_as_float(s_i) * 0.0625f;  // 16 P * (s / 16) = float(P) * s exactly
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                v4i part = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa[t][0], w_lo, v4i{0, 0, 0, 0}, 0, 0, 0);
+                part = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa[t][1], w_hi, part, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if constexpr (!INT_SCALE) {
+                        acc[t][r] = fmaf((float)part[r], s_f, acc[t][r]);  // C' += float(C_g) * s_g
+                    } else if constexpr (WIDE) {
+                        int prod = (part[r] >> 4) * s_i;
+                        asm volatile("" : "+v"(prod));  // else a 64-bit multiply-add with register pairs
+                        acc[t][r] += prod;
+                    } else {
+                        acc[t][r] += __mul24(part[r] >> 4, s_i);  // C'' += C_g * s_g^INT
+                    }
+                }
+            }
+            // The slot's registers are free now and take the same slot of the next turn.  (Not earlier: a request
+            // issued while the old weights or the old scale are still needed gets registers of its own, and the
+            // compiler then copies them over behind a wait for the whole ring.)
+            __builtin_amdgcn_sched_barrier(0);
+            issue(u);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        issue_advance();
+        const int adv = min(DT, left_c);
+        rem_c -= adv;
+        step_c += adv;
+        left_c -= adv;
+        if (left_c == 0) {
+            // ---- the segment is complete: its row tile is finished (epilogue, or this slab's partial), or it is one
+            // of the two pieces a wave can share with its neighbours (its first and its last segment)
+            if (seg_whole) {
+                if (p.slabs == 1) {
+                    epilogue(tile_c, acc);
+                } else {
+                    store_partial(tile_c, acc);
+                    if (done_hi == done_lo) done_lo = tile_c;
+                    done_hi = tile_c + 1;
+                }
+            } else if (seg_first) {
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) headp[t][r] = acc[t][r];
+                head_tile = tile_c;
+            } else {
+                tail_tile = tile_c;  // a later unfinished segment can only be the wave's last one: it stays in acc
+            }
+            if (rem_c > 0) {
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[t][r] = 0;
+                seg_first = false;
+                ++tile_c;
+                step_c = 0;
+                left_c = min(ksl, rem_c);
+                seg_whole = left_c == ksl;
+            }
+        }
+    }
+
+    // ---- pieces of row tiles shared by several waves meet in LDS (the activations are no longer needed)
+    lds_barrier();
+    int* slots = reinterpret_cast<int*>(smem);  // [wave][2][MT][64 lanes][4]
+    auto slot_ptr = [&](int w, int which, int t) { return slots + (((w * 2 + which) * MT + t) * kWave + lane) * 4; };
+    if (head_tile >= 0) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            v4i o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if constexpr (INT_SCALE) o[r] = headp[t][r];
+                else o[r] = __float_as_int(headp[t][r]);
+            }
+            *reinterpret_cast<v4i*>(slot_ptr(wave, 0, t)) = o;
+        }
+    }
+    if (tail_tile >= 0) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            v4i o;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if constexpr (INT_SCALE) o[r] = acc[t][r];
+                else o[r] = __float_as_int(acc[t][r]);
+            }
+            *reinterpret_cast<v4i*>(slot_ptr(wave, 1, t)) = o;
+        }
+    }
+    lds_barrier();
+
+    // Row tile tt of this workgroup is shared if its first and last block belong to different waves; wave
+    // (tt - t0) mod W adds the pieces in wave order.  Block x belongs to wave floor(((x + 1) W - 1) / B).
+    auto shared_tile_sum = [&](int tt, acc_t (&v)[MT][4]) -> bool {
+        const int start = (tt - t0) * ksl;
+        const int wf = ((start + 1) * W - 1) / B, wl = ((start + ksl) * W - 1) / B;
+        if (wf == wl) return false;
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[t][r] = 0;
+        for (int w = wf; w <= wl; ++w) {
+            const int wb0 = (int)((long long)w * B / W);
+            const int which = (t0 + wb0 / ksl == tt) ? 0 : 1;  // the wave's first segment, or its last
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                const v4i o = *reinterpret_cast<const v4i*>(slot_ptr(w, which, t));
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if constexpr (INT_SCALE) v[t][r] += o[r];
+                    else v[t][r] += __int_as_float(o[r]);
+                }
+            }
+        }
+        return true;
+    };
+
+    if (p.slabs == 1) {
+        for (int tt = t0 + wave; tt < t1; tt += W) {
+            acc_t v[MT][4];
+            if (!shared_tile_sum(tt, v)) continue;
+            epilogue(tt, v);
+        }
+        return;
+    }
+
+    // ---- K split across workgroups: store this workgroup's partial tiles, then raise each tile's arrival counter;
+    // whoever arrives last adds the slabs' partials in slab order and runs the epilogue.
+    for (int tt = t0 + wave; tt < t1; tt += W) {
+        acc_t v[MT][4];
+        if (shared_tile_sum(tt, v)) store_partial(tt, v);
+    }
+    __threadfence();  // release: the partials above (and the ones stored from the main loop) before the counters
+    auto arrive = [&](int tt) {
+        int old = 0;
+        if (lane == 0) old = atomicAdd(a.counters + tt, 1);
+        old = __builtin_amdgcn_readfirstlane(old);
+        if (old != p.slabs - 1) return;
+        __threadfence();  // acquire: the other slabs' partials
+        acc_t v[MT][4];
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[t][r] = 0;
+        for (int s = 0; s < p.slabs; ++s) {
+            const int32_t* src = a.partials + ((size_t)(tt * p.slabs + s) * MT) * 256 + lane * 4;
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                const v4i o = *reinterpret_cast<const v4i*>(src + t * 256);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if constexpr (INT_SCALE) v[t][r] += o[r];
+                    else v[t][r] += __int_as_float(o[r]);
+                }
+            }
+        }
+        epilogue(tt, v);
+        if (lane == 0) a.counters[tt] = 0;  // left zero for the next call
+    };
+    for (int tt = done_lo; tt < done_hi; ++tt) arrive(tt);
+    for (int tt = t0 + wave; tt < t1; tt += W) {
+        const int start = (tt - t0) * ksl;
+        if (((start + 1) * W - 1) / B != ((start + ksl) * W - 1) / B) arrive(tt);
+    }
+}
+
+template <int MT, int DT, int WAVES, bool INT_SCALE, bool FUSEQ>
+__global__ __launch_bounds__(WAVES * kWave) void gemm_decode_pk_kernel(PkArgs a, PkKernelPlan p) {
+    extern __shared__ __align__(16) unsigned char smem_pk[];
+    if constexpr (INT_SCALE) {
+        const int flags = *reinterpret_cast<const int32_t*>(a.spack);
+        if (flags & kPkFlagWide) decode_pk_body<MT, DT, WAVES, true, FUSEQ, true>(a, p, smem_pk);
+        else decode_pk_body<MT, DT, WAVES, true, FUSEQ, false>(a, p, smem_pk);
+    } else {
+        decode_pk_body<MT, DT, WAVES, false, FUSEQ, false>(a, p, smem_pk);
+    }
+}
+
+template <int MT, int DT, int WAVES, bool INT_SCALE, bool FUSEQ>
+hipError_t launch_pk(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan, int device, hipStream_t stream) {
+    auto kern = gemm_decode_pk_kernel<MT, DT, WAVES, INT_SCALE, FUSEQ>;
+    if (plan.lds_bytes > 64 * 1024) {
+        static bool raised[64] = {};  // per instantiation and device
+        if (device < 0 || device >= 64 || !raised[device]) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+            if (device >= 0 && device < 64) raised[device] = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3(plan.slabs * plan.wg_per_slab), dim3(WAVES * kWave), plan.lds_bytes, stream, a, kp);
+    return hipGetLastError();
+}
+
+template <bool INT_SCALE>
+hipError_t dispatch_pk(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan, int device, hipStream_t stream) {
+    if (a.x_fp16) return launch_pk<1, 4, 16, INT_SCALE, true>(a, kp, plan, device, stream);
+    if (plan.mt == 1) return launch_pk<1, 4, 16, INT_SCALE, false>(a, kp, plan, device, stream);
+    if (plan.mt == 2) return launch_pk<2, 4, 16, INT_SCALE, false>(a, kp, plan, device, stream);
+    return launch_pk<4, 6, 8, INT_SCALE, false>(a, kp, plan, device, stream);
+}
+
+constexpr size_t kActBudget = 128 * 1024;  // LDS bytes for the slab's activations (the fused quantiser's scratch follows)
+
+}  // namespace
+
+// The split of a problem over the chip; false if this kernel does not cover it.
+bool pk_decode_plan(int M, int N, int K, int group, bool fp16_in, PkPlan* plan) {
+    if (M < 1 || M > 64 || K % 128 != 0 || group % 128 != 0 || K % group != 0) return false;
+    if (fp16_in && (M != 1 || (K >> 3) > kFuseChunks * 1024)) return false;
+    if (pk_weight_bytes(N, K) >= (1ull << 31)) return false;
+    PkPlan pl;
+    pl.mt = M <= 16 ? 1 : M <= 32 ? 2 : 4;
+    pl.waves = pl.mt == 4 ? 8 : 16;  // four token tiles need more than 128 registers per lane
+    int rows = 16;
+    if (pl.mt == 1) {
+        rows = 1;
+        while (rows < M) rows *= 2;
+    }
+    pl.rows = rows;
+    const int steps = K / 128;
+    const int n16 = (N + 15) / 16;
+    const int cus = cu_count();
+    const size_t per_step = (size_t)rows * pl.mt * 128;
+    const int max_steps = (int)(kActBudget / per_step);  // >= 16
+    const int s_min = (steps + max_steps - 1) / max_steps;
+    // More slabs than the activations need can even out the shares (tiles per workgroup x steps per slab is what a
+    // workgroup carries) at the price of more partial tiles: take the best of a few candidates.
+    int best = s_min;
+    double best_cost = 0.0;
+    for (int s = s_min; s <= s_min + 4 && s <= steps && s <= cus; ++s) {
+        const int wgs = cus / s;
+        const double load = (double)((n16 + wgs - 1) / wgs) * (double)((steps + s - 1) / s);
+        const double cost = load * (1.0 + 0.04 * (s - 1));
+        if (s == s_min || cost < best_cost) {
+            best = s;
+            best_cost = cost;
+        }
+    }
+    pl.slabs = best;
+    pl.wg_per_slab = cus / best;
+    if (pl.wg_per_slab < 1) return false;
+    if (best > 1 && n16 > kPkMaxTiles) return false;
+    pl.max_steps = (steps + best - 1) / best;
+    const size_t act = per_step * pl.max_steps;
+    const size_t slots = (size_t)pl.waves * 2 * pl.mt * 1024;
+    const int tiles_max = (n16 + pl.wg_per_slab - 1) / pl.wg_per_slab;
+    if (tiles_max > 256) return false;  // the workgroup's channel scales take 64 bytes of LDS per row tile
+    // LDS: [activations of the slab, later the pieces of shared tiles | 64 bytes: the waves' absmax | channel scales]
+    pl.cs_offset = (int)(act > slots ? act : slots) + 64;
+    pl.lds_bytes = (size_t)pl.cs_offset + (size_t)tiles_max * 64;
+    *plan = pl;
+    return true;
+}
+
+size_t pk_decode_workspace_bytes(int M, int N, int K, int group) {
+    PkPlan pl;
+    if (!pk_decode_plan(M, N, K, group, false, &pl) || pl.slabs == 1) return 0;
+    return kPkCounterBytes + (size_t)((N + 15) / 16) * pl.slabs * pl.mt * 1024;
+}
+
+hipError_t launch_gemm_decode_pk(const PkArgs& a, bool int_scale, hipStream_t stream) {
+    PkPlan plan;
+    if (!pk_decode_plan(a.M, a.N, a.K, a.group, a.x_fp16 != nullptr, &plan)) return hipErrorInvalidValue;
+    PkKernelPlan kp;
+    kp.n16 = (a.N + 15) / 16;
+    kp.steps = a.K / 128;
+    kp.num_groups = a.K / a.group;
+    kp.spg = a.group / 128;
+    kp.slabs = plan.slabs;
+    kp.wg_per_slab = plan.wg_per_slab;
+    kp.rows = plan.rows;
+    kp.cs_offset = plan.cs_offset;
+    kp.wbytes = pk_weight_bytes(a.N, a.K);
+    kp.sbytes = pk_scale_bytes(a.N, a.K, a.group) - kPkHeaderBytes;
+    int device = -1;
+    (void)hipGetDevice(&device);
+    return int_scale ? dispatch_pk<true>(a, kp, plan, device, stream) : dispatch_pk<false>(a, kp, plan, device, stream);
+}
+
+}  // namespace intscale

@@ -1,0 +1,70 @@
+// The kernel layout of a quantised weight matrix ("prepacked"; written once, offline, by is_prepack_w4) and what the
+// kernels that consume it share.  The paper converts the amplified scales to INT32 offline and names an "efficient
+// weight processing" step without describing it (Sec. 4.2); this is that step for gfx950.
+//
+// Weights.  The matrix is cut into blocks of 16 weight rows x 128 k (one MFMA operand pair of a K step), 1 KB each,
+// stored [row tile t][K step s].  Inside a block, 16-byte chunk (kb, r) at byte kb * 256 + r * 16 belongs to MFMA
+// lane kb * 16 + r: weight row 16 t + r, and in byte j of the chunk
+//     bits 0-3 = q[n, 128 s + 16 kb + j]          (first  v_mfma_i32_16x16x64_i8 of the step: k 0..63)
+//     bits 4-7 = q[n, 128 s + 64 + 16 kb + j]     (second one: k 64..127)
+// as two's-complement nibbles.  So a wave fetches a block with one 16-byte load per lane, fully coalesced, and two
+// bit operations per register turn it into the two B operands; the matching A operands are 16 consecutive codes of a
+// token row.  Rows past N are zero.
+//
+// Scales.  [row tile t][group g][16 rows] 32-bit words (integer or float), after a 256-byte header:
+//     word 0 = flags (bit 0: some integer scale does not fit 24 signed bits; bit 1: float scales), 1 = N, 2 = K, 3 = group.
+// The 16 scales a wave needs with a block are 64 contiguous bytes, and consecutive groups of a tile follow each other.
+#pragma once
+#include "is_common.h"
+
+namespace intscale {
+
+constexpr int kPkHeaderBytes = 256;
+constexpr int kPkFlagWide = 1, kPkFlagFloat = 2;
+constexpr int kPkBlockBytes = 1024;
+
+inline size_t pk_weight_bytes(int N, int K) { return (size_t)((N + 15) / 16) * (size_t)(K / 128) * kPkBlockBytes; }
+inline size_t pk_scale_bytes(int N, int K, int group) {
+    return kPkHeaderBytes + (size_t)((N + 15) / 16) * (size_t)(K / group) * 64;
+}
+
+// Cross-workgroup K split of the decode kernel: the first kPkCounterBytes of its workspace are one arrival counter per
+// row tile (zero between calls), the partial accumulators follow.
+constexpr size_t kPkCounterBytes = 64 * 1024;
+constexpr int kPkMaxTiles = (int)(kPkCounterBytes / 4);
+
+struct PkPlan {
+    int waves;        // waves per workgroup
+    int mt;           // 16-row token tiles (1, 2, 4)
+    int rows;         // token rows kept per tile in LDS (power of two <= 16)
+    int slabs;        // K split across workgroups (1 = none)
+    int wg_per_slab;  // workgroups per slab
+    int max_steps;    // K steps of the longest slab
+    int cs_offset;    // LDS byte offset of the workgroup's channel scales
+    size_t lds_bytes;
+};
+
+// Arguments of the kernels that read the prepacked layout.
+struct PkArgs {
+    const int8_t* xq;        // [M,K] or nullptr when x_fp16 is given
+    const __half* x_fp16;    // [M,K] (one token, quantised in the kernel) or nullptr
+    const float* a_scale;    // [M]
+    float* a_scale_out;      // x_fp16: receives the token scale (may be nullptr)
+    const uint8_t* wpack;    // weights, kernel layout
+    const uint8_t* spack;    // scales, kernel layout (header included)
+    const float* chan_scale; // [N] or nullptr
+    __half* out;             // [M,N]
+    int32_t* acc_out;        // [M,N] or nullptr
+    int32_t* counters;       // K split: arrival counters per row tile
+    int32_t* partials;       // K split: [tile][slab][mt][64 lanes][4]
+    int M, N, K, group;
+    int alpha_log2;
+};
+
+bool pk_decode_plan(int M, int N, int K, int group, bool fp16_in, PkPlan* plan);
+size_t pk_decode_workspace_bytes(int M, int N, int K, int group);
+hipError_t launch_prepack_w4(const uint8_t* qweight, const void* scale, bool float_scales, int N, int K, int group,
+                             uint8_t* wpack, uint8_t* spack, hipStream_t stream);
+hipError_t launch_gemm_decode_pk(const PkArgs& a, bool int_scale, hipStream_t stream);
+
+}  // namespace intscale

@@ -1,0 +1,218 @@
+"""GPU parity of the prepacked route (kernel layout of the weights + the weight-streaming decode kernel) against the
+CPU oracle, through the C ABI: the packed layout byte for byte against its definition written out in numpy, int32
+accumulators bit-exact, fp16 outputs within the stated tolerance, for every token-tile count, every number of token
+rows kept in LDS, with and without the K split across workgroups, ragged N, wide scales, wide groups, the float-scale
+twin, and the one-call linear layer on fp16 activations.
+"""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from oracle import oracle as O
+from test_gpu_parity import check_fs, check_out, dev, host, rand_quantised
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+G = 128
+
+
+@pytest.fixture(scope="module")
+def P():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2405_14597_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+def packed_layout_numpy(qweight, scale, group):
+    """The kernel layout as include/intscale.h defines it, element by element."""
+    N, K2 = qweight.shape
+    K = 2 * K2
+    q = O.unpack_int4(qweight).astype(np.int64) & 0xF          # two's-complement nibbles [N,K]
+    n16, steps = (N + 15) // 16, K // 128
+    qp = np.zeros((n16 * 16, K), np.int64)
+    qp[:N] = q
+    w = np.zeros((n16, steps, 4, 16, 16), np.uint8)             # [tile][step][kb][row][byte]
+    for kb in range(4):
+        for j in range(16):
+            lo = qp[:, np.arange(steps) * 128 + 16 * kb + j]           # [rows, steps]
+            hi = qp[:, np.arange(steps) * 128 + 64 + 16 * kb + j]
+            b = (lo | (hi << 4)).astype(np.uint8).reshape(n16, 16, steps)
+            w[:, :, kb, :, j] = b.transpose(0, 2, 1)
+    NG = K // group
+    sp = np.zeros((n16 * 16, NG), scale.dtype)
+    sp[:N] = scale
+    s = sp.reshape(n16, 16, NG).transpose(0, 2, 1)                # [tile][group][row]
+    return w.reshape(-1), np.ascontiguousarray(s).reshape(-1)
+
+
+@pytest.mark.parametrize("N,K,group", [(16, 128, 128), (40, 1024, 128), (272, 4096, 256), (100, 1536, 512)])
+def test_prepack_layout(P, N, K, group):
+    rng = np.random.default_rng(N + K)
+    q = rng.integers(-8, 8, size=(N, K)).astype(np.int8)
+    qw = O.pack_int4(q)
+    IS = rng.integers(-2 ** 20, 2 ** 20, size=(N, K // group)).astype(np.int32)
+    s = rng.random((N, K // group)).astype(np.float32)
+    for scale, is_float in ((IS, False), (s, True)):
+        pk = P.is_prepack_w4(dev(qw), dev(scale), group)
+        w_ref, s_ref = packed_layout_numpy(qw, scale, group)
+        assert np.array_equal(host(pk.wpack), w_ref)
+        sp = host(pk.spack)
+        header = sp[:256].view(np.int32)
+        assert header[0] == (2 if is_float else 0) and tuple(header[1:4]) == (N, K, group)
+        assert np.array_equal(sp[256:].view(scale.dtype), s_ref)
+    wide = IS.copy()
+    wide[N // 2, 0] = 2 ** 23
+    assert host(P.is_prepack_w4(dev(qw), dev(wide), group).spack)[:4].view(np.int32)[0] == 1
+    wide[N // 2, 0] = -2 ** 23
+    assert host(P.is_prepack_w4(dev(qw), dev(wide), group).spack)[:4].view(np.int32)[0] == 0
+
+
+# (M, N, K): one, two and four token tiles; 1, 2, 4, 8, 16 token rows kept in LDS; fewer blocks than waves; row tiles
+# shared by several waves and whole tiles inside one wave; many tiles per workgroup; K split across workgroups
+# (K = 11008 at 16 rows, 8192 and 28672 at 32 rows, 4096 and 11008 at 64 rows); ragged N
+PK_SHAPES = [(1, 16, 128), (1, 4096, 4096), (1, 100, 20480), (2, 4200, 1024), (3, 272, 2048), (5, 8208, 512),
+             (8, 4096, 4096), (9, 40, 1024), (16, 272, 1024), (16, 5008, 11008), (16, 12288, 256), (17, 40, 1024),
+             (24, 4120, 1024), (32, 4360, 8192), (32, 528, 28672), (33, 100, 2048), (48, 2064, 3584), (64, 4096, 1024),
+             (64, 48, 11008), (64, 8208, 4096), (40, 4200, 1024), (1, 22016, 4096), (16, 22016, 4096), (7, 1, 256)]
+
+
+@pytest.mark.parametrize("M,N,K", PK_SHAPES)
+def test_prepacked_gemm_intscale_bit_exact_acc(P, M, N, K):
+    rng = np.random.default_rng(1500 + M + N + K)
+    xq, qw, IS, s, sa, c = rand_quantised(rng, M, N, K)
+    ref = O.gemm_w4a8_intscale(xq, sa, qw, IS, c, G, 10)
+    pk = P.is_prepack_w4(dev(qw), dev(IS), G)
+    out, acc = P.is_gemm_w4a8_intscale_prepacked(dev(xq), dev(sa), pk, dev(c), 10, want_acc=True)
+    assert np.array_equal(host(acc), ref.acc), "int32 accumulators differ"
+    check_out(host(out), ref.out, f"M{M} N{N} K{K}")
+    ref1 = O.gemm_w4a8_intscale(xq, sa, qw, IS, None, G, 7)
+    out1, acc1 = P.is_gemm_w4a8_intscale_prepacked(dev(xq), dev(sa), pk, None, 7)
+    assert acc1 is None
+    check_out(host(out1), ref1.out)
+
+
+@pytest.mark.parametrize("M,N,K", PK_SHAPES)
+def test_prepacked_gemm_floatscale(P, M, N, K):
+    rng = np.random.default_rng(2500 + M + N + K)
+    xq, qw, IS, s, sa, c = rand_quantised(rng, M, N, K)
+    fs = O.gemm_w4a8_floatscale(xq, sa, qw, s, G)
+    pk = P.is_prepack_w4(dev(qw), dev(s), G)
+    out = P.is_gemm_w4a8_floatscale_prepacked(dev(xq), dev(sa), pk)
+    check_fs(host(out), fs, f"M{M} N{N} K{K}")
+
+
+@pytest.mark.parametrize("M,K", [(16, 4096), (64, 4096), (32, 8192)])
+def test_prepacked_extreme_codes_and_wide_scales(P, M, K):
+    """All codes at -128 / -8, negative and wider-than-24-bit integer scales, wrap-around; with and without K split."""
+    N = 32
+    xq = np.full((M, K), -128, np.int8)
+    q = np.full((N, K), -8, np.int8)
+    xq[1::2] = 127
+    q[::3] = 7
+    rng = np.random.default_rng(5)
+    sa = np.ones(M, np.float32)
+    for IS in (np.full((N, K // G), 511, np.int32), np.full((N, K // G), 40000, np.int32),
+               rng.integers(-2 ** 31, 2 ** 31, size=(N, K // G), dtype=np.int64).astype(np.int32),
+               rng.integers(-2 ** 23, 2 ** 23, size=(N, K // G), dtype=np.int64).astype(np.int32)):
+        ref = O.gemm_w4a8_intscale(xq, sa, O.pack_int4(q), IS, None, G, 10)
+        pk = P.is_prepack_w4(dev(O.pack_int4(q)), dev(IS), G)
+        out, acc = P.is_gemm_w4a8_intscale_prepacked(dev(xq), dev(sa), pk, None, 10, want_acc=True)
+        assert np.array_equal(host(acc), ref.acc)
+        check_out(host(out), ref.out)
+
+
+@pytest.mark.parametrize("M", [3, 40])
+@pytest.mark.parametrize("group", [256, 384, 1536])
+def test_prepacked_wider_groups(P, M, group):
+    """Several K steps share a scale (group = K is the coarse-grained GEMM, Table 2's first column)."""
+    N, K = 80, 1536
+    rng = np.random.default_rng(group + M)
+    xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+    q = rng.integers(-8, 8, size=(N, K)).astype(np.int8)
+    IS = rng.integers(0, 300, size=(N, K // group)).astype(np.int32)
+    s = rng.random((N, K // group)).astype(np.float32) * 0.01
+    sa = rng.random(M).astype(np.float32)
+    qw = O.pack_int4(q)
+    ref = O.gemm_w4a8_intscale(xq, sa, qw, IS, None, group, 8)
+    out, acc = P.is_gemm_w4a8_intscale_prepacked(dev(xq), dev(sa), P.is_prepack_w4(dev(qw), dev(IS), group), None, 8,
+                                                 want_acc=True)
+    assert np.array_equal(host(acc), ref.acc)
+    check_out(host(out), ref.out)
+    fs = O.gemm_w4a8_floatscale(xq, sa, qw, s, group)
+    check_fs(host(P.is_gemm_w4a8_floatscale_prepacked(dev(xq), dev(sa), P.is_prepack_w4(dev(qw), dev(s), group))), fs)
+
+
+def test_prepacked_split_k_workspace_reuse(P):
+    """The arrival counters of the K split are left zero: one zeroed workspace serves call after call, of different
+    shapes, and the results do not change from call to call."""
+    shapes = [(64, 2064, 4096), (32, 528, 8192), (64, 48, 11008), (64, 2064, 4096)]
+    need = max(P.is_gemm_prepacked_workspace_bytes(M, N, K, G) for M, N, K in shapes)
+    assert need > 0
+    ws = torch.zeros((need,), dtype=torch.uint8, device="cuda:0")
+    for rep, (M, N, K) in enumerate(shapes):
+        rng = np.random.default_rng(300 + M + N + K)
+        xq, qw, IS, s, sa, c = rand_quantised(rng, M, N, K)
+        ref = O.gemm_w4a8_intscale(xq, sa, qw, IS, c, G, 10)
+        pk = P.is_prepack_w4(dev(qw), dev(IS), G)
+        for _ in range(2):
+            out, acc = P.is_gemm_w4a8_intscale_prepacked(dev(xq), dev(sa), pk, dev(c), 10, want_acc=True, workspace=ws)
+            assert np.array_equal(host(acc), ref.acc), f"call {rep}"
+            check_out(host(out), ref.out)
+        fs = O.gemm_w4a8_floatscale(xq, sa, qw, s, G)
+        pkf = P.is_prepack_w4(dev(qw), dev(s), G)
+        a = P.is_gemm_w4a8_floatscale_prepacked(dev(xq), dev(sa), pkf, workspace=ws)
+        b = P.is_gemm_w4a8_floatscale_prepacked(dev(xq), dev(sa), pkf, workspace=ws)
+        check_fs(host(a), fs)
+        assert torch.equal(a, b), "float-scale partials are added in a fixed order"
+    torch.cuda.synchronize()
+    assert int(ws[: 64 * 1024].view(torch.int32).abs().max()) == 0
+
+
+LINEAR_PK_SHAPES = [(1, 4096, 4096), (1, 12288, 4096), (1, 4096, 11008), (1, 272, 12288), (1, 40, 1024), (1, 16, 128),
+                    (1, 64, 28672), (1, 4360, 13312), (1, 48, 40960), (8, 4096, 4096), (64, 48, 11008), (33, 300, 1024)]
+
+
+@pytest.mark.parametrize("M,N,K", LINEAR_PK_SHAPES)
+def test_prepacked_linear_fp16_activations(P, M, N, K):
+    rng = np.random.default_rng(7500 + M + N + K)
+    _, qw, IS, s, _, c = rand_quantised(rng, 1, N, K)
+    x = S.activations_outlier(M, K, 77 + K % 13)
+    xq_ref, sa_ref = O.quantize_act_int8_token(x)
+    ref = O.gemm_w4a8_intscale(xq_ref, sa_ref, qw, IS, c, G, 10)
+    out, acc = P.is_linear_w4a8_intscale_prepacked(dev(x), P.is_prepack_w4(dev(qw), dev(IS), G), dev(c), 10,
+                                                   want_acc=True)
+    assert np.array_equal(host(acc), ref.acc), "int32 accumulators differ"
+    check_out(host(out), ref.out, f"M{M} N{N} K{K}")
+    fs = O.gemm_w4a8_floatscale(xq_ref, sa_ref, qw, s, G)
+    out_fs = P.is_linear_w4a8_floatscale_prepacked(dev(x), P.is_prepack_w4(dev(qw), dev(s), G))
+    check_fs(host(out_fs), fs, f"M{M} N{N} K{K}")
+
+
+def test_prepacked_linear_token_scale_and_zero_token(P):
+    """The one-kernel route writes the token's scale where the two-kernel route does; an all-zero token gives scale 0
+    and an all-zero output."""
+    N, K = 512, 4096
+    rng = np.random.default_rng(7100)
+    _, qw, IS, s, _, c = rand_quantised(rng, 1, N, K)
+    pk = P.is_prepack_w4(dev(qw), dev(IS), G)
+    x = S.activations_student_t(1, K, 5)
+    _, sa_ref = O.quantize_act_int8_token(x)
+    ws = torch.zeros((P.is_linear_prepacked_workspace_bytes(1, N, K, G),), dtype=torch.uint8, device="cuda:0")
+    P.is_linear_w4a8_intscale_prepacked(dev(x), pk, dev(c), 10, workspace=ws)
+    off = (K + 255) // 256 * 256
+    assert np.array_equal(host(ws[off:off + 4]).view(np.float32), sa_ref)
+    out, acc = P.is_linear_w4a8_intscale_prepacked(dev(np.zeros((1, K), np.float16)), pk, dev(c), 10, want_acc=True)
+    assert not host(acc).any() and not host(out).any()
+
+
+def test_prepacked_empty_and_unsupported(P):
+    rng = np.random.default_rng(3)
+    xq, qw, IS, s, sa, c = rand_quantised(rng, 1, 16, 128)
+    pk = P.is_prepack_w4(dev(qw), dev(IS), G)
+    e8 = torch.empty((0, 128), dtype=torch.int8, device="cuda:0")
+    e32 = torch.empty((0,), dtype=torch.float32, device="cuda:0")
+    out, _ = P.is_gemm_w4a8_intscale_prepacked(e8, e32, pk, None, 10)
+    assert out.shape == (0, 16)
