@@ -20,6 +20,8 @@
 // whose A operands come from LDS, one shift and one v_mad_i32_i24 per partial product (Eq. (2): C'' += C_g * s_g^INT),
 // against a convert and a multiply-add for the float-scale form (Eq. (1)).  The epilogue is the one conversion of
 // Eq. (2): float(acc) * s_a[m] * c[n] / alpha.
+#include <stdlib.h>
+
 #include "act_common.h"
 #include "pk_common.h"
 
@@ -46,127 +48,84 @@ struct PkKernelPlan {
     int num_groups;   // K / group
     int spg;          // K steps per group
     int slabs;        // K split across workgroups
-    int wg_per_slab;
+    int steps_q, steps_r;  // K steps per slab: steps_q, one more for the first steps_r slabs
+    int tiles_q, tiles_r;  // row tiles per workgroup of a slab: tiles_q, one more for the first tiles_r workgroups
     int rows;         // token rows kept per tile in LDS (power of two)
-    int cs_offset;    // LDS byte offset of the workgroup's channel scales (behind the activations / the shared pieces)
+    int slot_offset;  // LDS byte offset of the pieces of shared tiles (0: they reuse the activations' space)
+    int cs_offset;    // LDS byte offset of the workgroup's channel scales
     size_t wbytes, sbytes;
 };
 
-template <int MT, int DT, int WAVES, bool INT_SCALE, bool FUSEQ, bool WIDE>
+// Optional timeline of a launch (built with -DPK_TRACE only; used to find where a short kernel's time goes).
+#ifdef PK_TRACE
+__device__ unsigned long long g_pk_trace[256 * 2 * 8];
+#define PK_MARK(i)                                                                                          \
+    do {                                                                                                    \
+        if ((wave == 0 || wave == W - 1) && lane == 0 && blockIdx.y == 0 && blockIdx.x < 256)               \
+            g_pk_trace[(blockIdx.x * 2 + (wave ? 1 : 0)) * 8 + (i)] = __builtin_amdgcn_s_memrealtime();    \
+    } while (0)
+#else
+#define PK_MARK(i)
+#endif
+
+__device__ __forceinline__ int mad_i24(int a, int b, int c) {
+    int r;
+    asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+template <int MT, int DT, int WAVES, bool INT_SCALE, bool FUSEQ>
 __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPlan& p, unsigned char* smem) {
     using acc_t = typename std::conditional<INT_SCALE, int, float>::type;
     static_assert(DT >= 2 && DT <= 8, "ring of 2 to 8 blocks");
     constexpr int W = WAVES;
+    static_assert((W & (W - 1)) == 0, "waves per workgroup: a power of two");
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int li = lane & 15, kb = lane >> 4;
+    PK_MARK(0);
+    // "some integer scale needs more than 24 signed bits" (left in the header by the prepacking): asked for here,
+    // needed only in the first scale step, so that the request is not waited for ahead of the weight stream
+    const int pk_flags = *reinterpret_cast<const int32_t*>(a.spack);
 
-    // ---- this workgroup's slab and row tiles, this wave's blocks
-    const int slab = blockIdx.x / p.wg_per_slab;
-    const int jw = blockIdx.x - slab * p.wg_per_slab;
-    const int s_lo = (int)((long long)slab * p.steps / p.slabs);
-    const int ksl = (int)((long long)(slab + 1) * p.steps / p.slabs) - s_lo;
-    const int t0 = (int)((long long)jw * p.n16 / p.wg_per_slab);
-    const int t1 = (int)((long long)(jw + 1) * p.n16 / p.wg_per_slab);
+    // ---- this workgroup's slab and row tiles, this wave's blocks.  (Grid: x = workgroup inside its slab, y = slab.
+    // Even shares without a division: the first `..._r` owners take one more than `..._q`.)  Everything up to the
+    // first requests of the weight stream is kept short: all waves of a SIMD run it at the same time, and the HBM
+    // latency only starts to count down behind it.
+    const int slab = blockIdx.y;
+    const int jw = blockIdx.x;
+    const int s_lo = slab * p.steps_q + min(slab, p.steps_r);
+    const int ksl = p.steps_q + (slab < p.steps_r ? 1 : 0);
+    const int t0 = jw * p.tiles_q + min(jw, p.tiles_r);
+    const int t1 = t0 + p.tiles_q + (jw < p.tiles_r ? 1 : 0);
     const int B = (t1 - t0) * ksl;
     if (B <= 0) return;  // uniform over the workgroup, before any barrier
-    const int b0 = (int)((long long)wave * B / W), b1 = (int)((long long)(wave + 1) * B / W);
-
+    const int b0 = (wave * B) / W, b1 = ((wave + 1) * B) / W;
     const rsrc_t wres = make_rsrc(a.wpack, p.wbytes);
     const rsrc_t sres = make_rsrc(a.spack + kPkHeaderBytes, p.sbytes);
-    const rsrc_t cres = make_rsrc(a.chan_scale, a.chan_scale ? (size_t)a.N * 4 : 0);
-
-    // ---- the activations of the slab: requested first (loads return in issue order), written to LDS below.
-    // A fill unit is 8 token rows x one K step (8 x 128 bytes); unit u = step * RB + row block.
-    const int rs = p.rows;
-    const int unit_b = 64 * rs;  // bytes of one (step, token tile, MFMA half) unit: 4 k-chunks x rs rows x 16 bytes
-    const int step_stride = MT * 2 * unit_b;
-    [[maybe_unused]] uint4 xh[FUSEQ ? kFuseChunks : 1];
-    [[maybe_unused]] v4i xraw[FUSEQ ? 1 : kFill];
-    const int RB = (a.M + 7) >> 3;
-    const int units = ksl * RB;
-    const float inv_rb = 1.0f / (float)RB;
-    [[maybe_unused]] auto fill_load = [&](int base) {
-        const rsrc_t xres = make_rsrc(a.xq, (size_t)a.M * a.K);
-#pragma unroll
-        for (int i = 0; i < kFill; ++i) {
-            const int u = base + i * W + wave;
-            const int step = (int)(((float)u + 0.5f) * inv_rb);  // u / RB, exact for u < 2^20
-            const int row = (u - step * RB) * 8 + (lane >> 3);
-            const bool ok = u < units && row < a.M;
-            xraw[i] = __builtin_amdgcn_raw_buffer_load_b128(
-                xres, ok ? row * a.K + (s_lo + step) * 128 + (lane & 7) * 16 : kOutOfRange, 0, 0);
-        }
-    };
-    [[maybe_unused]] auto fill_store = [&](int base) {
-#pragma unroll
-        for (int i = 0; i < kFill; ++i) {
-            const int u = base + i * W + wave;
-            const int step = (int)(((float)u + 0.5f) * inv_rb);
-            const int row = (u - step * RB) * 8 + (lane >> 3);
-            const int c8 = lane & 7;
-            if (u < units && row < a.M)
-                *reinterpret_cast<v4i*>(smem + ((step * MT + (row >> 4)) * 2 + (c8 >> 2)) * unit_b + (c8 & 3) * 16 * rs +
-                                        (row & 15) * 16) = xraw[i];
-        }
-    };
-    if constexpr (FUSEQ) {
-        const uint4* xrow = reinterpret_cast<const uint4*>(a.x_fp16);
-        const int chunks = a.K >> 3;
-#pragma unroll
-        for (int i = 0; i < kFuseChunks; ++i) {
-            const int c = (int)threadIdx.x + i * W * kWave;
-            xh[i] = c < chunks ? xrow[c] : make_uint4(0u, 0u, 0u, 0u);
-        }
-    } else {
-        fill_load(0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-
-    // ---- token scales of this lane's output rows
-    float sa[MT][4];
-    if constexpr (!FUSEQ) {
-#pragma unroll
-        for (int t = 0; t < MT; ++t)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int m = 16 * t + 4 * kb + r;
-                sa[t][r] = m < a.M ? a.a_scale[m] : 0.0f;
-            }
-    }
-    // channel scales of this workgroup's row tiles: into LDS (behind the activations), so that an epilogue in
-    // mid-stream never waits on the vector memory counter, behind which the whole weight stream queues
-    float* lds_cs = reinterpret_cast<float*>(smem + p.cs_offset);
-    {
-        const int words = (t1 - t0) * 16;
-        for (int i = threadIdx.x; i < words; i += W * kWave) {
-            const float c = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(cres, (t0 * 16 + i) * 4, 0, 0));
-            lds_cs[i] = a.chan_scale ? c : 1.0f;
-        }
-    }
 
     // ---- the weight stream.  A wave's blocks are cut into segments (its run of K steps inside one row tile), a
     // segment into turns of DT blocks; the last turn of a segment is filled up with empty blocks (requests that lie
-    // outside the buffer and return zeros, with a zero scale), so that the ring of DT register slots always starts a
-    // segment at slot 0 and the turn below is straight-line code: slot u of a turn is requested while slot u of the
-    // turn before is used.
+    // outside the buffer and return zeros), so that the ring of DT register slots always starts a segment at slot 0
+    // and slot u of a turn is requested while slot u of the turn before is used, in straight-line code.
     v4i wq[DT];
     int scl[DT];
-    const float inv_spg = 1.0f / (float)p.spg;
     const int w_lane = lane * 16, s_lane = li * 4;
     // issue cursor (one turn ahead of the consume cursor)
     int rem_i = b1 - b0;
-    int tile_i, step_i, left_i;
-    {
-        const int q = b0 / ksl;
-        tile_i = t0 + q;
-        step_i = b0 - q * ksl;
-        left_i = min(ksl - step_i, rem_i);
-    }
+    // the tile of the wave's first block: floor(floor(wave * tiles * ksl / W) / ksl) = floor(wave * tiles / W)
+    const int q0 = (wave * (t1 - t0)) / W;
+    int tile_i = t0 + q0, step_i = b0 - q0 * ksl;
+    int left_i = min(ksl - step_i, rem_i);
     int woff_i = 0, soff_i = 0, sub_i = 0;
     auto issue_state = [&]() {
         const int s_abs = s_lo + step_i;
-        const int g = (int)(((float)s_abs + 0.5f) * inv_spg);  // s_abs / spg, exact below 2^20
+        int g = s_abs;  // s_abs / spg
+        if (p.spg != 1) {
+            g = __builtin_amdgcn_readfirstlane((int)(((float)s_abs + 0.5f) * __builtin_amdgcn_rcpf((float)p.spg)));
+            if (g * p.spg > s_abs) --g;
+            else if ((g + 1) * p.spg <= s_abs) ++g;
+        }
         woff_i = (tile_i * p.steps + s_abs) * kPkBlockBytes;
         soff_i = (tile_i * p.num_groups + g) * 64;
         sub_i = s_abs - g * p.spg;
@@ -200,6 +159,85 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
     for (int u = 0; u < DT; ++u) issue(u);
     issue_advance();
     __builtin_amdgcn_sched_barrier(0);
+    PK_MARK(1);
+
+    // ---- the activations of the slab, requested behind the stream's first blocks and written to LDS below.
+    // A fill unit is 8 token rows x one K step (8 x 128 bytes); unit u = step * (row blocks) + row block.
+    const int rs = p.rows;
+    const int unit_b = 64 * rs;  // bytes of one (step, token tile, MFMA half) unit: 4 k-chunks x rs rows x 16 bytes
+    const int step_stride = MT * 2 * unit_b;
+    [[maybe_unused]] uint4 xh[FUSEQ ? kFuseChunks : 1];
+    [[maybe_unused]] v4i xraw[FUSEQ ? 1 : kFill];
+    // row blocks of 8 token rows, rounded up to a power of two (rows past M are masked): unit -> (step, row block) by shifts
+    const int rb_log = a.M <= 8 ? 0 : a.M <= 16 ? 1 : a.M <= 32 ? 2 : 3;
+    const int units = ksl << rb_log;
+    [[maybe_unused]] auto fill_load = [&](int base) {
+        const rsrc_t xres = make_rsrc(a.xq, (size_t)a.M * a.K);
+#pragma unroll
+        for (int i = 0; i < kFill; ++i) {
+            const int u = base + i * W + wave;
+            if (i > 0 && base + i * W >= units) break;  // uniform: nothing left for any wave
+            const int step = u >> rb_log;
+            const int row = ((u - (step << rb_log)) << 3) + (lane >> 3);
+            const bool ok = u < units && row < a.M;
+            xraw[i] = __builtin_amdgcn_raw_buffer_load_b128(
+                xres, ok ? row * a.K + (s_lo + step) * 128 + (lane & 7) * 16 : kOutOfRange, 0, 0);
+        }
+    };
+    [[maybe_unused]] auto fill_store = [&](int base) {
+#pragma unroll
+        for (int i = 0; i < kFill; ++i) {
+            const int u = base + i * W + wave;
+            if (i > 0 && base + i * W >= units) break;
+            const int step = u >> rb_log;
+            const int row = ((u - (step << rb_log)) << 3) + (lane >> 3);
+            const int c8 = lane & 7;
+            if (u < units && row < a.M)
+                *reinterpret_cast<v4i*>(smem + ((step * MT + (row >> 4)) * 2 + (c8 >> 2)) * unit_b + (c8 & 3) * 16 * rs +
+                                        (row & 15) * 16) = xraw[i];
+        }
+    };
+    if constexpr (FUSEQ) {
+        const uint4* xrow = reinterpret_cast<const uint4*>(a.x_fp16);
+        const int chunks = a.K >> 3;
+#pragma unroll
+        for (int i = 0; i < kFuseChunks; ++i) {
+            const int c = (int)threadIdx.x + i * W * kWave;
+            xh[i] = c < chunks ? xrow[c] : make_uint4(0u, 0u, 0u, 0u);
+        }
+    } else {
+        fill_load(0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- token scales of this lane's output rows; channel scales of this workgroup's row tiles.  The latter go
+    // through LDS, so that an epilogue in mid-stream never waits on the vector memory counter, behind which the whole
+    // weight stream queues.
+    float sa[MT][4];
+    if constexpr (!FUSEQ) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int m = 16 * t + 4 * kb + r;
+                sa[t][r] = m < a.M ? a.a_scale[m] : 0.0f;
+            }
+    }
+    float* lds_cs = reinterpret_cast<float*>(smem + p.cs_offset);
+    constexpr int kCsPerThread = 1024 / (W * kWave) * 4;  // 256 row tiles x 16 rows per workgroup at most
+    const int cs_words = (t1 - t0) * 16;
+    float cs_reg[kCsPerThread];
+    {
+        const rsrc_t cres = make_rsrc(a.chan_scale, a.chan_scale ? (size_t)a.N * 4 : 0);
+#pragma unroll
+        for (int i = 0; i < kCsPerThread; ++i) {
+            const int w = (int)threadIdx.x + i * W * kWave;
+            cs_reg[i] = __int_as_float(
+                __builtin_amdgcn_raw_buffer_load_b32(cres, w < cs_words ? (t0 * 16 + w) * 4 : kOutOfRange, 0, 0));
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    PK_MARK(2);
 
     // ---- activations into LDS
     if constexpr (FUSEQ) {
@@ -224,7 +262,7 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) sa[0][r] = s_a;
-        if (a.a_scale_out && blockIdx.x == 0 && threadIdx.x == 0) *a.a_scale_out = s_a;
+        if (a.a_scale_out && slab == 0 && t0 == 0 && threadIdx.x == 0) *a.a_scale_out = s_a;  // the owner of tile 0
     } else {
         fill_store(0);
         for (int base = kFill * W; base < units; base += kFill * W) {
@@ -232,11 +270,18 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
             fill_store(base);
         }
     }
+#pragma unroll
+    for (int i = 0; i < kCsPerThread; ++i) {
+        const int w = (int)threadIdx.x + i * W * kWave;
+        if (w < cs_words) lds_cs[w] = a.chan_scale ? cs_reg[i] : 1.0f;
+    }
     lds_barrier();
+    PK_MARK(3);
 
     // ---- main loop
     const float inv_alpha = __int_as_float((127 - a.alpha_log2) << 23);  // 2^-alpha_log2, exact
-    const int a_lane = kb * 16 * rs + (li & (rs - 1)) * 16;
+    // (the fused quantiser leaves the whole token in LDS, not just this slab's K steps)
+    const int a_lane = kb * 16 * rs + (li & (rs - 1)) * 16 + (FUSEQ ? s_lo * step_stride : 0);
     acc_t acc[MT][4], headp[MT][4];
 #pragma unroll
     for (int t = 0; t < MT; ++t)
@@ -271,121 +316,170 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
                 }
             }
     };
+    // K split: a partial tile travels through the workspace as MT x 4 rows of 64 words (one per lane), written and read
+    // with device-scope accesses (they go past the L2 of the writer's or reader's own XCD), so that no cache has to be
+    // written back or invalidated as a whole.
     auto store_partial = [&](int tile, const acc_t (&v)[MT][4]) {
-        int32_t* dst = a.partials + ((size_t)(tile * p.slabs + slab) * MT) * 256 + lane * 4;
+        int32_t* dst = a.partials + ((size_t)(tile * p.slabs + slab) * MT) * 256 + lane;
 #pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            v4i o;
+        for (int t = 0; t < MT; ++t)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                if constexpr (INT_SCALE) o[r] = v[t][r];
-                else o[r] = __float_as_int(v[t][r]);
+                int o;
+                if constexpr (INT_SCALE) o = v[t][r];
+                else o = __float_as_int(v[t][r]);
+                __hip_atomic_store(dst + (t * 4 + r) * kWave, o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            *reinterpret_cast<v4i*>(dst + t * 256) = o;
-        }
     };
 
     // consume cursor
     int rem_c = b1 - b0;
-    int tile_c, step_c, left_c;
-    {
-        const int q = b0 / ksl;
-        tile_c = t0 + q;
-        step_c = b0 - q * ksl;
-        left_c = min(ksl - step_c, rem_c);
-    }
+    int tile_c = t0 + q0, step_c = b0 - q0 * ksl;
+    int left_c = min(ksl - step_c, rem_c);
     bool seg_whole = step_c == 0 && left_c == ksl;
     bool seg_first = true;
-    while (rem_c > 0) {
-        // ---- one turn of the ring: straight-line code
-        sub_run = sub_i;
-        goff_run = 0;
+    int a_addr = a_lane + step_c * step_stride;  // LDS address of this lane's first A operand of the next block
+    // A operands of one block, from LDS
+    auto read_operands = [&](v4i (&xa)[MT][2]) {
 #pragma unroll
-        for (int u = 0; u < DT; ++u) {
-            const int a_off = a_lane + (u < left_c ? (step_c + u) * step_stride : 0);  // empty block: any valid address
-            v4i xa[MT][2];
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if constexpr (MT > 1) xa[t][h] = *reinterpret_cast<const v4i*>(smem + a_addr + (t * 2 + h) * 1024);
+                else xa[t][h] = *reinterpret_cast<const v4i*>(smem + a_addr + h * unit_b);
+            }
+        a_addr += step_stride;
+    };
+    // One block: unpack, multiply, scale step
+    auto slot = [&](auto wide_c, int u, const v4i (&xa)[MT][2]) {
+        constexpr bool WIDE = decltype(wide_c)::value;
+        v4i w_lo, w_hi;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t pk = (uint32_t)wq[u][q];
+            w_lo[q] = (int)((pk << 4) & 0xF0F0F0F0u);
+            w_hi[q] = (int)(pk & 0xF0F0F0F0u);
+        }
+        const int s_i = scl[u];
+        const float s_f = __int_as_float(s_i) * 0.0625f;  // 16 P * (s / 16) = float(P) * s exactly
+        v4i part[MT];
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            part[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa[t][0], w_lo, v4i{0, 0, 0, 0}, 0, 0, 0);
+            part[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa[t][1], w_hi, part[t], 0, 0, 0);
+        }
+        if constexpr (!INT_SCALE) {
 #pragma unroll
             for (int t = 0; t < MT; ++t)
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    if constexpr (MT > 1) xa[t][h] = *reinterpret_cast<const v4i*>(smem + a_off + (t * 2 + h) * 1024);
-                    else xa[t][h] = *reinterpret_cast<const v4i*>(smem + a_off + h * unit_b);
-                }
-            v4i w_lo, w_hi;
+                for (int r = 0; r < 4; ++r) acc[t][r] = fmaf((float)part[t][r], s_f, acc[t][r]);  // C' += float(C_g) * s_g
+        } else if constexpr (WIDE) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t pk = (uint32_t)wq[u][q];
-                w_lo[q] = (int)((pk << 4) & 0xF0F0F0F0u);
-                w_hi[q] = (int)(pk & 0xF0F0F0F0u);
-            }
-            const int s_i = scl[u];
-            const float s_f = __int_as_float(s_i) * 0.0625f;  // 16 P * (s / 16) = float(P) * s exactly
-#pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                v4i part = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa[t][0], w_lo, v4i{0, 0, 0, 0}, 0, 0, 0);
-                part = __builtin_amdgcn_mfma_i32_16x16x64_i8(xa[t][1], w_hi, part, 0, 0, 0);
+            for (int t = 0; t < MT; ++t)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    if constexpr (!INT_SCALE) {
-                        acc[t][r] = fmaf((float)part[r], s_f, acc[t][r]);  // C' += float(C_g) * s_g
-                    } else if constexpr (WIDE) {
-                        int prod = (part[r] >> 4) * s_i;
-                        asm volatile("" : "+v"(prod));  // else a 64-bit multiply-add with register pairs
-                        acc[t][r] += prod;
-                    } else {
-                        acc[t][r] += __mul24(part[r] >> 4, s_i);  // C'' += C_g * s_g^INT
-                    }
+                    int prod = (part[t][r] >> 4) * s_i;
+                    asm volatile("" : "+v"(prod));  // else a 64-bit multiply-add with register pairs
+                    acc[t][r] += prod;
                 }
-            }
-            // The slot's registers are free now and take the same slot of the next turn.  (Not earlier: a request
-            // issued while the old weights or the old scale are still needed gets registers of its own, and the
-            // compiler then copies them over behind a wait for the whole ring.)
-            __builtin_amdgcn_sched_barrier(0);
-            issue(u);
-            __builtin_amdgcn_sched_barrier(0);
+        } else {
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[t][r] = mad_i24(part[t][r] >> 4, s_i, acc[t][r]);  // C'' += C_g * s_g^INT
         }
-        issue_advance();
-        const int adv = min(DT, left_c);
-        rem_c -= adv;
-        step_c += adv;
-        left_c -= adv;
-        if (left_c == 0) {
-            // ---- the segment is complete: its row tile is finished (epilogue, or this slab's partial), or it is one
-            // of the two pieces a wave can share with its neighbours (its first and its last segment)
-            if (seg_whole) {
-                if (p.slabs == 1) {
-                    epilogue(tile_c, acc);
-                } else {
-                    store_partial(tile_c, acc);
-                    if (done_hi == done_lo) done_lo = tile_c;
-                    done_hi = tile_c + 1;
-                }
-            } else if (seg_first) {
+    };
+    // One turn of the ring.  REFILL: every slot, once used, takes the same slot of the next turn (the wave's last turn
+    // requests nothing).  FULL: all DT blocks of the turn exist: no block is tested, and the operands of the next block
+    // are read from LDS while the current one is multiplied.
+    auto turn = [&](auto wide_c, auto refill_c, auto full_c) {
+        constexpr bool REFILL = decltype(refill_c)::value;
+        constexpr bool FULL = decltype(full_c)::value;
+        sub_run = sub_i;
+        goff_run = 0;
+        v4i xa[2][MT][2];
+        if constexpr (FULL) read_operands(xa[0]);
 #pragma unroll
-                for (int t = 0; t < MT; ++t)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) headp[t][r] = acc[t][r];
-                head_tile = tile_c;
+        for (int u = 0; u < DT; ++u) {
+            if constexpr (FULL) {
+                if (u + 1 < DT) read_operands(xa[(u + 1) & 1]);
+                slot(wide_c, u, xa[u & 1]);
             } else {
-                tail_tile = tile_c;  // a later unfinished segment can only be the wave's last one: it stays in acc
+                if (u < left_c) {  // an empty block at the end of a segment is skipped
+                    read_operands(xa[0]);
+                    slot(wide_c, u, xa[0]);
+                }
             }
-            if (rem_c > 0) {
-#pragma unroll
-                for (int t = 0; t < MT; ++t)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[t][r] = 0;
-                seg_first = false;
-                ++tile_c;
-                step_c = 0;
-                left_c = min(ksl, rem_c);
-                seg_whole = left_c == ksl;
+            if constexpr (REFILL) {
+                // The slot's registers are free now.  (Not earlier: a request issued while the old weights or the old
+                // scale are still needed gets registers of its own, and the compiler then copies them over behind a
+                // wait for the whole ring.)
+                __builtin_amdgcn_sched_barrier(0);
+                issue(u);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-    }
+    };
+    // (the loop exists twice: with the 24-bit multiply of the scale step, and with full 32-bit multiplies)
+    auto run_loop = [&](auto wide_c) {
+        while (rem_c > 0) {
+            if (rem_i > 0) {
+                if (left_c >= DT) turn(wide_c, std::true_type{}, std::true_type{});
+                else turn(wide_c, std::true_type{}, std::false_type{});
+                issue_advance();
+            } else {  // nothing is left to request: these blocks are the wave's last
+                if (left_c >= DT) turn(wide_c, std::false_type{}, std::true_type{});
+                else turn(wide_c, std::false_type{}, std::false_type{});
+            }
+            const int adv = min(DT, left_c);
+            rem_c -= adv;
+            step_c += adv;
+            left_c -= adv;
+            if (left_c == 0) {
+                // ---- the segment is complete: its row tile is finished (epilogue, or this slab's partial), or it is one
+                // of the two pieces a wave can share with its neighbours (its first and its last segment)
+                if (seg_whole) {
+                    if (p.slabs == 1) {
+                        epilogue(tile_c, acc);
+                    } else {
+                        store_partial(tile_c, acc);
+                        if (done_hi == done_lo) done_lo = tile_c;
+                        done_hi = tile_c + 1;
+                    }
+                } else if (seg_first) {
+    #pragma unroll
+                    for (int t = 0; t < MT; ++t)
+    #pragma unroll
+                        for (int r = 0; r < 4; ++r) headp[t][r] = acc[t][r];
+                    head_tile = tile_c;
+                } else {
+                    tail_tile = tile_c;  // a later unfinished segment can only be the wave's last one: it stays in acc
+                }
+                if (rem_c > 0) {
+    #pragma unroll
+                    for (int t = 0; t < MT; ++t)
+    #pragma unroll
+                        for (int r = 0; r < 4; ++r) acc[t][r] = 0;
+                    seg_first = false;
+                    ++tile_c;
+                    step_c = 0;
+                    a_addr = a_lane;
+                    left_c = min(ksl, rem_c);
+                    seg_whole = left_c == ksl;
+                }
+            }
+        }
+    };
+    if (INT_SCALE && (pk_flags & kPkFlagWide) != 0) run_loop(std::true_type{});
+    else run_loop(std::false_type{});
+    PK_MARK(4);
 
-    // ---- pieces of row tiles shared by several waves meet in LDS (the activations are no longer needed)
-    lds_barrier();
-    int* slots = reinterpret_cast<int*>(smem);  // [wave][2][MT][64 lanes][4]
+    // ---- pieces of row tiles shared by several waves meet in LDS (in the activations' space once nobody reads them
+    // any more, or behind them where there is room)
+    if (p.slot_offset == 0) lds_barrier();
+    // [wave][2][MT][64 lanes][4] words, then one tag per piece: the row tile it belongs to, or -1
+    int* slots = reinterpret_cast<int*>(smem + p.slot_offset);
+    int* tags = slots + W * 2 * MT * kWave * 4;
     auto slot_ptr = [&](int w, int which, int t) { return slots + (((w * 2 + which) * MT + t) * kWave + lane) * 4; };
     if (head_tile >= 0) {
 #pragma unroll
@@ -411,30 +505,42 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
             *reinterpret_cast<v4i*>(slot_ptr(wave, 1, t)) = o;
         }
     }
+    if (lane < 2) tags[wave * 2 + lane] = lane == 0 ? head_tile : tail_tile;
     lds_barrier();
+    PK_MARK(5);
 
-    // Row tile tt of this workgroup is shared if its first and last block belong to different waves; wave
-    // (tt - t0) mod W adds the pieces in wave order.  Block x belongs to wave floor(((x + 1) W - 1) / B).
+    // Wave (tt - t0) mod W adds the pieces of row tile tt, in wave order; a tile without pieces was finished by a
+    // single wave in the main loop.  Pieces are found by their tags: lane i < 2 W looks at piece i.
+    static_assert(2 * W <= kWave, "one lane per piece tag");
+    const int my_tag = lane < 2 * W ? tags[lane] : -1;
     auto shared_tile_sum = [&](int tt, acc_t (&v)[MT][4]) -> bool {
-        const int start = (tt - t0) * ksl;
-        const int wf = ((start + 1) * W - 1) / B, wl = ((start + ksl) * W - 1) / B;
-        if (wf == wl) return false;
+        unsigned long long pieces = __ballot(my_tag == tt);
+        if (pieces == 0) return false;
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll
             for (int r = 0; r < 4; ++r) v[t][r] = 0;
-        for (int w = wf; w <= wl; ++w) {
-            const int wb0 = (int)((long long)w * B / W);
-            const int which = (t0 + wb0 / ksl == tt) ? 0 : 1;  // the wave's first segment, or its last
+        while (pieces != 0) {
+            // up to four pieces at a time, their reads in flight together
+            v4i o[4][MT];
+            bool use[4];
 #pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                const v4i o = *reinterpret_cast<const v4i*>(slot_ptr(w, which, t));
+            for (int i = 0; i < 4; ++i) {
+                use[i] = pieces != 0;
+                const int idx = use[i] ? __builtin_ctzll(pieces) : 0;
+                if (use[i]) pieces &= pieces - 1;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    if constexpr (INT_SCALE) v[t][r] += o[r];
-                    else v[t][r] += __int_as_float(o[r]);
-                }
+                for (int t = 0; t < MT; ++t) o[i][t] = *reinterpret_cast<const v4i*>(slot_ptr(idx >> 1, idx & 1, t));
             }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        if constexpr (INT_SCALE) v[t][r] += use[i] ? o[i][t][r] : 0;
+                        else v[t][r] += use[i] ? __int_as_float(o[i][t][r]) : 0.0f;
+                    }
         }
         return true;
     };
@@ -445,6 +551,7 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
             if (!shared_tile_sum(tt, v)) continue;
             epilogue(tt, v);
         }
+        PK_MARK(6);
         return;
     }
 
@@ -454,50 +561,43 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
         acc_t v[MT][4];
         if (shared_tile_sum(tt, v)) store_partial(tt, v);
     }
-    __threadfence();  // release: the partials above (and the ones stored from the main loop) before the counters
+    // the partials above (and the ones stored from the main loop) have been written through before a counter is raised
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     auto arrive = [&](int tt) {
         int old = 0;
-        if (lane == 0) old = atomicAdd(a.counters + tt, 1);
+        if (lane == 0) old = __hip_atomic_fetch_add(a.counters + tt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         old = __builtin_amdgcn_readfirstlane(old);
         if (old != p.slabs - 1) return;
-        __threadfence();  // acquire: the other slabs' partials
+        // the last to arrive: every slab's partial is in the workspace; add them in slab order
         acc_t v[MT][4];
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll
             for (int r = 0; r < 4; ++r) v[t][r] = 0;
         for (int s = 0; s < p.slabs; ++s) {
-            const int32_t* src = a.partials + ((size_t)(tt * p.slabs + s) * MT) * 256 + lane * 4;
+            int32_t* src = a.partials + ((size_t)(tt * p.slabs + s) * MT) * 256 + lane;
 #pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                const v4i o = *reinterpret_cast<const v4i*>(src + t * 256);
+            for (int t = 0; t < MT; ++t)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    if constexpr (INT_SCALE) v[t][r] += o[r];
-                    else v[t][r] += __int_as_float(o[r]);
+                    const int o = __hip_atomic_load(src + (t * 4 + r) * kWave, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if constexpr (INT_SCALE) v[t][r] += o;
+                    else v[t][r] += __int_as_float(o);
                 }
-            }
         }
         epilogue(tt, v);
-        if (lane == 0) a.counters[tt] = 0;  // left zero for the next call
+        if (lane == 0) __hip_atomic_store(a.counters + tt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // zero for the next call
     };
     for (int tt = done_lo; tt < done_hi; ++tt) arrive(tt);
-    for (int tt = t0 + wave; tt < t1; tt += W) {
-        const int start = (tt - t0) * ksl;
-        if (((start + 1) * W - 1) / B != ((start + ksl) * W - 1) / B) arrive(tt);
-    }
+    for (int tt = t0 + wave; tt < t1; tt += W)
+        if (__ballot(my_tag == tt) != 0) arrive(tt);
+    PK_MARK(6);
 }
 
 template <int MT, int DT, int WAVES, bool INT_SCALE, bool FUSEQ>
 __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_pk_kernel(PkArgs a, PkKernelPlan p) {
     extern __shared__ __align__(16) unsigned char smem_pk[];
-    if constexpr (INT_SCALE) {
-        const int flags = *reinterpret_cast<const int32_t*>(a.spack);
-        if (flags & kPkFlagWide) decode_pk_body<MT, DT, WAVES, true, FUSEQ, true>(a, p, smem_pk);
-        else decode_pk_body<MT, DT, WAVES, true, FUSEQ, false>(a, p, smem_pk);
-    } else {
-        decode_pk_body<MT, DT, WAVES, false, FUSEQ, false>(a, p, smem_pk);
-    }
+    decode_pk_body<MT, DT, WAVES, INT_SCALE, FUSEQ>(a, p, smem_pk);
 }
 
 template <int MT, int DT, int WAVES, bool INT_SCALE, bool FUSEQ>
@@ -512,16 +612,28 @@ hipError_t launch_pk(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan
             if (device >= 0 && device < 64) raised[device] = true;
         }
     }
-    hipLaunchKernelGGL(kern, dim3(plan.slabs * plan.wg_per_slab), dim3(WAVES * kWave), plan.lds_bytes, stream, a, kp);
+    hipLaunchKernelGGL(kern, dim3(plan.wg_per_slab, plan.slabs), dim3(WAVES * kWave), plan.lds_bytes, stream, a, kp);
     return hipGetLastError();
+}
+
+template <bool INT_SCALE, bool FUSEQ, int MT>
+hipError_t dispatch_waves(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan, int device, hipStream_t stream) {
+    if constexpr (MT == 4) {
+        if (plan.waves == 4) return launch_pk<4, 6, 4, INT_SCALE, false>(a, kp, plan, device, stream);
+        return launch_pk<4, 6, 8, INT_SCALE, false>(a, kp, plan, device, stream);
+    } else {
+        if (plan.waves == 4) return launch_pk<MT, 4, 4, INT_SCALE, FUSEQ>(a, kp, plan, device, stream);
+        if (plan.waves == 8) return launch_pk<MT, 4, 8, INT_SCALE, FUSEQ>(a, kp, plan, device, stream);
+        return launch_pk<MT, 4, 16, INT_SCALE, FUSEQ>(a, kp, plan, device, stream);
+    }
 }
 
 template <bool INT_SCALE>
 hipError_t dispatch_pk(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan, int device, hipStream_t stream) {
-    if (a.x_fp16) return launch_pk<1, 4, 16, INT_SCALE, true>(a, kp, plan, device, stream);
-    if (plan.mt == 1) return launch_pk<1, 4, 16, INT_SCALE, false>(a, kp, plan, device, stream);
-    if (plan.mt == 2) return launch_pk<2, 4, 16, INT_SCALE, false>(a, kp, plan, device, stream);
-    return launch_pk<4, 6, 8, INT_SCALE, false>(a, kp, plan, device, stream);
+    if (a.x_fp16) return dispatch_waves<INT_SCALE, true, 1>(a, kp, plan, device, stream);
+    if (plan.mt == 1) return dispatch_waves<INT_SCALE, false, 1>(a, kp, plan, device, stream);
+    if (plan.mt == 2) return dispatch_waves<INT_SCALE, false, 2>(a, kp, plan, device, stream);
+    return dispatch_waves<INT_SCALE, false, 4>(a, kp, plan, device, stream);
 }
 
 constexpr size_t kActBudget = 128 * 1024;  // LDS bytes for the slab's activations (the fused quantiser's scratch follows)
@@ -535,7 +647,6 @@ bool pk_decode_plan(int M, int N, int K, int group, bool fp16_in, PkPlan* plan) 
     if (pk_weight_bytes(N, K) >= (1ull << 31)) return false;
     PkPlan pl;
     pl.mt = M <= 16 ? 1 : M <= 32 ? 2 : 4;
-    pl.waves = pl.mt == 4 ? 8 : 16;  // four token tiles need more than 128 registers per lane
     int rows = 16;
     if (pl.mt == 1) {
         rows = 1;
@@ -551,27 +662,54 @@ bool pk_decode_plan(int M, int N, int K, int group, bool fp16_in, PkPlan* plan) 
     // More slabs than the activations need can even out the shares (tiles per workgroup x steps per slab is what a
     // workgroup carries) at the price of more partial tiles: take the best of a few candidates.
     int best = s_min;
+    int forced = 0;  // INTSCALE_PK_SLABS=n (experiments): n slabs, if the activations allow
+    if (const char* e = getenv("INTSCALE_PK_SLABS")) forced = atoi(e);
     double best_cost = 0.0;
     for (int s = s_min; s <= s_min + 4 && s <= steps && s <= cus; ++s) {
         const int wgs = cus / s;
+        // blocks a workgroup carries (a CU takes about 23 per microsecond); a K split that is not forced costs about
+        // 2 microseconds of store, counter and reload at the end, and its partial tiles some traffic
         const double load = (double)((n16 + wgs - 1) / wgs) * (double)((steps + s - 1) / s);
-        const double cost = load * (1.0 + 0.04 * (s - 1));
+        const double cost = load * (1.0 + 0.04 * (s - 1)) + (s > 1 ? 46.0 : 0.0);
         if (s == s_min || cost < best_cost) {
             best = s;
             best_cost = cost;
         }
     }
+    if (forced >= s_min && forced <= steps && forced <= cus) best = forced;
     pl.slabs = best;
     pl.wg_per_slab = cus / best;
     if (pl.wg_per_slab < 1) return false;
     if (best > 1 && n16 > kPkMaxTiles) return false;
     pl.max_steps = (steps + best - 1) / best;
-    const size_t act = per_step * pl.max_steps;
-    const size_t slots = (size_t)pl.waves * 2 * pl.mt * 1024;
     const int tiles_max = (n16 + pl.wg_per_slab - 1) / pl.wg_per_slab;
-    if (tiles_max > 256) return false;  // the workgroup's channel scales take 64 bytes of LDS per row tile
-    // LDS: [activations of the slab, later the pieces of shared tiles | 64 bytes: the waves' absmax | channel scales]
-    pl.cs_offset = (int)(act > slots ? act : slots) + 64;
+    if (tiles_max > 256) return false;  // a workgroup stages at most 4096 channel scales
+    // Waves per workgroup: enough for every wave to have a full turn of the ring (fewer, fatter waves start sooner and
+    // leave fewer pieces to add up), 16 at most; four token tiles need more than 128 registers per lane: 8 at most.
+    const int dt = pl.mt == 4 ? 6 : 4;
+    const long long blocks = (long long)tiles_max * pl.max_steps;
+    int waves = pl.mt == 4 ? 8 : 4;
+    while (waves < (pl.mt == 4 ? 8 : 16) && (long long)waves * 2 * dt <= blocks) waves *= 2;
+    if (fp16_in)
+        while ((K >> 3) > kFuseChunks * waves * kWave) waves *= 2;  // the token's chunks over the threads
+    if (const char* e = getenv("INTSCALE_PK_WAVES")) {  // experiments
+        const int w = atoi(e);
+        if ((w == 4 || w == 8 || (w == 16 && pl.mt != 4)) && (!fp16_in || (K >> 3) <= kFuseChunks * w * kWave)) waves = w;
+    }
+    pl.waves = waves;
+    // LDS: [activations of the slab | pieces of shared tiles (behind the activations if there is room, else in their
+    // place) | 64 bytes: the waves' absmax | channel scales]
+    // (the fused quantiser keeps the whole token in LDS, whatever the slab)
+    const size_t act = fp16_in ? (size_t)K : per_step * pl.max_steps;
+    const size_t slots = (size_t)pl.waves * 2 * pl.mt * 1024 + 256;  // pieces, then their tags
+    const size_t tail = 64 + (size_t)tiles_max * 64;
+    if (act + slots + tail <= 160 * 1024) {
+        pl.slot_offset = (int)act;
+        pl.cs_offset = (int)(act + slots) + 64;
+    } else {
+        pl.slot_offset = 0;
+        pl.cs_offset = (int)(act > slots ? act : slots) + 64;
+    }
     pl.lds_bytes = (size_t)pl.cs_offset + (size_t)tiles_max * 64;
     *plan = pl;
     return true;
@@ -592,9 +730,13 @@ hipError_t launch_gemm_decode_pk(const PkArgs& a, bool int_scale, hipStream_t st
     kp.num_groups = a.K / a.group;
     kp.spg = a.group / 128;
     kp.slabs = plan.slabs;
-    kp.wg_per_slab = plan.wg_per_slab;
+    kp.steps_q = kp.steps / plan.slabs;
+    kp.steps_r = kp.steps % plan.slabs;
+    kp.tiles_q = kp.n16 / plan.wg_per_slab;
+    kp.tiles_r = kp.n16 % plan.wg_per_slab;
     kp.rows = plan.rows;
     kp.cs_offset = plan.cs_offset;
+    kp.slot_offset = plan.slot_offset;
     kp.wbytes = pk_weight_bytes(a.N, a.K);
     kp.sbytes = pk_scale_bytes(a.N, a.K, a.group) - kPkHeaderBytes;
     int device = -1;

@@ -40,6 +40,7 @@ struct PkPlan {
     int slabs;        // K split across workgroups (1 = none)
     int wg_per_slab;  // workgroups per slab
     int max_steps;    // K steps of the longest slab
+    int slot_offset;  // LDS byte offset of the pieces of shared tiles (0: in the activations' place)
     int cs_offset;    // LDS byte offset of the workgroup's channel scales
     size_t lds_bytes;
 };
