@@ -351,7 +351,7 @@ size_t is_gemm_prepacked_workspace_bytes(int M, int N, int K, int group) {
     if (M < 0 || check_pk_shape(N, K, group) != IS_OK) return 0;
     if (M == 0) return 0;
     if (M <= 64) return pk_decode_workspace_bytes(M, N, K, group);
-    return 0;
+    return gemm_tile_pk_workspace_bytes(M, K);  // prepared activations and zero-point corrections
 }
 
 static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_scale, float* a_scale_out,
@@ -362,10 +362,11 @@ static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_s
     const int shape = check_pk_shape(N, K, group);
     if (shape != IS_OK) return shape;
     if (int_scale && (alpha_log2 < 0 || alpha_log2 > 30)) return IS_ERR_INVALID_ARG;
-    if (M > 64) return IS_ERR_UNSUPPORTED;
+    if (M > (1 << 20)) return IS_ERR_UNSUPPORTED;
     if (!ok_opt(workspace)) return IS_ERR_INVALID_ARG;
     PkPlan plan;
-    if (M > 0 && !pk_decode_plan(M, N, K, group, x_fp16 != nullptr, &plan)) return IS_ERR_UNSUPPORTED;
+    if (M > 0 && M <= 64 && !pk_decode_plan(M, N, K, group, x_fp16 != nullptr, &plan)) return IS_ERR_UNSUPPORTED;
+    if (M > 64 && (long long)((M + 15) / 16) * 16 * K >= (1LL << 31)) return IS_ERR_UNSUPPORTED;  // 32-bit offsets
     const size_t need = is_gemm_prepacked_workspace_bytes(M, N, K, group);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return IS_ERR_WORKSPACE;
     if (!ok_ptr(wpack) || !ok_ptr(spack) || !ok_opt(chan_scale)) return IS_ERR_INVALID_ARG;
@@ -384,12 +385,13 @@ static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_s
     a.out = static_cast<__half*>(out_fp16);
     a.acc_out = acc_out;
     a.counters = static_cast<int32_t*>(workspace);
-    a.partials = need > 0 ? reinterpret_cast<int32_t*>(static_cast<unsigned char*>(workspace) + kPkCounterBytes) : nullptr;
+    a.partials = (need > 0 && M <= 64) ? reinterpret_cast<int32_t*>(static_cast<unsigned char*>(workspace) + kPkCounterBytes) : nullptr;
     a.M = M;
     a.N = N;
     a.K = K;
     a.group = group;
     a.alpha_log2 = int_scale ? alpha_log2 : 0;
+    if (M > 64) return hip_status(launch_gemm_tile_pk(a, int_scale, workspace, static_cast<hipStream_t>(stream)));
     return hip_status(launch_gemm_decode_pk(a, int_scale, static_cast<hipStream_t>(stream)));
 }
 
@@ -420,7 +422,6 @@ static int linear_pk_common(const void* x_fp16, const void* wpack, const void* s
     if (M < 0) return IS_ERR_INVALID_ARG;
     const int shape = check_pk_shape(N, K, group);
     if (shape != IS_OK) return shape;
-    if (M > 64) return IS_ERR_UNSUPPORTED;
     const size_t need = is_linear_prepacked_workspace_bytes(M, N, K, group);
     if (!ok_opt(workspace)) return IS_ERR_INVALID_ARG;
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return IS_ERR_WORKSPACE;
@@ -435,11 +436,14 @@ static int linear_pk_common(const void* x_fp16, const void* wpack, const void* s
     if (M == 1 && pk_decode_plan(1, N, K, group, true, &plan))  // one token: quantised inside the GEMM kernel
         return gemm_pk_common(nullptr, x_fp16, nullptr, sa, wpack, spack, chan_scale, M, N, K, group, alpha_log2,
                               out_fp16, acc_out, rest, rest_bytes, stream, int_scale);
+    if (M > 64 && gemm_tile_pk_takes_fp16(K))  // many tokens: the tiled kernel's preparation quantises on the way
+        return gemm_pk_common(nullptr, x_fp16, sa, sa, wpack, spack, chan_scale, M, N, K, group, alpha_log2, out_fp16,
+                              acc_out, rest, rest_bytes, stream, int_scale);
     // the arguments of the GEMM are checked before the quantiser is enqueued
     if (!ok_ptr(wpack) || !ok_ptr(spack) || !ok_opt(chan_scale) || !ok_ptr(out_fp16) || !ok_opt(acc_out))
         return IS_ERR_INVALID_ARG;
     if (int_scale && (alpha_log2 < 0 || alpha_log2 > 30)) return IS_ERR_INVALID_ARG;
-    if (!pk_decode_plan(M, N, K, group, false, &plan)) return IS_ERR_UNSUPPORTED;
+    if (M <= 64 && !pk_decode_plan(M, N, K, group, false, &plan)) return IS_ERR_UNSUPPORTED;
     const int st = hip_status(launch_quantize_act(static_cast<const __half*>(x_fp16), M, K, xq, sa,
                                                   static_cast<hipStream_t>(stream)));
     if (st != IS_OK) return st;

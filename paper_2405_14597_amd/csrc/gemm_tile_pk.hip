@@ -1,0 +1,397 @@
+// MFMA-bound regime (more than 64 token rows: prefill) of the fine-grained W4A8 GEMM on prepacked weights.
+// Integer-scale form: Eq. (2) / Table 2 "Ours" of the Integer Scale paper; float-scale form: Eq. (1) / Table 2 "Atom".
+// The two differ only in the per-group scale step, where the paper's saving lives: one v_mad_i32_i24 per partial
+// product against a convert plus a multiply-add.
+//
+// What bounds this regime on gfx950.  A v_mfma_i32_16x16x64_i8 keeps the matrix pipe busy for 16 cycles, and an
+// ordinary vector instruction costs the SIMD's issue port about 4; Eq. (2)'s scale step alone is 2 of those per MFMA
+// at group size 128 (Eq. (1)'s is 4), so every further vector instruction per MFMA comes straight off the matrix
+// pipe's share.  The int4 -> int8 unpacking is the largest such cost, and it is paid per wave and K step for the
+// wave's weight rows whatever the number of token rows it multiplies them with; so a wave here owns 128 token rows x
+// 64 weight rows (8 x 4 MFMA sub-tiles): 0.75 unpack instructions per MFMA, half of what a 64 x 64 wave tile pays.
+//
+// Tiling.  A workgroup is 4 waves (1 x 4) on 128 token rows x 256 weight rows, one wave per SIMD, 256 registers per
+// wave; two workgroups share a CU (their 67 KB of LDS each allow it), so every SIMD holds two waves of DIFFERENT
+// workgroups: they meet no common barrier, drift apart by themselves, and one's unpacking and LDS waits fall under the
+// other's MFMAs.
+//
+// Operand pipeline.  K advances in steps of 128 (one MFMA pair) through two LDS stages.  Both operands come in
+// layouts that are already the order the MFMA lanes want (weights: the prepacked 1 KB blocks of pk_common.h;
+// activations: 2 KB blocks of 16 token rows x 128 k written by the preparation kernel below), so they travel from
+// global memory straight into LDS (buffer loads with the LDS bit: no staging registers, no address arithmetic per
+// lane beyond one offset) and every LDS read of a wave is one contiguous kilobyte: no bank conflicts, no swizzle.
+// The group scales of the step's 256 weight rows and the zero-point corrections of its 128 token rows ride along.
+//
+// int4 -> int8 with a zero point: a packed word XOR 0x08.. AND 0x0F.. is q + 8 for the low nibbles (one three-input
+// bit operation), the high nibbles take a shift more; the product sum comes out as P + 8 * sum_k x[m,k], and the
+// correction -8 * sum_k x[m,k] per (token row, K step), computed once by the preparation kernel, enters each MFMA
+// chain as its initial accumulator, so the chain returns P exactly and the scale step costs one instruction per element.
+#include "act_common.h"
+#include "pk_common.h"
+#include "tile_common.h"
+
+namespace intscale {
+namespace {
+
+constexpr int kTM = 128, kTN = 256;     // workgroup tile: token rows x weight rows
+constexpr int kTThreads = 256;          // 4 waves, one per SIMD
+constexpr int kMS = 8, kNS = 4;         // 16-row sub-tiles per wave: token rows, weight rows
+// (the corrections take 512 bytes; their load writes a full kilobyte, the upper half zeros)
+constexpr int kABytes = kTM * 128, kBBytes = kTN * 64, kScBytes = kTN * 4, kC0Bytes = 1024;
+constexpr int kStage = kABytes + kBBytes + kScBytes + kC0Bytes;  // 34816
+constexpr int kXcdCount = 8;            // workgroup i is dispatched to XCD i % 8
+constexpr int kGroupRows = 8;           // tile rows of the block of tiles an XCD works on at a time
+
+// ---- preparation of the activations: 2 KB blocks [16-row tile][K step] = [MFMA half h][k chunk kb][row r][16 codes],
+// the 16 codes of (h, kb) being k = 128 s + 64 h + 16 kb .. + 15 of row 16 mt + r, and the zero-point corrections
+// c0[tile][step][r] = -8 * sum over the step's 128 codes.  One workgroup per token row; 8 lanes share a K step.
+__device__ __forceinline__ void store_prepared(int m, int c, uint4 v, int steps, int8_t* __restrict__ xp,
+                                               int32_t* __restrict__ c0, bool valid) {
+    int sum = 0;
+    if (valid) {
+        sum = __builtin_amdgcn_sdot4((int)v.x, 0x01010101, sum, false);
+        sum = __builtin_amdgcn_sdot4((int)v.y, 0x01010101, sum, false);
+        sum = __builtin_amdgcn_sdot4((int)v.z, 0x01010101, sum, false);
+        sum = __builtin_amdgcn_sdot4((int)v.w, 0x01010101, sum, false);
+        const size_t blk = (size_t)(m >> 4) * steps + (c >> 3);
+        *reinterpret_cast<uint4*>(xp + blk * 2048 + ((c >> 2) & 1) * 1024 + (c & 3) * 256 + (m & 15) * 16) = v;
+    }
+    sum += __shfl_xor(sum, 1, kWave);
+    sum += __shfl_xor(sum, 2, kWave);
+    sum += __shfl_xor(sum, 4, kWave);
+    if ((threadIdx.x & 7) == 0 && valid) c0[((size_t)(m >> 4) * steps + (c >> 3)) * 16 + (m & 15)] = -8 * sum;
+}
+
+__global__ __launch_bounds__(256) void prepare_activations_pk_kernel(const int8_t* __restrict__ xq, int M, int K,
+                                                                     int8_t* __restrict__ xp, int32_t* __restrict__ c0) {
+    const int m = blockIdx.x;
+    const uint4* row = reinterpret_cast<const uint4*>(xq + (size_t)m * K);
+    const int nchunk = K >> 4, steps = K >> 7;
+    for (int cb = 0; cb < nchunk; cb += 256) {
+        const int c = cb + threadIdx.x;
+        const bool valid = c < nchunk;
+        store_prepared(m, c, valid ? row[c] : make_uint4(0u, 0u, 0u, 0u), steps, xp, c0, valid);
+    }
+}
+
+// The same straight from fp16 activations (the linear call): the per-token quantiser of Appendix A.1 and the
+// preparation in one pass, the row held in registers (CH chunks of 16 values per lane) between absmax and rounding.
+template <int CH>
+__global__ __launch_bounds__(256) void quantize_prepare_activations_pk_kernel(const __half* __restrict__ x, int M, int K,
+                                                                              int8_t* __restrict__ xp,
+                                                                              int32_t* __restrict__ c0,
+                                                                              float* __restrict__ a_scale) {
+    __shared__ float red[4];
+    const int m = blockIdx.x;
+    const int lane = threadIdx.x;
+    const uint4* row = reinterpret_cast<const uint4*>(x + (size_t)m * K);  // 8 fp16 values each
+    const int nchunk = K >> 4, steps = K >> 7;
+    uint4 v[CH][2];
+    float amax = 0.0f;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+        const int c = lane + j * 256;
+        v[j][0] = c < nchunk ? row[2 * c] : make_uint4(0u, 0u, 0u, 0u);
+        v[j][1] = c < nchunk ? row[2 * c + 1] : make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int j = 0; j < CH; ++j) amax = fmaxf(amax, fmaxf(absmax8(v[j][0]), absmax8(v[j][1])));
+    amax = block_max<4>(amax, red);
+    const float s = amax / 127.0f;
+    if (lane == 0) a_scale[m] = s;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+        const int c = lane + j * 256;
+        const uint2 lo = quantize8(v[j][0], s), hi = quantize8(v[j][1], s);  // the canonical 16 codes, in k order
+        store_prepared(m, c, make_uint4(lo.x, lo.y, hi.x, hi.y), steps, xp, c0, c < nchunk);
+    }
+}
+
+typedef float v4f_t __attribute__((ext_vector_type(4)));
+
+// One output tile.  WIDE: 32-bit multiplies in the integer scale step (some scale does not fit 24 signed bits).
+template <bool INT_SCALE, bool WIDE>
+__device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restrict__ xp, const int32_t* __restrict__ c0,
+                                        unsigned char* smem) {
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wn = __builtin_amdgcn_readfirstlane(tid / kWave);  // the wave's 64 weight rows of the tile's 256
+    const int li = lane & 15, kb = lane >> 4;
+
+    // ---- which tile: XCD x (workgroups x, x + 8, ...) gets one contiguous range of linear tile numbers, and a range
+    // walks the output in blocks of kGroupRows tile rows, column by column (shared operand tiles meet in that XCD's L2)
+    const int tiles_n = (a.N + kTN - 1) / kTN;
+    const int tiles_m = (a.M + kTM - 1) / kTM;
+    int tile_m, tile_n;
+    {
+        const int total = tiles_m * tiles_n;
+        const int q = total / kXcdCount, rem = total - q * kXcdCount;
+        const int xcd = blockIdx.x % kXcdCount, idx = blockIdx.x / kXcdCount;
+        const int lid = xcd * q + min(xcd, rem) + idx;
+        const int gsz = kGroupRows * tiles_n;
+        const int g = lid / gsz, r = lid - g * gsz;
+        const int gm = min(kGroupRows, tiles_m - g * kGroupRows);
+        tile_n = r / gm;
+        tile_m = g * kGroupRows + (r - tile_n * gm);
+    }
+    const int m0 = tile_m * kTM, n0 = tile_n * kTN;
+    const int steps = a.K >> 7;
+    const int NG = a.K / a.group;
+    const int spg = a.group >> 7;
+    const int m16 = (a.M + 15) >> 4, n16 = (a.N + 15) >> 4;
+
+    // ---- loader roles.  Per step and wave: the 2 KB blocks of two 16-row token tiles (4 loads of 1 KB), the 1 KB
+    // blocks of four 16-row weight tiles; wave 0 also the step's 256 scales, wave 1 its 128 corrections.  Tiles past
+    // the end of a tensor lie outside its descriptor and read as zero.
+    const v4i xdesc = make_desc(xp, (size_t)m16 * steps * 2048);
+    const v4i wdesc = make_desc(a.wpack, (size_t)n16 * steps * kPkBlockBytes);
+    v4i adesc = make_desc(nullptr, 0);
+    int aux_voff = (int)0x80000000u, aux_step = 0, aux_group = 0;
+    if (wn == 0) {
+        adesc = make_desc(a.spack + kPkHeaderBytes, (size_t)n16 * NG * 64);
+        const int nt = (n0 >> 4) + (lane >> 2);
+        aux_voff = nt < n16 ? nt * NG * 64 + (lane & 3) * 16 : (int)0x80000000u;
+        aux_group = 64;
+    } else if (wn == 1) {
+        adesc = make_desc(c0, (size_t)m16 * steps * 64);
+        const int mt = (m0 >> 4) + (lane >> 2);
+        aux_voff = (lane < 32 && mt < m16) ? mt * steps * 64 + (lane & 3) * 16 : (int)0x80000000u;
+        aux_step = 64;
+    }
+    int x_voff[4], w_voff[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int mt = (m0 >> 4) + 2 * wn + (i >> 1);
+        x_voff[i] = mt < m16 ? mt * steps * 2048 + (i & 1) * 1024 + lane * 16 : (int)0x80000000u;
+        const int nt = (n0 >> 4) + 4 * wn + i;
+        w_voff[i] = nt < n16 ? nt * steps * kPkBlockBytes + lane * 16 : (int)0x80000000u;
+    }
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+    const unsigned lds_x = wn * 4096, lds_w = kABytes + wn * 4096;
+    const unsigned lds_aux = kABytes + kBBytes + (wn == 1 ? kScBytes : 0);
+    int rq_x = 0, rq_w = 0, rq_aux = 0, rq_sub = 0;
+    auto request_step = [&](int t) {
+        const unsigned base = lds0 + (t & 1) * kStage;
+        if (t < steps) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) load_to_lds_b128(xdesc, base, lds_x + i * 1024, x_voff[i], rq_x);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) load_to_lds_b128(wdesc, base, lds_w + i * 1024, w_voff[i], rq_w);
+            if (wn < 2) load_to_lds_b128(adesc, base, lds_aux, aux_voff, rq_aux);
+        }
+        rq_x += 2048;
+        rq_w += kPkBlockBytes;
+        const bool group_done = ++rq_sub == spg;
+        rq_sub = group_done ? 0 : rq_sub;
+        rq_aux += aux_step + (group_done ? aux_group : 0);
+    };
+
+    // ---- consumer roles: lane (li, kb) of MFMA 16x16x64 feeds row / column li and k chunk kb; its 4 results are
+    // weight row li, token rows 4 kb .. + 3 of the sub-tile
+    const int lane16 = lane * 16;
+    const int b_off = kABytes + wn * 4096 + lane16;
+    const int sc_off = kABytes + kBBytes + (wn * 64 + li) * 4;
+    const int ci_off = kABytes + kBBytes + kScBytes + kb * 16;
+
+    using acc4 = typename std::conditional<INT_SCALE, v4i, v4f_t>::type;
+    acc4 acc[kMS][kNS];
+#pragma unroll
+    for (int i = 0; i < kMS; ++i)
+#pragma unroll
+        for (int j = 0; j < kNS; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0;
+
+    auto scale_into = [&](acc4& dst, const v4i& part, int sc_i) {
+        const float s_f = __int_as_float(sc_i);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if constexpr (!INT_SCALE) dst[r] = fmaf((float)part[r], s_f, dst[r]);  // C' += float(C_g) * s_g
+            else if constexpr (WIDE) {
+                int prod = part[r] * sc_i;
+                asm volatile("" : "+v"(prod));  // else a 64-bit multiply-add with register pairs
+                dst[r] += prod;
+            } else dst[r] += __mul24(part[r], sc_i);  // C'' += C_g * s_g^INT
+        }
+    };
+
+    request_step(0);
+    for (int s = 0; s < steps; ++s) {
+        // this wave's requests for step s have landed; past the barrier so have everybody's, and everybody has
+        // finished reading the other stage, which the requests for step s + 1 now overwrite
+        asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+        request_step(s + 1);
+        const unsigned char* st = smem + (s & 1) * kStage;
+
+        // the wave's four weight sub-tiles of this step: unpack once, use for all eight token sub-tiles
+        v4i bu[kNS][2];
+        int scl[kNS];
+#pragma unroll
+        for (int j = 0; j < kNS; ++j) {
+            const v4i raw = *reinterpret_cast<const v4i*>(st + b_off + j * 1024);
+            scl[j] = *reinterpret_cast<const int*>(st + sc_off + j * 64);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t pw = (uint32_t)raw[q];
+                bu[j][0][q] = (int)((pw ^ 0x08080808u) & 0x0F0F0F0Fu);         // k 0..63 of the step: low nibbles
+                bu[j][1][q] = (int)(((pw >> 4) ^ 0x08080808u) & 0x0F0F0F0Fu);  // k 64..127: high nibbles
+            }
+        }
+        v4i part[2][kNS];
+        v4i af[2][2], ci[2];
+        af[0][0] = *reinterpret_cast<const v4i*>(st + lane16);
+        af[0][1] = *reinterpret_cast<const v4i*>(st + 1024 + lane16);
+        ci[0] = *reinterpret_cast<const v4i*>(st + ci_off);
+#pragma unroll
+        for (int i = 0; i < kMS; ++i) {
+            const int cur = i & 1, nxt = cur ^ 1;
+            if (i + 1 < kMS) {  // operands of the next token sub-tile, read while this one is multiplied
+                af[nxt][0] = *reinterpret_cast<const v4i*>(st + (i + 1) * 2048 + lane16);
+                af[nxt][1] = *reinterpret_cast<const v4i*>(st + (i + 1) * 2048 + 1024 + lane16);
+                ci[nxt] = *reinterpret_cast<const v4i*>(st + ci_off + (i + 1) * 64);
+            }
+#pragma unroll
+            for (int j = 0; j < kNS; ++j)
+                part[cur][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[cur][0], bu[j][0], ci[cur], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < kNS; ++j)
+                part[cur][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[cur][1], bu[j][1], part[cur][j], 0, 0, 0);
+            // the scale step of the sub-tile before, under this one's MFMAs
+            if (i > 0) {
+#pragma unroll
+                for (int j = 0; j < kNS; ++j) scale_into(acc[i - 1][j], part[nxt][j], scl[j]);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kNS; ++j) scale_into(acc[kMS - 1][j], part[(kMS - 1) & 1][j], scl[j]);
+    }
+
+    // ---- epilogue, once per output: FLOAT(acc) * s_a[m] * c[n] / alpha (Eq. (2)), or facc * s_a[m] (Eq. (1))
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");  // nobody reads operand tiles any more
+    const float inv_alpha = __int_as_float((127 - a.alpha_log2) << 23);
+    const int m_rows = min(kTM, a.M - m0), n_rows = min(kTN, a.N - n0);
+    // Rows of 8-aligned length go through an fp16 copy of the tile in LDS and leave as 16-byte stores; otherwise (and
+    // for the diagnostic accumulator output) element by element.
+    const bool staged = (a.N & 7) == 0 && a.acc_out == nullptr;
+    constexpr int kPitch = 264;  // halves per LDS row: 256 + 8, so that rows keep 16-byte alignment
+    __half* otile = reinterpret_cast<__half*>(smem);
+    float sa[kMS][4];
+#pragma unroll
+    for (int i = 0; i < kMS; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int ml = i * 16 + 4 * kb + r;
+            sa[i][r] = ml < m_rows ? a.a_scale[m0 + ml] : 0.0f;
+        }
+#pragma unroll
+    for (int j = 0; j < kNS; ++j) {
+        const int nl = wn * 64 + j * 16 + li;
+        const int n = n0 + nl;
+        float c = 1.0f;
+        if constexpr (INT_SCALE) {
+            if (a.chan_scale && nl < n_rows) c = a.chan_scale[n];
+            c *= inv_alpha;
+        }
+#pragma unroll
+        for (int i = 0; i < kMS; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int ml = i * 16 + 4 * kb + r;
+                __half h;
+                if constexpr (INT_SCALE) h = __float2half_rn((float)acc[i][j][r] * sa[i][r] * c);
+                else h = __float2half_rn(acc[i][j][r] * sa[i][r]);
+                if (staged) {
+                    otile[ml * kPitch + nl] = h;
+                } else if (ml < m_rows && nl < n_rows) {
+                    const size_t o = (size_t)(m0 + ml) * a.N + n;
+                    if constexpr (INT_SCALE) {
+                        if (a.acc_out) a.acc_out[o] = acc[i][j][r];
+                    }
+                    a.out[o] = h;
+                }
+            }
+    }
+    if (staged) {
+        __syncthreads();
+        const int chunk = tid & 31;  // 8 outputs
+        if (chunk * 8 < n_rows) {
+#pragma unroll
+            for (int pass = 0; pass < kTM / 8; ++pass) {
+                const int ml = pass * 8 + (tid >> 5);
+                if (ml < m_rows)
+                    *reinterpret_cast<uint4*>(a.out + (size_t)(m0 + ml) * a.N + n0 + chunk * 8) =
+                        *reinterpret_cast<const uint4*>(otile + ml * kPitch + chunk * 8);
+            }
+        }
+    }
+}
+
+// (two waves per SIMD, from two workgroups: this also keeps the MFMA results in ordinary vector registers, where the
+// scale step reads them; with a whole SIMD to itself the compiler would put them into accumulation registers and copy)
+template <bool INT_SCALE>
+__global__ __launch_bounds__(kTThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_tile_pk_kernel(PkArgs a, const int8_t* __restrict__ xp,
+                                                                 const int32_t* __restrict__ c0) {
+    extern __shared__ __align__(16) unsigned char smem_tpk[];
+    if constexpr (INT_SCALE) {
+        const int flags = *reinterpret_cast<const int32_t*>(a.spack);
+        if (flags & kPkFlagWide) tile_pk<true, true>(a, xp, c0, smem_tpk);
+        else tile_pk<true, false>(a, xp, c0, smem_tpk);
+    } else {
+        tile_pk<false, false>(a, xp, c0, smem_tpk);
+    }
+}
+
+size_t xp_bytes(int M, int K) { return pad256((size_t)((M + 15) / 16) * 16 * K); }
+size_t c0_bytes(int M, int K) { return pad256((size_t)((M + 15) / 16) * (K / 128) * 64); }
+
+}  // namespace
+
+// workspace = [prepared activations: ceil(M/16) x K/128 blocks of 2 KB | corrections: ceil(M/16) x K/128 x 16 words]
+size_t gemm_tile_pk_workspace_bytes(int M, int K) { return xp_bytes(M, K) + c0_bytes(M, K); }
+
+// rows the fused quantiser + preparation holds in registers: 8 chunks of 16 values per lane, 256 lanes
+bool gemm_tile_pk_takes_fp16(int K) { return (K & 15) == 0 && (K >> 4) <= 8 * 256; }
+
+hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace, hipStream_t stream) {
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    int8_t* xp = reinterpret_cast<int8_t*>(ws);
+    int32_t* c0 = reinterpret_cast<int32_t*>(ws + xp_bytes(a.M, a.K));
+    if (a.x_fp16) {  // fp16 activations: quantised on the way, the token scales go to a.a_scale_out (= a.a_scale)
+        const int nchunk = a.K >> 4;
+#define QP_PK(CH)                                                                                                    \
+    hipLaunchKernelGGL(quantize_prepare_activations_pk_kernel<CH>, dim3(a.M), dim3(256), 0, stream, a.x_fp16, a.M, a.K, \
+                       xp, c0, a.a_scale_out)
+        if (nchunk <= 256) QP_PK(1);
+        else if (nchunk <= 2 * 256) QP_PK(2);
+        else if (nchunk <= 4 * 256) QP_PK(4);
+        else QP_PK(8);
+#undef QP_PK
+    } else {
+        hipLaunchKernelGGL(prepare_activations_pk_kernel, dim3(a.M), dim3(256), 0, stream, a.xq, a.M, a.K, xp, c0);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t smem = 2 * (size_t)kStage;
+    const int tiles = ((a.N + kTN - 1) / kTN) * ((a.M + kTM - 1) / kTM);
+    int device = -1;
+    (void)hipGetDevice(&device);
+    static bool raised[2][64] = {};
+    auto raise = [&](const void* kern, int which) -> hipError_t {
+        if (device >= 0 && device < 64 && raised[which][device]) return hipSuccess;
+        hipError_t r = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (r == hipSuccess && device >= 0 && device < 64) raised[which][device] = true;
+        return r;
+    };
+    if (int_scale) {
+        e = raise(reinterpret_cast<const void*>(gemm_tile_pk_kernel<true>), 0);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(gemm_tile_pk_kernel<true>, dim3(tiles), dim3(kTThreads), smem, stream, a, xp, c0);
+    } else {
+        e = raise(reinterpret_cast<const void*>(gemm_tile_pk_kernel<false>), 1);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(gemm_tile_pk_kernel<false>, dim3(tiles), dim3(kTThreads), smem, stream, a, xp, c0);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace intscale

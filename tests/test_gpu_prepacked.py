@@ -208,6 +208,68 @@ def test_prepacked_linear_token_scale_and_zero_token(P):
     assert not host(acc).any() and not host(out).any()
 
 
+# more than 64 token rows: the tiled kernel on the prepacked layout (ragged row and column tiles, one and many K steps,
+# N not a multiple of 8: element-wise epilogue; several tiles per XCD)
+TILE_PK_SHAPES = [(65, 256, 128), (129, 300, 1024), (256, 512, 2048), (300, 700, 1152), (513, 257, 512), (128, 256, 4096),
+                  (1000, 1040, 256), (70, 16, 384)]
+
+
+@pytest.mark.parametrize("M,N,K", TILE_PK_SHAPES)
+def test_prepacked_tiled_gemm(P, M, N, K):
+    rng = np.random.default_rng(3500 + M + N + K)
+    xq, qw, IS, s, sa, c = rand_quantised(rng, M, N, K)
+    xq[0], xq[1] = -128, 127                 # extreme codes on both sides
+    q = O.unpack_int4(qw)
+    q[0], q[1] = -8, 7
+    qw = O.pack_int4(q)
+    ref = O.gemm_w4a8_intscale(xq, sa, qw, IS, c, G, 10)
+    pk = P.is_prepack_w4(dev(qw), dev(IS), G)
+    out, acc = P.is_gemm_w4a8_intscale_prepacked(dev(xq), dev(sa), pk, dev(c), 10, want_acc=True)
+    assert np.array_equal(host(acc), ref.acc), "int32 accumulators differ"
+    check_out(host(out), ref.out, f"M{M} N{N} K{K}")
+    out1, _ = P.is_gemm_w4a8_intscale_prepacked(dev(xq), dev(sa), pk, dev(c), 10)   # the staged epilogue
+    check_out(host(out1), ref.out, f"M{M} N{N} K{K} (no accumulator export)")
+    fs = O.gemm_w4a8_floatscale(xq, sa, qw, s, G)
+    out_fs = P.is_gemm_w4a8_floatscale_prepacked(dev(xq), dev(sa), P.is_prepack_w4(dev(qw), dev(s), G))
+    check_fs(host(out_fs), fs, f"M{M} N{N} K{K}")
+
+
+@pytest.mark.parametrize("M,N,K,group", [(200, 300, 1024, 128), (129, 520, 2048, 256), (130, 80, 1536, 1536)])
+def test_prepacked_tiled_wide_scales_and_groups(P, M, N, K, group):
+    """Scales beyond 24 bits (the 32-bit multiply instance, bit-exact modulo 2^32), groups of several K steps."""
+    rng = np.random.default_rng(77 + M)
+    xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+    q = rng.integers(-8, 8, size=(N, K)).astype(np.int8)
+    sa = rng.random(M).astype(np.float32)
+    qw = O.pack_int4(q)
+    for IS in (rng.integers(-2 ** 31, 2 ** 31, size=(N, K // group), dtype=np.int64).astype(np.int32),
+               np.where(rng.random((N, K // group)) < 0.05, 2 ** 24, 5).astype(np.int32),
+               rng.integers(0, 1025, size=(N, K // group)).astype(np.int32)):
+        ref = O.gemm_w4a8_intscale(xq, sa, qw, IS, None, group, 10)
+        out, acc = P.is_gemm_w4a8_intscale_prepacked(dev(xq), dev(sa), P.is_prepack_w4(dev(qw), dev(IS), group), None, 10,
+                                                     want_acc=True)
+        assert np.array_equal(host(acc), ref.acc)
+        check_out(host(out), ref.out)
+
+
+@pytest.mark.parametrize("M,N,K", [(130, 512, 4096), (70, 272, 8192), (200, 256, 14336), (66, 128, 28672), (257, 40, 2048),
+                                   (70, 48, 40960)])
+def test_prepacked_tiled_linear_fp16(P, M, N, K):
+    """More than 64 fp16 tokens: the tiled kernel's preparation quantises on the way (1, 2, 4, 8 chunks per lane), and
+    rows too long for that (quantiser kernel first)."""
+    rng = np.random.default_rng(7600 + M + N + K)
+    _, qw, IS, s, _, c = rand_quantised(rng, 1, N, K)
+    x = S.activations_student_t(M, K, 78 + K % 13)
+    xq_ref, sa_ref = O.quantize_act_int8_token(x)
+    ref = O.gemm_w4a8_intscale(xq_ref, sa_ref, qw, IS, c, G, 10)
+    out, acc = P.is_linear_w4a8_intscale_prepacked(dev(x), P.is_prepack_w4(dev(qw), dev(IS), G), dev(c), 10,
+                                                   want_acc=True)
+    assert np.array_equal(host(acc), ref.acc), "int32 accumulators differ"
+    check_out(host(out), ref.out, f"M{M} N{N} K{K}")
+    fs = O.gemm_w4a8_floatscale(xq_ref, sa_ref, qw, s, G)
+    check_fs(host(P.is_linear_w4a8_floatscale_prepacked(dev(x), P.is_prepack_w4(dev(qw), dev(s), G))), fs)
+
+
 def test_prepacked_empty_and_unsupported(P):
     rng = np.random.default_rng(3)
     xq, qw, IS, s, sa, c = rand_quantised(rng, 1, 16, 128)
