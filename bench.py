@@ -1,22 +1,27 @@
 #!/usr/bin/env python3
 """Benchmark of the fine-grained W4A8 integer-scale linear layer on one MI355X.
 
-Workload (N=1): the LLaMA-2-7B-shaped decode linears (qkv 4096->12288, o_proj 4096->4096, gate_up 4096->22016,
-down 11008->4096; group-128 int4 weights, int8 per-token activations, alpha = 2^10) at batch M in {1, 16, 64}.
-One step is one pass of the whole hot path over that workload: for every batch size and every one of `--layers`
-layers (32, each with its own weight buffers, so every GEMM streams cold weights from HBM as in a real decode
-step), the per-token activation quantiser followed by the integer-scale GEMM (for one token, M = 1, both behind the library's one-kernel linear call, whose
-decode kernel quantises the token itself).  Inputs are synthetic (seeded) and
-resident in HBM before the timed region.  Launches of one (batch, linear) pair are recorded into a HIP graph and
-replayed back to back; HIP events between the graph launches give each kernel's average duration inside the timed
-region.
+Default workload (N=1): the LLaMA-2-70B-shaped linears (qkv 8192->10240, o_proj 8192->8192, gate 8192->28672,
+down 28672->8192; group-128 int4 weights in the kernel layout written offline by is_prepack_w4, int8 per-token
+activations, alpha = 2^10) in decode (M = 1 and M = 32 token rows) and in prefill (M = 2048).  One step is one pass of the
+whole hot path over that workload: for every M, every linear and every one of `--layers` layers (each with its own
+weight buffers, so every decode GEMM streams cold weights from HBM as in a real decode step), the linear call on fp16
+activations: the per-token activation quantiser and the integer-scale GEMM of Eq. (2) with its float epilogue (one
+kernel for M = 1, quantiser + weight-streaming kernel for M = 32, quantising preparation pass + MFMA-bound tiled kernel
+for M = 2048).  Inputs are synthetic (seeded) and resident in HBM before the timed region.  The launches of one
+(M, linear) pair are recorded into a HIP graph and replayed; HIP events between the replays give each pair's average
+duration inside the timed region.
 
-Prints ONE JSON line.  `value` is the whole step's algorithmic bytes per second (the regime is HBM-bound); TOPS,
-per-shape figures and the integer-scale vs float-scale speedup ride along in the same line.
+Prints ONE JSON line.  `value` is the whole step's int8 tera-operations per second (the step's time is dominated by the
+MFMA-bound prefill GEMMs, whose kernel is the `roofline` entry; the HBM-bound decode kernel has its own entry,
+`roofline_hbm`).  Per shape the line carries the time of the step's call, of the integer-scale and of the float-scale
+GEMM call alone (Eq. (1), built the same way) with their ratio, the time a plain streaming read of the same bytes
+takes, and the roofline fractions; `alpha_sweep` shows the accuracy / overflow trade-off of the amplifier on one layer.
 
-`--workload prefill` measures the other regime instead: the LLaMA-3-8B-shaped prefill linears (qkv 4096->6144,
-gate_up 4096->28672, down 14336->4096) at M = 4096 heavy-tailed token rows; there `value` is int8 tera-operations
-per second and the roofline is the dense int8 MFMA peak.
+`--workload llama2_7b` (M in {1, 16, 64}) and `--workload llama3_8b` (M = 4096, Student-t activations) run the same
+code on those shapes; `decode_canonical`, `prefill_canonical`, `moe`, `w8a8` and `producers` measure the calls that
+take the canonical layouts (per-call layout, no offline pass), the mixture-of-experts form, fine-grained W8A8 and the
+fused activation producers.
 """
 from __future__ import annotations
 
@@ -42,7 +47,8 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--layers", type=int, default=32, help="distinct weight copies per linear (LLaMA-2-7B has 32 layers)")
+    ap.add_argument("--layers", type=int, default=None,
+                    help="distinct weight copies per linear (default: 8 for llama2_70b, 32 for llama2_7b, 4 for llama3_8b)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-floatscale", action="store_true", help="skip the float-scale comparison pass")
     ap.add_argument("--coarse", action="store_true",
@@ -51,7 +57,12 @@ def parse_args():
                     help="M = 1: quantiser kernel + GEMM kernel instead of the one-kernel linear call")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--cpu-sample-layers", type=int, default=32)
-    ap.add_argument("--workload", choices=("decode", "prefill", "moe", "w8a8", "producers"), default="decode")
+    ap.add_argument("--no-traffic", action="store_true",
+                    help="do not look up the measured HBM traffic in profiles/ (roofline.traffic = null); without this "
+                         "flag a missing figure is an error")
+    ap.add_argument("--workload", default="llama2_70b",
+                    choices=("llama2_70b", "llama2_7b", "llama3_8b", "decode_canonical", "prefill_canonical", "moe",
+                             "w8a8", "producers"))
     return ap.parse_args()
 
 
@@ -84,18 +95,25 @@ def measured_peaks(P, torch):
                     "v_mfma_i32_16x16x64_i8, two waves per SIMD")
 
 
+TRAFFIC_REQUIRED = True   # --no-traffic clears it
+
+
 def measured_traffic(kernel, workload):
     """HBM bytes per launch of `kernel` as measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE, scaled by what
-    the same counters read for a copy of known size); the figures sit in the profile summary of this workload as lines
-    `TRAFFIC <kernel name> <bytes per launch>`.  None when no such line exists."""
-    path = os.path.join(ROOT, "profiles", f"bench_{workload}_pmc_traffic.txt")
-    if not os.path.exists(path):
+    the same counters read for kernels of known size); the figures sit in the profile summary of this workload as lines
+    `TRAFFIC <kernel name> <bytes per launch>`.  A missing file or line ends the run with an error (the figure would
+    silently read null otherwise), unless --no-traffic says that none is wanted."""
+    if not TRAFFIC_REQUIRED:
         return None
-    for ln in open(path):
-        parts = ln.rstrip("\n").split("\t")
-        if len(parts) == 3 and parts[0] == "TRAFFIC" and parts[1] == kernel:
-            return float(parts[2])
-    return None
+    path = os.path.join(ROOT, "profiles", f"bench_{workload}_pmc_traffic.txt")
+    if os.path.exists(path):
+        for ln in open(path):
+            parts = ln.rstrip("\n").split("\t")
+            if len(parts) == 3 and parts[0] == "TRAFFIC" and parts[1] == kernel:
+                return float(parts[2])
+    print(f"bench.py: no measured HBM traffic for kernel '{kernel}' in {path}: collect it (see the commands in "
+          f"profiles/) or pass --no-traffic", file=sys.stderr)
+    sys.exit(3)
 
 
 class Segment:
@@ -124,12 +142,18 @@ class Segment:
 
 
 def main():
+    global TRAFFIC_REQUIRED
     args = parse_args()
+    TRAFFIC_REQUIRED = not args.no_traffic
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (one process, one MI355X); run with --gpus 1. "
               "Multi-GPU sharding is a design note, not a measured path.", file=sys.stderr)
         sys.exit(2)
-    if args.workload == "prefill":
+    if args.workload in FAMILIES:
+        return family_main(args)
+    if args.layers is None:
+        args.layers = 32
+    if args.workload == "prefill_canonical":
         return prefill_main(args)
     if args.workload == "w8a8":
         return w8a8_main(args)
@@ -403,6 +427,331 @@ def main():
         "overflow": overflow,
         "hot_cache_us_by_shape": hot_detail,
         "roofline": roofline,
+        "measured_peaks": peaks,
+        "cpu_baseline": cpu,
+        "shapes": shapes,
+    }
+    print(json.dumps(line))
+
+
+FAMILIES = {
+    # workload -> configuration index of the input recipe, linears (name -> (K, N)), token-row counts, default layers
+    "llama2_70b": dict(config=2, label="llama2-70b", skip=("up",), batches=(1, 32, 2048), layers=8),
+    "llama2_7b": dict(config=1, label="llama2-7b", skip=(), batches=(1, 16, 64), layers=32),
+    "llama3_8b": dict(config=3, label="llama3-8b", skip=(), batches=(4096,), layers=4),
+}
+
+
+def family_main(args):
+    """The linear layers of one model family on the prepacked route: every (M, linear) pair is one segment of the step."""
+    import numpy as np
+    import torch
+
+    import paper_2405_14597_amd as P
+    import synth_inputs as S
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    P.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    fam = FAMILIES[args.workload]
+    cfg = fam["config"]
+    table = {"llama2_70b": S.LLAMA2_70B, "llama2_7b": S.LLAMA2_7B, "llama3_8b": S.LLAMA3_8B}[args.workload]
+    linears = [(n, kn) for n, kn in table.items() if n not in fam["skip"]]
+    batches = fam["batches"]
+    L = args.layers or fam["layers"]
+    use_graph = not args.no_graph
+
+    # ---------------------------------------------------------------- data: one layer drawn on the host, quantised and
+    # prepacked on the GPU by the library (the offline step), then copied into L distinct buffers (timing does not
+    # depend on the values); both scale forms, for the float-scale twin
+    weights = {}
+    for idx, (name, (K, N)) in enumerate(linears):
+        w = torch.from_numpy(S.make_weights(cfg, N, K, S.seed_for(cfg, idx, 1))).to(dev)
+        qw = P.is_quantize_weights_int4_group(w, GROUP, ALPHA_LOG2, P.IS_SCALE_NORM)
+        del w
+        pi = P.is_prepack_w4(qw.qweight, qw.scale_i32, GROUP)
+        pf = P.is_prepack_w4(qw.qweight, qw.scale_f32, GROUP)
+        torch.cuda.synchronize()
+        weights[name] = dict(
+            canon=qw,
+            pi=[pi] + [P.PackedWeights(pi.wpack.clone(), pi.spack.clone(), *pi[2:]) for _ in range(L - 1)],
+            pf=[pf] + [P.PackedWeights(pf.wpack.clone(), pf.spack.clone(), *pf[2:]) for _ in range(L - 1)],
+            c=[qw.chan_scale] + [qw.chan_scale.clone() for _ in range(L - 1)])
+    acts = {}
+    for M in batches:
+        for idx, (name, (K, N)) in enumerate(linears):
+            x = torch.from_numpy(S.make_activations(cfg, M, K, S.seed_for(cfg, idx, 2) + M)).to(dev)
+            xq, sa = P.is_quantize_act_int8_token(x)
+            acts[(M, name)] = dict(
+                x=x, xq=xq, sa=sa, out=torch.empty((M, N), dtype=torch.float16, device=dev),
+                # workspaces start zeroed: the K split's arrival counters live there and every call leaves them zero
+                lws=torch.zeros(max(1, P.is_linear_prepacked_workspace_bytes(M, N, K, GROUP)), dtype=torch.uint8, device=dev),
+                gws=torch.zeros(max(1, P.is_gemm_prepacked_workspace_bytes(M, N, K, GROUP)), dtype=torch.uint8, device=dev))
+    torch.cuda.synchronize()
+
+    def alg_bytes(M, N, K, fp16_in):
+        b = S.algorithmic_bytes(M, N, K, GROUP)
+        return b + M * K - 4 * M if fp16_in else b      # fp16 rows in instead of int8 codes and their scales
+
+    # ---------------------------------------------------------------- segments
+    def make_segments(kind):
+        """kind: 'linear' (the step: fp16 in), 'gemm_is' / 'gemm_fs' (the GEMM calls alone: int8 codes in)."""
+        segs = []
+        for M in batches:
+            for name, (K, N) in linears:
+                a, w = acts[(M, name)], weights[name]
+                if kind == "linear":
+                    def fn(a=a, w=w):
+                        for l in range(L):
+                            P.is_linear_w4a8_intscale_prepacked(a["x"], w["pi"][l], w["c"][l], ALPHA_LOG2, out=a["out"],
+                                                                workspace=a["lws"])
+                    kernels = P.is_describe_prepacked(M, N, K, GROUP, True, True)
+                elif kind == "gemm_is":
+                    def fn(a=a, w=w):
+                        for l in range(L):
+                            P.is_gemm_w4a8_intscale_prepacked(a["xq"], a["sa"], w["pi"][l], w["c"][l], ALPHA_LOG2,
+                                                              out=a["out"], workspace=a["gws"])
+                    kernels = P.is_describe_prepacked(M, N, K, GROUP, True, False)
+                else:
+                    def fn(a=a, w=w):
+                        for l in range(L):
+                            P.is_gemm_w4a8_floatscale_prepacked(a["xq"], a["sa"], w["pf"][l], out=a["out"],
+                                                                workspace=a["gws"])
+                    kernels = P.is_describe_prepacked(M, N, K, GROUP, False, False)
+                seg = Segment(f"{name}_M{M}", kernels[-1], L, L * alg_bytes(M, N, K, kind == "linear"),
+                              L * S.algorithmic_ops(M, N, K), fn, use_graph, torch)
+                seg.M, seg.K, seg.N, seg.kernels = M, K, N, kernels
+                segs.append(seg)
+        return segs
+
+    def run_steps(segs, n, timed):
+        for _ in range(n):
+            ev = torch.cuda.Event(enable_timing=True)
+            ev.record()
+            for s in segs:
+                s.run()
+                nxt = torch.cuda.Event(enable_timing=True)
+                nxt.record()
+                if timed:
+                    s.pending.append((ev, nxt))
+                ev = nxt
+
+    def timed_pass(segs, steps, warmup):
+        run_steps(segs, warmup, False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(segs, steps, True)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for s in segs:
+            s.elapsed_ms = sum(a.elapsed_time(b) for a, b in s.pending)
+            s.count = len(s.pending) * s.launches
+            s.pending = []
+        return (t1 - t0) / steps
+
+    def per_call_us(s):
+        return 1e3 * s.elapsed_ms / max(s.count, 1)
+
+    segs = make_segments("linear")
+    sec_per_step = timed_pass(segs, args.steps, args.warmup)
+    step_ops = sum(s.ops for s in segs)
+    step_bytes = sum(s.alg_bytes for s in segs)
+
+    # the GEMM calls alone, integer scale and its float-scale twin (one kernel per decode call, so the decode kernel's
+    # own duration comes out of this pass; the tiled call is its preparation kernel + the tile kernel)
+    n_cmp = max(3, args.steps // 2)
+    g_is = make_segments("gemm_is")
+    timed_pass(g_is, n_cmp, 2)
+    g_fs = None
+    if not args.no_floatscale:
+        g_fs = make_segments("gemm_fs")
+        timed_pass(g_fs, n_cmp, 2)
+
+    # a plain streaming read of the same number of bytes as each decode GEMM (cold: a different buffer every launch)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    probe_us = {}
+    pool = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    pool.fill_(1)
+    for s in g_is:
+        if s.M > 64:
+            continue
+        nb = (s.alg_bytes // s.launches) // 16 * 16
+        slots = max(1, min(8, pool.numel() // nb))
+        views = [pool[i * nb:(i + 1) * nb] for i in range(slots)]
+        reps = 4 * slots
+        for v in views:
+            P.is_probe_stream_read(v, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for r in range(reps):
+            P.is_probe_stream_read(views[r % slots], sink)
+        e1.record()
+        torch.cuda.synchronize()
+        probe_us[s.name] = 1e3 * e0.elapsed_time(e1) / reps
+    del pool
+
+    shapes = []
+    for i, s in enumerate(segs):
+        g = g_is[i]
+        call_us, gemm_us = per_call_us(s), per_call_us(g)
+        bytes_call = g.alg_bytes / g.launches
+        ops_call = g.ops / g.launches
+        row = dict(name=s.name, M=s.M, K=s.K, N=s.N, kernels=s.kernels, step_call_us=round(call_us, 3),
+                   gemm_us=round(gemm_us, 3))
+        if g_fs is not None:
+            fs_us = per_call_us(g_fs[i])
+            row["floatscale_gemm_us"] = round(fs_us, 3)
+            row["floatscale_over_intscale"] = round(fs_us / gemm_us, 4)
+        if s.M <= 64:
+            row["gbs"] = round(bytes_call / gemm_us / 1e3, 1)
+            row["hbm_frac"] = round(bytes_call / gemm_us / 1e3 / HBM_PEAK_GBS, 4)
+            row["stream_read_same_bytes_us"] = round(probe_us[s.name], 3)
+            row["gemm_over_stream_read"] = round(gemm_us / probe_us[s.name], 3)
+        else:
+            row["tops"] = round(ops_call / gemm_us / 1e6, 1)
+            row["mfma_frac"] = round(ops_call / gemm_us / 1e6 / MFMA_I8_PEAK_TOPS, 4)
+        shapes.append(row)
+
+    # ---------------------------------------------------------------- rooflines: per kernel instantiation, from the
+    # GEMM-only pass; the dominant one by time inside the step is `roofline`
+    by_kernel = {}
+    for s in g_is:
+        k = by_kernel.setdefault(s.kernel, dict(ms=0.0, launches=0, bytes=0.0, ops=0.0, tiled=s.M > 64))
+        k["ms"] += s.elapsed_ms
+        k["launches"] += s.count
+        k["bytes"] += s.alg_bytes * (s.count / s.launches)
+        k["ops"] += s.ops * (s.count / s.launches)
+    peaks = measured_peaks(P, torch)
+    profile = f"{args.workload}"
+
+    def roof(name, k):
+        us = 1e3 * k["ms"] / k["launches"]
+        if k["tiled"]:
+            ach = k["ops"] / k["launches"] / us / 1e6
+            return dict(bound="mfma", kernel=name, achieved=round(ach, 1), peak=MFMA_I8_PEAK_TOPS, unit="TOP/s",
+                        frac=round(ach / MFMA_I8_PEAK_TOPS, 4), traffic=measured_traffic(name, profile),
+                        avg_launch_us=round(us, 3), alg_ops_per_launch=round(k["ops"] / k["launches"]),
+                        frac_of_measured_peak=round(ach / peaks["mfma_i8_tops"], 4),
+                        note="duration = the GEMM call on int8 codes: this kernel plus its activation preparation "
+                             "kernel (a few per cent of the call; the committed kernel trace has both)")
+        ach = k["bytes"] / k["launches"] / us / 1e3
+        return dict(bound="hbm", kernel=name, achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(ach / HBM_PEAK_GBS, 4), traffic=measured_traffic(name, profile),
+                    avg_launch_us=round(us, 3), alg_bytes_per_launch=round(k["bytes"] / k["launches"]),
+                    frac_of_measured_peak=round(ach / peaks["hbm_read_gbs"], 4))
+
+    ranked = sorted(by_kernel.items(), key=lambda kv: -kv[1]["ms"])
+    roofline = roof(*ranked[0])
+    other = [kv for kv in ranked if kv[1]["tiled"] != ranked[0][1]["tiled"]]
+    roofline_other = roof(*other[0]) if other else None
+
+    speedup = None
+    if g_fs is not None:
+        speedup = dict(
+            all=round(sum(s.elapsed_ms for s in g_fs) / sum(s.elapsed_ms for s in g_is), 4),
+            decode=None if not any(s.M <= 64 for s in g_is) else round(
+                sum(s.elapsed_ms for s in g_fs if s.M <= 64) / sum(s.elapsed_ms for s in g_is if s.M <= 64), 4),
+            prefill=None if not any(s.M > 64 for s in g_is) else round(
+                sum(s.elapsed_ms for s in g_fs if s.M > 64) / sum(s.elapsed_ms for s in g_is if s.M > 64), 4))
+
+    # ---------------------------------------------------------------- amplifier sweep on one layer (Sec. 4.1, Fig. 4):
+    # integer-scale output against the float-scale output of the same quantised weights, and the worst-case bound
+    sweep = None
+    if not args.no_floatscale:
+        name, (K, N) = linears[-1]
+        M = min(batches[-1], 32) if batches[-1] > 64 else batches[-1]
+        idx = len(linears) - 1
+        w = torch.from_numpy(S.make_weights(cfg, N, K, S.seed_for(cfg, idx, 1))).to(dev)
+        a = acts[(M if (M, name) in acts else batches[0], name)]
+        sweep = []
+        for al in (6, 8, 10, 12):
+            qw = P.is_quantize_weights_int4_group(w, GROUP, al, P.IS_SCALE_NORM)
+            ref = P.is_gemm_w4a8_floatscale(a["xq"], a["sa"], qw.qweight, qw.scale_f32, GROUP).float()
+            # (scale_f32 is the whole float group scale; scale_i32 its amplified, rounded quotient by chan_scale)
+            got, _ = P.is_gemm_w4a8_intscale_prepacked(a["xq"], a["sa"], P.is_prepack_w4(qw.qweight, qw.scale_i32, GROUP),
+                                                       qw.chan_scale, al)
+            bound = int(P.is_intscale_overflow_bound(qw.scale_i32, GROUP).cpu()[0])
+            err = (got.float() - ref).abs()
+            sweep.append(dict(alpha_log2=al, mean_rel_err_vs_floatscale=float(err.mean() / ref.abs().mean()),
+                              max_abs_err_over_mean_abs=float(err.max() / ref.abs().mean()),
+                              worst_case_bound_log2=round(float(np.log2(max(1, bound))), 2)))
+        sweep = dict(linear=name, M=a["xq"].shape[0], rows=sweep,
+                     note="error of Eq. (2) against Eq. (1) on the same int4 weights; bound = max_n sum_g |IS| * G * 1024, "
+                          "int32 cannot overflow iff its log2 is below 31")
+        del w
+
+    # ---------------------------------------------------------------- CPU oracle on a bounded sample of the same step
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        cap = 2048         # token rows per call the oracle is timed on (its time is linear in M)
+        t_cpu, cpu_ops = 0.0, 0
+        ok_all, rel_all = True, 0.0
+        for idx, (name, (K, N)) in enumerate(linears):
+            hw = O.quantize_weights_int4_group(S.make_weights(cfg, N, K, S.seed_for(cfg, idx, 1)), GROUP, ALPHA_LOG2,
+                                               O.SCALE_NORM)
+            for M in batches:
+                hx = S.make_activations(cfg, M, K, S.seed_for(cfg, idx, 2) + M)[:cap]
+                t0 = time.perf_counter()
+                xq, sa = O.quantize_act_int8_token(hx)
+                ref = O.gemm_w4a8_intscale(xq, sa, hw.qweight, hw.scale_i32, hw.chan_scale, GROUP, ALPHA_LOG2)
+                t_cpu += time.perf_counter() - t0
+                cpu_ops += S.algorithmic_ops(hx.shape[0], N, K)
+                # the oracle's result doubles as a live parity check of the step's call (first layer's weights)
+                a, w = acts[(M, name)], weights[name]
+                out, acc = P.is_linear_w4a8_intscale_prepacked(a["x"], w["pi"][0], w["c"][0], ALPHA_LOG2, want_acc=True,
+                                                               workspace=a["lws"])
+                torch.cuda.synchronize()
+                rows = hx.shape[0]
+                ok_all = ok_all and bool(np.array_equal(acc[:rows].cpu().numpy(), ref.acc))
+                got = out[:rows].cpu().numpy().astype(np.float64)
+                rel_all = max(rel_all, float(np.max(np.abs(got - ref.out) / np.maximum(np.abs(ref.out), 1e-3))))
+                del out, acc, got, ref
+            del hw
+        cpu = dict(value=round(cpu_ops / t_cpu / 1e12, 5), unit="TOP/s", cores=O.num_threads(), kind="oracle",
+                   sample=f"one layer of the step: {len(linears)} linears x M in {list(batches)} (quantiser + integer-scale "
+                          f"GEMM), at most {cap} token rows per call, {t_cpu:.1f} s",
+                   parity=dict(acc_bit_exact=ok_all, max_rel_err=rel_all))
+
+    value = step_ops / sec_per_step / 1e12
+    decode_bytes = sum(s.alg_bytes for s in segs if s.M <= 64)
+    decode_ms = sum(s.elapsed_ms / (s.count / s.launches) for s in segs if s.M <= 64 and s.count)
+    prefill_ops = sum(s.ops for s in segs if s.M > 64)
+    prefill_ms = sum(s.elapsed_ms / (s.count / s.launches) for s in segs if s.M > 64 and s.count)
+    line = {
+        "metric": "W4A8 integer-scale GEMM TOPS + HBM GB/s (% roofline); speedup vs float-scale",
+        "value": round(value, 1),
+        "unit": "TOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(1e3 * sec_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": f"{fam['label']} linears ({', '.join(n for n, _ in linears)}), W4 group-{GROUP} x A8 "
+                               f"per-token, alpha=2^{ALPHA_LOG2}, M in {list(batches)} (fp16 activations in, fp16 out), "
+                               f"{L} layers of distinct weights per step",
+                   "layout": "prepacked offline (is_prepack_w4); the canonical-layout calls are --workload "
+                             "decode_canonical / prefill_canonical",
+                   "launch": "hip-graph" if use_graph else "eager", "scale_mode": "norm"},
+        "decode": None if not decode_ms else dict(
+            gbs=round(decode_bytes / decode_ms / 1e6, 1), hbm_frac=round(decode_bytes / decode_ms / 1e6 / HBM_PEAK_GBS, 4),
+            ms_per_step=round(decode_ms, 4), note="linear calls of the step with M <= 64, quantiser included"),
+        "prefill": None if not prefill_ms else dict(
+            tops=round(prefill_ops / prefill_ms / 1e9, 1),
+            mfma_frac=round(prefill_ops / prefill_ms / 1e9 / MFMA_I8_PEAK_TOPS, 4), ms_per_step=round(prefill_ms, 4),
+            note="linear calls of the step with M > 64, quantising preparation pass included"),
+        "speedup_vs_floatscale": speedup,
+        "roofline": roofline,
+        "roofline_hbm" if roofline["bound"] == "mfma" else "roofline_mfma": roofline_other,
+        "alpha_sweep": sweep,
         "measured_peaks": peaks,
         "cpu_baseline": cpu,
         "shapes": shapes,

@@ -164,12 +164,16 @@ int is_prepack_w4(const void* qweight, const int32_t* scale_i32, const float* sc
  * The GEMMs of Eq. (2) and Eq. (1) on prepacked weights: same arithmetic and results as is_gemm_w4a8_intscale /
  * is_gemm_w4a8_floatscale (accumulators bit for bit; the float-scale sums in a different but fixed order).
  *   qweight_packed, scales_packed   from is_prepack_w4 (integer scales for the first, float scales for the second)
- *   workspace   at least is_gemm_prepacked_workspace_bytes(M,N,K,group) bytes (0 for most decode shapes).  When it is
- *               not 0 the K dimension is split across workgroups and the first 64 KB of the workspace are arrival
- *               counters: they must be ZERO when a call starts and every call leaves them zero, so zero the workspace
- *               once after allocating it.  Calls sharing one workspace must not overlap.
- * Covered: 1 <= M <= 64 (the weight-streaming kernel).  IS_ERR_UNSUPPORTED beyond, and for N above
- * 16 * 256 * (compute units) rows.  M = 0 is a no-op.
+ *   workspace   at least is_gemm_prepacked_workspace_bytes(M,N,K,group) bytes.
+ *               M <= 64 (the weight-streaming kernel): 0 for most shapes; when it is not 0 the K dimension is split
+ *               across workgroups and the first 64 KB of the workspace are arrival counters: they must be ZERO when a
+ *               call starts and every call leaves them zero, so zero the workspace once after allocating it.
+ *               M > 64 (the MFMA-bound tiled kernel): the activations re-ordered into MFMA operand blocks
+ *               (ceil(M/16) * 16 * K bytes) and one zero-point correction per token row and K step; written by a
+ *               preparation kernel of the call, no requirement on the contents.
+ *               Calls sharing one workspace must not overlap.
+ * Covered: M >= 1, N up to 16 * 256 * (compute units) rows when M <= 64, ceil(M/16) * 16 * K below 2^31 beyond
+ * (IS_ERR_UNSUPPORTED otherwise).  M = 0 is a no-op.
  */
 size_t is_gemm_prepacked_workspace_bytes(int M, int N, int K, int group);
 int is_gemm_w4a8_intscale_prepacked(const int8_t* xq, const float* a_scale, const void* qweight_packed,
@@ -183,7 +187,8 @@ int is_gemm_w4a8_floatscale_prepacked(const int8_t* xq, const float* a_scale, co
 /*
  * The linear layer on fp16 activations and prepacked weights: Appendix A.1 per token, then Eq. (2) / Eq. (1), with the
  * results of is_quantize_act_int8_token followed by the prepacked GEMM, to the bit.  One token (M = 1, K <= 32768) is
- * quantised inside the GEMM kernel (one launch); otherwise the quantiser runs first.
+ * quantised inside the GEMM kernel (one launch); more than 64 tokens (K <= 32768) are quantised by the tiled kernel's
+ * preparation pass; otherwise the quantiser runs first.
  *   workspace   at least is_linear_prepacked_workspace_bytes(M,N,K,group) bytes: quantised activations [M,K], token
  *               scales [M] (each padded to 256 bytes), then the GEMM's workspace, whose zero-counter rule applies.
  */
@@ -195,6 +200,14 @@ int is_linear_w4a8_intscale_prepacked(const void* x_fp16, const void* qweight_pa
 int is_linear_w4a8_floatscale_prepacked(const void* x_fp16, const void* qweight_packed, const void* scales_packed, int M,
                                         int N, int K, int group, void* out_fp16, void* workspace,
                                         size_t workspace_bytes, void* stream);
+
+/*
+ * Which kernels the prepacked calls launch for a shape, as a kernel trace (rocprofv3 --kernel-trace) names them, in
+ * launch order and separated by '\n' (the stand-alone activation quantiser of the linear call for 2 <= M <= 64, when
+ * it runs, is not listed).  Host-only: nothing is launched.  int_scale: Eq. (2) or Eq. (1) form; fp16_in: the linear
+ * call rather than the GEMM call.  Writes a NUL-terminated string of at most names_len bytes.
+ */
+int is_describe_prepacked(int M, int N, int K, int group, int int_scale, int fp16_in, char* names, size_t names_len);
 
 /*
  * Mixture-of-experts form (Sec. 5.4 measures Mixtral 8x7B): one launch over `num_experts` weight sets.
@@ -276,6 +289,9 @@ int is_probe_mfma_i8(int iters, int* sink, double* ops_out, void* stream);
 const char* is_status_string(int status);
 /* Text of the last HIP error this thread's calls ran into (static storage; "" if none). */
 const char* is_last_hip_error(void);
+/* Digest (16 hex digits) of the sources this library was compiled from; the Python binding rebuilds when it differs
+ * from the digest of the sources beside it. */
+const char* is_source_hash(void);
 
 #ifdef __cplusplus
 }

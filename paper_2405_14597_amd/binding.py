@@ -51,6 +51,8 @@ EXPORTED_SYMBOLS = (
     "is_linear_prepacked_workspace_bytes",
     "is_linear_w4a8_intscale_prepacked",
     "is_linear_w4a8_floatscale_prepacked",
+    "is_describe_prepacked",
+    "is_source_hash",
     "is_probe_stream_read",
     "is_probe_mfma_i8",
     "is_status_string",
@@ -72,11 +74,12 @@ def library_path() -> str:
 
 
 def load_library() -> ctypes.CDLL:
-    """Load libintscale.so; build it first only if no built library is there."""
+    """Load libintscale.so; build it first if none is there, or if the one there was compiled from other sources than
+    the ones beside it (the library carries a digest of its sources)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB_PATH):
+    if _build.needs_build():
         _build.build_library(force=True)
     # The library and torch must share ONE HIP runtime (device pointers and streams cross between them), so torch's
     # runtime is loaded first and libintscale.so's libamdhip64 dependency resolves to it.
@@ -152,6 +155,10 @@ def load_library() -> ctypes.CDLL:
     lib.is_status_string.restype = ctypes.c_char_p
     lib.is_last_hip_error.argtypes = []
     lib.is_last_hip_error.restype = ctypes.c_char_p
+    lib.is_source_hash.argtypes = []
+    lib.is_source_hash.restype = ctypes.c_char_p
+    lib.is_describe_prepacked.argtypes = [ci, ci, ci, ci, ci, ci, ctypes.c_char_p, sz]
+    lib.is_describe_prepacked.restype = ci
     _lib = lib
     return lib
 
@@ -287,6 +294,13 @@ def _workspace(nbytes: int, device, workspace):
     return ws, nbytes
 
 
+def _release_workspace(ws, workspace, stream) -> None:
+    """A workspace this module allocated goes back to torch's allocator when the call returns, while the kernels may
+    still be queued: tell the allocator which stream uses it, so the block is not handed out on another stream early."""
+    if ws is not None and workspace is None and stream is not None and hasattr(stream, "cuda_stream"):
+        ws.record_stream(stream)
+
+
 def is_gemm_w4a8_intscale(xq, a_scale, qweight, scale_i32, chan_scale, group: int, alpha_log2: int, out=None,
                           acc_out=None, want_acc: bool = False, workspace=None, stream=None):
     """Returns (out fp16 [M,N], acc int32 [M,N] or None)."""
@@ -311,6 +325,7 @@ def is_gemm_w4a8_intscale(xq, a_scale, qweight, scale_i32, chan_scale, group: in
                                              group, alpha_log2, _p(out), _p(acc_out), _p(ws), ws_bytes,
                                              _stream_handle(stream))
     _check("is_gemm_w4a8_intscale", st)
+    _release_workspace(ws, workspace, stream)
     return out, acc_out
 
 
@@ -329,6 +344,7 @@ def is_gemm_w4a8_floatscale(xq, a_scale, qweight, scale_f32, group: int, out=Non
     st = load_library().is_gemm_w4a8_floatscale(_p(xq), _p(a_scale), _p(qweight), _p(scale_f32), M, N, K, group,
                                                _p(out), _p(ws), ws_bytes, _stream_handle(stream))
     _check("is_gemm_w4a8_floatscale", st)
+    _release_workspace(ws, workspace, stream)
     return out
 
 
@@ -359,6 +375,7 @@ def is_linear_w4a8_intscale(x, qweight, scale_i32, chan_scale, group: int, alpha
                                                alpha_log2, _p(out), _p(acc_out), _p(ws), ws_bytes,
                                                _stream_handle(stream))
     _check("is_linear_w4a8_intscale", st)
+    _release_workspace(ws, workspace, stream)
     return out, acc_out
 
 
@@ -376,6 +393,7 @@ def is_linear_w4a8_floatscale(x, qweight, scale_f32, group: int, out=None, works
     st = load_library().is_linear_w4a8_floatscale(_p(x), _p(qweight), _p(scale_f32), M, N, K, group, _p(out), _p(ws),
                                                  ws_bytes, _stream_handle(stream))
     _check("is_linear_w4a8_floatscale", st)
+    _release_workspace(ws, workspace, stream)
     return out
 
 
@@ -427,6 +445,7 @@ def is_gemm_w8a8_intscale(xq, a_scale, qweight8, scale_i32, chan_scale, group: i
                                              group, alpha_log2, _p(out), _p(acc_out), _p(ws), ws_bytes,
                                              _stream_handle(stream))
     _check("is_gemm_w8a8_intscale", st)
+    _release_workspace(ws, workspace, stream)
     return out, acc_out
 
 
@@ -445,6 +464,7 @@ def is_gemm_w8a8_floatscale(xq, a_scale, qweight8, scale_f32, group: int, out=No
     st = load_library().is_gemm_w8a8_floatscale(_p(xq), _p(a_scale), _p(qweight8), _p(scale_f32), M, N, K, group,
                                                _p(out), _p(ws), ws_bytes, _stream_handle(stream))
     _check("is_gemm_w8a8_floatscale", st)
+    _release_workspace(ws, workspace, stream)
     return out
 
 
@@ -471,6 +491,7 @@ def is_gemm_w4a8_intscale_safe(xq, a_scale, qweight, scale_i32, chan_scale, grou
                                                   N, K, group, alpha_log2, _p(out), _p(ws), ws_bytes,
                                                   _stream_handle(stream))
     _check("is_gemm_w4a8_intscale_safe", st)
+    _release_workspace(ws, workspace, stream)
     return out
 
 
@@ -510,6 +531,7 @@ def is_gemm_w4a8_intscale_grouped(xq, a_scale, qweight, scale_i32, chan_scale, r
                                                      _p(row_offsets), E, M, N, K, group, alpha_log2, _p(out),
                                                      _p(acc_out), _p(ws), ws_bytes, _stream_handle(stream))
     _check("is_gemm_w4a8_intscale_grouped", st)
+    _release_workspace(ws, workspace, stream)
     return out, acc_out
 
 
@@ -531,6 +553,7 @@ def is_gemm_w4a8_floatscale_grouped(xq, a_scale, qweight, scale_f32, row_offsets
                                                        _p(row_offsets), E, M, N, K, group, _p(out), _p(ws), ws_bytes,
                                                        _stream_handle(stream))
     _check("is_gemm_w4a8_floatscale_grouped", st)
+    _release_workspace(ws, workspace, stream)
     return out
 
 
@@ -591,6 +614,15 @@ def is_linear_prepacked_workspace_bytes(M: int, N: int, K: int, group: int) -> i
     return int(load_library().is_linear_prepacked_workspace_bytes(M, N, K, group))
 
 
+def is_describe_prepacked(M: int, N: int, K: int, group: int, int_scale: bool = True, fp16_in: bool = False):
+    """Names of the kernels the prepacked GEMM (or, fp16_in, linear) call launches for this shape, in launch order, as a
+    kernel trace shows them.  Host-only."""
+    buf = ctypes.create_string_buffer(512)
+    st = load_library().is_describe_prepacked(M, N, K, group, int(int_scale), int(fp16_in), buf, len(buf))
+    _check("is_describe_prepacked", st)
+    return buf.value.decode().split("\n")
+
+
 def _zero_workspace(nbytes: int, device, workspace):
     """The prepacked GEMMs want their arrival counters zero: a fresh workspace is zero-filled."""
     torch = _torch()
@@ -625,8 +657,7 @@ def is_gemm_w4a8_intscale_prepacked(xq, a_scale, packed: PackedWeights, chan_sca
                                                        _p(chan_scale), M, N, K, group, alpha_log2, _p(out), _p(acc_out),
                                                        _p(ws), ws_bytes, _stream_handle(stream))
     _check("is_gemm_w4a8_intscale_prepacked", st)
-    if ws is not None and workspace is None and stream is not None:
-        ws.record_stream(stream)
+    _release_workspace(ws, workspace, stream)
     return out, acc_out
 
 
@@ -645,8 +676,7 @@ def is_gemm_w4a8_floatscale_prepacked(xq, a_scale, packed: PackedWeights, out=No
     st = load_library().is_gemm_w4a8_floatscale_prepacked(_p(xq), _p(a_scale), _p(packed.wpack), _p(packed.spack), M, N,
                                                          K, group, _p(out), _p(ws), ws_bytes, _stream_handle(stream))
     _check("is_gemm_w4a8_floatscale_prepacked", st)
-    if ws is not None and workspace is None and stream is not None:
-        ws.record_stream(stream)
+    _release_workspace(ws, workspace, stream)
     return out
 
 
@@ -673,8 +703,7 @@ def is_linear_w4a8_intscale_prepacked(x, packed: PackedWeights, chan_scale, alph
                                                          K, group, alpha_log2, _p(out), _p(acc_out), _p(ws), ws_bytes,
                                                          _stream_handle(stream))
     _check("is_linear_w4a8_intscale_prepacked", st)
-    if ws is not None and workspace is None and stream is not None:
-        ws.record_stream(stream)
+    _release_workspace(ws, workspace, stream)
     return out, acc_out
 
 
@@ -692,6 +721,5 @@ def is_linear_w4a8_floatscale_prepacked(x, packed: PackedWeights, out=None, work
     st = load_library().is_linear_w4a8_floatscale_prepacked(_p(x), _p(packed.wpack), _p(packed.spack), M, N, K, group,
                                                            _p(out), _p(ws), ws_bytes, _stream_handle(stream))
     _check("is_linear_w4a8_floatscale_prepacked", st)
-    if ws is not None and workspace is None and stream is not None:
-        ws.record_stream(stream)
+    _release_workspace(ws, workspace, stream)
     return out

@@ -26,12 +26,30 @@ def sources():
     return [os.path.join(CSRC, s) for s in SOURCES]
 
 
-def needs_build() -> bool:
+def source_hash() -> str:
+    """Digest of every file the library is compiled from (and of the flags); the library carries the digest it was
+    built from (is_source_hash), so a stale build is recognised whatever the files' time stamps say."""
+    import hashlib
+    h = hashlib.sha256(" ".join(HIPCC_FLAGS).encode())
+    for path in sources() + [os.path.join(CSRC, x) for x in HEADERS] + [os.path.join(INCLUDE, "intscale.h")]:
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def built_hash():
+    """The digest the built library carries, None if there is no library (or it predates the digest)."""
     if not os.path.exists(LIB_PATH):
-        return True
-    t = os.path.getmtime(LIB_PATH)
-    deps = sources() + [os.path.join(CSRC, h) for h in HEADERS] + [os.path.join(INCLUDE, "intscale.h")]
-    return any(os.path.getmtime(d) > t for d in deps)
+        return None
+    import re
+    with open(LIB_PATH, "rb") as f:
+        m = re.search(rb"intscale-source-hash:([0-9a-f]{16})", f.read())
+    return m.group(1).decode() if m else None
+
+
+def needs_build() -> bool:
+    return built_hash() != source_hash()
 
 
 def build_library(force: bool = True, verbose: bool = False, extra_flags=()) -> str:
@@ -42,7 +60,7 @@ def build_library(force: bool = True, verbose: bool = False, extra_flags=()) -> 
     # one object per source, compiled side by side, then one link (the objects live in a scratch folder)
     import concurrent.futures
     import tempfile
-    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"] + [f'-DINTSCALE_SOURCE_HASH="{source_hash()}"']
     with tempfile.TemporaryDirectory(prefix="intscale_build_") as tmp:
         def compile_one(src):
             obj = os.path.join(tmp, os.path.basename(src) + ".o")

@@ -74,6 +74,14 @@ const char* is_status_string(int status) {
 
 const char* is_last_hip_error(void) { return g_hip_error; }
 
+#ifndef INTSCALE_SOURCE_HASH
+#define INTSCALE_SOURCE_HASH "0000000000000000"
+#endif
+const char* is_source_hash(void) {
+    static const char tagged[] = "intscale-source-hash:" INTSCALE_SOURCE_HASH;
+    return tagged + sizeof("intscale-source-hash:") - 1;
+}
+
 int is_probe_stream_read(const void* src, size_t bytes, int* sink, void* stream) {
     if (!ok_ptr(src) || sink == nullptr || (reinterpret_cast<uintptr_t>(sink) & 3u) || bytes == 0 || (bytes & 15))
         return IS_ERR_INVALID_ARG;
@@ -468,11 +476,29 @@ int is_linear_w4a8_floatscale_prepacked(const void* x_fp16, const void* qweight_
                             workspace, workspace_bytes, stream, false);
 }
 
+int is_describe_prepacked(int M, int N, int K, int group, int int_scale, int fp16_in, char* names, size_t names_len) {
+    if (names == nullptr || names_len == 0) return IS_ERR_INVALID_ARG;
+    names[0] = '\0';
+    if (M < 1) return IS_ERR_INVALID_ARG;
+    const int shape = check_pk_shape(N, K, group);
+    if (shape != IS_OK) return shape;
+    if (M > 64) {
+        gemm_tile_pk_kernel_names(K, int_scale != 0, fp16_in != 0 && gemm_tile_pk_takes_fp16(K), names, names_len);
+        return IS_OK;
+    }
+    PkPlan plan;
+    const bool fused = fp16_in != 0 && M == 1 && pk_decode_plan(1, N, K, group, true, &plan);
+    if (!fused && !pk_decode_plan(M, N, K, group, false, &plan)) return IS_ERR_UNSUPPORTED;
+    pk_decode_kernel_name(plan, int_scale != 0, fused, names, names_len);
+    return IS_OK;
+}
+
 // ---- fine-grained W8A8
 static int check_w8_shape(int M, int N, int K, int group) {
     if (M < 0 || N <= 0 || K <= 0 || group <= 0 || K % group != 0) return IS_ERR_INVALID_ARG;
     if (group % 128 != 0) return IS_ERR_UNSUPPORTED;
     if (M > (1 << 20) || K > (1 << 20) || (long long)N * (K / group) * 4 >= (1LL << 31)) return IS_ERR_UNSUPPORTED;
+    if ((long long)N * K >= (1LL << 31)) return IS_ERR_UNSUPPORTED;  // the kernel's weight offsets are 32-bit
     return IS_OK;
 }
 

@@ -20,6 +20,7 @@
 // whose A operands come from LDS, one shift and one v_mad_i32_i24 per partial product (Eq. (2): C'' += C_g * s_g^INT),
 // against a convert and a multiply-add for the float-scale form (Eq. (1)).  The epilogue is the one conversion of
 // Eq. (2): float(acc) * s_a[m] * c[n] / alpha.
+#include <stdio.h>
 #include <stdlib.h>
 
 #include "act_common.h"
@@ -616,15 +617,21 @@ hipError_t launch_pk(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan
     return hipGetLastError();
 }
 
+// Blocks in flight per wave: four token tiles leave registers for six, fewer leave the latency to cover with four.
+constexpr int ring_depth(int mt) { return mt == 4 ? 6 : 4; }
+// Waves per workgroup the instantiations exist for (dispatch_waves and pk_decode_kernel_name both round with this).
+constexpr int waves_instance(int mt, int waves) { return waves <= 4 ? 4 : (waves <= 8 || mt == 4) ? 8 : 16; }
+
 template <bool INT_SCALE, bool FUSEQ, int MT>
 hipError_t dispatch_waves(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan, int device, hipStream_t stream) {
-    if constexpr (MT == 4) {
-        if (plan.waves == 4) return launch_pk<4, 6, 4, INT_SCALE, false>(a, kp, plan, device, stream);
-        return launch_pk<4, 6, 8, INT_SCALE, false>(a, kp, plan, device, stream);
-    } else {
-        if (plan.waves == 4) return launch_pk<MT, 4, 4, INT_SCALE, FUSEQ>(a, kp, plan, device, stream);
-        if (plan.waves == 8) return launch_pk<MT, 4, 8, INT_SCALE, FUSEQ>(a, kp, plan, device, stream);
-        return launch_pk<MT, 4, 16, INT_SCALE, FUSEQ>(a, kp, plan, device, stream);
+    constexpr int DT = ring_depth(MT);
+    constexpr bool FQ = MT == 1 && FUSEQ;
+    switch (waves_instance(MT, plan.waves)) {
+        case 4: return launch_pk<MT, DT, 4, INT_SCALE, FQ>(a, kp, plan, device, stream);
+        case 8: return launch_pk<MT, DT, 8, INT_SCALE, FQ>(a, kp, plan, device, stream);
+        default:
+            if constexpr (MT != 4) return launch_pk<MT, DT, 16, INT_SCALE, FQ>(a, kp, plan, device, stream);
+            return hipErrorInvalidValue;
     }
 }
 
@@ -686,7 +693,7 @@ bool pk_decode_plan(int M, int N, int K, int group, bool fp16_in, PkPlan* plan) 
     if (tiles_max > 256) return false;  // a workgroup stages at most 4096 channel scales
     // Waves per workgroup: enough for every wave to have a full turn of the ring (fewer, fatter waves start sooner and
     // leave fewer pieces to add up), 16 at most; four token tiles need more than 128 registers per lane: 8 at most.
-    const int dt = pl.mt == 4 ? 6 : 4;
+    const int dt = ring_depth(pl.mt);
     const long long blocks = (long long)tiles_max * pl.max_steps;
     int waves = pl.mt == 4 ? 8 : 4;
     while (waves < (pl.mt == 4 ? 8 : 16) && (long long)waves * 2 * dt <= blocks) waves *= 2;
@@ -713,6 +720,13 @@ bool pk_decode_plan(int M, int N, int K, int group, bool fp16_in, PkPlan* plan) 
     pl.lds_bytes = (size_t)pl.cs_offset + (size_t)tiles_max * 64;
     *plan = pl;
     return true;
+}
+
+// The instantiation launch_gemm_decode_pk picks for this plan, as a kernel trace names it.
+void pk_decode_kernel_name(const PkPlan& plan, bool int_scale, bool fp16_in, char* buf, size_t len) {
+    const int mt = fp16_in ? 1 : plan.mt;
+    snprintf(buf, len, "gemm_decode_pk_kernel<%d, %d, %d, %s, %s>", mt, ring_depth(mt), waves_instance(mt, plan.waves),
+             int_scale ? "true" : "false", fp16_in ? "true" : "false");
 }
 
 size_t pk_decode_workspace_bytes(int M, int N, int K, int group) {

@@ -26,6 +26,8 @@
 // bit operation), the high nibbles take a shift more; the product sum comes out as P + 8 * sum_k x[m,k], and the
 // correction -8 * sum_k x[m,k] per (token row, K step), computed once by the preparation kernel, enters each MFMA
 // chain as its initial accumulator, so the chain returns P exactly and the scale step costs one instruction per element.
+#include <stdio.h>
+
 #include "act_common.h"
 #include "pk_common.h"
 #include "tile_common.h"
@@ -341,6 +343,12 @@ __global__ __launch_bounds__(kTThreads) __attribute__((amdgpu_waves_per_eu(2, 2)
     }
 }
 
+// 16-value chunks of a token row per lane of the fused quantiser + preparation (256 lanes per row)
+int prepare_chunks(int K) {
+    const int nchunk = K >> 4;
+    return nchunk <= 256 ? 1 : nchunk <= 2 * 256 ? 2 : nchunk <= 4 * 256 ? 4 : 8;
+}
+
 size_t xp_bytes(int M, int K) { return pad256((size_t)((M + 15) / 16) * 16 * K); }
 size_t c0_bytes(int M, int K) { return pad256((size_t)((M + 15) / 16) * (K / 128) * 64); }
 
@@ -352,19 +360,27 @@ size_t gemm_tile_pk_workspace_bytes(int M, int K) { return xp_bytes(M, K) + c0_b
 // rows the fused quantiser + preparation holds in registers: 8 chunks of 16 values per lane, 256 lanes
 bool gemm_tile_pk_takes_fp16(int K) { return (K & 15) == 0 && (K >> 4) <= 8 * 256; }
 
+void gemm_tile_pk_kernel_names(int K, bool int_scale, bool fp16_in, char* buf, size_t len) {
+    char prep[96];
+    if (fp16_in) snprintf(prep, sizeof prep, "quantize_prepare_activations_pk_kernel<%d>", prepare_chunks(K));
+    else snprintf(prep, sizeof prep, "prepare_activations_pk_kernel");
+    snprintf(buf, len, "%s\ngemm_tile_pk_kernel<%s>", prep, int_scale ? "true" : "false");
+}
+
 hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace, hipStream_t stream) {
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     int8_t* xp = reinterpret_cast<int8_t*>(ws);
     int32_t* c0 = reinterpret_cast<int32_t*>(ws + xp_bytes(a.M, a.K));
     if (a.x_fp16) {  // fp16 activations: quantised on the way, the token scales go to a.a_scale_out (= a.a_scale)
-        const int nchunk = a.K >> 4;
 #define QP_PK(CH)                                                                                                    \
     hipLaunchKernelGGL(quantize_prepare_activations_pk_kernel<CH>, dim3(a.M), dim3(256), 0, stream, a.x_fp16, a.M, a.K, \
                        xp, c0, a.a_scale_out)
-        if (nchunk <= 256) QP_PK(1);
-        else if (nchunk <= 2 * 256) QP_PK(2);
-        else if (nchunk <= 4 * 256) QP_PK(4);
-        else QP_PK(8);
+        switch (prepare_chunks(a.K)) {
+            case 1: QP_PK(1); break;
+            case 2: QP_PK(2); break;
+            case 4: QP_PK(4); break;
+            default: QP_PK(8); break;
+        }
 #undef QP_PK
     } else {
         hipLaunchKernelGGL(prepare_activations_pk_kernel, dim3(a.M), dim3(256), 0, stream, a.xq, a.M, a.K, xp, c0);

@@ -140,6 +140,69 @@ def test_linear_argument_validation():
     assert lib.is_linear_w4a8_floatscale(A, A, None, 8, 16, 256, 128, A, A, need, None) == bad
 
 
+def test_w8a8_rejects_weights_of_2gib_and_more():
+    """The W8A8 kernels index the int8 weights with 32-bit offsets: N * K >= 2^31 must be refused, not wrapped."""
+    lib = P.load_library()
+    call = lambda N, K: lib.is_gemm_w8a8_intscale(A, A, A, A, None, 8, N, K, 128, 10, A, None, None, 0, None)
+    assert call(1 << 16, 1 << 15) == P.IS_ERR_UNSUPPORTED          # exactly 2^31 weights
+    assert call(1 << 17, 1 << 15) == P.IS_ERR_UNSUPPORTED
+    assert lib.is_gemm_w8a8_workspace_bytes(8, 1 << 16, 1 << 15, 128) == 0
+    assert call(1 << 16, (1 << 15) - 128) != P.IS_ERR_UNSUPPORTED  # just below: passes the shape check
+
+
+def test_prepacked_argument_validation():
+    lib = P.load_library()
+    bad, uns = P.IS_ERR_INVALID_ARG, P.IS_ERR_UNSUPPORTED
+    assert lib.is_prepack_w4_weight_bytes(16, 256) == 2048 and lib.is_prepack_w4_weight_bytes(17, 256) == 4096
+    assert lib.is_prepack_w4_scale_bytes(16, 256, 128) == 256 + 2 * 64
+    assert lib.is_prepack_w4_weight_bytes(16, 200) == 0 and lib.is_prepack_w4_scale_bytes(16, 256, 64) == 0
+    pre = lambda **kw: lib.is_prepack_w4(kw.get("q", A), kw.get("si", A), kw.get("sf", None), 16, kw.get("K", 256),
+                                         kw.get("G", 128), kw.get("wp", A), kw.get("sp", A), None)
+    assert pre(q=None) == bad and pre(wp=None) == bad and pre(sp=None) == bad
+    assert pre(si=None) == bad and pre(sf=A) == bad            # exactly one kind of scales
+    assert pre(G=64) == uns and pre(K=192, G=64) == uns and pre(K=250) == bad
+    gemm = lambda **kw: lib.is_gemm_w4a8_intscale_prepacked(
+        kw.get("xq", A), kw.get("sa", A), kw.get("wp", A), kw.get("sp", A), kw.get("c", None), kw.get("M", 8), 16,
+        kw.get("K", 256), kw.get("G", 128), kw.get("a", 10), kw.get("out", A), None, kw.get("ws", None),
+        kw.get("wsb", 0), None)
+    assert gemm(xq=None) == bad and gemm(sa=None) == bad and gemm(wp=None) == bad and gemm(sp=None) == bad
+    assert gemm(out=None) == bad and gemm(a=31) == bad and gemm(M=-1) == bad and gemm(c=A + 4) == bad
+    assert gemm(G=64) == uns and gemm(M=0) == P.IS_OK
+    need = lib.is_gemm_prepacked_workspace_bytes(128, 16, 256, 128)   # tiled route: prepared activations
+    assert need >= 128 * 256
+    assert gemm(M=128, ws=None) == P.IS_ERR_WORKSPACE and gemm(M=128, ws=A, wsb=need - 1) == P.IS_ERR_WORKSPACE
+    lneed = lib.is_linear_prepacked_workspace_bytes(8, 16, 256, 128)
+    lin = lambda **kw: lib.is_linear_w4a8_intscale_prepacked(
+        kw.get("x", A), kw.get("wp", A), kw.get("sp", A), None, kw.get("M", 8), 16, kw.get("K", 256), 128, 10,
+        kw.get("out", A), None, kw.get("ws", A), kw.get("wsb", lneed), None)
+    assert lneed >= 8 * 256 + 8 * 4
+    assert lin(x=None) == bad and lin(wp=None) == bad and lin(out=None) == bad and lin(K=250) == bad
+    assert lin(ws=None) == P.IS_ERR_WORKSPACE and lin(wsb=lneed - 1) == P.IS_ERR_WORKSPACE
+    assert lin(M=0, ws=None, wsb=0) == P.IS_OK
+
+
+def test_describe_prepacked_names_the_kernels():
+    one = P.is_describe_prepacked(1, 8192, 8192, 128, True, True)
+    assert len(one) == 1 and one[0].startswith("gemm_decode_pk_kernel<1, ") and one[0].endswith("true, true>")
+    dec = P.is_describe_prepacked(32, 8192, 8192, 128, False, False)
+    assert dec[0].startswith("gemm_decode_pk_kernel<2, ") and dec[0].endswith("false, false>")
+    til = P.is_describe_prepacked(2048, 8192, 8192, 128, True, True)
+    assert til == ["quantize_prepare_activations_pk_kernel<2>", "gemm_tile_pk_kernel<true>"]
+    assert P.is_describe_prepacked(2048, 8192, 8192, 128, False, False)[0] == "prepare_activations_pk_kernel"
+    with pytest.raises(P.IntScaleError):
+        P.is_describe_prepacked(8, 16, 256, 64)
+    lib = P.load_library()
+    buf = ctypes.create_string_buffer(8)
+    assert lib.is_describe_prepacked(1, 16, 256, 128, 1, 0, buf, 8) == P.IS_OK and len(buf.value) <= 7   # truncated, terminated
+    assert lib.is_describe_prepacked(1, 16, 256, 128, 1, 0, None, 8) == P.IS_ERR_INVALID_ARG
+
+
+def test_library_carries_the_digest_of_its_sources():
+    from paper_2405_14597_amd import build
+    assert P.load_library().is_source_hash().decode() == build.source_hash() == build.built_hash()
+    assert not build.needs_build()
+
+
 def test_missing_device_is_reported_not_hidden():
     """With valid arguments the call reaches HIP; without a GPU that must surface as IS_ERR_HIP, never as success."""
     import torch
