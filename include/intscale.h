@@ -185,6 +185,24 @@ int is_gemm_w4a8_floatscale_prepacked(const int8_t* xq, const float* a_scale, co
                                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * is_gemm_w4a8_intscale_prepacked for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results, without the workspace: the
+ * call uses a fixed scratch array inside the library (IS_NOALLOC_SCRATCH_BYTES of device memory per GPU, held until
+ * the process ends) and allocates nothing, on the device or through any library.
+ *   - Shapes whose is_gemm_prepacked_workspace_bytes(M,N,K,group) exceeds IS_NOALLOC_SCRATCH_BYTES return
+ *     IS_ERR_WORKSPACE before anything is enqueued (covered: every M <= 64 shape, and tiled shapes up to about
+ *     ceil(M/16) * 16 * K = 31 MiB).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two threads)
+ *     race on it; serialise them or give the overlapping ones the workspace form.
+ *   - The first call on a device resolves the array's address (hipGetSymbolAddress); make that call outside a graph
+ *     capture.  The K split's arrival counters are cleared by a small kernel of the call, not by a memset.
+ */
+#define IS_NOALLOC_SCRATCH_BYTES (32u << 20)
+int is_gemm_w4a8_intscale_prepacked_noalloc(const int8_t* xq, const float* a_scale, const void* qweight_packed,
+                                            const void* scales_packed, const float* chan_scale, int M, int N, int K,
+                                            int group, int alpha_log2, void* out_fp16, int32_t* acc_out, void* stream);
+
+/*
  * The linear layer on fp16 activations and prepacked weights: Appendix A.1 per token, then Eq. (2) / Eq. (1), with the
  * results of is_quantize_act_int8_token followed by the prepacked GEMM, to the bit.  One token (M = 1, K <= 32768) is
  * quantised inside the GEMM kernel (one launch); more than 64 tokens (K <= 32768) are quantised by the tiled kernel's

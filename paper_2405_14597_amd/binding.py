@@ -48,6 +48,7 @@ EXPORTED_SYMBOLS = (
     "is_gemm_prepacked_workspace_bytes",
     "is_gemm_w4a8_intscale_prepacked",
     "is_gemm_w4a8_floatscale_prepacked",
+    "is_gemm_w4a8_intscale_prepacked_noalloc",
     "is_linear_prepacked_workspace_bytes",
     "is_linear_w4a8_intscale_prepacked",
     "is_linear_w4a8_floatscale_prepacked",
@@ -141,6 +142,8 @@ def load_library() -> ctypes.CDLL:
     lib.is_gemm_w4a8_intscale_prepacked.restype = ci
     lib.is_gemm_w4a8_floatscale_prepacked.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, vp, vp, sz, vp]
     lib.is_gemm_w4a8_floatscale_prepacked.restype = ci
+    lib.is_gemm_w4a8_intscale_prepacked_noalloc.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp]
+    lib.is_gemm_w4a8_intscale_prepacked_noalloc.restype = ci
     lib.is_linear_prepacked_workspace_bytes.argtypes = [ci, ci, ci, ci]
     lib.is_linear_prepacked_workspace_bytes.restype = sz
     lib.is_linear_w4a8_intscale_prepacked.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
@@ -658,6 +661,33 @@ def is_gemm_w4a8_intscale_prepacked(xq, a_scale, packed: PackedWeights, chan_sca
                                                        _p(ws), ws_bytes, _stream_handle(stream))
     _check("is_gemm_w4a8_intscale_prepacked", st)
     _release_workspace(ws, workspace, stream)
+    return out, acc_out
+
+
+IS_NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def is_gemm_w4a8_intscale_prepacked_noalloc(xq, a_scale, packed: PackedWeights, chan_scale, alpha_log2: int, out,
+                                            acc_out=None, stream=None):
+    """The prepacked integer-scale GEMM on the library's fixed scratch: nothing is allocated, here or in the library, so
+    `out` (fp16 [M,N]) and, if wanted, `acc_out` (int32 [M,N]) come from the caller.  Calls that overlap on one GPU
+    race on the scratch."""
+    torch = _torch()
+    M, K = xq.shape
+    N, group = packed.N, packed.group
+    if K != packed.K or packed.float_scales:
+        raise ValueError("packed weights: K mismatch or float scales")
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    if chan_scale is not None:
+        _require(chan_scale, torch.float32, (N,), "chan_scale")
+    _require(out, torch.float16, (M, N), "out")
+    if acc_out is not None:
+        _require(acc_out, torch.int32, (M, N), "acc_out")
+    st = load_library().is_gemm_w4a8_intscale_prepacked_noalloc(_p(xq), _p(a_scale), _p(packed.wpack), _p(packed.spack),
+                                                               _p(chan_scale), M, N, K, group, alpha_log2, _p(out),
+                                                               _p(acc_out), _stream_handle(stream))
+    _check("is_gemm_w4a8_intscale_prepacked_noalloc", st)
     return out, acc_out
 
 

@@ -2,10 +2,17 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "is_common.h"
 #include "pk_common.h"
 
 using namespace intscale;
+
+// Workspace of the prepacked integer-scale GEMM for callers that cannot allocate.  Every GPU the library runs on holds
+// one copy (at its own address) until the process ends; in host code the array's name is only a handle for
+// hipGetSymbolAddress (static_scratch below), the kernels get the resolved address.
+static __device__ __align__(256) unsigned char scratch[IS_NOALLOC_SCRATCH_BYTES];
 
 namespace {
 
@@ -55,6 +62,32 @@ hipError_t launch_gemm(const GemmArgs& a, bool int_scale, void* workspace, hipSt
     hipError_t err = hipSuccess;
     if (!general_forced() && try_launch_gemm_decode(a, int_scale, stream, &err)) return err;
     return launch_gemm_skinny(a, int_scale, stream);
+}
+
+__global__ void zero_words_kernel(int32_t* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+// This device's copy of `scratch`, resolved once per device with that device current.
+int static_scratch(void** ptr_out) {
+    constexpr int kMaxDevices = 64;
+    static void* resolved[kMaxDevices] = {};
+    static std::mutex lock;
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return hip_status(e);
+    if (device < 0 || device >= kMaxDevices) return IS_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> hold(lock);
+    if (resolved[device] == nullptr) {  // once per device, with that device current
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_status(e);
+        if (p == nullptr) return IS_ERR_HIP;
+        resolved[device] = p;
+    }
+    *ptr_out = resolved[device];
+    return IS_OK;
 }
 
 }  // namespace
@@ -365,7 +398,7 @@ size_t is_gemm_prepacked_workspace_bytes(int M, int N, int K, int group) {
 static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_scale, float* a_scale_out,
                           const void* wpack, const void* spack, const float* chan_scale, int M, int N, int K, int group,
                           int alpha_log2, void* out_fp16, int32_t* acc_out, void* workspace, size_t workspace_bytes,
-                          void* stream, bool int_scale) {
+                          void* stream, bool int_scale, bool clear_counters = false) {
     if (M < 0) return IS_ERR_INVALID_ARG;
     const int shape = check_pk_shape(N, K, group);
     if (shape != IS_OK) return shape;
@@ -400,6 +433,13 @@ static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_s
     a.group = group;
     a.alpha_log2 = int_scale ? alpha_log2 : 0;
     if (M > 64) return hip_status(launch_gemm_tile_pk(a, int_scale, workspace, static_cast<hipStream_t>(stream)));
+    if (clear_counters && a.partials != nullptr) {  // a workspace whose last user may not have left the counters zero
+        const int n16 = (N + 15) / 16;
+        hipLaunchKernelGGL(zero_words_kernel, dim3((n16 + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
+                           a.counters, n16);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_status(e);
+    }
     return hip_status(launch_gemm_decode_pk(a, int_scale, static_cast<hipStream_t>(stream)));
 }
 
@@ -416,6 +456,26 @@ int is_gemm_w4a8_floatscale_prepacked(const int8_t* xq, const float* a_scale, co
                                       void* workspace, size_t workspace_bytes, void* stream) {
     return gemm_pk_common(xq, nullptr, a_scale, nullptr, qweight_packed, scales_packed, nullptr, M, N, K, group, 0,
                           out_fp16, nullptr, workspace, workspace_bytes, stream, false);
+}
+
+int is_gemm_w4a8_intscale_prepacked_noalloc(const int8_t* xq, const float* a_scale, const void* qweight_packed,
+                                            const void* scales_packed, const float* chan_scale, int M, int N, int K,
+                                            int group, int alpha_log2, void* out_fp16, int32_t* acc_out, void* stream) {
+    if (M < 0) return IS_ERR_INVALID_ARG;
+    const int shape = check_pk_shape(N, K, group);
+    if (shape != IS_OK) return shape;
+    const size_t need = is_gemm_prepacked_workspace_bytes(M, N, K, group);
+    if (need > (size_t)IS_NOALLOC_SCRATCH_BYTES) return IS_ERR_WORKSPACE;  // beyond the fixed scratch: use the other call
+    void* ws = nullptr;
+    if (need > 0) {
+        const int st = static_scratch(&ws);
+        if (st != IS_OK) return st;
+    }
+    // The array keeps what the last call left: the arrival counters of the K split are cleared on the stream first
+    // (by a kernel, so that the call can be captured into a graph); everything else is written before it is read.
+    return gemm_pk_common(xq, nullptr, a_scale, nullptr, qweight_packed, scales_packed, chan_scale, M, N, K, group,
+                          alpha_log2, out_fp16, acc_out, ws, need > 0 ? (size_t)IS_NOALLOC_SCRATCH_BYTES : 0, stream, true,
+                          /*clear_counters=*/true);
 }
 
 size_t is_linear_prepacked_workspace_bytes(int M, int N, int K, int group) {

@@ -181,6 +181,20 @@ def test_prepacked_argument_validation():
     assert lin(M=0, ws=None, wsb=0) == P.IS_OK
 
 
+def test_noalloc_argument_validation():
+    """The entry point without a workspace checks shapes and the size of its fixed scratch before any HIP call."""
+    lib = P.load_library()
+    bad = P.IS_ERR_INVALID_ARG
+    call = lambda **kw: lib.is_gemm_w4a8_intscale_prepacked_noalloc(
+        kw.get("xq", A), kw.get("sa", A), kw.get("wp", A), kw.get("sp", A), None, kw.get("M", 8), kw.get("N", 16),
+        kw.get("K", 256), kw.get("G", 128), kw.get("a", 10), kw.get("out", A), None, None)
+    assert call(M=-1) == bad and call(K=250) == bad and call(G=64) == P.IS_ERR_UNSUPPORTED
+    assert call(xq=None) == bad and call(wp=None) == bad and call(out=None) == bad and call(a=31) == bad
+    assert call(M=0) == P.IS_OK
+    assert lib.is_gemm_prepacked_workspace_bytes(2048, 256, 28672, 128) > P.IS_NOALLOC_SCRATCH_BYTES
+    assert call(M=2048, N=256, K=28672) == P.IS_ERR_WORKSPACE
+
+
 def test_describe_prepacked_names_the_kernels():
     one = P.is_describe_prepacked(1, 8192, 8192, 128, True, True)
     assert len(one) == 1 and one[0].startswith("gemm_decode_pk_kernel<1, ") and one[0].endswith("true, true>")
