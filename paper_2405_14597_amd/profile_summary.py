@@ -42,12 +42,12 @@ def short(name: str) -> str:
 
 
 def read_counters(path):
-    """{kernel: {counter: (average per dispatch, dispatches)}} of one counter-collection CSV."""
+    """{kernel: {counter: (average per dispatch, dispatches, largest dispatch)}} of one counter-collection CSV."""
     acc = collections.defaultdict(lambda: collections.defaultdict(list))
     with open(path, newline="") as f:
         for r in csv.DictReader(f):
             acc[r["Kernel_Name"]][r["Counter_Name"]].append(float(r["Counter_Value"]))
-    return {k: {c: (sum(v) / len(v), len(v)) for c, v in cs.items()} for k, cs in acc.items()}
+    return {k: {c: (sum(v) / len(v), len(v), max(v)) for c, v in cs.items()} for k, cs in acc.items()}
 
 
 def ours(name: str) -> bool:
@@ -71,8 +71,9 @@ def calibration(table, counter, pick, known_bytes):
     cands = [(k, v[counter]) for k, v in table.items() if counter in v and pick(k)]
     if not cands:
         sys.exit(f"profile_summary: no calibration kernel for {counter} in this pass")
-    k, (avg, n) = max(cands, key=lambda kv: kv[1][0])
-    return k, avg, known_bytes / (avg * 1024.0)
+    # the kernel runs at other sizes too in the same command: its largest dispatch is the one of known size
+    k, (avg, n, top) = max(cands, key=lambda kv: kv[1][2])
+    return k, top, known_bytes / (top * 1024.0)
 
 
 def cmd_traffic(args):
@@ -82,14 +83,14 @@ def cmd_traffic(args):
     print("HBM traffic per dispatch, one MI355X, from two rocprofv3 counter passes")
     print(f"commands (from /tmp, TMPDIR=/tmp): rocprofv3 --pmc FETCH_SIZE --kernel-trace -d <out> -o p --output-format csv -- {args.command}")
     print(f"                                   rocprofv3 --pmc WRITE_SIZE --kernel-trace -d <out> -o p --output-format csv -- {args.command}")
-    print(f"scaling: the 1 GiB streaming-read probe of the same run reads FETCH_SIZE = {vf:.0f} per dispatch, the 1 GiB fill before")
+    print(f"scaling: the 1 GiB streaming-read probe of the same run reads FETCH_SIZE = {vf:.0f}, the 1 GiB fill before")
     print(f"         it WRITE_SIZE = {vw:.0f} (KiB expected: {GIB // 1024}), so bytes = counter * 1024 * {sf:.3f} (fetch) and * {sw:.3f} (write)")
     print("columns: TRAFFIC, kernel, HBM bytes per dispatch (fetch + write) | then fetch bytes, write bytes, dispatches\n")
     order = sorted((k for k in fe if ours(k) and "FETCH_SIZE" in fe[k]),
                    key=lambda k: -fe[k]["FETCH_SIZE"][0] * fe[k]["FETCH_SIZE"][1])
     for k in order:
         fb = fe[k]["FETCH_SIZE"][0] * 1024 * sf
-        wb = wr.get(k, {}).get("WRITE_SIZE", (0.0, 0))[0] * 1024 * sw
+        wb = wr.get(k, {}).get("WRITE_SIZE", (0.0, 0, 0.0))[0] * 1024 * sw
         print(f"TRAFFIC\t{short(k)}\t{fb + wb:.0f}")
         print(f"#\t{short(k)}\tfetch {fb:.0f}\twrite {wb:.0f}\tdispatches {fe[k]['FETCH_SIZE'][1]}")
 
@@ -101,7 +102,7 @@ def cmd_counters(args):
         for k, cs in read_counters(path).items():
             if not ours(k):
                 continue
-            for c, (avg, n) in cs.items():
+            for c, (avg, n, _) in cs.items():
                 merged[short(k)][c] = avg
                 merged[short(k)]["dispatches"] = n
                 if c not in names:
