@@ -205,8 +205,8 @@ int is_gemm_w4a8_intscale_prepacked_noalloc(const int8_t* xq, const float* a_sca
 /*
  * The linear layer on fp16 activations and prepacked weights: Appendix A.1 per token, then Eq. (2) / Eq. (1), with the
  * results of is_quantize_act_int8_token followed by the prepacked GEMM, to the bit.  One token (M = 1, K <= 32768) is
- * quantised inside the GEMM kernel (one launch); more than 64 tokens (K <= 32768) are quantised by the tiled kernel's
- * preparation pass; otherwise the quantiser runs first.
+ * quantised inside the GEMM kernel (one launch); more than 64 tokens are quantised by the tiled kernel's preparation
+ * pass; otherwise the quantiser runs first.
  *   workspace   at least is_linear_prepacked_workspace_bytes(M,N,K,group) bytes: quantised activations [M,K], token
  *               scales [M] (each padded to 256 bytes), then the GEMM's workspace, whose zero-counter rule applies.
  */

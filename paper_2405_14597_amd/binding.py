@@ -80,7 +80,10 @@ def load_library() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    if _build.needs_build():
+    if "INTSCALE_LIBRARY" in os.environ:      # somebody else's build: loaded as it is
+        if not os.path.exists(_build.LIB_PATH):
+            raise IntScaleError("load_library", IS_ERR_INVALID_ARG, f"INTSCALE_LIBRARY={_build.LIB_PATH} does not exist")
+    elif _build.needs_build():
         _build.build_library(force=True)
     # The library and torch must share ONE HIP runtime (device pointers and streams cross between them), so torch's
     # runtime is loaded first and libintscale.so's libamdhip64 dependency resolves to it.

@@ -88,6 +88,11 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
     // "some integer scale needs more than 24 signed bits" (left in the header by the prepacking): asked for here,
     // needed only in the first scale step, so that the request is not waited for ahead of the weight stream
     const int pk_flags = *reinterpret_cast<const int32_t*>(a.spack);
+    // All kernel arguments travel in one round trip: without this the ones first used behind a branch are asked for
+    // there, and waited for a second time.
+    asm volatile("" ::"s"(a.xq), "s"(a.x_fp16), "s"(a.a_scale), "s"(a.a_scale_out), "s"(a.chan_scale), "s"(a.out),
+                 "s"(a.acc_out), "s"(a.counters), "s"(a.partials), "s"(a.M), "s"(a.N), "s"(a.alpha_log2), "s"(p.rows),
+                 "s"(p.slot_offset), "s"(p.cs_offset), "s"(p.n16), "s"(p.slabs));
 
     // ---- this workgroup's slab and row tiles, this wave's blocks.  (Grid: x = workgroup inside its slab, y = slab.
     // Even shares without a division: the first `..._r` owners take one more than `..._q`.)  Everything up to the
@@ -99,8 +104,8 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
     const int ksl = p.steps_q + (slab < p.steps_r ? 1 : 0);
     const int t0 = jw * p.tiles_q + min(jw, p.tiles_r);
     const int t1 = t0 + p.tiles_q + (jw < p.tiles_r ? 1 : 0);
-    const int B = (t1 - t0) * ksl;
-    if (B <= 0) return;  // uniform over the workgroup, before any barrier
+    const int B = (t1 - t0) * ksl;  // (a workgroup without blocks leaves behind its first, empty, requests: an early
+                                    // exit here would split the kernel-argument loads into two round trips)
     const int b0 = (wave * B) / W, b1 = ((wave + 1) * B) / W;
     const rsrc_t wres = make_rsrc(a.wpack, p.wbytes);
     const rsrc_t sres = make_rsrc(a.spack + kPkHeaderBytes, p.sbytes);
@@ -161,6 +166,7 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
     issue_advance();
     __builtin_amdgcn_sched_barrier(0);
     PK_MARK(1);
+    if (B <= 0) return;  // uniform over the workgroup, before any barrier; its requests lay outside the buffers
 
     // ---- the activations of the slab, requested behind the stream's first blocks and written to LDS below.
     // A fill unit is 8 token rows x one K step (8 x 128 bytes); unit u = step * (row blocks) + row block.
@@ -300,20 +306,25 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
         const int n = tile * 16 + li;
         if (n >= a.N) return;
         const float cc = lds_cs[(tile - t0) * 16 + li] * inv_alpha;
+        // Element index of this lane's first output (M <= 64 rows: 32 bits are enough).  Opaque to the compiler, or it
+        // keeps one 64-bit address per row and output tensor in registers across the whole K loop.
+        int first = 4 * kb * a.N + n;
+        asm volatile("" : "+v"(first));
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int m = 16 * t + 4 * kb + r;
                 if (m < a.M) {
+                    const int at = first + (16 * t + r) * a.N;
                     float o;
                     if constexpr (INT_SCALE) {
                         o = (float)v[t][r] * sa[t][r] * cc;
-                        if (a.acc_out) a.acc_out[(size_t)m * a.N + n] = v[t][r];
+                        if (a.acc_out) a.acc_out[at] = v[t][r];
                     } else {
                         o = v[t][r] * sa[t][r];
                     }
-                    a.out[(size_t)m * a.N + n] = __float2half_rn(o);
+                    a.out[at] = __float2half_rn(o);
                 }
             }
     };
@@ -618,7 +629,10 @@ hipError_t launch_pk(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan
 }
 
 // Blocks in flight per wave: four token tiles leave registers for six, fewer leave the latency to cover with four.
-constexpr int ring_depth(int mt) { return mt == 4 ? 6 : 4; }
+#ifndef INTSCALE_PK_RING  // (a build-time switch for experiments)
+#define INTSCALE_PK_RING 4
+#endif
+constexpr int ring_depth(int mt) { return mt == 4 ? 6 : INTSCALE_PK_RING; }
 // Waves per workgroup the instantiations exist for (dispatch_waves and pk_decode_kernel_name both round with this).
 constexpr int waves_instance(int mt, int waves) { return waves <= 4 ? 4 : (waves <= 8 || mt == 4) ? 8 : 16; }
 

@@ -46,67 +46,106 @@ constexpr int kGroupRows = 8;           // tile rows of the block of tiles an XC
 
 // ---- preparation of the activations: 2 KB blocks [16-row tile][K step] = [MFMA half h][k chunk kb][row r][16 codes],
 // the 16 codes of (h, kb) being k = 128 s + 64 h + 16 kb .. + 15 of row 16 mt + r, and the zero-point corrections
-// c0[tile][step][r] = -8 * sum over the step's 128 codes.  One workgroup per token row; 8 lanes share a K step.
-__device__ __forceinline__ void store_prepared(int m, int c, uint4 v, int steps, int8_t* __restrict__ xp,
-                                               int32_t* __restrict__ c0, bool valid) {
-    int sum = 0;
-    if (valid) {
-        sum = __builtin_amdgcn_sdot4((int)v.x, 0x01010101, sum, false);
-        sum = __builtin_amdgcn_sdot4((int)v.y, 0x01010101, sum, false);
-        sum = __builtin_amdgcn_sdot4((int)v.z, 0x01010101, sum, false);
-        sum = __builtin_amdgcn_sdot4((int)v.w, 0x01010101, sum, false);
-        const size_t blk = (size_t)(m >> 4) * steps + (c >> 3);
-        *reinterpret_cast<uint4*>(xp + blk * 2048 + ((c >> 2) & 1) * 1024 + (c & 3) * 256 + (m & 15) * 16) = v;
-    }
-    sum += __shfl_xor(sum, 1, kWave);
-    sum += __shfl_xor(sum, 2, kWave);
-    sum += __shfl_xor(sum, 4, kWave);
-    if ((threadIdx.x & 7) == 0 && valid) c0[((size_t)(m >> 4) * steps + (c >> 3)) * 16 + (m & 15)] = -8 * sum;
+// c0[tile][step][r] = -8 * sum over the step's 128 codes.  A wave works on whole blocks of one 16-row tile: lane
+// (kb, r) fetches its 16 codes of row r and the wave writes each half block as one contiguous kilobyte; rows past M
+// become zeros.
+__device__ __forceinline__ int sum16(uint4 v) {
+    int sum = __builtin_amdgcn_sdot4((int)v.x, 0x01010101, 0, false);
+    sum = __builtin_amdgcn_sdot4((int)v.y, 0x01010101, sum, false);
+    sum = __builtin_amdgcn_sdot4((int)v.z, 0x01010101, sum, false);
+    return __builtin_amdgcn_sdot4((int)v.w, 0x01010101, sum, false);
 }
 
+// One block: the two half blocks of lane (kb, r), and the row's correction through the four kb lanes of the row.
+__device__ __forceinline__ void store_block(size_t blk, int lane, uint4 lo, uint4 hi, int8_t* __restrict__ xp,
+                                            int32_t* __restrict__ c0) {
+    uint4* dst = reinterpret_cast<uint4*>(xp + blk * 2048);
+    dst[lane] = lo;
+    dst[64 + lane] = hi;
+    int sum = sum16(lo) + sum16(hi);
+    sum += __shfl_xor(sum, 16, kWave);
+    sum += __shfl_xor(sum, 32, kWave);
+    if (lane < 16) c0[blk * 16 + lane] = -8 * sum;
+}
+
+constexpr int kPrepSteps = 4;  // K steps per wave of the int8 preparation (8 loads of 16 bytes in flight per lane)
+
+// Quantised activations in: grid (16-row tiles, K steps / (4 waves * kPrepSteps)).
 __global__ __launch_bounds__(256) void prepare_activations_pk_kernel(const int8_t* __restrict__ xq, int M, int K,
                                                                      int8_t* __restrict__ xp, int32_t* __restrict__ c0) {
-    const int m = blockIdx.x;
-    const uint4* row = reinterpret_cast<const uint4*>(xq + (size_t)m * K);
-    const int nchunk = K >> 4, steps = K >> 7;
-    for (int cb = 0; cb < nchunk; cb += 256) {
-        const int c = cb + threadIdx.x;
-        const bool valid = c < nchunk;
-        store_prepared(m, c, valid ? row[c] : make_uint4(0u, 0u, 0u, 0u), steps, xp, c0, valid);
-    }
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int r = lane & 15, kb = lane >> 4;
+    const int mt = blockIdx.x, m = 16 * mt + r;
+    const int steps = K >> 7;
+    const int s0 = (blockIdx.y * 4 + wave) * kPrepSteps;
+    const int8_t* src = xq + (size_t)min(m, M - 1) * K + kb * 16;
+    uint4 v[kPrepSteps][2];
+#pragma unroll
+    for (int j = 0; j < kPrepSteps; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int st = min(s0 + j, steps - 1);
+            v[j][h] = *reinterpret_cast<const uint4*>(src + st * 128 + h * 64);
+            if (m >= M) v[j][h] = make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+    for (int j = 0; j < kPrepSteps; ++j)
+        if (s0 + j < steps) store_block((size_t)mt * steps + s0 + j, lane, v[j][0], v[j][1], xp, c0);
 }
 
 // The same straight from fp16 activations (the linear call): the per-token quantiser of Appendix A.1 and the
-// preparation in one pass, the row held in registers (CH chunks of 16 values per lane) between absmax and rounding.
-template <int CH>
-__global__ __launch_bounds__(256) void quantize_prepare_activations_pk_kernel(const __half* __restrict__ x, int M, int K,
-                                                                              int8_t* __restrict__ xp,
-                                                                              int32_t* __restrict__ c0,
-                                                                              float* __restrict__ a_scale) {
+// preparation, in two kernels so that both fill the chip: the token scales first (one workgroup per row), then the
+// rounding on the block grid of the kernel above (the second read of the activations comes from cache).
+__global__ __launch_bounds__(256) void token_scales_kernel(const __half* __restrict__ x, int M, int K,
+                                                           float* __restrict__ a_scale) {
     __shared__ float red[4];
     const int m = blockIdx.x;
-    const int lane = threadIdx.x;
     const uint4* row = reinterpret_cast<const uint4*>(x + (size_t)m * K);  // 8 fp16 values each
-    const int nchunk = K >> 4, steps = K >> 7;
-    uint4 v[CH][2];
+    const int n8 = K >> 3;
     float amax = 0.0f;
+    for (int c = threadIdx.x; c < n8; c += 4 * 256) {  // four loads in flight per lane
+        uint4 v[4];
 #pragma unroll
-    for (int j = 0; j < CH; ++j) {
-        const int c = lane + j * 256;
-        v[j][0] = c < nchunk ? row[2 * c] : make_uint4(0u, 0u, 0u, 0u);
-        v[j][1] = c < nchunk ? row[2 * c + 1] : make_uint4(0u, 0u, 0u, 0u);
+        for (int j = 0; j < 4; ++j) v[j] = row[min(c + j * 256, n8 - 1)];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) amax = fmaxf(amax, absmax8(v[j]));
     }
-#pragma unroll
-    for (int j = 0; j < CH; ++j) amax = fmaxf(amax, fmaxf(absmax8(v[j][0]), absmax8(v[j][1])));
     amax = block_max<4>(amax, red);
-    const float s = amax / 127.0f;
-    if (lane == 0) a_scale[m] = s;
+    if (threadIdx.x == 0) a_scale[m] = amax / 127.0f;
+}
+
+__global__ __launch_bounds__(256) void quantize_prepare_activations_pk_kernel(const __half* __restrict__ x, int M, int K,
+                                                                              const float* __restrict__ a_scale,
+                                                                              int8_t* __restrict__ xp,
+                                                                              int32_t* __restrict__ c0) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int r = lane & 15, kb = lane >> 4;
+    const int mt = blockIdx.x, m = 16 * mt + r;
+    const int steps = K >> 7;
+    const int s0 = (blockIdx.y * 4 + wave) * kPrepSteps;
+    const __half* src = x + (size_t)min(m, M - 1) * K + kb * 16;
+    const float s = a_scale[min(m, M - 1)];
+    uint4 v[kPrepSteps][2][2];
 #pragma unroll
-    for (int j = 0; j < CH; ++j) {
-        const int c = lane + j * 256;
-        const uint2 lo = quantize8(v[j][0], s), hi = quantize8(v[j][1], s);  // the canonical 16 codes, in k order
-        store_prepared(m, c, make_uint4(lo.x, lo.y, hi.x, hi.y), steps, xp, c0, c < nchunk);
-    }
+    for (int j = 0; j < kPrepSteps; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int st = min(s0 + j, steps - 1);
+                v[j][h][q] = *reinterpret_cast<const uint4*>(src + st * 128 + h * 64 + q * 8);
+            }
+#pragma unroll
+    for (int j = 0; j < kPrepSteps; ++j)
+        if (s0 + j < steps) {
+            uint4 codes[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint2 lo = quantize8(v[j][h][0], s), hi = quantize8(v[j][h][1], s);  // the canonical 16 codes
+                codes[h] = m < M ? make_uint4(lo.x, lo.y, hi.x, hi.y) : make_uint4(0u, 0u, 0u, 0u);
+            }
+            store_block((size_t)mt * steps + s0 + j, lane, codes[0], codes[1], xp, c0);
+        }
 }
 
 typedef float v4f_t __attribute__((ext_vector_type(4)));
@@ -343,12 +382,6 @@ __global__ __launch_bounds__(kTThreads) __attribute__((amdgpu_waves_per_eu(2, 2)
     }
 }
 
-// 16-value chunks of a token row per lane of the fused quantiser + preparation (256 lanes per row)
-int prepare_chunks(int K) {
-    const int nchunk = K >> 4;
-    return nchunk <= 256 ? 1 : nchunk <= 2 * 256 ? 2 : nchunk <= 4 * 256 ? 4 : 8;
-}
-
 size_t xp_bytes(int M, int K) { return pad256((size_t)((M + 15) / 16) * 16 * K); }
 size_t c0_bytes(int M, int K) { return pad256((size_t)((M + 15) / 16) * (K / 128) * 64); }
 
@@ -357,12 +390,11 @@ size_t c0_bytes(int M, int K) { return pad256((size_t)((M + 15) / 16) * (K / 128
 // workspace = [prepared activations: ceil(M/16) x K/128 blocks of 2 KB | corrections: ceil(M/16) x K/128 x 16 words]
 size_t gemm_tile_pk_workspace_bytes(int M, int K) { return xp_bytes(M, K) + c0_bytes(M, K); }
 
-// rows the fused quantiser + preparation holds in registers: 8 chunks of 16 values per lane, 256 lanes
-bool gemm_tile_pk_takes_fp16(int K) { return (K & 15) == 0 && (K >> 4) <= 8 * 256; }
+bool gemm_tile_pk_takes_fp16(int K) { return (K & 127) == 0; }
 
 void gemm_tile_pk_kernel_names(int K, bool int_scale, bool fp16_in, char* buf, size_t len) {
     char prep[96];
-    if (fp16_in) snprintf(prep, sizeof prep, "quantize_prepare_activations_pk_kernel<%d>", prepare_chunks(K));
+    if (fp16_in) snprintf(prep, sizeof prep, "token_scales_kernel\nquantize_prepare_activations_pk_kernel");
     else snprintf(prep, sizeof prep, "prepare_activations_pk_kernel");
     snprintf(buf, len, "%s\ngemm_tile_pk_kernel<%s>", prep, int_scale ? "true" : "false");
 }
@@ -371,19 +403,15 @@ hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace,
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     int8_t* xp = reinterpret_cast<int8_t*>(ws);
     int32_t* c0 = reinterpret_cast<int32_t*>(ws + xp_bytes(a.M, a.K));
+    const int mtiles = (a.M + 15) / 16;
+    const int per_wg = 4 * kPrepSteps;
+    const dim3 blocks(mtiles, ((a.K >> 7) + per_wg - 1) / per_wg);
     if (a.x_fp16) {  // fp16 activations: quantised on the way, the token scales go to a.a_scale_out (= a.a_scale)
-#define QP_PK(CH)                                                                                                    \
-    hipLaunchKernelGGL(quantize_prepare_activations_pk_kernel<CH>, dim3(a.M), dim3(256), 0, stream, a.x_fp16, a.M, a.K, \
-                       xp, c0, a.a_scale_out)
-        switch (prepare_chunks(a.K)) {
-            case 1: QP_PK(1); break;
-            case 2: QP_PK(2); break;
-            case 4: QP_PK(4); break;
-            default: QP_PK(8); break;
-        }
-#undef QP_PK
+        hipLaunchKernelGGL(token_scales_kernel, dim3(a.M), dim3(256), 0, stream, a.x_fp16, a.M, a.K, a.a_scale_out);
+        hipLaunchKernelGGL(quantize_prepare_activations_pk_kernel, blocks, dim3(256), 0, stream, a.x_fp16, a.M, a.K,
+                           a.a_scale_out, xp, c0);
     } else {
-        hipLaunchKernelGGL(prepare_activations_pk_kernel, dim3(a.M), dim3(256), 0, stream, a.xq, a.M, a.K, xp, c0);
+        hipLaunchKernelGGL(prepare_activations_pk_kernel, blocks, dim3(256), 0, stream, a.xq, a.M, a.K, xp, c0);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
