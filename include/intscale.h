@@ -9,13 +9,25 @@
  *
  * Conventions for every entry point
  *   - Every tensor pointer is a DEVICE pointer owned by the caller, 16-byte aligned, dense row-major.
- *     The library allocates nothing, keeps no state between calls and never synchronises.
+ *     The library allocates nothing and never synchronises.  No result depends on an earlier call; the process state
+ *     it does keep is housekeeping: the compute-unit count of the device (read once), which kernels have had their
+ *     LDS limit raised on which device, the resolved address of the fixed scratch of the *_noalloc call, and the
+ *     environment switches INTSCALE_FORCE_KERNEL / INTSCALE_PK_SLABS / INTSCALE_PK_WAVES / INTSCALE_SKINNY_* (tests
+ *     and experiments; unset in production), read at each call.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
  *   - Return value: IS_OK, or a negative IS_ERR_* code.  Arguments are validated before any HIP call; on an
  *     argument error nothing is enqueued and the outputs are untouched.
  *   - Notation: X is [M,K] (tokens x in-features), W is [N,K] (out-features x in-features, so the layer is
  *     X * W^T as in Eq. (1)); groups run along K; NG = K / group; alpha = 2^alpha_log2.
  *   - Rounding is round-half-to-even everywhere; the quantisers divide in IEEE fp32.
+ *   - Group sizes.  The quantisers take any even group size that divides K (Appendix A.2).  The GEMMs take multiples
+ *     of 128 only and return IS_ERR_UNSUPPORTED for 32 and 64: their K step is one pair of 16x16x64 MFMAs (128 k) with
+ *     ONE scale step behind it, and a group of 64 or 32 would need two or four scale steps per K step, on the path
+ *     whose cost is exactly those steps.  The paper measures group 128 only (Sec. 5.1, Table 1), so this is recorded
+ *     as a restriction rather than built.
+ *   - Values the device computes stay on the device: the amplifier found by the heuristic search is written to a
+ *     DEVICE int (alpha_log2_dev), not returned through a host pointer, because returning it would force a
+ *     synchronisation inside the call; read it back when convenient.
  *
  * Canonical layouts
  *   qweight    uint8 [N, K/2]   byte j of row n = q[n,2j] in bits 0-3 | q[n,2j+1] in bits 4-7, two's-complement nibbles

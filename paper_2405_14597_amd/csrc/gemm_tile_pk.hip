@@ -199,13 +199,15 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
         aux_voff = (lane < 32 && mt < m16) ? mt * steps * 64 + (lane & 3) * 16 : (int)0x80000000u;
         aux_step = 64;
     }
-    int x_voff[4], w_voff[4];
+    // (the offsets of the 8 tile loads are a scalar each plus the lane's 16 bytes: kept in scalar registers and added
+    // at the request; the whole offset has to travel in the vector offset, which is what the range check sees)
+    int x_soff[4], w_soff[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int mt = (m0 >> 4) + 2 * wn + (i >> 1);
-        x_voff[i] = mt < m16 ? mt * steps * 2048 + (i & 1) * 1024 + lane * 16 : (int)0x80000000u;
+        x_soff[i] = mt < m16 ? mt * steps * 2048 + (i & 1) * 1024 : (int)0x80000000u;
         const int nt = (n0 >> 4) + 4 * wn + i;
-        w_voff[i] = nt < n16 ? nt * steps * kPkBlockBytes + lane * 16 : (int)0x80000000u;
+        w_soff[i] = nt < n16 ? nt * steps * kPkBlockBytes : (int)0x80000000u;
     }
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
     const unsigned lds_x = wn * 4096, lds_w = kABytes + wn * 4096;
@@ -215,9 +217,9 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
         const unsigned base = lds0 + (t & 1) * kStage;
         if (t < steps) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) load_to_lds_b128(xdesc, base, lds_x + i * 1024, x_voff[i], rq_x);
+            for (int i = 0; i < 4; ++i) load_to_lds_b128(xdesc, base, lds_x + i * 1024, x_soff[i] + rq_x + lane * 16, 0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) load_to_lds_b128(wdesc, base, lds_w + i * 1024, w_voff[i], rq_w);
+            for (int i = 0; i < 4; ++i) load_to_lds_b128(wdesc, base, lds_w + i * 1024, w_soff[i] + rq_w + lane * 16, 0);
             if (wn < 2) load_to_lds_b128(adesc, base, lds_aux, aux_voff, rq_aux);
         }
         rq_x += 2048;

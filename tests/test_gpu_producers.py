@@ -118,3 +118,52 @@ def test_silu_mul_quantize_empty(P):
     gu = torch.empty((0, 256), dtype=torch.float16, device="cuda:0")
     xq, sa = P.is_silu_mul_quantize_act_int8_token(gu)
     assert xq.shape == (0, 128) and sa.shape == (0,)
+
+
+# ---- the same two calls against the plain definitions in double precision (nothing of the oracle, no polynomial):
+# y = x / sqrt(mean(x^2) + eps) * gamma and h = g / (1 + exp(-g)) * u, rounded to fp16, then Appendix A.1 per row.
+def _check_against_plain_definition(h64, xq, sa):
+    """h64: the producer's output in double precision.  The kernel rounds its own single-precision value to fp16, which
+    can differ from fp16(h64) by one fp16 step (relative 2^-10) where h64 sits next to a rounding boundary; that bounds
+    what may differ downstream:
+      token scale: s_a * 127 within one fp16 step of the row's absmax;
+      codes: equal to rint(h64 / s_a) except where that quotient lies within |q| * 2^-10 (+ 1e-4) of a half-integer,
+             and there by one at most."""
+    M, K = h64.shape
+    assert xq.shape == (M, K) and sa.shape == (M,)
+    amax = np.abs(h64).max(axis=1)
+    step16 = np.spacing(amax.astype(np.float16)).astype(np.float64)
+    assert np.all(np.abs(sa.astype(np.float64) * 127.0 - amax) <= step16 * 1.001 + 1e-30)
+    live = sa > 0
+    assert np.all(xq[~live] == 0)
+    q = h64[live] / sa[live].astype(np.float64)[:, None]
+    want = np.clip(np.rint(q), -128, 127)
+    diff = xq[live].astype(np.int64) - want.astype(np.int64)
+    eps = np.abs(q) * 2.0 ** -10 + 1e-4
+    near_half = np.abs(np.abs(q - np.floor(q)) - 0.5) <= eps
+    assert np.all((diff == 0) | (near_half & (np.abs(diff) <= 1)))
+    assert np.count_nonzero(diff) <= 0.02 * diff.size + 4      # and such places are rare
+
+
+@pytest.mark.parametrize("M,K,eps", [(1, 4096, 1e-5), (33, 5120, 1e-5), (5, 8192, 1e-6), (2, 28672, 1e-5),
+                                     (300, 2048, 1e-5), (130, 11008, 1e-2)])
+def test_rmsnorm_quantize_against_plain_double_precision_definition(P, M, K, eps):
+    x = S.activations_outlier(M, K, 300 + K % 89).astype(np.float16)
+    if M > 2:
+        x[1] = 0
+    gamma = _gamma(K, 11)
+    x64, g64 = x.astype(np.float64), gamma.astype(np.float64)
+    y64 = x64 / np.sqrt(np.mean(x64 * x64, axis=1, keepdims=True) + eps) * g64[None, :]
+    xq, sa = P.is_rmsnorm_quantize_act_int8_token(dev(x), dev(gamma), eps)
+    _check_against_plain_definition(y64, host(xq), host(sa))
+
+
+@pytest.mark.parametrize("M,I", [(1, 11008), (16, 11008), (64, 14336), (3, 28672), (300, 2048), (2, 8)])
+def test_silu_mul_quantize_against_plain_double_precision_definition(P, M, I):
+    gu = S.activations_outlier(M, 2 * I, 400 + I % 83).astype(np.float16)
+    if M > 2:
+        gu[1] = 0
+    g64, u64 = gu[:, :I].astype(np.float64), gu[:, I:].astype(np.float64)
+    h64 = g64 / (1.0 + np.exp(-g64)) * u64
+    xq, sa = P.is_silu_mul_quantize_act_int8_token(dev(gu))
+    _check_against_plain_definition(h64, host(xq), host(sa))

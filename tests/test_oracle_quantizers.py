@@ -142,14 +142,33 @@ def test_amplifier_search_cap_and_empty():
     assert O.amplifier_log2(np.zeros(4, dtype=np.float32)) == 0
 
 
-def test_heuristic_amplifier_on_llm_like_weights(golden_dir):
-    """Sec. 4.1 / Fig. 3(b): LLM-scale weights need 9 or 10 shifts; the amplified scales are then all >= 1."""
-    facts = json.load(open(os.path.join(golden_dir, "paper_facts.json")))
-    w = S.weights_gaussian(512, 4096, seed=9)
+@pytest.mark.parametrize("sigma", [0.02, 0.012, 0.008, 0.006, 0.004])
+def test_heuristic_amplifier_is_the_first_power_of_two_that_lifts_every_scale_to_one(sigma):
+    """Sec. 4.1 (the heuristic search of Listing 1), written out here as the plain doubling loop: the amplifier is the
+    first power of two whose product with the smallest group scale reaches 1."""
+    w = S.weights_gaussian(512, 4096, seed=9, sigma=sigma)
     r = O.quantize_weights_int4_group(w, 128, -1, O.SCALE_RAW)
-    assert r.alpha_log2 in facts["typical_bit_shifts"]["value"] or r.alpha_log2 == 8
+    smin = float(r.scale_f32.min())
+    shifts, amp = 0, 1.0
+    while smin * amp < 1.0:
+        amp *= 2.0
+        shifts += 1
+    assert r.alpha_log2 == shifts
     assert r.scale_i32.min() >= 1
-    assert r.alpha_log2 == O.amplifier_log2(r.scale_f32)
+
+
+def test_heuristic_amplifier_on_llm_like_weights(golden_dir):
+    """Sec. 4.1 / Fig. 3(b): the layers of LLaMA-2-7B need 9 or 10 shifts, that is, their smallest group scale lies in
+    [2^-10, 2^-8).  Gaussian weights put it there for a standard deviation of 0.004 to 0.012 (the bulk of an LLM's
+    linear layers); the benchmark recipe's 0.02 has its smallest scale at 2^-7.6 and needs 8, which is why that value
+    is not part of this pin."""
+    facts = json.load(open(os.path.join(golden_dir, "paper_facts.json")))
+    for sigma in (0.012, 0.008, 0.006, 0.004):
+        w = S.weights_gaussian(512, 4096, seed=9, sigma=sigma)
+        r = O.quantize_weights_int4_group(w, 128, -1, O.SCALE_RAW)
+        assert r.alpha_log2 in facts["typical_bit_shifts"]["value"], sigma
+        assert 2.0 ** -10 <= float(r.scale_f32.min()) < 2.0 ** -8
+        assert r.scale_i32.min() >= 1
 
 
 def test_act_quantizer_hand_example():
