@@ -181,8 +181,10 @@ int is_prepack_w4(const void* qweight, const int32_t* scale_i32, const float* sc
  *               across workgroups and the first 64 KB of the workspace are arrival counters: they must be ZERO when a
  *               call starts and every call leaves them zero, so zero the workspace once after allocating it.
  *               M > 64 (the MFMA-bound tiled kernel): the activations re-ordered into MFMA operand blocks
- *               (ceil(M/16) * 16 * K bytes) and one zero-point correction per token row and K step; written by a
- *               preparation kernel of the call, no requirement on the contents.
+ *               (ceil(M/16) * 16 * K bytes) and one zero-point correction per token row and K step, written by a
+ *               preparation kernel of the call; when the last round of output tiles would leave most of the chip idle,
+ *               also partial tiles (up to 64 MB) of a K split of that round, reduced exactly in int32 (the float-scale
+ *               form adds its float partial sums in a fixed order).  No requirement on the contents.
  *               Calls sharing one workspace must not overlap.
  * Covered: M >= 1, N up to 16 * 256 * (compute units) rows when M <= 64, ceil(M/16) * 16 * K below 2^31 beyond
  * (IS_ERR_UNSUPPORTED otherwise).  M = 0 is a no-op.
@@ -203,7 +205,7 @@ int is_gemm_w4a8_floatscale_prepacked(const int8_t* xq, const float* a_scale, co
  * the process ends) and allocates nothing, on the device or through any library.
  *   - Shapes whose is_gemm_prepacked_workspace_bytes(M,N,K,group) exceeds IS_NOALLOC_SCRATCH_BYTES return
  *     IS_ERR_WORKSPACE before anything is enqueued (covered: every M <= 64 shape, and tiled shapes up to about
- *     ceil(M/16) * 16 * K = 31 MiB).
+ *     ceil(M/16) * 16 * K = 31 MiB; the tiled route splits its last round only as far as the rest of the scratch allows).
  *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two threads)
  *     race on it; serialise them or give the overlapping ones the workspace form.
  *   - The first call on a device resolves the array's address (hipGetSymbolAddress); make that call outside a graph

@@ -392,13 +392,13 @@ size_t is_gemm_prepacked_workspace_bytes(int M, int N, int K, int group) {
     if (M < 0 || check_pk_shape(N, K, group) != IS_OK) return 0;
     if (M == 0) return 0;
     if (M <= 64) return pk_decode_workspace_bytes(M, N, K, group);
-    return gemm_tile_pk_workspace_bytes(M, K);  // prepared activations and zero-point corrections
+    return gemm_tile_pk_workspace_bytes(M, N, K);  // prepared activations, corrections, partial tiles of the last round
 }
 
 static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_scale, float* a_scale_out,
                           const void* wpack, const void* spack, const float* chan_scale, int M, int N, int K, int group,
                           int alpha_log2, void* out_fp16, int32_t* acc_out, void* workspace, size_t workspace_bytes,
-                          void* stream, bool int_scale, bool clear_counters = false) {
+                          void* stream, bool int_scale, bool fixed_scratch = false) {
     if (M < 0) return IS_ERR_INVALID_ARG;
     const int shape = check_pk_shape(N, K, group);
     if (shape != IS_OK) return shape;
@@ -408,7 +408,9 @@ static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_s
     PkPlan plan;
     if (M > 0 && M <= 64 && !pk_decode_plan(M, N, K, group, x_fp16 != nullptr, &plan)) return IS_ERR_UNSUPPORTED;
     if (M > 64 && (long long)((M + 15) / 16) * 16 * K >= (1LL << 31)) return IS_ERR_UNSUPPORTED;  // 32-bit offsets
-    const size_t need = is_gemm_prepacked_workspace_bytes(M, N, K, group);
+    // (on the fixed scratch the tiled route takes what it needs at least: the K split of its last round uses what is left)
+    const size_t need = (fixed_scratch && M > 64) ? gemm_tile_pk_min_workspace_bytes(M, K)
+                                                  : is_gemm_prepacked_workspace_bytes(M, N, K, group);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return IS_ERR_WORKSPACE;
     if (!ok_ptr(wpack) || !ok_ptr(spack) || !ok_opt(chan_scale)) return IS_ERR_INVALID_ARG;
     if (M == 0) return IS_OK;
@@ -432,8 +434,9 @@ static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_s
     a.K = K;
     a.group = group;
     a.alpha_log2 = int_scale ? alpha_log2 : 0;
-    if (M > 64) return hip_status(launch_gemm_tile_pk(a, int_scale, workspace, static_cast<hipStream_t>(stream)));
-    if (clear_counters && a.partials != nullptr) {  // a workspace whose last user may not have left the counters zero
+    if (M > 64)
+        return hip_status(launch_gemm_tile_pk(a, int_scale, workspace, workspace_bytes, static_cast<hipStream_t>(stream)));
+    if (fixed_scratch && a.partials != nullptr) {  // a workspace whose last user may not have left the counters zero
         const int n16 = (N + 15) / 16;
         hipLaunchKernelGGL(zero_words_kernel, dim3((n16 + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
                            a.counters, n16);
@@ -464,7 +467,7 @@ int is_gemm_w4a8_intscale_prepacked_noalloc(const int8_t* xq, const float* a_sca
     if (M < 0) return IS_ERR_INVALID_ARG;
     const int shape = check_pk_shape(N, K, group);
     if (shape != IS_OK) return shape;
-    const size_t need = is_gemm_prepacked_workspace_bytes(M, N, K, group);
+    const size_t need = M > 64 ? gemm_tile_pk_min_workspace_bytes(M, K) : is_gemm_prepacked_workspace_bytes(M, N, K, group);
     if (need > (size_t)IS_NOALLOC_SCRATCH_BYTES) return IS_ERR_WORKSPACE;  // beyond the fixed scratch: use the other call
     void* ws = nullptr;
     if (need > 0) {
@@ -475,7 +478,7 @@ int is_gemm_w4a8_intscale_prepacked_noalloc(const int8_t* xq, const float* a_sca
     // (by a kernel, so that the call can be captured into a graph); everything else is written before it is read.
     return gemm_pk_common(xq, nullptr, a_scale, nullptr, qweight_packed, scales_packed, chan_scale, M, N, K, group,
                           alpha_log2, out_fp16, acc_out, ws, need > 0 ? (size_t)IS_NOALLOC_SCRATCH_BYTES : 0, stream, true,
-                          /*clear_counters=*/true);
+                          /*fixed_scratch=*/true);
 }
 
 size_t is_linear_prepacked_workspace_bytes(int M, int N, int K, int group) {

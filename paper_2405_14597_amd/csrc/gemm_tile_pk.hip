@@ -27,6 +27,7 @@
 // correction -8 * sum_k x[m,k] per (token row, K step), computed once by the preparation kernel, enters each MFMA
 // chain as its initial accumulator, so the chain returns P exactly and the scale step costs one instruction per element.
 #include <stdio.h>
+#include <stdlib.h>
 
 #include "act_common.h"
 #include "pk_common.h"
@@ -43,6 +44,24 @@ constexpr int kABytes = kTM * 128, kBBytes = kTN * 64, kScBytes = kTN * 4, kC0By
 constexpr int kStage = kABytes + kBBytes + kScBytes + kC0Bytes;  // 34816
 constexpr int kXcdCount = 8;            // workgroup i is dispatched to XCD i % 8
 constexpr int kGroupRows = 8;           // tile rows of the block of tiles an XCD works on at a time
+
+// The last, partial round of tiles.  With two workgroups per compute unit the chip works on `slots` tiles at a time;
+// when the tiles % slots left for the last round are fewer than half the compute units, most of the chip would idle
+// for a whole tile time.  Their K range is then cut into `parts`, one workgroup each: it stores its accumulators (exact int32, or the float
+// partial sums) as a partial tile in the workspace, and the last of a tile's parts to arrive adds them up in part
+// order and runs the epilogue (same protocol as the K split of the decode kernel: device-scope stores, one counter
+// per tile, which the last arriver sets back to zero).
+struct TileSplit {
+    int whole;           // tiles computed over all of K by one workgroup: workgroups [0, whole)
+    int rem;             // tiles of the last round: workgroup whole + p works on part p / rem of tile whole + p % rem
+    int parts;           // K parts per such tile (1: rem = 0)
+    int32_t* counters;   // [rem], zero when the kernel starts
+    int32_t* partials;   // [rem][parts][kPartWords]
+};
+constexpr int kPartWords = kTM * kTN;                      // one partial tile: 128 KB
+constexpr size_t kCounterBytes = 2048;                     // up to 512 tiles in the last round
+constexpr size_t kPartialCap = (size_t)64 << 20;           // at most this much workspace for partial tiles
+constexpr int kMinPartSteps = 8;                           // K steps a part has at least
 
 // ---- preparation of the activations: 2 KB blocks [16-row tile][K step] = [MFMA half h][k chunk kb][row r][16 codes],
 // the 16 codes of (h, kb) being k = 128 s + 64 h + 16 kb .. + 15 of row 16 mt + r, and the zero-point corrections
@@ -72,7 +91,10 @@ constexpr int kPrepSteps = 4;  // K steps per wave of the int8 preparation (8 lo
 
 // Quantised activations in: grid (16-row tiles, K steps / (4 waves * kPrepSteps)).
 __global__ __launch_bounds__(256) void prepare_activations_pk_kernel(const int8_t* __restrict__ xq, int M, int K,
-                                                                     int8_t* __restrict__ xp, int32_t* __restrict__ c0) {
+                                                                     int8_t* __restrict__ xp, int32_t* __restrict__ c0,
+                                                                     int32_t* __restrict__ counters, int ncounters) {
+    if (blockIdx.x == 0 && blockIdx.y == 0)  // the tiled kernel's arrival counters start at zero
+        for (int i = threadIdx.x; i < ncounters; i += 256) counters[i] = 0;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int r = lane & 15, kb = lane >> 4;
     const int mt = blockIdx.x, m = 16 * mt + r;
@@ -117,7 +139,11 @@ __global__ __launch_bounds__(256) void token_scales_kernel(const __half* __restr
 __global__ __launch_bounds__(256) void quantize_prepare_activations_pk_kernel(const __half* __restrict__ x, int M, int K,
                                                                               const float* __restrict__ a_scale,
                                                                               int8_t* __restrict__ xp,
-                                                                              int32_t* __restrict__ c0) {
+                                                                              int32_t* __restrict__ c0,
+                                                                              int32_t* __restrict__ counters,
+                                                                              int ncounters) {
+    if (blockIdx.x == 0 && blockIdx.y == 0)  // the tiled kernel's arrival counters start at zero
+        for (int i = threadIdx.x; i < ncounters; i += 256) counters[i] = 0;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int r = lane & 15, kb = lane >> 4;
     const int mt = blockIdx.x, m = 16 * mt + r;
@@ -153,7 +179,7 @@ typedef float v4f_t __attribute__((ext_vector_type(4)));
 // One output tile.  WIDE: 32-bit multiplies in the integer scale step (some scale does not fit 24 signed bits).
 template <bool INT_SCALE, bool WIDE>
 __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restrict__ xp, const int32_t* __restrict__ c0,
-                                        unsigned char* smem) {
+                                        const TileSplit& sp, unsigned char* smem) {
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wn = __builtin_amdgcn_readfirstlane(tid / kWave);  // the wave's 64 weight rows of the tile's 256
@@ -164,11 +190,19 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
     const int tiles_n = (a.N + kTN - 1) / kTN;
     const int tiles_m = (a.M + kTM - 1) / kTM;
     int tile_m, tile_n;
+    int part = 0, tail_tile = -1;  // a tile of the last round: which K part, which of the round's tiles
     {
-        const int total = tiles_m * tiles_n;
-        const int q = total / kXcdCount, rem = total - q * kXcdCount;
-        const int xcd = blockIdx.x % kXcdCount, idx = blockIdx.x / kXcdCount;
-        const int lid = xcd * q + min(xcd, rem) + idx;
+        int lid;
+        if ((int)blockIdx.x < sp.whole) {
+            const int q = sp.whole / kXcdCount, rem = sp.whole - q * kXcdCount;
+            const int xcd = blockIdx.x % kXcdCount, idx = blockIdx.x / kXcdCount;
+            lid = xcd * q + min(xcd, rem) + idx;
+        } else {
+            const int pidx = blockIdx.x - sp.whole;
+            part = pidx / sp.rem;
+            tail_tile = pidx - part * sp.rem;
+            lid = sp.whole + tail_tile;
+        }
         const int gsz = kGroupRows * tiles_n;
         const int g = lid / gsz, r = lid - g * gsz;
         const int gm = min(kGroupRows, tiles_m - g * kGroupRows);
@@ -179,6 +213,9 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
     const int steps = a.K >> 7;
     const int NG = a.K / a.group;
     const int spg = a.group >> 7;
+    // this workgroup's K steps
+    const int s_begin = tail_tile < 0 ? 0 : (part * steps) / sp.parts;
+    const int s_end = tail_tile < 0 ? steps : ((part + 1) * steps) / sp.parts;
     const int m16 = (a.M + 15) >> 4, n16 = (a.N + 15) >> 4;
 
     // ---- loader roles.  Per step and wave: the 2 KB blocks of two 16-row token tiles (4 loads of 1 KB), the 1 KB
@@ -212,10 +249,12 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
     const unsigned lds_x = wn * 4096, lds_w = kABytes + wn * 4096;
     const unsigned lds_aux = kABytes + kBBytes + (wn == 1 ? kScBytes : 0);
-    int rq_x = 0, rq_w = 0, rq_aux = 0, rq_sub = 0;
+    const int g_begin = s_begin / spg;
+    int rq_x = s_begin * 2048, rq_w = s_begin * kPkBlockBytes, rq_sub = s_begin - g_begin * spg;
+    int rq_aux = s_begin * aux_step + g_begin * aux_group;
     auto request_step = [&](int t) {
         const unsigned base = lds0 + (t & 1) * kStage;
-        if (t < steps) {
+        if (t < s_end) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) load_to_lds_b128(xdesc, base, lds_x + i * 1024, x_soff[i] + rq_x + lane * 16, 0);
 #pragma unroll
@@ -258,8 +297,8 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
         }
     };
 
-    request_step(0);
-    for (int s = 0; s < steps; ++s) {
+    request_step(s_begin);
+    for (int s = s_begin; s < s_end; ++s) {
         // this wave's requests for step s have landed; past the barrier so have everybody's, and everybody has
         // finished reading the other stage, which the requests for step s + 1 now overwrite
         asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
@@ -311,6 +350,75 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
 
     // ---- epilogue, once per output: FLOAT(acc) * s_a[m] * c[n] / alpha (Eq. (2)), or facc * s_a[m] (Eq. (1))
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");  // nobody reads operand tiles any more
+    if (tail_tile >= 0) {
+        // a K part of a tile of the last round: through the workspace; partial tile = [sub-tile i][j][thread][4],
+        // written and read 16 bytes per lane with device-scope accesses (they go past the L2 of the writer's or
+        // reader's own XCD, so that no cache has to be written back or invalidated as a whole)
+        v4i* mine = reinterpret_cast<v4i*>(sp.partials + ((size_t)tail_tile * sp.parts + part) * kPartWords) + tid;
+#pragma unroll
+        for (int i = 0; i < kMS; ++i)
+#pragma unroll
+            for (int j = 0; j < kNS; ++j) {
+                v4i bits4;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if constexpr (INT_SCALE) bits4[r] = acc[i][j][r];
+                    else bits4[r] = __float_as_int(acc[i][j][r]);
+                }
+                asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(mine + (i * kNS + j) * kTThreads), "v"(bits4)
+                             : "memory");
+            }
+        // every wave's partial sums have been written through before the tile's counter is raised
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        int* flag = reinterpret_cast<int*>(smem);
+        if (tid == 0)
+            *flag = __hip_atomic_fetch_add(sp.counters + tail_tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const int arrived = *flag;
+        __syncthreads();  // (the flag's place is the output tile's below)
+        if (arrived != sp.parts - 1) return;
+        // the last part to arrive: all parts are in the workspace; add them in part order, whoever came last
+#pragma unroll
+        for (int i = 0; i < kMS; ++i)
+#pragma unroll
+            for (int j = 0; j < kNS; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[i][j][r] = 0;
+        for (int q = 0; q < sp.parts; ++q) {
+            const v4i* src = reinterpret_cast<const v4i*>(sp.partials + ((size_t)tail_tile * sp.parts + q) * kPartWords) + tid;
+#pragma unroll
+            for (int i = 0; i < kMS; i += 4) {  // 16 loads of 16 bytes in flight per lane (the operand registers are free now)
+                v4i got[4][kNS];
+#pragma unroll
+                for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+                    for (int j = 0; j < kNS; ++j)
+                        asm volatile("global_load_dwordx4 %0, %1, off sc1"
+                                     : "=v"(got[ii][j])
+                                     : "v"(src + ((i + ii) * kNS + j) * kTThreads)
+                                     : "memory");
+                // (the results pass through the wait, so that nothing is scheduled to use them before it)
+                asm volatile("s_waitcnt vmcnt(0)"
+                             : "+v"(got[0][0]), "+v"(got[0][1]), "+v"(got[0][2]), "+v"(got[0][3]), "+v"(got[1][0]),
+                               "+v"(got[1][1]), "+v"(got[1][2]), "+v"(got[1][3]), "+v"(got[2][0]), "+v"(got[2][1]),
+                               "+v"(got[2][2]), "+v"(got[2][3]), "+v"(got[3][0]), "+v"(got[3][1]), "+v"(got[3][2]),
+                               "+v"(got[3][3])
+                             :
+                             : "memory");
+#pragma unroll
+                for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+                    for (int j = 0; j < kNS; ++j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            if constexpr (INT_SCALE) acc[i + ii][j][r] += got[ii][j][r];
+                            else acc[i + ii][j][r] += __int_as_float(got[ii][j][r]);
+                        }
+            }
+        }
+        if (tid == 0) __hip_atomic_store(sp.counters + tail_tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     const float inv_alpha = __int_as_float((127 - a.alpha_log2) << 23);
     const int m_rows = min(kTM, a.M - m0), n_rows = min(kTN, a.N - n0);
     // Rows of 8-aligned length go through an fp16 copy of the tile in LDS and leave as 16-byte stores; otherwise (and
@@ -373,24 +481,56 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
 // scale step reads them; with a whole SIMD to itself the compiler would put them into accumulation registers and copy)
 template <bool INT_SCALE>
 __global__ __launch_bounds__(kTThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_tile_pk_kernel(PkArgs a, const int8_t* __restrict__ xp,
-                                                                 const int32_t* __restrict__ c0) {
+                                                                 const int32_t* __restrict__ c0, TileSplit sp) {
     extern __shared__ __align__(16) unsigned char smem_tpk[];
     if constexpr (INT_SCALE) {
         const int flags = *reinterpret_cast<const int32_t*>(a.spack);
-        if (flags & kPkFlagWide) tile_pk<true, true>(a, xp, c0, smem_tpk);
-        else tile_pk<true, false>(a, xp, c0, smem_tpk);
+        if (flags & kPkFlagWide) tile_pk<true, true>(a, xp, c0, sp, smem_tpk);
+        else tile_pk<true, false>(a, xp, c0, sp, smem_tpk);
     } else {
-        tile_pk<false, false>(a, xp, c0, smem_tpk);
+        tile_pk<false, false>(a, xp, c0, sp, smem_tpk);
     }
 }
 
 size_t xp_bytes(int M, int K) { return pad256((size_t)((M + 15) / 16) * 16 * K); }
 size_t c0_bytes(int M, int K) { return pad256((size_t)((M + 15) / 16) * (K / 128) * 64); }
 
+// The split of the last round, given `avail` bytes for partial tiles (0: no split).
+void plan_tail(int M, int N, int K, size_t avail, int* whole, int* rem, int* parts) {
+    const int tiles = ((N + kTN - 1) / kTN) * ((M + kTM - 1) / kTM);
+    const int steps = K >> 7;
+    const int slots = min(2 * cu_count(), (int)(kCounterBytes / 4));
+    const int left = tiles % slots;
+    int p = 1;
+    if (left > 0) {
+        // up to one workgroup per compute unit: a workgroup that has its compute unit to itself runs at about 1.7 times
+        // the rate of one that shares it, so filling both places of a unit with half-length parts gains nothing
+        p = min(min((slots / 2) / left, 8), steps / kMinPartSteps);
+        if (const char* e = getenv("INTSCALE_TILE_PARTS")) p = min(p, max(1, atoi(e)));  // experiments: at most this many
+        p = (int)min((size_t)p, min(avail, kPartialCap) / ((size_t)left * kPartWords * 4));
+    }
+    if (p < 2) {
+        *whole = tiles;
+        *rem = 0;
+        *parts = 1;
+    } else {
+        *whole = tiles - left;
+        *rem = left;
+        *parts = p;
+    }
+}
+
 }  // namespace
 
-// workspace = [prepared activations: ceil(M/16) x K/128 blocks of 2 KB | corrections: ceil(M/16) x K/128 x 16 words]
-size_t gemm_tile_pk_workspace_bytes(int M, int K) { return xp_bytes(M, K) + c0_bytes(M, K); }
+// workspace = [prepared activations: ceil(M/16) x K/128 blocks of 2 KB | corrections: ceil(M/16) x K/128 x 16 words |
+//              arrival counters of the last round's tiles | their partial tiles]; the launch splits the last round as
+//              far as the bytes it is given allow, and not at all below gemm_tile_pk_min_workspace_bytes + one round
+size_t gemm_tile_pk_min_workspace_bytes(int M, int K) { return xp_bytes(M, K) + c0_bytes(M, K) + kCounterBytes; }
+size_t gemm_tile_pk_workspace_bytes(int M, int N, int K) {
+    int whole, rem, parts;
+    plan_tail(M, N, K, kPartialCap, &whole, &rem, &parts);
+    return gemm_tile_pk_min_workspace_bytes(M, K) + (size_t)rem * parts * kPartWords * 4;
+}
 
 bool gemm_tile_pk_takes_fp16(int K) { return (K & 127) == 0; }
 
@@ -401,24 +541,32 @@ void gemm_tile_pk_kernel_names(int K, bool int_scale, bool fp16_in, char* buf, s
     snprintf(buf, len, "%s\ngemm_tile_pk_kernel<%s>", prep, int_scale ? "true" : "false");
 }
 
-hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace, hipStream_t stream) {
+hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace, size_t workspace_bytes,
+                               hipStream_t stream) {
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     int8_t* xp = reinterpret_cast<int8_t*>(ws);
     int32_t* c0 = reinterpret_cast<int32_t*>(ws + xp_bytes(a.M, a.K));
+    const size_t fixed = gemm_tile_pk_min_workspace_bytes(a.M, a.K);
+    if (workspace_bytes < fixed) return hipErrorInvalidValue;
+    TileSplit sp;
+    plan_tail(a.M, a.N, a.K, workspace_bytes - fixed, &sp.whole, &sp.rem, &sp.parts);
+    sp.counters = reinterpret_cast<int32_t*>(ws + fixed - kCounterBytes);
+    sp.partials = reinterpret_cast<int32_t*>(ws + fixed);
     const int mtiles = (a.M + 15) / 16;
     const int per_wg = 4 * kPrepSteps;
     const dim3 blocks(mtiles, ((a.K >> 7) + per_wg - 1) / per_wg);
     if (a.x_fp16) {  // fp16 activations: quantised on the way, the token scales go to a.a_scale_out (= a.a_scale)
         hipLaunchKernelGGL(token_scales_kernel, dim3(a.M), dim3(256), 0, stream, a.x_fp16, a.M, a.K, a.a_scale_out);
         hipLaunchKernelGGL(quantize_prepare_activations_pk_kernel, blocks, dim3(256), 0, stream, a.x_fp16, a.M, a.K,
-                           a.a_scale_out, xp, c0);
+                           a.a_scale_out, xp, c0, sp.counters, sp.rem);
     } else {
-        hipLaunchKernelGGL(prepare_activations_pk_kernel, blocks, dim3(256), 0, stream, a.xq, a.M, a.K, xp, c0);
+        hipLaunchKernelGGL(prepare_activations_pk_kernel, blocks, dim3(256), 0, stream, a.xq, a.M, a.K, xp, c0,
+                           sp.counters, sp.rem);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t smem = 2 * (size_t)kStage;
-    const int tiles = ((a.N + kTN - 1) / kTN) * ((a.M + kTM - 1) / kTM);
+    const int tiles = sp.whole + sp.rem * sp.parts;  // workgroups
     int device = -1;
     (void)hipGetDevice(&device);
     static bool raised[2][64] = {};
@@ -431,11 +579,11 @@ hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace,
     if (int_scale) {
         e = raise(reinterpret_cast<const void*>(gemm_tile_pk_kernel<true>), 0);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(gemm_tile_pk_kernel<true>, dim3(tiles), dim3(kTThreads), smem, stream, a, xp, c0);
+        hipLaunchKernelGGL(gemm_tile_pk_kernel<true>, dim3(tiles), dim3(kTThreads), smem, stream, a, xp, c0, sp);
     } else {
         e = raise(reinterpret_cast<const void*>(gemm_tile_pk_kernel<false>), 1);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(gemm_tile_pk_kernel<false>, dim3(tiles), dim3(kTThreads), smem, stream, a, xp, c0);
+        hipLaunchKernelGGL(gemm_tile_pk_kernel<false>, dim3(tiles), dim3(kTThreads), smem, stream, a, xp, c0, sp);
     }
     return hipGetLastError();
 }

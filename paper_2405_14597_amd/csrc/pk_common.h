@@ -70,9 +70,11 @@ hipError_t launch_gemm_decode_pk(const PkArgs& a, bool int_scale, hipStream_t st
 void pk_decode_kernel_name(const PkPlan& plan, bool int_scale, bool fp16_in, char* buf, size_t len);
 // MFMA-bound tiled kernel on the prepacked layout (more than 64 token rows); x_fp16 set: a.a_scale_out (= a.a_scale)
 // receives the token scales.
-size_t gemm_tile_pk_workspace_bytes(int M, int K);
+size_t gemm_tile_pk_workspace_bytes(int M, int N, int K);   // what the launch makes full use of
+size_t gemm_tile_pk_min_workspace_bytes(int M, int K);      // what it needs at least (then without the K split of the last round)
 bool gemm_tile_pk_takes_fp16(int K);
-hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace, hipStream_t stream);
+hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace, size_t workspace_bytes,
+                               hipStream_t stream);
 // The kernels launch_gemm_tile_pk runs, in order, as a kernel trace names them, separated by '\n'.
 void gemm_tile_pk_kernel_names(int K, bool int_scale, bool fp16_in, char* buf, size_t len);
 

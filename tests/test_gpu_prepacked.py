@@ -234,9 +234,11 @@ def test_prepacked_tiled_gemm(P, M, N, K):
     check_fs(host(out_fs), fs, f"M{M} N{N} K{K}")
 
 
-@pytest.mark.parametrize("M,N,K,group", [(200, 300, 1024, 128), (129, 520, 2048, 256), (130, 80, 1536, 1536)])
+@pytest.mark.parametrize("M,N,K,group", [(200, 300, 1024, 128), (129, 520, 2048, 256), (130, 80, 1536, 1536),
+                                         (129, 300, 6144, 384)])
 def test_prepacked_tiled_wide_scales_and_groups(P, M, N, K, group):
-    """Scales beyond 24 bits (the 32-bit multiply instance, bit-exact modulo 2^32), groups of several K steps."""
+    """Scales beyond 24 bits (the 32-bit multiply instance, bit-exact modulo 2^32), groups of several K steps (the last:
+    K parts of the last round's tiles that begin inside a group)."""
     rng = np.random.default_rng(77 + M)
     xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
     q = rng.integers(-8, 8, size=(N, K)).astype(np.int8)
@@ -252,11 +254,32 @@ def test_prepacked_tiled_wide_scales_and_groups(P, M, N, K, group):
         check_out(host(out), ref.out)
 
 
+def test_prepacked_tiled_workspace_contents_do_not_matter(P):
+    """The tiled route writes what it reads of its workspace (its preparation kernel also clears the arrival counters
+    of the K split of the last round): a workspace full of ones, used twice, gives the same bits."""
+    M, N, K = 300, 520, 4096
+    assert P.is_gemm_prepacked_workspace_bytes(M, N, K, G) > (M + 15) // 16 * 16 * K + 2 ** 20   # partial tiles in it
+    rng = np.random.default_rng(4100)
+    xq, qw, IS, s, sa, c = rand_quantised(rng, M, N, K)
+    ref = O.gemm_w4a8_intscale(xq, sa, qw, IS, c, G, 10)
+    pk = P.is_prepack_w4(dev(qw), dev(IS), G)
+    ws = torch.full((P.is_gemm_prepacked_workspace_bytes(M, N, K, G),), 0xFF, dtype=torch.uint8, device="cuda:0")
+    for _ in range(2):
+        out, acc = P.is_gemm_w4a8_intscale_prepacked(dev(xq), dev(sa), pk, dev(c), 10, want_acc=True, workspace=ws)
+        assert np.array_equal(host(acc), ref.acc), "int32 accumulators differ"
+        check_out(host(out), ref.out)
+    pkf = P.is_prepack_w4(dev(qw), dev(s), G)
+    a = P.is_gemm_w4a8_floatscale_prepacked(dev(xq), dev(sa), pkf, workspace=ws)
+    b = P.is_gemm_w4a8_floatscale_prepacked(dev(xq), dev(sa), pkf, workspace=ws)
+    assert torch.equal(a, b)          # float partial sums are added in part order, whoever arrives last
+    check_fs(host(a), O.gemm_w4a8_floatscale(xq, sa, qw, s, G))
+
+
 @pytest.mark.parametrize("M,N,K", [(130, 512, 4096), (70, 272, 8192), (200, 256, 14336), (66, 128, 28672), (257, 40, 2048),
                                    (70, 48, 40960)])
 def test_prepacked_tiled_linear_fp16(P, M, N, K):
-    """More than 64 fp16 tokens: the tiled kernel's preparation quantises on the way (1, 2, 4, 8 chunks per lane), and
-    rows too long for that (quantiser kernel first)."""
+    """More than 64 fp16 tokens: the tiled kernel's preparation quantises on the way (token scales, then rounding on the
+    block grid)."""
     rng = np.random.default_rng(7600 + M + N + K)
     _, qw, IS, s, _, c = rand_quantised(rng, 1, N, K)
     x = S.activations_student_t(M, K, 78 + K % 13)
