@@ -19,9 +19,8 @@ GEMM call alone (Eq. (1), built the same way) with their ratio, the time a plain
 takes, and the roofline fractions; `alpha_sweep` shows the accuracy / overflow trade-off of the amplifier on one layer.
 
 `--workload llama2_7b` (M in {1, 16, 64}) and `--workload llama3_8b` (M = 4096, Student-t activations) run the same
-code on those shapes; `decode_canonical`, `prefill_canonical`, `moe`, `w8a8` and `producers` measure the calls that
-take the canonical layouts (per-call layout, no offline pass), the mixture-of-experts form, fine-grained W8A8 and the
-fused activation producers.
+code on those shapes; `moe`, `w8a8` and `producers` measure the mixture-of-experts form, fine-grained W8A8 and the
+fused activation producers (calls that take the canonical layouts).
 """
 from __future__ import annotations
 
@@ -52,17 +51,14 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-floatscale", action="store_true", help="skip the float-scale comparison pass")
     ap.add_argument("--coarse", action="store_true",
-                    help="prefill workload: coarse-grained weights, one group per weight row (the paper's upper bound)")
-    ap.add_argument("--no-fused-token", action="store_true",
-                    help="M = 1: quantiser kernel + GEMM kernel instead of the one-kernel linear call")
+                    help="model-family workloads: coarse-grained weights, one group per weight row (the paper's upper "
+                         "bound for the fine-grained kernels, Table 2 / Fig. 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
-    ap.add_argument("--cpu-sample-layers", type=int, default=32)
     ap.add_argument("--no-traffic", action="store_true",
                     help="do not look up the measured HBM traffic in profiles/ (roofline.traffic = null); without this "
                          "flag a missing figure is an error")
     ap.add_argument("--workload", default="llama2_70b",
-                    choices=("llama2_70b", "llama2_7b", "llama3_8b", "decode_canonical", "prefill_canonical", "moe",
-                             "w8a8", "producers"))
+                    choices=("llama2_70b", "llama2_7b", "llama3_8b", "moe", "w8a8", "producers"))
     return ap.parse_args()
 
 
@@ -153,285 +149,12 @@ def main():
         return family_main(args)
     if args.layers is None:
         args.layers = 32
-    if args.workload == "prefill_canonical":
-        return prefill_main(args)
     if args.workload == "w8a8":
         return w8a8_main(args)
     if args.workload == "moe":
         return moe_main(args)
-    if args.workload == "producers":
-        return producers_main(args)
+    return producers_main(args)
 
-    import numpy as np
-    import torch
-
-    import paper_2405_14597_amd as P
-    import synth_inputs as S
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    P.load_library()
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    L = args.layers
-    use_graph = not args.no_graph
-
-    # ---------------------------------------------------------------- data: one layer drawn on the host, quantised on
-    # the GPU by the library, then copied into L distinct buffers (timing does not depend on the values).
-    linears = list(S.LLAMA2_7B.items())        # name -> (K, N)
-    weights = {}
-    for idx, (name, (K, N)) in enumerate(linears):
-        w = torch.from_numpy(S.make_weights(1, N, K, S.seed_for(1, idx, 1))).to(dev)
-        qw = P.is_quantize_weights_int4_group(w, GROUP, ALPHA_LOG2, P.IS_SCALE_NORM)
-        del w
-        weights[name] = dict(
-            q=qw.qweight.unsqueeze(0).repeat(L, 1, 1),
-            si=qw.scale_i32.unsqueeze(0).repeat(L, 1, 1),
-            sf=qw.scale_f32.unsqueeze(0).repeat(L, 1, 1),
-            c=qw.chan_scale.unsqueeze(0).repeat(L, 1),
-        )
-    acts = {}
-    for M in BATCHES:
-        for idx, (name, (K, N)) in enumerate(linears):
-            x = torch.from_numpy(S.make_activations(1, M, K, S.seed_for(1, idx, 2) + M)).to(dev)
-            acts[(M, name)] = dict(
-                x=x, xq=torch.empty((M, K), dtype=torch.int8, device=dev),
-                sa=torch.empty((M,), dtype=torch.float32, device=dev),
-                out=torch.empty((M, N), dtype=torch.float16, device=dev))
-    torch.cuda.synchronize()
-
-    def kernel_name(M, K, int_scale, fused=False):
-        """Name of the kernel instantiation the library picks for this shape (mirrors its dispatch; used to match the
-        per-kernel figures here with a rocprofv3 kernel trace)."""
-        tag = "true" if int_scale else "false"
-        ng = K // GROUP
-        spg = GROUP // 128
-        mt = 1 if M <= 16 else 2 if M <= 32 else 4
-        xs16 = -(-ng // 16) * spg
-        waves = 16 if (mt == 1 or (mt == 2 and xs16 <= 2)) else 8
-        xs = -(-ng // waves) * spg
-        fits = xs <= ((10 if M == 1 else 6) if mt == 1 else (2 if waves == 16 else 8) if mt == 2 else 4)
-        if M <= 64 and waves <= ng and fits:
-            lds_operands = False
-            if mt == 1:
-                lds_operands = xs > 6             # one token, long K: operands read from LDS
-                xs_t, dt = (2, 4) if xs <= 2 else (4, 2) if xs <= 4 else (6, 1) if xs <= 6 else (10, 1)
-            elif mt == 2:
-                xs_t, dt = (2, 4) if waves == 16 else (8, 1)
-            else:
-                xs_t, dt = 4, 1
-            return (f"gemm_decode_kernel<{mt}, {xs_t}, {dt}, {waves}, {tag}, {'true' if fused else 'false'}, "
-                    f"{'true' if lds_operands else 'false'}>")
-        mt = 1 if M <= 16 else 2 if M <= 32 else 3 if M <= 48 else 4
-        return f"gemm_skinny_kernel<{mt}, ...>"
-
-    # ---------------------------------------------------------------- segments of one step
-    safe_ws = {}
-    lin_ws = {}
-
-    def make_segments(int_scale: bool, with_quant: bool, safe: bool = False, hot: bool = False):
-        """hot: every launch reads the first layer's weights (they stay in the 256 MB Infinity Cache / L2)."""
-        segs = []
-        for M in BATCHES:
-            for name, (K, N) in linears:
-                a, w = acts[(M, name)], weights[name]
-                if with_quant and M == 1 and int_scale and not safe and not args.no_fused_token:
-                    # one token: the linear call (fp16 in), whose decode kernel quantises the token itself
-                    kname = kernel_name(M, K, True, fused=True)
-                    if kname.startswith("gemm_decode_kernel"):
-                        if (M, name) not in lin_ws:
-                            lin_ws[(M, name)] = torch.empty(P.is_linear_workspace_bytes(M, N, K, GROUP),
-                                                            dtype=torch.uint8, device=dev)
-
-                        def fl(a=a, w=w, ws=lin_ws[(M, name)]):
-                            for l in range(L):
-                                P.is_linear_w4a8_intscale(a["x"], w["q"][l], w["si"][l], w["c"][l], GROUP, ALPHA_LOG2,
-                                                          out=a["out"], workspace=ws)
-                        # fp16 token in instead of int8 codes and their scale
-                        nbytes = S.algorithmic_bytes(M, N, K, GROUP) + M * K - 4 * M
-                        segs.append(Segment(f"linear_{name}_M{M}", kname, L, L * nbytes, L * S.algorithmic_ops(M, N, K),
-                                            fl, use_graph, torch))
-                        continue
-                if with_quant:
-                    def fq(a=a):
-                        for _ in range(L):
-                            P.is_quantize_act_int8_token(a["x"], a["xq"], a["sa"])
-                    segs.append(Segment(f"quant_{name}_M{M}", "quantize_act_kernel", L, L * (3 * M * K + 4 * M), 0, fq,
-                                        use_graph, torch))
-                if safe:
-                    key = (M, name)
-                    if key not in safe_ws:
-                        safe_ws[key] = torch.empty(P.is_gemm_safe_workspace_bytes(M, N, K, GROUP), dtype=torch.uint8,
-                                                   device=dev)
-
-                    def fg(a=a, w=w, ws=safe_ws[key]):
-                        for l in range(L):
-                            P.is_gemm_w4a8_intscale_safe(a["xq"], a["sa"], w["q"][l], w["si"][l], w["c"][l], GROUP,
-                                                         ALPHA_LOG2, out=a["out"], workspace=ws)
-                elif int_scale:
-                    def fg(a=a, w=w):
-                        for l in range(L):
-                            l = 0 if hot else l
-                            P.is_gemm_w4a8_intscale(a["xq"], a["sa"], w["q"][l], w["si"][l], w["c"][l], GROUP,
-                                                    ALPHA_LOG2, out=a["out"])
-                else:
-                    def fg(a=a, w=w):
-                        for l in range(L):
-                            P.is_gemm_w4a8_floatscale(a["xq"], a["sa"], w["q"][l], w["sf"][l], GROUP, out=a["out"])
-                kname = kernel_name(M, K, int_scale)
-                segs.append(Segment(f"gemm_{name}_M{M}", kname, L, L * S.algorithmic_bytes(M, N, K, GROUP),
-                                    L * S.algorithmic_ops(M, N, K), fg, use_graph, torch))
-        return segs
-
-    def run_steps(segs, n, timed):
-        for _ in range(n):
-            ev = torch.cuda.Event(enable_timing=True)
-            ev.record()
-            for s in segs:
-                s.run()
-                nxt = torch.cuda.Event(enable_timing=True)
-                nxt.record()
-                if timed:
-                    s.pending.append((ev, nxt))
-                ev = nxt
-
-    def timed_pass(segs, steps, warmup):
-        run_steps(segs, warmup, False)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        run_steps(segs, steps, True)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        for s in segs:
-            s.elapsed_ms = sum(a.elapsed_time(b) for a, b in s.pending)
-            s.count = len(s.pending) * s.launches
-            s.pending = []
-        return (t1 - t0) / steps
-
-    segs = make_segments(int_scale=True, with_quant=True)
-    sec_per_step = timed_pass(segs, args.steps, args.warmup)
-    step_bytes = sum(s.alg_bytes for s in segs)
-    step_ops = sum(s.ops for s in segs)
-
-    shapes = []
-    for s in segs:
-        us = 1e3 * s.elapsed_ms / max(s.count, 1)
-        per_launch_bytes = s.alg_bytes / s.launches
-        shapes.append(dict(name=s.name, kernel=s.kernel, us=round(us, 3), gbs=round(per_launch_bytes / us / 1e3, 1),
-                           tops=round(s.ops / s.launches / us / 1e6, 3),
-                           hbm_frac=round(per_launch_bytes / us / 1e3 / HBM_PEAK_GBS, 4)))
-
-    # dominant kernel = the instantiation with the most time inside the timed region
-    by_kernel = {}
-    for s in segs:
-        k = by_kernel.setdefault(s.kernel, dict(ms=0.0, launches=0, bytes=0.0))
-        k["ms"] += s.elapsed_ms
-        k["launches"] += s.count
-        k["bytes"] += s.alg_bytes * (s.count / s.launches)
-    dom_name, dom = max(by_kernel.items(), key=lambda kv: kv[1]["ms"])
-    dom_us = 1e3 * dom["ms"] / dom["launches"]
-    dom_bytes = dom["bytes"] / dom["launches"]
-    achieved = dom_bytes / dom_us / 1e3
-    roofline = dict(bound="hbm", kernel=dom_name, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=measured_traffic(dom_name, "llama2_7b_decode"),
-                    avg_launch_us=round(dom_us, 3), alg_bytes_per_launch=round(dom_bytes))
-    peaks = measured_peaks(P, torch)
-    roofline["frac_of_measured_peak"] = round(achieved / peaks["hbm_read_gbs"], 4)
-
-    # ---------------------------------------------------------------- float-scale comparison (GEMM launches only)
-    speedup = None
-    fs_detail = None
-    overflow = None
-    hot_detail = None
-    if not args.no_floatscale:
-        is_g = make_segments(int_scale=True, with_quant=False)
-        fs_g = make_segments(int_scale=False, with_quant=False)
-        n = max(3, args.steps // 2)
-        t_is = timed_pass(is_g, n, 2)
-        t_fs = timed_pass(fs_g, n, 2)
-        speedup = t_fs / t_is
-        fs_detail = {a.name: round(b.elapsed_ms / max(a.elapsed_ms, 1e-9), 4) for a, b in zip(is_g, fs_g)}
-        # the overflow-safe form (integer scales, amplifier taken out per group) and each layer's worst-case bound
-        safe_g = make_segments(int_scale=True, with_quant=False, safe=True)
-        timed_pass(safe_g, n, 2)
-        overflow = dict(
-            safe_over_intscale_by_shape={a.name: round(b.elapsed_ms / max(a.elapsed_ms, 1e-9), 4)
-                                         for a, b in zip(is_g, safe_g)},
-            worst_case_bound_log2={name: round(float(np.log2(max(1, int(
-                P.is_intscale_overflow_bound(weights[name]["si"][0], GROUP).cpu()[0])))), 2) for name, _ in linears},
-            note="bound = max_n sum_g |IS| * G * 1024; a layer cannot overflow int32 iff it is below 31")
-        # hot-cache figure: the same weights at every launch (cache-resident), for contrast with the cold stream above
-        hot_g = make_segments(int_scale=True, with_quant=False, hot=True)
-        timed_pass(hot_g, n, 2)
-        hot_detail = {a.name: round(1e3 * a.elapsed_ms / max(a.count, 1), 3) for a in hot_g}
-        del is_g, fs_g, safe_g, hot_g
-
-    # ---------------------------------------------------------------- CPU oracle on a bounded sample of the same step
-    cpu = None
-    if not args.no_cpu_baseline:
-        from oracle import oracle as O
-        n_layers = max(1, args.cpu_sample_layers)
-        host_w = {}
-        for idx, (name, (K, N)) in enumerate(linears):
-            host_w[name] = O.quantize_weights_int4_group(S.make_weights(1, N, K, S.seed_for(1, idx, 1)), GROUP,
-                                                         ALPHA_LOG2, O.SCALE_NORM)
-        host_x = {(M, name): S.make_activations(1, M, K, S.seed_for(1, idx, 2) + M)
-                  for M in BATCHES for idx, (name, (K, N)) in enumerate(linears)}
-        t0 = time.perf_counter()
-        cpu_bytes = 0
-        for _ in range(n_layers):
-            for M in BATCHES:
-                for name, (K, N) in linears:
-                    xq, sa = O.quantize_act_int8_token(host_x[(M, name)])
-                    hw = host_w[name]
-                    ref = O.gemm_w4a8_intscale(xq, sa, hw.qweight, hw.scale_i32, hw.chan_scale, GROUP, ALPHA_LOG2)
-                    cpu_bytes += S.algorithmic_bytes(M, N, K, GROUP) + 3 * M * K + 4 * M
-        dt = time.perf_counter() - t0
-        # the last oracle result doubles as a live parity check of the GPU path
-        a = acts[(BATCHES[-1], linears[-1][0])]
-        w = weights[linears[-1][0]]
-        P.is_quantize_act_int8_token(a["x"], a["xq"], a["sa"])
-        out, acc = P.is_gemm_w4a8_intscale(a["xq"], a["sa"], w["q"][0], w["si"][0], w["c"][0], GROUP, ALPHA_LOG2,
-                                           want_acc=True)
-        torch.cuda.synchronize()
-        acc_ok = bool(np.array_equal(acc.cpu().numpy(), ref.acc))
-        got = out.cpu().numpy().astype(np.float64)
-        rel = float(np.max(np.abs(got - ref.out) / np.maximum(np.abs(ref.out), 1e-3)))
-        cpu = dict(value=round(cpu_bytes / dt / 1e9, 3), unit="GB/s", cores=O.num_threads(), kind="oracle",
-                   sample=f"{n_layers} of {L} layers x 4 linears x M in {list(BATCHES)} (quantiser + integer-scale GEMM), "
-                          f"{dt:.1f} s",
-                   parity=dict(acc_bit_exact=acc_ok, max_rel_err=rel))
-
-    value = step_bytes / sec_per_step / 1e9
-    line = {
-        "metric": "W4A8 integer-scale GEMM TOPS + HBM GB/s (% roofline); speedup vs float-scale",
-        "value": round(value, 1),
-        "unit": "GB/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": round(1e3 * sec_per_step, 4),
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "int8",
-        "data": "synthetic",
-        "config": {"workload": "llama2-7b decode linears (qkv, o_proj, gate_up, down), W4 group-128 x A8 per-token, "
-                               f"alpha=2^{ALPHA_LOG2}, M in {list(BATCHES)}, {L} layers of distinct weights",
-                   "launch": "hip-graph" if use_graph else "eager", "scale_mode": "norm"},
-        "tops": round(step_ops / sec_per_step / 1e12, 3),
-        "hbm_frac": round(value / HBM_PEAK_GBS, 4),
-        "speedup_vs_floatscale": None if speedup is None else round(speedup, 4),
-        "floatscale_over_intscale_by_shape": fs_detail,
-        "overflow": overflow,
-        "hot_cache_us_by_shape": hot_detail,
-        "roofline": roofline,
-        "measured_peaks": peaks,
-        "cpu_baseline": cpu,
-        "shapes": shapes,
-    }
-    print(json.dumps(line))
 
 
 FAMILIES = {
@@ -464,16 +187,19 @@ def family_main(args):
     L = args.layers or fam["layers"]
     use_graph = not args.no_graph
 
+    def grp(K):
+        return K if args.coarse else GROUP
+
     # ---------------------------------------------------------------- data: one layer drawn on the host, quantised and
     # prepacked on the GPU by the library (the offline step), then copied into L distinct buffers (timing does not
     # depend on the values); both scale forms, for the float-scale twin
     weights = {}
     for idx, (name, (K, N)) in enumerate(linears):
         w = torch.from_numpy(S.make_weights(cfg, N, K, S.seed_for(cfg, idx, 1))).to(dev)
-        qw = P.is_quantize_weights_int4_group(w, GROUP, ALPHA_LOG2, P.IS_SCALE_NORM)
+        qw = P.is_quantize_weights_int4_group(w, grp(K), ALPHA_LOG2, P.IS_SCALE_NORM)
         del w
-        pi = P.is_prepack_w4(qw.qweight, qw.scale_i32, GROUP)
-        pf = P.is_prepack_w4(qw.qweight, qw.scale_f32, GROUP)
+        pi = P.is_prepack_w4(qw.qweight, qw.scale_i32, grp(K))
+        pf = P.is_prepack_w4(qw.qweight, qw.scale_f32, grp(K))
         torch.cuda.synchronize()
         weights[name] = dict(
             canon=qw,
@@ -488,12 +214,12 @@ def family_main(args):
             acts[(M, name)] = dict(
                 x=x, xq=xq, sa=sa, out=torch.empty((M, N), dtype=torch.float16, device=dev),
                 # workspaces start zeroed: the K split's arrival counters live there and every call leaves them zero
-                lws=torch.zeros(max(1, P.is_linear_prepacked_workspace_bytes(M, N, K, GROUP)), dtype=torch.uint8, device=dev),
-                gws=torch.zeros(max(1, P.is_gemm_prepacked_workspace_bytes(M, N, K, GROUP)), dtype=torch.uint8, device=dev))
+                lws=torch.zeros(max(1, P.is_linear_prepacked_workspace_bytes(M, N, K, grp(K))), dtype=torch.uint8, device=dev),
+                gws=torch.zeros(max(1, P.is_gemm_prepacked_workspace_bytes(M, N, K, grp(K))), dtype=torch.uint8, device=dev))
     torch.cuda.synchronize()
 
     def alg_bytes(M, N, K, fp16_in):
-        b = S.algorithmic_bytes(M, N, K, GROUP)
+        b = S.algorithmic_bytes(M, N, K, grp(K))
         return b + M * K - 4 * M if fp16_in else b      # fp16 rows in instead of int8 codes and their scales
 
     # ---------------------------------------------------------------- segments
@@ -508,19 +234,19 @@ def family_main(args):
                         for l in range(L):
                             P.is_linear_w4a8_intscale_prepacked(a["x"], w["pi"][l], w["c"][l], ALPHA_LOG2, out=a["out"],
                                                                 workspace=a["lws"])
-                    kernels = P.is_describe_prepacked(M, N, K, GROUP, True, True)
+                    kernels = P.is_describe_prepacked(M, N, K, grp(K), True, True)
                 elif kind == "gemm_is":
                     def fn(a=a, w=w):
                         for l in range(L):
                             P.is_gemm_w4a8_intscale_prepacked(a["xq"], a["sa"], w["pi"][l], w["c"][l], ALPHA_LOG2,
                                                               out=a["out"], workspace=a["gws"])
-                    kernels = P.is_describe_prepacked(M, N, K, GROUP, True, False)
+                    kernels = P.is_describe_prepacked(M, N, K, grp(K), True, False)
                 else:
                     def fn(a=a, w=w):
                         for l in range(L):
                             P.is_gemm_w4a8_floatscale_prepacked(a["xq"], a["sa"], w["pf"][l], out=a["out"],
                                                                 workspace=a["gws"])
-                    kernels = P.is_describe_prepacked(M, N, K, GROUP, False, False)
+                    kernels = P.is_describe_prepacked(M, N, K, grp(K), False, False)
                 seg = Segment(f"{name}_M{M}", kernels[-1], L, L * alg_bytes(M, N, K, kind == "linear"),
                               L * S.algorithmic_ops(M, N, K), fn, use_graph, torch)
                 seg.M, seg.K, seg.N, seg.kernels = M, K, N, kernels
@@ -669,12 +395,12 @@ def family_main(args):
         a = acts[(M if (M, name) in acts else batches[0], name)]
         sweep = []
         for al in (6, 8, 10, 12):
-            qw = P.is_quantize_weights_int4_group(w, GROUP, al, P.IS_SCALE_NORM)
-            ref = P.is_gemm_w4a8_floatscale(a["xq"], a["sa"], qw.qweight, qw.scale_f32, GROUP).float()
+            qw = P.is_quantize_weights_int4_group(w, grp(K), al, P.IS_SCALE_NORM)
+            ref = P.is_gemm_w4a8_floatscale(a["xq"], a["sa"], qw.qweight, qw.scale_f32, grp(K)).float()
             # (scale_f32 is the whole float group scale; scale_i32 its amplified, rounded quotient by chan_scale)
-            got, _ = P.is_gemm_w4a8_intscale_prepacked(a["xq"], a["sa"], P.is_prepack_w4(qw.qweight, qw.scale_i32, GROUP),
+            got, _ = P.is_gemm_w4a8_intscale_prepacked(a["xq"], a["sa"], P.is_prepack_w4(qw.qweight, qw.scale_i32, grp(K)),
                                                        qw.chan_scale, al)
-            bound = int(P.is_intscale_overflow_bound(qw.scale_i32, GROUP).cpu()[0])
+            bound = int(P.is_intscale_overflow_bound(qw.scale_i32, grp(K)).cpu()[0])
             err = (got.float() - ref).abs()
             sweep.append(dict(alpha_log2=al, mean_rel_err_vs_floatscale=float(err.mean() / ref.abs().mean()),
                               max_abs_err_over_mean_abs=float(err.max() / ref.abs().mean()),
@@ -692,13 +418,13 @@ def family_main(args):
         t_cpu, cpu_ops = 0.0, 0
         ok_all, rel_all = True, 0.0
         for idx, (name, (K, N)) in enumerate(linears):
-            hw = O.quantize_weights_int4_group(S.make_weights(cfg, N, K, S.seed_for(cfg, idx, 1)), GROUP, ALPHA_LOG2,
+            hw = O.quantize_weights_int4_group(S.make_weights(cfg, N, K, S.seed_for(cfg, idx, 1)), grp(K), ALPHA_LOG2,
                                                O.SCALE_NORM)
             for M in batches:
                 hx = S.make_activations(cfg, M, K, S.seed_for(cfg, idx, 2) + M)[:cap]
                 t0 = time.perf_counter()
                 xq, sa = O.quantize_act_int8_token(hx)
-                ref = O.gemm_w4a8_intscale(xq, sa, hw.qweight, hw.scale_i32, hw.chan_scale, GROUP, ALPHA_LOG2)
+                ref = O.gemm_w4a8_intscale(xq, sa, hw.qweight, hw.scale_i32, hw.chan_scale, grp(K), ALPHA_LOG2)
                 t_cpu += time.perf_counter() - t0
                 cpu_ops += S.algorithmic_ops(hx.shape[0], N, K)
                 # the oracle's result doubles as a live parity check of the step's call (first layer's weights)
@@ -735,11 +461,10 @@ def family_main(args):
         "vs_baseline": None,
         "dtype": "int8",
         "data": "synthetic",
-        "config": {"workload": f"{fam['label']} linears ({', '.join(n for n, _ in linears)}), W4 group-{GROUP} x A8 "
+        "config": {"workload": f"{fam['label']} linears ({', '.join(n for n, _ in linears)}), W4 {'coarse-grained (one group per weight row)' if args.coarse else f'group-{GROUP}'} x A8 "
                                f"per-token, alpha=2^{ALPHA_LOG2}, M in {list(batches)} (fp16 activations in, fp16 out), "
                                f"{L} layers of distinct weights per step",
-                   "layout": "prepacked offline (is_prepack_w4); the canonical-layout calls are --workload "
-                             "decode_canonical / prefill_canonical",
+                   "layout": "weights prepacked offline (is_prepack_w4)",
                    "launch": "hip-graph" if use_graph else "eager", "scale_mode": "norm"},
         "decode": None if not decode_ms else dict(
             gbs=round(decode_bytes / decode_ms / 1e6, 1), hbm_frac=round(decode_bytes / decode_ms / 1e6 / HBM_PEAK_GBS, 4),
@@ -752,178 +477,6 @@ def family_main(args):
         "roofline": roofline,
         "roofline_hbm" if roofline["bound"] == "mfma" else "roofline_mfma": roofline_other,
         "alpha_sweep": sweep,
-        "measured_peaks": peaks,
-        "cpu_baseline": cpu,
-        "shapes": shapes,
-    }
-    print(json.dumps(line))
-
-
-def prefill_main(args):
-    """LLaMA-3-8B-shaped prefill at M = 4096: per linear, the activation quantiser and the integer-scale GEMM."""
-    import numpy as np
-    import torch
-
-    import paper_2405_14597_amd as P
-    import synth_inputs as S
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    P.load_library()
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    M = 4096
-    linears = list(S.LLAMA3_8B.items())
-    data = []
-    for idx, (name, (K, N)) in enumerate(linears):
-        w = torch.from_numpy(S.make_weights(3, N, K, S.seed_for(3, idx, 1))).to(dev)
-        grp = K if args.coarse else GROUP   # --coarse: one group per weight row (Table 2, first column)
-        qw = P.is_quantize_weights_int4_group(w, grp, ALPHA_LOG2, P.IS_SCALE_NORM)
-        del w
-        x = torch.from_numpy(S.make_activations(3, M, K, S.seed_for(3, idx, 2))).to(dev)
-        data.append(dict(name=name, K=K, N=N, G=grp, qw=qw, x=x, xq=torch.empty((M, K), dtype=torch.int8, device=dev),
-                         sa=torch.empty((M,), dtype=torch.float32, device=dev),
-                         out=torch.empty((M, N), dtype=torch.float16, device=dev),
-                         ws=torch.empty(P.is_gemm_workspace_bytes(M, N, K, grp), dtype=torch.uint8, device=dev)))
-    torch.cuda.synchronize()
-
-    def quant(d):
-        P.is_quantize_act_int8_token(d["x"], d["xq"], d["sa"])
-
-    def gemm_is(d):
-        q = d["qw"]
-        P.is_gemm_w4a8_intscale(d["xq"], d["sa"], q.qweight, q.scale_i32, q.chan_scale, d["G"], ALPHA_LOG2, out=d["out"],
-                                workspace=d["ws"])
-
-    def gemm_fs(d):
-        q = d["qw"]
-        P.is_gemm_w4a8_floatscale(d["xq"], d["sa"], q.qweight, q.scale_f32, d["G"], out=d["out"], workspace=d["ws"])
-
-    def timed(fns, steps, warmup):
-        """fns: list of (label, callable); returns seconds per step and per-label average milliseconds."""
-        for _ in range(warmup):
-            for _, f in fns:
-                f()
-        torch.cuda.synchronize()
-        marks = []
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            ev = torch.cuda.Event(enable_timing=True)
-            ev.record()
-            for label, f in fns:
-                f()
-                nxt = torch.cuda.Event(enable_timing=True)
-                nxt.record()
-                marks.append((label, ev, nxt))
-                ev = nxt
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        per = {}
-        for label, a, b in marks:
-            per[label] = per.get(label, 0.0) + a.elapsed_time(b)
-        return (t1 - t0) / steps, {k: v / steps for k, v in per.items()}
-
-    def linear_is(d):
-        q = d["qw"]
-        P.is_linear_w4a8_intscale(d["x"], q.qweight, q.scale_i32, q.chan_scale, d["G"], ALPHA_LOG2, out=d["out"],
-                                  workspace=d["lws"])
-
-    # One step: every linear on its fp16 activations through the linear call (quantiser inside the tiled kernel's
-    # activation preparation); with --no-fused-token the quantiser kernel and the GEMM call one after the other.
-    fns = []
-    for d in data:
-        if args.no_fused_token:
-            fns.append((f"quant_{d['name']}", lambda d=d: quant(d)))
-            fns.append((f"gemm_{d['name']}", lambda d=d: gemm_is(d)))
-        else:
-            d["lws"] = torch.empty(P.is_linear_workspace_bytes(M, d["N"], d["K"], d["G"]), dtype=torch.uint8, device=dev)
-            fns.append((f"linear_{d['name']}", lambda d=d: linear_is(d)))
-    sec_per_step, per_step = timed(fns, args.steps, args.warmup)
-    # the GEMM calls alone (quantised activations in), for the roofline figure of the tile kernel
-    _, per = timed([(f"gemm_{d['name']}", lambda d=d: gemm_is(d)) for d in data] +
-                   [(f"quant_{d['name']}", lambda d=d: quant(d)) for d in data], max(3, args.steps // 2), 2)
-    step_ops = sum(S.algorithmic_ops(M, d["N"], d["K"]) for d in data)
-    shapes = []
-    gemm_ms = gemm_ops = 0.0
-    for d in data:
-        ms = per[f"gemm_{d['name']}"]
-        ops = S.algorithmic_ops(M, d["N"], d["K"])
-        gemm_ms += ms
-        gemm_ops += ops
-        shapes.append(dict(name=f"gemm_{d['name']}_M{M}", us=round(1e3 * ms, 2), tops=round(ops / ms / 1e9, 1),
-                           mfma_frac=round(ops / ms / 1e9 / MFMA_I8_PEAK_TOPS, 4),
-                           quant_us=round(1e3 * per[f"quant_{d['name']}"], 2),
-                           step_call_us=round(1e3 * sum(v for k, v in per_step.items() if k.endswith("_" + d["name"])), 2)))
-    achieved = gemm_ops / gemm_ms / 1e9
-    kernel = "gemm_prefill_kernel<true, true>" if args.coarse else "gemm_prefill_kernel<true, false>"
-    roofline = dict(bound="mfma", kernel=kernel, achieved=round(achieved, 1), peak=MFMA_I8_PEAK_TOPS, unit="TOP/s",
-                    frac=round(achieved / MFMA_I8_PEAK_TOPS, 4), traffic=measured_traffic(kernel, "llama3_8b_prefill"),
-                    avg_launch_us=round(1e3 * gemm_ms / len(data), 2),
-                    note="per GEMM call: the tile kernel plus its two preparation kernels (about 6 % of the call)")
-    peaks = measured_peaks(P, torch)
-    roofline["frac_of_measured_peak"] = round(achieved / peaks["mfma_i8_tops"], 4)
-
-    speedup = fs_detail = None
-    if not args.no_floatscale:
-        n = max(3, args.steps // 2)
-        _, per_is = timed([(d["name"], lambda d=d: gemm_is(d)) for d in data], n, 2)
-        _, per_fs = timed([(d["name"], lambda d=d: gemm_fs(d)) for d in data], n, 2)
-        speedup = sum(per_fs.values()) / sum(per_is.values())
-        fs_detail = {k: round(per_fs[k] / per_is[k], 4) for k in per_is}
-
-    cpu = None
-    if not args.no_cpu_baseline:
-        from oracle import oracle as O
-        # the whole workload once: every linear at all M token rows
-        cpu_ops = 0
-        dt = 0.0
-        ok_all, rel_all = True, 0.0
-        for idx, d in enumerate(data):
-            K, N = d["K"], d["N"]
-            hw = O.quantize_weights_int4_group(S.make_weights(3, N, K, S.seed_for(3, idx, 1)), d["G"], ALPHA_LOG2,
-                                               O.SCALE_NORM)
-            hx = S.make_activations(3, M, K, S.seed_for(3, idx, 2))
-            t0 = time.perf_counter()
-            xq, sa = O.quantize_act_int8_token(hx)
-            ref = O.gemm_w4a8_intscale(xq, sa, hw.qweight, hw.scale_i32, hw.chan_scale, d["G"], ALPHA_LOG2)
-            dt += time.perf_counter() - t0
-            cpu_ops += S.algorithmic_ops(M, N, K)
-            # the oracle result doubles as a live parity check of the GPU path
-            quant(d)
-            q = d["qw"]
-            out, acc = P.is_gemm_w4a8_intscale(d["xq"], d["sa"], q.qweight, q.scale_i32, q.chan_scale, d["G"],
-                                               ALPHA_LOG2, want_acc=True)
-            torch.cuda.synchronize()
-            ok_all = ok_all and bool(np.array_equal(acc.cpu().numpy(), ref.acc))
-            got = out.cpu().numpy().astype(np.float64)
-            rel_all = max(rel_all, float(np.max(np.abs(got - ref.out) / np.maximum(np.abs(ref.out), 1e-3))))
-            del hw, hx, ref, out, acc, got
-        cpu = dict(value=round(cpu_ops / dt / 1e12, 4), unit="TOP/s", cores=O.num_threads(), kind="oracle",
-                   sample=f"the whole workload once (3 linears x {M} token rows, quantiser + integer-scale GEMM), {dt:.1f} s",
-                   parity=dict(acc_bit_exact=ok_all, max_rel_err=rel_all))
-
-    value = step_ops / sec_per_step / 1e12
-    line = {
-        "metric": "W4A8 integer-scale GEMM TOPS + HBM GB/s (% roofline); speedup vs float-scale",
-        "value": round(value, 1),
-        "unit": "TOP/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": round(1e3 * sec_per_step, 4),
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "int8",
-        "data": "synthetic",
-        "config": {"workload": f"llama3-8b prefill linears (qkv, gate_up, down) at M={M} Student-t token rows, W4 "
-                               f"{'coarse-grained (one group per weight row)' if args.coarse else 'group-128'} "
-                               f"x A8 per-token, alpha=2^{ALPHA_LOG2}", "launch": "eager", "scale_mode": "norm"},
-        "mfma_frac": round(value / MFMA_I8_PEAK_TOPS, 4),
-        "speedup_vs_floatscale": None if speedup is None else round(speedup, 4),
-        "floatscale_over_intscale_by_shape": fs_detail,
-        "roofline": roofline,
         "measured_peaks": peaks,
         "cpu_baseline": cpu,
         "shapes": shapes,
@@ -1011,7 +564,7 @@ def w8a8_main(args):
     dom_kernel = "gemm_skinny_kernel<%d, 1, 2, true, true, true>" % (1 if dom <= 16 else 2 if dom <= 32 else 3 if dom <= 48 else 4)
     roofline = dict(bound="hbm", kernel=dom_kernel, achieved=round(alg_bytes(dom) / per[dom] / 1e3, 1),
                     peak=HBM_PEAK_GBS, unit="GB/s", frac=round(alg_bytes(dom) / per[dom] / 1e3 / HBM_PEAK_GBS, 4),
-                    traffic=measured_traffic(dom_kernel, "llama3_8b_w8a8"),
+                    traffic=measured_traffic(dom_kernel, "w8a8"),
                     avg_launch_us=round(per[dom], 2), note=f"the M = {dom} call; M = 4096 (tiled kernel, MFMA bound): "
                     f"{2.0 * 4096 * N * K / per[4096] / 1e6:.0f} TOP/s = {2.0 * 4096 * N * K / per[4096] / 1e6 / MFMA_I8_PEAK_TOPS:.3f} of the int8 peak")
     peaks = measured_peaks(P, torch)
@@ -1136,7 +689,7 @@ def producers_main(args):
     ach = alg_bytes(big, dom) / per[(big, dom)] / 1e3
     kern = "silu_mul_quantize_resident_kernel<8, 256>" if dom == "silu" else "rmsnorm_quantize_resident_kernel<2, 256>"
     roofline = dict(bound="hbm", kernel=kern, achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(ach / HBM_PEAK_GBS, 4), traffic=measured_traffic(kern, "llama3_8b_producers"),
+                    frac=round(ach / HBM_PEAK_GBS, 4), traffic=measured_traffic(kern, "producers"),
                     avg_launch_us=round(per[(big, dom)], 2))
     peaks = measured_peaks(P, torch)
     roofline["frac_of_measured_peak"] = round(ach / peaks["hbm_read_gbs"], 4)
@@ -1262,7 +815,7 @@ def moe_main(args):
     achieved = sum(alg_bytes(d) for d in data) / tot_ms / 1e6
     kernel = "gemm_prefill_kernel<true, false>"
     roofline = dict(bound="hbm", kernel=kernel, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=measured_traffic(kernel, "mixtral_moe"),
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=measured_traffic(kernel, "moe"),
                     avg_launch_us=round(1e3 * tot_ms / len(data), 2),
                     note="per grouped call (tile kernel plus preparation kernels); near the ridge: per-shape "
                          "roofline_frac takes the larger of the HBM and the MFMA time")

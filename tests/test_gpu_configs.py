@@ -1,5 +1,6 @@
 """GPU parity at the full sizes of the five benchmark configurations, end to end (fp16 in, fp16 out) through the
-C ABI, in the launch configuration bench.py times (default kernel choice, caller-provided outputs and workspace).
+C ABI, in the launch configuration bench.py times (default kernel choice, caller-provided outputs and workspace), on
+both routes: the calls on the canonical layouts and the calls on the kernel layout written by is_prepack_w4.
 Every stage is compared with the CPU oracle on the same seeded inputs: quantised codes, float and integer scales and
 int32 accumulators bit for bit, fp16 outputs within the stated tolerance; the float-scale twin against the oracle's
 double-precision Eq. (1).
@@ -92,6 +93,23 @@ def run_linear(P, layer, x, alpha, mode, what, float_twin=True):
         fs_r = O.gemm_w4a8_floatscale(xq_r, sa_r, ref_w.qweight, ref_w.scale_f32, G)
         fs = P.is_gemm_w4a8_floatscale(xq, sa, got_w.qweight, got_w.scale_f32, G, workspace=ws)
         check_fs(host(fs), fs_r, what)
+    # The prepacked route, as bench.py times it: weights converted to the kernel layout, the linear call on the fp16
+    # activations with a zeroed workspace of the caller's (used twice), then the float-scale twin on the same layout.
+    pk = P.is_prepack_w4(got_w.qweight, got_w.scale_i32, G)
+    pws = torch.zeros(max(1, P.is_linear_prepacked_workspace_bytes(M, layer.N, layer.K, G)), dtype=torch.uint8,
+                      device="cuda:0")
+    outp = torch.empty((M, layer.N), dtype=torch.float16, device="cuda:0")
+    P.is_linear_w4a8_intscale_prepacked(dev(x), pk, got_w.chan_scale, alpha, out=outp, workspace=pws)
+    check_out(host(outp), ref.out, what + " (prepacked)")
+    outp2, accp = P.is_linear_w4a8_intscale_prepacked(dev(x), pk, got_w.chan_scale, alpha, want_acc=True, workspace=pws)
+    assert np.array_equal(host(accp), ref.acc), f"{what}: int32 accumulators of the prepacked linear call"
+    check_out(host(outp2), ref.out, what + " (prepacked)")
+    del pk, outp2, accp
+    if float_twin:
+        pkf = P.is_prepack_w4(got_w.qweight, got_w.scale_f32, G)
+        fsp = P.is_linear_w4a8_floatscale_prepacked(dev(x), pkf, workspace=pws)
+        check_fs(host(fsp), fs_r, what + " (prepacked)")
+        del pkf, fsp
     if M <= 16:
         # the linear call on the fp16 activations (bench.py uses it for one token: the decode kernel quantises itself)
         lws = torch.empty(P.is_linear_workspace_bytes(M, layer.N, layer.K, G), dtype=torch.uint8, device="cuda:0")
