@@ -50,9 +50,6 @@ def parse_args():
                     help="distinct weight copies per linear (default: 8 for llama2_70b, 32 for llama2_7b, 4 for llama3_8b)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-floatscale", action="store_true", help="skip the float-scale comparison pass")
-    ap.add_argument("--coarse", action="store_true",
-                    help="model-family workloads: coarse-grained weights, one group per weight row (the paper's upper "
-                         "bound for the fine-grained kernels, Table 2 / Fig. 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip timing the CPU oracle")
     ap.add_argument("--no-traffic", action="store_true",
                     help="do not look up the measured HBM traffic in profiles/ (roofline.traffic = null); without this "
@@ -188,7 +185,7 @@ def family_main(args):
     use_graph = not args.no_graph
 
     def grp(K):
-        return K if args.coarse else GROUP
+        return GROUP
 
     # ---------------------------------------------------------------- data: one layer drawn on the host, quantised and
     # prepacked on the GPU by the library (the offline step), then copied into L distinct buffers (timing does not
@@ -461,7 +458,7 @@ def family_main(args):
         "vs_baseline": None,
         "dtype": "int8",
         "data": "synthetic",
-        "config": {"workload": f"{fam['label']} linears ({', '.join(n for n, _ in linears)}), W4 {'coarse-grained (one group per weight row)' if args.coarse else f'group-{GROUP}'} x A8 "
+        "config": {"workload": f"{fam['label']} linears ({', '.join(n for n, _ in linears)}), W4 group-{GROUP} x A8 "
                                f"per-token, alpha=2^{ALPHA_LOG2}, M in {list(batches)} (fp16 activations in, fp16 out), "
                                f"{L} layers of distinct weights per step",
                    "layout": "weights prepacked offline (is_prepack_w4)",
