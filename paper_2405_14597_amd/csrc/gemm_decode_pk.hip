@@ -178,30 +178,58 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
     // row blocks of 8 token rows, rounded up to a power of two (rows past M are masked): unit -> (step, row block) by shifts
     const int rb_log = a.M <= 8 ? 0 : a.M <= 16 ? 1 : a.M <= 32 ? 2 : 3;
     const int units = ksl << rb_log;
+    // A wave's units of one batch are W apart: the same row block, K steps (W >> rb_log) apart.  What depends on the
+    // lane is worked out once; a request or an LDS write then costs one addition (all waves of the unit run this
+    // prologue at the same time, and its instructions queue in front of the weight stream's first use).
+    const int fill_dstep = W >> rb_log;
+    const int fill_step0 = wave >> rb_log;
+    const int fill_row = ((wave & ((1 << rb_log) - 1)) << 3) + (lane >> 3);
+    const int fill_c8 = lane & 7;
+    const int fill_goff =
+        fill_row < a.M ? fill_row * a.K + (s_lo + fill_step0) * 128 + fill_c8 * 16 : kOutOfRange;  // stays out of range
+    const int fill_loff = ((fill_step0 * MT + (fill_row >> 4)) * 2 + (fill_c8 >> 2)) * unit_b + (fill_c8 & 3) * 16 * rs +
+                          (fill_row & 15) * 16;
+    // (a batch made of whole rounds over the waves, the usual case, runs without a test per unit)
+    const bool fill_has_place = fill_row < (MT == 1 ? rs : 16 * MT);  // rows past M arrive as zeros; rows without a place in LDS are not written
     [[maybe_unused]] auto fill_load = [&](int base) {
         const rsrc_t xres = make_rsrc(a.xq, (size_t)a.M * a.K);
+        const int st0 = base >> rb_log;
+        const int rounds = min(kFill, (units - base) / W);  // rounds in which every wave has a unit
+        if (rounds == kFill || rounds * W == units - base) {  // and no wave has one beyond them
+            const int goff = fill_goff + st0 * 128;
 #pragma unroll
-        for (int i = 0; i < kFill; ++i) {
-            const int u = base + i * W + wave;
-            if (i > 0 && base + i * W >= units) break;  // uniform: nothing left for any wave
-            const int step = u >> rb_log;
-            const int row = ((u - (step << rb_log)) << 3) + (lane >> 3);
-            const bool ok = u < units && row < a.M;
-            xraw[i] = __builtin_amdgcn_raw_buffer_load_b128(
-                xres, ok ? row * a.K + (s_lo + step) * 128 + (lane & 7) * 16 : kOutOfRange, 0, 0);
+            for (int i = 0; i < kFill; ++i) {
+                if (i >= rounds) break;
+                xraw[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, goff + i * fill_dstep * 128, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kFill; ++i) {
+                if (i > 0 && base + i * W >= units) break;  // uniform: nothing left for any wave
+                const int st = st0 + i * fill_dstep;
+                xraw[i] = __builtin_amdgcn_raw_buffer_load_b128(
+                    xres, st + fill_step0 < ksl ? fill_goff + st * 128 : kOutOfRange, 0, 0);
+            }
         }
     };
     [[maybe_unused]] auto fill_store = [&](int base) {
+        const int st0 = base >> rb_log;
+        if (!fill_has_place) return;
+        const int rounds = min(kFill, (units - base) / W);
+        if (rounds == kFill || rounds * W == units - base) {
+            unsigned char* dst = smem + fill_loff + st0 * step_stride;
 #pragma unroll
-        for (int i = 0; i < kFill; ++i) {
-            const int u = base + i * W + wave;
-            if (i > 0 && base + i * W >= units) break;
-            const int step = u >> rb_log;
-            const int row = ((u - (step << rb_log)) << 3) + (lane >> 3);
-            const int c8 = lane & 7;
-            if (u < units && row < a.M)
-                *reinterpret_cast<v4i*>(smem + ((step * MT + (row >> 4)) * 2 + (c8 >> 2)) * unit_b + (c8 & 3) * 16 * rs +
-                                        (row & 15) * 16) = xraw[i];
+            for (int i = 0; i < kFill; ++i) {
+                if (i >= rounds) break;
+                *reinterpret_cast<v4i*>(dst + i * fill_dstep * step_stride) = xraw[i];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kFill; ++i) {
+                if (i > 0 && base + i * W >= units) break;
+                const int st = st0 + i * fill_dstep;
+                if (st + fill_step0 < ksl) *reinterpret_cast<v4i*>(smem + fill_loff + st * step_stride) = xraw[i];
+            }
         }
     };
     if constexpr (FUSEQ) {
@@ -222,13 +250,12 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
     // weight stream queues.
     float sa[MT][4];
     if constexpr (!FUSEQ) {
+        const rsrc_t ares = make_rsrc(a.a_scale, (size_t)a.M * 4);  // rows past M read as zero
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int m = 16 * t + 4 * kb + r;
-                sa[t][r] = m < a.M ? a.a_scale[m] : 0.0f;
-            }
+            for (int r = 0; r < 4; ++r)
+                sa[t][r] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(ares, (16 * t + 4 * kb + r) * 4, 0, 0));
     }
     float* lds_cs = reinterpret_cast<float*>(smem + p.cs_offset);
     constexpr int kCsPerThread = 1024 / (W * kWave) * 4;  // 256 row tiles x 16 rows per workgroup at most
