@@ -724,7 +724,8 @@ def producers_main(args):
 def moe_main(args):
     """Mixtral-8x7B-shaped expert FFN as grouped GEMMs: 8 experts, 512 tokens, top-2 uniform router (1024 token rows,
     uneven per expert); w1 and w3 4096->14336, w2 14336->4096.  One step = quantiser + grouped integer-scale GEMM per
-    linear, over `--layers` (default 4 here) distinct sets of expert weights so that the weights come from HBM."""
+    linear on prepacked experts, over `--layers` (default 4 here) distinct sets of expert weights so that the weights come
+    from HBM.  The canonical-layout grouped call is timed beside it (`canonical_us_by_shape`)."""
     import numpy as np
     import torch
 
@@ -756,22 +757,34 @@ def moe_main(args):
                          xq=torch.empty((M, K), dtype=torch.int8, device=dev),
                          sa=torch.empty((M,), dtype=torch.float32, device=dev),
                          out=torch.empty((M, N), dtype=torch.float16, device=dev),
-                         ws=torch.empty(P.is_gemm_grouped_workspace_bytes(E, M, N, K, GROUP), dtype=torch.uint8, device=dev)))
+                         ws=torch.empty(P.is_gemm_grouped_workspace_bytes(E, M, N, K, GROUP), dtype=torch.uint8, device=dev),
+                         pws=torch.empty(P.is_gemm_grouped_prepacked_workspace_bytes(E, M, N, K, GROUP), dtype=torch.uint8,
+                                         device=dev)))
+        d = data[-1]
+        d["pi"] = [P.is_prepack_w4_experts(d["q"][l], d["si"][l], GROUP) for l in range(L)]
+        d["pf"] = [P.is_prepack_w4_experts(d["q"][l], d["sf"][l], GROUP) for l in range(L)]
         del qs
     torch.cuda.synchronize()
 
     def quant(d):
         P.is_quantize_act_int8_token(d["x"], d["xq"], d["sa"])
 
-    def gemm(d, l, int_scale):
-        if int_scale:
+    def gemm(d, l, int_scale, canonical=False):
+        if not canonical:
+            if int_scale:
+                P.is_gemm_w4a8_intscale_grouped_prepacked(d["xq"], d["sa"], d["pi"][l], d["c"][l], d["off"], ALPHA_LOG2,
+                                                          out=d["out"], workspace=d["pws"])
+            else:
+                P.is_gemm_w4a8_floatscale_grouped_prepacked(d["xq"], d["sa"], d["pf"][l], d["off"], out=d["out"],
+                                                            workspace=d["pws"])
+        elif int_scale:
             P.is_gemm_w4a8_intscale_grouped(d["xq"], d["sa"], d["q"][l], d["si"][l], d["c"][l], d["off"], GROUP, ALPHA_LOG2,
                                             out=d["out"], workspace=d["ws"])
         else:
             P.is_gemm_w4a8_floatscale_grouped(d["xq"], d["sa"], d["q"][l], d["sf"][l], d["off"], GROUP, out=d["out"],
                                               workspace=d["ws"])
 
-    def run(int_scale, with_quant, steps, warmup):
+    def run(int_scale, with_quant, steps, warmup, canonical=False):
         per = {d["name"]: 0.0 for d in data}
         for it in range(warmup + steps):
             if it == warmup:
@@ -783,7 +796,7 @@ def moe_main(args):
                         quant(d)
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                     e0.record()
-                    gemm(d, l, int_scale)
+                    gemm(d, l, int_scale, canonical)
                     e1.record()
                     if it >= warmup:
                         d.setdefault("marks", []).append((e0, e1))
@@ -810,7 +823,7 @@ def moe_main(args):
                            roofline_frac=round(max(t_hbm, t_mfma) / (ms * 1e-3), 4)))
     tot_ms = sum(per.values())
     achieved = sum(alg_bytes(d) for d in data) / tot_ms / 1e6
-    kernel = "gemm_prefill_kernel<true, false>"
+    kernel = "gemm_tile_grouped_pk_kernel<true>"
     roofline = dict(bound="hbm", kernel=kernel, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4), traffic=measured_traffic(kernel, "moe"),
                     avg_launch_us=round(1e3 * tot_ms / len(data), 2),
@@ -818,13 +831,15 @@ def moe_main(args):
                          "roofline_frac takes the larger of the HBM and the MFMA time")
     peaks = measured_peaks(P, torch)
     roofline["frac_of_measured_peak"] = round(achieved / peaks["hbm_read_gbs"], 4)
-    speedup = fs_detail = None
+    speedup = fs_detail = canon = None
     if not args.no_floatscale:
         n = max(3, args.steps // 2)
         _, per_is = run(True, False, n, 2)
         _, per_fs = run(False, False, n, 2)
         speedup = sum(per_fs.values()) / sum(per_is.values())
         fs_detail = {k: round(per_fs[k] / per_is[k], 4) for k in per_is}
+        _, per_canon = run(True, False, n, 2, canonical=True)
+        canon = {k: round(1e3 * v, 2) for k, v in per_canon.items()}
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import oracle as O
@@ -841,8 +856,8 @@ def moe_main(args):
             acc_ref, out_ref = O.gemm_w4a8_intscale_grouped(xq_h, sa_h, q_h, si_h, c_h, off_h, GROUP, ALPHA_LOG2)
             dt += time.perf_counter() - t0
             cpu_bytes += alg_bytes(d) + 3 * d["M"] * d["K"] + 4 * d["M"]
-            out, acc = P.is_gemm_w4a8_intscale_grouped(d["xq"], d["sa"], d["q"][0], d["si"][0], d["c"][0], d["off"], GROUP,
-                                                       ALPHA_LOG2, want_acc=True)
+            out, acc = P.is_gemm_w4a8_intscale_grouped_prepacked(d["xq"], d["sa"], d["pi"][0], d["c"][0], d["off"],
+                                                                 ALPHA_LOG2, want_acc=True, workspace=d["pws"])
             torch.cuda.synchronize()
             ok_all = ok_all and bool(np.array_equal(acc.cpu().numpy(), acc_ref))
             got, want = out.cpu().numpy().astype(np.float64), out_ref.astype(np.float64)
@@ -859,10 +874,10 @@ def moe_main(args):
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"mixtral-8x7b expert FFN (w1, w3, w2) as grouped GEMMs over {E} experts, {TOKENS} tokens top-{TOPK} "
                                f"uniform router, W4 group-128 x A8 per-token, alpha=2^{ALPHA_LOG2}, {L} sets of expert weights",
-                   "launch": "eager", "scale_mode": "norm"},
+                   "layout": "experts prepacked offline (is_prepack_w4)", "launch": "eager", "scale_mode": "norm"},
         "tops": round(step_ops / sec_per_step / 1e12, 3), "hbm_frac": round(value / HBM_PEAK_GBS, 4),
         "speedup_vs_floatscale": None if speedup is None else round(speedup, 4),
-        "floatscale_over_intscale_by_shape": fs_detail, "roofline": roofline, "measured_peaks": peaks,
+        "floatscale_over_intscale_by_shape": fs_detail, "canonical_us_by_shape": canon, "roofline": roofline, "measured_peaks": peaks,
         "cpu_baseline": cpu, "shapes": shapes,
     }
     print(json.dumps(line))

@@ -234,6 +234,28 @@ int is_linear_w4a8_floatscale_prepacked(const void* x_fp16, const void* qweight_
                                         size_t workspace_bytes, void* stream);
 
 /*
+ * Mixture-of-experts form on the kernel layout (Sec. 5.4): as is_gemm_w4a8_*_grouped, with the `num_experts` weight
+ * sets prepacked one by one by is_prepack_w4 and stored back to back: expert e's weights at qweight_packed +
+ * e * is_prepack_w4_weight_bytes(N,K), its scales (header included) at scales_packed + e * is_prepack_w4_scale_bytes(
+ * N,K,group).  chan_scale [E,N] (may be NULL), row_offsets device int32 [E+1] as for the canonical grouped calls.
+ * Every row count takes the MFMA-bound tiled kernel with 128-row tiles per expert (the call is built for prefill-sized
+ * batches; for a handful of rows per expert the canonical grouped call streams the weights better).  The workspace
+ * (is_gemm_grouped_prepacked_workspace_bytes, contents arbitrary) receives the activations re-ordered into MFMA
+ * operand blocks with every expert padded to whole 16-row tiles, the zero-point corrections and a table of the row
+ * tiles.  Limits: num_experts <= 1024, (ceil(M_total/16) + num_experts) * 16 * K below 2^31.
+ */
+size_t is_gemm_grouped_prepacked_workspace_bytes(int num_experts, int M_total, int N, int K, int group);
+int is_gemm_w4a8_intscale_grouped_prepacked(const int8_t* xq, const float* a_scale, const void* qweight_packed,
+                                            const void* scales_packed, const float* chan_scale,
+                                            const int32_t* row_offsets, int num_experts, int M_total, int N, int K,
+                                            int group, int alpha_log2, void* out_fp16, int32_t* acc_out, void* workspace,
+                                            size_t workspace_bytes, void* stream);
+int is_gemm_w4a8_floatscale_grouped_prepacked(const int8_t* xq, const float* a_scale, const void* qweight_packed,
+                                              const void* scales_packed, const int32_t* row_offsets, int num_experts,
+                                              int M_total, int N, int K, int group, void* out_fp16, void* workspace,
+                                              size_t workspace_bytes, void* stream);
+
+/*
  * Which kernels the prepacked calls launch for a shape, as a kernel trace (rocprofv3 --kernel-trace) names them, in
  * launch order and separated by '\n' (the stand-alone activation quantiser of the linear call for 2 <= M <= 64, when
  * it runs, is not listed).  Host-only: nothing is launched.  int_scale: Eq. (2) or Eq. (1) form; fp16_in: the linear

@@ -52,6 +52,9 @@ EXPORTED_SYMBOLS = (
     "is_linear_prepacked_workspace_bytes",
     "is_linear_w4a8_intscale_prepacked",
     "is_linear_w4a8_floatscale_prepacked",
+    "is_gemm_grouped_prepacked_workspace_bytes",
+    "is_gemm_w4a8_intscale_grouped_prepacked",
+    "is_gemm_w4a8_floatscale_grouped_prepacked",
     "is_describe_prepacked",
     "is_source_hash",
     "is_probe_stream_read",
@@ -147,6 +150,13 @@ def load_library() -> ctypes.CDLL:
     lib.is_gemm_w4a8_floatscale_prepacked.restype = ci
     lib.is_gemm_w4a8_intscale_prepacked_noalloc.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp]
     lib.is_gemm_w4a8_intscale_prepacked_noalloc.restype = ci
+    lib.is_gemm_grouped_prepacked_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.is_gemm_grouped_prepacked_workspace_bytes.restype = sz
+    lib.is_gemm_w4a8_intscale_grouped_prepacked.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, sz,
+                                                            vp]
+    lib.is_gemm_w4a8_intscale_grouped_prepacked.restype = ci
+    lib.is_gemm_w4a8_floatscale_grouped_prepacked.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, sz, vp]
+    lib.is_gemm_w4a8_floatscale_grouped_prepacked.restype = ci
     lib.is_linear_prepacked_workspace_bytes.argtypes = [ci, ci, ci, ci]
     lib.is_linear_prepacked_workspace_bytes.restype = sz
     lib.is_linear_w4a8_intscale_prepacked.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
@@ -618,6 +628,94 @@ def is_gemm_prepacked_workspace_bytes(M: int, N: int, K: int, group: int) -> int
 
 def is_linear_prepacked_workspace_bytes(M: int, N: int, K: int, group: int) -> int:
     return int(load_library().is_linear_prepacked_workspace_bytes(M, N, K, group))
+
+
+class PackedExperts(NamedTuple):
+    wpack: "object"    # uint8 [E, weight bytes]: every expert's weights in the kernel layout, back to back
+    spack: "object"    # uint8 [E, scale bytes]: every expert's scales (header included)
+    E: int
+    N: int
+    K: int
+    group: int
+    float_scales: bool
+
+
+def is_prepack_w4_experts(qweight, scale, group: int, stream=None) -> PackedExperts:
+    """qweight [E,N,K/2] + scale_i32 or scale_f32 [E,N,K/group] -> every expert prepacked by is_prepack_w4, back to back."""
+    torch = _torch()
+    lib = load_library()
+    E, N, K2 = qweight.shape
+    K = 2 * K2
+    _require(qweight, torch.uint8, (E, N, K2), "qweight")
+    if scale.dtype not in (torch.int32, torch.float32):
+        raise ValueError("scale: int32 or float32 expected")
+    _require(scale, scale.dtype, (E, N, K // group), "scale")
+    wb, sb = int(lib.is_prepack_w4_weight_bytes(N, K)), int(lib.is_prepack_w4_scale_bytes(N, K, group))
+    if wb == 0 or sb == 0:
+        raise IntScaleError("is_prepack_w4", IS_ERR_UNSUPPORTED)
+    wpack = torch.empty((E, wb), dtype=torch.uint8, device=qweight.device)
+    spack = torch.empty((E, sb), dtype=torch.uint8, device=qweight.device)
+    is_float = scale.dtype == torch.float32
+    for e in range(E):
+        st = lib.is_prepack_w4(_p(qweight[e]), None if is_float else _p(scale[e]), _p(scale[e]) if is_float else None, N, K,
+                               group, _p(wpack[e]), _p(spack[e]), _stream_handle(stream))
+        _check("is_prepack_w4", st)
+    return PackedExperts(wpack, spack, E, N, K, group, is_float)
+
+
+def is_gemm_grouped_prepacked_workspace_bytes(E: int, M: int, N: int, K: int, group: int) -> int:
+    return int(load_library().is_gemm_grouped_prepacked_workspace_bytes(E, M, N, K, group))
+
+
+def is_gemm_w4a8_intscale_grouped_prepacked(xq, a_scale, packed: PackedExperts, chan_scale, row_offsets, alpha_log2: int,
+                                            out=None, acc_out=None, want_acc: bool = False, workspace=None, stream=None):
+    """Mixture-of-experts form on prepacked experts. Returns (out fp16 [M,N], acc or None)."""
+    torch = _torch()
+    M, K = xq.shape
+    E, N, group = packed.E, packed.N, packed.group
+    if K != packed.K or packed.float_scales:
+        raise ValueError("packed experts: K mismatch or float scales")
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    _require(row_offsets, torch.int32, (E + 1,), "row_offsets")
+    if chan_scale is not None:
+        _require(chan_scale, torch.float32, (E, N), "chan_scale")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    _require(out, torch.float16, (M, N), "out")
+    if acc_out is None and want_acc:
+        acc_out = torch.empty((M, N), dtype=torch.int32, device=xq.device)
+    if acc_out is not None:
+        _require(acc_out, torch.int32, (M, N), "acc_out")
+    ws, ws_bytes = _workspace(is_gemm_grouped_prepacked_workspace_bytes(E, M, N, K, group), xq.device, workspace)
+    st = load_library().is_gemm_w4a8_intscale_grouped_prepacked(
+        _p(xq), _p(a_scale), _p(packed.wpack), _p(packed.spack), _p(chan_scale), _p(row_offsets), E, M, N, K, group,
+        alpha_log2, _p(out), _p(acc_out), _p(ws), ws_bytes, _stream_handle(stream))
+    _check("is_gemm_w4a8_intscale_grouped_prepacked", st)
+    _release_workspace(ws, workspace, stream)
+    return out, acc_out
+
+
+def is_gemm_w4a8_floatscale_grouped_prepacked(xq, a_scale, packed: PackedExperts, row_offsets, out=None, workspace=None,
+                                              stream=None):
+    torch = _torch()
+    M, K = xq.shape
+    E, N, group = packed.E, packed.N, packed.group
+    if K != packed.K or not packed.float_scales:
+        raise ValueError("packed experts: K mismatch or integer scales")
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    _require(row_offsets, torch.int32, (E + 1,), "row_offsets")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=xq.device)
+    _require(out, torch.float16, (M, N), "out")
+    ws, ws_bytes = _workspace(is_gemm_grouped_prepacked_workspace_bytes(E, M, N, K, group), xq.device, workspace)
+    st = load_library().is_gemm_w4a8_floatscale_grouped_prepacked(
+        _p(xq), _p(a_scale), _p(packed.wpack), _p(packed.spack), _p(row_offsets), E, M, N, K, group, _p(out), _p(ws),
+        ws_bytes, _stream_handle(stream))
+    _check("is_gemm_w4a8_floatscale_grouped_prepacked", st)
+    _release_workspace(ws, workspace, stream)
+    return out
 
 
 def is_describe_prepacked(M: int, N: int, K: int, group: int, int_scale: bool = True, fp16_in: bool = False):

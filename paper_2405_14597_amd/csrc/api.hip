@@ -481,6 +481,75 @@ int is_gemm_w4a8_intscale_prepacked_noalloc(const int8_t* xq, const float* a_sca
                           /*fixed_scratch=*/true);
 }
 
+// ---- mixture-of-experts form on the kernel layout: num_experts weight sets, prepacked one by one, back to back
+static int check_grouped_pk(int E, int M, int N, int K, int group) {
+    if (E <= 0 || M < 0) return IS_ERR_INVALID_ARG;
+    const int shape = check_pk_shape(N, K, group);
+    if (shape != IS_OK) return shape;
+    if (E > 1024 || M > (1 << 20)) return IS_ERR_UNSUPPORTED;
+    if (((long long)(M + 15) / 16 + E) * 16 * K >= (1LL << 31)) return IS_ERR_UNSUPPORTED;  // 32-bit offsets
+    return IS_OK;
+}
+
+size_t is_gemm_grouped_prepacked_workspace_bytes(int num_experts, int M_total, int N, int K, int group) {
+    if (check_grouped_pk(num_experts, M_total, N, K, group) != IS_OK || M_total == 0) return 0;
+    return gemm_tile_grouped_pk_workspace_bytes(num_experts, M_total, N, K);
+}
+
+static int gemm_grouped_pk_common(const int8_t* xq, const float* a_scale, const void* wpack, const void* spack,
+                                  const float* chan_scale, const int32_t* row_offsets, int E, int M, int N, int K,
+                                  int group, int alpha_log2, void* out_fp16, int32_t* acc_out, void* workspace,
+                                  size_t workspace_bytes, void* stream, bool int_scale) {
+    const int shape = check_grouped_pk(E, M, N, K, group);
+    if (shape != IS_OK) return shape;
+    if (int_scale && (alpha_log2 < 0 || alpha_log2 > 30)) return IS_ERR_INVALID_ARG;
+    if (row_offsets == nullptr || (reinterpret_cast<uintptr_t>(row_offsets) & 3u)) return IS_ERR_INVALID_ARG;
+    if (!ok_opt(workspace)) return IS_ERR_INVALID_ARG;
+    const size_t need = is_gemm_grouped_prepacked_workspace_bytes(E, M, N, K, group);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return IS_ERR_WORKSPACE;
+    if (!ok_ptr(wpack) || !ok_ptr(spack) || !ok_opt(chan_scale)) return IS_ERR_INVALID_ARG;
+    if (M == 0) return IS_OK;
+    if (!ok_ptr(xq) || a_scale == nullptr || (reinterpret_cast<uintptr_t>(a_scale) & 3u)) return IS_ERR_INVALID_ARG;
+    if (!ok_ptr(out_fp16) || !ok_opt(acc_out)) return IS_ERR_INVALID_ARG;
+    PkArgs a;
+    a.xq = xq;
+    a.x_fp16 = nullptr;
+    a.a_scale = a_scale;
+    a.a_scale_out = nullptr;
+    a.wpack = static_cast<const uint8_t*>(wpack);
+    a.spack = static_cast<const uint8_t*>(spack);
+    a.chan_scale = chan_scale;
+    a.out = static_cast<__half*>(out_fp16);
+    a.acc_out = acc_out;
+    a.counters = nullptr;
+    a.partials = nullptr;
+    a.M = M;
+    a.N = N;
+    a.K = K;
+    a.group = group;
+    a.alpha_log2 = int_scale ? alpha_log2 : 0;
+    return hip_status(launch_gemm_tile_grouped_pk(a, row_offsets, E, pk_weight_bytes(N, K), pk_scale_bytes(N, K, group),
+                                                  int_scale, workspace, static_cast<hipStream_t>(stream)));
+}
+
+int is_gemm_w4a8_intscale_grouped_prepacked(const int8_t* xq, const float* a_scale, const void* qweight_packed,
+                                            const void* scales_packed, const float* chan_scale,
+                                            const int32_t* row_offsets, int num_experts, int M_total, int N, int K,
+                                            int group, int alpha_log2, void* out_fp16, int32_t* acc_out, void* workspace,
+                                            size_t workspace_bytes, void* stream) {
+    return gemm_grouped_pk_common(xq, a_scale, qweight_packed, scales_packed, chan_scale, row_offsets, num_experts,
+                                  M_total, N, K, group, alpha_log2, out_fp16, acc_out, workspace, workspace_bytes, stream,
+                                  true);
+}
+
+int is_gemm_w4a8_floatscale_grouped_prepacked(const int8_t* xq, const float* a_scale, const void* qweight_packed,
+                                              const void* scales_packed, const int32_t* row_offsets, int num_experts,
+                                              int M_total, int N, int K, int group, void* out_fp16, void* workspace,
+                                              size_t workspace_bytes, void* stream) {
+    return gemm_grouped_pk_common(xq, a_scale, qweight_packed, scales_packed, nullptr, row_offsets, num_experts, M_total,
+                                  N, K, group, 0, out_fp16, nullptr, workspace, workspace_bytes, stream, false);
+}
+
 size_t is_linear_prepacked_workspace_bytes(int M, int N, int K, int group) {
     if (M < 0 || check_pk_shape(N, K, group) != IS_OK) return 0;
     if (M == 0) return 0;

@@ -27,6 +27,8 @@
 // correction -8 * sum_k x[m,k] per (token row, K step), computed once by the preparation kernel, enters each MFMA
 // chain as its initial accumulator, so the chain returns P exactly and the scale step costs one instruction per element.
 #include <stdio.h>
+
+#include <algorithm>
 #include <stdlib.h>
 
 #include "act_common.h"
@@ -57,6 +59,18 @@ struct TileSplit {
     int parts;           // K parts per such tile (1: rem = 0)
     int32_t* counters;   // [rem], zero when the kernel starts
     int32_t* partials;   // [rem][parts][kPartWords]
+};
+// Mixture-of-experts form: token rows sorted by expert, expert e owning rows [row_offsets[e], row_offsets[e+1]) and the
+// e-th of num_experts prepacked weight sets.  The preparation kernel pads every expert to whole 16-row tiles (so that no
+// operand block mixes experts) and lists the 128-row tiles that exist in a table; a workgroup of the tiled kernel
+// takes one table entry and one tile column.
+struct TileGroups {
+    const int32_t* row_offsets;  // device, [num_experts + 1]
+    int num_experts;
+    int slots;                   // table entries there is room for: ceil(M/128) + num_experts
+    int padded16;                // 16-row tiles there is room for: ceil(M/16) + num_experts
+    int32_t* table;              // [0] = entries in use, then 4 words per entry: expert, first 16-row tile, first row, rows
+    size_t wstride, sstride;     // bytes from one expert's packed weights / scales to the next
 };
 constexpr int kPartWords = kTM * kTN;                      // one partial tile: 128 KB
 constexpr size_t kCounterBytes = 2048;                     // up to 512 tiles in the last round
@@ -113,6 +127,63 @@ __global__ __launch_bounds__(256) void prepare_activations_pk_kernel(const int8_
 #pragma unroll
     for (int j = 0; j < kPrepSteps; ++j)
         if (s0 + j < steps) store_block((size_t)mt * steps + s0 + j, lane, v[j][0], v[j][1], xp, c0);
+}
+
+// Mixture-of-experts form of the kernel above: block x is a 16-row tile of the padded row space (the 16-row tiles of
+// expert 0, then those of expert 1, ...); the first workgroup also lists the 128-row tiles.
+__global__ __launch_bounds__(256) void prepare_activations_grouped_pk_kernel(const int8_t* __restrict__ xq, int K,
+                                                                             TileGroups tg, int8_t* __restrict__ xp,
+                                                                             int32_t* __restrict__ c0,
+                                                                             int32_t* __restrict__ counters,
+                                                                             int ncounters) {
+    if (blockIdx.x == 0 && blockIdx.y == 0)  // the tiled kernel's arrival counters start at zero
+        for (int i = threadIdx.x; i < ncounters; i += 256) counters[i] = 0;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        int used = 0, base16 = 0;
+        for (int e = 0; e < tg.num_experts; ++e) {
+            const int lo = tg.row_offsets[e], rows = tg.row_offsets[e + 1] - lo;
+            for (int t = 0; t * kTM < rows && used < tg.slots; ++t, ++used) {
+                int32_t* entry = tg.table + 4 + 4 * used;
+                entry[0] = e;
+                entry[1] = base16 + t * (kTM / 16);
+                entry[2] = lo + t * kTM;
+                entry[3] = min(kTM, rows - t * kTM);
+            }
+            base16 += (rows + 15) >> 4;
+        }
+        tg.table[0] = used;
+    }
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int r = lane & 15, kb = lane >> 4;
+    // which expert's rows this 16-row tile holds (uniform over the workgroup)
+    const int pt = blockIdx.x;
+    int row0 = 0, rows = 0;
+    for (int e = 0, base16 = 0; e < tg.num_experts; ++e) {
+        const int lo = tg.row_offsets[e], me = tg.row_offsets[e + 1] - lo;
+        const int n16 = (me + 15) >> 4;
+        if (pt < base16 + n16) {
+            row0 = lo + 16 * (pt - base16);
+            rows = min(16, me - 16 * (pt - base16));
+            break;
+        }
+        base16 += n16;
+    }
+    if (rows == 0) return;  // past the last expert's tiles
+    const int steps = K >> 7;
+    const int s0 = (blockIdx.y * 4 + wave) * kPrepSteps;
+    const int8_t* src = xq + (size_t)(row0 + min(r, rows - 1)) * K + kb * 16;
+    uint4 v[kPrepSteps][2];
+#pragma unroll
+    for (int j = 0; j < kPrepSteps; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int st = min(s0 + j, steps - 1);
+            v[j][h] = *reinterpret_cast<const uint4*>(src + st * 128 + h * 64);
+            if (r >= rows) v[j][h] = make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+    for (int j = 0; j < kPrepSteps; ++j)
+        if (s0 + j < steps) store_block((size_t)pt * steps + s0 + j, lane, v[j][0], v[j][1], xp, c0);
 }
 
 // The same straight from fp16 activations (the linear call): the per-token quantiser of Appendix A.1 and the
@@ -177,9 +248,11 @@ __global__ __launch_bounds__(256) void quantize_prepare_activations_pk_kernel(co
 typedef float v4f_t __attribute__((ext_vector_type(4)));
 
 // One output tile.  WIDE: 32-bit multiplies in the integer scale step (some scale does not fit 24 signed bits).
-template <bool INT_SCALE, bool WIDE>
+// GROUPED: the mixture-of-experts form; `entry` is the workgroup's line of the tile table and `tile_n_g` its tile column.
+template <bool INT_SCALE, bool WIDE, bool GROUPED>
 __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restrict__ xp, const int32_t* __restrict__ c0,
-                                        const TileSplit& sp, unsigned char* smem) {
+                                        const TileSplit& sp, const TileGroups& tg, const int32_t* entry, int tile_n_g,
+                                        unsigned char* smem) {
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wn = __builtin_amdgcn_readfirstlane(tid / kWave);  // the wave's 64 weight rows of the tile's 256
@@ -189,9 +262,15 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
     // walks the output in blocks of kGroupRows tile rows, column by column (shared operand tiles meet in that XCD's L2)
     const int tiles_n = (a.N + kTN - 1) / kTN;
     const int tiles_m = (a.M + kTM - 1) / kTM;
-    int tile_m, tile_n;
+    int tile_m = 0, tile_n;
     int part = 0, tail_tile = -1;  // a tile of the last round: which K part, which of the round's tiles
-    {
+    if constexpr (GROUPED) {
+        tile_n = tile_n_g;
+        if (sp.parts > 1) {  // every tile's K range is cut (few tiles for the chip): workgroup = (tile, part)
+            part = blockIdx.x % sp.parts;
+            tail_tile = blockIdx.x / sp.parts;
+        }
+    } else {
         int lid;
         if ((int)blockIdx.x < sp.whole) {
             const int q = sp.whole / kXcdCount, rem = sp.whole - q * kXcdCount;
@@ -209,31 +288,40 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
         tile_n = r / gm;
         tile_m = g * kGroupRows + (r - tile_n * gm);
     }
-    const int m0 = tile_m * kTM, n0 = tile_n * kTN;
+    const int n0 = tile_n * kTN;
+    // the tile's token rows: first 16-row tile of the prepared activations, first row of the tensors, how many
+    const int expert = GROUPED ? entry[0] : 0;
+    const int mt0 = GROUPED ? entry[1] : tile_m * (kTM / 16);
+    const int m0 = GROUPED ? entry[2] : tile_m * kTM;
+    const int m_rows = GROUPED ? entry[3] : min(kTM, a.M - m0);
+    const int mt_end = mt0 + ((m_rows + 15) >> 4);  // 16-row tiles from here on are not this tile's (they read as zero)
+    const uint8_t* wpack = a.wpack + (GROUPED ? (size_t)expert * tg.wstride : 0);
+    const uint8_t* spack = a.spack + (GROUPED ? (size_t)expert * tg.sstride : 0);
+    const float* chan_scale = a.chan_scale ? a.chan_scale + (GROUPED ? (size_t)expert * a.N : 0) : nullptr;
     const int steps = a.K >> 7;
     const int NG = a.K / a.group;
     const int spg = a.group >> 7;
     // this workgroup's K steps
     const int s_begin = tail_tile < 0 ? 0 : (part * steps) / sp.parts;
     const int s_end = tail_tile < 0 ? steps : ((part + 1) * steps) / sp.parts;
-    const int m16 = (a.M + 15) >> 4, n16 = (a.N + 15) >> 4;
+    const int m16 = GROUPED ? tg.padded16 : (a.M + 15) >> 4, n16 = (a.N + 15) >> 4;
 
     // ---- loader roles.  Per step and wave: the 2 KB blocks of two 16-row token tiles (4 loads of 1 KB), the 1 KB
     // blocks of four 16-row weight tiles; wave 0 also the step's 256 scales, wave 1 its 128 corrections.  Tiles past
     // the end of a tensor lie outside its descriptor and read as zero.
     const v4i xdesc = make_desc(xp, (size_t)m16 * steps * 2048);
-    const v4i wdesc = make_desc(a.wpack, (size_t)n16 * steps * kPkBlockBytes);
+    const v4i wdesc = make_desc(wpack, (size_t)n16 * steps * kPkBlockBytes);
     v4i adesc = make_desc(nullptr, 0);
     int aux_voff = (int)0x80000000u, aux_step = 0, aux_group = 0;
     if (wn == 0) {
-        adesc = make_desc(a.spack + kPkHeaderBytes, (size_t)n16 * NG * 64);
+        adesc = make_desc(spack + kPkHeaderBytes, (size_t)n16 * NG * 64);
         const int nt = (n0 >> 4) + (lane >> 2);
         aux_voff = nt < n16 ? nt * NG * 64 + (lane & 3) * 16 : (int)0x80000000u;
         aux_group = 64;
     } else if (wn == 1) {
         adesc = make_desc(c0, (size_t)m16 * steps * 64);
-        const int mt = (m0 >> 4) + (lane >> 2);
-        aux_voff = (lane < 32 && mt < m16) ? mt * steps * 64 + (lane & 3) * 16 : (int)0x80000000u;
+        const int mt = mt0 + (lane >> 2);
+        aux_voff = (lane < 32 && mt < mt_end) ? mt * steps * 64 + (lane & 3) * 16 : (int)0x80000000u;
         aux_step = 64;
     }
     // (the offsets of the 8 tile loads are a scalar each plus the lane's 16 bytes: kept in scalar registers and added
@@ -241,8 +329,8 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
     int x_soff[4], w_soff[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int mt = (m0 >> 4) + 2 * wn + (i >> 1);
-        x_soff[i] = mt < m16 ? mt * steps * 2048 + (i & 1) * 1024 : (int)0x80000000u;
+        const int mt = mt0 + 2 * wn + (i >> 1);
+        x_soff[i] = mt < mt_end ? mt * steps * 2048 + (i & 1) * 1024 : (int)0x80000000u;
         const int nt = (n0 >> 4) + 4 * wn + i;
         w_soff[i] = nt < n16 ? nt * steps * kPkBlockBytes : (int)0x80000000u;
     }
@@ -420,7 +508,7 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
         if (tid == 0) __hip_atomic_store(sp.counters + tail_tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     const float inv_alpha = __int_as_float((127 - a.alpha_log2) << 23);
-    const int m_rows = min(kTM, a.M - m0), n_rows = min(kTN, a.N - n0);
+    const int n_rows = min(kTN, a.N - n0);
     // Rows of 8-aligned length go through an fp16 copy of the tile in LDS and leave as 16-byte stores; otherwise (and
     // for the diagnostic accumulator output) element by element.
     const bool staged = (a.N & 7) == 0 && a.acc_out == nullptr;
@@ -440,7 +528,7 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
         const int n = n0 + nl;
         float c = 1.0f;
         if constexpr (INT_SCALE) {
-            if (a.chan_scale && nl < n_rows) c = a.chan_scale[n];
+            if (chan_scale && nl < n_rows) c = chan_scale[n];
             c *= inv_alpha;
         }
 #pragma unroll
@@ -483,12 +571,34 @@ template <bool INT_SCALE>
 __global__ __launch_bounds__(kTThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_tile_pk_kernel(PkArgs a, const int8_t* __restrict__ xp,
                                                                  const int32_t* __restrict__ c0, TileSplit sp) {
     extern __shared__ __align__(16) unsigned char smem_tpk[];
+    const TileGroups none{};
     if constexpr (INT_SCALE) {
         const int flags = *reinterpret_cast<const int32_t*>(a.spack);
-        if (flags & kPkFlagWide) tile_pk<true, true>(a, xp, c0, sp, smem_tpk);
-        else tile_pk<true, false>(a, xp, c0, sp, smem_tpk);
+        if (flags & kPkFlagWide) tile_pk<true, true, false>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
+        else tile_pk<true, false, false>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
     } else {
-        tile_pk<false, false>(a, xp, c0, sp, smem_tpk);
+        tile_pk<false, false, false>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
+    }
+}
+
+// Mixture-of-experts form: workgroup b takes table entry b / (tile columns) and tile column b % (tile columns); the
+// entries in use come first, so the workgroups without one sit at the end of the grid and leave at once.
+template <bool INT_SCALE>
+__global__ __launch_bounds__(kTThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_tile_grouped_pk_kernel(
+    PkArgs a, const int8_t* __restrict__ xp, const int32_t* __restrict__ c0, TileGroups tg, TileSplit sp) {
+    extern __shared__ __align__(16) unsigned char smem_tpk[];
+    const int tiles_n = (a.N + kTN - 1) / kTN;
+    const int tile = blockIdx.x / sp.parts;  // (slot, tile column); sp.parts workgroups share it
+    const int slot = tile / tiles_n;
+    if (slot >= tg.table[0]) return;  // uniform over the workgroup, before any barrier
+    const int32_t* entry = tg.table + 4 + 4 * slot;
+    const int tile_n = tile - slot * tiles_n;
+    if constexpr (INT_SCALE) {
+        const int flags = *reinterpret_cast<const int32_t*>(a.spack + (size_t)entry[0] * tg.sstride);  // this expert's
+        if (flags & kPkFlagWide) tile_pk<true, true, true>(a, xp, c0, sp, tg, entry, tile_n, smem_tpk);
+        else tile_pk<true, false, true>(a, xp, c0, sp, tg, entry, tile_n, smem_tpk);
+    } else {
+        tile_pk<false, false, true>(a, xp, c0, sp, tg, entry, tile_n, smem_tpk);
     }
 }
 
@@ -584,6 +694,76 @@ hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace,
         e = raise(reinterpret_cast<const void*>(gemm_tile_pk_kernel<false>), 1);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(gemm_tile_pk_kernel<false>, dim3(tiles), dim3(kTThreads), smem, stream, a, xp, c0, sp);
+    }
+    return hipGetLastError();
+}
+
+// ---- mixture-of-experts form
+// workspace = [prepared activations, every expert padded to whole 16-row tiles | corrections | table of 128-row tiles]
+// K parts per tile of the grouped form: when all the tiles there can be fit the chip at once several times over
+static int grouped_parts(int E, int M, int N, int K) {
+    const long long tiles = ((long long)(M + kTM - 1) / kTM + E) * ((N + kTN - 1) / kTN);
+    const long long p = (2LL * cu_count()) / tiles;
+    int parts = (int)std::min<long long>(std::min<long long>(p, 8), (K >> 7) / kMinPartSteps);
+    if (parts < 2 || tiles * parts * (long long)kPartWords * 4 > (long long)kPartialCap) parts = 1;
+    return parts;
+}
+
+size_t gemm_tile_grouped_pk_workspace_bytes(int E, int M, int N, int K) {
+    const size_t padded16 = (size_t)(M + 15) / 16 + E;
+    const size_t slots = (size_t)(M + kTM - 1) / kTM + E;
+    const size_t tiles = slots * ((N + kTN - 1) / kTN);
+    const int parts = grouped_parts(E, M, N, K);
+    return pad256(padded16 * 16 * K) + pad256(padded16 * (K / 128) * 64) + pad256((4 + 4 * slots) * 4) +
+           (parts > 1 ? pad256(tiles * 4) + tiles * parts * kPartWords * 4 : 0);
+}
+
+hipError_t launch_gemm_tile_grouped_pk(const PkArgs& a, const int32_t* row_offsets, int E, size_t wstride,
+                                       size_t sstride, bool int_scale, void* workspace, hipStream_t stream) {
+    TileGroups tg;
+    tg.row_offsets = row_offsets;
+    tg.num_experts = E;
+    tg.padded16 = (a.M + 15) / 16 + E;
+    tg.slots = (a.M + kTM - 1) / kTM + E;
+    tg.wstride = wstride;
+    tg.sstride = sstride;
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    int8_t* xp = reinterpret_cast<int8_t*>(ws);
+    const size_t xbytes = pad256((size_t)tg.padded16 * 16 * a.K);
+    int32_t* c0 = reinterpret_cast<int32_t*>(ws + xbytes);
+    unsigned char* at = ws + xbytes + pad256((size_t)tg.padded16 * (a.K / 128) * 64);
+    tg.table = reinterpret_cast<int32_t*>(at);
+    at += pad256((4 + 4 * (size_t)tg.slots) * 4);
+    const int tiles = tg.slots * ((a.N + kTN - 1) / kTN);
+    TileSplit sp{};
+    sp.parts = grouped_parts(E, a.M, a.N, a.K);
+    sp.rem = sp.parts > 1 ? tiles : 0;
+    sp.counters = reinterpret_cast<int32_t*>(at);
+    sp.partials = reinterpret_cast<int32_t*>(at + pad256((size_t)tiles * 4));
+    const int per_wg = 4 * kPrepSteps;
+    hipLaunchKernelGGL(prepare_activations_grouped_pk_kernel, dim3(tg.padded16, ((a.K >> 7) + per_wg - 1) / per_wg),
+                       dim3(256), 0, stream, a.xq, a.K, tg, xp, c0, sp.counters, sp.rem);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t smem = 2 * (size_t)kStage;
+    const int grid = tiles * sp.parts;
+    int device = -1;
+    (void)hipGetDevice(&device);
+    static bool raised[2][64] = {};
+    auto raise = [&](const void* kern, int which) -> hipError_t {
+        if (device >= 0 && device < 64 && raised[which][device]) return hipSuccess;
+        hipError_t r = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (r == hipSuccess && device >= 0 && device < 64) raised[which][device] = true;
+        return r;
+    };
+    if (int_scale) {
+        e = raise(reinterpret_cast<const void*>(gemm_tile_grouped_pk_kernel<true>), 0);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(gemm_tile_grouped_pk_kernel<true>, dim3(grid), dim3(kTThreads), smem, stream, a, xp, c0, tg, sp);
+    } else {
+        e = raise(reinterpret_cast<const void*>(gemm_tile_grouped_pk_kernel<false>), 1);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(gemm_tile_grouped_pk_kernel<false>, dim3(grid), dim3(kTThreads), smem, stream, a, xp, c0, tg, sp);
     }
     return hipGetLastError();
 }

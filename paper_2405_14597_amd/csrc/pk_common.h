@@ -75,6 +75,12 @@ size_t gemm_tile_pk_min_workspace_bytes(int M, int K);      // what it needs at 
 bool gemm_tile_pk_takes_fp16(int K);
 hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace, size_t workspace_bytes,
                                hipStream_t stream);
+// Mixture-of-experts form of the tiled kernel: a.xq / a.a_scale / a.out hold all experts' rows sorted by expert,
+// row_offsets (device, [E+1]) their ranges; a.wpack / a.spack point at E prepacked weight sets wstride / sstride bytes
+// apart, a.chan_scale at [E][N] (or nullptr).  a.M is the total number of rows.
+size_t gemm_tile_grouped_pk_workspace_bytes(int E, int M, int N, int K);
+hipError_t launch_gemm_tile_grouped_pk(const PkArgs& a, const int32_t* row_offsets, int E, size_t wstride,
+                                       size_t sstride, bool int_scale, void* workspace, hipStream_t stream);
 // The kernels launch_gemm_tile_pk runs, in order, as a kernel trace names them, separated by '\n'.
 void gemm_tile_pk_kernel_names(int K, bool int_scale, bool fp16_in, char* buf, size_t len);
 

@@ -181,6 +181,28 @@ def test_prepacked_argument_validation():
     assert lin(M=0, ws=None, wsb=0) == P.IS_OK
 
 
+def test_grouped_prepacked_argument_validation():
+    lib = P.load_library()
+    bad, uns = P.IS_ERR_INVALID_ARG, P.IS_ERR_UNSUPPORTED
+    need = lib.is_gemm_grouped_prepacked_workspace_bytes(4, 300, 48, 1024, 128)
+    # activations padded per expert to 16-row tiles, corrections, table
+    assert need >= (300 // 16 + 4) * 16 * 1024
+    assert lib.is_gemm_grouped_prepacked_workspace_bytes(4, 0, 48, 1024, 128) == 0
+    assert lib.is_gemm_grouped_prepacked_workspace_bytes(0, 300, 48, 1024, 128) == 0
+    assert lib.is_gemm_grouped_prepacked_workspace_bytes(4, 300, 48, 1000, 128) == 0
+    call = lambda **kw: lib.is_gemm_w4a8_intscale_grouped_prepacked(
+        kw.get("xq", A), kw.get("sa", A), kw.get("wp", A), kw.get("sp", A), kw.get("c", None), kw.get("off", A),
+        kw.get("E", 4), kw.get("M", 300), 48, kw.get("K", 1024), kw.get("G", 128), kw.get("a", 10), kw.get("out", A), None,
+        kw.get("ws", A), kw.get("wsb", need), None)
+    assert call(xq=None) == bad and call(sa=None) == bad and call(wp=None) == bad and call(sp=None) == bad
+    assert call(off=None) == bad and call(off=A + 2) == bad and call(out=None) == bad and call(a=31) == bad
+    assert call(E=0) == bad and call(M=-1) == bad and call(K=1000) == bad and call(c=A + 4) == bad
+    assert call(G=64) == uns and call(E=2000) == uns
+    assert call(ws=None) == P.IS_ERR_WORKSPACE and call(wsb=need - 1) == P.IS_ERR_WORKSPACE
+    assert call(M=0, ws=None, wsb=0) == P.IS_OK
+    assert lib.is_gemm_w4a8_floatscale_grouped_prepacked(A, A, A, A, None, 4, 300, 48, 1024, 128, A, A, need, None) == bad
+
+
 def test_noalloc_argument_validation():
     """The entry point without a workspace checks shapes and the size of its fixed scratch before any HIP call."""
     lib = P.load_library()

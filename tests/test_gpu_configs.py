@@ -227,3 +227,15 @@ def test_config4_mixtral_grouped(P, index, name):
     fs_ref, fs_mag = O.gemm_w4a8_floatscale_grouped(xq_r, sa_r, qw, sf, offsets, G)
     fs = host(P.is_gemm_w4a8_floatscale_grouped(xq, sa, dev(qw), dev(sf), dev(offsets), G)).astype(np.float64)
     assert np.all(np.abs(fs - fs_ref) <= 1e-2 * np.abs(fs_ref) + 2e-5 * fs_mag + 2.0 ** -24)
+    # the prepacked route, as bench.py times it (experts prepacked back to back, caller's workspace and output)
+    pk = P.is_prepack_w4_experts(dev(qw), dev(si), G)
+    ws = torch.empty(P.is_gemm_grouped_prepacked_workspace_bytes(E, M, N, K, G), dtype=torch.uint8, device="cuda:0")
+    outp = torch.empty((M, N), dtype=torch.float16, device="cuda:0")
+    P.is_gemm_w4a8_intscale_grouped_prepacked(xq, sa, pk, dev(cs), dev(offsets), 10, out=outp, workspace=ws)
+    gotp = host(outp).astype(np.float64)
+    assert np.all(np.abs(gotp - want) <= 2.0 ** -10 * np.abs(want) + 2.0 ** -24), name + " (prepacked)"
+    _, accp = P.is_gemm_w4a8_intscale_grouped_prepacked(xq, sa, pk, dev(cs), dev(offsets), 10, want_acc=True, workspace=ws)
+    assert np.array_equal(host(accp), acc_ref), "int32 accumulators (prepacked)"
+    fsp = host(P.is_gemm_w4a8_floatscale_grouped_prepacked(xq, sa, P.is_prepack_w4_experts(dev(qw), dev(sf), G),
+                                                           dev(offsets), workspace=ws)).astype(np.float64)
+    assert np.all(np.abs(fsp - fs_ref) <= 1e-2 * np.abs(fs_ref) + 2e-5 * fs_mag + 2.0 ** -24)

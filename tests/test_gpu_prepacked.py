@@ -293,6 +293,53 @@ def test_prepacked_tiled_linear_fp16(P, M, N, K):
     check_fs(host(P.is_linear_w4a8_floatscale_prepacked(dev(x), P.is_prepack_w4(dev(qw), dev(s), G))), fs)
 
 
+# mixture-of-experts form on prepacked experts: experts without rows, with a few rows (padded to a 16-row tile), with
+# several 128-row tiles, with exactly one full tile; ragged tile columns; a wide-scale expert among narrow ones
+@pytest.mark.parametrize("counts,N,K", [([5, 0, 17, 64, 1, 0, 33, 8], 48, 1024), ([0, 0, 3], 48, 512), ([130, 2], 48, 1024),
+                                        ([0, 300, 0, 129, 70], 520, 1024), ([128, 128, 128], 256, 2048),
+                                        ([0, 0, 0, 270], 48, 1024), ([257, 1, 1], 264, 4096), ([16, 15, 17, 1], 272, 128)])
+def test_prepacked_grouped_gemm(P, counts, N, K):
+    E = len(counts)
+    rng = np.random.default_rng(sum(counts) + N)
+    M = sum(counts)
+    off = np.zeros(E + 1, np.int32)
+    off[1:] = np.cumsum(counts)
+    xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+    sa = (rng.random(M) + 0.01).astype(np.float32)
+    q = np.stack([O.pack_int4(rng.integers(-8, 8, size=(N, K)).astype(np.int8)) for _ in range(E)])
+    IS = rng.integers(0, 1025, size=(E, N, K // G)).astype(np.int32)
+    IS[E - 1, 0, 0] = 2 ** 25                     # the last expert needs 32-bit multiplies, the others do not
+    s = (rng.random((E, N, K // G)) * 0.01).astype(np.float32)
+    c = (rng.random((E, N)) + 0.01).astype(np.float32)
+    acc_ref, out_ref = O.gemm_w4a8_intscale_grouped(xq, sa, q, IS, c, off, G, 10)
+    pk = P.is_prepack_w4_experts(dev(q), dev(IS), G)
+    ws = torch.full((P.is_gemm_grouped_prepacked_workspace_bytes(E, M, N, K, G),), 0xFF, dtype=torch.uint8, device="cuda:0")
+    for _ in range(2):                            # the workspace's contents do not matter
+        out, acc = P.is_gemm_w4a8_intscale_grouped_prepacked(dev(xq), dev(sa), pk, dev(c), dev(off), 10, want_acc=True,
+                                                             workspace=ws)
+        assert np.array_equal(host(acc), acc_ref)
+        assert np.array_equal(host(out), out_ref) or np.allclose(host(out).astype(np.float64), out_ref.astype(np.float64),
+                                                                 rtol=2e-3, atol=2.0 ** -24)
+    out2, _ = P.is_gemm_w4a8_intscale_grouped_prepacked(dev(xq), dev(sa), pk, dev(c), dev(off), 10)   # staged epilogue
+    assert np.allclose(host(out2).astype(np.float64), out_ref.astype(np.float64), rtol=2e-3, atol=2.0 ** -24)
+    fs_ref, fs_mag = O.gemm_w4a8_floatscale_grouped(xq, sa, q, s, off, G)
+    fs = host(P.is_gemm_w4a8_floatscale_grouped_prepacked(dev(xq), dev(sa), P.is_prepack_w4_experts(dev(q), dev(s), G),
+                                                          dev(off))).astype(np.float64)
+    assert np.all(np.abs(fs - fs_ref) <= 1e-2 * np.abs(fs_ref) + 2e-5 * fs_mag + 2.0 ** -24)
+
+
+def test_prepacked_grouped_empty(P):
+    E, N, K = 3, 48, 256
+    pk = P.is_prepack_w4_experts(torch.zeros((E, N, K // 2), dtype=torch.uint8, device="cuda:0"),
+                                 torch.ones((E, N, K // G), dtype=torch.int32, device="cuda:0"), G)
+    off = torch.zeros(E + 1, dtype=torch.int32, device="cuda:0")
+    out, _ = P.is_gemm_w4a8_intscale_grouped_prepacked(torch.empty((0, K), dtype=torch.int8, device="cuda:0"),
+                                                       torch.empty((0,), dtype=torch.float32, device="cuda:0"), pk, None,
+                                                       off, 10)
+    assert out.shape == (0, N)
+    assert P.is_gemm_grouped_prepacked_workspace_bytes(E, 0, N, K, G) == 0
+
+
 def test_prepacked_empty_and_unsupported(P):
     rng = np.random.default_rng(3)
     xq, qw, IS, s, sa, c = rand_quantised(rng, 1, 16, 128)
