@@ -265,6 +265,7 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
         const rsrc_t cres = make_rsrc(a.chan_scale, a.chan_scale ? (size_t)a.N * 4 : 0);
 #pragma unroll
         for (int i = 0; i < kCsPerThread; ++i) {
+            if (i > 0 && i * W * kWave >= cs_words) break;  // uniform: a workgroup seldom has more than a few tiles
             const int w = (int)threadIdx.x + i * W * kWave;
             cs_reg[i] = __int_as_float(
                 __builtin_amdgcn_raw_buffer_load_b32(cres, w < cs_words ? (t0 * 16 + w) * 4 : kOutOfRange, 0, 0));
@@ -306,6 +307,7 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
     }
 #pragma unroll
     for (int i = 0; i < kCsPerThread; ++i) {
+        if (i > 0 && i * W * kWave >= cs_words) break;
         const int w = (int)threadIdx.x + i * W * kWave;
         if (w < cs_words) lds_cs[w] = a.chan_scale ? cs_reg[i] : 1.0f;
     }
