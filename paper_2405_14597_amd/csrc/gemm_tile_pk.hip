@@ -13,7 +13,13 @@
 // Tiling.  A workgroup is 4 waves (1 x 4) on 128 token rows x 256 weight rows, one wave per SIMD, 256 registers per
 // wave; two workgroups share a CU (their 67 KB of LDS each allow it), so every SIMD holds two waves of DIFFERENT
 // workgroups: they meet no common barrier, drift apart by themselves, and one's unpacking and LDS waits fall under the
-// other's MFMAs.
+// other's MFMAs.  (A SIMD issues one instruction at a time over all its waves, so the second wave adds about a fifth,
+// not a factor of two: a workgroup alone on a CU runs at 1.7 times the rate of one that shares it.)
+//
+// Rounds.  The chip works on 2 x CUs tiles at a time.  When the tiles left for the last round are fewer than half the
+// CUs their K range is cut into parts, one workgroup each, and the last part of a tile to arrive adds the partial
+// tiles up (TileSplit below).  The mixture-of-experts form runs the same tile code on row tiles listed per expert
+// (TileGroups).
 //
 // Operand pipeline.  K advances in steps of 128 (one MFMA pair) through two LDS stages.  Both operands come in
 // layouts that are already the order the MFMA lanes want (weights: the prepacked 1 KB blocks of pk_common.h;
