@@ -339,21 +339,25 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
         // keeps one 64-bit address per row and output tensor in registers across the whole K loop.
         int first = 4 * kb * a.N + n;
         asm volatile("" : "+v"(first));
+        if constexpr (INT_SCALE) {
+            if (a.acc_out) {  // (the diagnostic export of the accumulators: one test per tile, not per output)
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (16 * t + 4 * kb + r < a.M) a.acc_out[first + (16 * t + r) * a.N] = v[t][r];
+            }
+        }
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int m = 16 * t + 4 * kb + r;
                 if (m < a.M) {
-                    const int at = first + (16 * t + r) * a.N;
                     float o;
-                    if constexpr (INT_SCALE) {
-                        o = (float)v[t][r] * sa[t][r] * cc;
-                        if (a.acc_out) a.acc_out[at] = v[t][r];
-                    } else {
-                        o = v[t][r] * sa[t][r];
-                    }
-                    a.out[at] = __float2half_rn(o);
+                    if constexpr (INT_SCALE) o = (float)v[t][r] * sa[t][r] * cc;
+                    else o = v[t][r] * sa[t][r];
+                    a.out[first + (16 * t + r) * a.N] = __float2half_rn(o);
                 }
             }
     };
