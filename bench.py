@@ -823,7 +823,7 @@ def moe_main(args):
                            roofline_frac=round(max(t_hbm, t_mfma) / (ms * 1e-3), 4)))
     tot_ms = sum(per.values())
     achieved = sum(alg_bytes(d) for d in data) / tot_ms / 1e6
-    kernel = "gemm_tile_grouped_pk_kernel<true>"
+    kernel = P.is_describe_grouped_prepacked(E, data[0]["M"], data[0]["N"], data[0]["K"], GROUP, True)[-1]
     roofline = dict(bound="hbm", kernel=kernel, achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4), traffic=measured_traffic(kernel, "moe"),
                     avg_launch_us=round(1e3 * tot_ms / len(data), 2),

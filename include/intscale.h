@@ -262,6 +262,9 @@ int is_gemm_w4a8_floatscale_grouped_prepacked(const int8_t* xq, const float* a_s
  * call rather than the GEMM call.  Writes a NUL-terminated string of at most names_len bytes.
  */
 int is_describe_prepacked(int M, int N, int K, int group, int int_scale, int fp16_in, char* names, size_t names_len);
+/* The same for the grouped prepacked calls (the tile shape depends on the rows per expert on average). */
+int is_describe_grouped_prepacked(int num_experts, int M_total, int N, int K, int group, int int_scale, char* names,
+                                  size_t names_len);
 
 /*
  * Mixture-of-experts form (Sec. 5.4 measures Mixtral 8x7B): one launch over `num_experts` weight sets.

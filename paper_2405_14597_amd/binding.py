@@ -56,6 +56,7 @@ EXPORTED_SYMBOLS = (
     "is_gemm_w4a8_intscale_grouped_prepacked",
     "is_gemm_w4a8_floatscale_grouped_prepacked",
     "is_describe_prepacked",
+    "is_describe_grouped_prepacked",
     "is_source_hash",
     "is_probe_stream_read",
     "is_probe_mfma_i8",
@@ -175,6 +176,8 @@ def load_library() -> ctypes.CDLL:
     lib.is_source_hash.restype = ctypes.c_char_p
     lib.is_describe_prepacked.argtypes = [ci, ci, ci, ci, ci, ci, ctypes.c_char_p, sz]
     lib.is_describe_prepacked.restype = ci
+    lib.is_describe_grouped_prepacked.argtypes = [ci, ci, ci, ci, ci, ci, ctypes.c_char_p, sz]
+    lib.is_describe_grouped_prepacked.restype = ci
     _lib = lib
     return lib
 
@@ -724,6 +727,14 @@ def is_describe_prepacked(M: int, N: int, K: int, group: int, int_scale: bool = 
     buf = ctypes.create_string_buffer(512)
     st = load_library().is_describe_prepacked(M, N, K, group, int(int_scale), int(fp16_in), buf, len(buf))
     _check("is_describe_prepacked", st)
+    return buf.value.decode().split("\n")
+
+
+def is_describe_grouped_prepacked(num_experts: int, M_total: int, N: int, K: int, group: int, int_scale: bool = True):
+    """The same for the grouped prepacked GEMM call."""
+    buf = ctypes.create_string_buffer(512)
+    st = load_library().is_describe_grouped_prepacked(num_experts, M_total, N, K, group, int(int_scale), buf, len(buf))
+    _check("is_describe_grouped_prepacked", st)
     return buf.value.decode().split("\n")
 
 

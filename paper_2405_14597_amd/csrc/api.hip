@@ -625,6 +625,17 @@ int is_describe_prepacked(int M, int N, int K, int group, int int_scale, int fp1
     return IS_OK;
 }
 
+int is_describe_grouped_prepacked(int num_experts, int M_total, int N, int K, int group, int int_scale, char* names,
+                                  size_t names_len) {
+    if (names == nullptr || names_len == 0) return IS_ERR_INVALID_ARG;
+    names[0] = '\0';
+    if (M_total < 1) return IS_ERR_INVALID_ARG;
+    const int shape = check_grouped_pk(num_experts, M_total, N, K, group);
+    if (shape != IS_OK) return shape;
+    gemm_tile_grouped_pk_kernel_names(num_experts, M_total, int_scale != 0, names, names_len);
+    return IS_OK;
+}
+
 // ---- fine-grained W8A8
 static int check_w8_shape(int M, int N, int K, int group) {
     if (M < 0 || N <= 0 || K <= 0 || group <= 0 || K % group != 0) return IS_ERR_INVALID_ARG;

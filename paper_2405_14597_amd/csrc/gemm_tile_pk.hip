@@ -48,8 +48,9 @@ constexpr int kTM = 128, kTN = 256;     // workgroup tile: token rows x weight r
 constexpr int kTThreads = 256;          // 4 waves, one per SIMD
 constexpr int kMS = 8, kNS = 4;         // 16-row sub-tiles per wave: token rows, weight rows
 // (the corrections take 512 bytes; their load writes a full kilobyte, the upper half zeros)
-constexpr int kABytes = kTM * 128, kBBytes = kTN * 64, kScBytes = kTN * 4, kC0Bytes = 1024;
-constexpr int kStage = kABytes + kBBytes + kScBytes + kC0Bytes;  // 34816
+constexpr int kBBytes = kTN * 64, kScBytes = kTN * 4, kC0Bytes = 1024;
+// One LDS stage of a tile of MS 16-row sub-tiles per wave (MS * 16 token rows): 34816 bytes at 128 rows, 26624 at 64
+constexpr int stage_bytes(int MS) { return MS * 16 * 128 + kBBytes + kScBytes + kC0Bytes; }
 constexpr int kXcdCount = 8;            // workgroup i is dispatched to XCD i % 8
 constexpr int kGroupRows = 8;           // tile rows of the block of tiles an XCD works on at a time
 
@@ -78,7 +79,7 @@ struct TileGroups {
     int32_t* table;              // [0] = entries in use, then 4 words per entry: expert, first 16-row tile, first row, rows
     size_t wstride, sstride;     // bytes from one expert's packed weights / scales to the next
 };
-constexpr int kPartWords = kTM * kTN;                      // one partial tile: 128 KB
+constexpr int kPartWords = kTM * kTN;                      // one partial tile of 128 rows: 128 KB
 constexpr size_t kCounterBytes = 2048;                     // up to 512 tiles in the last round
 constexpr size_t kPartialCap = (size_t)64 << 20;           // at most this much workspace for partial tiles
 constexpr int kMinPartSteps = 8;                           // K steps a part has at least
@@ -145,17 +146,30 @@ __global__ __launch_bounds__(256) void prepare_activations_grouped_pk_kernel(con
     if (blockIdx.x == 0 && blockIdx.y == 0)  // the tiled kernel's arrival counters start at zero
         for (int i = threadIdx.x; i < ncounters; i += 256) counters[i] = 0;
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-        int used = 0, base16 = 0;
-        for (int e = 0; e < tg.num_experts; ++e) {
-            const int lo = tg.row_offsets[e], rows = tg.row_offsets[e + 1] - lo;
-            for (int t = 0; t * kTM < rows && used < tg.slots; ++t, ++used) {
-                int32_t* entry = tg.table + 4 + 4 * used;
-                entry[0] = e;
-                entry[1] = base16 + t * (kTM / 16);
-                entry[2] = lo + t * kTM;
-                entry[3] = min(kTM, rows - t * kTM);
+        // Entries with the most rows first (the tiled kernel's cost grows with an entry's rows and workgroups start in
+        // grid order: the short ones then fill the gaps the long ones leave).  Only an expert's last entry can be
+        // short: the first pass lists every entry of more than 64 rows, the others the last entries of 33..64,
+        // 17..32 and 1..16 rows.
+        constexpr int tr = kTM;
+        int used = 0;
+        for (int pass = 0; pass < 4; ++pass) {
+            const int above = pass == 0 ? 64 : pass == 1 ? 32 : pass == 2 ? 16 : 0;
+            const int upto = pass == 0 ? tr : pass == 1 ? 64 : pass == 2 ? 32 : 16;
+            int base16 = 0;
+            for (int e = 0; e < tg.num_experts; ++e) {
+                const int lo = tg.row_offsets[e], rows = tg.row_offsets[e + 1] - lo;
+                const int nt = (rows + tr - 1) / tr;
+                for (int t = tr > upto ? max(nt - 1, 0) : 0; t < nt && used < tg.slots; ++t) {  // (full entries: tr rows)
+                    const int have = min(tr, rows - t * tr);
+                    if (have <= above || have > upto) continue;
+                    int32_t* entry = tg.table + 4 + 4 * used++;
+                    entry[0] = e;
+                    entry[1] = base16 + t * (tr / 16);
+                    entry[2] = lo + t * tr;
+                    entry[3] = have;
+                }
+                base16 += (rows + 15) >> 4;
             }
-            base16 += (rows + 15) >> 4;
         }
         tg.table[0] = used;
     }
@@ -255,10 +269,15 @@ typedef float v4f_t __attribute__((ext_vector_type(4)));
 
 // One output tile.  WIDE: 32-bit multiplies in the integer scale step (some scale does not fit 24 signed bits).
 // GROUPED: the mixture-of-experts form; `entry` is the workgroup's line of the tile table and `tile_n_g` its tile column.
-template <bool INT_SCALE, bool WIDE, bool GROUPED>
+// MS: 16-row token sub-tiles per wave (the tile has MS * 16 token rows).
+template <bool INT_SCALE, bool WIDE, bool GROUPED, int MS>
 __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restrict__ xp, const int32_t* __restrict__ c0,
                                         const TileSplit& sp, const TileGroups& tg, const int32_t* entry, int tile_n_g,
                                         unsigned char* smem) {
+    constexpr int TM = MS * 16, ABytes = TM * 128, Stage = stage_bytes(MS);
+    constexpr int RB = MS < 4 ? MS : 4;       // sub-tiles of a partial tile read at a time when parts are added up
+    constexpr int XL = MS >= 2 ? MS / 2 : 1;  // kilobyte loads of activations per wave and step
+    static_assert(MS == 1 || MS == 2 || MS == 4 || MS == 8, "the tile has 16, 32, 64 or 128 token rows");
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wn = __builtin_amdgcn_readfirstlane(tid / kWave);  // the wave's 64 weight rows of the tile's 256
@@ -267,7 +286,7 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
     // ---- which tile: XCD x (workgroups x, x + 8, ...) gets one contiguous range of linear tile numbers, and a range
     // walks the output in blocks of kGroupRows tile rows, column by column (shared operand tiles meet in that XCD's L2)
     const int tiles_n = (a.N + kTN - 1) / kTN;
-    const int tiles_m = (a.M + kTM - 1) / kTM;
+    const int tiles_m = (a.M + TM - 1) / TM;
     int tile_m = 0, tile_n;
     int part = 0, tail_tile = -1;  // a tile of the last round: which K part, which of the round's tiles
     if constexpr (GROUPED) {
@@ -297,9 +316,9 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
     const int n0 = tile_n * kTN;
     // the tile's token rows: first 16-row tile of the prepared activations, first row of the tensors, how many
     const int expert = GROUPED ? entry[0] : 0;
-    const int mt0 = GROUPED ? entry[1] : tile_m * (kTM / 16);
-    const int m0 = GROUPED ? entry[2] : tile_m * kTM;
-    const int m_rows = GROUPED ? entry[3] : min(kTM, a.M - m0);
+    const int mt0 = GROUPED ? entry[1] : tile_m * MS;
+    const int m0 = GROUPED ? entry[2] : tile_m * TM;
+    const int m_rows = GROUPED ? entry[3] : min(TM, a.M - m0);
     const int mt_end = mt0 + ((m_rows + 15) >> 4);  // 16-row tiles from here on are not this tile's (they read as zero)
     const uint8_t* wpack = a.wpack + (GROUPED ? (size_t)expert * tg.wstride : 0);
     const uint8_t* spack = a.spack + (GROUPED ? (size_t)expert * tg.sstride : 0);
@@ -312,9 +331,9 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
     const int s_end = tail_tile < 0 ? steps : ((part + 1) * steps) / sp.parts;
     const int m16 = GROUPED ? tg.padded16 : (a.M + 15) >> 4, n16 = (a.N + 15) >> 4;
 
-    // ---- loader roles.  Per step and wave: the 2 KB blocks of two 16-row token tiles (4 loads of 1 KB), the 1 KB
-    // blocks of four 16-row weight tiles; wave 0 also the step's 256 scales, wave 1 its 128 corrections.  Tiles past
-    // the end of a tensor lie outside its descriptor and read as zero.
+    // ---- loader roles.  Per step and wave: a quarter of the tile's 2 KB blocks of 16 token rows (XL loads of 1 KB),
+    // the 1 KB blocks of four 16-row weight tiles; wave 0 also the step's 256 scales, wave 1 the corrections of its
+    // token rows.  Tiles past the end of a tensor lie outside its descriptor and read as zero.
     const v4i xdesc = make_desc(xp, (size_t)m16 * steps * 2048);
     const v4i wdesc = make_desc(wpack, (size_t)n16 * steps * kPkBlockBytes);
     v4i adesc = make_desc(nullptr, 0);
@@ -327,30 +346,35 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
     } else if (wn == 1) {
         adesc = make_desc(c0, (size_t)m16 * steps * 64);
         const int mt = mt0 + (lane >> 2);
-        aux_voff = (lane < 32 && mt < mt_end) ? mt * steps * 64 + (lane & 3) * 16 : (int)0x80000000u;
+        aux_voff = (lane < 4 * MS && mt < mt_end) ? mt * steps * 64 + (lane & 3) * 16 : (int)0x80000000u;
         aux_step = 64;
     }
     // (the offsets of the 8 tile loads are a scalar each plus the lane's 16 bytes: kept in scalar registers and added
     // at the request; the whole offset has to travel in the vector offset, which is what the range check sees)
-    int x_soff[4], w_soff[4];
+    int x_soff[XL], w_soff[4];
+#pragma unroll
+    for (int i = 0; i < XL; ++i) {  // the wave's half blocks wn * XL + i of the tile's 2 * MS
+        const int mt = mt0 + ((wn * XL + i) >> 1);
+        x_soff[i] = mt < mt_end ? mt * steps * 2048 + ((wn * XL + i) & 1) * 1024 : (int)0x80000000u;
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int mt = mt0 + 2 * wn + (i >> 1);
-        x_soff[i] = mt < mt_end ? mt * steps * 2048 + (i & 1) * 1024 : (int)0x80000000u;
         const int nt = (n0 >> 4) + 4 * wn + i;
         w_soff[i] = nt < n16 ? nt * steps * kPkBlockBytes : (int)0x80000000u;
     }
     const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
-    const unsigned lds_x = wn * 4096, lds_w = kABytes + wn * 4096;
-    const unsigned lds_aux = kABytes + kBBytes + (wn == 1 ? kScBytes : 0);
+    const unsigned lds_x = wn * XL * 1024, lds_w = ABytes + wn * 4096;
+    const unsigned lds_aux = ABytes + kBBytes + (wn == 1 ? kScBytes : 0);
     const int g_begin = s_begin / spg;
     int rq_x = s_begin * 2048, rq_w = s_begin * kPkBlockBytes, rq_sub = s_begin - g_begin * spg;
     int rq_aux = s_begin * aux_step + g_begin * aux_group;
     auto request_step = [&](int t) {
-        const unsigned base = lds0 + (t & 1) * kStage;
+        const unsigned base = lds0 + (t & 1) * Stage;
         if (t < s_end) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) load_to_lds_b128(xdesc, base, lds_x + i * 1024, x_soff[i] + rq_x + lane * 16, 0);
+            for (int i = 0; i < XL; ++i)
+                if (MS >= 2 || wn < 2)  // (a 16-row tile has two half blocks: waves 0 and 1)
+                    load_to_lds_b128(xdesc, base, lds_x + i * 1024, x_soff[i] + rq_x + lane * 16, 0);
 #pragma unroll
             for (int i = 0; i < 4; ++i) load_to_lds_b128(wdesc, base, lds_w + i * 1024, w_soff[i] + rq_w + lane * 16, 0);
             if (wn < 2) load_to_lds_b128(adesc, base, lds_aux, aux_voff, rq_aux);
@@ -365,14 +389,14 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
     // ---- consumer roles: lane (li, kb) of MFMA 16x16x64 feeds row / column li and k chunk kb; its 4 results are
     // weight row li, token rows 4 kb .. + 3 of the sub-tile
     const int lane16 = lane * 16;
-    const int b_off = kABytes + wn * 4096 + lane16;
-    const int sc_off = kABytes + kBBytes + (wn * 64 + li) * 4;
-    const int ci_off = kABytes + kBBytes + kScBytes + kb * 16;
+    const int b_off = ABytes + wn * 4096 + lane16;
+    const int sc_off = ABytes + kBBytes + (wn * 64 + li) * 4;
+    const int ci_off = ABytes + kBBytes + kScBytes + kb * 16;
 
     using acc4 = typename std::conditional<INT_SCALE, v4i, v4f_t>::type;
-    acc4 acc[kMS][kNS];
+    acc4 acc[MS][kNS];
 #pragma unroll
-    for (int i = 0; i < kMS; ++i)
+    for (int i = 0; i < MS; ++i)
 #pragma unroll
         for (int j = 0; j < kNS; ++j)
 #pragma unroll
@@ -397,7 +421,7 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
         // finished reading the other stage, which the requests for step s + 1 now overwrite
         asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
         request_step(s + 1);
-        const unsigned char* st = smem + (s & 1) * kStage;
+        const unsigned char* st = smem + (s & 1) * Stage;
 
         // the wave's four weight sub-tiles of this step: unpack once, use for all eight token sub-tiles
         v4i bu[kNS][2];
@@ -419,9 +443,9 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
         af[0][1] = *reinterpret_cast<const v4i*>(st + 1024 + lane16);
         ci[0] = *reinterpret_cast<const v4i*>(st + ci_off);
 #pragma unroll
-        for (int i = 0; i < kMS; ++i) {
+        for (int i = 0; i < MS; ++i) {
             const int cur = i & 1, nxt = cur ^ 1;
-            if (i + 1 < kMS) {  // operands of the next token sub-tile, read while this one is multiplied
+            if (i + 1 < MS) {  // operands of the next token sub-tile, read while this one is multiplied
                 af[nxt][0] = *reinterpret_cast<const v4i*>(st + (i + 1) * 2048 + lane16);
                 af[nxt][1] = *reinterpret_cast<const v4i*>(st + (i + 1) * 2048 + 1024 + lane16);
                 ci[nxt] = *reinterpret_cast<const v4i*>(st + ci_off + (i + 1) * 64);
@@ -439,7 +463,7 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
             }
         }
 #pragma unroll
-        for (int j = 0; j < kNS; ++j) scale_into(acc[kMS - 1][j], part[(kMS - 1) & 1][j], scl[j]);
+        for (int j = 0; j < kNS; ++j) scale_into(acc[MS - 1][j], part[(MS - 1) & 1][j], scl[j]);
     }
 
     // ---- epilogue, once per output: FLOAT(acc) * s_a[m] * c[n] / alpha (Eq. (2)), or facc * s_a[m] (Eq. (1))
@@ -450,7 +474,7 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
         // reader's own XCD, so that no cache has to be written back or invalidated as a whole)
         v4i* mine = reinterpret_cast<v4i*>(sp.partials + ((size_t)tail_tile * sp.parts + part) * kPartWords) + tid;
 #pragma unroll
-        for (int i = 0; i < kMS; ++i)
+        for (int i = 0; i < MS; ++i)
 #pragma unroll
             for (int j = 0; j < kNS; ++j) {
                 v4i bits4;
@@ -459,7 +483,10 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
                     if constexpr (INT_SCALE) bits4[r] = acc[i][j][r];
                     else bits4[r] = __float_as_int(acc[i][j][r]);
                 }
-                asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(mine + (i * kNS + j) * kTThreads), "v"(bits4)
+                // (a store of more than 8 bytes reads its data registers up to two cycles after it issues, and the
+                // compiler, which inserts the wait for its own stores, does not see one inside an asm statement:
+                // without the two idle cycles the next address computation may land in the first data registers)
+                asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(mine + (i * kNS + j) * kTThreads), "v"(bits4)
                              : "memory");
             }
         // every wave's partial sums have been written through before the tile's counter is raised
@@ -474,7 +501,7 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
         if (arrived != sp.parts - 1) return;
         // the last part to arrive: all parts are in the workspace; add them in part order, whoever came last
 #pragma unroll
-        for (int i = 0; i < kMS; ++i)
+        for (int i = 0; i < MS; ++i)
 #pragma unroll
             for (int j = 0; j < kNS; ++j)
 #pragma unroll
@@ -482,10 +509,10 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
         for (int q = 0; q < sp.parts; ++q) {
             const v4i* src = reinterpret_cast<const v4i*>(sp.partials + ((size_t)tail_tile * sp.parts + q) * kPartWords) + tid;
 #pragma unroll
-            for (int i = 0; i < kMS; i += 4) {  // 16 loads of 16 bytes in flight per lane (the operand registers are free now)
-                v4i got[4][kNS];
+            for (int i = 0; i < MS; i += RB) {  // up to 16 loads of 16 bytes in flight per lane (the operand registers are free now)
+                v4i got[RB][kNS];
 #pragma unroll
-                for (int ii = 0; ii < 4; ++ii)
+                for (int ii = 0; ii < RB; ++ii)
 #pragma unroll
                     for (int j = 0; j < kNS; ++j)
                         asm volatile("global_load_dwordx4 %0, %1, off sc1"
@@ -493,15 +520,14 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
                                      : "v"(src + ((i + ii) * kNS + j) * kTThreads)
                                      : "memory");
                 // (the results pass through the wait, so that nothing is scheduled to use them before it)
-                asm volatile("s_waitcnt vmcnt(0)"
-                             : "+v"(got[0][0]), "+v"(got[0][1]), "+v"(got[0][2]), "+v"(got[0][3]), "+v"(got[1][0]),
-                               "+v"(got[1][1]), "+v"(got[1][2]), "+v"(got[1][3]), "+v"(got[2][0]), "+v"(got[2][1]),
-                               "+v"(got[2][2]), "+v"(got[2][3]), "+v"(got[3][0]), "+v"(got[3][1]), "+v"(got[3][2]),
-                               "+v"(got[3][3])
-                             :
-                             : "memory");
 #pragma unroll
-                for (int ii = 0; ii < 4; ++ii)
+                for (int ii = 0; ii < RB; ++ii)  // (the first of these waits, the others only tie their registers)
+                    asm volatile("s_waitcnt vmcnt(0)"
+                                 : "+v"(got[ii][0]), "+v"(got[ii][1]), "+v"(got[ii][2]), "+v"(got[ii][3])
+                                 :
+                                 : "memory");
+#pragma unroll
+                for (int ii = 0; ii < RB; ++ii)
 #pragma unroll
                     for (int j = 0; j < kNS; ++j)
 #pragma unroll
@@ -520,9 +546,9 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
     const bool staged = (a.N & 7) == 0 && a.acc_out == nullptr;
     constexpr int kPitch = 264;  // halves per LDS row: 256 + 8, so that rows keep 16-byte alignment
     __half* otile = reinterpret_cast<__half*>(smem);
-    float sa[kMS][4];
+    float sa[MS][4];
 #pragma unroll
-    for (int i = 0; i < kMS; ++i)
+    for (int i = 0; i < MS; ++i)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int ml = i * 16 + 4 * kb + r;
@@ -538,7 +564,7 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
             c *= inv_alpha;
         }
 #pragma unroll
-        for (int i = 0; i < kMS; ++i)
+        for (int i = 0; i < MS; ++i)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int ml = i * 16 + 4 * kb + r;
@@ -561,7 +587,7 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
         const int chunk = tid & 31;  // 8 outputs
         if (chunk * 8 < n_rows) {
 #pragma unroll
-            for (int pass = 0; pass < kTM / 8; ++pass) {
+            for (int pass = 0; pass < TM / 8; ++pass) {
                 const int ml = pass * 8 + (tid >> 5);
                 if (ml < m_rows)
                     *reinterpret_cast<uint4*>(a.out + (size_t)(m0 + ml) * a.N + n0 + chunk * 8) =
@@ -580,15 +606,30 @@ __global__ __launch_bounds__(kTThreads) __attribute__((amdgpu_waves_per_eu(2, 2)
     const TileGroups none{};
     if constexpr (INT_SCALE) {
         const int flags = *reinterpret_cast<const int32_t*>(a.spack);
-        if (flags & kPkFlagWide) tile_pk<true, true, false>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
-        else tile_pk<true, false, false>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
+        if (flags & kPkFlagWide) tile_pk<true, true, false, kMS>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
+        else tile_pk<true, false, false, kMS>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
     } else {
-        tile_pk<false, false, false>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
+        tile_pk<false, false, false, kMS>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
     }
 }
 
 // Mixture-of-experts form: workgroup b takes table entry b / (tile columns) and tile column b % (tile columns); the
-// entries in use come first, so the workgroups without one sit at the end of the grid and leave at once.
+// entries in use come first, so the workgroups without one sit at the end of the grid and leave at once.  An entry is
+// up to 128 token rows of one expert; a wave's instructions per K step are a fixed share (its weights' unpacking, the
+// requests, the bookkeeping) plus a share per 16 token rows, so the entry's rows pick the instance: 16, 32, 64 or 128.
+template <bool INT_SCALE, int MS>
+__device__ __forceinline__ void grouped_tile(const PkArgs& a, const int8_t* __restrict__ xp, const int32_t* __restrict__ c0,
+                                             const TileSplit& sp, const TileGroups& tg, const int32_t* entry, int tile_n,
+                                             unsigned char* smem) {
+    if constexpr (INT_SCALE) {
+        const int flags = *reinterpret_cast<const int32_t*>(a.spack + (size_t)entry[0] * tg.sstride);  // this expert's
+        if (flags & kPkFlagWide) tile_pk<true, true, true, MS>(a, xp, c0, sp, tg, entry, tile_n, smem);
+        else tile_pk<true, false, true, MS>(a, xp, c0, sp, tg, entry, tile_n, smem);
+    } else {
+        tile_pk<false, false, true, MS>(a, xp, c0, sp, tg, entry, tile_n, smem);
+    }
+}
+
 template <bool INT_SCALE>
 __global__ __launch_bounds__(kTThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_tile_grouped_pk_kernel(
     PkArgs a, const int8_t* __restrict__ xp, const int32_t* __restrict__ c0, TileGroups tg, TileSplit sp) {
@@ -599,13 +640,11 @@ __global__ __launch_bounds__(kTThreads) __attribute__((amdgpu_waves_per_eu(2, 2)
     if (slot >= tg.table[0]) return;  // uniform over the workgroup, before any barrier
     const int32_t* entry = tg.table + 4 + 4 * slot;
     const int tile_n = tile - slot * tiles_n;
-    if constexpr (INT_SCALE) {
-        const int flags = *reinterpret_cast<const int32_t*>(a.spack + (size_t)entry[0] * tg.sstride);  // this expert's
-        if (flags & kPkFlagWide) tile_pk<true, true, true>(a, xp, c0, sp, tg, entry, tile_n, smem_tpk);
-        else tile_pk<true, false, true>(a, xp, c0, sp, tg, entry, tile_n, smem_tpk);
-    } else {
-        tile_pk<false, false, true>(a, xp, c0, sp, tg, entry, tile_n, smem_tpk);
-    }
+    const int rows = entry[3];
+    if (rows > 64) grouped_tile<INT_SCALE, 8>(a, xp, c0, sp, tg, entry, tile_n, smem_tpk);
+    else if (rows > 32) grouped_tile<INT_SCALE, 4>(a, xp, c0, sp, tg, entry, tile_n, smem_tpk);
+    else if (rows > 16) grouped_tile<INT_SCALE, 2>(a, xp, c0, sp, tg, entry, tile_n, smem_tpk);
+    else grouped_tile<INT_SCALE, 1>(a, xp, c0, sp, tg, entry, tile_n, smem_tpk);
 }
 
 size_t xp_bytes(int M, int K) { return pad256((size_t)((M + 15) / 16) * 16 * K); }
@@ -681,7 +720,7 @@ hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace,
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const size_t smem = 2 * (size_t)kStage;
+    const size_t smem = 2 * (size_t)stage_bytes(kMS);
     const int tiles = sp.whole + sp.rem * sp.parts;  // workgroups
     int device = -1;
     (void)hipGetDevice(&device);
@@ -705,7 +744,8 @@ hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace,
 }
 
 // ---- mixture-of-experts form
-// workspace = [prepared activations, every expert padded to whole 16-row tiles | corrections | table of 128-row tiles]
+// workspace = [prepared activations, every expert padded to whole 16-row tiles | corrections | table of row tiles |
+//              arrival counters and partial tiles when the K range is cut]
 // K parts per tile of the grouped form: when all the tiles there can be fit the chip at once several times over
 static int grouped_parts(int E, int M, int N, int K) {
     const long long tiles = ((long long)(M + kTM - 1) / kTM + E) * ((N + kTN - 1) / kTN);
@@ -721,7 +761,28 @@ size_t gemm_tile_grouped_pk_workspace_bytes(int E, int M, int N, int K) {
     const size_t tiles = slots * ((N + kTN - 1) / kTN);
     const int parts = grouped_parts(E, M, N, K);
     return pad256(padded16 * 16 * K) + pad256(padded16 * (K / 128) * 64) + pad256((4 + 4 * slots) * 4) +
-           (parts > 1 ? pad256(tiles * 4) + tiles * parts * kPartWords * 4 : 0);
+           (parts > 1 ? pad256(tiles * 4) + tiles * parts * (size_t)kPartWords * 4 : 0);
+}
+
+void gemm_tile_grouped_pk_kernel_names(int E, int M, bool int_scale, char* buf, size_t len) {
+    snprintf(buf, len, "prepare_activations_grouped_pk_kernel\ngemm_tile_grouped_pk_kernel<%s>", int_scale ? "true" : "false");
+}
+
+template <typename Kernel>
+static hipError_t launch_grouped_instance(Kernel kernel, int which, size_t smem, const PkArgs& a, const int8_t* xp,
+                                          const int32_t* c0, const TileGroups& tg, const TileSplit& sp, int grid,
+                                          hipStream_t stream) {
+    int device = -1;
+    (void)hipGetDevice(&device);
+    static bool raised[2][64] = {};
+    if (!(device >= 0 && device < 64 && raised[which][device])) {
+        hipError_t r = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (r != hipSuccess) return r;
+        if (device >= 0 && device < 64) raised[which][device] = true;
+    }
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kTThreads), smem, stream, a, xp, c0, tg, sp);
+    return hipGetLastError();
 }
 
 hipError_t launch_gemm_tile_grouped_pk(const PkArgs& a, const int32_t* row_offsets, int E, size_t wstride,
@@ -751,27 +812,10 @@ hipError_t launch_gemm_tile_grouped_pk(const PkArgs& a, const int32_t* row_offse
                        dim3(256), 0, stream, a.xq, a.K, tg, xp, c0, sp.counters, sp.rem);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const size_t smem = 2 * (size_t)kStage;
     const int grid = tiles * sp.parts;
-    int device = -1;
-    (void)hipGetDevice(&device);
-    static bool raised[2][64] = {};
-    auto raise = [&](const void* kern, int which) -> hipError_t {
-        if (device >= 0 && device < 64 && raised[which][device]) return hipSuccess;
-        hipError_t r = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (r == hipSuccess && device >= 0 && device < 64) raised[which][device] = true;
-        return r;
-    };
-    if (int_scale) {
-        e = raise(reinterpret_cast<const void*>(gemm_tile_grouped_pk_kernel<true>), 0);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(gemm_tile_grouped_pk_kernel<true>, dim3(grid), dim3(kTThreads), smem, stream, a, xp, c0, tg, sp);
-    } else {
-        e = raise(reinterpret_cast<const void*>(gemm_tile_grouped_pk_kernel<false>), 1);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(gemm_tile_grouped_pk_kernel<false>, dim3(grid), dim3(kTThreads), smem, stream, a, xp, c0, tg, sp);
-    }
-    return hipGetLastError();
+    const size_t smem = 2 * (size_t)stage_bytes(kMS);
+    return int_scale ? launch_grouped_instance(gemm_tile_grouped_pk_kernel<true>, 0, smem, a, xp, c0, tg, sp, grid, stream)
+                     : launch_grouped_instance(gemm_tile_grouped_pk_kernel<false>, 1, smem, a, xp, c0, tg, sp, grid, stream);
 }
 
 }  // namespace intscale

@@ -83,5 +83,6 @@ hipError_t launch_gemm_tile_grouped_pk(const PkArgs& a, const int32_t* row_offse
                                        size_t sstride, bool int_scale, void* workspace, hipStream_t stream);
 // The kernels launch_gemm_tile_pk runs, in order, as a kernel trace names them, separated by '\n'.
 void gemm_tile_pk_kernel_names(int K, bool int_scale, bool fp16_in, char* buf, size_t len);
+void gemm_tile_grouped_pk_kernel_names(int E, int M, bool int_scale, char* buf, size_t len);
 
 }  // namespace intscale

@@ -231,6 +231,11 @@ def test_describe_prepacked_names_the_kernels():
     buf = ctypes.create_string_buffer(8)
     assert lib.is_describe_prepacked(1, 16, 256, 128, 1, 0, buf, 8) == P.IS_OK and len(buf.value) <= 7   # truncated, terminated
     assert lib.is_describe_prepacked(1, 16, 256, 128, 1, 0, None, 8) == P.IS_ERR_INVALID_ARG
+    grp = P.is_describe_grouped_prepacked(8, 1024, 14336, 4096, 128, True)
+    assert grp == ["prepare_activations_grouped_pk_kernel", "gemm_tile_grouped_pk_kernel<true>"]
+    assert P.is_describe_grouped_prepacked(8, 1024, 14336, 4096, 128, False)[1] == "gemm_tile_grouped_pk_kernel<false>"
+    assert lib.is_describe_grouped_prepacked(0, 16, 256, 128, 128, 1, buf, 8) == P.IS_ERR_INVALID_ARG
+    assert lib.is_describe_grouped_prepacked(2, 16, 256, 128, 64, 1, buf, 8) == P.IS_ERR_UNSUPPORTED
 
 
 def test_library_carries_the_digest_of_its_sources():

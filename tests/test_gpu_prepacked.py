@@ -294,10 +294,13 @@ def test_prepacked_tiled_linear_fp16(P, M, N, K):
 
 
 # mixture-of-experts form on prepacked experts: experts without rows, with a few rows (padded to a 16-row tile), with
-# several 128-row tiles, with exactly one full tile; ragged tile columns; a wide-scale expert among narrow ones
+# several row tiles, with exactly one or two full tiles; ragged tile columns; a wide-scale expert among narrow ones.  The
+# row counts cover the kernel's four instances per table entry (1..16, 17..32, 33..64, 65..128 rows), alone and with the
+# K range cut into parts (K >= 2048 here).
 @pytest.mark.parametrize("counts,N,K", [([5, 0, 17, 64, 1, 0, 33, 8], 48, 1024), ([0, 0, 3], 48, 512), ([130, 2], 48, 1024),
                                         ([0, 300, 0, 129, 70], 520, 1024), ([128, 128, 128], 256, 2048),
-                                        ([0, 0, 0, 270], 48, 1024), ([257, 1, 1], 264, 4096), ([16, 15, 17, 1], 272, 128)])
+                                        ([0, 0, 0, 270], 48, 1024), ([257, 1, 1], 264, 4096), ([16, 15, 17, 1], 272, 128),
+                                        ([400], 48, 1024), ([700, 500], 264, 512), ([0, 900], 48, 2048)])
 def test_prepacked_grouped_gemm(P, counts, N, K):
     E = len(counts)
     rng = np.random.default_rng(sum(counts) + N)
