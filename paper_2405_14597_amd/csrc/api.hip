@@ -486,7 +486,7 @@ static int check_grouped_pk(int E, int M, int N, int K, int group) {
     if (E <= 0 || M < 0) return IS_ERR_INVALID_ARG;
     const int shape = check_pk_shape(N, K, group);
     if (shape != IS_OK) return shape;
-    if (E > 1024 || M > (1 << 20)) return IS_ERR_UNSUPPORTED;
+    if (E > kPkMaxExperts || M > (1 << 20)) return IS_ERR_UNSUPPORTED;
     if (((long long)(M + 15) / 16 + E) * 16 * K >= (1LL << 31)) return IS_ERR_UNSUPPORTED;  // 32-bit offsets
     return IS_OK;
 }

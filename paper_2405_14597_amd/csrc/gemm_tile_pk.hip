@@ -145,6 +145,12 @@ __global__ __launch_bounds__(256) void prepare_activations_grouped_pk_kernel(con
                                                                              int ncounters) {
     if (blockIdx.x == 0 && blockIdx.y == 0)  // the tiled kernel's arrival counters start at zero
         for (int i = threadIdx.x; i < ncounters; i += 256) counters[i] = 0;
+    // (the first workgroup keeps the row offsets in LDS: the table is built by one thread, four passes over them)
+    __shared__ int32_t offs[kPkMaxExperts + 1];
+    if (blockIdx.x == 0 && blockIdx.y == 0) {
+        for (int i = threadIdx.x; i <= tg.num_experts; i += 256) offs[i] = tg.row_offsets[i];
+        __syncthreads();
+    }
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
         // Entries with the most rows first (the tiled kernel's cost grows with an entry's rows and workgroups start in
         // grid order: the short ones then fill the gaps the long ones leave).  Only an expert's last entry can be
@@ -157,7 +163,7 @@ __global__ __launch_bounds__(256) void prepare_activations_grouped_pk_kernel(con
             const int upto = pass == 0 ? tr : pass == 1 ? 64 : pass == 2 ? 32 : 16;
             int base16 = 0;
             for (int e = 0; e < tg.num_experts; ++e) {
-                const int lo = tg.row_offsets[e], rows = tg.row_offsets[e + 1] - lo;
+                const int lo = offs[e], rows = offs[e + 1] - lo;
                 const int nt = (rows + tr - 1) / tr;
                 for (int t = tr > upto ? max(nt - 1, 0) : 0; t < nt && used < tg.slots; ++t) {  // (full entries: tr rows)
                     const int have = min(tr, rows - t * tr);

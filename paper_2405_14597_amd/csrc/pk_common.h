@@ -22,6 +22,7 @@ namespace intscale {
 constexpr int kPkHeaderBytes = 256;
 constexpr int kPkFlagWide = 1, kPkFlagFloat = 2;
 constexpr int kPkBlockBytes = 1024;
+constexpr int kPkMaxExperts = 1024;  // weight sets of the grouped form at most
 
 inline size_t pk_weight_bytes(int N, int K) { return (size_t)((N + 15) / 16) * (size_t)(K / 128) * kPkBlockBytes; }
 inline size_t pk_scale_bytes(int N, int K, int group) {
