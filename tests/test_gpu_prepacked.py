@@ -331,6 +331,35 @@ def test_prepacked_grouped_gemm(P, counts, N, K):
     assert np.all(np.abs(fs - fs_ref) <= 1e-2 * np.abs(fs_ref) + 2e-5 * fs_mag + 2.0 ** -24)
 
 
+def test_prepacked_grouped_random_shapes_match_the_canonical_call(P):
+    """Many random expert row counts (all four row-count instances of the kernel, K ranges cut or not, a wide-scale expert now
+    and then), each twice on a workspace of arbitrary contents: the accumulators of the prepacked grouped call against
+    those of the canonical grouped call, which the tests above and test_gpu_configs.py hold to the oracle."""
+    rng = np.random.default_rng(20240597)
+    for case in range(120):
+        E = int(rng.integers(1, 13))
+        counts = rng.integers(0, [20, 70, 140, 300][int(rng.integers(0, 4))] + 1, size=E)
+        if counts.sum() == 0:
+            counts[0] = 5
+        M = int(counts.sum())
+        N = int(rng.choice([16, 48, 200, 256, 264, 520, 1024]))
+        K = int(rng.choice([128, 256, 1024, 2048, 4096]))
+        off = torch.tensor(np.concatenate([[0], np.cumsum(counts)]).astype(np.int32), device="cuda:0")
+        q = torch.randint(0, 256, (E, N, K // 2), dtype=torch.uint8, device="cuda:0")
+        si = torch.randint(0, 1025, (E, N, K // G), dtype=torch.int32, device="cuda:0")
+        if rng.random() < 0.3:
+            si[int(rng.integers(0, E)), 0, 0] = 2 ** 25
+        xq = torch.randint(-128, 128, (M, K), dtype=torch.int8, device="cuda:0")
+        sa = torch.rand(M, device="cuda:0") + 0.1
+        _, ref = P.is_gemm_w4a8_intscale_grouped(xq, sa, q, si, None, off, G, 10, want_acc=True)
+        pk = P.is_prepack_w4_experts(q, si, G)
+        ws = torch.empty(max(16, P.is_gemm_grouped_prepacked_workspace_bytes(E, M, N, K, G)), dtype=torch.uint8, device="cuda:0")
+        for _ in range(2):
+            ws.random_(0, 256)
+            _, acc = P.is_gemm_w4a8_intscale_grouped_prepacked(xq, sa, pk, None, off, 10, want_acc=True, workspace=ws)
+            assert torch.equal(acc, ref), f"case {case}: rows per expert {counts.tolist()}, N {N}, K {K}"
+
+
 def test_prepacked_grouped_empty(P):
     E, N, K = 3, 48, 256
     pk = P.is_prepack_w4_experts(torch.zeros((E, N, K // 2), dtype=torch.uint8, device="cuda:0"),
