@@ -569,7 +569,7 @@ def w8a8_main(args):
     speedup = fs_detail = None
     if not args.no_floatscale:
         n = max(3, args.steps // 2)
-        _, per_is = run(True, False, n, 2)
+        per_is = per
         _, per_fs = run(False, False, n, 2)
         fs_detail = {f"M{M}": round(per_fs[M] / per_is[M], 4) for M in MS}
         speedup = sum(per_fs.values()) / sum(per_is.values())
@@ -784,29 +784,50 @@ def moe_main(args):
             P.is_gemm_w4a8_floatscale_grouped(d["xq"], d["sa"], d["q"][l], d["sf"][l], d["off"], GROUP, out=d["out"],
                                               workspace=d["ws"])
 
+    replays = {}
+
+    def replay_of(d, int_scale, with_quant, canonical):
+        """The L calls of one linear (one per set of expert weights) as one HIP graph (eager with --no-graph)."""
+        key = (d["name"], int_scale, with_quant, canonical)
+        if key not in replays:
+            def calls():
+                for l in range(L):
+                    if with_quant:
+                        quant(d)
+                    gemm(d, l, int_scale, canonical)
+            if args.no_graph:
+                replays[key] = calls
+            else:
+                calls()                # every buffer is touched before capture
+                torch.cuda.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    calls()
+                replays[key] = g.replay
+        return replays[key]
+
     def run(int_scale, with_quant, steps, warmup, canonical=False):
         per = {d["name"]: 0.0 for d in data}
+        fns = [replay_of(d, int_scale, with_quant, canonical) for d in data]
         for it in range(warmup + steps):
             if it == warmup:
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
-            for d in data:
-                for l in range(L):
-                    if with_quant:
-                        quant(d)
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
-                    gemm(d, l, int_scale, canonical)
-                    e1.record()
-                    if it >= warmup:
-                        d.setdefault("marks", []).append((e0, e1))
+            for d, fn in zip(data, fns):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fn()
+                e1.record()
+                if it >= warmup:
+                    d.setdefault("marks", []).append((e0, e1))
         torch.cuda.synchronize()
         sec = (time.perf_counter() - t0) / steps
         for d in data:
             per[d["name"]] = sum(a.elapsed_time(b) for a, b in d.pop("marks")) / (steps * L)
         return sec, per
 
-    sec_per_step, per = run(True, True, args.steps, args.warmup)
+    sec_per_step, _ = run(True, True, args.steps, args.warmup)     # the step: quantiser + grouped GEMM per linear
+    _, per = run(True, False, max(3, args.steps // 2), 2)          # the grouped GEMM calls alone (per-shape figures)
 
     def alg_bytes(d):  # every expert's weights and scales once, the routed rows once
         return E * (d["N"] * d["K"] // 2 + 4 * d["N"] * (d["K"] // GROUP) + 4 * d["N"]) + d["M"] * d["K"] + 2 * d["M"] * d["N"] + 4 * d["M"]
@@ -834,7 +855,7 @@ def moe_main(args):
     speedup = fs_detail = canon = None
     if not args.no_floatscale:
         n = max(3, args.steps // 2)
-        _, per_is = run(True, False, n, 2)
+        per_is = per
         _, per_fs = run(False, False, n, 2)
         speedup = sum(per_fs.values()) / sum(per_is.values())
         fs_detail = {k: round(per_fs[k] / per_is[k], 4) for k in per_is}
@@ -874,7 +895,8 @@ def moe_main(args):
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"mixtral-8x7b expert FFN (w1, w3, w2) as grouped GEMMs over {E} experts, {TOKENS} tokens top-{TOPK} "
                                f"uniform router, W4 group-128 x A8 per-token, alpha=2^{ALPHA_LOG2}, {L} sets of expert weights",
-                   "layout": "experts prepacked offline (is_prepack_w4)", "launch": "eager", "scale_mode": "norm"},
+                   "layout": "experts prepacked offline (is_prepack_w4)",
+                   "launch": "eager" if args.no_graph else "hip-graph", "scale_mode": "norm"},
         "tops": round(step_ops / sec_per_step / 1e12, 3), "hbm_frac": round(value / HBM_PEAK_GBS, 4),
         "speedup_vs_floatscale": None if speedup is None else round(speedup, 4),
         "floatscale_over_intscale_by_shape": fs_detail, "canonical_us_by_shape": canon, "roofline": roofline, "measured_peaks": peaks,
