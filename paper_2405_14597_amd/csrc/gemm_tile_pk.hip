@@ -145,12 +145,11 @@ __global__ __launch_bounds__(256) void prepare_activations_grouped_pk_kernel(con
                                                                              int ncounters) {
     if (blockIdx.x == 0 && blockIdx.y == 0)  // the tiled kernel's arrival counters start at zero
         for (int i = threadIdx.x; i < ncounters; i += 256) counters[i] = 0;
-    // (the first workgroup keeps the row offsets in LDS: the table is built by one thread, four passes over them)
+    // (every workgroup fetches the row offsets into LDS in one round trip: the search for its expert below, and the
+    // table, which one thread builds in four passes, would otherwise wait for global memory expert by expert)
     __shared__ int32_t offs[kPkMaxExperts + 1];
-    if (blockIdx.x == 0 && blockIdx.y == 0) {
-        for (int i = threadIdx.x; i <= tg.num_experts; i += 256) offs[i] = tg.row_offsets[i];
-        __syncthreads();
-    }
+    for (int i = threadIdx.x; i <= tg.num_experts; i += 256) offs[i] = tg.row_offsets[i];
+    __syncthreads();
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
         // Entries with the most rows first (the tiled kernel's cost grows with an entry's rows and workgroups start in
         // grid order: the short ones then fill the gaps the long ones leave).  Only an expert's last entry can be
@@ -185,7 +184,7 @@ __global__ __launch_bounds__(256) void prepare_activations_grouped_pk_kernel(con
     const int pt = blockIdx.x;
     int row0 = 0, rows = 0;
     for (int e = 0, base16 = 0; e < tg.num_experts; ++e) {
-        const int lo = tg.row_offsets[e], me = tg.row_offsets[e + 1] - lo;
+        const int lo = offs[e], me = offs[e + 1] - lo;
         const int n16 = (me + 15) >> 4;
         if (pt < base16 + n16) {
             row0 = lo + 16 * (pt - base16);
