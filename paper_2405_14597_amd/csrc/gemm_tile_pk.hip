@@ -19,7 +19,8 @@
 // Rounds.  The chip works on 2 x CUs tiles at a time.  When the tiles left for the last round are fewer than half the
 // CUs their K range is cut into parts, one workgroup each, and the last part of a tile to arrive adds the partial
 // tiles up (TileSplit below).  The mixture-of-experts form runs the same tile code on row tiles listed per expert
-// (TileGroups).
+// (TileGroups), in four instances for tiles of up to 16, 32, 64 and 128 token rows: a wave's instructions per K step
+// are a fixed share plus a share per 16 token rows, and an expert's last tile is often a dozen rows.
 //
 // Operand pipeline.  K advances in steps of 128 (one MFMA pair) through two LDS stages.  Both operands come in
 // layouts that are already the order the MFMA lanes want (weights: the prepacked 1 KB blocks of pk_common.h;
