@@ -26,6 +26,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import gc
 import os
 import sys
 import time
@@ -137,6 +138,10 @@ class Segment:
 def main():
     global TRAFFIC_REQUIRED
     args = parse_args()
+    # The interpreter's cyclic collector stays off for the whole run (reference counting frees everything here): a full
+    # collection takes some 20 ms with this many live objects, it fell into the same place of the timed loop in every
+    # run, and the GPU ran dry there (seen as one step of one segment 25 times longer than the others).
+    gc.disable()
     TRAFFIC_REQUIRED = not args.no_traffic
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (one process, one MI355X); run with --gpus 1. "
@@ -265,10 +270,14 @@ def family_main(args):
     def timed_pass(segs, steps, warmup):
         run_steps(segs, warmup, False)
         torch.cuda.synchronize()
+        gc.collect()
         t0 = time.perf_counter()
         run_steps(segs, steps, True)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
+        if os.environ.get("BENCH_TRACE_STEPS"):  # per step and segment, to stderr: where a one-off stall fell
+            for s in segs:
+                print(s.name, " ".join(f"{a.elapsed_time(b):.3f}" for a, b in s.pending), file=sys.stderr)
         for s in segs:
             s.elapsed_ms = sum(a.elapsed_time(b) for a, b in s.pending)
             s.count = len(s.pending) * s.launches
