@@ -56,7 +56,7 @@ def parse_args():
                     help="do not look up the measured HBM traffic in profiles/ (roofline.traffic = null); without this "
                          "flag a missing figure is an error")
     ap.add_argument("--workload", default="llama2_70b",
-                    choices=("llama2_70b", "llama2_7b", "llama3_8b", "moe", "w8a8", "producers"))
+                    choices=("llama2_70b", "llama2_7b", "llama3_8b", "moe", "w8a8", "producers", "gate_up"))
     return ap.parse_args()
 
 
@@ -155,6 +155,8 @@ def main():
         return w8a8_main(args)
     if args.workload == "moe":
         return moe_main(args)
+    if args.workload == "gate_up":
+        return gate_up_main(args)
     return producers_main(args)
 
 
@@ -726,6 +728,147 @@ def producers_main(args):
         "config": {"workload": f"llama3-8b producers: RMSNorm+quant on [M,{K}], SiLU*up+quant on [M,2*{inter}], "
                                f"M in {list(MS)}; value = the M = {big} pair", "launch": "eager"},
         "roofline": roofline, "measured_peaks": peaks, "cpu_baseline": cpu, "shapes": shapes,
+    }
+    print(json.dumps(line))
+
+
+def gate_up_main(args):
+    """The front half of a gated feed-forward block, from the quantised input of gate_up to the quantised input of
+    `down`, two ways on the prepacked route: (fused) the gate_up GEMM with SiLU(gate) * up as its epilogue, then the plain
+    activation quantiser on [M, inter]; (unfused) the plain GEMM to [M, 2 inter], then SiLU * up folded into the
+    quantiser.  LLaMA-3-8B (4096 -> 2 x 14336) at M = 4096 and LLaMA-2-70B (8192 -> 2 x 28672) at M = 2048 (tiled
+    kernel: the epilogue is fused), and both at M = 32 (weight-streaming kernel: the [M, 2 inter] tensor goes through the
+    workspace and a second kernel).  Each sequence is replayed as a HIP graph over `--layers` (default 2) weight copies.
+    `value` = int8 operations of the fused sequences / their time."""
+    import numpy as np
+    import torch
+
+    import paper_2405_14597_amd as P
+    import synth_inputs as S
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    P.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    L = args.layers if args.layers != 32 else 2
+    cases = [("llama3-8b", 3, S.LLAMA3_8B["gate_up"][0], S.LLAMA3_8B["down"][0], (32, 4096)),
+             ("llama2-70b", 2, S.LLAMA2_70B["gate"][0], S.LLAMA2_70B["gate"][1], (32, 2048))]
+    segs, same = [], {}
+    for label, cfg, K, inter, batches in cases:
+        w = torch.from_numpy(S.make_weights(cfg, 2 * inter, K, S.seed_for(cfg, 2, 1))).to(dev)
+        qw = P.is_quantize_weights_int4_group(w, GROUP, ALPHA_LOG2, P.IS_SCALE_NORM)
+        del w
+        plain = P.is_prepack_w4(qw.qweight, qw.scale_i32, GROUP)
+        paired = P.is_prepack_w4_gate_up(qw.qweight, qw.scale_i32, qw.chan_scale, GROUP)
+        torch.cuda.synchronize()
+        plains = [plain] + [P.PackedWeights(plain.wpack.clone(), plain.spack.clone(), *plain[2:]) for _ in range(L - 1)]
+        paireds = [paired] + [P.PackedGateUp(P.PackedWeights(paired.packed.wpack.clone(), paired.packed.spack.clone(),
+                                                             *paired.packed[2:]), paired.chan_scale, inter)
+                              for _ in range(L - 1)]
+        for M in batches:
+            x = torch.from_numpy(S.make_activations(cfg, M, K, S.seed_for(cfg, 2, 2) + M)).to(dev)
+            xq, sa = P.is_quantize_act_int8_token(x)
+            b = dict(xq=xq, sa=sa, gu=torch.empty((M, 2 * inter), dtype=torch.float16, device=dev),
+                     h=torch.empty((M, inter), dtype=torch.float16, device=dev),
+                     hq=torch.empty((M, inter), dtype=torch.int8, device=dev),
+                     hs=torch.empty((M,), dtype=torch.float32, device=dev),
+                     fws=torch.zeros(max(1, P.is_gemm_gate_up_silu_prepacked_workspace_bytes(M, inter, K, GROUP)),
+                                     dtype=torch.uint8, device=dev),
+                     gws=torch.zeros(max(1, P.is_gemm_prepacked_workspace_bytes(M, 2 * inter, K, GROUP)),
+                                     dtype=torch.uint8, device=dev))
+
+            def fused(b=b, paireds=paireds):
+                for l in range(L):
+                    P.is_gemm_w4a8_intscale_gate_up_silu_prepacked(b["xq"], b["sa"], paireds[l], ALPHA_LOG2, out=b["h"],
+                                                                   workspace=b["fws"])
+                    P.is_quantize_act_int8_token(b["h"], b["hq"], b["hs"])
+
+            def unfused(b=b, plains=plains, c=qw.chan_scale):
+                for l in range(L):
+                    P.is_gemm_w4a8_intscale_prepacked(b["xq"], b["sa"], plains[l], c, ALPHA_LOG2, out=b["gu"],
+                                                      workspace=b["gws"])
+                    P.is_silu_mul_quantize_act_int8_token(b["gu"], b["hq"], b["hs"])
+
+            # the two sequences give the same codes and token scales (both round the same fp16 products)
+            fused()
+            got = (b["hq"].clone(), b["hs"].clone())
+            unfused()
+            torch.cuda.synchronize()
+            same[f"{label}_M{M}"] = bool(torch.equal(got[0], b["hq"]) and torch.equal(got[1], b["hs"]))
+            for kind, fn in (("fused", fused), ("unfused", unfused)):
+                seg = Segment(f"{label}_M{M}_{kind}", kind, L, 0, L * S.algorithmic_ops(M, 2 * inter, K), fn,
+                              not args.no_graph, torch)
+                seg.M, seg.K, seg.inter, seg.kind, seg.label = M, K, inter, kind, label
+                segs.append(seg)
+    torch.cuda.synchronize()
+
+    def run_steps(n, timed):
+        for _ in range(n):
+            ev = torch.cuda.Event(enable_timing=True)
+            ev.record()
+            for s in segs:
+                s.run()
+                nxt = torch.cuda.Event(enable_timing=True)
+                nxt.record()
+                if timed:
+                    s.pending.append((ev, nxt))
+                ev = nxt
+
+    run_steps(args.warmup, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(args.steps, True)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    us = {s.name: 1e3 * sum(a.elapsed_time(b) for a, b in s.pending) / (len(s.pending) * L) for s in segs}
+    shapes = []
+    for s in segs:
+        if s.kind != "fused":
+            continue
+        other = s.name.replace("_fused", "_unfused")
+        shapes.append(dict(name=f"{s.label}_M{s.M}", K=s.K, inter=s.inter, fused_us=round(us[s.name], 2),
+                           unfused_us=round(us[other], 2), unfused_over_fused=round(us[other] / us[s.name], 3),
+                           fused_tops=round(s.ops / L / us[s.name] / 1e6, 1)))
+    fused = [s for s in segs if s.kind == "fused"]
+    value = sum(s.ops / L for s in fused) / sum(us[s.name] for s in fused) / 1e6
+    big = max(fused, key=lambda s: us[s.name])
+    ach = big.ops / L / us[big.name] / 1e6
+    roofline = dict(bound="mfma", kernel="gemm_tile_pk_kernel (SiLU * up epilogue) + quantiser", achieved=round(ach, 1),
+                    peak=MFMA_I8_PEAK_TOPS, unit="TOP/s", frac=round(ach / MFMA_I8_PEAK_TOPS, 4), traffic=None,
+                    avg_launch_us=round(us[big.name], 2), shape=big.name)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        rng = np.random.default_rng(11)
+        M, inter, K = 1024, 14336, 4096
+        xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+        sa = (rng.random(M) * 0.02 + 0.001).astype(np.float32)
+        q = O.pack_int4(rng.integers(-8, 8, size=(2 * inter, K)).astype(np.int8))
+        IS = rng.integers(0, 1025, size=(2 * inter, K // GROUP)).astype(np.int32)
+        c = (rng.random(2 * inter) * 0.01 + 0.001).astype(np.float32)
+        t0 = time.perf_counter()
+        r = O.gemm_w4a8_intscale(xq, sa, q, IS, c, GROUP, ALPHA_LOG2)
+        h_ref = O.silu_mul_fp16(r.out.astype(np.float16))
+        dt = time.perf_counter() - t0
+        t = lambda a: torch.from_numpy(a).to(dev)
+        gu = P.is_prepack_w4_gate_up(t(q), t(IS), t(c), GROUP)
+        h, _ = P.is_gemm_w4a8_intscale_gate_up_silu_prepacked(t(xq), t(sa), gu, ALPHA_LOG2)
+        got, want = h.cpu().numpy().astype(np.float64), h_ref.astype(np.float64)
+        cpu = dict(value=round(2.0 * M * 2 * inter * K / dt / 1e12, 4), unit="TOP/s", cores=O.num_threads(), kind="oracle",
+                   sample=f"GEMM of Eq. (2) (C, threaded) + SiLU * up (numpy) once at M = {M}, inter = {inter}, K = {K} "
+                          f"(llama3-8b gate_up, a quarter of the rows), {dt:.1f} s",
+                   parity=dict(within_1e_2=bool(np.all(np.abs(got - want) <= 1e-2 * np.abs(want) + 2.0 ** -24))))
+    line = {
+        "metric": "gate_up GEMM with SiLU(gate) * up epilogue + quantiser: int8 TOP/s (% roofline)",
+        "value": round(value, 1), "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(1e3 * sec, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8 x int4 -> int32", "data": "synthetic",
+        "config": {"workload": "gated feed-forward front half (quantised x -> quantised input of down), fused epilogue "
+                               "against GEMM + SiLU*up quantiser: llama3-8b M in {32, 4096}, llama2-70b M in {32, 2048}",
+                   "launch": "eager" if args.no_graph else "HIP graph per sequence", "layers": L},
+        "roofline": roofline, "cpu_baseline": cpu, "shapes": shapes, "fused_equals_unfused_bit_for_bit": same,
     }
     print(json.dumps(line))
 

@@ -256,6 +256,36 @@ int is_gemm_w4a8_floatscale_grouped_prepacked(const int8_t* xq, const float* a_s
                                               size_t workspace_bytes, void* stream);
 
 /*
+ * Fused gate / up projection of a gated feed-forward block with SiLU(gate) * up as the GEMM's epilogue (Sec. 4.2 names
+ * kernel fusion around the GEMM; the LLaMA and Mixtral blocks of Sec. 5 are of this form).
+ *   is_prepack_w4_gate_up: qweight [2 inter, K/2], scales [2 inter, K/group] and chan_scale [2 inter] (may be NULL,
+ *     then chan_scale_packed must be NULL too) of the fused projection in canonical order, rows [0, inter) the gate's
+ *     and [inter, 2 inter) the up's.  Writes the kernel layout of is_prepack_w4 with the rows paired: packed rows
+ *     32 p .. 32 p + 15 are gate rows 16 p .. 16 p + 15, packed rows 32 p + 16 .. 32 p + 31 the up rows of the same
+ *     outputs; chan_scale_packed [2 inter] receives the channel scales in that order.  Buffer sizes as for
+ *     is_prepack_w4 with N = 2 inter.  inter must be a multiple of 16 (IS_ERR_UNSUPPORTED otherwise).
+ *   is_gemm_w4a8_*_gate_up_silu_prepacked: out [M, inter] fp16, out[m, n] = fp16(SiLU(g) * u) with g, u the fp16
+ *     results of the integer-scale (float-scale) GEMM of Eq. (2) (Eq. (1)) for gate row n and up row n: the value of
+ *     the unfused sequence GEMM -> fp16 tensor -> SiLU * up, bit for bit, without the [M, 2 inter] tensor's trip
+ *     through memory when M > 64 (the epilogue of the tiled kernel; for M <= 64 the weight-streaming kernel writes
+ *     that tensor into the workspace and a second kernel reads it).  SiLU(g) = g / (1 + e^-g) in single precision,
+ *     e^-g by the operation sequence stated in the oracle.  acc_out (may be NULL): [M, 2 inter] int32 accumulators
+ *     in the packed row order.  workspace >= is_gemm_gate_up_silu_prepacked_workspace_bytes(M, inter, K, group),
+ *     zero-filled once (same rules as the prepacked GEMM's).
+ */
+int is_prepack_w4_gate_up(const void* qweight, const int32_t* scale_i32, const float* scale_f32, const float* chan_scale,
+                          int inter, int K, int group, void* qweight_packed, void* scales_packed,
+                          float* chan_scale_packed, void* stream);
+size_t is_gemm_gate_up_silu_prepacked_workspace_bytes(int M, int inter, int K, int group);
+int is_gemm_w4a8_intscale_gate_up_silu_prepacked(const int8_t* xq, const float* a_scale, const void* qweight_packed,
+                                                 const void* scales_packed, const float* chan_scale_packed, int M,
+                                                 int inter, int K, int group, int alpha_log2, void* out_fp16,
+                                                 int32_t* acc_out, void* workspace, size_t workspace_bytes, void* stream);
+int is_gemm_w4a8_floatscale_gate_up_silu_prepacked(const int8_t* xq, const float* a_scale, const void* qweight_packed,
+                                                   const void* scales_packed, int M, int inter, int K, int group,
+                                                   void* out_fp16, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Which kernels the prepacked calls launch for a shape, as a kernel trace (rocprofv3 --kernel-trace) names them, in
  * launch order and separated by '\n' (the stand-alone activation quantiser of the linear call for 2 <= M <= 64, when
  * it runs, is not listed).  Host-only: nothing is launched.  int_scale: Eq. (2) or Eq. (1) form; fp16_in: the linear

@@ -55,6 +55,10 @@ EXPORTED_SYMBOLS = (
     "is_gemm_grouped_prepacked_workspace_bytes",
     "is_gemm_w4a8_intscale_grouped_prepacked",
     "is_gemm_w4a8_floatscale_grouped_prepacked",
+    "is_prepack_w4_gate_up",
+    "is_gemm_gate_up_silu_prepacked_workspace_bytes",
+    "is_gemm_w4a8_intscale_gate_up_silu_prepacked",
+    "is_gemm_w4a8_floatscale_gate_up_silu_prepacked",
     "is_describe_prepacked",
     "is_describe_grouped_prepacked",
     "is_source_hash",
@@ -149,6 +153,14 @@ def load_library() -> ctypes.CDLL:
     lib.is_gemm_w4a8_intscale_prepacked.restype = ci
     lib.is_gemm_w4a8_floatscale_prepacked.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, vp, vp, sz, vp]
     lib.is_gemm_w4a8_floatscale_prepacked.restype = ci
+    lib.is_prepack_w4_gate_up.argtypes = [vp, vp, vp, vp, ci, ci, ci, vp, vp, vp, vp]
+    lib.is_prepack_w4_gate_up.restype = ci
+    lib.is_gemm_gate_up_silu_prepacked_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.is_gemm_gate_up_silu_prepacked_workspace_bytes.restype = sz
+    lib.is_gemm_w4a8_intscale_gate_up_silu_prepacked.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.is_gemm_w4a8_intscale_gate_up_silu_prepacked.restype = ci
+    lib.is_gemm_w4a8_floatscale_gate_up_silu_prepacked.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, vp, vp, sz, vp]
+    lib.is_gemm_w4a8_floatscale_gate_up_silu_prepacked.restype = ci
     lib.is_gemm_w4a8_intscale_prepacked_noalloc.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp]
     lib.is_gemm_w4a8_intscale_prepacked_noalloc.restype = ci
     lib.is_gemm_grouped_prepacked_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
@@ -774,6 +786,93 @@ def is_gemm_w4a8_intscale_prepacked(xq, a_scale, packed: PackedWeights, chan_sca
     _check("is_gemm_w4a8_intscale_prepacked", st)
     _release_workspace(ws, workspace, stream)
     return out, acc_out
+
+
+class PackedGateUp(NamedTuple):
+    packed: PackedWeights   # the fused projection, N = 2 * inter, gate / up rows paired by 16-row tile
+    chan_scale: "object"    # float32 [2 * inter] in the packed row order, or None
+    inter: int
+
+
+def is_prepack_w4_gate_up(qweight, scale, chan_scale, group: int, stream=None) -> PackedGateUp:
+    """Canonical fused gate_up projection (rows [0, inter) gate, [inter, 2 inter) up) -> kernel layout with the rows of
+    gate and up paired, for the GEMMs with the SiLU(gate) * up epilogue."""
+    torch = _torch()
+    lib = load_library()
+    N, K2 = qweight.shape
+    K, inter = 2 * K2, N // 2
+    if N != 2 * inter:
+        raise ValueError("qweight: an even number of rows (gate and up) expected")
+    _require(qweight, torch.uint8, (N, K2), "qweight")
+    if scale.dtype not in (torch.int32, torch.float32):
+        raise ValueError("scale: int32 or float32 expected")
+    _require(scale, scale.dtype, (N, K // group), "scale")
+    if chan_scale is not None:
+        _require(chan_scale, torch.float32, (N,), "chan_scale")
+    wb, sb = int(lib.is_prepack_w4_weight_bytes(N, K)), int(lib.is_prepack_w4_scale_bytes(N, K, group))
+    if wb == 0 or sb == 0:
+        raise IntScaleError("is_prepack_w4_gate_up", IS_ERR_UNSUPPORTED)
+    wpack = torch.empty((wb,), dtype=torch.uint8, device=qweight.device)
+    spack = torch.empty((sb,), dtype=torch.uint8, device=qweight.device)
+    cpack = None if chan_scale is None else torch.empty((N,), dtype=torch.float32, device=qweight.device)
+    is_float = scale.dtype == torch.float32
+    st = lib.is_prepack_w4_gate_up(_p(qweight), None if is_float else _p(scale), _p(scale) if is_float else None,
+                                   _p(chan_scale), inter, K, group, _p(wpack), _p(spack), _p(cpack), _stream_handle(stream))
+    _check("is_prepack_w4_gate_up", st)
+    return PackedGateUp(PackedWeights(wpack, spack, N, K, group, is_float), cpack, inter)
+
+
+def is_gemm_gate_up_silu_prepacked_workspace_bytes(M: int, inter: int, K: int, group: int) -> int:
+    return int(load_library().is_gemm_gate_up_silu_prepacked_workspace_bytes(M, inter, K, group))
+
+
+def is_gemm_w4a8_intscale_gate_up_silu_prepacked(xq, a_scale, gate_up: PackedGateUp, alpha_log2: int, out=None,
+                                                 acc_out=None, want_acc: bool = False, workspace=None, stream=None):
+    """Returns (out fp16 [M, inter] = SiLU(gate) * up, acc int32 [M, 2 inter] in the packed row order or None)."""
+    torch = _torch()
+    M, K = xq.shape
+    packed, inter = gate_up.packed, gate_up.inter
+    if K != packed.K or packed.float_scales:
+        raise ValueError("packed weights: K mismatch or float scales")
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    if out is None:
+        out = torch.empty((M, inter), dtype=torch.float16, device=xq.device)
+    _require(out, torch.float16, (M, inter), "out")
+    if acc_out is None and want_acc:
+        acc_out = torch.empty((M, 2 * inter), dtype=torch.int32, device=xq.device)
+    if acc_out is not None:
+        _require(acc_out, torch.int32, (M, 2 * inter), "acc_out")
+    ws, ws_bytes = _zero_workspace(is_gemm_gate_up_silu_prepacked_workspace_bytes(M, inter, K, packed.group), xq.device,
+                                   workspace)
+    st = load_library().is_gemm_w4a8_intscale_gate_up_silu_prepacked(
+        _p(xq), _p(a_scale), _p(packed.wpack), _p(packed.spack), _p(gate_up.chan_scale), M, inter, K, packed.group,
+        alpha_log2, _p(out), _p(acc_out), _p(ws), ws_bytes, _stream_handle(stream))
+    _check("is_gemm_w4a8_intscale_gate_up_silu_prepacked", st)
+    _release_workspace(ws, workspace, stream)
+    return out, acc_out
+
+
+def is_gemm_w4a8_floatscale_gate_up_silu_prepacked(xq, a_scale, gate_up: PackedGateUp, out=None, workspace=None,
+                                                   stream=None):
+    torch = _torch()
+    M, K = xq.shape
+    packed, inter = gate_up.packed, gate_up.inter
+    if K != packed.K or not packed.float_scales:
+        raise ValueError("packed weights: K mismatch or integer scales")
+    _require(xq, torch.int8, (M, K), "xq")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    if out is None:
+        out = torch.empty((M, inter), dtype=torch.float16, device=xq.device)
+    _require(out, torch.float16, (M, inter), "out")
+    ws, ws_bytes = _zero_workspace(is_gemm_gate_up_silu_prepacked_workspace_bytes(M, inter, K, packed.group), xq.device,
+                                   workspace)
+    st = load_library().is_gemm_w4a8_floatscale_gate_up_silu_prepacked(
+        _p(xq), _p(a_scale), _p(packed.wpack), _p(packed.spack), M, inter, K, packed.group, _p(out), _p(ws), ws_bytes,
+        _stream_handle(stream))
+    _check("is_gemm_w4a8_floatscale_gate_up_silu_prepacked", st)
+    _release_workspace(ws, workspace, stream)
+    return out
 
 
 IS_NOALLOC_SCRATCH_BYTES = 32 << 20

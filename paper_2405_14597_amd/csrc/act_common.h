@@ -32,6 +32,38 @@ __device__ __forceinline__ float absmax8(uint4 v) {
     return m;
 }
 
+// e^t and SiLU(g) * u as fixed sequences of separately rounded single-precision operations (no contraction into
+// fused multiply-adds): the fp16 result may decide integer codes further on, so every user computes it the same way.
+__device__ __forceinline__ float exp_steps(float t) {
+#pragma clang fp contract(off)
+    t = fminf(fmaxf(t, -87.0f), 88.0f);
+    const float n = rintf(t * 1.4426950408889634f);
+    const float r = (t - n * 0.693145751953125f) - n * 1.428606765330187e-06f;
+    float p = (float)(1.0 / 720.0);
+    p = p * r + (float)(1.0 / 120.0);
+    p = p * r + (float)(1.0 / 24.0);
+    p = p * r + (float)(1.0 / 6.0);
+    p = p * r + 0.5f;
+    p = p * r + 1.0f;
+    p = p * r + 1.0f;
+    return ldexpf(p, (int)n);
+}
+
+// A single-precision value that is about to be converted to fp16, as the rounded fp32 value it is: without this the
+// compiler may merge the last multiply into the conversion (v_fma_mixlo_f16 rounds the exact product once, straight to
+// fp16), which differs from "round to fp32, then to fp16" wherever the fp32 result falls on an fp16 tie.
+__device__ __forceinline__ float rounded_f32(float v) {
+    asm("" : "+v"(v));
+    return v;
+}
+
+__device__ __forceinline__ float silu_mul(float g, float u) {
+#pragma clang fp contract(off)
+    const float e = exp_steps(-g);
+    return rounded_f32((g / (1.0f + e)) * u);
+}
+
+
 __device__ __forceinline__ int quant_code(float x, float s, float lo, float hi) {
     // s > 0 is checked by the caller
     float r = rintf(x / s);

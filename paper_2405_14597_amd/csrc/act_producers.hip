@@ -60,30 +60,9 @@ __device__ __forceinline__ uint4 normalize8(uint4 v, uint4 g, float r) {
     for (int i = 0; i < 4; ++i) {
         float2 f = __half22float2(hv[i]);
         float2 w = __half22float2(hg[i]);
-        ho[i] = __floats2half2_rn((f.x * r) * w.x, (f.y * r) * w.y);
+        ho[i] = __floats2half2_rn(rounded_f32((f.x * r) * w.x), rounded_f32((f.y * r) * w.y));
     }
     return out;
-}
-
-__device__ __forceinline__ float exp_steps(float t) {
-#pragma clang fp contract(off)
-    t = fminf(fmaxf(t, -87.0f), 88.0f);
-    const float n = rintf(t * 1.4426950408889634f);
-    const float r = (t - n * 0.693145751953125f) - n * 1.428606765330187e-06f;
-    float p = (float)(1.0 / 720.0);
-    p = p * r + (float)(1.0 / 120.0);
-    p = p * r + (float)(1.0 / 24.0);
-    p = p * r + (float)(1.0 / 6.0);
-    p = p * r + 0.5f;
-    p = p * r + 1.0f;
-    p = p * r + 1.0f;
-    return ldexpf(p, (int)n);
-}
-
-__device__ __forceinline__ float silu_mul(float g, float u) {
-#pragma clang fp contract(off)
-    const float e = exp_steps(-g);
-    return (g / (1.0f + e)) * u;
 }
 
 __device__ __forceinline__ uint4 silu_mul8(uint4 g, uint4 u) {
@@ -277,6 +256,28 @@ hipError_t launch_silu_mul_quantize_act(const __half* gate_up, int M, int inter,
     else
         hipLaunchKernelGGL(silu_mul_quantize_kernel, grid, dim3(kActThreads), 0, stream, gate_up, M, inter, xq, a_scale);
 #undef SILU_LAUNCH
+    return hipGetLastError();
+}
+
+// The fp16 output of a GEMM whose weight rows alternate gate / up by 16-row tile (is_prepack_w4_gate_up), [M, N]:
+// out[m, 16 p + r] = fp16(SiLU(gu[m, 32 p + r]) * gu[m, 32 p + 16 + r]), [M, N / 2].  One thread per 8 outputs.
+namespace {
+__global__ __launch_bounds__(256) void silu_mul_paired_kernel(const __half* __restrict__ gu, int M, int N,
+                                                              __half* __restrict__ out) {
+    const int inter = N >> 1, chunks = inter >> 3;
+    const size_t at = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (at >= (size_t)M * chunks) return;
+    const int m = (int)(at / chunks), c = (int)(at - (size_t)m * chunks);  // outputs 8 c .. 8 c + 7 of row m
+    const int p = c >> 1, h = c & 1;
+    const __half* row = gu + (size_t)m * N + 32 * p + 8 * h;
+    const uint4 g = *reinterpret_cast<const uint4*>(row), u = *reinterpret_cast<const uint4*>(row + 16);
+    *reinterpret_cast<uint4*>(out + (size_t)m * inter + 8 * c) = silu_mul8(g, u);
+}
+}  // namespace
+
+hipError_t launch_silu_mul_paired(const __half* gu, int M, int N, __half* out, hipStream_t stream) {
+    const size_t work = (size_t)M * (N >> 4);
+    hipLaunchKernelGGL(silu_mul_paired_kernel, dim3((unsigned)((work + 255) / 256)), dim3(256), 0, stream, gu, M, N, out);
     return hipGetLastError();
 }
 

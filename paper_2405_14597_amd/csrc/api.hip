@@ -398,7 +398,7 @@ size_t is_gemm_prepacked_workspace_bytes(int M, int N, int K, int group) {
 static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_scale, float* a_scale_out,
                           const void* wpack, const void* spack, const float* chan_scale, int M, int N, int K, int group,
                           int alpha_log2, void* out_fp16, int32_t* acc_out, void* workspace, size_t workspace_bytes,
-                          void* stream, bool int_scale, bool fixed_scratch = false) {
+                          void* stream, bool int_scale, bool fixed_scratch = false, bool pair = false) {
     if (M < 0) return IS_ERR_INVALID_ARG;
     const int shape = check_pk_shape(N, K, group);
     if (shape != IS_OK) return shape;
@@ -434,6 +434,7 @@ static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_s
     a.K = K;
     a.group = group;
     a.alpha_log2 = int_scale ? alpha_log2 : 0;
+    a.pair = (pair && M > 64) ? 1 : 0;  // (the fused epilogue is the tiled kernel's)
     if (M > 64)
         return hip_status(launch_gemm_tile_pk(a, int_scale, workspace, workspace_bytes, static_cast<hipStream_t>(stream)));
     if (fixed_scratch && a.partials != nullptr) {  // a workspace whose last user may not have left the counters zero
@@ -459,6 +460,72 @@ int is_gemm_w4a8_floatscale_prepacked(const int8_t* xq, const float* a_scale, co
                                       void* workspace, size_t workspace_bytes, void* stream) {
     return gemm_pk_common(xq, nullptr, a_scale, nullptr, qweight_packed, scales_packed, nullptr, M, N, K, group, 0,
                           out_fp16, nullptr, workspace, workspace_bytes, stream, false);
+}
+
+// ---- fused gate / up projection with SiLU(gate) * up as the epilogue (rows paired by is_prepack_w4_gate_up)
+int is_prepack_w4_gate_up(const void* qweight, const int32_t* scale_i32, const float* scale_f32, const float* chan_scale,
+                          int inter, int K, int group, void* qweight_packed, void* scales_packed,
+                          float* chan_scale_packed, void* stream) {
+    if (inter <= 0 || inter > (1 << 29)) return IS_ERR_INVALID_ARG;
+    if (inter % 16 != 0) return IS_ERR_UNSUPPORTED;  // gate and up tiles alternate by 16 rows
+    const int N = 2 * inter;
+    const int shape = check_pk_shape(N, K, group);
+    if (shape != IS_OK) return shape;
+    if ((scale_i32 == nullptr) == (scale_f32 == nullptr)) return IS_ERR_INVALID_ARG;  // exactly one kind of scales
+    if ((chan_scale == nullptr) != (chan_scale_packed == nullptr)) return IS_ERR_INVALID_ARG;
+    if (chan_scale != nullptr && ((reinterpret_cast<uintptr_t>(chan_scale) | reinterpret_cast<uintptr_t>(chan_scale_packed)) & 3u))
+        return IS_ERR_INVALID_ARG;
+    const void* scale = scale_i32 ? static_cast<const void*>(scale_i32) : static_cast<const void*>(scale_f32);
+    if (!ok_ptr(qweight) || !ok_ptr(scale) || !ok_ptr(qweight_packed) || !ok_ptr(scales_packed)) return IS_ERR_INVALID_ARG;
+    return hip_status(launch_prepack_w4(static_cast<const uint8_t*>(qweight), scale, scale_f32 != nullptr, N, K, group,
+                                        static_cast<uint8_t*>(qweight_packed), static_cast<uint8_t*>(scales_packed),
+                                        static_cast<hipStream_t>(stream), inter, chan_scale, chan_scale_packed));
+}
+
+size_t is_gemm_gate_up_silu_prepacked_workspace_bytes(int M, int inter, int K, int group) {
+    if (M <= 0 || inter <= 0 || inter > (1 << 29) || inter % 16 != 0 || check_pk_shape(2 * inter, K, group) != IS_OK) return 0;
+    const size_t gemm = is_gemm_prepacked_workspace_bytes(M, 2 * inter, K, group);
+    // up to 64 token rows: the weight-streaming kernel writes the [M, 2 inter] fp16 tensor here, a second kernel reads it
+    return M <= 64 ? pad_256(gemm) + pad_256((size_t)M * 2 * inter * 2) : gemm;
+}
+
+static int gate_up_silu_common(const int8_t* xq, const float* a_scale, const void* wpack, const void* spack,
+                               const float* chan_scale_packed, int M, int inter, int K, int group, int alpha_log2,
+                               void* out_fp16, int32_t* acc_out, void* workspace, size_t workspace_bytes, void* stream,
+                               bool int_scale) {
+    if (M < 0 || inter <= 0 || inter > (1 << 29)) return IS_ERR_INVALID_ARG;
+    if (inter % 16 != 0) return IS_ERR_UNSUPPORTED;
+    const int N = 2 * inter;
+    if (M == 0 || M > 64)
+        return gemm_pk_common(xq, nullptr, a_scale, nullptr, wpack, spack, chan_scale_packed, M, N, K, group, alpha_log2,
+                              out_fp16, acc_out, workspace, workspace_bytes, stream, int_scale, false, true);
+    const int shape = check_pk_shape(N, K, group);
+    if (shape != IS_OK) return shape;
+    const size_t need = is_gemm_gate_up_silu_prepacked_workspace_bytes(M, inter, K, group);
+    if (!ok_opt(workspace)) return IS_ERR_INVALID_ARG;
+    if (workspace == nullptr || workspace_bytes < need) return IS_ERR_WORKSPACE;
+    if (!ok_ptr(out_fp16)) return IS_ERR_INVALID_ARG;
+    const size_t gemm = pad_256(is_gemm_prepacked_workspace_bytes(M, N, K, group));
+    __half* gu = reinterpret_cast<__half*>(static_cast<unsigned char*>(workspace) + gemm);
+    const int st = gemm_pk_common(xq, nullptr, a_scale, nullptr, wpack, spack, chan_scale_packed, M, N, K, group,
+                                  alpha_log2, gu, acc_out, workspace, gemm, stream, int_scale);
+    if (st != IS_OK) return st;
+    return hip_status(launch_silu_mul_paired(gu, M, N, static_cast<__half*>(out_fp16), static_cast<hipStream_t>(stream)));
+}
+
+int is_gemm_w4a8_intscale_gate_up_silu_prepacked(const int8_t* xq, const float* a_scale, const void* qweight_packed,
+                                                 const void* scales_packed, const float* chan_scale_packed, int M,
+                                                 int inter, int K, int group, int alpha_log2, void* out_fp16,
+                                                 int32_t* acc_out, void* workspace, size_t workspace_bytes, void* stream) {
+    return gate_up_silu_common(xq, a_scale, qweight_packed, scales_packed, chan_scale_packed, M, inter, K, group,
+                               alpha_log2, out_fp16, acc_out, workspace, workspace_bytes, stream, true);
+}
+
+int is_gemm_w4a8_floatscale_gate_up_silu_prepacked(const int8_t* xq, const float* a_scale, const void* qweight_packed,
+                                                   const void* scales_packed, int M, int inter, int K, int group,
+                                                   void* out_fp16, void* workspace, size_t workspace_bytes, void* stream) {
+    return gate_up_silu_common(xq, a_scale, qweight_packed, scales_packed, nullptr, M, inter, K, group, 0, out_fp16,
+                               nullptr, workspace, workspace_bytes, stream, false);
 }
 
 int is_gemm_w4a8_intscale_prepacked_noalloc(const int8_t* xq, const float* a_scale, const void* qweight_packed,

@@ -276,7 +276,8 @@ typedef float v4f_t __attribute__((ext_vector_type(4)));
 // One output tile.  WIDE: 32-bit multiplies in the integer scale step (some scale does not fit 24 signed bits).
 // GROUPED: the mixture-of-experts form; `entry` is the workgroup's line of the tile table and `tile_n_g` its tile column.
 // MS: 16-row token sub-tiles per wave (the tile has MS * 16 token rows).
-template <bool INT_SCALE, bool WIDE, bool GROUPED, int MS>
+// SILU: the weight rows alternate gate / up by 16-row tile and the epilogue writes fp16(SiLU(gate) * up), half as wide.
+template <bool INT_SCALE, bool WIDE, bool GROUPED, int MS, bool SILU = false>
 __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restrict__ xp, const int32_t* __restrict__ c0,
                                         const TileSplit& sp, const TileGroups& tg, const int32_t* entry, int tile_n_g,
                                         unsigned char* smem) {
@@ -549,7 +550,7 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
     const int n_rows = min(kTN, a.N - n0);
     // Rows of 8-aligned length go through an fp16 copy of the tile in LDS and leave as 16-byte stores; otherwise (and
     // for the diagnostic accumulator output) element by element.
-    const bool staged = (a.N & 7) == 0 && a.acc_out == nullptr;
+    const bool staged = (a.N & (SILU ? 15 : 7)) == 0 && a.acc_out == nullptr;
     constexpr int kPitch = 264;  // halves per LDS row: 256 + 8, so that rows keep 16-byte alignment
     __half* otile = reinterpret_cast<__half*>(smem);
     float sa[MS][4];
@@ -560,23 +561,76 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
             const int ml = i * 16 + 4 * kb + r;
             sa[i][r] = ml < m_rows ? a.a_scale[m0 + ml] : 0.0f;
         }
+    auto channel = [&](int j) {  // what an accumulator of weight sub-tile j is multiplied by besides the token scale
+        const int nl = wn * 64 + j * 16 + li;
+        float c = 1.0f;
+        if constexpr (INT_SCALE) {
+            if (chan_scale && nl < n_rows) c = chan_scale[n0 + nl];
+            c *= inv_alpha;
+        }
+        return c;
+    };
+    auto result = [&](const acc4& v, int r, float s, float c) {
+        if constexpr (INT_SCALE) return (float)v[r] * s * c;
+        else return v[r] * s;
+    };
+    if constexpr (SILU) {
+        // Sub-tiles 2q and 2q + 1 of a wave are the gate and up rows of the same 16 outputs: the lane holds both.  The
+        // result is DEFINED as the unfused pipeline (GEMM output rounded to fp16, then SiLU * up on those values), so
+        // that fusing changes no bit; it saves the [M, N] tensor's trip through memory.
+        const int out_n = a.N >> 1, out_n0 = n0 >> 1, out_rows = n_rows >> 1;
+#pragma unroll
+        for (int q = 0; q < kNS / 2; ++q) {
+            const float cg = channel(2 * q), cu = channel(2 * q + 1);
+            const int ol = wn * 32 + q * 16 + li;  // output column inside the tile's 128
+#pragma unroll
+            for (int i = 0; i < MS; ++i)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int ml = i * 16 + 4 * kb + r;
+                    const float g = __half2float(__float2half_rn(result(acc[i][2 * q], r, sa[i][r], cg)));
+                    const float u = __half2float(__float2half_rn(result(acc[i][2 * q + 1], r, sa[i][r], cu)));
+                    const __half h = __float2half_rn(silu_mul(g, u));  // (the product arrives rounded to fp32)
+                    if (staged) {
+                        otile[ml * kPitch + ol] = h;
+                    } else if (ml < m_rows && ol < out_rows) {
+                        a.out[(size_t)(m0 + ml) * out_n + out_n0 + ol] = h;
+                        if constexpr (INT_SCALE) {
+                            if (a.acc_out) {
+                                const size_t o = (size_t)(m0 + ml) * a.N + n0 + wn * 64 + 2 * q * 16 + li;
+                                a.acc_out[o] = acc[i][2 * q][r];
+                                a.acc_out[o + 16] = acc[i][2 * q + 1][r];
+                            }
+                        }
+                    }
+                }
+        }
+        if (staged) {
+            __syncthreads();
+            const int chunk = tid & 15;  // 8 outputs
+            if (chunk * 8 < out_rows) {
+#pragma unroll
+                for (int pass = 0; pass < TM / 16; ++pass) {
+                    const int ml = pass * 16 + (tid >> 4);
+                    if (ml < m_rows)
+                        *reinterpret_cast<uint4*>(a.out + (size_t)(m0 + ml) * out_n + out_n0 + chunk * 8) =
+                            *reinterpret_cast<const uint4*>(otile + ml * kPitch + chunk * 8);
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < kNS; ++j) {
         const int nl = wn * 64 + j * 16 + li;
         const int n = n0 + nl;
-        float c = 1.0f;
-        if constexpr (INT_SCALE) {
-            if (chan_scale && nl < n_rows) c = chan_scale[n];
-            c *= inv_alpha;
-        }
+        const float c = channel(j);
 #pragma unroll
         for (int i = 0; i < MS; ++i)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int ml = i * 16 + 4 * kb + r;
-                __half h;
-                if constexpr (INT_SCALE) h = __float2half_rn((float)acc[i][j][r] * sa[i][r] * c);
-                else h = __float2half_rn(acc[i][j][r] * sa[i][r]);
+                const __half h = __float2half_rn(result(acc[i][j], r, sa[i][r], c));
                 if (staged) {
                     otile[ml * kPitch + nl] = h;
                 } else if (ml < m_rows && nl < n_rows) {
@@ -616,6 +670,22 @@ __global__ __launch_bounds__(kTThreads) __attribute__((amdgpu_waves_per_eu(2, 2)
         else tile_pk<true, false, false, kMS>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
     } else {
         tile_pk<false, false, false, kMS>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
+    }
+}
+
+// The same on gate / up rows that alternate by 16-row tile, with SiLU(gate) * up as the epilogue (Sec. 4.2 names kernel
+// fusion around the GEMM; the LLaMA feed-forward block applies this to the fused gate_up projection).
+template <bool INT_SCALE>
+__global__ __launch_bounds__(kTThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_tile_silu_pk_kernel(
+    PkArgs a, const int8_t* __restrict__ xp, const int32_t* __restrict__ c0, TileSplit sp) {
+    extern __shared__ __align__(16) unsigned char smem_tpk[];
+    const TileGroups none{};
+    if constexpr (INT_SCALE) {
+        const int flags = *reinterpret_cast<const int32_t*>(a.spack);
+        if (flags & kPkFlagWide) tile_pk<true, true, false, kMS, true>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
+        else tile_pk<true, false, false, kMS, true>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
+    } else {
+        tile_pk<false, false, false, kMS, true>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
     }
 }
 
@@ -695,11 +765,11 @@ size_t gemm_tile_pk_workspace_bytes(int M, int N, int K) {
 
 bool gemm_tile_pk_takes_fp16(int K) { return (K & 127) == 0; }
 
-void gemm_tile_pk_kernel_names(int K, bool int_scale, bool fp16_in, char* buf, size_t len) {
+void gemm_tile_pk_kernel_names(int K, bool int_scale, bool fp16_in, char* buf, size_t len, bool silu) {
     char prep[96];
     if (fp16_in) snprintf(prep, sizeof prep, "token_scales_kernel\nquantize_prepare_activations_pk_kernel");
     else snprintf(prep, sizeof prep, "prepare_activations_pk_kernel");
-    snprintf(buf, len, "%s\ngemm_tile_pk_kernel<%s>", prep, int_scale ? "true" : "false");
+    snprintf(buf, len, "%s\ngemm_tile%s_pk_kernel<%s>", prep, silu ? "_silu" : "", int_scale ? "true" : "false");
 }
 
 hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace, size_t workspace_bytes,
@@ -730,23 +800,19 @@ hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace,
     const int tiles = sp.whole + sp.rem * sp.parts;  // workgroups
     int device = -1;
     (void)hipGetDevice(&device);
-    static bool raised[2][64] = {};
-    auto raise = [&](const void* kern, int which) -> hipError_t {
-        if (device >= 0 && device < 64 && raised[which][device]) return hipSuccess;
-        hipError_t r = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (r == hipSuccess && device >= 0 && device < 64) raised[which][device] = true;
-        return r;
+    static bool raised[4][64] = {};
+    auto launch = [&](auto kernel, int which) -> hipError_t {
+        if (!(device >= 0 && device < 64 && raised[which][device])) {
+            hipError_t r = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (r != hipSuccess) return r;
+            if (device >= 0 && device < 64) raised[which][device] = true;
+        }
+        hipLaunchKernelGGL(kernel, dim3(tiles), dim3(kTThreads), smem, stream, a, xp, c0, sp);
+        return hipGetLastError();
     };
-    if (int_scale) {
-        e = raise(reinterpret_cast<const void*>(gemm_tile_pk_kernel<true>), 0);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(gemm_tile_pk_kernel<true>, dim3(tiles), dim3(kTThreads), smem, stream, a, xp, c0, sp);
-    } else {
-        e = raise(reinterpret_cast<const void*>(gemm_tile_pk_kernel<false>), 1);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(gemm_tile_pk_kernel<false>, dim3(tiles), dim3(kTThreads), smem, stream, a, xp, c0, sp);
-    }
-    return hipGetLastError();
+    if (a.pair) return int_scale ? launch(gemm_tile_silu_pk_kernel<true>, 2) : launch(gemm_tile_silu_pk_kernel<false>, 3);
+    return int_scale ? launch(gemm_tile_pk_kernel<true>, 0) : launch(gemm_tile_pk_kernel<false>, 1);
 }
 
 // ---- mixture-of-experts form

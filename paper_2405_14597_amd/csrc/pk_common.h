@@ -20,7 +20,7 @@
 namespace intscale {
 
 constexpr int kPkHeaderBytes = 256;
-constexpr int kPkFlagWide = 1, kPkFlagFloat = 2;
+constexpr int kPkFlagWide = 1, kPkFlagFloat = 2, kPkFlagPaired = 4;  // (paired: gate / up rows alternate by 16-row tile)
 constexpr int kPkBlockBytes = 1024;
 constexpr int kPkMaxExperts = 1024;  // weight sets of the grouped form at most
 
@@ -61,12 +61,19 @@ struct PkArgs {
     int32_t* partials;       // K split: [tile][slab][mt][64 lanes][4]
     int M, N, K, group;
     int alpha_log2;
+    // 1: the weight rows alternate gate / up by 16-row tile (is_prepack_w4_gate_up) and the output is
+    // fp16(SiLU(gate) * up), [M, N/2]; acc_out stays [M, N] in the packed row order.  Tiled kernel only.
+    int pair = 0;
 };
 
 bool pk_decode_plan(int M, int N, int K, int group, bool fp16_in, PkPlan* plan);
 size_t pk_decode_workspace_bytes(int M, int N, int K, int group);
 hipError_t launch_prepack_w4(const uint8_t* qweight, const void* scale, bool float_scales, int N, int K, int group,
-                             uint8_t* wpack, uint8_t* spack, hipStream_t stream);
+                             uint8_t* wpack, uint8_t* spack, hipStream_t stream, int pair_inter = 0,
+                             const float* chan_scale = nullptr, float* chan_scale_packed = nullptr);
+// out[m, n] = fp16(SiLU(gu[m, 32 p + r]) * gu[m, 32 p + 16 + r]) for n = 16 p + r: the fp16 output of a GEMM on paired rows
+// (the route for up to 64 token rows, whose kernel has no fused epilogue)
+hipError_t launch_silu_mul_paired(const __half* gu, int M, int N, __half* out, hipStream_t stream);
 hipError_t launch_gemm_decode_pk(const PkArgs& a, bool int_scale, hipStream_t stream);
 void pk_decode_kernel_name(const PkPlan& plan, bool int_scale, bool fp16_in, char* buf, size_t len);
 // MFMA-bound tiled kernel on the prepacked layout (more than 64 token rows); x_fp16 set: a.a_scale_out (= a.a_scale)
@@ -83,7 +90,7 @@ size_t gemm_tile_grouped_pk_workspace_bytes(int E, int M, int N, int K);
 hipError_t launch_gemm_tile_grouped_pk(const PkArgs& a, const int32_t* row_offsets, int E, size_t wstride,
                                        size_t sstride, bool int_scale, void* workspace, hipStream_t stream);
 // The kernels launch_gemm_tile_pk runs, in order, as a kernel trace names them, separated by '\n'.
-void gemm_tile_pk_kernel_names(int K, bool int_scale, bool fp16_in, char* buf, size_t len);
+void gemm_tile_pk_kernel_names(int K, bool int_scale, bool fp16_in, char* buf, size_t len, bool silu = false);
 void gemm_tile_grouped_pk_kernel_names(int E, int M, bool int_scale, char* buf, size_t len);
 
 }  // namespace intscale

@@ -217,6 +217,33 @@ def test_noalloc_argument_validation():
     assert call(M=2048, N=256, K=28672) == P.IS_ERR_WORKSPACE
 
 
+def test_gate_up_silu_argument_validation():
+    lib = P.load_library()
+    bad, uns = P.IS_ERR_INVALID_ARG, P.IS_ERR_UNSUPPORTED
+    pre = lambda **kw: lib.is_prepack_w4_gate_up(kw.get("q", A), kw.get("si", A), kw.get("sf", None), kw.get("c", None),
+                                                 kw.get("inter", 16), kw.get("K", 256), kw.get("G", 128), kw.get("wp", A),
+                                                 kw.get("sp", A), kw.get("cp", None), None)
+    assert pre(q=None) == bad and pre(wp=None) == bad and pre(sp=None) == bad and pre(si=None) == bad and pre(sf=A) == bad
+    assert pre(c=A) == bad and pre(cp=A) == bad          # channel scales in and out go together
+    assert pre(inter=0) == bad and pre(inter=24) == uns and pre(G=64) == uns and pre(K=250) == bad
+    wsb = lib.is_gemm_gate_up_silu_prepacked_workspace_bytes
+    assert wsb(8, 24, 256, 128) == 0 and wsb(8, 16, 256, 64) == 0 and wsb(0, 16, 256, 128) == 0
+    # up to 64 token rows: the [M, 2 inter] fp16 tensor on top of the GEMM's own workspace
+    assert wsb(8, 16, 256, 128) == lib.is_gemm_prepacked_workspace_bytes(8, 32, 256, 128) + 8 * 32 * 2
+    assert wsb(128, 16, 256, 128) == lib.is_gemm_prepacked_workspace_bytes(128, 32, 256, 128)
+    gemm = lambda **kw: lib.is_gemm_w4a8_intscale_gate_up_silu_prepacked(
+        kw.get("xq", A), kw.get("sa", A), kw.get("wp", A), kw.get("sp", A), kw.get("c", None), kw.get("M", 8),
+        kw.get("inter", 16), kw.get("K", 256), kw.get("G", 128), kw.get("a", 10), kw.get("out", A), None, kw.get("ws", A),
+        kw.get("wsb", 1 << 20), None)
+    assert gemm(inter=0) == bad and gemm(inter=24) == uns and gemm(M=-1) == bad and gemm(G=64) == uns
+    assert gemm(ws=None) == P.IS_ERR_WORKSPACE and gemm(wsb=100) == P.IS_ERR_WORKSPACE and gemm(out=None) == bad
+    assert gemm(M=128, ws=None, wsb=0) == P.IS_ERR_WORKSPACE and gemm(M=128, xq=None) == bad and gemm(M=128, a=31) == bad
+    assert gemm(M=0, ws=None, wsb=0) == P.IS_OK
+    fs = lib.is_gemm_w4a8_floatscale_gate_up_silu_prepacked
+    assert fs(A, A, A, A, 8, 24, 256, 128, A, A, 1 << 20, None) == uns
+    assert fs(A, A, A, A, 128, 16, 256, 128, None, A, 1 << 20, None) == bad
+
+
 def test_describe_prepacked_names_the_kernels():
     one = P.is_describe_prepacked(1, 8192, 8192, 128, True, True)
     assert len(one) == 1 and one[0].startswith("gemm_decode_pk_kernel<1, ") and one[0].endswith("true, true>")
