@@ -114,6 +114,46 @@ def test_silu_mul_quantize_prefill_size(P):
     assert np.array_equal(host(xq), xq_ref)
 
 
+def _fp16_tie_pairs(count, seed):
+    """(gate, up) fp16 pairs whose single-precision product SiLU(gate) * up lies exactly half way between two fp16
+    values while the exact product does not: rounding it once, straight to fp16, gives the other neighbour."""
+    rng = np.random.default_rng(seed)
+    gs, us = [], []
+    while len(gs) < count:
+        g = (rng.uniform(3.0, 8.0, 1 << 20)).astype(np.float16)
+        u = (rng.uniform(4.0, 8.0, 1 << 20) * rng.choice([-1.0, 1.0], 1 << 20)).astype(np.float16)
+        s32 = O.silu_f32(g.astype(np.float32))
+        p32 = s32 * u.astype(np.float32)
+        tie = (p32.view(np.uint32) & 0x1FFF) == 0x1000          # 13 bits below fp16's last place: exactly one half
+        exact = s32.astype(np.float64) * u.astype(np.float64)
+        once = exact.astype(np.float16)                            # the exact product rounded once
+        twice = p32.astype(np.float16)
+        pick = np.flatnonzero(tie & (once != twice))
+        gs += g[pick].tolist()
+        us += u[pick].tolist()
+    return np.array(gs[:count], np.float16), np.array(us[:count], np.float16)
+
+
+def test_silu_mul_rounds_to_fp32_before_fp16(P):
+    """The product is rounded to single precision and then to fp16 (the stated definition), also where a conversion
+    merged into the multiply would round differently: rows whose largest product sits on such a tie (its fp16 value
+    is the token scale) and rows made of such products only."""
+    g, u = _fp16_tie_pairs(96, 77)
+    assert np.abs(O.silu_f32(g.astype(np.float32)) * u.astype(np.float32)).min() > 8.0
+    rng = np.random.default_rng(78)
+    M, inter = 64, 2048
+    gate = rng.standard_normal((M, inter)).astype(np.float16)
+    up = rng.standard_normal((M, inter)).astype(np.float16)
+    gate[:, 5], up[:, 5] = g[:M], u[:M]                            # the row's absmax
+    gate[:32, 100:132], up[:32, 100:132] = g[64:96], u[64:96]
+    gu = np.concatenate([gate, up], axis=1)
+    for rows in (gu, gu[:3], np.repeat(gu, 5, axis=0)):            # 1024 lanes per row, and 256
+        xq_ref, sa_ref = O.silu_mul_quantize_act_int8_token(rows)
+        xq, sa = P.is_silu_mul_quantize_act_int8_token(dev(rows))
+        assert np.array_equal(host(sa), sa_ref)
+        assert np.array_equal(host(xq), xq_ref)
+
+
 def test_silu_mul_quantize_empty(P):
     gu = torch.empty((0, 256), dtype=torch.float16, device="cuda:0")
     xq, sa = P.is_silu_mul_quantize_act_int8_token(gu)

@@ -113,3 +113,15 @@ def test_tiled_prepacked_kernel_instruction_level():
                 assert not (_vgprs(u.split(";")[0]) & dst) or u.startswith("global_load_dwordx4"), \
                     f"line {j}: `{u}` names registers of the load at line {i} before its wait"
     assert stores > 0 and loads > 0
+
+
+@pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not installed")
+def test_producers_round_to_fp32_before_fp16():
+    """RMSNorm and SiLU * up are defined with every operation rounded to single precision and the result then rounded
+    to fp16 (their codes are compared bit for bit).  The compiler can merge a final multiply into the conversion
+    (v_fma_mixlo_f16 / v_fma_mixhi_f16: one rounding of the exact product), which gives the other fp16 neighbour when
+    the fp32 product is an fp16 tie: no such instruction may be left in the producers."""
+    with tempfile.TemporaryDirectory() as tmp:
+        text = _compile_to_asm("act_producers.hip", tmp)
+    assert "v_cvt_pk_f16_f32" in text or "v_cvt_f16_f32" in text
+    assert not re.search(r"v_fma_mix(lo|hi)_f16", text)
