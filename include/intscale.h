@@ -20,11 +20,11 @@
  *   - Notation: X is [M,K] (tokens x in-features), W is [N,K] (out-features x in-features, so the layer is
  *     X * W^T as in Eq. (1)); groups run along K; NG = K / group; alpha = 2^alpha_log2.
  *   - Rounding is round-half-to-even everywhere; the quantisers divide in IEEE fp32.
- *   - Group sizes.  The quantisers take any even group size that divides K (Appendix A.2).  The GEMMs take multiples
- *     of 128 only and return IS_ERR_UNSUPPORTED for 32 and 64: their K step is one pair of 16x16x64 MFMAs (128 k) with
- *     ONE scale step behind it, and a group of 64 or 32 would need two or four scale steps per K step, on the path
- *     whose cost is exactly those steps.  The paper measures group 128 only (Sec. 5.1, Table 1), so this is recorded
- *     as a restriction rather than built.
+ *   - Group sizes.  The quantisers take any even group size that divides K (Appendix A.2).  The W4A8 GEMMs and linear
+ *     calls on the canonical layouts (plain, grouped, overflow-safe) take multiples of 128, and 32 and 64; other sizes
+ *     return IS_ERR_UNSUPPORTED.  Groups of 32 and 64 run one covering kernel for every M (one matrix instruction and
+ *     one scale step per group; no workspace), not the tuned kernels: the paper measures group 128 only (Sec. 5.1,
+ *     Table 1).  The calls on the kernel layout (is_prepack_w4 and *_prepacked) and W8A8 take multiples of 128 only.
  *   - Values the device computes stay on the device: the amplifier found by the heuristic search is written to a
  *     DEVICE int (alpha_log2_dev), not returned through a host pointer, because returning it would force a
  *     synchronisation inside the call; read it back when convenient.
@@ -115,7 +115,7 @@ int is_silu_mul_quantize_act_int8_token(const void* gate_up_fp16, int M, int int
  *   chan_scale   may be NULL (all ones)
  *   acc_out      may be NULL; otherwise receives the raw int32 accumulators [M,N]
  *   workspace    device scratch of at least is_gemm_workspace_bytes(M,N,K,group) bytes (may be NULL when that is 0)
- * Requirements: K and group multiples of 128 with group dividing K (group = K gives the coarse-grained GEMM of
+ * Requirements: group a multiple of 128, or 32 or 64, dividing K (group = K gives the coarse-grained GEMM of
  * Table 2's first column); 0 <= alpha_log2 <= 30; N >= 1; M >= 0 (M = 0 is a no-op).
  * Any int32 scale is accepted and multiplied exactly modulo 2^32.
  */

@@ -11,7 +11,8 @@ INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.environ.get("INTSCALE_LIBRARY", os.path.join(PKG_DIR, "libintscale.so"))
 
 SOURCES = ["api.hip", "quantize.hip", "act_producers.hip", "gemm_skinny.hip", "gemm_decode.hip", "gemm_prefill.hip",
-           "gemm_tile_w8.hip", "overflow.hip", "probe.hip", "prepack.hip", "gemm_decode_pk.hip", "gemm_tile_pk.hip"]
+           "gemm_tile_w8.hip", "overflow.hip", "probe.hip", "prepack.hip", "gemm_decode_pk.hip", "gemm_tile_pk.hip",
+           "gemm_small_group.hip"]
 HEADERS = ["is_common.h", "act_common.h", "tile_common.h", "pk_common.h"]
 
 HIPCC_FLAGS = [

@@ -33,7 +33,8 @@ inline bool ok_opt(const void* p) { return p == nullptr || aligned16(p); }
 int check_gemm_shape(int M, int N, int K, int group) {
     if (M < 0 || N <= 0 || K <= 0 || group <= 0) return IS_ERR_INVALID_ARG;
     if (K % group != 0 || (K & 1) || (group & 1)) return IS_ERR_INVALID_ARG;
-    if (group % 128 != 0) return IS_ERR_UNSUPPORTED;  // the kernels consume K in steps of 128
+    // the kernels consume K in steps of 128; groups of 32 and 64 have a covering kernel of their own
+    if (group % 128 != 0 && !gemm_small_group_covers(group)) return IS_ERR_UNSUPPORTED;
     if (M > (1 << 20)) return IS_ERR_UNSUPPORTED;  // launch-grid limit of the row-chunk dimension
     // the kernels address each tensor (one expert's weights and scales) with 32-bit byte offsets below 2 GB
     if ((long long)N * (K / 2) >= (1LL << 31) || (long long)N * (K / group) * 4 >= (1LL << 31) || K > (1 << 20))
@@ -55,10 +56,13 @@ bool general_forced_off() {
     return force && strcmp(force, "tiled") == 0;
 }
 
-bool wants_prefill(int M, int num_experts) { return !general_forced() && M > 64 * num_experts; }
+bool wants_prefill(int M, int num_experts, int group) {
+    return !general_forced() && !gemm_small_group_covers(group) && M > 64 * num_experts;
+}
 
 hipError_t launch_gemm(const GemmArgs& a, bool int_scale, void* workspace, hipStream_t stream) {
-    if (wants_prefill(a.M, a.num_experts)) return launch_gemm_prefill(a, int_scale, workspace, stream);
+    if (gemm_small_group_covers(a.group)) return launch_gemm_small_group(a, int_scale, stream);
+    if (wants_prefill(a.M, a.num_experts, a.group)) return launch_gemm_prefill(a, int_scale, workspace, stream);
     hipError_t err = hipSuccess;
     if (!general_forced() && try_launch_gemm_decode(a, int_scale, stream, &err)) return err;
     return launch_gemm_skinny(a, int_scale, stream);
@@ -190,12 +194,12 @@ size_t is_gemm_workspace_bytes(int M, int N, int K, int group) {
     if (check_gemm_shape(M, N, K, group) != IS_OK) return 0;
     // decode-sized problems reduce in LDS and need nothing; the tiled kernel keeps its zero-point corrections, a
     // transposed copy of the scales and a reordered copy of the activations
-    return wants_prefill(M, 1) ? gemm_prefill_workspace_bytes(1, M, N, K, group) : 0;
+    return wants_prefill(M, 1, group) ? gemm_prefill_workspace_bytes(1, M, N, K, group) : 0;
 }
 
 size_t is_gemm_grouped_workspace_bytes(int num_experts, int M_total, int N, int K, int group) {
     if (num_experts <= 0 || check_gemm_shape(M_total, N, K, group) != IS_OK) return 0;
-    return wants_prefill(M_total, num_experts) ? gemm_prefill_workspace_bytes(num_experts, M_total, N, K, group) : 0;
+    return wants_prefill(M_total, num_experts, group) ? gemm_prefill_workspace_bytes(num_experts, M_total, N, K, group) : 0;
 }
 
 static int gemm_common(const int8_t* xq, const float* a_scale, const void* qweight, const void* scale,
@@ -294,7 +298,7 @@ static int linear_common(const void* x_fp16, const void* qweight, const void* sc
     int8_t* xq = reinterpret_cast<int8_t*>(ws);
     float* sa = reinterpret_cast<float*>(ws + pad_256((size_t)M * K));
     unsigned char* rest = ws + pad_256((size_t)M * K) + pad_256((size_t)M * 4);
-    if (M == 1 && !general_forced()) {
+    if (M == 1 && !general_forced() && !gemm_small_group_covers(group)) {
         // one token: the decode kernel quantises it itself (every workgroup its own copy, the waves their K slices)
         GemmArgs a;
         a.xq = nullptr;
@@ -317,7 +321,7 @@ static int linear_common(const void* x_fp16, const void* qweight, const void* sc
         hipError_t err = hipSuccess;
         if (try_launch_linear_decode(a, int_scale, static_cast<hipStream_t>(stream), &err)) return hip_status(err);
     }
-    if (wants_prefill(M, 1) && gemm_prefill_takes_fp16(K)) {
+    if (wants_prefill(M, 1, group) && gemm_prefill_takes_fp16(K)) {
         // many tokens: the tiled kernel's activation preparation quantises on the way (no canonical codes written)
         GemmArgs a;
         a.xq = nullptr;

@@ -56,6 +56,9 @@ hipError_t launch_quantize_weights(const __half* w, int N, int K, int group, int
                                    uint8_t* qweight, float* scale_f32, int32_t* scale_i32, float* chan_scale,
                                    int* alpha_log2_dev, hipStream_t stream, int bits = 4);  // bits: 4 or 8 (one byte per code)
 hipError_t launch_gemm_skinny(const GemmArgs& a, bool int_scale, hipStream_t stream);
+// Groups of 32 and 64 (gemm_small_group.hip): one kernel for every M, plain and grouped form.
+bool gemm_small_group_covers(int group);
+hipError_t launch_gemm_small_group(const GemmArgs& a, bool int_scale, hipStream_t stream);
 bool try_launch_gemm_decode(const GemmArgs& a, bool int_scale, hipStream_t stream, hipError_t* err);
 // The same with the activation quantiser inside the kernel (a.x_fp16 set, a.M == 1).
 bool try_launch_linear_decode(const GemmArgs& a, bool int_scale, hipStream_t stream, hipError_t* err);

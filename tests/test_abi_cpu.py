@@ -57,7 +57,12 @@ def test_gemm_argument_validation():
     assert gemm_is(lib, K=200) == bad               # K not a multiple of group
     assert gemm_is(lib, a=-1) == bad
     assert gemm_is(lib, a=31) == bad
-    assert gemm_is(lib, K=192, G=64) == P.IS_ERR_UNSUPPORTED   # groups narrower than the kernels' K step
+    assert gemm_is(lib, K=192, G=96) == P.IS_ERR_UNSUPPORTED   # neither a multiple of 128 nor 32 or 64
+    assert gemm_is(lib, K=192, G=64, M=0) == P.IS_OK and gemm_is(lib, K=96, G=32, M=0) == P.IS_OK
+    assert gemm_is(lib, K=192, G=64, sc=None) == bad
+    # groups of 32 and 64 run a kernel that needs no workspace, whatever M is
+    assert lib.is_gemm_workspace_bytes(4096, 16, 256, 64) == 0 and lib.is_gemm_workspace_bytes(4096, 16, 256, 128) > 0
+    assert lib.is_gemm_grouped_workspace_bytes(2, 4096, 16, 256, 32) == 0
     assert gemm_is(lib, M=0) == P.IS_OK             # empty batch: nothing to do, nothing launched
     assert lib.is_gemm_workspace_bytes(8, 16, 256, 128) == 0
 
