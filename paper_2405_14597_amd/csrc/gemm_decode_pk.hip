@@ -721,10 +721,15 @@ bool pk_decode_plan(int M, int N, int K, int group, bool fp16_in, PkPlan* plan) 
     double best_cost = 0.0;
     for (int s = s_min; s <= s_min + 4 && s <= steps && s <= cus; ++s) {
         const int wgs = cus / s;
-        // blocks a workgroup carries (a CU takes about 23 per microsecond); a K split that is not forced costs about
-        // 2 microseconds of store, counter and reload at the end, and its partial tiles some traffic
-        const double load = (double)((n16 + wgs - 1) / wgs) * (double)((steps + s - 1) / s);
-        const double cost = load * (1.0 + 0.04 * (s - 1)) + (s > 1 ? 46.0 : 0.0);
+        // In units of one block's time (a CU takes about 23 per microsecond): the blocks a workgroup carries; for a K
+        // split about 2 microseconds of store, counter and reload at the end, and its partial tiles, mt KB each, written
+        // once and read once; the slab of the activations every workgroup pulls from L2 before its first block (about
+        // 2 microseconds for 128 KB).
+        const int slab_steps = (steps + s - 1) / s;
+        const int wg_tiles = (n16 + wgs - 1) / wgs;
+        const double load = (double)wg_tiles * (double)slab_steps;
+        const double fill = 46.0 * (double)(per_step * slab_steps) / (double)kActBudget;
+        const double cost = load + (s > 1 ? 46.0 + 2.0 * pl.mt * wg_tiles : 0.0) + fill;
         if (s == s_min || cost < best_cost) {
             best = s;
             best_cost = cost;
