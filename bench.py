@@ -83,10 +83,14 @@ def measured_peaks(P, torch):
     ms_read = time_ms(lambda: P.is_probe_stream_read(buf, sink), 10)
     ops = P.is_probe_mfma_i8(2000, sink)
     ms_mfma = time_ms(lambda: P.is_probe_mfma_i8(2000, sink), 5)
+    ops_r = P.is_probe_mfma_i8_random(2000, sink)
+    ms_mfma_r = time_ms(lambda: P.is_probe_mfma_i8_random(2000, sink), 5)
     del buf
     return dict(hbm_read_gbs=round(nbytes / ms_read / 1e6, 1), mfma_i8_tops=round(ops / ms_mfma / 1e9, 1),
+                mfma_i8_tops_random_operands=round(ops_r / ms_mfma_r / 1e9, 1),
                 how="library probe kernels, same run: 1 GiB streaming read; register-only loop of independent "
-                    "v_mfma_i32_16x16x64_i8, two waves per SIMD")
+                    "v_mfma_i32_16x16x64_i8, two waves per SIMD, on constant operands and on operands that change "
+                    "from one MFMA to the next (the chip lowers its clock when the matrix pipe's inputs toggle)")
 
 
 TRAFFIC_REQUIRED = True   # --no-traffic clears it
@@ -370,6 +374,7 @@ def family_main(args):
                         frac=round(ach / MFMA_I8_PEAK_TOPS, 4), traffic=measured_traffic(name, profile),
                         avg_launch_us=round(us, 3), alg_ops_per_launch=round(k["ops"] / k["launches"]),
                         frac_of_measured_peak=round(ach / peaks["mfma_i8_tops"], 4),
+                        frac_of_measured_peak_random_operands=round(ach / peaks["mfma_i8_tops_random_operands"], 4),
                         note="duration = the GEMM call on int8 codes: this kernel plus its activation preparation "
                              "kernel (a few per cent of the call; the committed kernel trace has both)")
         ach = k["bytes"] / k["launches"] / us / 1e3

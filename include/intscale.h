@@ -366,11 +366,15 @@ size_t is_gemm_safe_workspace_bytes(int M, int N, int K, int group);
  *   is_probe_stream_read  reads `bytes` bytes (a multiple of 16) at `src` (device) once, 16 bytes per lane
  *   is_probe_mfma_i8      every wave of a chip-filling launch issues `iters` rounds of 16 independent
  *                         v_mfma_i32_16x16x64_i8 on registers; *ops_out (host, may be NULL) = int8 operations done
- * `sink` is a device int the kernels may write (4-byte aligned).  Both enqueue one kernel on `stream`; time them with
+ *   is_probe_mfma_i8_random  the same loop on operands that differ from one MFMA to the next (pseudo-random bytes):
+ *                         the chip lowers its clock when the matrix pipe's inputs toggle, so this is the rate a real
+ *                         contraction can reach, the one above the rate at the highest clock
+ * `sink` is a device int the kernels may write (4-byte aligned).  Each enqueues one kernel on `stream`; time them with
  * events.  Errors as for the other calls.
  */
 int is_probe_stream_read(const void* src, size_t bytes, int* sink, void* stream);
 int is_probe_mfma_i8(int iters, int* sink, double* ops_out, void* stream);
+int is_probe_mfma_i8_random(int iters, int* sink, double* ops_out, void* stream);
 
 /* Human-readable name of a status code (static storage). */
 const char* is_status_string(int status);

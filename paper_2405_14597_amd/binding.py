@@ -64,6 +64,7 @@ EXPORTED_SYMBOLS = (
     "is_source_hash",
     "is_probe_stream_read",
     "is_probe_mfma_i8",
+    "is_probe_mfma_i8_random",
     "is_status_string",
     "is_last_hip_error",
 )
@@ -180,6 +181,8 @@ def load_library() -> ctypes.CDLL:
     lib.is_probe_stream_read.restype = ci
     lib.is_probe_mfma_i8.argtypes = [ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.is_probe_mfma_i8.restype = ci
+    lib.is_probe_mfma_i8_random.argtypes = [ci, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.is_probe_mfma_i8_random.restype = ci
     lib.is_status_string.argtypes = [ci]
     lib.is_status_string.restype = ctypes.c_char_p
     lib.is_last_hip_error.argtypes = []
@@ -599,6 +602,14 @@ def is_probe_mfma_i8(iters: int, sink, stream=None) -> float:
     """Enqueues the int8 MFMA loop; returns the int8 operations it performs."""
     ops = ctypes.c_double(0.0)
     _check("is_probe_mfma_i8", load_library().is_probe_mfma_i8(iters, _p(sink), ctypes.byref(ops), _stream_handle(stream)))
+    return float(ops.value)
+
+
+def is_probe_mfma_i8_random(iters: int, sink, stream=None) -> float:
+    """The same loop on operands that change from one MFMA to the next; returns the int8 operations it performs."""
+    ops = ctypes.c_double(0.0)
+    _check("is_probe_mfma_i8_random",
+           load_library().is_probe_mfma_i8_random(iters, _p(sink), ctypes.byref(ops), _stream_handle(stream)))
     return float(ops.value)
 
 

@@ -130,6 +130,11 @@ int is_probe_mfma_i8(int iters, int* sink, double* ops_out, void* stream) {
     return hip_status(launch_probe_mfma_i8(iters, sink, ops_out, static_cast<hipStream_t>(stream)));
 }
 
+int is_probe_mfma_i8_random(int iters, int* sink, double* ops_out, void* stream) {
+    if (iters <= 0 || sink == nullptr || (reinterpret_cast<uintptr_t>(sink) & 3u)) return IS_ERR_INVALID_ARG;
+    return hip_status(launch_probe_mfma_i8(iters, sink, ops_out, static_cast<hipStream_t>(stream), true));
+}
+
 static int quantize_weights_common(const void* w_fp16, int N, int K, int group, int alpha_log2, int scale_mode,
                                    void* qweight, float* scale_f32, int32_t* scale_i32, float* chan_scale,
                                    int* alpha_log2_dev, void* stream, int bits) {

@@ -82,6 +82,6 @@ hipError_t launch_derive_safe_scales(const int32_t* scale_i32, const float* chan
 
 // Measurement aids: a streaming read of `bytes` bytes, and a loop of independent int8 MFMAs (*ops = operations done).
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, int* sink, hipStream_t stream);
-hipError_t launch_probe_mfma_i8(int iters, int* sink, double* ops, hipStream_t stream);
+hipError_t launch_probe_mfma_i8(int iters, int* sink, double* ops, hipStream_t stream, bool random_operands = false);
 
 }  // namespace intscale
