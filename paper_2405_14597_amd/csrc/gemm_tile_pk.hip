@@ -457,54 +457,20 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
                 af[nxt][1] = *reinterpret_cast<const v4i*>(st + (i + 1) * 2048 + 1024 + lane16);
                 ci[nxt] = *reinterpret_cast<const v4i*>(st + ci_off + (i + 1) * 64);
             }
-#if defined(INTSCALE_TILE_VAR) && (INTSCALE_TILE_VAR & 1)
-            __builtin_amdgcn_s_setprio(1);
-#endif
 #pragma unroll
             for (int j = 0; j < kNS; ++j)
                 part[cur][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[cur][0], bu[j][0], ci[cur], 0, 0, 0);
 #pragma unroll
             for (int j = 0; j < kNS; ++j)
                 part[cur][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[cur][1], bu[j][1], part[cur][j], 0, 0, 0);
-#if defined(INTSCALE_TILE_VAR) && (INTSCALE_TILE_VAR & 1)
-            __builtin_amdgcn_s_setprio(0);
-#endif
             // the scale step of the sub-tile before, under this one's MFMAs
             if (i > 0) {
 #pragma unroll
                 for (int j = 0; j < kNS; ++j) scale_into(acc[i - 1][j], part[nxt][j], scl[j]);
             }
-#if defined(INTSCALE_TILE_VAR) && (INTSCALE_TILE_VAR & 2)
-            __builtin_amdgcn_sched_barrier(0);
-#endif
         }
 #pragma unroll
         for (int j = 0; j < kNS; ++j) scale_into(acc[MS - 1][j], part[(MS - 1) & 1][j], scl[j]);
-#if defined(INTSCALE_TILE_SCHED)
-        // The order the step's instructions are issued in (the compiler, left alone, reads a sub-tile's operands just in
-        // front of their use and puts a sub-tile's scale step right behind its own MFMAs, so that the wave waits for
-        // both): every MFMA with its share of the vector instructions that do not depend on it behind it.
-        if constexpr (INT_SCALE && !WIDE && !GROUPED && MS == 8) {
-            constexpr int kVpm0 = INTSCALE_TILE_SCHED_V0;  // unpacking: vector instructions per MFMA of the first sub-tile
-            __builtin_amdgcn_sched_group_barrier(0x100, INTSCALE_TILE_SCHED_D0, 0);  // weights, scales, first operands
-#pragma unroll
-            for (int q = 0; q < 2 * kNS; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x002, kVpm0, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (q == 0) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);  // operands of the second sub-tile
-            }
-#pragma unroll
-            for (int i = 1; i < MS; ++i) {
-                if (i + 1 < MS) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
-#pragma unroll
-                for (int q = 0; q < 2 * kNS; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-                }
-            }
-            __builtin_amdgcn_sched_group_barrier(0x002, 4 * kNS, 0);
-        }
-#endif
     }
 
     // ---- epilogue, once per output: FLOAT(acc) * s_a[m] * c[n] / alpha (Eq. (2)), or facc * s_a[m] (Eq. (1))
