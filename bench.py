@@ -20,7 +20,7 @@ takes, and the roofline fractions; `alpha_sweep` shows the accuracy / overflow t
 
 `--workload llama2_7b` (M in {1, 16, 64}) and `--workload llama3_8b` (M = 4096, Student-t activations) run the same
 code on those shapes; `moe`, `w8a8` and `producers` measure the mixture-of-experts form, fine-grained W8A8 and the
-fused activation producers (calls that take the canonical layouts).
+fused activation producers; `gate_up` the gate_up GEMM with SiLU(gate) * up as its epilogue against the unfused sequence.
 """
 from __future__ import annotations
 
@@ -62,7 +62,8 @@ def parse_args():
 
 def measured_peaks(P, torch):
     """What this chip delivers, from the same run: a plain streaming read of 1 GiB out of HBM, and a register-only
-    loop of int8 MFMAs (the library's two probe kernels, timed with events)."""
+    loop of int8 MFMAs, on constant operands and on operands that change from one MFMA to the next (the library's probe
+    kernels, timed with events)."""
     dev = torch.device("cuda:0")
     buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     buf.fill_(1)
