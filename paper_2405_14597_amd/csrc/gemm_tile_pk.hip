@@ -213,62 +213,72 @@ __global__ __launch_bounds__(256) void prepare_activations_grouped_pk_kernel(con
 }
 
 // The same straight from fp16 activations (the linear call): the per-token quantiser of Appendix A.1 and the
-// preparation, in two kernels so that both fill the chip: the token scales first (one workgroup per row), then the
-// rounding on the block grid of the kernel above (the second read of the activations comes from cache).
-__global__ __launch_bounds__(256) void token_scales_kernel(const __half* __restrict__ x, int M, int K,
-                                                           float* __restrict__ a_scale) {
-    __shared__ float red[4];
-    const int m = blockIdx.x;
-    const uint4* row = reinterpret_cast<const uint4*>(x + (size_t)m * K);  // 8 fp16 values each
-    const int n8 = K >> 3;
-    float amax = 0.0f;
-    for (int c = threadIdx.x; c < n8; c += 4 * 256) {  // four loads in flight per lane
-        uint4 v[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = row[min(c + j * 256, n8 - 1)];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) amax = fmaxf(amax, absmax8(v[j]));
-    }
-    amax = block_max<4>(amax, red);
-    if (threadIdx.x == 0) a_scale[m] = amax / 127.0f;
-}
+// preparation in one kernel.  A workgroup of 16 waves takes 8 token rows (half of a 16-row
+// tile), reads them once, keeps the first kResidentSteps K steps of every wave in registers between the row maximum and
+// the rounding (longer rows are read a second time, from cache), and writes its half of every 2 KB block as 128-byte
+// pieces.  256 workgroups for 2048 rows: the chip is full, and the activations cross the memory interface once.
+// Lane (h, kb, r): row r of the eight, the 16 codes k = 64 h + 16 kb .. + 15 of a K step; wave w takes the K steps
+// w, w + 16, ...
+constexpr int kRowsPerWg = 8, kRowWaves = 16, kResidentSteps = 8;
 
-__global__ __launch_bounds__(256) void quantize_prepare_activations_pk_kernel(const __half* __restrict__ x, int M, int K,
-                                                                              const float* __restrict__ a_scale,
-                                                                              int8_t* __restrict__ xp,
-                                                                              int32_t* __restrict__ c0,
-                                                                              int32_t* __restrict__ counters,
-                                                                              int ncounters) {
-    if (blockIdx.x == 0 && blockIdx.y == 0)  // the tiled kernel's arrival counters start at zero
-        for (int i = threadIdx.x; i < ncounters; i += 256) counters[i] = 0;
+__global__ __launch_bounds__(kRowWaves* kWave) void quantize_prepare_rows_pk_kernel(const __half* __restrict__ x, int M, int K,
+                                                                                   float* __restrict__ a_scale,
+                                                                                   int8_t* __restrict__ xp,
+                                                                                   int32_t* __restrict__ c0,
+                                                                                   int32_t* __restrict__ counters,
+                                                                                   int ncounters) {
+    __shared__ float red[kRowWaves][kRowsPerWg];
+    if (blockIdx.x == 0)  // the tiled kernel's arrival counters start at zero
+        for (int i = threadIdx.x; i < ncounters; i += kRowWaves * kWave) counters[i] = 0;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int r = lane & 15, kb = lane >> 4;
-    const int mt = blockIdx.x, m = 16 * mt + r;
+    const int r = lane & 7, kb = (lane >> 3) & 3, h = lane >> 5;
+    const int mt = blockIdx.x >> 1, half = blockIdx.x & 1;
+    const int m = 16 * mt + 8 * half + r;
     const int steps = K >> 7;
-    const int s0 = (blockIdx.y * 4 + wave) * kPrepSteps;
-    const __half* src = x + (size_t)min(m, M - 1) * K + kb * 16;
-    const float s = a_scale[min(m, M - 1)];
-    uint4 v[kPrepSteps][2][2];
+    const uint4* src = reinterpret_cast<const uint4*>(x + (size_t)min(m, M - 1) * K + h * 64 + kb * 16);  // + 16 uint4 per step
+    uint4 v[kResidentSteps][2];
+    float amax = 0.0f;
 #pragma unroll
-    for (int j = 0; j < kPrepSteps; ++j)
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                const int st = min(s0 + j, steps - 1);
-                v[j][h][q] = *reinterpret_cast<const uint4*>(src + st * 128 + h * 64 + q * 8);
-            }
-#pragma unroll
-    for (int j = 0; j < kPrepSteps; ++j)
-        if (s0 + j < steps) {
-            uint4 codes[2];
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const uint2 lo = quantize8(v[j][h][0], s), hi = quantize8(v[j][h][1], s);  // the canonical 16 codes
-                codes[h] = m < M ? make_uint4(lo.x, lo.y, hi.x, hi.y) : make_uint4(0u, 0u, 0u, 0u);
-            }
-            store_block((size_t)mt * steps + s0 + j, lane, codes[0], codes[1], xp, c0);
+    for (int j = 0; j < kResidentSteps; ++j) {
+        const int st = wave + j * kRowWaves;
+        v[j][0] = v[j][1] = make_uint4(0u, 0u, 0u, 0u);
+        if (st < steps) {  // (uniform over the wave)
+            v[j][0] = src[st * 16];
+            v[j][1] = src[st * 16 + 1];
         }
+    }
+#pragma unroll
+    for (int j = 0; j < kResidentSteps; ++j) amax = fmaxf(amax, fmaxf(absmax8(v[j][0]), absmax8(v[j][1])));
+    for (int st = wave + kResidentSteps * kRowWaves; st < steps; st += kRowWaves)
+        amax = fmaxf(amax, fmaxf(absmax8(src[st * 16]), absmax8(src[st * 16 + 1])));
+    // the row's maximum: over the lanes (h, kb) of the row, then over the waves
+    amax = fmaxf(amax, __shfl_xor(amax, 8, kWave));
+    amax = fmaxf(amax, __shfl_xor(amax, 16, kWave));
+    amax = fmaxf(amax, __shfl_xor(amax, 32, kWave));
+    if (lane < kRowsPerWg) red[wave][lane] = amax;
+    __syncthreads();
+    amax = red[0][r];
+#pragma unroll
+    for (int w = 1; w < kRowWaves; ++w) amax = fmaxf(amax, red[w][r]);
+    const float s = amax / 127.0f;  // Appendix A.1, n = 8
+    if (threadIdx.x < kRowsPerWg && m < M) a_scale[m] = s;
+    auto emit = [&](int st, uint4 lo8, uint4 hi8) {
+        const uint2 lo = quantize8(lo8, s), hi = quantize8(hi8, s);  // the canonical 16 codes
+        const uint4 codes = m < M ? make_uint4(lo.x, lo.y, hi.x, hi.y) : make_uint4(0u, 0u, 0u, 0u);
+        const size_t blk = (size_t)mt * steps + st;
+        reinterpret_cast<uint4*>(xp + blk * 2048)[h * 64 + kb * 16 + 8 * half + r] = codes;
+        int sum = sum16(codes);
+        sum += __shfl_xor(sum, 8, kWave);
+        sum += __shfl_xor(sum, 16, kWave);
+        sum += __shfl_xor(sum, 32, kWave);
+        if (lane < kRowsPerWg) c0[blk * 16 + 8 * half + lane] = -8 * sum;
+    };
+#pragma unroll
+    for (int j = 0; j < kResidentSteps; ++j) {
+        const int st = wave + j * kRowWaves;
+        if (st < steps) emit(st, v[j][0], v[j][1]);  // (uniform over the wave)
+    }
+    for (int st = wave + kResidentSteps * kRowWaves; st < steps; st += kRowWaves) emit(st, src[st * 16], src[st * 16 + 1]);
 }
 
 typedef float v4f_t __attribute__((ext_vector_type(4)));
@@ -767,7 +777,7 @@ bool gemm_tile_pk_takes_fp16(int K) { return (K & 127) == 0; }
 
 void gemm_tile_pk_kernel_names(int K, bool int_scale, bool fp16_in, char* buf, size_t len, bool silu) {
     char prep[96];
-    if (fp16_in) snprintf(prep, sizeof prep, "token_scales_kernel\nquantize_prepare_activations_pk_kernel");
+    if (fp16_in) snprintf(prep, sizeof prep, "quantize_prepare_rows_pk_kernel");
     else snprintf(prep, sizeof prep, "prepare_activations_pk_kernel");
     snprintf(buf, len, "%s\ngemm_tile%s_pk_kernel<%s>", prep, silu ? "_silu" : "", int_scale ? "true" : "false");
 }
@@ -787,9 +797,8 @@ hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace,
     const int per_wg = 4 * kPrepSteps;
     const dim3 blocks(mtiles, ((a.K >> 7) + per_wg - 1) / per_wg);
     if (a.x_fp16) {  // fp16 activations: quantised on the way, the token scales go to a.a_scale_out (= a.a_scale)
-        hipLaunchKernelGGL(token_scales_kernel, dim3(a.M), dim3(256), 0, stream, a.x_fp16, a.M, a.K, a.a_scale_out);
-        hipLaunchKernelGGL(quantize_prepare_activations_pk_kernel, blocks, dim3(256), 0, stream, a.x_fp16, a.M, a.K,
-                           a.a_scale_out, xp, c0, sp.counters, sp.rem);
+        hipLaunchKernelGGL(quantize_prepare_rows_pk_kernel, dim3(2 * mtiles), dim3(kRowWaves * kWave), 0, stream, a.x_fp16,
+                           a.M, a.K, a.a_scale_out, xp, c0, sp.counters, sp.rem);
     } else {
         hipLaunchKernelGGL(prepare_activations_pk_kernel, blocks, dim3(256), 0, stream, a.xq, a.M, a.K, xp, c0,
                            sp.counters, sp.rem);

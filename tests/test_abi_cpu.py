@@ -255,7 +255,7 @@ def test_describe_prepacked_names_the_kernels():
     dec = P.is_describe_prepacked(32, 8192, 8192, 128, False, False)
     assert dec[0].startswith("gemm_decode_pk_kernel<2, ") and dec[0].endswith("false, false>")
     til = P.is_describe_prepacked(2048, 8192, 8192, 128, True, True)
-    assert til == ["token_scales_kernel", "quantize_prepare_activations_pk_kernel", "gemm_tile_pk_kernel<true>"]
+    assert til == ["quantize_prepare_rows_pk_kernel", "gemm_tile_pk_kernel<true>"]
     assert P.is_describe_prepacked(2048, 8192, 8192, 128, False, False)[0] == "prepare_activations_pk_kernel"
     with pytest.raises(P.IntScaleError):
         P.is_describe_prepacked(8, 16, 256, 64)

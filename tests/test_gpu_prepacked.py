@@ -276,13 +276,15 @@ def test_prepacked_tiled_workspace_contents_do_not_matter(P):
 
 
 @pytest.mark.parametrize("M,N,K", [(130, 512, 4096), (70, 272, 8192), (200, 256, 14336), (66, 128, 28672), (257, 40, 2048),
-                                   (70, 48, 40960)])
+                                   (70, 48, 40960), (72, 32, 256), (89, 16, 128), (300, 48, 1152)])
 def test_prepacked_tiled_linear_fp16(P, M, N, K):
-    """More than 64 fp16 tokens: the tiled kernel's preparation quantises on the way (token scales, then rounding on the
-    block grid)."""
+    """More than 64 fp16 tokens: the tiled kernel's preparation quantises on the way (a workgroup per 8 token rows: row
+    maxima, then the rounding into the kernel layout; rows longer than the registers hold are read twice).  Fewer K
+    steps than waves, 8-row halves past M, an all-zero row."""
     rng = np.random.default_rng(7600 + M + N + K)
     _, qw, IS, s, _, c = rand_quantised(rng, 1, N, K)
     x = S.activations_student_t(M, K, 78 + K % 13)
+    x[M // 2] = 0
     xq_ref, sa_ref = O.quantize_act_int8_token(x)
     ref = O.gemm_w4a8_intscale(xq_ref, sa_ref, qw, IS, c, G, 10)
     out, acc = P.is_linear_w4a8_intscale_prepacked(dev(x), P.is_prepack_w4(dev(qw), dev(IS), G), dev(c), 10,
