@@ -159,16 +159,10 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
             goff_run += 64;
         }
     };
-    issue_state();
-    sub_run = sub_i;
-#pragma unroll
-    for (int u = 0; u < DT; ++u) issue(u);
-    issue_advance();
-    __builtin_amdgcn_sched_barrier(0);
-    PK_MARK(1);
-    if (B <= 0) return;  // uniform over the workgroup, before any barrier; its requests lay outside the buffers
-
-    // ---- the activations of the slab, requested behind the stream's first blocks and written to LDS below.
+    // ---- the activations of the slab: requested in FRONT of the weight stream and written to LDS below.  A wave's
+    // loads return in order, and these come from L2: asked for first, they are in LDS while the first weights are
+    // still on their way from HBM; asked for behind the ring's first blocks they arrive behind them, and the fill
+    // and its barrier then stand between the weights' arrival and their use (about 1 us per call).
     // A fill unit is 8 token rows x one K step (8 x 128 bytes); unit u = step * (row blocks) + row block.
     const int rs = p.rows;
     const int unit_b = 64 * rs;  // bytes of one (step, token tile, MFMA half) unit: 4 k-chunks x rs rows x 16 bytes
@@ -245,9 +239,36 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
     }
     __builtin_amdgcn_sched_barrier(0);
 
-    // ---- token scales of this lane's output rows; channel scales of this workgroup's row tiles.  The latter go
-    // through LDS, so that an epilogue in mid-stream never waits on the vector memory counter, behind which the whole
-    // weight stream queues.
+    // The channel scales of this workgroup's row tiles pass through LDS in front of the main loop (so that an epilogue in
+    // mid-stream never waits on the vector memory counter, behind which the whole weight stream queues).  Up to 32 token
+    // rows they are asked for here, in front of the weight stream, so that the LDS writes below wait for them and not
+    // for the whole first ring; with four token tiles (8 waves, twice the loads per lane) that costs more than it saves.
+    float* lds_cs = reinterpret_cast<float*>(smem + p.cs_offset);
+    constexpr int kCsPerThread = 1024 / (W * kWave) * 4;  // 256 row tiles x 16 rows per workgroup at most
+    constexpr bool kCsFirst = MT < 4;
+    const int cs_words = (t1 - t0) * 16;
+    float cs_reg[kCsPerThread];
+    auto load_cs = [&]() {
+        const rsrc_t cres = make_rsrc(a.chan_scale, a.chan_scale ? (size_t)a.N * 4 : 0);
+#pragma unroll
+        for (int i = 0; i < kCsPerThread; ++i) {
+            if (i > 0 && i * W * kWave >= cs_words) break;  // uniform: a workgroup seldom has more than a few tiles
+            const int w = (int)threadIdx.x + i * W * kWave;
+            cs_reg[i] = __int_as_float(
+                __builtin_amdgcn_raw_buffer_load_b32(cres, w < cs_words ? (t0 * 16 + w) * 4 : kOutOfRange, 0, 0));
+        }
+    };
+    if constexpr (kCsFirst) load_cs();
+    issue_state();
+    sub_run = sub_i;
+#pragma unroll
+    for (int u = 0; u < DT; ++u) issue(u);
+    issue_advance();
+    __builtin_amdgcn_sched_barrier(0);
+    PK_MARK(1);
+    if (B <= 0) return;  // uniform over the workgroup, before any barrier; its requests lay outside the buffers
+
+    // ---- token scales of this lane's output rows
     float sa[MT][4];
     if constexpr (!FUSEQ) {
         const rsrc_t ares = make_rsrc(a.a_scale, (size_t)a.M * 4);  // rows past M read as zero
@@ -257,20 +278,7 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
             for (int r = 0; r < 4; ++r)
                 sa[t][r] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(ares, (16 * t + 4 * kb + r) * 4, 0, 0));
     }
-    float* lds_cs = reinterpret_cast<float*>(smem + p.cs_offset);
-    constexpr int kCsPerThread = 1024 / (W * kWave) * 4;  // 256 row tiles x 16 rows per workgroup at most
-    const int cs_words = (t1 - t0) * 16;
-    float cs_reg[kCsPerThread];
-    {
-        const rsrc_t cres = make_rsrc(a.chan_scale, a.chan_scale ? (size_t)a.N * 4 : 0);
-#pragma unroll
-        for (int i = 0; i < kCsPerThread; ++i) {
-            if (i > 0 && i * W * kWave >= cs_words) break;  // uniform: a workgroup seldom has more than a few tiles
-            const int w = (int)threadIdx.x + i * W * kWave;
-            cs_reg[i] = __int_as_float(
-                __builtin_amdgcn_raw_buffer_load_b32(cres, w < cs_words ? (t0 * 16 + w) * 4 : kOutOfRange, 0, 0));
-        }
-    }
+    if constexpr (!kCsFirst) load_cs();
     __builtin_amdgcn_sched_barrier(0);
     PK_MARK(2);
 
