@@ -627,16 +627,32 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
         for (int t = 0; t < MT; ++t)
 #pragma unroll
             for (int r = 0; r < 4; ++r) v[t][r] = 0;
-        for (int s = 0; s < p.slabs; ++s) {
-            int32_t* src = a.partials + ((size_t)(tt * p.slabs + s) * MT) * 256 + lane;
+        // (kSlabsAtOnce slabs' partials are in flight together: a round trip to memory per slab was most of what the
+        // last arriver spends; they are added in slab order all the same)
+        constexpr int kSlabsAtOnce = MT == 4 ? 2 : 4;
+        for (int s0 = 0; s0 < p.slabs; s0 += kSlabsAtOnce) {
+            int o[kSlabsAtOnce][MT][4];
 #pragma unroll
-            for (int t = 0; t < MT; ++t)
+            for (int u = 0; u < kSlabsAtOnce; ++u) {
+                if (u > 0 && s0 + u >= p.slabs) break;  // uniform
+                int32_t* src = a.partials + ((size_t)(tt * p.slabs + s0 + u) * MT) * 256 + lane;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int o = __hip_atomic_load(src + (t * 4 + r) * kWave, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if constexpr (INT_SCALE) v[t][r] += o;
-                    else v[t][r] += __int_as_float(o);
-                }
+                for (int t = 0; t < MT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        o[u][t][r] = __hip_atomic_load(src + (t * 4 + r) * kWave, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+            for (int u = 0; u < kSlabsAtOnce; ++u) {
+                if (u > 0 && s0 + u >= p.slabs) break;
+#pragma unroll
+                for (int t = 0; t < MT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        if constexpr (INT_SCALE) v[t][r] += o[u][t][r];
+                        else v[t][r] += __int_as_float(o[u][t][r]);
+                    }
+            }
         }
         epilogue(tt, v);
         if (lane == 0) __hip_atomic_store(a.counters + tt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // zero for the next call
