@@ -185,8 +185,23 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
                           (fill_row & 15) * 16;
     // (a batch made of whole rounds over the waves, the usual case, runs without a test per unit)
     const bool fill_has_place = fill_row < (MT == 1 ? rs : 16 * MT);  // rows past M arrive as zeros; rows without a place in LDS are not written
+    // One token row: its codes are contiguous and the operand order is the natural order of k, so the fill is a plain
+    // copy, 16 bytes per lane, and only the first waves take part (8 KB are 8 wave loads; dealt by the unit scheme
+    // above, every wave would fetch four pieces of 128 bytes, and the barrier behind the fill would wait for the
+    // last wave's share, which is requested a microsecond and more after the first wave's).
+    const int row_chunks = ksl * 8;
+    const bool one_row = MT == 1 && rs == 1 && row_chunks <= kFill * W * kWave;
     [[maybe_unused]] auto fill_load = [&](int base) {
         const rsrc_t xres = make_rsrc(a.xq, (size_t)a.M * a.K);
+        if (one_row) {
+#pragma unroll
+            for (int i = 0; i < kFill; ++i) {
+                if ((i * W + wave) * kWave >= row_chunks) break;  // uniform over the wave
+                const int c = (int)threadIdx.x + i * W * kWave;
+                xraw[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, c < row_chunks ? s_lo * 128 + c * 16 : kOutOfRange, 0, 0);
+            }
+            return;
+        }
         const int st0 = base >> rb_log;
         const int rounds = min(kFill, (units - base) / W);  // rounds in which every wave has a unit
         if (rounds == kFill || rounds * W == units - base) {  // and no wave has one beyond them
@@ -207,6 +222,15 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
         }
     };
     [[maybe_unused]] auto fill_store = [&](int base) {
+        if (one_row) {
+#pragma unroll
+            for (int i = 0; i < kFill; ++i) {
+                if ((i * W + wave) * kWave >= row_chunks) break;
+                const int c = (int)threadIdx.x + i * W * kWave;
+                if (c < row_chunks) *reinterpret_cast<v4i*>(smem + c * 16) = xraw[i];
+            }
+            return;
+        }
         const int st0 = base >> rb_log;
         if (!fill_has_place) return;
         const int rounds = min(kFill, (units - base) / W);
@@ -308,7 +332,7 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
         if (a.a_scale_out && slab == 0 && t0 == 0 && threadIdx.x == 0) *a.a_scale_out = s_a;  // the owner of tile 0
     } else {
         fill_store(0);
-        for (int base = kFill * W; base < units; base += kFill * W) {
+        for (int base = kFill * W; base < units && !one_row; base += kFill * W) {
             fill_load(base);
             fill_store(base);
         }
