@@ -75,7 +75,9 @@ __device__ __forceinline__ int mad_i24(int a, int b, int c) {
     return r;
 }
 
-template <int MT, int DT, int WAVES, bool INT_SCALE, bool FUSEQ>
+// NR: result registers per lane and token tile that carry token rows of the call (lane (li, kb) holds token rows
+// 16 t + 4 kb + r): 4 in general, 1 for a single token row, whose scale step then costs a quarter of the instructions.
+template <int MT, int DT, int WAVES, int NR, bool INT_SCALE, bool FUSEQ>
 __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPlan& p, unsigned char* smem) {
     using acc_t = typename std::conditional<INT_SCALE, int, float>::type;
     static_assert(DT >= 2 && DT <= 8, "ring of 2 to 8 blocks");
@@ -449,12 +451,12 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
 #pragma unroll
             for (int t = 0; t < MT; ++t)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) acc[t][r] = fmaf((float)part[t][r], s_f, acc[t][r]);  // C' += float(C_g) * s_g
+                for (int r = 0; r < NR; ++r) acc[t][r] = fmaf((float)part[t][r], s_f, acc[t][r]);  // C' += float(C_g) * s_g
         } else if constexpr (WIDE) {
 #pragma unroll
             for (int t = 0; t < MT; ++t)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
+                for (int r = 0; r < NR; ++r) {
                     int prod = (part[t][r] >> 4) * s_i;
                     asm volatile("" : "+v"(prod));  // else a 64-bit multiply-add with register pairs
                     acc[t][r] += prod;
@@ -463,7 +465,7 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
 #pragma unroll
             for (int t = 0; t < MT; ++t)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) acc[t][r] = mad_i24(part[t][r] >> 4, s_i, acc[t][r]);  // C'' += C_g * s_g^INT
+                for (int r = 0; r < NR; ++r) acc[t][r] = mad_i24(part[t][r] >> 4, s_i, acc[t][r]);  // C'' += C_g * s_g^INT
         }
     };
     // One turn of the ring.  REFILL: every slot, once used, takes the same slot of the next turn (the wave's last turn
@@ -687,15 +689,15 @@ __device__ __forceinline__ void decode_pk_body(const PkArgs& a, const PkKernelPl
     PK_MARK(6);
 }
 
-template <int MT, int DT, int WAVES, bool INT_SCALE, bool FUSEQ>
+template <int MT, int DT, int WAVES, int NR, bool INT_SCALE, bool FUSEQ>
 __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_pk_kernel(PkArgs a, PkKernelPlan p) {
     extern __shared__ __align__(16) unsigned char smem_pk[];
-    decode_pk_body<MT, DT, WAVES, INT_SCALE, FUSEQ>(a, p, smem_pk);
+    decode_pk_body<MT, DT, WAVES, NR, INT_SCALE, FUSEQ>(a, p, smem_pk);
 }
 
-template <int MT, int DT, int WAVES, bool INT_SCALE, bool FUSEQ>
+template <int MT, int DT, int WAVES, int NR, bool INT_SCALE, bool FUSEQ>
 hipError_t launch_pk(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan, int device, hipStream_t stream) {
-    auto kern = gemm_decode_pk_kernel<MT, DT, WAVES, INT_SCALE, FUSEQ>;
+    auto kern = gemm_decode_pk_kernel<MT, DT, WAVES, NR, INT_SCALE, FUSEQ>;
     if (plan.lds_bytes > 64 * 1024) {
         static bool raised[64] = {};  // per instantiation and device
         if (device < 0 || device >= 64 || !raised[device]) {
@@ -717,25 +719,26 @@ constexpr int ring_depth(int mt) { return mt == 4 ? 6 : INTSCALE_PK_RING; }
 // Waves per workgroup the instantiations exist for (dispatch_waves and pk_decode_kernel_name both round with this).
 constexpr int waves_instance(int mt, int waves) { return waves <= 4 ? 4 : (waves <= 8 || mt == 4) ? 8 : 16; }
 
-template <bool INT_SCALE, bool FUSEQ, int MT>
+template <bool INT_SCALE, bool FUSEQ, int MT, int NR>
 hipError_t dispatch_waves(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan, int device, hipStream_t stream) {
     constexpr int DT = ring_depth(MT);
     constexpr bool FQ = MT == 1 && FUSEQ;
     switch (waves_instance(MT, plan.waves)) {
-        case 4: return launch_pk<MT, DT, 4, INT_SCALE, FQ>(a, kp, plan, device, stream);
-        case 8: return launch_pk<MT, DT, 8, INT_SCALE, FQ>(a, kp, plan, device, stream);
+        case 4: return launch_pk<MT, DT, 4, NR, INT_SCALE, FQ>(a, kp, plan, device, stream);
+        case 8: return launch_pk<MT, DT, 8, NR, INT_SCALE, FQ>(a, kp, plan, device, stream);
         default:
-            if constexpr (MT != 4) return launch_pk<MT, DT, 16, INT_SCALE, FQ>(a, kp, plan, device, stream);
+            if constexpr (MT != 4) return launch_pk<MT, DT, 16, NR, INT_SCALE, FQ>(a, kp, plan, device, stream);
             return hipErrorInvalidValue;
     }
 }
 
 template <bool INT_SCALE>
 hipError_t dispatch_pk(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan, int device, hipStream_t stream) {
-    if (a.x_fp16) return dispatch_waves<INT_SCALE, true, 1>(a, kp, plan, device, stream);
-    if (plan.mt == 1) return dispatch_waves<INT_SCALE, false, 1>(a, kp, plan, device, stream);
-    if (plan.mt == 2) return dispatch_waves<INT_SCALE, false, 2>(a, kp, plan, device, stream);
-    return dispatch_waves<INT_SCALE, false, 4>(a, kp, plan, device, stream);
+    if (a.x_fp16) return dispatch_waves<INT_SCALE, true, 1, 1>(a, kp, plan, device, stream);
+    if (a.M == 1) return dispatch_waves<INT_SCALE, false, 1, 1>(a, kp, plan, device, stream);
+    if (plan.mt == 1) return dispatch_waves<INT_SCALE, false, 1, 4>(a, kp, plan, device, stream);
+    if (plan.mt == 2) return dispatch_waves<INT_SCALE, false, 2, 4>(a, kp, plan, device, stream);
+    return dispatch_waves<INT_SCALE, false, 4, 4>(a, kp, plan, device, stream);
 }
 
 constexpr size_t kActBudget = 128 * 1024;  // LDS bytes for the slab's activations (the fused quantiser's scratch follows)
@@ -825,7 +828,8 @@ bool pk_decode_plan(int M, int N, int K, int group, bool fp16_in, PkPlan* plan) 
 // The instantiation launch_gemm_decode_pk picks for this plan, as a kernel trace names it.
 void pk_decode_kernel_name(const PkPlan& plan, bool int_scale, bool fp16_in, char* buf, size_t len) {
     const int mt = fp16_in ? 1 : plan.mt;
-    snprintf(buf, len, "gemm_decode_pk_kernel<%d, %d, %d, %s, %s>", mt, ring_depth(mt), waves_instance(mt, plan.waves),
+    const int nr = fp16_in || (plan.mt == 1 && plan.rows == 1) ? 1 : 4;  // one token row (plan.rows = 1 only then)
+    snprintf(buf, len, "gemm_decode_pk_kernel<%d, %d, %d, %d, %s, %s>", mt, ring_depth(mt), waves_instance(mt, plan.waves), nr,
              int_scale ? "true" : "false", fp16_in ? "true" : "false");
 }
 
