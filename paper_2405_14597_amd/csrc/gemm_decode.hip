@@ -546,13 +546,9 @@ hipError_t launch_decode(const GemmArgs& a, const DecodePlan& p, int grid, hipSt
                         (FUSEQ || XLDS ? (size_t)WAVES * (4 + XS * 128) : 0);
     auto kern = gemm_decode_kernel<MT, XS, DT, WAVES, INT_SCALE, FUSEQ, XLDS>;
     if (smem > 64 * 1024) {
-        static bool raised = false;  // per instantiation
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            if (e != hipSuccess) return e;
-            raised = true;
-        }
+        static LdsLimit limit;  // per instantiation
+        const hipError_t e = limit.raise(reinterpret_cast<const void*>(kern));
+        if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES * kWave), smem, stream, a, p);
     return hipGetLastError();

@@ -696,16 +696,12 @@ __global__ __launch_bounds__(WAVES * kWave) void gemm_decode_pk_kernel(PkArgs a,
 }
 
 template <int MT, int DT, int WAVES, int NR, bool INT_SCALE, bool FUSEQ>
-hipError_t launch_pk(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan, int device, hipStream_t stream) {
+hipError_t launch_pk(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan, hipStream_t stream) {
     auto kern = gemm_decode_pk_kernel<MT, DT, WAVES, NR, INT_SCALE, FUSEQ>;
     if (plan.lds_bytes > 64 * 1024) {
-        static bool raised[64] = {};  // per instantiation and device
-        if (device < 0 || device >= 64 || !raised[device]) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            if (e != hipSuccess) return e;
-            if (device >= 0 && device < 64) raised[device] = true;
-        }
+        static LdsLimit limit;  // per instantiation
+        const hipError_t e = limit.raise(reinterpret_cast<const void*>(kern));
+        if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kern, dim3(plan.wg_per_slab, plan.slabs), dim3(WAVES * kWave), plan.lds_bytes, stream, a, kp);
     return hipGetLastError();
@@ -720,25 +716,25 @@ constexpr int ring_depth(int mt) { return mt == 4 ? 6 : INTSCALE_PK_RING; }
 constexpr int waves_instance(int mt, int waves) { return waves <= 4 ? 4 : (waves <= 8 || mt == 4) ? 8 : 16; }
 
 template <bool INT_SCALE, bool FUSEQ, int MT, int NR>
-hipError_t dispatch_waves(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan, int device, hipStream_t stream) {
+hipError_t dispatch_waves(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan, hipStream_t stream) {
     constexpr int DT = ring_depth(MT);
     constexpr bool FQ = MT == 1 && FUSEQ;
     switch (waves_instance(MT, plan.waves)) {
-        case 4: return launch_pk<MT, DT, 4, NR, INT_SCALE, FQ>(a, kp, plan, device, stream);
-        case 8: return launch_pk<MT, DT, 8, NR, INT_SCALE, FQ>(a, kp, plan, device, stream);
+        case 4: return launch_pk<MT, DT, 4, NR, INT_SCALE, FQ>(a, kp, plan, stream);
+        case 8: return launch_pk<MT, DT, 8, NR, INT_SCALE, FQ>(a, kp, plan, stream);
         default:
-            if constexpr (MT != 4) return launch_pk<MT, DT, 16, NR, INT_SCALE, FQ>(a, kp, plan, device, stream);
+            if constexpr (MT != 4) return launch_pk<MT, DT, 16, NR, INT_SCALE, FQ>(a, kp, plan, stream);
             return hipErrorInvalidValue;
     }
 }
 
 template <bool INT_SCALE>
-hipError_t dispatch_pk(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan, int device, hipStream_t stream) {
-    if (a.x_fp16) return dispatch_waves<INT_SCALE, true, 1, 1>(a, kp, plan, device, stream);
-    if (a.M == 1) return dispatch_waves<INT_SCALE, false, 1, 1>(a, kp, plan, device, stream);
-    if (plan.mt == 1) return dispatch_waves<INT_SCALE, false, 1, 4>(a, kp, plan, device, stream);
-    if (plan.mt == 2) return dispatch_waves<INT_SCALE, false, 2, 4>(a, kp, plan, device, stream);
-    return dispatch_waves<INT_SCALE, false, 4, 4>(a, kp, plan, device, stream);
+hipError_t dispatch_pk(const PkArgs& a, const PkKernelPlan& kp, const PkPlan& plan, hipStream_t stream) {
+    if (a.x_fp16) return dispatch_waves<INT_SCALE, true, 1, 1>(a, kp, plan, stream);
+    if (a.M == 1) return dispatch_waves<INT_SCALE, false, 1, 1>(a, kp, plan, stream);
+    if (plan.mt == 1) return dispatch_waves<INT_SCALE, false, 1, 4>(a, kp, plan, stream);
+    if (plan.mt == 2) return dispatch_waves<INT_SCALE, false, 2, 4>(a, kp, plan, stream);
+    return dispatch_waves<INT_SCALE, false, 4, 4>(a, kp, plan, stream);
 }
 
 constexpr size_t kActBudget = 128 * 1024;  // LDS bytes for the slab's activations (the fused quantiser's scratch follows)
@@ -857,9 +853,7 @@ hipError_t launch_gemm_decode_pk(const PkArgs& a, bool int_scale, hipStream_t st
     kp.slot_offset = plan.slot_offset;
     kp.wbytes = pk_weight_bytes(a.N, a.K);
     kp.sbytes = pk_scale_bytes(a.N, a.K, a.group) - kPkHeaderBytes;
-    int device = -1;
-    (void)hipGetDevice(&device);
-    return int_scale ? dispatch_pk<true>(a, kp, plan, device, stream) : dispatch_pk<false>(a, kp, plan, device, stream);
+    return int_scale ? dispatch_pk<true>(a, kp, plan, stream) : dispatch_pk<false>(a, kp, plan, stream);
 }
 
 }  // namespace intscale

@@ -549,13 +549,9 @@ hipError_t launch_tile(const GemmArgs& a, const int8_t* xp, const int32_t* s8, c
     const size_t smem = (size_t)kStages * kStageBytes;
     const int tiles_m = a.row_offsets ? tile_slots(a.M, a.num_experts) : (a.M + kBM - 1) / kBM;
     const int tiles = ((a.N + kBN - 1) / kBN) * tiles_m;
-    static bool raised = false;
-    if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_prefill_kernel<INT_SCALE, COARSE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
+    static LdsLimit limit;  // per instantiation
+    const hipError_t e = limit.raise(reinterpret_cast<const void*>(gemm_prefill_kernel<INT_SCALE, COARSE>));
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((gemm_prefill_kernel<INT_SCALE, COARSE>), dim3(tiles), dim3(kThreads), smem, stream, a, xp, s8,
                        scale_t, flag, tile_table);
     return hipGetLastError();

@@ -407,16 +407,10 @@ hipError_t launch_one(const GemmArgs& a, const SkinnyConfig& c, hipStream_t stre
     auto k1 = gemm_skinny_kernel<MT, R, D, INT_SCALE, true, W8>;
     auto k2 = gemm_skinny_kernel<MT, R, D, INT_SCALE, false, W8>;
     if (smem > 64 * 1024) {
-        static bool raised = false;  // per instantiation
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               160 * 1024);
-            if (e == hipSuccess)
-                e = hipFuncSetAttribute(reinterpret_cast<const void*>(k2), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        160 * 1024);
-            if (e != hipSuccess) return e;
-            raised = true;
-        }
+        static LdsLimit limit1, limit2;  // per instantiation
+        hipError_t e = limit1.raise(reinterpret_cast<const void*>(k1));
+        if (e == hipSuccess) e = limit2.raise(reinterpret_cast<const void*>(k2));
+        if (e != hipSuccess) return e;
     }
     if (a.group == kStepK) hipLaunchKernelGGL(k1, grid, dim3(c.nwaves * kWave), smem, stream, a);
     else hipLaunchKernelGGL(k2, grid, dim3(c.nwaves * kWave), smem, stream, a);

@@ -807,16 +807,10 @@ hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace,
     if (e != hipSuccess) return e;
     const size_t smem = 2 * (size_t)stage_bytes(kMS);
     const int tiles = sp.whole + sp.rem * sp.parts;  // workgroups
-    int device = -1;
-    (void)hipGetDevice(&device);
-    static bool raised[4][64] = {};
+    static LdsLimit limits[4];
     auto launch = [&](auto kernel, int which) -> hipError_t {
-        if (!(device >= 0 && device < 64 && raised[which][device])) {
-            hipError_t r = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-            if (r != hipSuccess) return r;
-            if (device >= 0 && device < 64) raised[which][device] = true;
-        }
+        const hipError_t r = limits[which].raise(reinterpret_cast<const void*>(kernel), (int)smem);
+        if (r != hipSuccess) return r;
         hipLaunchKernelGGL(kernel, dim3(tiles), dim3(kTThreads), smem, stream, a, xp, c0, sp);
         return hipGetLastError();
     };
@@ -853,15 +847,9 @@ template <typename Kernel>
 static hipError_t launch_grouped_instance(Kernel kernel, int which, size_t smem, const PkArgs& a, const int8_t* xp,
                                           const int32_t* c0, const TileGroups& tg, const TileSplit& sp, int grid,
                                           hipStream_t stream) {
-    int device = -1;
-    (void)hipGetDevice(&device);
-    static bool raised[2][64] = {};
-    if (!(device >= 0 && device < 64 && raised[which][device])) {
-        hipError_t r = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (r != hipSuccess) return r;
-        if (device >= 0 && device < 64) raised[which][device] = true;
-    }
+    static LdsLimit limits[2];  // (this template has one instantiation per kernel type: `which` tells its two users apart)
+    const hipError_t r = limits[which].raise(reinterpret_cast<const void*>(kernel), (int)smem);
+    if (r != hipSuccess) return r;
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(kTThreads), smem, stream, a, xp, c0, tg, sp);
     return hipGetLastError();
 }

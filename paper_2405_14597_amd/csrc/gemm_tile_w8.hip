@@ -328,13 +328,9 @@ hipError_t launch_w8_tile(const GemmArgs& a, const int32_t* scale_t, const int32
     const size_t smem = (size_t)kStages * kStageBytes;
     const int tiles_m = a.row_offsets ? tile_slots(a.M, a.num_experts) : (a.M + kBM - 1) / kBM;
     const int tiles = ((a.N + kBN - 1) / kBN) * tiles_m;
-    static bool raised = false;
-    if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_w8_kernel<INT_SCALE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
+    static LdsLimit limit;  // per instantiation
+    const hipError_t e = limit.raise(reinterpret_cast<const void*>(gemm_w8_kernel<INT_SCALE>));
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((gemm_w8_kernel<INT_SCALE>), dim3(tiles), dim3(kThreads), smem, stream, a, scale_t, flag,
                        tile_table);
     return hipGetLastError();

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "intscale.h"
 
 namespace intscale {
@@ -13,6 +15,22 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kWave = 64;
+
+// A kernel that uses more than 64 KB of dynamic LDS needs its limit raised, once per kernel and device.  One object per
+// kernel (a function-local static of the launcher's instantiation); bit d of `done` = raised on device d.  Safe from
+// several host threads: the attribute call is idempotent and the mask is only ever or-ed into.
+struct LdsLimit {
+    std::atomic<unsigned long long> done{0};
+    hipError_t raise(const void* kernel, int bytes = 160 * 1024) {
+        int device = -1;
+        if (hipGetDevice(&device) != hipSuccess) device = -1;
+        const bool tracked = device >= 0 && device < 64;
+        if (tracked && ((done.load(std::memory_order_acquire) >> device) & 1ull)) return hipSuccess;
+        const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e == hipSuccess && tracked) done.fetch_or(1ull << device, std::memory_order_release);
+        return e;
+    }
+};
 
 // Everything a GEMM launch needs. Plain data so that it can be passed by value to a kernel.
 struct GemmArgs {
