@@ -11,9 +11,10 @@
  *   - Every tensor pointer is a DEVICE pointer owned by the caller, 16-byte aligned, dense row-major.
  *     The library allocates nothing and never synchronises.  No result depends on an earlier call; the process state
  *     it does keep is housekeeping: the compute-unit count of the device (read once), which kernels have had their
- *     LDS limit raised on which device, the resolved address of the fixed scratch of the *_noalloc call, and the
- *     environment switches INTSCALE_FORCE_KERNEL / INTSCALE_PK_SLABS / INTSCALE_PK_WAVES / INTSCALE_SKINNY_* (tests
- *     and experiments; unset in production), read at each call.
+ *     LDS limit raised on which device, the resolved address of the fixed scratch of the *_noalloc call, the routing
+ *     override of is_set_kernel_route, and the environment switches INTSCALE_FORCE_KERNEL / INTSCALE_PK_SLABS /
+ *     INTSCALE_PK_WAVES / INTSCALE_TILE_PARTS / INTSCALE_SKINNY_* (tests and experiments; unset in production), each
+ *     read once per process, at its first use: no launch reads the environment.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
  *   - Return value: IS_OK, or a negative IS_ERR_* code.  Arguments are validated before any HIP call; on an
  *     argument error nothing is enqueued and the outputs are untouched.
@@ -375,6 +376,16 @@ size_t is_gemm_safe_workspace_bytes(int M, int N, int K, int group);
 int is_probe_stream_read(const void* src, size_t bytes, int* sink, void* stream);
 int is_probe_mfma_i8(int iters, int* sink, double* ops_out, void* stream);
 int is_probe_mfma_i8_random(int iters, int* sink, double* ops_out, void* stream);
+
+/*
+ * For tests and experiments (not part of the method): which kernel the calls on the canonical layouts take.
+ *   0  the library chooses by shape (the default);
+ *   1  every call goes to the general kernel where it covers the shape;
+ *   2  the W8A8 GEMMs go to the tiled kernel whatever M is.
+ * The setting is process-wide and starts from INTSCALE_FORCE_KERNEL=general|tiled (read once).  Returns the setting
+ * that was in force before, or IS_ERR_INVALID_ARG.  Results do not depend on it (every route computes the same bits).
+ */
+int is_set_kernel_route(int route);
 
 /* Human-readable name of a status code (static storage). */
 const char* is_status_string(int status);

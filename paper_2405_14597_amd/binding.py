@@ -65,6 +65,7 @@ EXPORTED_SYMBOLS = (
     "is_probe_stream_read",
     "is_probe_mfma_i8",
     "is_probe_mfma_i8_random",
+    "is_set_kernel_route",
     "is_status_string",
     "is_last_hip_error",
 )
@@ -183,6 +184,8 @@ def load_library() -> ctypes.CDLL:
     lib.is_probe_mfma_i8.restype = ci
     lib.is_probe_mfma_i8_random.argtypes = [ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.is_probe_mfma_i8_random.restype = ci
+    lib.is_set_kernel_route.argtypes = [ci]
+    lib.is_set_kernel_route.restype = ci
     lib.is_status_string.argtypes = [ci]
     lib.is_status_string.restype = ctypes.c_char_p
     lib.is_last_hip_error.argtypes = []
@@ -195,6 +198,17 @@ def load_library() -> ctypes.CDLL:
     lib.is_describe_grouped_prepacked.restype = ci
     _lib = lib
     return lib
+
+
+KERNEL_ROUTES = {"auto": 0, "general": 1, "tiled": 2}
+
+
+def is_set_kernel_route(route) -> str:
+    """Routing override for tests and experiments ("auto", "general", "tiled"); returns the one in force before."""
+    code = KERNEL_ROUTES[route] if isinstance(route, str) else int(route)
+    before = load_library().is_set_kernel_route(code)
+    _check("is_set_kernel_route", before if before < 0 else 0)
+    return {v: k for k, v in KERNEL_ROUTES.items()}[before]
 
 
 def status_string(status: int) -> str:

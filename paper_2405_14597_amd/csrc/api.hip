@@ -44,17 +44,22 @@ int check_gemm_shape(int M, int N, int K, int group) {
 
 // Regime selection by the number of token rows.  More than 64 rows (per expert on average, for the grouped form)
 // go to the MFMA-bound tiled kernel, which needs workspace for its zero-point corrections.
-bool general_forced() {
-    // INTSCALE_FORCE_KERNEL=general routes everything to the general kernel (used by the tests to cover it).
-    const char* force = getenv("INTSCALE_FORCE_KERNEL");
-    return force && strcmp(force, "general") == 0;
+// Routing override (tests and experiments): 0 automatic, 1 everything the general kernel covers goes to it, 2 the
+// W8A8 GEMMs go to the tiled kernel whatever M is.  Starts from INTSCALE_FORCE_KERNEL=general|tiled, read once;
+// is_set_kernel_route changes it afterwards.  Nothing on the launch path reads the environment.
+std::atomic<int> g_route{-1};
+int kernel_route() {
+    int r = g_route.load(std::memory_order_relaxed);
+    if (r < 0) {
+        const char* force = getenv("INTSCALE_FORCE_KERNEL");
+        r = force == nullptr ? 0 : strcmp(force, "general") == 0 ? 1 : strcmp(force, "tiled") == 0 ? 2 : 0;
+        int unset = -1;
+        if (!g_route.compare_exchange_strong(unset, r)) r = unset;  // (a setter came first)
+    }
+    return r;
 }
-
-bool general_forced_off() {
-    // INTSCALE_FORCE_KERNEL=tiled sends the W8A8 GEMMs to the tiled kernel whatever M is (used by the tests to cover it).
-    const char* force = getenv("INTSCALE_FORCE_KERNEL");
-    return force && strcmp(force, "tiled") == 0;
-}
+bool general_forced() { return kernel_route() == 1; }
+bool general_forced_off() { return kernel_route() == 2; }
 
 bool wants_prefill(int M, int num_experts, int group) {
     return !general_forced() && !gemm_small_group_covers(group) && M > 64 * num_experts;
@@ -97,6 +102,13 @@ int static_scratch(void** ptr_out) {
 }  // namespace
 
 extern "C" {
+
+int is_set_kernel_route(int route) {
+    if (route < 0 || route > 2) return IS_ERR_INVALID_ARG;
+    const int before = kernel_route();
+    g_route.store(route, std::memory_order_relaxed);
+    return before;
+}
 
 const char* is_status_string(int status) {
     switch (status) {

@@ -763,8 +763,7 @@ bool pk_decode_plan(int M, int N, int K, int group, bool fp16_in, PkPlan* plan) 
     // More slabs than the activations need can even out the shares (tiles per workgroup x steps per slab is what a
     // workgroup carries) at the price of more partial tiles: take the best of a few candidates.
     int best = s_min;
-    int forced = 0;  // INTSCALE_PK_SLABS=n (experiments): n slabs, if the activations allow
-    if (const char* e = getenv("INTSCALE_PK_SLABS")) forced = atoi(e);
+    static const int forced = env_int("INTSCALE_PK_SLABS", 0);  // =n (experiments; read once): n slabs, if the activations allow
     double best_cost = 0.0;
     for (int s = s_min; s <= s_min + 4 && s <= steps && s <= cus; ++s) {
         const int wgs = cus / s;
@@ -798,8 +797,9 @@ bool pk_decode_plan(int M, int N, int K, int group, bool fp16_in, PkPlan* plan) 
     while (waves < (pl.mt == 4 ? 8 : 16) && (long long)waves * 2 * dt <= blocks) waves *= 2;
     if (fp16_in)
         while ((K >> 3) > kFuseChunks * waves * kWave) waves *= 2;  // the token's chunks over the threads
-    if (const char* e = getenv("INTSCALE_PK_WAVES")) {  // experiments
-        const int w = atoi(e);
+    static const int env_waves = env_int("INTSCALE_PK_WAVES", 0);  // experiments; read once
+    if (env_waves) {
+        const int w = env_waves;
         if ((w == 4 || w == 8 || (w == 16 && pl.mt != 4)) && (!fp16_in || (K >> 3) <= kFuseChunks * w * kWave)) waves = w;
     }
     pl.waves = waves;

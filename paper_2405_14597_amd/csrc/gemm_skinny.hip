@@ -358,11 +358,6 @@ struct SkinnyConfig {
     int mt, r, d, nwaves;
 };
 
-int env_int(const char* name, int fallback) {
-    const char* v = getenv(name);
-    return v ? atoi(v) : fallback;
-}
-
 // Tile shape and wave count for a problem.  Aim: a few thousand waves in flight over 256 CUs, each with D*R KB of
 // weight loads outstanding, and at least one workgroup per CU.
 SkinnyConfig choose_config(const GemmArgs& a) {
@@ -379,11 +374,13 @@ SkinnyConfig choose_config(const GemmArgs& a) {
     } else if ((long long)((a.N + 31) / 32) * m_chunks >= 512) {
         c.r = 2;
     }
-    c.r = env_int("INTSCALE_SKINNY_R", c.r);
+    static const int env_r = env_int("INTSCALE_SKINNY_R", 0);  // experiments; read once
+    if (env_r) c.r = env_r;
     if (c.r != 1 && c.r != 2 && c.r != 4) c.r = 1;
     // 48 or 64 token rows: the staged activations leave registers for two steps in flight, not four
     c.d = (c.mt >= 3 || c.mt * c.r >= 8) ? 2 : 4;
-    c.d = env_int("INTSCALE_SKINNY_D", c.d);
+    static const int env_d = env_int("INTSCALE_SKINNY_D", 0);
+    if (env_d) c.d = env_d;
     if (c.d != 2 && c.d != 4) c.d = 2;
     if (a.w_bits == 8) c.d = 2;
     const long long tiles = (long long)((a.N + 16 * c.r - 1) / (16 * c.r)) * m_chunks;
@@ -391,7 +388,8 @@ SkinnyConfig choose_config(const GemmArgs& a) {
     // LDS: nwaves * R * MT KB for the reduction, at most 64 KB.
     const int cap = max_waves(c.mt, c.r, c.d, a.w_bits == 8);
     while (nw * 2 <= cap && nw * 2 <= NG && tiles * nw < 4096) nw *= 2;
-    nw = env_int("INTSCALE_SKINNY_WAVES", nw);
+    static const int env_w = env_int("INTSCALE_SKINNY_WAVES", 0);
+    if (env_w) nw = env_w;
     if (nw < 1) nw = 1;
     while (nw > 1 && (nw > NG || nw > cap)) nw /= 2;
     c.nwaves = nw;

@@ -747,7 +747,8 @@ void plan_tail(int M, int N, int K, size_t avail, int* whole, int* rem, int* par
         // up to one workgroup per compute unit: a workgroup that has its compute unit to itself runs at about 1.7 times
         // the rate of one that shares it, so filling both places of a unit with half-length parts gains nothing
         p = min(min((slots / 2) / left, 8), steps / kMinPartSteps);
-        if (const char* e = getenv("INTSCALE_TILE_PARTS")) p = min(p, max(1, atoi(e)));  // experiments: at most this many
+        static const int env_parts = env_int("INTSCALE_TILE_PARTS", 0);  // experiments (read once): at most this many
+        if (env_parts) p = min(p, max(1, env_parts));
         p = (int)min((size_t)p, min(avail, kPartialCap) / ((size_t)left * kPartWords * 4));
     }
     if (p < 2) {

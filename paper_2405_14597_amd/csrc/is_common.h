@@ -4,6 +4,7 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include <atomic>
 
@@ -15,6 +16,13 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kWave = 64;
+
+// An environment switch for experiments, as an integer (`unset` when absent).  Callers keep the value in a
+// function-local static, so the environment is read once per process and not on every launch.
+inline int env_int(const char* name, int unset) {
+    const char* v = getenv(name);
+    return v ? atoi(v) : unset;
+}
 
 // A kernel that uses more than 64 KB of dynamic LDS needs its limit raised, once per kernel and device.  One object per
 // kernel (a function-local static of the launcher's instantiation); bit d of `done` = raised on device d.  Safe from

@@ -270,6 +270,20 @@ def test_describe_prepacked_names_the_kernels():
     assert lib.is_describe_grouped_prepacked(2, 16, 256, 128, 64, 1, buf, 8) == P.IS_ERR_UNSUPPORTED
 
 
+def test_kernel_route_override_is_a_host_setting():
+    """The routing override of the tests is a call, not an environment read on the launch path: it returns the setting
+    in force before, rejects unknown routes and leaves the setting alone when it does."""
+    lib = P.load_library()
+    first = P.is_set_kernel_route("general")
+    try:
+        assert P.is_set_kernel_route("tiled") == "general"
+        assert lib.is_set_kernel_route(3) == P.IS_ERR_INVALID_ARG and lib.is_set_kernel_route(-1) == P.IS_ERR_INVALID_ARG
+        assert P.is_set_kernel_route("auto") == "tiled"
+    finally:
+        P.is_set_kernel_route(first)
+    assert P.is_set_kernel_route(first) == first
+
+
 def test_library_carries_the_digest_of_its_sources():
     from paper_2405_14597_amd import build
     assert P.load_library().is_source_hash().decode() == build.source_hash() == build.built_hash()

@@ -25,13 +25,19 @@ def P():
 
 
 @pytest.fixture(params=["auto", "general"])
-def kernel(request, monkeypatch):
+def kernel(request, P):
     """Runs a test twice: with the library's own kernel choice, and with everything forced onto the general kernel."""
-    if request.param == "general":
-        monkeypatch.setenv("INTSCALE_FORCE_KERNEL", "general")
-    else:
-        monkeypatch.delenv("INTSCALE_FORCE_KERNEL", raising=False)
-    return request.param
+    before = P.is_set_kernel_route(request.param)
+    yield request.param
+    P.is_set_kernel_route(before)
+
+
+@pytest.fixture
+def route_setting(P):
+    """A function that sets the library's routing override for the rest of the test."""
+    before = P.is_set_kernel_route("auto")
+    yield P.is_set_kernel_route
+    P.is_set_kernel_route(before)
 
 
 def dev(a):
@@ -411,13 +417,10 @@ def test_w8_weight_quantizer_bit_exact(P, N, K, group, alpha, mode):
                                          (1, 4096, 14336, 128), (24, 1040, 2048, 256), (33, 100, 1024, 1024),
                                          (48, 2064, 3584, 128)])
 @pytest.mark.parametrize("route", ["auto", "tiled"])
-def test_w8a8_gemm(P, monkeypatch, route, M, N, K, group):
+def test_w8a8_gemm(P, route_setting, route, M, N, K, group):
     """Up to 64 token rows the library takes the general (bandwidth-bound) kernel, above that the tiled one; "tiled"
     sends every shape to the tiled kernel."""
-    if route == "tiled":
-        monkeypatch.setenv("INTSCALE_FORCE_KERNEL", "tiled")
-    else:
-        monkeypatch.delenv("INTSCALE_FORCE_KERNEL", raising=False)
+    route_setting(route)
     rng = np.random.default_rng(4000 + M + N + K)
     xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
     q = rng.integers(-128, 128, size=(N, K)).astype(np.int8)
