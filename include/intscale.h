@@ -178,6 +178,8 @@ int is_prepack_w4(const void* qweight, const int32_t* scale_i32, const float* sc
  * is_gemm_w4a8_floatscale (accumulators bit for bit; the float-scale sums in a different but fixed order).
  *   qweight_packed, scales_packed   from is_prepack_w4 (integer scales for the first, float scales for the second)
  *   workspace   at least is_gemm_prepacked_workspace_bytes(M,N,K,group) bytes.
+ *               (Which kernel: the tiled one for M > 64, and for 33 <= M <= 64 when N * K >= 2^27; else the
+ *               weight-streaming one.  Ask is_gemm_prepacked_workspace_bytes / is_describe_prepacked, do not guess.)
  *               M <= 64 (the weight-streaming kernel): 0 for most shapes; when it is not 0 the K dimension is split
  *               across workgroups and the first 64 KB of the workspace are arrival counters: they must be ZERO when a
  *               call starts and every call leaves them zero, so zero the workspace once after allocating it.
@@ -381,7 +383,8 @@ int is_probe_mfma_i8_random(int iters, int* sink, double* ops_out, void* stream)
  * For tests and experiments (not part of the method): which kernel the calls on the canonical layouts take.
  *   0  the library chooses by shape (the default);
  *   1  every call goes to the general kernel where it covers the shape;
- *   2  the W8A8 GEMMs go to the tiled kernel whatever M is.
+ *   2  the W8A8 GEMMs go to the tiled kernel whatever M is;
+ *   3  the prepacked calls of 33..64 token rows go to the tiled kernel whatever the size of the weights.
  * The setting is process-wide and starts from INTSCALE_FORCE_KERNEL=general|tiled (read once).  Returns the setting
  * that was in force before, or IS_ERR_INVALID_ARG.  Results do not depend on it (every route computes the same bits).
  */

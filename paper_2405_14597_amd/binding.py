@@ -200,11 +200,11 @@ def load_library() -> ctypes.CDLL:
     return lib
 
 
-KERNEL_ROUTES = {"auto": 0, "general": 1, "tiled": 2}
+KERNEL_ROUTES = {"auto": 0, "general": 1, "tiled": 2, "tiled64": 3}
 
 
 def is_set_kernel_route(route) -> str:
-    """Routing override for tests and experiments ("auto", "general", "tiled"); returns the one in force before."""
+    """Routing override for tests and experiments ("auto", "general", "tiled", "tiled64"); returns the one in force before."""
     code = KERNEL_ROUTES[route] if isinstance(route, str) else int(route)
     before = load_library().is_set_kernel_route(code)
     _check("is_set_kernel_route", before if before < 0 else 0)

@@ -45,7 +45,7 @@ int check_gemm_shape(int M, int N, int K, int group) {
 // Regime selection by the number of token rows.  More than 64 rows (per expert on average, for the grouped form)
 // go to the MFMA-bound tiled kernel, which needs workspace for its zero-point corrections.
 // Routing override (tests and experiments): 0 automatic, 1 everything the general kernel covers goes to it, 2 the
-// W8A8 GEMMs go to the tiled kernel whatever M is.  Starts from INTSCALE_FORCE_KERNEL=general|tiled, read once;
+// W8A8 GEMMs go to the tiled kernel whatever M is, 3 the prepacked calls of 33..64 rows go to the tiled kernel.  Starts from INTSCALE_FORCE_KERNEL=general|tiled, read once;
 // is_set_kernel_route changes it afterwards.  Nothing on the launch path reads the environment.
 std::atomic<int> g_route{-1};
 int kernel_route() {
@@ -60,6 +60,15 @@ int kernel_route() {
 }
 bool general_forced() { return kernel_route() == 1; }
 bool general_forced_off() { return kernel_route() == 2; }
+
+// Which of the two kernels on the prepacked layout a call takes.  More than 64 token rows: the tiled one.  33..64 rows:
+// the weight-streaming kernel cannot keep a long K slab of 64 rows in LDS, so it splits K many times and moves partial
+// tiles and activation slabs of about the weights' own size; from 2^27 weights on (measured: LLaMA-2-70B gate 50 -> 47 us,
+// down 62 -> 53 us at 64 rows; every smaller shape of the LLaMA-2-7B / LLaMA-3-8B / LLaMA-2-70B layers is slower there)
+// the tiled kernel's 64-row instance is ahead.  Same bits either way; route 3 sends every such call there (tests).
+bool pk_takes_tile(int M, int N, int K) {
+    return M > 64 || (M > 32 && (kernel_route() == 3 || (long long)N * K >= (1LL << 27)));
+}
 
 bool wants_prefill(int M, int num_experts, int group) {
     return !general_forced() && !gemm_small_group_covers(group) && M > 64 * num_experts;
@@ -104,7 +113,7 @@ int static_scratch(void** ptr_out) {
 extern "C" {
 
 int is_set_kernel_route(int route) {
-    if (route < 0 || route > 2) return IS_ERR_INVALID_ARG;
+    if (route < 0 || route > 3) return IS_ERR_INVALID_ARG;
     const int before = kernel_route();
     g_route.store(route, std::memory_order_relaxed);
     return before;
@@ -412,7 +421,7 @@ int is_prepack_w4(const void* qweight, const int32_t* scale_i32, const float* sc
 size_t is_gemm_prepacked_workspace_bytes(int M, int N, int K, int group) {
     if (M < 0 || check_pk_shape(N, K, group) != IS_OK) return 0;
     if (M == 0) return 0;
-    if (M <= 64) return pk_decode_workspace_bytes(M, N, K, group);
+    if (!pk_takes_tile(M, N, K)) return pk_decode_workspace_bytes(M, N, K, group);
     return gemm_tile_pk_workspace_bytes(M, N, K);  // prepared activations, corrections, partial tiles of the last round
 }
 
@@ -427,10 +436,11 @@ static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_s
     if (M > (1 << 20)) return IS_ERR_UNSUPPORTED;
     if (!ok_opt(workspace)) return IS_ERR_INVALID_ARG;
     PkPlan plan;
-    if (M > 0 && M <= 64 && !pk_decode_plan(M, N, K, group, x_fp16 != nullptr, &plan)) return IS_ERR_UNSUPPORTED;
-    if (M > 64 && (long long)((M + 15) / 16) * 16 * K >= (1LL << 31)) return IS_ERR_UNSUPPORTED;  // 32-bit offsets
+    const bool tiled = pk_takes_tile(M, N, K);
+    if (M > 0 && !tiled && !pk_decode_plan(M, N, K, group, x_fp16 != nullptr, &plan)) return IS_ERR_UNSUPPORTED;
+    if (tiled && (long long)((M + 15) / 16) * 16 * K >= (1LL << 31)) return IS_ERR_UNSUPPORTED;  // 32-bit offsets
     // (on the fixed scratch the tiled route takes what it needs at least: the K split of its last round uses what is left)
-    const size_t need = (fixed_scratch && M > 64) ? gemm_tile_pk_min_workspace_bytes(M, K)
+    const size_t need = (fixed_scratch && tiled) ? gemm_tile_pk_min_workspace_bytes(M, K)
                                                   : is_gemm_prepacked_workspace_bytes(M, N, K, group);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return IS_ERR_WORKSPACE;
     if (!ok_ptr(wpack) || !ok_ptr(spack) || !ok_opt(chan_scale)) return IS_ERR_INVALID_ARG;
@@ -449,14 +459,14 @@ static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_s
     a.out = static_cast<__half*>(out_fp16);
     a.acc_out = acc_out;
     a.counters = static_cast<int32_t*>(workspace);
-    a.partials = (need > 0 && M <= 64) ? reinterpret_cast<int32_t*>(static_cast<unsigned char*>(workspace) + kPkCounterBytes) : nullptr;
+    a.partials = (need > 0 && !tiled) ? reinterpret_cast<int32_t*>(static_cast<unsigned char*>(workspace) + kPkCounterBytes) : nullptr;
     a.M = M;
     a.N = N;
     a.K = K;
     a.group = group;
     a.alpha_log2 = int_scale ? alpha_log2 : 0;
-    a.pair = (pair && M > 64) ? 1 : 0;  // (the fused epilogue is the tiled kernel's)
-    if (M > 64)
+    a.pair = (pair && tiled) ? 1 : 0;  // (the fused epilogue is the tiled kernel's)
+    if (tiled)
         return hip_status(launch_gemm_tile_pk(a, int_scale, workspace, workspace_bytes, static_cast<hipStream_t>(stream)));
     if (fixed_scratch && a.partials != nullptr) {  // a workspace whose last user may not have left the counters zero
         const int n16 = (N + 15) / 16;
@@ -507,7 +517,7 @@ size_t is_gemm_gate_up_silu_prepacked_workspace_bytes(int M, int inter, int K, i
     if (M <= 0 || inter <= 0 || inter > (1 << 29) || inter % 16 != 0 || check_pk_shape(2 * inter, K, group) != IS_OK) return 0;
     const size_t gemm = is_gemm_prepacked_workspace_bytes(M, 2 * inter, K, group);
     // up to 64 token rows: the weight-streaming kernel writes the [M, 2 inter] fp16 tensor here, a second kernel reads it
-    return M <= 64 ? pad_256(gemm) + pad_256((size_t)M * 2 * inter * 2) : gemm;
+    return !pk_takes_tile(M, 2 * inter, K) ? pad_256(gemm) + pad_256((size_t)M * 2 * inter * 2) : gemm;
 }
 
 static int gate_up_silu_common(const int8_t* xq, const float* a_scale, const void* wpack, const void* spack,
@@ -517,7 +527,7 @@ static int gate_up_silu_common(const int8_t* xq, const float* a_scale, const voi
     if (M < 0 || inter <= 0 || inter > (1 << 29)) return IS_ERR_INVALID_ARG;
     if (inter % 16 != 0) return IS_ERR_UNSUPPORTED;
     const int N = 2 * inter;
-    if (M == 0 || M > 64)
+    if (M == 0 || pk_takes_tile(M, N, K))
         return gemm_pk_common(xq, nullptr, a_scale, nullptr, wpack, spack, chan_scale_packed, M, N, K, group, alpha_log2,
                               out_fp16, acc_out, workspace, workspace_bytes, stream, int_scale, false, true);
     const int shape = check_pk_shape(N, K, group);
@@ -555,7 +565,7 @@ int is_gemm_w4a8_intscale_prepacked_noalloc(const int8_t* xq, const float* a_sca
     if (M < 0) return IS_ERR_INVALID_ARG;
     const int shape = check_pk_shape(N, K, group);
     if (shape != IS_OK) return shape;
-    const size_t need = M > 64 ? gemm_tile_pk_min_workspace_bytes(M, K) : is_gemm_prepacked_workspace_bytes(M, N, K, group);
+    const size_t need = pk_takes_tile(M, N, K) ? gemm_tile_pk_min_workspace_bytes(M, K) : is_gemm_prepacked_workspace_bytes(M, N, K, group);
     if (need > (size_t)IS_NOALLOC_SCRATCH_BYTES) return IS_ERR_WORKSPACE;  // beyond the fixed scratch: use the other call
     void* ws = nullptr;
     if (need > 0) {
@@ -664,14 +674,15 @@ static int linear_pk_common(const void* x_fp16, const void* wpack, const void* s
     if (M == 1 && pk_decode_plan(1, N, K, group, true, &plan))  // one token: quantised inside the GEMM kernel
         return gemm_pk_common(nullptr, x_fp16, nullptr, sa, wpack, spack, chan_scale, M, N, K, group, alpha_log2,
                               out_fp16, acc_out, rest, rest_bytes, stream, int_scale);
-    if (M > 64 && gemm_tile_pk_takes_fp16(K))  // many tokens: the tiled kernel's preparation quantises on the way
+    if (M > 64 && gemm_tile_pk_takes_fp16(K))  // many tokens: the tiled kernel's preparation quantises on the way (a
+                                               // workgroup per 8 rows: too few of them below that)
         return gemm_pk_common(nullptr, x_fp16, sa, sa, wpack, spack, chan_scale, M, N, K, group, alpha_log2, out_fp16,
                               acc_out, rest, rest_bytes, stream, int_scale);
     // the arguments of the GEMM are checked before the quantiser is enqueued
     if (!ok_ptr(wpack) || !ok_ptr(spack) || !ok_opt(chan_scale) || !ok_ptr(out_fp16) || !ok_opt(acc_out))
         return IS_ERR_INVALID_ARG;
     if (int_scale && (alpha_log2 < 0 || alpha_log2 > 30)) return IS_ERR_INVALID_ARG;
-    if (M <= 64 && !pk_decode_plan(M, N, K, group, false, &plan)) return IS_ERR_UNSUPPORTED;
+    if (!pk_takes_tile(M, N, K) && !pk_decode_plan(M, N, K, group, false, &plan)) return IS_ERR_UNSUPPORTED;
     const int st = hip_status(launch_quantize_act(static_cast<const __half*>(x_fp16), M, K, xq, sa,
                                                   static_cast<hipStream_t>(stream)));
     if (st != IS_OK) return st;
@@ -702,8 +713,8 @@ int is_describe_prepacked(int M, int N, int K, int group, int int_scale, int fp1
     if (M < 1) return IS_ERR_INVALID_ARG;
     const int shape = check_pk_shape(N, K, group);
     if (shape != IS_OK) return shape;
-    if (M > 64) {
-        gemm_tile_pk_kernel_names(K, int_scale != 0, fp16_in != 0 && gemm_tile_pk_takes_fp16(K), names, names_len);
+    if (pk_takes_tile(M, N, K)) {
+        gemm_tile_pk_kernel_names(K, int_scale != 0, fp16_in != 0 && M > 64 && gemm_tile_pk_takes_fp16(K), names, names_len);
         return IS_OK;
     }
     PkPlan plan;

@@ -667,6 +667,26 @@ __device__ __forceinline__ void tile_pk(const PkArgs& a, const int8_t* __restric
     }
 }
 
+// The dense form's tile code: 128 token rows per tile, or, for calls of at most 64 rows (33..64 rows on large weight
+// matrices take this kernel, see pk_takes_tile), the 64-row instance, which runs half the MFMAs and scale steps.
+template <bool INT_SCALE, bool SILU, int MS>
+__device__ __forceinline__ void dense_tile_rows(const PkArgs& a, const int8_t* __restrict__ xp, const int32_t* __restrict__ c0,
+                                                const TileSplit& sp, const TileGroups& none, unsigned char* smem) {
+    if constexpr (INT_SCALE) {
+        const int flags = *reinterpret_cast<const int32_t*>(a.spack);
+        if (flags & kPkFlagWide) tile_pk<true, true, false, MS, SILU>(a, xp, c0, sp, none, nullptr, 0, smem);
+        else tile_pk<true, false, false, MS, SILU>(a, xp, c0, sp, none, nullptr, 0, smem);
+    } else {
+        tile_pk<false, false, false, MS, SILU>(a, xp, c0, sp, none, nullptr, 0, smem);
+    }
+}
+template <bool INT_SCALE, bool SILU>
+__device__ __forceinline__ void dense_tile(const PkArgs& a, const int8_t* __restrict__ xp, const int32_t* __restrict__ c0,
+                                           const TileSplit& sp, const TileGroups& none, unsigned char* smem) {
+    if (a.M <= 64) dense_tile_rows<INT_SCALE, SILU, 4>(a, xp, c0, sp, none, smem);
+    else dense_tile_rows<INT_SCALE, SILU, kMS>(a, xp, c0, sp, none, smem);
+}
+
 // (two waves per SIMD, from two workgroups: this also keeps the MFMA results in ordinary vector registers, where the
 // scale step reads them; with a whole SIMD to itself the compiler would put them into accumulation registers and copy)
 template <bool INT_SCALE>
@@ -674,13 +694,7 @@ __global__ __launch_bounds__(kTThreads) __attribute__((amdgpu_waves_per_eu(2, 2)
                                                                  const int32_t* __restrict__ c0, TileSplit sp) {
     extern __shared__ __align__(16) unsigned char smem_tpk[];
     const TileGroups none{};
-    if constexpr (INT_SCALE) {
-        const int flags = *reinterpret_cast<const int32_t*>(a.spack);
-        if (flags & kPkFlagWide) tile_pk<true, true, false, kMS>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
-        else tile_pk<true, false, false, kMS>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
-    } else {
-        tile_pk<false, false, false, kMS>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
-    }
+    dense_tile<INT_SCALE, false>(a, xp, c0, sp, none, smem_tpk);
 }
 
 // The same on gate / up rows that alternate by 16-row tile, with SiLU(gate) * up as the epilogue (Sec. 4.2 names kernel
@@ -690,13 +704,7 @@ __global__ __launch_bounds__(kTThreads) __attribute__((amdgpu_waves_per_eu(2, 2)
     PkArgs a, const int8_t* __restrict__ xp, const int32_t* __restrict__ c0, TileSplit sp) {
     extern __shared__ __align__(16) unsigned char smem_tpk[];
     const TileGroups none{};
-    if constexpr (INT_SCALE) {
-        const int flags = *reinterpret_cast<const int32_t*>(a.spack);
-        if (flags & kPkFlagWide) tile_pk<true, true, false, kMS, true>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
-        else tile_pk<true, false, false, kMS, true>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
-    } else {
-        tile_pk<false, false, false, kMS, true>(a, xp, c0, sp, none, nullptr, 0, smem_tpk);
-    }
+    dense_tile<INT_SCALE, true>(a, xp, c0, sp, none, smem_tpk);
 }
 
 // Mixture-of-experts form: workgroup b takes table entry b / (tile columns) and tile column b % (tile columns); the

@@ -277,7 +277,7 @@ def test_kernel_route_override_is_a_host_setting():
     first = P.is_set_kernel_route("general")
     try:
         assert P.is_set_kernel_route("tiled") == "general"
-        assert lib.is_set_kernel_route(3) == P.IS_ERR_INVALID_ARG and lib.is_set_kernel_route(-1) == P.IS_ERR_INVALID_ARG
+        assert lib.is_set_kernel_route(4) == P.IS_ERR_INVALID_ARG and lib.is_set_kernel_route(-1) == P.IS_ERR_INVALID_ARG
         assert P.is_set_kernel_route("auto") == "tiled"
     finally:
         P.is_set_kernel_route(first)

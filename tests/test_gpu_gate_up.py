@@ -97,6 +97,16 @@ def test_gate_up_silu_intscale(P, M, inter, K, wide):
     assert np.array_equal(host(h).view(np.uint16), O.silu_mul_fp16(canonical).view(np.uint16))
 
 
+@pytest.mark.parametrize("M,inter,K,wide", [(40, 272, 1024, False), (64, 48, 256, True), (33, 4096, 512, False)])
+def test_gate_up_silu_33_to_64_rows_on_the_tiled_kernel(P, M, inter, K, wide):
+    """The route large projections take at 33..64 rows: the tiled kernel's 64-row instance with the fused epilogue."""
+    before = P.is_set_kernel_route("tiled64")
+    try:
+        test_gate_up_silu_intscale(P, M, inter, K, wide)
+    finally:
+        P.is_set_kernel_route(before)
+
+
 @pytest.mark.parametrize("M,inter,K", [(8, 48, 256), (200, 272, 1024)])
 def test_gate_up_silu_floatscale(P, M, inter, K):
     rng = np.random.default_rng(9100 + M + inter)

@@ -234,6 +234,62 @@ def test_prepacked_tiled_gemm(P, M, N, K):
     check_fs(host(out_fs), fs, f"M{M} N{N} K{K}")
 
 
+@pytest.fixture
+def tiled64(P):
+    """Sends the prepacked calls of 33..64 rows to the tiled kernel whatever the size of the weights."""
+    before = P.is_set_kernel_route("tiled64")
+    yield
+    P.is_set_kernel_route(before)
+
+
+# 33..64 token rows on the tiled kernel's 64-row instance (the route large weight matrices take): ragged rows and
+# columns, one and many K steps, a K range cut into parts (few tile columns), N not a multiple of 8
+@pytest.mark.parametrize("M,N,K", [(33, 300, 1024), (64, 520, 2048), (48, 256, 128), (40, 1040, 4096), (64, 100, 11008),
+                                   (57, 4104, 512)])
+def test_prepacked_33_to_64_rows_on_the_tiled_kernel(P, tiled64, M, N, K):
+    assert P.is_describe_prepacked(M, N, K, G)[-1] == "gemm_tile_pk_kernel<true>"
+    rng = np.random.default_rng(3900 + M + N + K)
+    xq, qw, IS, s, sa, c = rand_quantised(rng, M, N, K)
+    xq[0], xq[M - 1] = -128, 127
+    ref = O.gemm_w4a8_intscale(xq, sa, qw, IS, c, G, 10)
+    pk = P.is_prepack_w4(dev(qw), dev(IS), G)
+    out, acc = P.is_gemm_w4a8_intscale_prepacked(dev(xq), dev(sa), pk, dev(c), 10, want_acc=True)
+    assert np.array_equal(host(acc), ref.acc), "int32 accumulators differ"
+    check_out(host(out), ref.out, f"M{M} N{N} K{K}")
+    out1, _ = P.is_gemm_w4a8_intscale_prepacked(dev(xq), dev(sa), pk, dev(c), 10)   # the staged epilogue
+    check_out(host(out1), ref.out, f"M{M} N{N} K{K} (no accumulator export)")
+    out_na = torch.empty((M, N), dtype=torch.float16, device="cuda:0")
+    acc_na = torch.empty((M, N), dtype=torch.int32, device="cuda:0")
+    P.is_gemm_w4a8_intscale_prepacked_noalloc(dev(xq), dev(sa), pk, dev(c), 10, out_na, acc_na)   # the fixed scratch
+    assert np.array_equal(host(acc_na), ref.acc) and np.array_equal(host(out_na), host(out))
+    fs = O.gemm_w4a8_floatscale(xq, sa, qw, s, G)
+    out_fs = P.is_gemm_w4a8_floatscale_prepacked(dev(xq), dev(sa), P.is_prepack_w4(dev(qw), dev(s), G))
+    check_fs(host(out_fs), fs, f"M{M} N{N} K{K}")
+    # the linear call on fp16 activations: stand-alone quantiser, then the same kernels
+    x = S.activations_outlier(M, K, 31 + K % 7)
+    xq_ref, sa_ref = O.quantize_act_int8_token(x)
+    ref_l = O.gemm_w4a8_intscale(xq_ref, sa_ref, qw, IS, c, G, 10)
+    out_l, acc_l = P.is_linear_w4a8_intscale_prepacked(dev(x), pk, dev(c), 10, want_acc=True)
+    assert np.array_equal(host(acc_l), ref_l.acc), "linear call: int32 accumulators differ"
+    check_out(host(out_l), ref_l.out, f"linear M{M} N{N} K{K}")
+
+
+@pytest.mark.parametrize("M,N,K", [(64, 8192, 28672), (40, 28672, 8192)])
+def test_prepacked_33_to_64_rows_on_large_weights_take_the_tiled_kernel(P, M, N, K):
+    """From 2^27 weights on the library itself picks the tiled kernel for 33..64 rows (the LLaMA-2-70B gate and down
+    projections), and the weight-streaming kernel below (its qkv projection)."""
+    assert P.is_describe_prepacked(M, N, K, G)[-1] == "gemm_tile_pk_kernel<true>"
+    assert P.is_describe_prepacked(M, 10240, 8192, G)[-1].startswith("gemm_decode_pk_kernel<4, ")
+    assert P.is_describe_prepacked(32, N, K, G)[-1].startswith("gemm_decode_pk_kernel<2, ")
+    rng = np.random.default_rng(3950 + M)
+    xq, qw, IS, s, sa, c = rand_quantised(rng, M, N, K)
+    ref = O.gemm_w4a8_intscale(xq, sa, qw, IS, c, G, 10)
+    pk = P.is_prepack_w4(dev(qw), dev(IS), G)
+    out, acc = P.is_gemm_w4a8_intscale_prepacked(dev(xq), dev(sa), pk, dev(c), 10, want_acc=True)
+    assert np.array_equal(host(acc), ref.acc), "int32 accumulators differ"
+    check_out(host(out), ref.out, f"M{M} N{N} K{K}")
+
+
 @pytest.mark.parametrize("M,N,K,group", [(200, 300, 1024, 128), (129, 520, 2048, 256), (130, 80, 1536, 1536),
                                          (129, 300, 6144, 384)])
 def test_prepacked_tiled_wide_scales_and_groups(P, M, N, K, group):
