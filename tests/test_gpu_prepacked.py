@@ -274,6 +274,33 @@ def test_prepacked_33_to_64_rows_on_the_tiled_kernel(P, tiled64, M, N, K):
     check_out(host(out_l), ref_l.out, f"linear M{M} N{N} K{K}")
 
 
+def test_prepacked_33_to_64_rows_random_shapes_match_the_canonical_call(P, tiled64):
+    """Random shapes of 33..64 rows on the tiled kernel's 64-row instance (a wide scale now and then), each twice on a
+    workspace of arbitrary contents, accumulators and fp16 outputs against the canonical call's, which the tests of
+    test_gpu_parity.py and test_gpu_configs.py hold to the oracle."""
+    rng = np.random.default_rng(20240598)
+    for case in range(80):
+        M = int(rng.integers(33, 65))
+        N = int(rng.choice([16, 48, 200, 256, 264, 520, 1024, 2056, 4096]))
+        K = int(rng.choice([128, 256, 1024, 2048, 4096, 11008, 14336]))
+        q = torch.randint(0, 256, (N, K // 2), dtype=torch.uint8, device="cuda:0")
+        si = torch.randint(0, 1025, (N, K // G), dtype=torch.int32, device="cuda:0")
+        if rng.random() < 0.3:
+            si[0, 0] = 2 ** 25
+        c = torch.rand((N,), device="cuda:0") + 0.5
+        xq = torch.randint(-128, 128, (M, K), dtype=torch.int8, device="cuda:0")
+        sa = torch.rand(M, device="cuda:0") + 0.1
+        ref_out, ref = P.is_gemm_w4a8_intscale(xq, sa, q, si, c, G, 10, want_acc=True)
+        pk = P.is_prepack_w4(q, si, G)
+        ws = torch.empty(max(16, P.is_gemm_prepacked_workspace_bytes(M, N, K, G)), dtype=torch.uint8, device="cuda:0")
+        for it in range(2):
+            ws.random_(0, 256)
+            out, acc = P.is_gemm_w4a8_intscale_prepacked(xq, sa, pk, c, 10, want_acc=it == 0, workspace=ws)
+            if it == 0:
+                assert torch.equal(acc, ref), f"case {case}: M {M}, N {N}, K {K}"
+            assert torch.equal(out, ref_out), f"case {case}: M {M}, N {N}, K {K} (fp16 outputs, pass {it})"
+
+
 @pytest.mark.parametrize("M,N,K", [(64, 8192, 28672), (40, 28672, 8192)])
 def test_prepacked_33_to_64_rows_on_large_weights_take_the_tiled_kernel(P, M, N, K):
     """From 2^27 weights on the library itself picks the tiled kernel for 33..64 rows (the LLaMA-2-70B gate and down
