@@ -250,6 +250,18 @@ def family_main(args):
                             P.is_gemm_w4a8_intscale_prepacked(a["xq"], a["sa"], w["pi"][l], w["c"][l], ALPHA_LOG2,
                                                               out=a["out"], workspace=a["gws"])
                     kernels = P.is_describe_prepacked(M, N, K, grp(K), True, False)
+                elif kind == "gemm_is_prepared":
+                    # the tiled kernel alone: the activations are prepared once (outside the replayed launches), the
+                    # layers' GEMMs run on the prepared workspace
+                    if len(P.is_describe_prepacked(M, N, K, grp(K), True, False)) < 2:
+                        continue
+                    P.is_prepare_activations_prepacked(a["xq"], a["gws"])
+
+                    def fn(a=a, w=w):
+                        for l in range(L):
+                            P.is_gemm_w4a8_intscale_prepacked_prepared(a["sa"], w["pi"][l], w["c"][l], ALPHA_LOG2,
+                                                                       a["gws"], out=a["out"])
+                    kernels = P.is_describe_prepacked(M, N, K, grp(K), True, False)[-1:]
                 else:
                     def fn(a=a, w=w):
                         for l in range(L):
@@ -308,6 +320,11 @@ def family_main(args):
     if not args.no_floatscale:
         g_fs = make_segments("gemm_fs")
         timed_pass(g_fs, n_cmp, 2)
+    # the tiled kernel by itself (its preparation kernel done once beforehand): the kernel's own launch duration
+    g_tile = make_segments("gemm_is_prepared")
+    if g_tile:
+        timed_pass(g_tile, n_cmp, 2)
+    tile_us = {s.name: per_call_us(s) for s in g_tile}
 
     # a plain streaming read of the same number of bytes as each decode GEMM (cold: a different buffer every launch)
     sink = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -353,17 +370,26 @@ def family_main(args):
         else:
             row["tops"] = round(ops_call / gemm_us / 1e6, 1)
             row["mfma_frac"] = round(ops_call / gemm_us / 1e6 / MFMA_I8_PEAK_TOPS, 4)
+            if s.name in tile_us:  # the tiled kernel alone, on prepared activations
+                row["tile_kernel_us"] = round(tile_us[s.name], 3)
+                row["tile_kernel_mfma_frac"] = round(ops_call / tile_us[s.name] / 1e6 / MFMA_I8_PEAK_TOPS, 4)
         shapes.append(row)
 
     # ---------------------------------------------------------------- rooflines: per kernel instantiation, from the
     # GEMM-only pass; the dominant one by time inside the step is `roofline`
     by_kernel = {}
     for s in g_is:
-        k = by_kernel.setdefault(s.kernel, dict(ms=0.0, launches=0, bytes=0.0, ops=0.0, tiled=s.M > 64))
-        k["ms"] += s.elapsed_ms
+        k = by_kernel.setdefault(s.kernel, dict(ms=0.0, launches=0, bytes=0.0, ops=0.0, tiled=s.M > 64, call_ms=0.0,
+                                                alone=True))
+        k["call_ms"] += s.elapsed_ms
         k["launches"] += s.count
         k["bytes"] += s.alg_bytes * (s.count / s.launches)
         k["ops"] += s.ops * (s.count / s.launches)
+        if s.name in tile_us:  # the kernel's own duration: the pass on prepared activations (same launches, same weights)
+            k["ms"] += tile_us[s.name] * s.count / 1e3
+        else:
+            k["ms"] += s.elapsed_ms
+            k["alone"] = len(s.kernels) == 1
     peaks = measured_peaks(P, torch)
     profile = f"{args.workload}"
 
@@ -376,8 +402,15 @@ def family_main(args):
                         avg_launch_us=round(us, 3), alg_ops_per_launch=round(k["ops"] / k["launches"]),
                         frac_of_measured_peak=round(ach / peaks["mfma_i8_tops"], 4),
                         frac_of_measured_peak_random_operands=round(ach / peaks["mfma_i8_tops_random_operands"], 4),
-                        note="duration = the GEMM call on int8 codes: this kernel plus its activation preparation "
-                             "kernel (a few per cent of the call; the committed kernel trace has both)")
+                        gemm_call_us=round(1e3 * k["call_ms"] / k["launches"], 3),
+                        frac_of_gemm_call=round(k["ops"] / k["launches"] / (1e3 * k["call_ms"] / k["launches"]) / 1e6
+                                                / MFMA_I8_PEAK_TOPS, 4),
+                        note="avg_launch_us = this kernel alone, timed with events around replayed launches of the "
+                             "GEMM on prepared activations (is_prepare_activations_prepacked once, then "
+                             "is_gemm_w4a8_intscale_prepacked_prepared per layer); gemm_call_us = the ordinary GEMM "
+                             "call on int8 codes, i.e. with its activation preparation kernel" if k["alone"] else
+                             "duration = the GEMM call on int8 codes: this kernel plus its activation preparation "
+                             "kernel")
         ach = k["bytes"] / k["launches"] / us / 1e3
         return dict(bound="hbm", kernel=name, achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(ach / HBM_PEAK_GBS, 4), traffic=measured_traffic(name, profile),

@@ -202,6 +202,31 @@ int is_gemm_w4a8_floatscale_prepacked(const int8_t* xq, const float* a_scale, co
                                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Activations that several GEMMs share (the q / k / v or the gate / up projections of one layer input): the tiled
+ * route's preparation of the quantised activations, done once, and the prepacked GEMMs on the prepared workspace,
+ * which then launch the tiled kernel alone.  Same arithmetic and results as the calls above (Eq. (2) / Eq. (1)), bit
+ * for bit.
+ *   is_prepare_activations_prepacked   xq int8 [M,K] -> the front part of `workspace`, whose size depends on M and K
+ *       only (MFMA operand blocks, zero-point corrections, zeroed arrival counters).  M > 32, K a multiple of
+ *       128, ceil(M/16) * 16 * K below 2^31 (IS_ERR_UNSUPPORTED otherwise).
+ *   is_gemm_w4a8_*_prepacked_prepared  as is_gemm_w4a8_*_prepacked without xq, on a workspace prepared for the same
+ *       M and K; any number of calls, with any N and weights, may follow one preparation, one after the other on the
+ *       same stream (each leaves the workspace prepared).  Only shapes that take the tiled kernel (M > 64, or
+ *       33 <= M <= 64 with N * K >= 2^27): IS_ERR_UNSUPPORTED otherwise, use the ordinary call.
+ *   workspace   the same buffer for all of them, at least is_gemm_prepacked_workspace_bytes(M, N, K, group) bytes of the
+ *       widest N (less is accepted down to the size for N = 1: the last round's K split then uses what there is).
+ */
+int is_prepare_activations_prepacked(const int8_t* xq, int M, int K, void* workspace, size_t workspace_bytes,
+                                     void* stream);
+int is_gemm_w4a8_intscale_prepacked_prepared(const float* a_scale, const void* qweight_packed, const void* scales_packed,
+                                             const float* chan_scale, int M, int N, int K, int group, int alpha_log2,
+                                             void* out_fp16, int32_t* acc_out, void* workspace, size_t workspace_bytes,
+                                             void* stream);
+int is_gemm_w4a8_floatscale_prepacked_prepared(const float* a_scale, const void* qweight_packed,
+                                               const void* scales_packed, int M, int N, int K, int group, void* out_fp16,
+                                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * is_gemm_w4a8_intscale_prepacked for callers that cannot allocate device memory: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results, without the workspace: the
  * call uses a fixed scratch array inside the library (IS_NOALLOC_SCRATCH_BYTES of device memory per GPU, held until

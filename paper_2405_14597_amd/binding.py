@@ -49,6 +49,9 @@ EXPORTED_SYMBOLS = (
     "is_gemm_w4a8_intscale_prepacked",
     "is_gemm_w4a8_floatscale_prepacked",
     "is_gemm_w4a8_intscale_prepacked_noalloc",
+    "is_prepare_activations_prepacked",
+    "is_gemm_w4a8_intscale_prepacked_prepared",
+    "is_gemm_w4a8_floatscale_prepacked_prepared",
     "is_linear_prepacked_workspace_bytes",
     "is_linear_w4a8_intscale_prepacked",
     "is_linear_w4a8_floatscale_prepacked",
@@ -165,6 +168,12 @@ def load_library() -> ctypes.CDLL:
     lib.is_gemm_w4a8_floatscale_gate_up_silu_prepacked.restype = ci
     lib.is_gemm_w4a8_intscale_prepacked_noalloc.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp]
     lib.is_gemm_w4a8_intscale_prepacked_noalloc.restype = ci
+    lib.is_prepare_activations_prepacked.argtypes = [vp, ci, ci, vp, sz, vp]
+    lib.is_prepare_activations_prepacked.restype = ci
+    lib.is_gemm_w4a8_intscale_prepacked_prepared.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
+    lib.is_gemm_w4a8_intscale_prepacked_prepared.restype = ci
+    lib.is_gemm_w4a8_floatscale_prepacked_prepared.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp, sz, vp]
+    lib.is_gemm_w4a8_floatscale_prepacked_prepared.restype = ci
     lib.is_gemm_grouped_prepacked_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.is_gemm_grouped_prepacked_workspace_bytes.restype = sz
     lib.is_gemm_w4a8_intscale_grouped_prepacked.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp, sz,
@@ -925,6 +934,60 @@ def is_gemm_w4a8_intscale_prepacked_noalloc(xq, a_scale, packed: PackedWeights, 
                                                                _p(acc_out), _stream_handle(stream))
     _check("is_gemm_w4a8_intscale_prepacked_noalloc", st)
     return out, acc_out
+
+
+def is_prepare_activations_prepacked(xq, workspace, stream=None):
+    """The tiled route's preparation of quantised activations [M,K] into `workspace` (a uint8 tensor the caller keeps
+    for the *_prepared GEMMs that follow; size it with is_gemm_prepacked_workspace_bytes of the widest N)."""
+    torch = _torch()
+    M, K = xq.shape
+    _require(xq, torch.int8, (M, K), "xq")
+    st = load_library().is_prepare_activations_prepacked(_p(xq), M, K, _p(workspace), workspace.numel(),
+                                                         _stream_handle(stream))
+    _check("is_prepare_activations_prepacked", st)
+    return workspace
+
+
+def is_gemm_w4a8_intscale_prepacked_prepared(a_scale, packed: PackedWeights, chan_scale, alpha_log2: int, workspace,
+                                             out=None, acc_out=None, want_acc=False, stream=None):
+    """The prepacked integer-scale GEMM on a workspace is_prepare_activations_prepacked has filled (tiled kernel only)."""
+    torch = _torch()
+    M = a_scale.shape[0]
+    N, K, group = packed.N, packed.K, packed.group
+    if packed.float_scales:
+        raise ValueError("packed weights: float scales")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    if chan_scale is not None:
+        _require(chan_scale, torch.float32, (N,), "chan_scale")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=a_scale.device)
+    _require(out, torch.float16, (M, N), "out")
+    if acc_out is None and want_acc:
+        acc_out = torch.empty((M, N), dtype=torch.int32, device=a_scale.device)
+    if acc_out is not None:
+        _require(acc_out, torch.int32, (M, N), "acc_out")
+    st = load_library().is_gemm_w4a8_intscale_prepacked_prepared(
+        _p(a_scale), _p(packed.wpack), _p(packed.spack), _p(chan_scale), M, N, K, group, alpha_log2, _p(out),
+        _p(acc_out), _p(workspace), workspace.numel(), _stream_handle(stream))
+    _check("is_gemm_w4a8_intscale_prepacked_prepared", st)
+    return out, acc_out
+
+
+def is_gemm_w4a8_floatscale_prepacked_prepared(a_scale, packed: PackedWeights, workspace, out=None, stream=None):
+    torch = _torch()
+    M = a_scale.shape[0]
+    N, K, group = packed.N, packed.K, packed.group
+    if not packed.float_scales:
+        raise ValueError("packed weights: integer scales")
+    _require(a_scale, torch.float32, (M,), "a_scale")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=a_scale.device)
+    _require(out, torch.float16, (M, N), "out")
+    st = load_library().is_gemm_w4a8_floatscale_prepacked_prepared(
+        _p(a_scale), _p(packed.wpack), _p(packed.spack), M, N, K, group, _p(out), _p(workspace), workspace.numel(),
+        _stream_handle(stream))
+    _check("is_gemm_w4a8_floatscale_prepacked_prepared", st)
+    return out
 
 
 def is_gemm_w4a8_floatscale_prepacked(xq, a_scale, packed: PackedWeights, out=None, workspace=None, stream=None):

@@ -428,7 +428,8 @@ size_t is_gemm_prepacked_workspace_bytes(int M, int N, int K, int group) {
 static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_scale, float* a_scale_out,
                           const void* wpack, const void* spack, const float* chan_scale, int M, int N, int K, int group,
                           int alpha_log2, void* out_fp16, int32_t* acc_out, void* workspace, size_t workspace_bytes,
-                          void* stream, bool int_scale, bool fixed_scratch = false, bool pair = false) {
+                          void* stream, bool int_scale, bool fixed_scratch = false, bool pair = false,
+                          bool prepared = false) {
     if (M < 0) return IS_ERR_INVALID_ARG;
     const int shape = check_pk_shape(N, K, group);
     if (shape != IS_OK) return shape;
@@ -440,12 +441,14 @@ static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_s
     if (M > 0 && !tiled && !pk_decode_plan(M, N, K, group, x_fp16 != nullptr, &plan)) return IS_ERR_UNSUPPORTED;
     if (tiled && (long long)((M + 15) / 16) * 16 * K >= (1LL << 31)) return IS_ERR_UNSUPPORTED;  // 32-bit offsets
     // (on the fixed scratch the tiled route takes what it needs at least: the K split of its last round uses what is left)
-    const size_t need = (fixed_scratch && tiled) ? gemm_tile_pk_min_workspace_bytes(M, K)
+    if (prepared && M > 0 && !tiled) return IS_ERR_UNSUPPORTED;  // (the weight-streaming kernel reads the codes themselves)
+    const size_t need = ((fixed_scratch || prepared) && tiled) ? gemm_tile_pk_min_workspace_bytes(M, K)
                                                   : is_gemm_prepacked_workspace_bytes(M, N, K, group);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return IS_ERR_WORKSPACE;
     if (!ok_ptr(wpack) || !ok_ptr(spack) || !ok_opt(chan_scale)) return IS_ERR_INVALID_ARG;
     if (M == 0) return IS_OK;
-    if (x_fp16 ? !ok_ptr(x_fp16) : (!ok_ptr(xq) || a_scale == nullptr || (reinterpret_cast<uintptr_t>(a_scale) & 3u)))
+    if (x_fp16 ? !ok_ptr(x_fp16)
+               : ((!prepared && !ok_ptr(xq)) || a_scale == nullptr || (reinterpret_cast<uintptr_t>(a_scale) & 3u)))
         return IS_ERR_INVALID_ARG;
     if (!ok_ptr(out_fp16) || !ok_opt(acc_out)) return IS_ERR_INVALID_ARG;
     PkArgs a;
@@ -467,7 +470,8 @@ static int gemm_pk_common(const int8_t* xq, const void* x_fp16, const float* a_s
     a.alpha_log2 = int_scale ? alpha_log2 : 0;
     a.pair = (pair && tiled) ? 1 : 0;  // (the fused epilogue is the tiled kernel's)
     if (tiled)
-        return hip_status(launch_gemm_tile_pk(a, int_scale, workspace, workspace_bytes, static_cast<hipStream_t>(stream)));
+        return hip_status(launch_gemm_tile_pk(a, int_scale, workspace, workspace_bytes, static_cast<hipStream_t>(stream),
+                                              prepared));
     if (fixed_scratch && a.partials != nullptr) {  // a workspace whose last user may not have left the counters zero
         const int n16 = (N + 15) / 16;
         hipLaunchKernelGGL(zero_words_kernel, dim3((n16 + 255) / 256), dim3(256), 0, static_cast<hipStream_t>(stream),
@@ -557,6 +561,33 @@ int is_gemm_w4a8_floatscale_gate_up_silu_prepacked(const int8_t* xq, const float
                                                    void* out_fp16, void* workspace, size_t workspace_bytes, void* stream) {
     return gate_up_silu_common(xq, a_scale, qweight_packed, scales_packed, nullptr, M, inter, K, group, 0, out_fp16,
                                nullptr, workspace, workspace_bytes, stream, false);
+}
+
+int is_prepare_activations_prepacked(const int8_t* xq, int M, int K, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+    if (M < 0 || K <= 0) return IS_ERR_INVALID_ARG;
+    if (K % 128 != 0 || K > (1 << 20) || M > (1 << 20)) return IS_ERR_UNSUPPORTED;
+    if (M > 0 && M <= 32) return IS_ERR_UNSUPPORTED;  // such calls take the weight-streaming kernel, which needs none
+    if ((long long)((M + 15) / 16) * 16 * K >= (1LL << 31)) return IS_ERR_UNSUPPORTED;  // 32-bit offsets
+    if (M == 0) return IS_OK;
+    if (!ok_ptr(workspace) || workspace_bytes < gemm_tile_pk_min_workspace_bytes(M, K)) return IS_ERR_WORKSPACE;
+    if (!ok_ptr(xq)) return IS_ERR_INVALID_ARG;
+    return hip_status(launch_prepare_activations_pk(xq, M, K, workspace, static_cast<hipStream_t>(stream)));
+}
+
+int is_gemm_w4a8_intscale_prepacked_prepared(const float* a_scale, const void* qweight_packed, const void* scales_packed,
+                                             const float* chan_scale, int M, int N, int K, int group, int alpha_log2,
+                                             void* out_fp16, int32_t* acc_out, void* workspace, size_t workspace_bytes,
+                                             void* stream) {
+    return gemm_pk_common(nullptr, nullptr, a_scale, nullptr, qweight_packed, scales_packed, chan_scale, M, N, K, group,
+                          alpha_log2, out_fp16, acc_out, workspace, workspace_bytes, stream, true, false, false, true);
+}
+
+int is_gemm_w4a8_floatscale_prepacked_prepared(const float* a_scale, const void* qweight_packed,
+                                               const void* scales_packed, int M, int N, int K, int group, void* out_fp16,
+                                               void* workspace, size_t workspace_bytes, void* stream) {
+    return gemm_pk_common(nullptr, nullptr, a_scale, nullptr, qweight_packed, scales_packed, nullptr, M, N, K, group, 0,
+                          out_fp16, nullptr, workspace, workspace_bytes, stream, false, false, false, true);
 }
 
 int is_gemm_w4a8_intscale_prepacked_noalloc(const int8_t* xq, const float* a_scale, const void* qweight_packed,

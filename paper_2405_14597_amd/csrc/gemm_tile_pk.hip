@@ -791,8 +791,24 @@ void gemm_tile_pk_kernel_names(int K, bool int_scale, bool fp16_in, char* buf, s
     snprintf(buf, len, "%s\ngemm_tile%s_pk_kernel<%s>", prep, silu ? "_silu" : "", int_scale ? "true" : "false");
 }
 
+// The preparation of quantised activations on its own (for activations that several GEMMs share): fills the fixed part
+// of the workspace and sets every arrival counter of the last-round split to zero, whatever N the GEMMs will have.
+hipError_t launch_prepare_activations_pk(const int8_t* xq, int M, int K, void* workspace, hipStream_t stream) {
+    unsigned char* ws = static_cast<unsigned char*>(workspace);
+    int8_t* xp = reinterpret_cast<int8_t*>(ws);
+    int32_t* c0 = reinterpret_cast<int32_t*>(ws + xp_bytes(M, K));
+    int32_t* counters = reinterpret_cast<int32_t*>(ws + gemm_tile_pk_min_workspace_bytes(M, K) - kCounterBytes);
+    const int per_wg = 4 * kPrepSteps;
+    const dim3 blocks((M + 15) / 16, ((K >> 7) + per_wg - 1) / per_wg);
+    hipLaunchKernelGGL(prepare_activations_pk_kernel, blocks, dim3(256), 0, stream, xq, M, K, xp, c0, counters,
+                       (int)(kCounterBytes / 4));
+    return hipGetLastError();
+}
+
+// prepared: the workspace already holds the activations' blocks, corrections and zeroed counters (the call above, or an
+// earlier launch on the same activations: every launch leaves the counters zero); only the tiled kernel is launched.
 hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace, size_t workspace_bytes,
-                               hipStream_t stream) {
+                               hipStream_t stream, bool prepared) {
     unsigned char* ws = static_cast<unsigned char*>(workspace);
     int8_t* xp = reinterpret_cast<int8_t*>(ws);
     int32_t* c0 = reinterpret_cast<int32_t*>(ws + xp_bytes(a.M, a.K));
@@ -805,7 +821,9 @@ hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace,
     const int mtiles = (a.M + 15) / 16;
     const int per_wg = 4 * kPrepSteps;
     const dim3 blocks(mtiles, ((a.K >> 7) + per_wg - 1) / per_wg);
-    if (a.x_fp16) {  // fp16 activations: quantised on the way, the token scales go to a.a_scale_out (= a.a_scale)
+    if (prepared) {
+        // nothing to prepare
+    } else if (a.x_fp16) {  // fp16 activations: quantised on the way, the token scales go to a.a_scale_out (= a.a_scale)
         hipLaunchKernelGGL(quantize_prepare_rows_pk_kernel, dim3(2 * mtiles), dim3(kRowWaves * kWave), 0, stream, a.x_fp16,
                            a.M, a.K, a.a_scale_out, xp, c0, sp.counters, sp.rem);
     } else {

@@ -82,7 +82,9 @@ size_t gemm_tile_pk_workspace_bytes(int M, int N, int K);   // what the launch m
 size_t gemm_tile_pk_min_workspace_bytes(int M, int K);      // what it needs at least (then without the K split of the last round)
 bool gemm_tile_pk_takes_fp16(int K);
 hipError_t launch_gemm_tile_pk(const PkArgs& a, bool int_scale, void* workspace, size_t workspace_bytes,
-                               hipStream_t stream);
+                               hipStream_t stream, bool prepared = false);
+// Its preparation of quantised activations alone (then launch_gemm_tile_pk with prepared = true, any number of times).
+hipError_t launch_prepare_activations_pk(const int8_t* xq, int M, int K, void* workspace, hipStream_t stream);
 // Mixture-of-experts form of the tiled kernel: a.xq / a.a_scale / a.out hold all experts' rows sorted by expert,
 // row_offsets (device, [E+1]) their ranges; a.wpack / a.spack point at E prepacked weight sets wstride / sstride bytes
 // apart, a.chan_scale at [E][N] (or nullptr).  a.M is the total number of rows.

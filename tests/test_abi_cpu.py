@@ -222,6 +222,30 @@ def test_noalloc_argument_validation():
     assert call(M=2048, N=256, K=28672) == P.IS_ERR_WORKSPACE
 
 
+def test_shared_preparation_argument_validation():
+    """The preparation of shared activations and the GEMMs on a prepared workspace check shapes, route and workspace
+    before any HIP call: only shapes of the tiled route have a preparation."""
+    lib = P.load_library()
+    bad, unsup = P.IS_ERR_INVALID_ARG, P.IS_ERR_UNSUPPORTED
+    big = 1 << 30
+    prep = lambda **kw: lib.is_prepare_activations_prepacked(kw.get("xq", A), kw.get("M", 128), kw.get("K", 256),
+                                                             kw.get("ws", A), kw.get("wsb", big), None)
+    assert prep(M=-1) == bad and prep(K=0) == bad and prep(K=200) == unsup and prep(M=32) == unsup and prep(M=1) == unsup
+    assert prep(M=0) == P.IS_OK
+    assert prep(ws=None) == P.IS_ERR_WORKSPACE and prep(wsb=1024) == P.IS_ERR_WORKSPACE and prep(xq=None) == bad
+    assert prep(M=1 << 20, K=1 << 12) == unsup      # 32-bit offsets
+    gemm = lambda **kw: lib.is_gemm_w4a8_intscale_prepacked_prepared(
+        kw.get("sa", A), kw.get("wp", A), kw.get("sp", A), None, kw.get("M", 128), kw.get("N", 16), kw.get("K", 256),
+        kw.get("G", 128), kw.get("a", 10), kw.get("out", A), None, kw.get("ws", A), kw.get("wsb", big), None)
+    assert gemm(M=64) == unsup and gemm(M=8) == unsup                      # the weight-streaming kernel's shapes
+    assert gemm(M=-1) == bad and gemm(G=64) == unsup and gemm(a=31) == bad
+    assert gemm(ws=None) == P.IS_ERR_WORKSPACE and gemm(wsb=64) == P.IS_ERR_WORKSPACE
+    assert gemm(sa=None) == bad and gemm(wp=None) == bad and gemm(out=None) == bad
+    assert gemm(M=0) == P.IS_OK
+    fs = lib.is_gemm_w4a8_floatscale_prepacked_prepared
+    assert fs(A, A, A, 64, 16, 256, 128, A, A, big, None) == unsup and fs(None, A, A, 128, 16, 256, 128, A, A, big, None) == bad
+
+
 def test_gate_up_silu_argument_validation():
     lib = P.load_library()
     bad, uns = P.IS_ERR_INVALID_ARG, P.IS_ERR_UNSUPPORTED

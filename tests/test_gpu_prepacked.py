@@ -274,6 +274,32 @@ def test_prepacked_33_to_64_rows_on_the_tiled_kernel(P, tiled64, M, N, K):
     check_out(host(out_l), ref_l.out, f"linear M{M} N{N} K{K}")
 
 
+@pytest.mark.parametrize("M,K", [(130, 1024), (2048, 2048), (65, 128), (300, 4096)])
+def test_prepacked_gemms_on_shared_prepared_activations(P, M, K):
+    """One preparation of the activations, then GEMMs with several weight sets of different widths on the prepared
+    workspace (last rounds with and without a K split, so the arrival counters are used and left zero in turn): the
+    accumulators and outputs of the ordinary prepacked call, bit for bit, and the oracle's accumulators."""
+    rng = np.random.default_rng(4100 + M + K)
+    widths = [520, 16, 4104, 256, 520]
+    xq = rng.integers(-128, 128, size=(M, K)).astype(np.int8)
+    sa = (rng.random(M).astype(np.float32) + 0.1)
+    ws = torch.empty(max(P.is_gemm_prepacked_workspace_bytes(M, n, K, G) for n in widths), dtype=torch.uint8, device="cuda:0")
+    ws.random_(0, 256)
+    P.is_prepare_activations_prepacked(dev(xq), ws)
+    for i, N in enumerate(widths):
+        _, qw, IS, s, _, c = rand_quantised(np.random.default_rng(4200 + N + i), 1, N, K)
+        pk = P.is_prepack_w4(dev(qw), dev(IS), G)
+        out, acc = P.is_gemm_w4a8_intscale_prepacked_prepared(dev(sa), pk, dev(c), 10, ws, want_acc=i % 2 == 0)
+        ref_out, ref_acc = P.is_gemm_w4a8_intscale_prepacked(dev(xq), dev(sa), pk, dev(c), 10, want_acc=True)
+        assert torch.equal(out, ref_out), f"N {N}"
+        if acc is not None:
+            assert torch.equal(acc, ref_acc), f"N {N}"
+            assert np.array_equal(host(acc), O.gemm_w4a8_intscale(xq, sa, qw, IS, c, G, 10).acc)
+        pf = P.is_prepack_w4(dev(qw), dev(s), G)
+        assert torch.equal(P.is_gemm_w4a8_floatscale_prepacked_prepared(dev(sa), pf, ws),
+                           P.is_gemm_w4a8_floatscale_prepacked(dev(xq), dev(sa), pf)), f"float scales, N {N}"
+
+
 def test_prepacked_33_to_64_rows_random_shapes_match_the_canonical_call(P, tiled64):
     """Random shapes of 33..64 rows on the tiled kernel's 64-row instance (a wide scale now and then), each twice on a
     workspace of arbitrary contents, accumulators and fp16 outputs against the canonical call's, which the tests of
