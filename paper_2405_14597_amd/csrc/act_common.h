@@ -82,7 +82,8 @@ constexpr int kActThreads = 256;
 // correctly rounded quotient both lie within 1.6e-5 of x / s (|x / s| <= 127, three roundings of 2^-24), so whenever t
 // is at least 5e-5 away from the nearest half-integer the two round to the same integer.  If any value of the wave
 // comes closer, all N are redone with the division itself (about one chunk of eight in thirty).
-template <int N>
+// CLAMP = false leaves the range to the caller (quantize8 below, whose packing saturates).
+template <int N, bool CLAMP = true>
 __device__ __forceinline__ void quant_codes(const float (&x)[N], float s, float (&q)[N]) {
     if (s > 0.0f) {
         const float r = 1.0f / s;
@@ -97,8 +98,10 @@ __device__ __forceinline__ void quant_codes(const float (&x)[N], float s, float 
 #pragma unroll
             for (int i = 0; i < N; ++i) q[i] = rintf(x[i] / s);
         }
+        if constexpr (CLAMP) {
 #pragma unroll
-        for (int i = 0; i < N; ++i) q[i] = fminf(fmaxf(q[i], -128.0f), 127.0f);
+            for (int i = 0; i < N; ++i) q[i] = fminf(fmaxf(q[i], -128.0f), 127.0f);
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < N; ++i) q[i] = 0.0f;
@@ -114,11 +117,15 @@ __device__ __forceinline__ uint2 quantize8(uint4 v, float s) {
         x[2 * i] = f.x;
         x[2 * i + 1] = f.y;
     }
-    quant_codes<8>(x, s, q);
+    quant_codes<8, false>(x, s, q);
+    // Codes to bytes: q + 128 (exact: q is an integer) goes through the saturating float -> unsigned byte conversion
+    // that also inserts the byte into its word (the clamp to [-128, 127] of Appendix A.1 is that saturation), and
+    // flipping the top bit of every byte turns the offset form into two's complement.  Three instructions per code
+    // fewer than clamp, convert, mask and shift.
     uint32_t packed[2] = {0u, 0u};
 #pragma unroll
-    for (int i = 0; i < 8; ++i) packed[i >> 2] |= ((uint32_t)(int)q[i] & 0xFFu) << ((i & 3) * 8);
-    return make_uint2(packed[0], packed[1]);
+    for (int i = 0; i < 8; ++i) packed[i >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(q[i] + 128.0f, i & 3, packed[i >> 2]);
+    return make_uint2(packed[0] ^ 0x80808080u, packed[1] ^ 0x80808080u);
 }
 
 // NW = waves in the workgroup; `red` holds NW floats
