@@ -87,14 +87,15 @@ template <int N, bool CLAMP = true>
 __device__ __forceinline__ void quant_codes(const float (&x)[N], float s, float (&q)[N]) {
     if (s > 0.0f) {
         const float r = 1.0f / s;
-        bool close = false;
+        float far = 0.0f;  // the largest distance of a t from its integer (one running maximum: a flag per value, or-ed
+                           // together, is several instructions per value once the compiler has packed the flags into bytes)
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             const float t = x[i] * r;
             q[i] = rintf(t);
-            close |= fabsf(t - q[i]) > 0.49995f;
+            far = fmaxf(far, fabsf(t - q[i]));
         }
-        if (__any(close)) {
+        if (__any(far > 0.49995f)) {
 #pragma unroll
             for (int i = 0; i < N; ++i) q[i] = rintf(x[i] / s);
         }
